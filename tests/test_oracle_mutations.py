@@ -1,0 +1,64 @@
+"""The pins must have teeth: plant one plausible mistake at a time in a scratch
+copy of the oracle's C source (on the CPU, never in the product), rebuild it,
+and require that at least one pin test fails."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+MUTATIONS = {
+    "tie_break_dropped": ("} else if (st->hop[v] == h && t < st->pred[v]) {",
+                          "} else if (0) {"),
+    "tie_break_takes_largest": ("st->hop[v] == h && t < st->pred[v]", "st->hop[v] == h && t > st->pred[v]"),
+    "mask_ignored": ("    if (!mask) return 1;\n", "    return 1;\n"),
+    "mask_bit_index_wrong": ("(mask[r >> 6] >> (r & 63))", "(mask[r >> 6] >> ((r + 1) & 63))"),
+    "subject_used_as_target": ("int32_t v = obj[t];\n    if (st->hop[v] == UNREACHED) {",
+                               "int32_t v = obj[t > 0 ? t - 1 : t];\n    if (st->hop[v] == UNREACHED) {"),
+    "one_hop_too_many": ("for (int h = 1; h <= k; ++h) {", "for (int h = 1; h <= k + 1; ++h) {"),
+    "one_hop_too_few": ("for (int h = 1; h <= k; ++h) {", "for (int h = 1; h < k; ++h) {"),
+    "traversed_counts_only_allowed": ("                    ++inspected;\n                    if (!relation_allowed(mask, rel[t])) continue;",
+                                      "                    if (!relation_allowed(mask, rel[t])) continue;\n                    ++inspected;"),
+    "seed_pred_zero": ("st->pred[e] = -1;", "st->pred[e] = 0;"),
+    "paths_forward_order": ("row[i] = c->stack[c->d - 1 - i];", "row[i] = c->stack[i];"),
+    "paths_wrong_level": ("if (c->hop[c->subj[t]] != level - 1) continue;", "if (c->hop[c->subj[t]] != level) continue;"),
+    "paths_ignore_mask": ("        if (!relation_allowed(c->mask, c->rel[t])) continue;\n", ""),
+}
+
+PIN_CALLS = [
+    lambda: [pins.test_hand_worked_example(m) for m in (0, 1)],
+    lambda: [pins.test_against_boolean_matrix_powers(s, m) for s in range(4) for m in (False, True)],
+    lambda: [pins.test_against_walk_enumeration(s, m) for s in range(4) for m in (False, True)],
+    lambda: pins.test_tie_break_smallest_edge_id_and_mask_selects_other_edge(),
+    lambda: pins.test_directed_cycle_never_lowers_the_seed(0),
+    lambda: pins.test_first_path_is_the_pred_chain(),
+]
+
+
+@pytest.mark.parametrize("name", sorted(MUTATIONS))
+def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
+    old, new = MUTATIONS[name]
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "khop_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation site vanished"
+    mutated = tmp_path / "mut.c"
+    mutated.write_text(src.replace(old, new))
+    lib_path = str(tmp_path / "libmut.so")
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", lib_path,
+                           str(mutated)])
+    good = oracle._load()
+    lib = ctypes.CDLL(lib_path)
+    for fn in ("oracle_khop", "oracle_paths", "oracle_free", "oracle_num_threads"):
+        getattr(lib, fn).argtypes = getattr(good, fn).argtypes
+        getattr(lib, fn).restype = getattr(good, fn).restype
+    monkeypatch.setattr(oracle, "_lib", lib)
+    caught = False
+    for call in PIN_CALLS:
+        try:
+            call()
+        except AssertionError:
+            caught = True
+            break
+    assert caught, f"no pin noticed the planted mistake '{name}'"
