@@ -1,0 +1,222 @@
+/*
+ * logoskg.h - C ABI of the MI355X (gfx950) batched k-hop knowledge-graph
+ * retrieval library.
+ *
+ * The operations follow the LogosKG paper's problem statement (Sec. 3.1: a KG
+ * is a set of triples (s, r, o); a query is a set of entities; k-hop retrieval
+ * returns every entity reachable from a seed within k relational steps) and
+ * its incidence-matrix formulation (Sec. 3.2-3.3): the column index t of SUB /
+ * row index t of OBJ and REL (Eq. 1-3) is the position of a triple in the
+ * arrays given to logoskg_build and is the triple's EDGE ID everywhere below;
+ * one hop is q.SUB.OBJ over the boolean semiring (Eq. 4), with the active
+ * triples t = q.SUB (Eq. 5-6) additionally filtered by a per-query relation
+ * whitelist before the OBJ product.
+ *
+ * Conventions
+ *   - Every call returns a logoskg_status; LOGOSKG_OK is 0.  A short text for
+ *     the last failure on the calling thread is kept by logoskg_last_error().
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HBM of the
+ *     graph's GPU.  Caller buffers are borrowed for the duration of the call.
+ *   - Entity ids are int32 in [0, num_entities), relation ids int32 in
+ *     [0, num_relations), num_relations <= 65536, num_triples < 2^31.
+ *   - A graph handle runs one call at a time (not thread safe).  Stream
+ *     arguments are hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef LOGOSKG_H
+#define LOGOSKG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct logoskg_graph logoskg_graph;   /* owns device (and pinned host) memory  */
+typedef struct logoskg_result logoskg_result; /* owns the device state of one k-hop call */
+
+typedef enum {
+    LOGOSKG_OK = 0,
+    LOGOSKG_EINVAL = 1,    /* null pointer, id out of range, k outside [0,254], bad sizes */
+    LOGOSKG_ENOMEM = 2,    /* host or device allocation failed, or budget below one shard  */
+    LOGOSKG_EDEVICE = 3,   /* a HIP call failed (text in logoskg_last_error)               */
+    LOGOSKG_ERANGE = 4,    /* a caller-provided capacity is too small                      */
+    LOGOSKG_EINTERNAL = 5
+} logoskg_status;
+
+#define LOGOSKG_MAX_QUERIES 1024 /* queries per logoskg_khop call: 16 uint64 words per entity */
+#define LOGOSKG_MAX_K 254
+#define LOGOSKG_MAX_PATHS 16
+
+/* ------------------------------------------------------------------ build */
+
+typedef struct {
+    uint32_t struct_size;            /* sizeof(logoskg_build_opts); zero the rest for defaults  */
+    int32_t device;                  /* HIP device ordinal                                      */
+    int32_t num_shards;              /* 0 or 1: whole graph resident in HBM.  >1: degree-aware
+                                        partition of the subjects (Sec. 3.4) into this many
+                                        shards kept in pinned host memory and cached in HBM      */
+    int32_t max_resident_shards;     /* cache capacity in shards (the paper's n); 0 = no cap     */
+    uint64_t hbm_shard_budget_bytes; /* cache capacity in bytes; 0 = no cap                      */
+    int32_t hub_min_degree;          /* rows with at least this many edges take the
+                                        block-per-row kernels; 0 = default.  Never changes
+                                        results.                                                 */
+    int32_t reserved;
+} logoskg_build_opts;
+
+/*
+ * Sec. 3.2, Eq. 1-3: turn the triple list into the device form of SUB, OBJ and
+ * REL - a subject-sorted CSR (objects and relation ids of each subject's
+ * triples) and an object-sorted CSR (subjects, relation ids and edge ids of
+ * each object's triples); both sorts are stable, so edge ids ascend inside a
+ * row.  Rows are split by degree into a group-per-row class and a
+ * block-per-row (hub) class.  With num_shards > 1 the subjects are also
+ * assigned to shards by descending degree, each to the currently lightest
+ * shard (Sec. 3.4, degree-aware partitioning; map P).
+ *
+ * subj/rel/obj: host, int32[num_triples].  Duplicated triples are legal (the
+ * smaller edge id wins ties); ids are validated (LOGOSKG_EINVAL).
+ * *out receives a handle to be released with logoskg_graph_free.
+ */
+logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                             int64_t num_triples, int32_t num_entities, int32_t num_relations,
+                             const logoskg_build_opts *opts, logoskg_graph **out);
+
+void logoskg_graph_free(logoskg_graph *g);
+
+typedef struct {
+    int64_t num_triples;
+    int32_t num_entities, num_relations;
+    int32_t num_shards;
+    int32_t hub_min_degree;
+    int64_t num_out_rows, num_out_hubs; /* subjects with >= 1 triple / in the hub class */
+    int64_t num_in_rows, num_in_hubs;   /* objects  with >= 1 triple / in the hub class */
+    int64_t device_bytes;               /* HBM held by the graph (CSR, lists, shard cache) */
+    int64_t pinned_host_bytes;          /* pinned host memory held by the shards            */
+    int64_t shard_loads, shard_evictions, shard_hits; /* cache counters since build (Sec. 3.4) */
+    int64_t shard_bytes_h2d;
+} logoskg_graph_info;
+
+logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg_graph_info *out);
+
+/* Sec. 3.4 metadata map P: shard of each subject entity (-1 for entities that are
+ * never a subject), and the number of triples per shard.  host outputs; either
+ * may be NULL. */
+logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_t *shard_of_entity /*[E]*/,
+                                       int64_t *triples_per_shard /*[num_shards]*/);
+
+/* ------------------------------------------------------------------- khop */
+
+#define LOGOSKG_DIR_AUTO 0u       /* choose push or pull per hop from the frontier's edge count */
+#define LOGOSKG_DIR_PUSH 1u       /* always expand from the frontier's subject rows             */
+#define LOGOSKG_DIR_PULL 2u       /* always gather over the object rows (resident graphs only)  */
+#define LOGOSKG_DIR_MASK 3u
+#define LOGOSKG_NO_COUNTS 4u      /* skip the per-query reached counts (planes only)            */
+
+typedef struct {
+    uint32_t struct_size;     /* sizeof(logoskg_query_batch)                                  */
+    int32_t num_queries;      /* Q in [1, LOGOSKG_MAX_QUERIES]                                */
+    int64_t num_seeds;        /* length of seeds                                               */
+    const int64_t *seed_off;  /* device int64[Q+1], ascending, seed_off[0]=0, [Q]=num_seeds    */
+    const int32_t *seeds;     /* device int32[num_seeds]; repeats inside a query collapse      */
+    int32_t k;                /* hops, 0..LOGOSKG_MAX_K                                        */
+    uint32_t flags;           /* LOGOSKG_DIR_* | LOGOSKG_NO_COUNTS                             */
+    const uint64_t *rel_mask; /* device uint64[Q][ceil(R/64)]: bit r%64 of word r/64 set when
+                                 the query may follow relation r; NULL = every relation        */
+    void *stream;             /* hipStream_t                                                   */
+} logoskg_query_batch;
+
+/*
+ * Sec. 3.1 / 3.3 (Eq. 4-6; Algorithm 1 when the graph is sharded): batched
+ * k-hop retrieval.  For query j and entity v the result records
+ *   hop_j(v)  = the least h <= k at which v is set in q_j^(h) (0 for seeds), and
+ *   the reached set {v : hop_j(v) defined}.
+ * Device state: one bit plane per hop level, entity-major, W = 1,2,4,8 or 16
+ * uint64 words per entity (bit j%64 of word j/64 belongs to query j), plus the
+ * OR of all levels ("visited").  Unless LOGOSKG_NO_COUNTS is set the per-query
+ * reached counts are computed too.  The call returns after the stream has been
+ * synchronised; bad seed ids or offsets are detected on the device and
+ * reported as LOGOSKG_EINVAL.
+ */
+logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_batch *batch,
+                            logoskg_result **out);
+
+typedef struct {
+    int32_t num_queries, k;
+    int32_t words_per_entity;    /* W */
+    int32_t num_levels;          /* k + 1 */
+    int64_t padded_entities;     /* rows per plane (num_entities rounded up to 64) */
+    const uint64_t *visited;     /* device uint64[padded_entities][W]              */
+    const uint64_t *levels;      /* device uint64[k+1][padded_entities][W]         */
+    int64_t total_reached;       /* sum over queries (-1 with LOGOSKG_NO_COUNTS)   */
+} logoskg_result_info;
+
+logoskg_status logoskg_result_get_info(const logoskg_result *r, logoskg_result_info *out);
+
+typedef struct {
+    int32_t direction;        /* LOGOSKG_DIR_PUSH or LOGOSKG_DIR_PULL; 0 = hop not run (empty frontier) */
+    int32_t shards_touched;   /* shards with an active subject (1 for resident graphs)                  */
+    int64_t active_rows;      /* subjects in the frontier with >= 1 triple                              */
+    int64_t frontier_edges;   /* sum of their out-degrees                                               */
+    int64_t rows_scanned;     /* pull: object rows visited that were not already complete               */
+    int64_t edges_scanned;    /* CSR entries actually read by the expansion kernels                     */
+    int64_t lines_gathered;   /* pull: frontier lines read; push: visited lines read                    */
+    int64_t entities_reached; /* entities with at least one new query bit at this hop                   */
+} logoskg_hop_stats;
+
+/* host out[k]; entry h-1 describes hop h. */
+logoskg_status logoskg_result_hop_stats(const logoskg_result *r, logoskg_hop_stats *out);
+
+/* host reached_off[Q+1]: prefix sums of the per-query reached counts. */
+logoskg_status logoskg_result_offsets(const logoskg_result *r, int64_t *reached_off);
+
+/*
+ * Per-query result lists for queries [q_begin, q_end): query-major, ascending
+ * entity id inside a query; position i of query q is
+ * reached_off[q] - reached_off[q_begin] + i.  entity, hop and pred_edge are
+ * device buffers of reached_off[q_end] - reached_off[q_begin] elements
+ * (capacity is checked: LOGOSKG_ERANGE); hop and pred_edge may be NULL.
+ *   pred_edge = the smallest edge id t with o_t = v, r_t allowed for the query
+ *   and hop(s_t) = hop(v) - 1 (the active triple of Eq. 5-7 that reaches v
+ *   first in edge-id order); -1 for seeds.
+ * Asynchronous on `stream`.
+ */
+logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q_begin, int32_t q_end,
+                                    int64_t capacity, int32_t *entity, uint8_t *hop,
+                                    int32_t *pred_edge, void *stream);
+
+/*
+ * traversed[q][h-1] = number of triples whose subject has hop h-1 for query q
+ * (the triples hop h inspects, whatever their relation): the numerator of the
+ * per-query "traversed edges per second" figure.  device int64[Q][k].
+ */
+logoskg_status logoskg_result_traversed(logoskg_result *r, int64_t *traversed, void *stream);
+
+void logoskg_result_free(logoskg_result *r);
+
+/* ------------------------------------------------------------------ paths */
+
+/*
+ * Sec. 3.3 "Path reconstruction" (Eq. 5-7), restricted to shortest paths: for
+ * pair i = (query_idx[i], target[i]) with hop(target) = d, the paths are the
+ * edge-id sequences (t_1..t_d) whose triples chain from a seed to the target
+ * through subjects at hops 0..d-1 with allowed relations.  They are ordered
+ * lexicographically by (t_d, t_{d-1}, .., t_1) and the first max_paths
+ * (1..LOGOSKG_MAX_PATHS) are written seed -> target into
+ * path_edges[i][p][0..d), the rest of each row of k entries is -1.
+ * path_count[i] = number written (0 if the target is not reached; 1 empty
+ * path if it is a seed).  All four arrays are device memory; path_edges is
+ * int32[n_pairs][max_paths][k].  Needs a resident (unsharded) graph.
+ * Asynchronous on `stream`.
+ */
+logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                             const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                             int32_t *path_count, int32_t *path_edges, void *stream);
+
+const char *logoskg_last_error(void);
+const char *logoskg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOGOSKG_H */

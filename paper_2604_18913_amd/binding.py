@@ -1,0 +1,341 @@
+"""ctypes binding of liblogoskg.so: argument marshalling only.
+
+Every step of the retrieval runs inside the library's HIP kernels.  If the
+library is missing this module raises; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import weakref
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblogoskg.so")
+_lib = None
+
+DIRECTIONS = {"auto": 0, "push": 1, "pull": 2}
+NO_COUNTS = 4
+STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EDEVICE", 4: "ERANGE", 5: "EINTERNAL"}
+
+
+class LogosKGError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"logoskg: {STATUS.get(status, status)}: {text}")
+        self.status = status
+
+
+class _BuildOpts(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("device", ctypes.c_int32),
+                ("num_shards", ctypes.c_int32), ("max_resident_shards", ctypes.c_int32),
+                ("hbm_shard_budget_bytes", ctypes.c_uint64), ("hub_min_degree", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class _QueryBatch(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("num_queries", ctypes.c_int32),
+                ("num_seeds", ctypes.c_int64), ("seed_off", ctypes.c_void_p),
+                ("seeds", ctypes.c_void_p), ("k", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("rel_mask", ctypes.c_void_p), ("stream", ctypes.c_void_p)]
+
+
+class _GraphInfo(ctypes.Structure):
+    _fields_ = [("num_triples", ctypes.c_int64), ("num_entities", ctypes.c_int32),
+                ("num_relations", ctypes.c_int32), ("num_shards", ctypes.c_int32),
+                ("hub_min_degree", ctypes.c_int32), ("num_out_rows", ctypes.c_int64),
+                ("num_out_hubs", ctypes.c_int64), ("num_in_rows", ctypes.c_int64),
+                ("num_in_hubs", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
+                ("pinned_host_bytes", ctypes.c_int64), ("shard_loads", ctypes.c_int64),
+                ("shard_evictions", ctypes.c_int64), ("shard_hits", ctypes.c_int64),
+                ("shard_bytes_h2d", ctypes.c_int64)]
+
+
+class _ResultInfo(ctypes.Structure):
+    _fields_ = [("num_queries", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("words_per_entity", ctypes.c_int32), ("num_levels", ctypes.c_int32),
+                ("padded_entities", ctypes.c_int64), ("visited", ctypes.c_void_p),
+                ("levels", ctypes.c_void_p), ("total_reached", ctypes.c_int64)]
+
+
+class _HopStats(ctypes.Structure):
+    _fields_ = [("direction", ctypes.c_int32), ("shards_touched", ctypes.c_int32),
+                ("active_rows", ctypes.c_int64), ("frontier_edges", ctypes.c_int64),
+                ("rows_scanned", ctypes.c_int64), ("edges_scanned", ctypes.c_int64),
+                ("lines_gathered", ctypes.c_int64), ("entities_reached", ctypes.c_int64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python paper_2604_18913_amd/build_ext.py` "
+                          "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I32, I64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.logoskg_build.restype = ctypes.c_int
+    lib.logoskg_build.argtypes = [P, P, P, I64, I32, I32, ctypes.POINTER(_BuildOpts), ctypes.POINTER(P)]
+    lib.logoskg_graph_free.restype = None
+    lib.logoskg_graph_free.argtypes = [P]
+    lib.logoskg_graph_get_info.restype = ctypes.c_int
+    lib.logoskg_graph_get_info.argtypes = [P, ctypes.POINTER(_GraphInfo)]
+    lib.logoskg_graph_partition.restype = ctypes.c_int
+    lib.logoskg_graph_partition.argtypes = [P, P, P]
+    lib.logoskg_khop.restype = ctypes.c_int
+    lib.logoskg_khop.argtypes = [P, ctypes.POINTER(_QueryBatch), ctypes.POINTER(P)]
+    lib.logoskg_result_get_info.restype = ctypes.c_int
+    lib.logoskg_result_get_info.argtypes = [P, ctypes.POINTER(_ResultInfo)]
+    lib.logoskg_result_hop_stats.restype = ctypes.c_int
+    lib.logoskg_result_hop_stats.argtypes = [P, P]
+    lib.logoskg_result_offsets.restype = ctypes.c_int
+    lib.logoskg_result_offsets.argtypes = [P, P]
+    lib.logoskg_result_fetch.restype = ctypes.c_int
+    lib.logoskg_result_fetch.argtypes = [P, I32, I32, I64, P, P, P, P]
+    lib.logoskg_result_traversed.restype = ctypes.c_int
+    lib.logoskg_result_traversed.argtypes = [P, P, P]
+    lib.logoskg_result_free.restype = None
+    lib.logoskg_result_free.argtypes = [P]
+    lib.logoskg_paths.restype = ctypes.c_int
+    lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_last_error.restype = ctypes.c_char_p
+    lib.logoskg_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def version() -> str:
+    return _load().logoskg_version().decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise LogosKGError(rc, _load().logoskg_last_error().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dev_tensor(x, dtype, device):
+    torch = _torch()
+    if isinstance(x, torch.Tensor):
+        return x.to(device=device, dtype=dtype).contiguous()
+    return torch.from_numpy(np.ascontiguousarray(x).astype(_NP[dtype], copy=False)).to(device)
+
+
+_NP = {}
+
+
+def _init_np():
+    torch = _torch()
+    _NP.update({torch.int32: np.int32, torch.int64: np.int64, torch.uint8: np.uint8})
+
+
+def _stream_handle(stream) -> int:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class Result:
+    """Device-resident state of one k-hop call (level planes, counts)."""
+
+    def __init__(self, graph: "Graph", handle: int):
+        self._g = graph
+        self._h = ctypes.c_void_p(handle)
+        info = _ResultInfo()
+        _check(_load().logoskg_result_get_info(self._h, ctypes.byref(info)))
+        self.num_queries = info.num_queries
+        self.k = info.k
+        self.words_per_entity = info.words_per_entity
+        self.padded_entities = info.padded_entities
+        self.total_reached = info.total_reached
+        self._levels_ptr = info.levels
+        self._visited_ptr = info.visited
+
+    def offsets(self) -> np.ndarray:
+        off = np.zeros(self.num_queries + 1, dtype=np.int64)
+        _check(_load().logoskg_result_offsets(self._h, off.ctypes.data_as(ctypes.c_void_p)))
+        return off
+
+    def hop_stats(self):
+        arr = (_HopStats * max(self.k, 1))()
+        _check(_load().logoskg_result_hop_stats(self._h, ctypes.cast(arr, ctypes.c_void_p)))
+        names = [f[0] for f in _HopStats._fields_]
+        return [{n: int(getattr(arr[i], n)) for n in names} for i in range(self.k)]
+
+    def fetch(self, q_begin: int = 0, q_end: Optional[int] = None, want_hop: bool = True,
+              want_pred: bool = True, stream=None, out=None):
+        """Query-major lists for queries [q_begin, q_end) as device tensors
+        (entity int32, hop uint8 or None, pred int32 or None)."""
+        torch = _torch()
+        q_end = self.num_queries if q_end is None else q_end
+        off = self.offsets()
+        n = int(off[q_end] - off[q_begin])
+        dev = self._g.device
+        if out is None:
+            entity = torch.empty(n, dtype=torch.int32, device=dev)
+            hop = torch.empty(n, dtype=torch.uint8, device=dev) if want_hop else None
+            pred = torch.empty(n, dtype=torch.int32, device=dev) if want_pred else None
+        else:
+            entity, hop, pred = out
+        _check(_load().logoskg_result_fetch(
+            self._h, q_begin, q_end, entity.numel(), entity.data_ptr(),
+            hop.data_ptr() if hop is not None else None,
+            pred.data_ptr() if pred is not None else None, _stream_handle(stream)))
+        return entity[:n], (hop[:n] if hop is not None else None), (pred[:n] if pred is not None else None)
+
+    def traversed(self, stream=None):
+        torch = _torch()
+        t = torch.empty((self.num_queries, self.k), dtype=torch.int64, device=self._g.device)
+        _check(_load().logoskg_result_traversed(self._h, t.data_ptr(), _stream_handle(stream)))
+        return t
+
+    def level_planes(self):
+        """Copy of the level planes as a uint8 view-friendly int64 tensor
+        [k+1, padded_entities, W] (device)."""
+        torch = _torch()
+        n = (self.k + 1) * self.padded_entities * self.words_per_entity
+        out = torch.empty(n, dtype=torch.int64, device=self._g.device)
+        torch.cuda.current_stream().synchronize()
+        rc = _hip().hipMemcpy(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(self._levels_ptr),
+                              ctypes.c_size_t(n * 8), 3)
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed with {rc}")
+        return out.view(self.k + 1, self.padded_entities, self.words_per_entity)
+
+    def close(self):
+        if self._h:
+            _load().logoskg_result_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+_hiprt = None
+
+
+def _hip():
+    global _hiprt
+    if _hiprt is None:
+        _hiprt = ctypes.CDLL("libamdhip64.so")
+    return _hiprt
+
+
+class Graph:
+    """A knowledge graph built on one GPU (``logoskg_build``)."""
+
+    def __init__(self, subj, rel, obj, num_entities: int, num_relations: int, device: int = 0,
+                 num_shards: int = 0, max_resident_shards: int = 0, hbm_shard_budget_bytes: int = 0,
+                 hub_min_degree: int = 0):
+        lib = _load()
+        torch = _torch()
+        if not _NP:
+            _init_np()
+        if not torch.cuda.is_available():
+            raise RuntimeError("logoskg needs a GPU (no CPU fallback)")
+        subj = np.ascontiguousarray(subj, dtype=np.int32)
+        rel = np.ascontiguousarray(rel, dtype=np.int32)
+        obj = np.ascontiguousarray(obj, dtype=np.int32)
+        if not (subj.shape == rel.shape == obj.shape and subj.ndim == 1):
+            raise ValueError("subj, rel, obj must be 1-D arrays of equal length")
+        opts = _BuildOpts(ctypes.sizeof(_BuildOpts), device, num_shards, max_resident_shards,
+                          hbm_shard_budget_bytes, hub_min_degree, 0)
+        h = ctypes.c_void_p()
+        _check(lib.logoskg_build(subj.ctypes.data_as(ctypes.c_void_p), rel.ctypes.data_as(ctypes.c_void_p),
+                                 obj.ctypes.data_as(ctypes.c_void_p), subj.shape[0], num_entities,
+                                 num_relations, ctypes.byref(opts), ctypes.byref(h)))
+        self._h = h
+        self._results = weakref.WeakSet()
+        self.device = torch.device("cuda", device)
+        self.num_entities = num_entities
+        self.num_relations = num_relations
+        self.num_triples = int(subj.shape[0])
+
+    def info(self) -> dict:
+        gi = _GraphInfo()
+        _check(_load().logoskg_graph_get_info(self._h, ctypes.byref(gi)))
+        return {f[0]: int(getattr(gi, f[0])) for f in _GraphInfo._fields_}
+
+    def partition(self):
+        n = max(self.info()["num_shards"], 1)
+        shard_of = np.zeros(self.num_entities, dtype=np.int32)
+        per = np.zeros(n, dtype=np.int64)
+        _check(_load().logoskg_graph_partition(self._h, shard_of.ctypes.data_as(ctypes.c_void_p),
+                                               per.ctypes.data_as(ctypes.c_void_p)))
+        return shard_of, per
+
+    def khop(self, seed_off, seeds, k: int, rel_mask=None, direction: str = "auto", counts: bool = True,
+             stream=None) -> Result:
+        """``logoskg_khop`` for up to 1024 queries; inputs may be numpy arrays
+        or device tensors (they are placed in HBM before the call)."""
+        torch = _torch()
+        seed_off_d = _dev_tensor(seed_off, torch.int64, self.device)
+        seeds_d = _dev_tensor(seeds, torch.int32, self.device)
+        mask_d = None
+        if rel_mask is not None:
+            if isinstance(rel_mask, torch.Tensor):
+                mask_d = rel_mask.to(self.device).contiguous()
+            else:
+                mask_d = torch.from_numpy(np.ascontiguousarray(rel_mask, dtype=np.uint64).view(np.int64)).to(self.device)
+            if mask_d.numel() != (seed_off_d.numel() - 1) * ((self.num_relations + 63) // 64):
+                raise ValueError("rel_mask must be [Q, ceil(R/64)] 64-bit words")
+        batch = _QueryBatch(ctypes.sizeof(_QueryBatch), seed_off_d.numel() - 1, seeds_d.numel(),
+                            seed_off_d.data_ptr(), seeds_d.data_ptr() if seeds_d.numel() else None, k,
+                            DIRECTIONS[direction] | (0 if counts else NO_COUNTS),
+                            mask_d.data_ptr() if mask_d is not None else None, _stream_handle(stream))
+        h = ctypes.c_void_p()
+        _check(_load().logoskg_khop(self._h, ctypes.byref(batch), ctypes.byref(h)))
+        res = Result(self, h.value)
+        self._results.add(res)
+        return res
+
+    def paths(self, result: Result, query_idx, target, max_paths: int = 16, stream=None):
+        """``logoskg_paths``: (count int32[n], edges int32[n, max_paths, k]) device tensors."""
+        torch = _torch()
+        q = _dev_tensor(query_idx, torch.int32, self.device)
+        t = _dev_tensor(target, torch.int32, self.device)
+        n = q.numel()
+        count = torch.empty(n, dtype=torch.int32, device=self.device)
+        edges = torch.empty((n, max_paths, result.k), dtype=torch.int32, device=self.device)
+        _check(_load().logoskg_paths(self._h, result._h, q.data_ptr(), t.data_ptr(), n, max_paths,
+                                     count.data_ptr(), edges.data_ptr() if edges.numel() else None,
+                                     _stream_handle(stream)))
+        return count, edges
+
+    def close(self):
+        if self._h:
+            for res in list(self._results):  # results borrow the graph's memory pool
+                res.close()
+            _load().logoskg_graph_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# Same names as the C entry points, for callers that prefer the flat form.
+def logoskg_build(subj, rel, obj, num_entities, num_relations, **opts) -> Graph:
+    return Graph(subj, rel, obj, num_entities, num_relations, **opts)
+
+
+def logoskg_khop(graph: Graph, seed_off, seeds, k, rel_mask=None, **kw) -> Result:
+    return graph.khop(seed_off, seeds, k, rel_mask, **kw)
+
+
+def logoskg_paths(graph: Graph, result: Result, query_idx, target, max_paths=16):
+    return graph.paths(result, query_idx, target, max_paths)

@@ -1,0 +1,238 @@
+// logoskg_build: triple list -> device CSR forms of the SUB and OBJ incidence
+// matrices (paper Sec. 3.2, Eq. 1-3) plus degree classes.  Host-side counting
+// sorts, then one upload.
+#include <algorithm>
+#include <numeric>
+
+#include "common.h"
+
+namespace lkg {
+
+static thread_local std::string g_err;
+
+void set_error(const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_err = buf;
+}
+
+const char *get_error() { return g_err.c_str(); }
+
+logoskg_status DevPool::alloc(void **out, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    bytes = (bytes + 255) & ~size_t(255);
+    auto it = free_.lower_bound(bytes);
+    if (it != free_.end() && it->first <= bytes * 2) {
+        *out = it->second;
+        live_[it->second] = it->first;
+        free_.erase(it);
+        return LOGOSKG_OK;
+    }
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        trim();  // give cached blocks back and retry once
+        e = hipMalloc(&p, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+            return LOGOSKG_ENOMEM;
+        }
+    }
+    held_ += bytes;
+    live_[p] = bytes;
+    *out = p;
+    return LOGOSKG_OK;
+}
+
+void DevPool::release(void *p) {
+    if (!p) return;
+    auto it = live_.find(p);
+    if (it == live_.end()) return;
+    free_.emplace(it->second, p);
+    live_.erase(it);
+}
+
+void DevPool::trim() {
+    for (auto &kv : free_) {
+        (void)hipFree(kv.second);
+        held_ -= kv.first;
+    }
+    free_.clear();
+}
+
+template <typename T>
+static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
+    size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
+    LKG_HIP(hipMalloc((void **)dst, bytes));
+    if (!src.empty()) LKG_HIP(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    *acct += bytes;
+    return LOGOSKG_OK;
+}
+
+// Rows with >= 1 entry split into tail / mid / hub lists by degree.
+static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_min,
+                          std::vector<int32_t> &tail, std::vector<int32_t> &mid,
+                          std::vector<int32_t> &hub) {
+    std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
+    for (int32_t v = 0; v < E; ++v) {
+        uint32_t d = off[v + 1] - off[v];
+        if (d == 0) continue;
+        if (d >= (uint32_t)hub_min) hub.push_back(v);
+        else if (d > (uint32_t)kTailMaxDegree) mid.push_back(v);
+        else bucket[d].push_back(v);
+    }
+    for (int d = kTailMaxDegree; d >= 1; --d) tail.insert(tail.end(), bucket[d].begin(), bucket[d].end());
+    std::stable_sort(mid.begin(), mid.end(), [&](int32_t a, int32_t b) {
+        return off[a + 1] - off[a] > off[b + 1] - off[b];
+    });
+}
+
+}  // namespace lkg
+
+using namespace lkg;
+
+extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                                        int64_t T, int32_t E, int32_t R,
+                                        const logoskg_build_opts *opts, logoskg_graph **out) {
+    if (!out) { set_error("out is NULL"); return LOGOSKG_EINVAL; }
+    *out = nullptr;
+    if (T < 0 || T >= (int64_t(1) << 31) || E <= 0 || R <= 0 || R > 65536) {
+        set_error("sizes out of range: T=%lld E=%d R=%d", (long long)T, E, R);
+        return LOGOSKG_EINVAL;
+    }
+    if (T > 0 && (!subj || !rel || !obj)) { set_error("triple arrays are NULL"); return LOGOSKG_EINVAL; }
+    logoskg_build_opts o;
+    memset(&o, 0, sizeof(o));
+    if (opts) {
+        if (opts->struct_size < 8 || opts->struct_size > sizeof(o)) {
+            set_error("logoskg_build_opts.struct_size is %u", opts->struct_size);
+            return LOGOSKG_EINVAL;
+        }
+        memcpy(&o, opts, opts->struct_size);
+    }
+    if (o.num_shards < 0 || o.num_shards > 127 || o.hub_min_degree < 0 || o.max_resident_shards < 0) {
+        set_error("bad build options");
+        return LOGOSKG_EINVAL;
+    }
+    for (int64_t t = 0; t < T; ++t) {
+        if ((uint32_t)subj[t] >= (uint32_t)E || (uint32_t)obj[t] >= (uint32_t)E ||
+            (uint32_t)rel[t] >= (uint32_t)R) {
+            set_error("triple %lld = (%d, %d, %d) is out of range", (long long)t, subj[t], rel[t], obj[t]);
+            return LOGOSKG_EINVAL;
+        }
+    }
+    int ndev = 0;
+    LKG_HIP(hipGetDeviceCount(&ndev));
+    if (o.device < 0 || o.device >= ndev) { set_error("device %d not present", o.device); return LOGOSKG_EINVAL; }
+    LKG_HIP(hipSetDevice(o.device));
+
+    logoskg_graph *g = new (std::nothrow) logoskg_graph();
+    if (!g) { set_error("out of host memory"); return LOGOSKG_ENOMEM; }
+    g->device = o.device;
+    g->E = E;
+    g->R = R;
+    g->T = T;
+    g->Epad = ((int64_t)E + 63) / 64 * 64;
+    g->hub_min = o.hub_min_degree > 0 ? std::max(o.hub_min_degree, kTailMaxDegree + 1) : kDefaultHubMin;
+    g->num_shards = o.num_shards > 1 ? o.num_shards : 1;
+
+    logoskg_status st = LOGOSKG_OK;
+    auto fail = [&](logoskg_status s) { logoskg_graph_free(g); return s; };
+    try {
+        // out-degrees are needed by both the resident and the sharded form
+        std::vector<uint32_t> ooff((size_t)E + 1, 0);
+        for (int64_t t = 0; t < T; ++t) ooff[(size_t)subj[t] + 1]++;
+        for (int32_t e = 0; e < E; ++e) {
+            uint32_t d = ooff[(size_t)e + 1];
+            if (d > 0) g->n_out_rows++;
+            if (d >= (uint32_t)g->hub_min) g->n_out_hubs++;
+            ooff[(size_t)e + 1] += ooff[e];
+        }
+        if ((st = upload(&g->out_off, ooff, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+
+        if (g->num_shards > 1) {
+            if ((st = build_shards(g, subj, rel, obj, &o)) != LOGOSKG_OK) return fail(st);
+        } else {
+            {   // SUB: stable counting sort by subject
+                std::vector<int32_t> oobj((size_t)T);
+                std::vector<uint16_t> orel((size_t)T);
+                std::vector<uint32_t> cur(ooff.begin(), ooff.end() - 1);
+                for (int64_t t = 0; t < T; ++t) {
+                    uint32_t p = cur[subj[t]]++;
+                    oobj[p] = obj[t];
+                    orel[p] = (uint16_t)rel[t];
+                }
+                if ((st = upload(&g->out_obj, oobj, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->out_rel, orel, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+            }
+            {   // OBJ: stable counting sort by object, edge ids ascend inside a row
+                std::vector<uint32_t> ioff((size_t)E + 1, 0);
+                for (int64_t t = 0; t < T; ++t) ioff[(size_t)obj[t] + 1]++;
+                for (int32_t e = 0; e < E; ++e) ioff[(size_t)e + 1] += ioff[e];
+                std::vector<int32_t> isub((size_t)T), ieid((size_t)T);
+                std::vector<uint16_t> irel((size_t)T);
+                std::vector<uint32_t> cur(ioff.begin(), ioff.end() - 1);
+                for (int64_t t = 0; t < T; ++t) {
+                    uint32_t p = cur[obj[t]]++;
+                    isub[p] = subj[t];
+                    irel[p] = (uint16_t)rel[t];
+                    ieid[p] = (int32_t)t;
+                }
+                if ((st = upload(&g->in_off, ioff, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_sub, isub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rel, irel, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_eid, ieid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                std::vector<int32_t> tail, mid, hub;
+                classify_rows(ioff, E, g->hub_min, tail, mid, hub);
+                g->in_rows.n_tail = (int64_t)tail.size();
+                g->in_rows.n_mid = (int64_t)mid.size();
+                g->in_rows.n_hub = (int64_t)hub.size();
+                if ((st = upload(&g->in_rows.tail, tail, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rows.mid, mid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rows.hub, hub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory while sorting %lld triples", (long long)T);
+        return fail(LOGOSKG_ENOMEM);
+    }
+
+    auto dev_alloc = [&](void **p, size_t bytes) -> logoskg_status {
+        LKG_HIP(hipMalloc(p, bytes));
+        g->static_bytes += bytes;
+        return LOGOSKG_OK;
+    };
+    size_t lb = (size_t)E * sizeof(int32_t);
+    if ((st = dev_alloc((void **)&g->fr_tail, lb)) != LOGOSKG_OK) return fail(st);
+    if ((st = dev_alloc((void **)&g->fr_mid, lb)) != LOGOSKG_OK) return fail(st);
+    if ((st = dev_alloc((void **)&g->fr_hub, lb)) != LOGOSKG_OK) return fail(st);
+    if ((st = dev_alloc((void **)&g->d_ctr, 64 * sizeof(unsigned long long))) != LOGOSKG_OK) return fail(st);
+    if (hipHostMalloc((void **)&g->h_ctr, 64 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
+        set_error("hipHostMalloc failed");
+        return fail(LOGOSKG_ENOMEM);
+    }
+    *out = g;
+    return LOGOSKG_OK;
+}
+
+extern "C" void logoskg_graph_free(logoskg_graph *g) {
+    if (!g) return;
+    (void)hipSetDevice(g->device);
+    free_shards(g);
+    void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
+                    g->in_rows.tail, g->in_rows.mid, g->in_rows.hub, g->fr_tail, g->fr_mid,
+                    g->fr_hub, g->d_ctr};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    if (g->h_ctr) (void)hipHostFree(g->h_ctr);
+    g->pool.trim();
+    delete g;
+}
+
+extern "C" const char *logoskg_last_error(void) { return lkg::get_error(); }
+extern "C" const char *logoskg_version(void) { return "logoskg-gfx950 0.1"; }

@@ -1,0 +1,183 @@
+// Internal declarations shared by the HIP translation units of liblogoskg.
+// Nothing here is part of the public ABI (see include/logoskg.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "logoskg.h"
+
+namespace lkg {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char *fmt, ...);
+const char *get_error();
+
+#define LKG_HIP(call)                                                              \
+    do {                                                                           \
+        hipError_t e_ = (call);                                                    \
+        if (e_ != hipSuccess) {                                                    \
+            lkg::set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),  \
+                           __FILE__, __LINE__);                                    \
+            return (e_ == hipErrorOutOfMemory) ? LOGOSKG_ENOMEM : LOGOSKG_EDEVICE; \
+        }                                                                          \
+    } while (0)
+
+#define LKG_TRY(call)                         \
+    do {                                      \
+        logoskg_status s_ = (call);           \
+        if (s_ != LOGOSKG_OK) return s_;      \
+    } while (0)
+
+// ---------------------------------------------------------------- device memory pool
+// k-hop calls need several planes of hundreds of MB each; hipMalloc/hipFree of
+// that size cost far more than the kernels, so freed blocks are kept and handed
+// out again (exact-size match first, else the smallest block that is large
+// enough and at most 2x the request).
+class DevPool {
+public:
+    logoskg_status alloc(void **out, size_t bytes);
+    void release(void *p);
+    void trim();  // hipFree everything that is not handed out
+    size_t bytes_held() const { return held_; }
+
+private:
+    std::multimap<size_t, void *> free_;
+    std::unordered_map<void *, size_t> live_;
+    size_t held_ = 0;
+};
+
+// ---------------------------------------------------------------- graph
+constexpr int kTailMaxDegree = 32;      // rows up to this degree: one W-lane group per row
+constexpr int kDefaultHubMin = 4096;    // rows from this degree: one block per row
+constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
+constexpr int kSuperTiles = 64;         // tiles per super tile (4096 entities)
+
+struct RowClasses {           // device lists of row ids, split by degree
+    int32_t *tail = nullptr;  // 1 .. kTailMaxDegree, sorted by descending degree
+    int32_t *mid = nullptr;   // kTailMaxDegree+1 .. hub_min-1, descending degree
+    int32_t *hub = nullptr;   // >= hub_min, ascending row id
+    int64_t n_tail = 0, n_mid = 0, n_hub = 0;
+};
+
+struct Shard;  // defined in shards.hip
+
+}  // namespace lkg
+
+struct logoskg_graph {
+    int device = 0;
+    int32_t E = 0, R = 0;
+    int64_t Epad = 0;  // E rounded up to a multiple of 64
+    int64_t T = 0;
+    int hub_min = lkg::kDefaultHubMin;
+    int num_shards = 1;
+
+    // subject-sorted CSR (SUB): row s -> objects / relations of its triples
+    uint32_t *out_off = nullptr;  // [E+1]
+    int32_t *out_obj = nullptr;   // [T]
+    uint16_t *out_rel = nullptr;  // [T]
+    // object-sorted CSR (OBJ): row v -> subjects / relations / edge ids of its triples
+    uint32_t *in_off = nullptr;  // [E+1]
+    int32_t *in_sub = nullptr;   // [T]
+    uint16_t *in_rel = nullptr;  // [T]
+    int32_t *in_eid = nullptr;   // [T]
+    lkg::RowClasses in_rows;     // static row lists for the pull kernels
+    int64_t n_out_rows = 0, n_out_hubs = 0;
+
+    // frontier work lists rebuilt every hop from the level's active bitmap
+    int32_t *fr_tail = nullptr, *fr_mid = nullptr, *fr_hub = nullptr;  // [E] each
+    unsigned long long *d_ctr = nullptr;  // device counters (see khop.hip)
+    unsigned long long *h_ctr = nullptr;  // pinned host mirror
+
+    std::vector<int32_t> shard_of;  // host copy of the map P (empty when unsharded)
+    std::vector<int64_t> shard_triples;
+    void *shards = nullptr;  // lkg::ShardSet* when num_shards > 1
+
+    lkg::DevPool pool;
+    size_t static_bytes = 0;
+    size_t pinned_bytes = 0;
+};
+
+struct logoskg_result {
+    logoskg_graph *g = nullptr;
+    int Q = 0, k = 0, W = 0;
+    int64_t Epad = 0;
+    bool has_mask = false;
+    bool has_counts = false;
+    unsigned long long *visited = nullptr;  // [Epad][W]
+    unsigned long long *levels = nullptr;   // [k+1][Epad][W]
+    uint32_t *act = nullptr;      // [k+1][Epad/32]: entity has a non-zero line in that level
+    unsigned long long *allow = nullptr;    // [R][W] relation -> queries that may follow it
+    // result-list bookkeeping (count pass)
+    uint8_t *tile_cnt = nullptr;    // [ntiles][64W]
+    uint16_t *tile_base = nullptr;  // [ntiles][64W] prefix inside the super tile
+    uint32_t *super_base = nullptr; // [nsuper][64W] prefix over super tiles
+    long long *d_reached_off = nullptr;  // [64W+1]
+    std::vector<int64_t> reached_off;  // host copy [Q+1]
+    std::vector<logoskg_hop_stats> stats;
+    long long *hub_slot = nullptr;    // [n_in_hub][64W] scratch of the last fetch
+};
+
+namespace lkg {
+
+// device-side helpers -------------------------------------------------------
+__device__ __forceinline__ int lane() { return (int)__lane_id(); }
+
+// True when any lane of the caller's aligned W-lane group has `p` set.  Every
+// lane of the group must be active at the call.
+template <int W>
+__device__ __forceinline__ bool group_any(bool p) {
+    if constexpr (W == 1) {
+        return p;
+    } else {
+        unsigned long long b = __ballot(p);
+        int g0 = lane() & ~(W - 1);
+        return ((b >> g0) & ((1ull << W) - 1ull)) != 0ull;
+    }
+}
+
+__device__ __forceinline__ bool wave_any(bool p) { return __ballot(p) != 0ull; }
+
+__device__ __forceinline__ unsigned long long shfl64(unsigned long long v, int src) {
+    int lo = __shfl((int)(unsigned)(v & 0xffffffffull), src);
+    int hi = __shfl((int)(unsigned)(v >> 32), src);
+    return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+}
+
+__device__ __forceinline__ unsigned long long shfl_xor64(unsigned long long v, int m) {
+    int lo = __shfl_xor((int)(unsigned)(v & 0xffffffffull), m);
+    int hi = __shfl_xor((int)(unsigned)(v >> 32), m);
+    return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+}
+
+__device__ __forceinline__ long long wave_sum(long long v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += (long long)shfl_xor64((unsigned long long)v, m);
+    return v;
+}
+
+// bits of word w (0..W-1) that belong to queries < Q
+__device__ __forceinline__ unsigned long long query_bits(int Q, int w) {
+    int lo = w * 64;
+    if (Q >= lo + 64) return ~0ull;
+    if (Q <= lo) return 0ull;
+    return (1ull << (Q - lo)) - 1ull;
+}
+
+inline int words_for_queries(int Q) { return Q <= 64 ? 1 : (Q <= 256 ? 4 : 16); }
+
+logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
+                               logoskg_hop_stats *hs);
+void free_shards(logoskg_graph *g);
+logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel,
+                            const int32_t *obj, const logoskg_build_opts *opts);
+
+}  // namespace lkg

@@ -1,0 +1,648 @@
+// logoskg_khop: batched k-hop expansion on one gfx950 GPU.
+//
+// State (paper Sec. 3.3): the query vectors q^(h) of up to 1024 queries are
+// packed entity-major, W uint64 words per entity (bit j%64 of word j/64 =
+// query j).  level[h] holds the bits that become set for the first time at hop
+// h, visited = OR of all levels so far, act[h] has one bit per entity whose
+// level[h] line is non-zero.
+//
+// One hop (Eq. 4, q.SUB.OBJ with the relation whitelist applied to the active
+// triples of Eq. 5) is evaluated in one of two directions:
+//   push: for every subject row in the frontier, OR its line into the lines of
+//         its objects (atomicOr), skipping bits already visited;
+//   pull: for every object row that still misses some query, OR the lines of
+//         its subjects that are in the frontier, stopping as soon as nothing
+//         is missing; no atomics, and visited is updated in the same kernel.
+// Both give the same level[h]; rows are handled by a W-lane group (degree <=
+// 32), a wavefront (up to hub_min) or a block (hubs).
+#include <algorithm>
+
+#include "common.h"
+
+namespace lkg {
+
+// indices into logoskg_graph::d_ctr
+enum {
+    C_NTAIL = 0, C_NMID = 1, C_NHUB = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
+    C_ROWS = 8, C_EDGES = 9, C_LINES = 10, C_TOTAL = 16
+};
+
+// ---------------------------------------------------------------- seeds, mask table
+__global__ void k_seed(int Q, long long num_seeds, const long long *__restrict__ seed_off,
+                       const int32_t *__restrict__ seeds, int32_t E, int W,
+                       unsigned long long *level0, unsigned long long *visited, uint32_t *act0,
+                       unsigned long long *ctr) {
+    int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= Q) return;
+    long long a = seed_off[q], b = seed_off[q + 1];
+    if (a < 0 || b < a || b > num_seeds || (q == 0 && a != 0) || (q == Q - 1 && b != num_seeds)) {
+        atomicOr(&ctr[C_ERR], 1ull);
+        return;
+    }
+    unsigned long long bit = 1ull << (q & 63);
+    for (long long i = a; i < b; ++i) {
+        int32_t e = seeds[i];
+        if ((uint32_t)e >= (uint32_t)E) {
+            atomicOr(&ctr[C_ERR], 2ull);
+            continue;
+        }
+        size_t idx = (size_t)e * W + (q >> 6);
+        atomicOr(&level0[idx], bit);
+        atomicOr(&visited[idx], bit);
+        atomicOr(&act0[e >> 5], 1u << (e & 31));
+    }
+}
+
+// allow[r][w]: bit b set when query 64w+b may follow relation r (the vector REL.m
+// of every query, transposed so that one triple's relation selects a whole line).
+__global__ void k_allow(int Q, int R, int W, int rel_words, const unsigned long long *__restrict__ rel_mask,
+                        unsigned long long *allow) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= R * W) return;
+    int r = i / W, w = i % W;
+    unsigned long long v = 0;
+    for (int b = 0; b < 64; ++b) {
+        int q = w * 64 + b;
+        if (q < Q && ((rel_mask[(size_t)q * rel_words + (r >> 6)] >> (r & 63)) & 1ull)) v |= 1ull << b;
+    }
+    allow[i] = v;
+}
+
+// ---------------------------------------------------------------- frontier census
+__device__ __forceinline__ int wave_excl_scan(int v, int &total) {
+    int x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d);
+        if (lane() >= d) x += y;
+    }
+    total = __shfl(x, 63);
+    return x - v;
+}
+
+// Turns the active bitmap of a level into three lists of subject rows (by
+// out-degree class) and the counters the host needs to pick the direction.
+__global__ void k_census(const uint32_t *__restrict__ act, long long nwords,
+                         const uint32_t *__restrict__ out_off, int hub_min, int write_lists,
+                         int32_t *list_tail, int32_t *list_mid, int32_t *list_hub,
+                         unsigned long long *ctr) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t word = i < nwords ? act[i] : 0u;
+    int ct = 0, cm = 0, ch = 0;
+    long long deg_sum = 0;
+    for (uint32_t m = word; m; m &= m - 1) {
+        int e = (int)(i * 32) + (__ffs((int)m) - 1);
+        uint32_t d = out_off[e + 1] - out_off[e];
+        deg_sum += d;
+        if (d >= (uint32_t)hub_min) ++ch;
+        else if (d > (uint32_t)kTailMaxDegree) ++cm;
+        else if (d > 0) ++ct;
+    }
+    int tt, tm, th;
+    int pt = wave_excl_scan(ct, tt), pm = wave_excl_scan(cm, tm), ph = wave_excl_scan(ch, th);
+    long long es = wave_sum(deg_sum);
+    long long na = wave_sum((long long)__popc(word));
+    unsigned long long bt = 0, bm = 0, bh = 0;
+    if (lane() == 0) {
+        if (tt) bt = atomicAdd(&ctr[C_NTAIL], (unsigned long long)tt);
+        if (tm) bm = atomicAdd(&ctr[C_NMID], (unsigned long long)tm);
+        if (th) bh = atomicAdd(&ctr[C_NHUB], (unsigned long long)th);
+        if (es) atomicAdd(&ctr[C_FEDGES], (unsigned long long)es);
+        if (na) atomicAdd(&ctr[C_NACTIVE], (unsigned long long)na);
+    }
+    if (!write_lists) return;
+    bt = shfl64(bt, 0) + pt;
+    bm = shfl64(bm, 0) + pm;
+    bh = shfl64(bh, 0) + ph;
+    for (uint32_t m = word; m; m &= m - 1) {
+        int e = (int)(i * 32) + (__ffs((int)m) - 1);
+        uint32_t d = out_off[e + 1] - out_off[e];
+        if (d >= (uint32_t)hub_min) list_hub[bh++] = e;
+        else if (d > (uint32_t)kTailMaxDegree) list_mid[bm++] = e;
+        else if (d > 0) list_tail[bt++] = e;
+    }
+}
+
+// ---------------------------------------------------------------- push
+__device__ __forceinline__ void mark_active(uint32_t *act, int e) {
+    uint32_t bit = 1u << (e & 31);
+    if (!(act[e >> 5] & bit)) atomicOr(&act[e >> 5], bit);
+}
+
+// One W-lane group per frontier row; its edges are walked one after another.
+template <int W, bool MASK>
+__global__ void __launch_bounds__(256)
+k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restrict__ ctr,
+            const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
+            const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
+            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
+            unsigned long long *cur, uint32_t *act_cur) {
+    long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
+    int lw = threadIdx.x & (W - 1);
+    long long n = (long long)ctr[C_NTAIL];
+    uint32_t lo = 0, hi = 0;
+    unsigned long long line = 0;
+    if (gidx < n) {
+        int s = rows[gidx];
+        lo = off[s];
+        hi = off[s + 1];
+        line = prev[(size_t)s * W + lw];
+    }
+    for (uint32_t j = lo; j < hi; ++j) {
+        int o = obj[j];
+        unsigned long long m = line;
+        if (MASK) m &= allow[(size_t)rel[j] * W + lw];
+        if (m) m &= ~visited[(size_t)o * W + lw];
+        if (m) atomicOr(&cur[(size_t)o * W + lw], m);
+        bool any = group_any<W>(m != 0);
+        if (any && lw == 0) mark_active(act_cur, o);
+    }
+}
+
+// 64 consecutive edges of one row, handled by a whole wavefront: every lane
+// loads one edge, then the 64/W groups take the edges in turn.
+template <int W, bool MASK>
+__device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned long long line,
+                                           const int32_t *__restrict__ obj, const uint16_t *__restrict__ rel,
+                                           const unsigned long long *__restrict__ allow,
+                                           const unsigned long long *__restrict__ visited,
+                                           unsigned long long *cur, uint32_t *act_cur) {
+    constexpr int GPW = 64 / W;
+    int lw = lane() & (W - 1), g = lane() / W;
+    uint32_t j = j0 + lane();
+    int o = -1, r = 0;
+    if (j < hi) {
+        o = obj[j];
+        if (MASK) r = rel[j];
+    }
+    int n = (int)min((uint32_t)64, hi - j0);
+    if constexpr (W == 1) {
+        if (o >= 0) {
+            unsigned long long m = line;
+            if (MASK) m &= allow[r];
+            if (m) m &= ~visited[o];
+            if (m) {
+                atomicOr(&cur[o], m);
+                mark_active(act_cur, o);
+            }
+        }
+    } else {
+        for (int i = 0; i < n; i += GPW) {
+            int idx = i + g;
+            int oc = __shfl(o, idx & 63);
+            int rc = MASK ? __shfl(r, idx & 63) : 0;
+            if (idx < n) {
+                unsigned long long m = line;
+                if (MASK) m &= allow[(size_t)rc * W + lw];
+                if (m) m &= ~visited[(size_t)oc * W + lw];
+                if (m) atomicOr(&cur[(size_t)oc * W + lw], m);
+                bool any = group_any<W>(m != 0);
+                if (any && lw == 0) mark_active(act_cur, oc);
+            }
+        }
+    }
+}
+
+// One wavefront per frontier row (mid class) or one block per row (hubs).
+template <int W, bool MASK, bool HUB>
+__global__ void __launch_bounds__(512)
+k_push_coop(const int32_t *__restrict__ rows, const unsigned long long *__restrict__ ctr,
+            const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
+            const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
+            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
+            unsigned long long *cur, uint32_t *act_cur) {
+    int nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
+    long long row = HUB ? (long long)blockIdx.x : (long long)blockIdx.x * nw + wave;
+    long long n = (long long)ctr[HUB ? C_NHUB : C_NMID];
+    if (row >= n) return;
+    int s = rows[row];
+    int lw = lane() & (W - 1);
+    unsigned long long line = prev[(size_t)s * W + lw];
+    uint32_t lo = off[s], hi = off[s + 1];
+    uint32_t step = HUB ? 64u * nw : 64u;
+    for (uint32_t j0 = lo + (HUB ? 64u * wave : 0u); j0 < hi; j0 += step)
+        push_chunk<W, MASK>(j0, hi, line, obj, rel, allow, visited, cur, act_cur);
+}
+
+// visited |= level[h] on the lines the push kernels touched.
+__global__ void k_update_visited(long long nwords64, int W, const uint32_t *__restrict__ act_cur,
+                                 const unsigned long long *__restrict__ cur, unsigned long long *visited) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nwords64) return;
+    long long e = i / W;
+    if ((act_cur[e >> 5] >> (e & 31)) & 1u) visited[i] |= cur[i];
+}
+
+// ---------------------------------------------------------------- pull
+// Removes up to 64/W candidates from the (wave-uniform) mask and returns the
+// lane position of the one that belongs to the caller's group, or -1.
+template <int W>
+__device__ __forceinline__ int take_candidates(unsigned long long &rest) {
+    constexpr int GPW = 64 / W;
+    int g = lane() / W, mine = -1;
+#pragma unroll
+    for (int t = 0; t < GPW; ++t) {
+        if (rest) {
+            int p = __ffsll((long long)rest) - 1;
+            rest &= rest - 1;
+            if (t == g) mine = p;
+        }
+    }
+    return mine;
+}
+
+// 64 consecutive in-edges of one object row: lanes test whether their edge's
+// subject is in the frontier, then the groups gather the frontier lines of the
+// candidates.  acc collects (per group) the OR of the gathered words.
+template <int W, bool MASK>
+__device__ __forceinline__ int pull_chunk(uint32_t j0, uint32_t hi, const int32_t *__restrict__ in_sub,
+                                          const uint16_t *__restrict__ in_rel,
+                                          const uint32_t *__restrict__ act_prev,
+                                          const unsigned long long *__restrict__ prev,
+                                          const unsigned long long *__restrict__ allow,
+                                          unsigned long long &acc) {
+    uint32_t j = j0 + lane();
+    int s = 0, r = 0;
+    bool cand = false;
+    if (j < hi) {
+        s = in_sub[j];
+        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+        if (MASK && cand) r = in_rel[j];
+    }
+    unsigned long long cm = __ballot(cand);
+    int ncand = __popcll(cm);
+    if constexpr (W == 1) {
+        if (cand) {
+            unsigned long long ln = prev[s];
+            if (MASK) ln &= allow[r];
+            acc |= ln;
+        }
+    } else {
+        int lw = lane() & (W - 1);
+        while (cm) {
+            int p = take_candidates<W>(cm);
+            int sc = __shfl(s, p < 0 ? 0 : p);
+            int rc = MASK ? __shfl(r, p < 0 ? 0 : p) : 0;
+            if (p >= 0) {
+                unsigned long long ln = prev[(size_t)sc * W + lw];
+                if (MASK) ln &= allow[(size_t)rc * W + lw];
+                acc |= ln;
+            }
+        }
+    }
+    return ncand;
+}
+
+template <int W>
+__device__ __forceinline__ unsigned long long or_across_groups(unsigned long long acc) {
+#pragma unroll
+    for (int m = W; m < 64; m <<= 1) acc |= shfl_xor64(acc, m);
+    return acc;
+}
+
+__device__ __forceinline__ void add_stats(unsigned long long *stats, long long rows, long long edges,
+                                          long long lines) {
+    // called by every lane of a wavefront with per-lane partial counts
+    rows = wave_sum(rows);
+    edges = wave_sum(edges);
+    lines = wave_sum(lines);
+    if (lane() == 0) {
+        if (rows) atomicAdd(&stats[C_ROWS], (unsigned long long)rows);
+        if (edges) atomicAdd(&stats[C_EDGES], (unsigned long long)edges);
+        if (lines) atomicAdd(&stats[C_LINES], (unsigned long long)lines);
+    }
+}
+
+// One W-lane group per object row (in-degree <= 32).
+template <int W, bool MASK>
+__global__ void __launch_bounds__(256)
+k_pull_tail(const int32_t *__restrict__ rows, long long n, int Q, const uint32_t *__restrict__ off,
+            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
+            const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
+            const unsigned long long *__restrict__ prev, unsigned long long *visited,
+            unsigned long long *cur, uint32_t *act_cur, unsigned long long *stats) {
+    long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
+    int lw = threadIdx.x & (W - 1);
+    uint32_t lo = 0, hi = 0;
+    int v = 0;
+    unsigned long long vis = 0, need = 0, acc = 0;
+    if (gidx < n) {
+        v = rows[gidx];
+        vis = visited[(size_t)v * W + lw];
+        need = ~vis & query_bits(Q, lw);
+        if (group_any<W>(need != 0)) {
+            lo = off[v];
+            hi = off[v + 1];
+        }
+    }
+    long long n_edges = 0, n_lines = 0;
+    for (uint32_t j = lo; j < hi; ++j) {
+        int s = in_sub[j];
+        ++n_edges;
+        if (!((act_prev[s >> 5] >> (s & 31)) & 1u)) continue;
+        unsigned long long ln = prev[(size_t)s * W + lw];
+        if (MASK) ln &= allow[(size_t)in_rel[j] * W + lw];
+        acc |= ln;
+        ++n_lines;
+        if (!group_any<W>((need & ~acc) != 0)) break;
+    }
+    unsigned long long nw = acc & need;
+    if (hi > lo && group_any<W>(nw != 0)) {
+        cur[(size_t)v * W + lw] = nw;
+        visited[(size_t)v * W + lw] = vis | nw;
+        if (lw == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
+    }
+    if (stats) {
+        bool lead = (lw == 0);
+        add_stats(stats, (lead && hi > lo) ? 1 : 0, lead ? n_edges : 0, lead ? n_lines : 0);
+    }
+}
+
+// One wavefront per object row (mid class) or one block per row (hubs).
+template <int W, bool MASK, bool HUB>
+__global__ void __launch_bounds__(512)
+k_pull_coop(const int32_t *__restrict__ rows, long long n, int Q, const uint32_t *__restrict__ off,
+            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
+            const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
+            const unsigned long long *__restrict__ prev, unsigned long long *visited,
+            unsigned long long *cur, uint32_t *act_cur, unsigned long long *stats) {
+    __shared__ unsigned long long sacc[16];
+    int nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
+    long long row = HUB ? (long long)blockIdx.x : (long long)blockIdx.x * nw + wave;
+    bool live = row < n;  // wave-uniform; block-uniform when HUB
+    int lw = lane() & (W - 1);
+    int v = live ? rows[row] : 0;
+    unsigned long long vis = 0, need = 0, acc = 0;
+    if (live) {
+        vis = visited[(size_t)v * W + lw];
+        need = ~vis & query_bits(Q, lw);
+    }
+    bool work = wave_any(need != 0);  // same on every wave of a hub block
+    if (HUB) {
+        if (threadIdx.x < 16) sacc[threadIdx.x] = 0;
+        __syncthreads();
+    }
+    long long n_edges = 0, n_lines = 0;
+    if (work) {
+        uint32_t lo = off[v], hi = off[v + 1];
+        uint32_t step = HUB ? 64u * nw : 64u;
+        int it = 0;
+        for (uint32_t j0 = lo + (HUB ? 64u * wave : 0u); j0 < hi; j0 += step, ++it) {
+            n_lines += pull_chunk<W, MASK>(j0, hi, in_sub, in_rel, act_prev, prev, allow, acc);
+            n_edges += min((uint32_t)64, hi - j0);
+            acc = or_across_groups<W>(acc);
+            if (HUB && (it & 3) == 3) {  // fold what the other waves found
+                if (lane() < W) acc |= atomicOr(&sacc[lane()], acc);
+                acc = shfl64(acc, lw);
+            }
+            if (!wave_any((need & ~acc) != 0)) break;
+        }
+    }
+    if (HUB) {
+        if (work && lane() < W) atomicOr(&sacc[lane()], acc);
+        __syncthreads();
+        acc = sacc[lw];
+    }
+    if (work && (!HUB || wave == 0)) {
+        unsigned long long nb = acc & need;
+        if (wave_any(nb != 0)) {
+            if (lane() < W) {
+                cur[(size_t)v * W + lane()] = nb;
+                visited[(size_t)v * W + lane()] = vis | nb;
+            }
+            if (lane() == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
+        }
+    }
+    if (stats) {
+        bool lead = lane() == 0;
+        add_stats(stats, (lead && work && (!HUB || wave == 0)) ? 1 : 0, lead ? n_edges : 0,
+                  lead ? n_lines : 0);
+    }
+}
+
+// ---------------------------------------------------------------- host side
+template <int W, bool MASK>
+static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
+                        hipStream_t st) {
+    const size_t plane = (size_t)r->Epad * W;
+    const unsigned long long *prev = r->levels + plane * (h - 1);
+    unsigned long long *cur = r->levels + plane * h;
+    uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
+    long long nt = (long long)hc[C_NTAIL], nm = (long long)hc[C_NMID], nh = (long long)hc[C_NHUB];
+    if (nt > 0) {
+        long long threads = nt * W;
+        k_push_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
+            g->fr_tail, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+    }
+    if (nm > 0)
+        k_push_coop<W, MASK, false><<<dim3((unsigned)((nm + 3) / 4)), dim3(256), 0, st>>>(
+            g->fr_mid, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+    if (nh > 0)
+        k_push_coop<W, MASK, true><<<dim3((unsigned)nh), dim3(512), 0, st>>>(
+            g->fr_hub, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+    long long nwords = (long long)plane;
+    k_update_visited<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(nwords, W, act_cur, cur,
+                                                                                  r->visited);
+}
+
+template <int W, bool MASK>
+static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_stats, hipStream_t st) {
+    const size_t plane = (size_t)r->Epad * W;
+    const unsigned long long *prev = r->levels + plane * (h - 1);
+    unsigned long long *cur = r->levels + plane * h;
+    const uint32_t *act_prev = r->act + (size_t)(r->Epad / 32) * (h - 1);
+    uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
+    unsigned long long *stats = want_stats ? g->d_ctr : nullptr;
+    const RowClasses &rc = g->in_rows;
+    if (rc.n_hub > 0)
+        k_pull_coop<W, MASK, true><<<dim3((unsigned)rc.n_hub), dim3(512), 0, st>>>(
+            rc.hub, rc.n_hub, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
+            act_cur, stats);
+    if (rc.n_mid > 0)
+        k_pull_coop<W, MASK, false><<<dim3((unsigned)((rc.n_mid + 3) / 4)), dim3(256), 0, st>>>(
+            rc.mid, rc.n_mid, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
+            act_cur, stats);
+    if (rc.n_tail > 0) {
+        long long threads = rc.n_tail * W;
+        k_pull_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
+            rc.tail, rc.n_tail, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
+            act_cur, stats);
+    }
+}
+
+template <int W>
+static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
+                    const unsigned long long *hc, hipStream_t st) {
+    if (pull) {
+        if (r->has_mask) launch_pull<W, true>(g, r, h, want_stats, st);
+        else launch_pull<W, false>(g, r, h, want_stats, st);
+    } else {
+        if (r->has_mask) launch_push<W, true>(g, r, h, hc, st);
+        else launch_push<W, false>(g, r, h, hc, st);
+    }
+}
+
+void launch_resident_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
+                         const unsigned long long *hc, hipStream_t st) {
+    switch (r->W) {
+        case 1: run_hop<1>(g, r, h, pull, want_stats, hc, st); break;
+        case 4: run_hop<4>(g, r, h, pull, want_stats, hc, st); break;
+        default: run_hop<16>(g, r, h, pull, want_stats, hc, st); break;
+    }
+}
+
+// Census of level h's active bitmap; leaves the counters in g->h_ctr (stream synchronised).
+static logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, bool write_lists, hipStream_t st) {
+    LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 5 * sizeof(unsigned long long), st));
+    long long nwords = r->Epad / 32;
+    k_census<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(
+        r->act + (size_t)nwords * h, nwords, g->out_off, g->hub_min, write_lists ? 1 : 0, g->fr_tail,
+        g->fr_mid, g->fr_hub, g->d_ctr);
+    LKG_HIP(hipGetLastError());
+    LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    LKG_HIP(hipStreamSynchronize(st));
+    return LOGOSKG_OK;
+}
+
+logoskg_status count_reached(logoskg_result *r, hipStream_t st);  // result.hip
+
+}  // namespace lkg
+
+using namespace lkg;
+
+extern "C" void logoskg_result_free(logoskg_result *r) {
+    if (!r) return;
+    logoskg_graph *g = r->g;
+    (void)hipSetDevice(g->device);
+    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->tile_cnt, r->tile_base,
+                    r->super_base, r->d_reached_off, r->hub_slot};
+    for (void *p : ptrs) g->pool.release(p);
+    delete r;
+}
+
+extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_batch *b, logoskg_result **out) {
+    if (!g || !b || !out) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    *out = nullptr;
+    if (b->struct_size != sizeof(logoskg_query_batch)) {
+        set_error("logoskg_query_batch.struct_size is %u, expected %zu", b->struct_size, sizeof(*b));
+        return LOGOSKG_EINVAL;
+    }
+    if (b->num_queries < 1 || b->num_queries > LOGOSKG_MAX_QUERIES || b->k < 0 || b->k > LOGOSKG_MAX_K ||
+        b->num_seeds < 0 || !b->seed_off || (b->num_seeds > 0 && !b->seeds)) {
+        set_error("bad query batch: Q=%d k=%d num_seeds=%lld", b->num_queries, b->k, (long long)b->num_seeds);
+        return LOGOSKG_EINVAL;
+    }
+    uint32_t dir = b->flags & LOGOSKG_DIR_MASK;
+    if (dir == 3u) { set_error("bad direction flags"); return LOGOSKG_EINVAL; }
+    if (g->num_shards > 1 && dir == LOGOSKG_DIR_PULL) {
+        set_error("pull is only available on resident graphs");
+        return LOGOSKG_EINVAL;
+    }
+    LKG_HIP(hipSetDevice(g->device));
+    hipStream_t st = (hipStream_t)b->stream;
+
+    logoskg_result *r = new (std::nothrow) logoskg_result();
+    if (!r) { set_error("out of host memory"); return LOGOSKG_ENOMEM; }
+    r->g = g;
+    r->Q = b->num_queries;
+    r->k = b->k;
+    r->W = words_for_queries(r->Q);
+    r->Epad = g->Epad;
+    r->has_mask = b->rel_mask != nullptr;
+    r->stats.assign((size_t)r->k, logoskg_hop_stats{});
+    const int W = r->W, k = r->k;
+    const size_t plane = (size_t)r->Epad * W;
+    const size_t actw = (size_t)r->Epad / 32;
+    logoskg_status s;
+    auto fail = [&](logoskg_status e) { logoskg_result_free(r); return e; };
+    if ((s = g->pool.alloc((void **)&r->visited, plane * 8)) != LOGOSKG_OK) return fail(s);
+    if ((s = g->pool.alloc((void **)&r->levels, plane * 8 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
+    if ((s = g->pool.alloc((void **)&r->act, actw * 4 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
+    if (r->has_mask && (s = g->pool.alloc((void **)&r->allow, (size_t)g->R * W * 8)) != LOGOSKG_OK) return fail(s);
+
+#define KH(call)                                  \
+    do {                                          \
+        logoskg_status s2_ = [&]() -> logoskg_status { LKG_HIP(call); return LOGOSKG_OK; }(); \
+        if (s2_ != LOGOSKG_OK) return fail(s2_);  \
+    } while (0)
+
+    KH(hipMemsetAsync(r->visited, 0, plane * 8, st));
+    KH(hipMemsetAsync(r->levels, 0, plane * 8 * (size_t)(k + 1), st));
+    KH(hipMemsetAsync(r->act, 0, actw * 4 * (size_t)(k + 1), st));
+    KH(hipMemsetAsync(g->d_ctr, 0, 64 * sizeof(unsigned long long), st));
+    if (r->has_mask) {
+        int n = g->R * W;
+        k_allow<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(r->Q, g->R, W, (g->R + 63) / 64,
+                                                             (const unsigned long long *)b->rel_mask,
+                                                             (unsigned long long *)r->allow);
+    }
+    k_seed<<<dim3((r->Q + 255) / 256), dim3(256), 0, st>>>(r->Q, (long long)b->num_seeds,
+                                                           (const long long *)b->seed_off, b->seeds, g->E, W,
+                                                           (unsigned long long *)r->levels,
+                                                           (unsigned long long *)r->visited, r->act, g->d_ctr);
+    KH(hipGetLastError());
+    bool want_stats = true;
+    if ((s = census(g, r, 0, k > 0, st)) != LOGOSKG_OK) return fail(s);
+    if (g->h_ctr[C_ERR]) {
+        set_error("seed_off / seeds are inconsistent or out of range (device check, code %llu)", g->h_ctr[C_ERR]);
+        return fail(LOGOSKG_EINVAL);
+    }
+    for (int h = 1; h <= k; ++h) {
+        logoskg_hop_stats &hs = r->stats[h - 1];
+        long long rows = (long long)(g->h_ctr[C_NTAIL] + g->h_ctr[C_NMID] + g->h_ctr[C_NHUB]);
+        long long fedges = (long long)g->h_ctr[C_FEDGES];
+        if (rows == 0) break;  // nothing can be reached any more: the remaining levels stay empty
+        hs.active_rows = rows;
+        hs.frontier_edges = fedges;
+        if (g->num_shards > 1) {
+            hs.direction = LOGOSKG_DIR_PUSH;
+            if ((s = run_sharded_hop(g, r, h, st, &hs)) != LOGOSKG_OK) return fail(s);
+            hs.edges_scanned = fedges;
+            hs.lines_gathered = fedges;
+        } else {
+            bool pull = dir == LOGOSKG_DIR_PULL || (dir == LOGOSKG_DIR_AUTO && fedges * 12 > g->T);
+            hs.direction = pull ? LOGOSKG_DIR_PULL : LOGOSKG_DIR_PUSH;
+            hs.shards_touched = 1;
+            unsigned long long hc[C_TOTAL];
+            memcpy(hc, g->h_ctr, sizeof(hc));
+            KH(hipMemsetAsync(g->d_ctr + C_ROWS, 0, 3 * sizeof(unsigned long long), st));
+            launch_resident_hop(g, r, h, pull, want_stats, hc, st);
+            KH(hipGetLastError());
+        }
+        if ((s = census(g, r, h, h < k, st)) != LOGOSKG_OK) return fail(s);
+        hs.entities_reached = (long long)g->h_ctr[C_NACTIVE];
+        if (hs.direction == LOGOSKG_DIR_PULL) {
+            hs.rows_scanned = (long long)g->h_ctr[C_ROWS];
+            hs.edges_scanned = (long long)g->h_ctr[C_EDGES];
+            hs.lines_gathered = (long long)g->h_ctr[C_LINES];
+        } else if (g->num_shards <= 1) {
+            hs.edges_scanned = fedges;
+            hs.lines_gathered = fedges;
+        }
+    }
+    if (!(b->flags & LOGOSKG_NO_COUNTS)) {
+        if ((s = count_reached(r, st)) != LOGOSKG_OK) return fail(s);
+    }
+#undef KH
+    *out = r;
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_result_get_info(const logoskg_result *r, logoskg_result_info *o) {
+    if (!r || !o) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    o->num_queries = r->Q;
+    o->k = r->k;
+    o->words_per_entity = r->W;
+    o->num_levels = r->k + 1;
+    o->padded_entities = r->Epad;
+    o->visited = (const uint64_t *)r->visited;
+    o->levels = (const uint64_t *)r->levels;
+    o->total_reached = r->has_counts ? r->reached_off.back() : -1;
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_result_hop_stats(const logoskg_result *r, logoskg_hop_stats *o) {
+    if (!r || (r->k > 0 && !o)) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    for (int i = 0; i < r->k; ++i) o[i] = r->stats[(size_t)i];
+    return LOGOSKG_OK;
+}

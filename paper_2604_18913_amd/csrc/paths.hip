@@ -1,0 +1,106 @@
+// logoskg_paths: shortest-path listing from the level planes (paper Sec. 3.3,
+// "Path reconstruction", Eq. 5-7).  A triple t is on a shortest path of query q
+// to its object when its subject sits exactly one hop closer to the seeds and
+// q allows its relation; chaining such triples backward from the target always
+// ends at a seed, so a depth-first walk over the object rows (edge ids
+// ascending) lists the paths in (t_d, t_{d-1}, .., t_1) order and can stop at
+// max_paths.
+#include "common.h"
+
+namespace lkg {
+
+__global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long long plane,
+                        const unsigned long long *__restrict__ levels,
+                        const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ in_off,
+                        const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
+                        const int32_t *__restrict__ in_eid, const int32_t *__restrict__ query_idx,
+                        const int32_t *__restrict__ target, int max_paths, int32_t *path_count,
+                        int32_t *path_edges, int32_t *stk_vertex, uint32_t *stk_pos, int32_t *stk_edge) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_pairs) return;
+    int32_t *out = path_edges + (size_t)i * max_paths * k;
+    for (long long x = 0; x < (long long)max_paths * k; ++x) out[x] = -1;
+    int q = query_idx[i], v = target[i];
+    path_count[i] = 0;
+    if ((uint32_t)q >= (uint32_t)Q || (uint32_t)v >= (uint32_t)E) return;
+    const int w = q >> 6;
+    const unsigned long long bit = 1ull << (q & 63);
+    int d = -1;
+    for (int h = 0; h <= k; ++h)
+        if (levels[(size_t)h * plane + (size_t)v * W + w] & bit) { d = h; break; }
+    if (d < 0) return;
+    if (d == 0) { path_count[i] = 1; return; }
+    // explicit stack, entry l (1..d) = the vertex at hop l of the partial path, the next
+    // in-edge position to try for it, and the edge chosen into it
+    int32_t *sv = stk_vertex + (size_t)i * k - 1;
+    uint32_t *sp = stk_pos + (size_t)i * k - 1;
+    int32_t *se = stk_edge + (size_t)i * k - 1;
+    int found = 0, l = d;
+    sv[d] = v;
+    sp[d] = in_off[v];
+    while (l <= d && found < max_paths) {
+        int x = sv[l];
+        uint32_t j = sp[l], hi = in_off[x + 1];
+        bool descended = false;
+        const unsigned long long *lv = levels + (size_t)(l - 1) * plane;
+        for (; j < hi; ++j) {
+            int s = in_sub[j];
+            if (!(lv[(size_t)s * W + w] & bit)) continue;
+            if (allow && !(allow[(size_t)in_rel[j] * W + w] & bit)) continue;
+            se[l] = in_eid[j];
+            if (l == 1) {
+                int32_t *row = out + (size_t)found * k;
+                for (int a = 1; a <= d; ++a) row[a - 1] = se[a];
+                if (++found >= max_paths) break;
+            } else {
+                sp[l] = j + 1;
+                sv[l - 1] = s;
+                sp[l - 1] = in_off[s];
+                --l;
+                descended = true;
+                break;
+            }
+        }
+        if (!descended) ++l;  // this vertex's row is exhausted: back to the vertex after it
+    }
+    path_count[i] = found;
+}
+
+}  // namespace lkg
+
+using namespace lkg;
+
+extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                        const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                                        int32_t *path_count, int32_t *path_edges, void *stream) {
+    if (!g || !r || r->g != g) { set_error("graph / result mismatch"); return LOGOSKG_EINVAL; }
+    if (n_pairs < 0 || max_paths < 1 || max_paths > LOGOSKG_MAX_PATHS) {
+        set_error("bad n_pairs / max_paths");
+        return LOGOSKG_EINVAL;
+    }
+    if (n_pairs == 0) return LOGOSKG_OK;
+    if (!query_idx || !target || !path_count || (r->k > 0 && !path_edges)) {
+        set_error("NULL argument");
+        return LOGOSKG_EINVAL;
+    }
+    if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
+    LKG_HIP(hipSetDevice(g->device));
+    hipStream_t st = (hipStream_t)stream;
+    const int k = r->k;
+    void *ws = nullptr;
+    size_t per = (size_t)n_pairs * (size_t)std::max(k, 1) * 4;
+    LKG_TRY(g->pool.alloc(&ws, per * 3));
+    int32_t *sv = (int32_t *)ws;
+    uint32_t *sp = (uint32_t *)((char *)ws + per);
+    int32_t *se = (int32_t *)((char *)ws + 2 * per);
+    k_paths<<<dim3((unsigned)((n_pairs + 127) / 128)), dim3(128), 0, st>>>(
+        n_pairs, r->Q, k, r->W, g->E, r->Epad * r->W, (const unsigned long long *)r->levels,
+        r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, g->in_sub, g->in_rel, g->in_eid,
+        query_idx, target, max_paths, path_count, path_edges, sv, sp, se);
+    hipError_t e = hipGetLastError();
+    hipError_t e2 = hipStreamSynchronize(st);  // the workspace goes back to the pool below
+    g->pool.release(ws);
+    LKG_HIP(e);
+    LKG_HIP(e2);
+    return LOGOSKG_OK;
+}

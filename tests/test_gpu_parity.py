@@ -1,0 +1,205 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.  All work is integer, so the
+bar is bit-exact equality."""
+import numpy as np
+import pytest
+
+import kggen
+import oracle
+from helpers import check_invariants
+
+pytestmark = pytest.mark.gpu
+
+
+def lkg():
+    import paper_2604_18913_amd as m
+    return m
+
+
+def run_gpu(w, direction="auto", hub_min_degree=0, k=None, want_traversed=True):
+    m = lkg()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=hub_min_degree)
+    res = g.khop(w.seed_off, w.seeds, w.k if k is None else k, w.rel_mask, direction=direction)
+    off = res.offsets()
+    ent, hop, pred = res.fetch()
+    trav = res.traversed().cpu().numpy() if want_traversed else None
+    out = (off, ent.cpu().numpy(), hop.cpu().numpy(), pred.cpu().numpy(), trav)
+    stats = res.hop_stats()
+    res.close()
+    g.close()
+    return out, stats
+
+
+def run_oracle(w, k=None):
+    return oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds,
+                       w.k if k is None else k, w.rel_mask)
+
+
+def assert_same(got, want, what=""):
+    names = ["reached_off", "entity", "hop", "pred", "traversed"]
+    for n, a, b in zip(names, got, want):
+        if a is None:
+            continue
+        assert a.shape == b.shape, f"{what}: {n} shape {a.shape} vs {b.shape}"
+        if not np.array_equal(a, b):
+            bad = np.nonzero(a.reshape(-1) != b.reshape(-1))[0]
+            raise AssertionError(f"{what}: {n} differs at {bad[:8]} ({bad.size} places): "
+                                 f"{a.reshape(-1)[bad[:8]]} vs {b.reshape(-1)[bad[:8]]}")
+
+
+@pytest.mark.parametrize("direction", ["auto", "push", "pull"])
+def test_config1_tiny(direction):
+    w = kggen.config1()
+    print("case config1", direction, flush=True)
+    got, stats = run_gpu(w, direction)
+    assert_same(got, run_oracle(w), f"config1/{direction}")
+    if direction != "auto":
+        assert all(s["direction"] in (0, {"push": 1, "pull": 2}[direction]) for s in stats)
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("direction", ["push", "pull"])
+def test_random_tiny_masked(seed, direction):
+    w = kggen.random_tiny(200 + seed, E=40 + 37 * seed, T=200 + 90 * seed, R=5, Q=7 + 20 * seed, k=4,
+                          masked=bool(seed % 2))
+    print("case tiny", seed, direction, flush=True)
+    got, _ = run_gpu(w, direction, hub_min_degree=33 + seed)
+    assert_same(got, run_oracle(w), f"tiny{seed}/{direction}")
+
+
+@pytest.mark.parametrize("Q", [1, 64, 65, 200, 256, 257, 1000, 1024])
+def test_query_counts_and_word_widths(Q):
+    w = kggen.config2(0.003, num_queries=Q)
+    print("case Q", Q, flush=True)
+    for direction in ("push", "pull"):
+        got, _ = run_gpu(w, direction, hub_min_degree=64)
+        assert_same(got, run_oracle(w), f"Q={Q}/{direction}")
+
+
+@pytest.mark.parametrize("direction,hub_min", [("auto", 0), ("push", 0), ("pull", 0), ("push", 50), ("pull", 50),
+                                               ("auto", 300)])
+def test_config2_one_percent(direction, hub_min):
+    # 30,000 entities / 300,000 triples / 1,024 queries: several tiles, ragged last tile,
+    # all three row classes, W = 16.
+    w = kggen.config2(0.01)
+    print("case config2/100", direction, hub_min, flush=True)
+    got, stats = run_gpu(w, direction, hub_min_degree=hub_min)
+    want = run_oracle(w)
+    assert_same(got, want, f"config2/100 {direction} hub_min={hub_min}")
+    check_invariants(w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask, *got[:4],
+                     queries=range(0, 1024, 97))
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_config3_relation_masks(k):
+    w = kggen.config3(0.01, k=k)
+    print("case config3/100 k", k, flush=True)
+    want = run_oracle(w)
+    for direction in ("auto", "push", "pull"):
+        got, _ = run_gpu(w, direction, hub_min_degree=200)
+        assert_same(got, want, f"config3/100 k={k} {direction}")
+
+
+def test_config4_and_5_shapes_resident():
+    for w in (kggen.config4(0.002, num_queries=1024), kggen.config5(0.0003)):
+        print("case", w.name, flush=True)
+        want = run_oracle(w)
+        for direction in ("auto", "push", "pull"):
+            got, _ = run_gpu(w, direction, hub_min_degree=128)
+            assert_same(got, want, f"{w.name} {direction}")
+
+
+def test_k_zero_and_large_k_and_dead_seeds():
+    w = kggen.config1()
+    got, _ = run_gpu(w, k=0)
+    assert_same(got, run_oracle(w, k=0), "k=0")
+    got, stats = run_gpu(w, k=40)
+    assert_same(got, run_oracle(w, k=40), "k=40")
+    # a query whose only seed has no out-edge reaches just the seed
+    outdeg = np.bincount(w.subj, minlength=w.num_entities)
+    dead = int(np.nonzero(outdeg == 0)[0][0])
+    w.seeds = np.full_like(w.seeds, dead)
+    got, _ = run_gpu(w, k=3)
+    assert_same(got, run_oracle(w, k=3), "dead seeds")
+    assert got[0][-1] == w.num_queries
+
+
+def test_fetch_subranges_and_optional_outputs():
+    m = lkg()
+    w = kggen.config2(0.004, num_queries=300)
+    want = run_oracle(w)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=100)
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    off = res.offsets()
+    assert np.array_equal(off, want[0])
+    for q0, q1 in [(0, 1), (5, 70), (64, 128), (100, 300), (299, 300), (17, 17)]:
+        ent, hop, pred = res.fetch(q0, q1)
+        a, b = off[q0], off[q1]
+        assert np.array_equal(ent.cpu().numpy(), want[1][a:b])
+        assert np.array_equal(hop.cpu().numpy(), want[2][a:b])
+        assert np.array_equal(pred.cpu().numpy(), want[3][a:b])
+    ent, hop, pred = res.fetch(want_hop=False, want_pred=False)
+    assert hop is None and pred is None and np.array_equal(ent.cpu().numpy(), want[1])
+    res.close()
+    g.close()
+
+
+def test_two_runs_are_bit_identical():
+    w = kggen.config3(0.01, k=3)
+    a, _ = run_gpu(w, "auto", hub_min_degree=100)
+    b, _ = run_gpu(w, "auto", hub_min_degree=100)
+    assert_same(a, b, "run-to-run")
+
+
+@pytest.mark.parametrize("masked", [False, True])
+def test_paths_against_oracle(masked):
+    m = lkg()
+    w = kggen.config3(0.004, k=4, num_queries=200) if masked else kggen.config2(0.004, num_queries=200)
+    print("case paths", masked, flush=True)
+    want = run_oracle(w)
+    pq, pt = kggen.sample_reached_pairs(7, want[0], want[1], 3000)
+    # add unreachable targets, seeds and out-of-range pairs
+    extra_q = np.array([0, 1, 2, 3], np.int32)
+    extra_t = np.array([w.num_entities - 1, int(w.seeds[w.seed_off[1]]), 0, 5], np.int32)
+    pq = np.concatenate([pq, extra_q])
+    pt = np.concatenate([pt, extra_t])
+    cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, pq, pt, 16,
+                                  w.rel_mask)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+    cnt, edges = g.paths(res, pq, pt, 16)
+    assert np.array_equal(cnt.cpu().numpy(), cnt_o)
+    assert np.array_equal(edges.cpu().numpy(), edges_o)
+    cnt3, edges3 = g.paths(res, pq, pt, 3)
+    assert np.array_equal(cnt3.cpu().numpy(), np.minimum(cnt_o, 3))
+    assert np.array_equal(edges3.cpu().numpy(), edges_o[:, :3])
+    res.close()
+    g.close()
+
+
+def test_bad_inputs_are_reported_not_faulted():
+    m = lkg()
+    w = kggen.config1()
+    with pytest.raises(m.LogosKGError):
+        bad = w.subj.copy()
+        bad[3] = w.num_entities
+        m.Graph(bad, w.rel, w.obj, w.num_entities, w.num_relations)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    seeds = w.seeds.copy()
+    seeds[5] = w.num_entities + 3
+    with pytest.raises(m.LogosKGError):
+        g.khop(w.seed_off, seeds, 2)
+    off = w.seed_off.copy()
+    off[7] = off[6] - 1
+    with pytest.raises(m.LogosKGError):
+        g.khop(off, w.seeds, 2)
+    with pytest.raises(m.LogosKGError):
+        g.khop(w.seed_off, w.seeds, 255)
+    res = g.khop(w.seed_off, w.seeds, 2)  # the handle still works afterwards
+    assert res.offsets()[-1] == run_oracle(w)[0][-1]
+    with pytest.raises(m.LogosKGError):
+        import torch
+        small = torch.empty(3, dtype=torch.int32, device=g.device)
+        res.fetch(out=(small, None, None))
+    res.close()
+    g.close()
