@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One step = one pass of logoskg_khop (seed scatter, 3 hops of push/pull
+expansion with the visited/level update, per-query counts) followed by
+logoskg_result_fetch of every query (query-major entity / hop / predecessor
+lists) on the 3,000,000-entity / 30,000,000-triple synthetic KG with 1,024
+queries (benchmark configs[1]).  Seeds and the graph are resident in HBM
+before the timed region; outputs stay in HBM.
+
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool) -> float:
+    """Bytes the named kernel has to move for the work units it reported
+    (rows / edges / lines / items), per the per-unit figures of the design doc."""
+    line = 8 * W
+    e_bytes = 4 + (2 if masked else 0)
+    rows, edges, lines, items = p["rows"], p["edges"], p["lines"], p["items"]
+    if kernel.startswith("pull_"):
+        # per scanned row: visited line read + new-level line written + two 4-byte offsets (the
+        # visited write-back is not counted); per edge: subject id (+ relation); per DISTINCT
+        # frontier line gathered: one line (caches are assumed to absorb repeats)
+        return rows * (2 * line + 8) + edges * e_bytes + items * line
+    if kernel == "fill_lists_pred":
+        # planes streamed once (visited + k+1 levels, `rows`-independent), list entries written
+        # (4 B entity + 1 B hop + 4 B pred), object-row entries walked (4 B subject), frontier lines
+        return items * 9 + edges * 4 + lines * line
+    if kernel == "pred_hub":
+        return edges * 4 + lines * line
+    if kernel in ("clear_planes", "count_tiles"):
+        return items * 8
+    return 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-queries", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding across GPUs, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import kggen
+    import paper_2604_18913_amd as lkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    t0 = time.time()
+    w = kggen.config2(args.scale)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    g = lkg.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    t_build = time.time() - t0
+    dev = g.device
+    seed_off = torch.from_numpy(w.seed_off).to(dev)
+    seeds = torch.from_numpy(w.seeds).to(dev)
+    Q, k = w.num_queries, w.k
+
+    # sizes are deterministic: one untimed call sizes the output buffers
+    res = g.khop(seed_off, seeds, k)
+    off = res.offsets()
+    total = int(off[-1])
+    W = res.words_per_entity
+    ent = torch.empty(total, dtype=torch.int32, device=dev)
+    hop = torch.empty(total, dtype=torch.uint8, device=dev)
+    pred = torch.empty(total, dtype=torch.int32, device=dev)
+    trav = res.traversed().cpu().numpy()
+    hop_stats = res.hop_stats()
+    res.close()
+    logical_edges = int(trav.sum())
+
+    def step():
+        r = g.khop(seed_off, seeds, k)
+        r.fetch(out=(ent, hop, pred))
+        return r
+
+    # work units of every kernel (counting mode; not timed)
+    g.profile_enable(2)
+    r = step()
+    torch.cuda.synchronize()
+    units = g.profile_read()
+    counted_stats = r.hop_stats()
+    physical_edges = int(sum(h["edges_scanned"] for h in counted_stats))
+    r.close()
+    g.profile_enable(0)
+
+    for _ in range(args.warmup):
+        step().close()
+    torch.cuda.synchronize()
+    g.profile_enable(1)
+    g.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step().close()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = g.profile_read()
+    g.profile_enable(0)
+
+    # un-instrumented timing of the same loop (no events at all)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step().close()
+    torch.cuda.synchronize()
+    dt_plain = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    qps = Q / (dt / args.steps)
+    kernels = {}
+    for name, p in prof.items():
+        if p["launches"] == 0:
+            continue
+        u = units.get(name, {})
+        per_step = {x: u.get(x, 0) for x in ("rows", "edges", "lines", "items")}
+        kernels[name] = dict(launches_per_step=p["launches"] / args.steps,
+                             ms_per_step=p["total_ms"] / args.steps,
+                             avg_ms=p["total_ms"] / p["launches"], **per_step)
+    expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items()
+                       if n.startswith(("push_", "pull_", "update_", "frontier_", "seed_", "clear_")))
+    dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+    dk = kernels[dom]
+    alg = algorithmic_bytes(dom, dk, W, k, False) / max(dk["launches_per_step"], 1)
+    achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
+    roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4))
+    # the same figure for every expansion kernel of the 3-hop batched expansion
+    exp = {}
+    for n, v in kernels.items():
+        b = algorithmic_bytes(n, v, W, k, False)
+        if b > 0 and v["ms_per_step"] > 0:
+            exp[n] = dict(GBps=round(b / (v["ms_per_step"] * 1e-3) / 1e9, 1),
+                          frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          ms_per_step=round(v["ms_per_step"], 4), bytes_per_step=int(b))
+
+    out = {
+        "metric": "queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)",
+        "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "configs[1]: 3,000,000 entities, 30,000,000 triples, 500 relations, "
+                               "1,024 queries x 1-5 seeds, k=3, no relation mask" +
+                               ("" if args.scale == 1.0 else f" (scaled by {args.scale})"),
+                   "num_entities": w.num_entities, "num_triples": w.num_triples, "num_queries": Q, "k": k,
+                   "words_per_entity": W, "reached_pairs": total,
+                   "directions": [h["direction"] for h in hop_stats]},
+        "gteps_logical": round(logical_edges / (dt / args.steps) / 1e9, 2),
+        "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
+        "logical_edges_per_step": logical_edges, "physical_edges_per_step": physical_edges,
+        "expansion_ms_per_step": round(expansion_ms, 4),
+        "expansion_queries_per_s": round(Q / (expansion_ms * 1e-3), 1) if expansion_ms > 0 else None,
+        "ms_per_step_without_events": round(dt_plain / args.steps * 1e3, 4),
+        "roofline": roofline,
+        "kernels": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                    for n, v in kernels.items()},
+        "kernel_hbm": exp,
+        "hop_stats": counted_stats,
+        "setup_s": {"generate": round(t_gen, 1), "build": round(t_build, 1)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle  # the cpu_baseline leg is the only user of the oracle here
+        nq = min(args.cpu_queries, Q)
+        so = w.seed_off[: nq + 1]
+        sd = w.seeds[: so[-1]]
+        t0 = time.perf_counter()
+        o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
+        t_cpu = time.perf_counter() - t0
+        got = g.khop(seed_off, seeds, k)
+        e2, h2, p2 = got.fetch(0, nq)
+        same = (np.array_equal(off[: nq + 1], o[0]) and np.array_equal(e2.cpu().numpy(), o[1])
+                and np.array_equal(h2.cpu().numpy(), o[2]) and np.array_equal(p2.cpu().numpy(), o[3]))
+        got.close()
+        out["cpu_baseline"] = {"value": round(nq / t_cpu, 2), "unit": "queries/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"first {nq} of the {Q} queries of the same workload, one query per "
+                                         f"thread, index build included ({t_cpu:.1f} s)",
+                               "matches_gpu": bool(same), "host_cpus": os.cpu_count()}
+    g.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -99,6 +99,29 @@ typedef struct {
 
 logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg_graph_info *out);
 
+/*
+ * Per-kernel timing for measurement runs.  enable = 1: every kernel launch of
+ * the library is bracketed by HIP events on the caller's stream.  enable = 2:
+ * in addition the pull and result kernels count the rows, CSR entries and
+ * bit-plane lines they actually touch (a few atomics per wavefront, so time
+ * with 1 and count with 2).  logoskg_profile_read drains the finished events:
+ * out[i] describes kernel class i (at most `capacity` entries are written,
+ * *n_out receives how many exist) and the accumulators restart from zero.
+ */
+typedef struct {
+    char name[32];
+    int64_t launches;
+    double total_ms, max_ms;
+    int64_t rows;   /* rows (entities) the launches worked on                  */
+    int64_t edges;  /* CSR entries read                                        */
+    int64_t lines;  /* W-word bit-plane lines gathered / updated through edges */
+    int64_t items;  /* kernel specific: list entries written, words streamed   */
+} logoskg_kernel_profile;
+
+logoskg_status logoskg_profile_enable(logoskg_graph *g, int32_t enable);
+logoskg_status logoskg_profile_read(logoskg_graph *g, logoskg_kernel_profile *out, int32_t capacity,
+                                    int32_t *n_out);
+
 /* Sec. 3.4 metadata map P: shard of each subject entity (-1 for entities that are
  * never a subject), and the number of triples per shard.  host outputs; either
  * may be NULL. */
@@ -158,9 +181,9 @@ typedef struct {
     int32_t shards_touched;   /* shards with an active subject (1 for resident graphs)                  */
     int64_t active_rows;      /* subjects in the frontier with >= 1 triple                              */
     int64_t frontier_edges;   /* sum of their out-degrees                                               */
-    int64_t rows_scanned;     /* pull: object rows visited that were not already complete               */
-    int64_t edges_scanned;    /* CSR entries actually read by the expansion kernels                     */
-    int64_t lines_gathered;   /* pull: frontier lines read; push: visited lines read                    */
+    int64_t rows_scanned;     /* pull: object rows visited that were not already complete (profiling on) */
+    int64_t edges_scanned;    /* CSR entries read by the expansion kernels (pull: profiling on)          */
+    int64_t lines_gathered;   /* pull: frontier lines read (profiling on); push: visited lines read      */
     int64_t entities_reached; /* entities with at least one new query bit at this hop                   */
 } logoskg_hop_stats;
 

@@ -66,6 +66,12 @@ class _HopStats(ctypes.Structure):
                 ("lines_gathered", ctypes.c_int64), ("entities_reached", ctypes.c_int64)]
 
 
+class _KernelProfile(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 32), ("launches", ctypes.c_int64),
+                ("total_ms", ctypes.c_double), ("max_ms", ctypes.c_double), ("rows", ctypes.c_int64),
+                ("edges", ctypes.c_int64), ("lines", ctypes.c_int64), ("items", ctypes.c_int64)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -77,6 +83,9 @@ def _load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python paper_2604_18913_amd/build_ext.py` "
                           "(there is no CPU fallback)")
+    # PyTorch ships its own HIP runtime; import it first so that the library binds to the
+    # same runtime instance that owns torch's device buffers and streams.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     P, I32, I64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.logoskg_build.restype = ctypes.c_int
@@ -103,6 +112,10 @@ def _load():
     lib.logoskg_result_free.argtypes = [P]
     lib.logoskg_paths.restype = ctypes.c_int
     lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_profile_enable.restype = ctypes.c_int
+    lib.logoskg_profile_enable.argtypes = [P, I32]
+    lib.logoskg_profile_read.restype = ctypes.c_int
+    lib.logoskg_profile_read.argtypes = [P, P, I32, ctypes.POINTER(I32)]
     lib.logoskg_last_error.restype = ctypes.c_char_p
     lib.logoskg_version.restype = ctypes.c_char_p
     _lib = lib
@@ -198,19 +211,6 @@ class Result:
         _check(_load().logoskg_result_traversed(self._h, t.data_ptr(), _stream_handle(stream)))
         return t
 
-    def level_planes(self):
-        """Copy of the level planes as a uint8 view-friendly int64 tensor
-        [k+1, padded_entities, W] (device)."""
-        torch = _torch()
-        n = (self.k + 1) * self.padded_entities * self.words_per_entity
-        out = torch.empty(n, dtype=torch.int64, device=self._g.device)
-        torch.cuda.current_stream().synchronize()
-        rc = _hip().hipMemcpy(ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(self._levels_ptr),
-                              ctypes.c_size_t(n * 8), 3)
-        if rc != 0:
-            raise RuntimeError(f"hipMemcpy failed with {rc}")
-        return out.view(self.k + 1, self.padded_entities, self.words_per_entity)
-
     def close(self):
         if self._h:
             _load().logoskg_result_free(self._h)
@@ -221,16 +221,6 @@ class Result:
             self.close()
         except Exception:
             pass
-
-
-_hiprt = None
-
-
-def _hip():
-    global _hiprt
-    if _hiprt is None:
-        _hiprt = ctypes.CDLL("libamdhip64.so")
-    return _hiprt
 
 
 class Graph:
@@ -267,6 +257,22 @@ class Graph:
         gi = _GraphInfo()
         _check(_load().logoskg_graph_get_info(self._h, ctypes.byref(gi)))
         return {f[0]: int(getattr(gi, f[0])) for f in _GraphInfo._fields_}
+
+    def profile_enable(self, level: int):
+        """0 = off, 1 = time every kernel launch with HIP events, 2 = also count work units."""
+        _check(_load().logoskg_profile_enable(self._h, level))
+
+    def profile_read(self) -> dict:
+        """Drain the per-kernel accumulators: name -> dict(launches, total_ms, ...)."""
+        n = ctypes.c_int32()
+        arr = (_KernelProfile * 64)()
+        _check(_load().logoskg_profile_read(self._h, ctypes.cast(arr, ctypes.c_void_p), 64, ctypes.byref(n)))
+        out = {}
+        for rec in arr[:n.value]:
+            out[rec.name.decode()] = dict(launches=int(rec.launches), total_ms=float(rec.total_ms),
+                                          max_ms=float(rec.max_ms), rows=int(rec.rows), edges=int(rec.edges),
+                                          lines=int(rec.lines), items=int(rec.items))
+        return out
 
     def partition(self):
         n = max(self.info()["num_shards"], 1)

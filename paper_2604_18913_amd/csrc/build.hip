@@ -65,6 +65,51 @@ void DevPool::trim() {
     free_.clear();
 }
 
+const char *const kKernelNames[KK_NUM] = {
+    "clear_planes", "seed_scatter", "frontier_census", "push_tail", "push_mid", "push_hub",
+    "update_visited", "pull_tail", "pull_mid", "pull_hub", "count_tiles", "scan_counts",
+    "fill_lists_pred", "pred_hub", "traversed", "paths", "shard_copy"};
+
+void Profiler::begin(int kind, hipStream_t st) {
+    if (!on) return;
+    hipEvent_t a = nullptr;
+    if (!spare.empty()) { a = spare.back(); spare.pop_back(); }
+    else if (hipEventCreate(&a) != hipSuccess) return;
+    (void)hipEventRecord(a, st);
+    cur_a = a;
+    cur_kind = kind;
+}
+
+void Profiler::end(hipStream_t st) {
+    if (!on || !cur_a) return;
+    hipEvent_t b = nullptr;
+    if (!spare.empty()) { b = spare.back(); spare.pop_back(); }
+    else if (hipEventCreate(&b) != hipSuccess) { spare.push_back(cur_a); cur_a = nullptr; return; }
+    (void)hipEventRecord(b, st);
+    recs.push_back({cur_kind, cur_a, b});
+    cur_a = nullptr;
+}
+
+void Profiler::drain() {
+    for (auto &r : recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            acc[r.kind].launches++;
+            acc[r.kind].total_ms += ms;
+            if (ms > acc[r.kind].max_ms) acc[r.kind].max_ms = ms;
+        }
+        spare.push_back(r.a);
+        spare.push_back(r.b);
+    }
+    recs.clear();
+}
+
+void Profiler::release() {
+    drain();
+    for (hipEvent_t e : spare) (void)hipEventDestroy(e);
+    spare.clear();
+}
+
 template <typename T>
 static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
     size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
@@ -211,8 +256,8 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     if ((st = dev_alloc((void **)&g->fr_tail, lb)) != LOGOSKG_OK) return fail(st);
     if ((st = dev_alloc((void **)&g->fr_mid, lb)) != LOGOSKG_OK) return fail(st);
     if ((st = dev_alloc((void **)&g->fr_hub, lb)) != LOGOSKG_OK) return fail(st);
-    if ((st = dev_alloc((void **)&g->d_ctr, 64 * sizeof(unsigned long long))) != LOGOSKG_OK) return fail(st);
-    if (hipHostMalloc((void **)&g->h_ctr, 64 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
+    if ((st = dev_alloc((void **)&g->d_ctr, C_TOTAL * sizeof(unsigned long long))) != LOGOSKG_OK) return fail(st);
+    if (hipHostMalloc((void **)&g->h_ctr, C_TOTAL * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
         return fail(LOGOSKG_ENOMEM);
     }
@@ -224,6 +269,7 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     if (!g) return;
     (void)hipSetDevice(g->device);
     free_shards(g);
+    g->prof.release();
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
                     g->in_rows.tail, g->in_rows.mid, g->in_rows.hub, g->fr_tail, g->fr_mid,
                     g->fr_hub, g->d_ctr};
@@ -236,3 +282,33 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
 
 extern "C" const char *logoskg_last_error(void) { return lkg::get_error(); }
 extern "C" const char *logoskg_version(void) { return "logoskg-gfx950 0.1"; }
+
+extern "C" logoskg_status logoskg_profile_enable(logoskg_graph *g, int32_t enable) {
+    if (!g) { set_error("NULL graph"); return LOGOSKG_EINVAL; }
+    g->prof.drain();
+    g->prof.on = enable != 0;
+    g->prof.counters = enable >= 2;
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_profile_read(logoskg_graph *g, logoskg_kernel_profile *out, int32_t capacity,
+                                               int32_t *n_out) {
+    if (!g || (capacity > 0 && !out)) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    (void)hipSetDevice(g->device);
+    g->prof.drain();
+    if (n_out) *n_out = KK_NUM;
+    for (int i = 0; i < KK_NUM && i < capacity; ++i) {
+        memset(&out[i], 0, sizeof(out[i]));
+        strncpy(out[i].name, kKernelNames[i], sizeof(out[i].name) - 1);
+        const Profiler::Acc &a = g->prof.acc[i];
+        out[i].launches = a.launches;
+        out[i].total_ms = a.total_ms;
+        out[i].max_ms = a.max_ms;
+        out[i].rows = a.units[0];
+        out[i].edges = a.units[1];
+        out[i].lines = a.units[2];
+        out[i].items = a.units[3];
+    }
+    for (int i = 0; i < KK_NUM; ++i) g->prof.acc[i] = Profiler::Acc();
+    return LOGOSKG_OK;
+}

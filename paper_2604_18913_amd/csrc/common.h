@@ -68,7 +68,42 @@ struct RowClasses {           // device lists of row ids, split by degree
     int64_t n_tail = 0, n_mid = 0, n_hub = 0;
 };
 
-struct Shard;  // defined in shards.hip
+// ---------------------------------------------------------------- profiling
+enum KernelKind {
+    KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_PUSH_TAIL, KK_PUSH_MID, KK_PUSH_HUB, KK_UPDATE, KK_PULL_TAIL,
+    KK_PULL_MID, KK_PULL_HUB, KK_COUNT, KK_SCAN, KK_FILL, KK_PRED_HUB, KK_TRAVERSED, KK_PATHS,
+    KK_SHARD_COPY, KK_NUM
+};
+extern const char *const kKernelNames[KK_NUM];
+
+// device counter slots (logoskg_graph::d_ctr); the statistics block holds four
+// words per kernel class: rows, edges, lines, items
+enum {
+    C_NTAIL = 0, C_NMID = 1, C_NHUB = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
+    C_STATS = 8, C_TOTAL = C_STATS + 4 * KK_NUM
+};
+
+struct Profiler {
+    bool on = false;        // bracket launches with events
+    bool counters = false;  // also count rows / edges / lines inside the kernels
+    struct Rec { int kind; hipEvent_t a, b; };
+    struct Acc { int64_t launches = 0; double total_ms = 0, max_ms = 0; int64_t units[4] = {0, 0, 0, 0}; };
+    std::vector<hipEvent_t> spare;
+    std::vector<Rec> recs;
+    Acc acc[KK_NUM];
+    hipEvent_t cur_a = nullptr;
+    int cur_kind = -1;
+    void begin(int kind, hipStream_t st);
+    void end(hipStream_t st);
+    void drain();
+    void release();
+};
+
+struct ProfScope {  // brackets the launches issued during its lifetime
+    Profiler &p; hipStream_t st;
+    ProfScope(Profiler &p_, int kind, hipStream_t st_) : p(p_), st(st_) { p.begin(kind, st); }
+    ~ProfScope() { p.end(st); }
+};
 
 }  // namespace lkg
 
@@ -102,6 +137,7 @@ struct logoskg_graph {
     void *shards = nullptr;  // lkg::ShardSet* when num_shards > 1
 
     lkg::DevPool pool;
+    lkg::Profiler prof;
     size_t static_bytes = 0;
     size_t pinned_bytes = 0;
 };

@@ -21,12 +21,6 @@
 
 namespace lkg {
 
-// indices into logoskg_graph::d_ctr
-enum {
-    C_NTAIL = 0, C_NMID = 1, C_NHUB = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
-    C_ROWS = 8, C_EDGES = 9, C_LINES = 10, C_TOTAL = 16
-};
-
 // ---------------------------------------------------------------- seeds, mask table
 __global__ void k_seed(int Q, long long num_seeds, const long long *__restrict__ seed_off,
                        const int32_t *__restrict__ seeds, int32_t E, int W,
@@ -307,9 +301,9 @@ __device__ __forceinline__ void add_stats(unsigned long long *stats, long long r
     edges = wave_sum(edges);
     lines = wave_sum(lines);
     if (lane() == 0) {
-        if (rows) atomicAdd(&stats[C_ROWS], (unsigned long long)rows);
-        if (edges) atomicAdd(&stats[C_EDGES], (unsigned long long)edges);
-        if (lines) atomicAdd(&stats[C_LINES], (unsigned long long)lines);
+        if (rows) atomicAdd(&stats[0], (unsigned long long)rows);
+        if (edges) atomicAdd(&stats[1], (unsigned long long)edges);
+        if (lines) atomicAdd(&stats[2], (unsigned long long)lines);
     }
 }
 
@@ -430,17 +424,26 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
     long long nt = (long long)hc[C_NTAIL], nm = (long long)hc[C_NMID], nh = (long long)hc[C_NHUB];
     if (nt > 0) {
+        ProfScope ps(g->prof, KK_PUSH_TAIL, st);
         long long threads = nt * W;
         k_push_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
             g->fr_tail, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+        g->prof.acc[KK_PUSH_TAIL].units[0] += g->prof.on ? nt : 0;
     }
-    if (nm > 0)
+    if (nm > 0) {
+        ProfScope ps(g->prof, KK_PUSH_MID, st);
         k_push_coop<W, MASK, false><<<dim3((unsigned)((nm + 3) / 4)), dim3(256), 0, st>>>(
             g->fr_mid, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
-    if (nh > 0)
+        g->prof.acc[KK_PUSH_MID].units[0] += g->prof.on ? nm : 0;
+    }
+    if (nh > 0) {
+        ProfScope ps(g->prof, KK_PUSH_HUB, st);
         k_push_coop<W, MASK, true><<<dim3((unsigned)nh), dim3(512), 0, st>>>(
             g->fr_hub, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+        g->prof.acc[KK_PUSH_HUB].units[0] += g->prof.on ? nh : 0;
+    }
     long long nwords = (long long)plane;
+    ProfScope ps(g->prof, KK_UPDATE, st);
     k_update_visited<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(nwords, W, act_cur, cur,
                                                                                   r->visited);
 }
@@ -452,21 +455,26 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
     unsigned long long *cur = r->levels + plane * h;
     const uint32_t *act_prev = r->act + (size_t)(r->Epad / 32) * (h - 1);
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
-    unsigned long long *stats = want_stats ? g->d_ctr : nullptr;
+    auto stats = [&](int kind) { return want_stats ? g->d_ctr + C_STATS + 4 * kind : nullptr; };
     const RowClasses &rc = g->in_rows;
-    if (rc.n_hub > 0)
+    if (rc.n_hub > 0) {
+        ProfScope ps(g->prof, KK_PULL_HUB, st);
         k_pull_coop<W, MASK, true><<<dim3((unsigned)rc.n_hub), dim3(512), 0, st>>>(
             rc.hub, rc.n_hub, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
-            act_cur, stats);
-    if (rc.n_mid > 0)
+            act_cur, stats(KK_PULL_HUB));
+    }
+    if (rc.n_mid > 0) {
+        ProfScope ps(g->prof, KK_PULL_MID, st);
         k_pull_coop<W, MASK, false><<<dim3((unsigned)((rc.n_mid + 3) / 4)), dim3(256), 0, st>>>(
             rc.mid, rc.n_mid, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
-            act_cur, stats);
+            act_cur, stats(KK_PULL_MID));
+    }
     if (rc.n_tail > 0) {
+        ProfScope ps(g->prof, KK_PULL_TAIL, st);
         long long threads = rc.n_tail * W;
         k_pull_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
             rc.tail, rc.n_tail, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
-            act_cur, stats);
+            act_cur, stats(KK_PULL_TAIL));
     }
 }
 
@@ -495,9 +503,12 @@ void launch_resident_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, 
 static logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, bool write_lists, hipStream_t st) {
     LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 5 * sizeof(unsigned long long), st));
     long long nwords = r->Epad / 32;
-    k_census<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(
-        r->act + (size_t)nwords * h, nwords, g->out_off, g->hub_min, write_lists ? 1 : 0, g->fr_tail,
-        g->fr_mid, g->fr_hub, g->d_ctr);
+    {
+        ProfScope ps(g->prof, KK_CENSUS, st);
+        k_census<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(
+            r->act + (size_t)nwords * h, nwords, g->out_off, g->hub_min, write_lists ? 1 : 0, g->fr_tail,
+            g->fr_mid, g->fr_hub, g->d_ctr);
+    }
     LKG_HIP(hipGetLastError());
     LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     LKG_HIP(hipStreamSynchronize(st));
@@ -566,10 +577,15 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
         if (s2_ != LOGOSKG_OK) return fail(s2_);  \
     } while (0)
 
-    KH(hipMemsetAsync(r->visited, 0, plane * 8, st));
-    KH(hipMemsetAsync(r->levels, 0, plane * 8 * (size_t)(k + 1), st));
-    KH(hipMemsetAsync(r->act, 0, actw * 4 * (size_t)(k + 1), st));
-    KH(hipMemsetAsync(g->d_ctr, 0, 64 * sizeof(unsigned long long), st));
+    {
+        ProfScope ps(g->prof, KK_CLEAR, st);
+        KH(hipMemsetAsync(r->visited, 0, plane * 8, st));
+        KH(hipMemsetAsync(r->levels, 0, plane * 8 * (size_t)(k + 1), st));
+        KH(hipMemsetAsync(r->act, 0, actw * 4 * (size_t)(k + 1), st));
+        KH(hipMemsetAsync(g->d_ctr, 0, C_TOTAL * sizeof(unsigned long long), st));
+        g->prof.acc[KK_CLEAR].units[3] += g->prof.on ? (long long)(plane * (size_t)(k + 2)) : 0;
+    }
+    g->prof.begin(KK_SEED, st);
     if (r->has_mask) {
         int n = g->R * W;
         k_allow<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(r->Q, g->R, W, (g->R + 63) / 64,
@@ -580,8 +596,9 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
                                                            (const long long *)b->seed_off, b->seeds, g->E, W,
                                                            (unsigned long long *)r->levels,
                                                            (unsigned long long *)r->visited, r->act, g->d_ctr);
+    g->prof.end(st);
     KH(hipGetLastError());
-    bool want_stats = true;
+    const bool want_stats = g->prof.counters;
     if ((s = census(g, r, 0, k > 0, st)) != LOGOSKG_OK) return fail(s);
     if (g->h_ctr[C_ERR]) {
         set_error("seed_off / seeds are inconsistent or out of range (device check, code %llu)", g->h_ctr[C_ERR]);
@@ -605,16 +622,22 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
             hs.shards_touched = 1;
             unsigned long long hc[C_TOTAL];
             memcpy(hc, g->h_ctr, sizeof(hc));
-            KH(hipMemsetAsync(g->d_ctr + C_ROWS, 0, 3 * sizeof(unsigned long long), st));
+            KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
             launch_resident_hop(g, r, h, pull, want_stats, hc, st);
             KH(hipGetLastError());
         }
         if ((s = census(g, r, h, h < k, st)) != LOGOSKG_OK) return fail(s);
         hs.entities_reached = (long long)g->h_ctr[C_NACTIVE];
         if (hs.direction == LOGOSKG_DIR_PULL) {
-            hs.rows_scanned = (long long)g->h_ctr[C_ROWS];
-            hs.edges_scanned = (long long)g->h_ctr[C_EDGES];
-            hs.lines_gathered = (long long)g->h_ctr[C_LINES];
+            for (int kind : {KK_PULL_TAIL, KK_PULL_MID, KK_PULL_HUB}) {
+                const unsigned long long *c = g->h_ctr + C_STATS + 4 * kind;
+                hs.rows_scanned += (long long)c[0];
+                hs.edges_scanned += (long long)c[1];
+                hs.lines_gathered += (long long)c[2];
+                for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)c[u];
+                // distinct frontier lines this kernel can have gathered
+                g->prof.acc[kind].units[3] += std::min((long long)c[2], hs.active_rows);
+            }
         } else if (g->num_shards <= 1) {
             hs.edges_scanned = fedges;
             hs.lines_gathered = fedges;

@@ -114,13 +114,14 @@ struct FillArgs {
     uint8_t *hop;
     int32_t *pred;
     long long *hub_slot;
+    unsigned long long *stats_fill, *stats_hub;  // rows / edges / lines counters or NULL
 };
 
 // Ordered walk over 64 in-edges [j0, j0+64) of entity row: resolves bits of
 // `rem` (lanes < W hold one word each) in ascending edge order.  `emit(hit,
 // eid)` is called by lanes whose word has newly resolved bits.
 template <int W, bool MASK, typename Emit>
-__device__ __forceinline__ void pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
+__device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
                                            const uint32_t *__restrict__ act_prev,
                                            const unsigned long long *__restrict__ prev,
                                            unsigned long long &rem, Emit emit) {
@@ -132,10 +133,12 @@ __device__ __forceinline__ void pred_chunk(uint32_t j0, uint32_t hi, const FillA
         cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
     }
     unsigned long long cm = __ballot(cand);
+    int gathered = 0;
     while (cm) {
         int c = __ffsll((long long)cm) - 1;
         cm &= cm - 1;
         int sc = __shfl(s, c);
+        ++gathered;
         unsigned long long hit = 0;
         if (lane() < W) {
             unsigned long long ln = prev[(size_t)sc * W + lane()];
@@ -149,6 +152,7 @@ __device__ __forceinline__ void pred_chunk(uint32_t j0, uint32_t hi, const FillA
             if (!wave_any(rem != 0)) break;
         }
     }
+    return gathered;
 }
 
 template <int W, int NB, bool MASK>
@@ -202,6 +206,7 @@ __global__ void k_fill(FillArgs a) {
 
     // predecessor edges: one wavefront per entity of the tile
     const int nwaves = blockDim.x >> 6;
+    long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int vi = wave; vi < 64; vi += nwaves) {
         int ev = (int)(tile * 64) + vi;
         if (ev >= a.E) break;
@@ -232,16 +237,23 @@ __global__ void k_fill(FillArgs a) {
             }
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+            ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
-                pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
+                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
                     for (unsigned long long m = hit; m; m &= m - 1) {
                         int q = v * 64 + (__ffsll((long long)m) - 1);
                         a.pred[slot_of(base, mT, q, vi)] = eid;
                     }
                 });
+                n_edges += min((uint32_t)64, hi - j0);
                 if (!wave_any(rem != 0)) break;
             }
         }
+    }
+    if (a.stats_fill && v == 0) {
+        if (n_rows) atomicAdd(&a.stats_fill[0], (unsigned long long)n_rows);
+        if (n_edges) atomicAdd(&a.stats_fill[1], (unsigned long long)n_edges);
+        if (n_lines) atomicAdd(&a.stats_fill[2], (unsigned long long)n_lines);
     }
 }
 
@@ -257,6 +269,7 @@ __global__ void __launch_bounds__(512) k_pred_hub(FillArgs a) {
     const int ev = a.hubs[hidx];
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6;
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
+    long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int h = 1; h <= a.k; ++h) {
         __syncthreads();
         if (t < 16)
@@ -267,20 +280,28 @@ __global__ void __launch_bounds__(512) k_pred_hub(FillArgs a) {
         for (uint32_t s0 = lo; s0 < hi; s0 += 64u * nw) {
             unsigned long long rem = lane() < W ? srem[lane()] : 0ull;
             if (!wave_any(rem != 0)) break;  // same decision in every wave
+            if (s0 == lo && wave == 0) ++n_rows;
             unsigned long long before = rem;
             uint32_t j0 = s0 + 64u * wave;
-            if (j0 < hi)
-                pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
+            if (j0 < hi) {
+                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
                     for (unsigned long long m = hit; m; m &= m - 1) {
                         int q = lane() * 64 + (__ffsll((long long)m) - 1);
                         atomicMin(&a.pred[a.hub_slot[(size_t)hidx * Qp + q]], eid);
                     }
                 });
+                n_edges += min((uint32_t)64, hi - j0);
+            }
             unsigned long long resolved = before & ~rem;
             __syncthreads();
             if (resolved) atomicAnd(&srem[lane()], ~resolved);
             __syncthreads();
         }
+    }
+    if (a.stats_hub && lane() == 0) {
+        if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
+        if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
+        if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
     }
 }
 
@@ -322,14 +343,21 @@ logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
     LKG_TRY(g->pool.alloc((void **)&r->super_base, (size_t)nsuper * Qp * 4));
     LKG_TRY(g->pool.alloc((void **)&r->d_reached_off, (size_t)(Qp + 1) * 8));
     dim3 grid((unsigned)ntiles), block(Qp);
-    switch (W) {
-        case 1: k_count<1><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
-        case 4: k_count<4><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
-        default: k_count<16><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
+    {
+        ProfScope ps(g->prof, KK_COUNT, st);
+        switch (W) {
+            case 1: k_count<1><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
+            case 4: k_count<4><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
+            default: k_count<16><<<grid, block, 0, st>>>(r->visited, Qp, r->tile_cnt); break;
+        }
+        g->prof.acc[KK_COUNT].units[3] += g->prof.on ? r->Epad * W : 0;
     }
-    k_scan_tiles<<<dim3((unsigned)nsuper), dim3(std::min(Qp, 256)), 0, st>>>(ntiles, Qp, r->tile_cnt, r->tile_base,
-                                                                         r->super_base);
-    k_scan_super<<<dim3(1), dim3(Qp), 0, st>>>(nsuper, r->Q, Qp, r->super_base, (long long *)r->d_reached_off);
+    {
+        ProfScope ps(g->prof, KK_SCAN, st);
+        k_scan_tiles<<<dim3((unsigned)nsuper), dim3(std::min(Qp, 256)), 0, st>>>(ntiles, Qp, r->tile_cnt,
+                                                                             r->tile_base, r->super_base);
+        k_scan_super<<<dim3(1), dim3(Qp), 0, st>>>(nsuper, r->Q, Qp, r->super_base, (long long *)r->d_reached_off);
+    }
     LKG_HIP(hipGetLastError());
     r->reached_off.assign((size_t)r->Q + 1, 0);
     LKG_HIP(hipMemcpyAsync(r->reached_off.data(), r->d_reached_off, (size_t)(r->Q + 1) * 8,
@@ -340,23 +368,27 @@ logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
 }
 
 template <int W, int NB>
-static void launch_fill(const FillArgs &a, bool mask, long long ntiles, hipStream_t st) {
+static void launch_fill(Profiler &prof, const FillArgs &a, bool mask, long long ntiles, hipStream_t st) {
     dim3 grid((unsigned)ntiles), block(64 * W);
-    if (mask) k_fill<W, NB, true><<<grid, block, 0, st>>>(a);
-    else k_fill<W, NB, false><<<grid, block, 0, st>>>(a);
+    {
+        ProfScope ps(prof, KK_FILL, st);
+        if (mask) k_fill<W, NB, true><<<grid, block, 0, st>>>(a);
+        else k_fill<W, NB, false><<<grid, block, 0, st>>>(a);
+    }
     if (a.pred && a.n_hubs > 0) {
+        ProfScope ps(prof, KK_PRED_HUB, st);
         if (mask) k_pred_hub<W, true><<<dim3((unsigned)a.n_hubs), dim3(512), 0, st>>>(a);
         else k_pred_hub<W, false><<<dim3((unsigned)a.n_hubs), dim3(512), 0, st>>>(a);
     }
 }
 
 template <int W>
-static void launch_fill_w(const FillArgs &a, bool mask, long long ntiles, hipStream_t st) {
+static void launch_fill_w(Profiler &prof, const FillArgs &a, bool mask, long long ntiles, hipStream_t st) {
     int nb = 1;
     while ((1 << nb) <= a.k) ++nb;
-    if (nb <= 2) launch_fill<W, 2>(a, mask, ntiles, st);
-    else if (nb <= 4) launch_fill<W, 4>(a, mask, ntiles, st);
-    else launch_fill<W, 8>(a, mask, ntiles, st);
+    if (nb <= 2) launch_fill<W, 2>(prof, a, mask, ntiles, st);
+    else if (nb <= 4) launch_fill<W, 4>(prof, a, mask, ntiles, st);
+    else launch_fill<W, 8>(prof, a, mask, ntiles, st);
 }
 
 }  // namespace lkg
@@ -403,13 +435,24 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.hubs = g->in_rows.hub; a.n_hubs = g->in_rows.n_hub;
     a.entity = entity; a.hop = hop; a.pred = pred; a.hub_slot = (long long *)r->hub_slot;
+    const bool counting = g->prof.counters;
+    a.stats_fill = counting ? g->d_ctr + C_STATS + 4 * KK_FILL : nullptr;
+    a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
+    if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
     const long long ntiles = r->Epad / kTileEntities;
     switch (W) {
-        case 1: launch_fill_w<1>(a, r->has_mask, ntiles, st); break;
-        case 4: launch_fill_w<4>(a, r->has_mask, ntiles, st); break;
-        default: launch_fill_w<16>(a, r->has_mask, ntiles, st); break;
+        case 1: launch_fill_w<1>(g->prof, a, r->has_mask, ntiles, st); break;
+        case 4: launch_fill_w<4>(g->prof, a, r->has_mask, ntiles, st); break;
+        default: launch_fill_w<16>(g->prof, a, r->has_mask, ntiles, st); break;
     }
     LKG_HIP(hipGetLastError());
+    if (g->prof.on) g->prof.acc[KK_FILL].units[3] += need;
+    if (counting) {  // measurement mode only: wait for the counters
+        LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+        LKG_HIP(hipStreamSynchronize(st));
+        for (int kind : {KK_FILL, KK_PRED_HUB})
+            for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)g->h_ctr[C_STATS + 4 * kind + u];
+    }
     return LOGOSKG_OK;
 }
 
@@ -424,6 +467,7 @@ extern "C" logoskg_status logoskg_result_traversed(logoskg_result *r, int64_t *t
     const long long nsuper = (ntiles + kSuperTiles - 1) / kSuperTiles;
     LKG_HIP(hipMemsetAsync(traversed, 0, (size_t)r->Q * r->k * 8, st));
     dim3 grid((unsigned)nsuper), block(64 * W);
+    ProfScope ps(g->prof, KK_TRAVERSED, st);
     unsigned long long *tr = (unsigned long long *)traversed;
     const unsigned long long *lv = (const unsigned long long *)r->levels;
     switch (W) {
