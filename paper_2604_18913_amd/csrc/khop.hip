@@ -636,7 +636,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
                 hs.lines_gathered += (long long)c[2];
                 for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)c[u];
                 // distinct frontier lines this kernel can have gathered
-                g->prof.acc[kind].units[3] += std::min((long long)c[2], hs.active_rows);
+                g->prof.acc[kind].units[3] += std::min<long long>((long long)c[2], (long long)hs.active_rows);
             }
         } else if (g->num_shards <= 1) {
             hs.edges_scanned = fedges;
