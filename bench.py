@@ -23,25 +23,30 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool) -> float:
-    """Bytes the named kernel has to move for the work units it reported
+def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_bytes: float) -> float:
+    """Bytes the named kernel has to move per step for the work units it reported
     (rows / edges / lines / items), per the per-unit figures of the design doc."""
     line = 8 * W
     e_bytes = 4 + (2 if masked else 0)
     rows, edges, lines, items = p["rows"], p["edges"], p["lines"], p["items"]
-    if kernel.startswith("pull_"):
-        # per scanned row: visited line read + new-level line written + two 4-byte offsets (the
-        # visited write-back is not counted); per edge: subject id (+ relation); per DISTINCT
-        # frontier line gathered: one line (caches are assumed to absorb repeats)
+    n = p.get("launches_per_step", 1)
+    if kernel.startswith("pull_") and kernel != "pull_finish":
+        # per scanned row (or row segment): visited line read + new-level line written + two 4-byte
+        # offsets (the visited write-back is not counted); per edge: subject id (+ relation);
+        # per DISTINCT frontier line gathered: one line (caches are assumed to absorb repeats)
         return rows * (2 * line + 8) + edges * e_bytes + items * line
-    if kernel == "fill_lists_pred":
-        # planes streamed once (visited + k+1 levels, `rows`-independent), list entries written
-        # (4 B entity + 1 B hop + 4 B pred), object-row entries walked (4 B subject), frontier lines
-        return items * 9 + edges * 4 + lines * line
+    if kernel == "lists":
+        # visited + levels 1..k streamed once; 4 B entity + 1 B hop written per list entry
+        return n * (k + 1) * plane_bytes + items * 5
+    if kernel == "pred":
+        # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked
+        return n * 2 * plane_bytes + items * 4 + edges * 4
     if kernel == "pred_hub":
-        return edges * 4 + lines * line
-    if kernel in ("clear_planes", "count_tiles"):
+        return edges * 4
+    if kernel == "clear_planes":
         return items * 8
+    if kernel == "count_tiles":
+        return items * 8 * 1.25  # plane read + uint16 per (tile, query) written
     return 0.0
 
 
@@ -82,6 +87,7 @@ def main():
     off = res.offsets()
     total = int(off[-1])
     W = res.words_per_entity
+    res_epad = res.padded_entities
     ent = torch.empty(total, dtype=torch.int32, device=dev)
     hop = torch.empty(total, dtype=torch.uint8, device=dev)
     pred = torch.empty(total, dtype=torch.int32, device=dev)
@@ -138,10 +144,11 @@ def main():
                              ms_per_step=p["total_ms"] / args.steps,
                              avg_ms=p["total_ms"] / p["launches"], **per_step)
     expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items()
-                       if n.startswith(("push_", "pull_", "update_", "frontier_", "seed_", "clear_")))
+                       if n.startswith(("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")))
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
-    alg = algorithmic_bytes(dom, dk, W, k, False) / max(dk["launches_per_step"], 1)
+    plane_bytes = float(res_epad * W * 8)
+    alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
@@ -149,7 +156,7 @@ def main():
     # the same figure for every expansion kernel of the 3-hop batched expansion
     exp = {}
     for n, v in kernels.items():
-        b = algorithmic_bytes(n, v, W, k, False)
+        b = algorithmic_bytes(n, v, W, k, False, plane_bytes)
         if b > 0 and v["ms_per_step"] > 0:
             exp[n] = dict(GBps=round(b / (v["ms_per_step"] * 1e-3) / 1e9, 1),
                           frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

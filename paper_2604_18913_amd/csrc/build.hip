@@ -66,9 +66,9 @@ void DevPool::trim() {
 }
 
 const char *const kKernelNames[KK_NUM] = {
-    "clear_planes", "seed_scatter", "frontier_census", "push_tail", "push_mid", "push_hub",
-    "update_visited", "pull_tail", "pull_mid", "pull_hub", "count_tiles", "scan_counts",
-    "fill_lists_pred", "pred_hub", "traversed", "paths", "shard_copy"};
+    "clear_planes", "seed_scatter", "frontier_census", "live_queries", "push_tail", "push_seg",
+    "update_visited", "pull_tail", "pull_seg", "pull_finish", "count_tiles", "scan_counts",
+    "lists", "pred", "pred_hub", "traversed", "paths", "shard_copy"};
 
 void Profiler::begin(int kind, hipStream_t st) {
     if (!on) return;
@@ -119,22 +119,29 @@ static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
     return LOGOSKG_OK;
 }
 
-// Rows with >= 1 entry split into tail / mid / hub lists by degree.
+// Object rows with >= 1 entry: short rows, segments of the longer ones (longest
+// rows first), rows with several segments, and the hub rows.
 static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_min,
-                          std::vector<int32_t> &tail, std::vector<int32_t> &mid,
-                          std::vector<int32_t> &hub) {
+                          std::vector<int32_t> &tail, std::vector<RowSegment> &seg,
+                          std::vector<int32_t> &multi, std::vector<int32_t> &hub, int64_t *n_long) {
     std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
+    std::vector<int32_t> longer;
     for (int32_t v = 0; v < E; ++v) {
         uint32_t d = off[v + 1] - off[v];
         if (d == 0) continue;
         if (d >= (uint32_t)hub_min) hub.push_back(v);
-        else if (d > (uint32_t)kTailMaxDegree) mid.push_back(v);
+        if (d > (uint32_t)kTailMaxDegree) longer.push_back(v);
         else bucket[d].push_back(v);
     }
     for (int d = kTailMaxDegree; d >= 1; --d) tail.insert(tail.end(), bucket[d].begin(), bucket[d].end());
-    std::stable_sort(mid.begin(), mid.end(), [&](int32_t a, int32_t b) {
+    std::stable_sort(longer.begin(), longer.end(), [&](int32_t a, int32_t b) {
         return off[a + 1] - off[a] > off[b + 1] - off[b];
     });
+    for (int32_t v : longer) {
+        if (off[v + 1] - off[v] > (uint32_t)kPullSegment) multi.push_back(v);
+        for (uint32_t j = off[v]; j < off[v + 1]; j += kPullSegment) seg.push_back({v, j});
+    }
+    *n_long = (int64_t)longer.size();
 }
 
 }  // namespace lkg
@@ -232,13 +239,16 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
                 if ((st = upload(&g->in_sub, isub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rel, irel, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_eid, ieid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                std::vector<int32_t> tail, mid, hub;
-                classify_rows(ioff, E, g->hub_min, tail, mid, hub);
+                std::vector<int32_t> tail, multi, hub;
+                std::vector<RowSegment> seg;
+                classify_rows(ioff, E, g->hub_min, tail, seg, multi, hub, &g->in_rows.n_long);
                 g->in_rows.n_tail = (int64_t)tail.size();
-                g->in_rows.n_mid = (int64_t)mid.size();
+                g->in_rows.n_seg = (int64_t)seg.size();
+                g->in_rows.n_multi = (int64_t)multi.size();
                 g->in_rows.n_hub = (int64_t)hub.size();
                 if ((st = upload(&g->in_rows.tail, tail, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                if ((st = upload(&g->in_rows.mid, mid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rows.seg, seg, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rows.multi, multi, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rows.hub, hub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
             }
         }
@@ -252,10 +262,9 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         g->static_bytes += bytes;
         return LOGOSKG_OK;
     };
-    size_t lb = (size_t)E * sizeof(int32_t);
-    if ((st = dev_alloc((void **)&g->fr_tail, lb)) != LOGOSKG_OK) return fail(st);
-    if ((st = dev_alloc((void **)&g->fr_mid, lb)) != LOGOSKG_OK) return fail(st);
-    if ((st = dev_alloc((void **)&g->fr_hub, lb)) != LOGOSKG_OK) return fail(st);
+    g->fr_seg_cap = (int64_t)E + T / kPushSegment + 64;  // every long row adds < deg/segment + 1 items
+    if ((st = dev_alloc((void **)&g->fr_tail, (size_t)E * sizeof(int32_t))) != LOGOSKG_OK) return fail(st);
+    if ((st = dev_alloc((void **)&g->fr_seg, (size_t)g->fr_seg_cap * sizeof(RowSegment))) != LOGOSKG_OK) return fail(st);
     if ((st = dev_alloc((void **)&g->d_ctr, C_TOTAL * sizeof(unsigned long long))) != LOGOSKG_OK) return fail(st);
     if (hipHostMalloc((void **)&g->h_ctr, C_TOTAL * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
@@ -271,8 +280,8 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     free_shards(g);
     g->prof.release();
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
-                    g->in_rows.tail, g->in_rows.mid, g->in_rows.hub, g->fr_tail, g->fr_mid,
-                    g->fr_hub, g->d_ctr};
+                    g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.hub, g->fr_tail,
+                    g->fr_seg, g->d_ctr};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (g->h_ctr) (void)hipHostFree(g->h_ctr);

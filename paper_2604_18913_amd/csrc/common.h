@@ -57,29 +57,39 @@ private:
 
 // ---------------------------------------------------------------- graph
 constexpr int kTailMaxDegree = 32;      // rows up to this degree: one W-lane group per row
-constexpr int kDefaultHubMin = 4096;    // rows from this degree: one block per row
+constexpr int kPullSegment = 1024;      // longer object rows are cut into segments of this many
+                                        // entries, one wavefront each
+constexpr int kPushSegment = 256;       // same for the subject rows of a push frontier
+constexpr int kDefaultHubMin = 4096;    // object rows from this degree: block-per-row predecessor kernel
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
-constexpr int kSuperTiles = 64;         // tiles per super tile (4096 entities)
+constexpr int kSuperTiles = 16;         // tiles per super tile (1024 entities)
+constexpr int kMegaSupers = 64;         // super tiles per mega tile (65536 entities)
 
-struct RowClasses {           // device lists of row ids, split by degree
-    int32_t *tail = nullptr;  // 1 .. kTailMaxDegree, sorted by descending degree
-    int32_t *mid = nullptr;   // kTailMaxDegree+1 .. hub_min-1, descending degree
-    int32_t *hub = nullptr;   // >= hub_min, ascending row id
-    int64_t n_tail = 0, n_mid = 0, n_hub = 0;
+struct RowSegment {  // part [begin, min(begin + segment, row end)) of one CSR row
+    int32_t row;
+    uint32_t begin;
+};
+
+struct RowClasses {             // device work lists over the object rows, split by degree
+    int32_t *tail = nullptr;    // rows with 1 .. kTailMaxDegree entries, descending degree
+    RowSegment *seg = nullptr;  // segments of the longer rows, longest rows first
+    int32_t *multi = nullptr;   // rows cut into more than one segment
+    int32_t *hub = nullptr;     // rows with >= hub_min entries, ascending row id
+    int64_t n_tail = 0, n_seg = 0, n_multi = 0, n_hub = 0, n_long = 0;  // n_long: rows behind seg
 };
 
 // ---------------------------------------------------------------- profiling
 enum KernelKind {
-    KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_PUSH_TAIL, KK_PUSH_MID, KK_PUSH_HUB, KK_UPDATE, KK_PULL_TAIL,
-    KK_PULL_MID, KK_PULL_HUB, KK_COUNT, KK_SCAN, KK_FILL, KK_PRED_HUB, KK_TRAVERSED, KK_PATHS,
-    KK_SHARD_COPY, KK_NUM
+    KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_LIVE, KK_PUSH_TAIL, KK_PUSH_SEG, KK_UPDATE, KK_PULL_TAIL,
+    KK_PULL_SEG, KK_PULL_FINISH, KK_COUNT, KK_SCAN, KK_LISTS, KK_PRED, KK_PRED_HUB, KK_TRAVERSED,
+    KK_PATHS, KK_SHARD_COPY, KK_NUM
 };
 extern const char *const kKernelNames[KK_NUM];
 
 // device counter slots (logoskg_graph::d_ctr); the statistics block holds four
 // words per kernel class: rows, edges, lines, items
 enum {
-    C_NTAIL = 0, C_NMID = 1, C_NHUB = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
+    C_NTAIL = 0, C_NSEG = 1, C_NROWS = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
     C_STATS = 8, C_TOTAL = C_STATS + 4 * KK_NUM
 };
 
@@ -128,7 +138,9 @@ struct logoskg_graph {
     int64_t n_out_rows = 0, n_out_hubs = 0;
 
     // frontier work lists rebuilt every hop from the level's active bitmap
-    int32_t *fr_tail = nullptr, *fr_mid = nullptr, *fr_hub = nullptr;  // [E] each
+    int32_t *fr_tail = nullptr;          // [E] frontier rows of degree <= kTailMaxDegree
+    lkg::RowSegment *fr_seg = nullptr;   // [fr_seg_cap] segments of the longer frontier rows
+    int64_t fr_seg_cap = 0;
     unsigned long long *d_ctr = nullptr;  // device counters (see khop.hip)
     unsigned long long *h_ctr = nullptr;  // pinned host mirror
 
@@ -152,10 +164,13 @@ struct logoskg_result {
     unsigned long long *levels = nullptr;   // [k+1][Epad][W]
     uint32_t *act = nullptr;      // [k+1][Epad/32]: entity has a non-zero line in that level
     unsigned long long *allow = nullptr;    // [R][W] relation -> queries that may follow it
-    // result-list bookkeeping (count pass)
-    uint8_t *tile_cnt = nullptr;    // [ntiles][64W]
-    uint16_t *tile_base = nullptr;  // [ntiles][64W] prefix inside the super tile
-    uint32_t *super_base = nullptr; // [nsuper][64W] prefix over super tiles
+    unsigned long long *live = nullptr;     // [k+1][16] queries whose level-h frontier has an out-edge
+    // result-list bookkeeping (count pass): for every query, the number of reached
+    // entities below a tile, as three nested exclusive prefixes
+    uint8_t *tile_cnt = nullptr;    // unused (kept zero)
+    uint16_t *tile_base = nullptr;  // [ntiles][64W]  tiles (64 entities) inside their super tile
+    uint32_t *super_base = nullptr; // [nsuper][64W]  super tiles (1024 entities) inside their mega tile
+    uint32_t *mega_base = nullptr;  // [nmega][64W]   mega tiles (65536 entities)
     long long *d_reached_off = nullptr;  // [64W+1]
     std::vector<int64_t> reached_off;  // host copy [Q+1]
     std::vector<logoskg_hop_stats> stats;
@@ -191,6 +206,12 @@ __device__ __forceinline__ unsigned long long shfl64(unsigned long long v, int s
 __device__ __forceinline__ unsigned long long shfl_xor64(unsigned long long v, int m) {
     int lo = __shfl_xor((int)(unsigned)(v & 0xffffffffull), m);
     int hi = __shfl_xor((int)(unsigned)(v >> 32), m);
+    return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+}
+
+__device__ __forceinline__ unsigned long long shfl_up64(unsigned long long v, int d) {
+    int lo = __shfl_up((int)(unsigned)(v & 0xffffffffull), d);
+    int hi = __shfl_up((int)(unsigned)(v >> 32), d);
     return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
 }
 

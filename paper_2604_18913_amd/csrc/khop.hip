@@ -10,11 +10,13 @@
 // triples of Eq. 5) is evaluated in one of two directions:
 //   push: for every subject row in the frontier, OR its line into the lines of
 //         its objects (atomicOr), skipping bits already visited;
-//   pull: for every object row that still misses some query, OR the lines of
-//         its subjects that are in the frontier, stopping as soon as nothing
-//         is missing; no atomics, and visited is updated in the same kernel.
-// Both give the same level[h]; rows are handled by a W-lane group (degree <=
-// 32), a wavefront (up to hub_min) or a block (hubs).
+//   pull: for every object row that still misses a query whose frontier is
+//         alive, OR the lines of its subjects that are in the frontier, and
+//         stop as soon as nothing is missing; no atomics on short rows, and
+//         visited is updated in the same kernel.
+// Both give the same level[h].  Rows of up to 32 entries are handled by a
+// W-lane group each; longer rows are cut into fixed-size segments, one
+// wavefront per segment, so a 100,000-entry hub spreads over many CUs.
 #include <algorithm>
 
 #include "common.h"
@@ -74,46 +76,88 @@ __device__ __forceinline__ int wave_excl_scan(int v, int &total) {
     return x - v;
 }
 
-// Turns the active bitmap of a level into three lists of subject rows (by
-// out-degree class) and the counters the host needs to pick the direction.
+// Turns the active bitmap of a level into the work lists of a push hop (short
+// subject rows; segments of the longer ones) and the counters the host needs
+// to pick the direction.
 __global__ void k_census(const uint32_t *__restrict__ act, long long nwords,
-                         const uint32_t *__restrict__ out_off, int hub_min, int write_lists,
-                         int32_t *list_tail, int32_t *list_mid, int32_t *list_hub,
-                         unsigned long long *ctr) {
+                         const uint32_t *__restrict__ out_off, int write_lists,
+                         int32_t *list_tail, RowSegment *list_seg, unsigned long long *ctr) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t word = i < nwords ? act[i] : 0u;
-    int ct = 0, cm = 0, ch = 0;
+    int ct = 0, cs = 0, cr = 0;
     long long deg_sum = 0;
     for (uint32_t m = word; m; m &= m - 1) {
         int e = (int)(i * 32) + (__ffs((int)m) - 1);
         uint32_t d = out_off[e + 1] - out_off[e];
         deg_sum += d;
-        if (d >= (uint32_t)hub_min) ++ch;
-        else if (d > (uint32_t)kTailMaxDegree) ++cm;
+        if (d > 0) ++cr;
+        if (d > (uint32_t)kTailMaxDegree) cs += (int)((d + kPushSegment - 1) / kPushSegment);
         else if (d > 0) ++ct;
     }
-    int tt, tm, th;
-    int pt = wave_excl_scan(ct, tt), pm = wave_excl_scan(cm, tm), ph = wave_excl_scan(ch, th);
+    int tt, ts;
+    int pt = wave_excl_scan(ct, tt), ps = wave_excl_scan(cs, ts);
     long long es = wave_sum(deg_sum);
     long long na = wave_sum((long long)__popc(word));
-    unsigned long long bt = 0, bm = 0, bh = 0;
+    long long nr = wave_sum((long long)cr);
+    unsigned long long bt = 0, bs = 0;
     if (lane() == 0) {
         if (tt) bt = atomicAdd(&ctr[C_NTAIL], (unsigned long long)tt);
-        if (tm) bm = atomicAdd(&ctr[C_NMID], (unsigned long long)tm);
-        if (th) bh = atomicAdd(&ctr[C_NHUB], (unsigned long long)th);
+        if (ts) bs = atomicAdd(&ctr[C_NSEG], (unsigned long long)ts);
+        if (nr) atomicAdd(&ctr[C_NROWS], (unsigned long long)nr);
         if (es) atomicAdd(&ctr[C_FEDGES], (unsigned long long)es);
         if (na) atomicAdd(&ctr[C_NACTIVE], (unsigned long long)na);
     }
     if (!write_lists) return;
     bt = shfl64(bt, 0) + pt;
-    bm = shfl64(bm, 0) + pm;
-    bh = shfl64(bh, 0) + ph;
+    bs = shfl64(bs, 0) + ps;
     for (uint32_t m = word; m; m &= m - 1) {
         int e = (int)(i * 32) + (__ffs((int)m) - 1);
-        uint32_t d = out_off[e + 1] - out_off[e];
-        if (d >= (uint32_t)hub_min) list_hub[bh++] = e;
-        else if (d > (uint32_t)kTailMaxDegree) list_mid[bm++] = e;
-        else if (d > 0) list_tail[bt++] = e;
+        uint32_t lo = out_off[e], hi = out_off[e + 1];
+        if (hi - lo > (uint32_t)kTailMaxDegree) {
+            for (uint32_t j = lo; j < hi; j += kPushSegment) list_seg[bs++] = RowSegment{e, j};
+        } else if (hi > lo) {
+            list_tail[bt++] = e;
+        }
+    }
+}
+
+template <int W>
+__device__ __forceinline__ unsigned long long or_across_groups(unsigned long long acc) {
+#pragma unroll
+    for (int m = W; m < 64; m <<= 1) acc |= shfl_xor64(acc, m);
+    return acc;
+}
+
+// live[w] = OR of the frontier lines of every subject row that has a triple:
+// the queries for which this hop can still reach something.  A pull row stops
+// as soon as it has all of them.
+template <int W>
+__global__ void __launch_bounds__(256)
+k_live(const int32_t *__restrict__ list_tail, const RowSegment *__restrict__ list_seg,
+       const unsigned long long *__restrict__ ctr, const uint32_t *__restrict__ out_off,
+       const unsigned long long *__restrict__ prev, unsigned long long *live) {
+    __shared__ unsigned long long sl[16];
+    if (threadIdx.x < 16) sl[threadIdx.x] = 0;
+    __syncthreads();
+    const long long nt = (long long)ctr[C_NTAIL], total = nt + (long long)ctr[C_NSEG];
+    const long long ngroups = (long long)gridDim.x * blockDim.x / W;
+    const int lw = threadIdx.x & (W - 1);
+    unsigned long long acc = 0;
+    for (long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W; i < total; i += ngroups) {
+        int row = -1;
+        if (i < nt) row = list_tail[i];
+        else {
+            RowSegment sg = list_seg[i - nt];
+            if (sg.begin == out_off[sg.row]) row = sg.row;  // count a long row once
+        }
+        if (row >= 0) acc |= prev[(size_t)row * W + lw];
+    }
+    acc = or_across_groups<W>(acc);
+    if (lane() < W && acc) atomicOr(&sl[lane()], acc);
+    __syncthreads();
+    if (threadIdx.x < W) {
+        unsigned long long x = sl[threadIdx.x];
+        if (x & ~live[threadIdx.x]) atomicOr(&live[threadIdx.x], x);
     }
 }
 
@@ -123,7 +167,7 @@ __device__ __forceinline__ void mark_active(uint32_t *act, int e) {
     if (!(act[e >> 5] & bit)) atomicOr(&act[e >> 5], bit);
 }
 
-// One W-lane group per frontier row; its edges are walked one after another.
+// One W-lane group per short frontier row; its edges are walked one after another.
 template <int W, bool MASK>
 __global__ void __launch_bounds__(256)
 k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restrict__ ctr,
@@ -153,8 +197,8 @@ k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restri
     }
 }
 
-// 64 consecutive edges of one row, handled by a whole wavefront: every lane
-// loads one edge, then the 64/W groups take the edges in turn.
+// 64 consecutive edges of one subject row, handled by a whole wavefront: every
+// lane loads one edge, then the 64/W groups take the edges in turn.
 template <int W, bool MASK>
 __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned long long line,
                                            const int32_t *__restrict__ obj, const uint16_t *__restrict__ rel,
@@ -197,24 +241,21 @@ __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned lo
     }
 }
 
-// One wavefront per frontier row (mid class) or one block per row (hubs).
-template <int W, bool MASK, bool HUB>
-__global__ void __launch_bounds__(512)
-k_push_coop(const int32_t *__restrict__ rows, const unsigned long long *__restrict__ ctr,
-            const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
-            const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
-            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
-            unsigned long long *cur, uint32_t *act_cur) {
-    int nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
-    long long row = HUB ? (long long)blockIdx.x : (long long)blockIdx.x * nw + wave;
-    long long n = (long long)ctr[HUB ? C_NHUB : C_NMID];
-    if (row >= n) return;
-    int s = rows[row];
+// One wavefront per segment of a long frontier row.
+template <int W, bool MASK>
+__global__ void __launch_bounds__(256)
+k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__restrict__ ctr,
+           const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
+           const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
+           const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
+           unsigned long long *cur, uint32_t *act_cur) {
+    long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (item >= (long long)ctr[C_NSEG]) return;
+    RowSegment sg = segs[item];
     int lw = lane() & (W - 1);
-    unsigned long long line = prev[(size_t)s * W + lw];
-    uint32_t lo = off[s], hi = off[s + 1];
-    uint32_t step = HUB ? 64u * nw : 64u;
-    for (uint32_t j0 = lo + (HUB ? 64u * wave : 0u); j0 < hi; j0 += step)
+    unsigned long long line = prev[(size_t)sg.row * W + lw];
+    uint32_t hi = min(sg.begin + (uint32_t)kPushSegment, off[sg.row + 1]);
+    for (uint32_t j0 = sg.begin; j0 < hi; j0 += 64)
         push_chunk<W, MASK>(j0, hi, line, obj, rel, allow, visited, cur, act_cur);
 }
 
@@ -247,7 +288,8 @@ __device__ __forceinline__ int take_candidates(unsigned long long &rest) {
 
 // 64 consecutive in-edges of one object row: lanes test whether their edge's
 // subject is in the frontier, then the groups gather the frontier lines of the
-// candidates.  acc collects (per group) the OR of the gathered words.
+// candidates, two rounds of loads in flight.  acc collects (per group) the OR
+// of the gathered words; returns the number of lines gathered.
 template <int W, bool MASK>
 __device__ __forceinline__ int pull_chunk(uint32_t j0, uint32_t hi, const int32_t *__restrict__ in_sub,
                                           const uint16_t *__restrict__ in_rel,
@@ -274,24 +316,21 @@ __device__ __forceinline__ int pull_chunk(uint32_t j0, uint32_t hi, const int32_
     } else {
         int lw = lane() & (W - 1);
         while (cm) {
-            int p = take_candidates<W>(cm);
-            int sc = __shfl(s, p < 0 ? 0 : p);
-            int rc = MASK ? __shfl(r, p < 0 ? 0 : p) : 0;
-            if (p >= 0) {
-                unsigned long long ln = prev[(size_t)sc * W + lw];
-                if (MASK) ln &= allow[(size_t)rc * W + lw];
-                acc |= ln;
+            int p0 = take_candidates<W>(cm);
+            int p1 = take_candidates<W>(cm);
+            int s0 = __shfl(s, p0 < 0 ? 0 : p0), s1 = __shfl(s, p1 < 0 ? 0 : p1);
+            int r0 = MASK ? __shfl(r, p0 < 0 ? 0 : p0) : 0, r1 = MASK ? __shfl(r, p1 < 0 ? 0 : p1) : 0;
+            unsigned long long l0 = 0, l1 = 0;
+            if (p0 >= 0) l0 = prev[(size_t)s0 * W + lw];
+            if (p1 >= 0) l1 = prev[(size_t)s1 * W + lw];
+            if (MASK) {
+                if (p0 >= 0) l0 &= allow[(size_t)r0 * W + lw];
+                if (p1 >= 0) l1 &= allow[(size_t)r1 * W + lw];
             }
+            acc |= l0 | l1;
         }
     }
     return ncand;
-}
-
-template <int W>
-__device__ __forceinline__ unsigned long long or_across_groups(unsigned long long acc) {
-#pragma unroll
-    for (int m = W; m < 64; m <<= 1) acc |= shfl_xor64(acc, m);
-    return acc;
 }
 
 __device__ __forceinline__ void add_stats(unsigned long long *stats, long long rows, long long edges,
@@ -307,37 +346,70 @@ __device__ __forceinline__ void add_stats(unsigned long long *stats, long long r
     }
 }
 
-// One W-lane group per object row (in-degree <= 32).
+template <int W>
+__device__ __forceinline__ unsigned group_ballot(bool p) {
+    if constexpr (W == 1) return p ? 1u : 0u;
+    else {
+        unsigned long long b = __ballot(p);
+        return (unsigned)((b >> (lane() & ~(W - 1))) & ((1ull << W) - 1ull));
+    }
+}
+
+// One W-lane group per short object row (<= 32 entries): the group's lanes load
+// W entries at once, then gather the frontier lines of the candidates.
 template <int W, bool MASK>
 __global__ void __launch_bounds__(256)
-k_pull_tail(const int32_t *__restrict__ rows, long long n, int Q, const uint32_t *__restrict__ off,
+k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__restrict__ off,
             const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
             const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
-            const unsigned long long *__restrict__ prev, unsigned long long *visited,
-            unsigned long long *cur, uint32_t *act_cur, unsigned long long *stats) {
+            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
+            unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
+            unsigned long long *stats) {
     long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
-    int lw = threadIdx.x & (W - 1);
+    const int lw = threadIdx.x & (W - 1), g0 = lane() & ~(W - 1);
     uint32_t lo = 0, hi = 0;
     int v = 0;
     unsigned long long vis = 0, need = 0, acc = 0;
     if (gidx < n) {
         v = rows[gidx];
         vis = visited[(size_t)v * W + lw];
-        need = ~vis & query_bits(Q, lw);
-        if (group_any<W>(need != 0)) {
-            lo = off[v];
-            hi = off[v + 1];
-        }
+        need = ~vis & live[lw];
+    }
+    if (group_any<W>(need != 0)) {
+        lo = off[v];
+        hi = off[v + 1];
     }
     long long n_edges = 0, n_lines = 0;
-    for (uint32_t j = lo; j < hi; ++j) {
-        int s = in_sub[j];
-        ++n_edges;
-        if (!((act_prev[s >> 5] >> (s & 31)) & 1u)) continue;
-        unsigned long long ln = prev[(size_t)s * W + lw];
-        if (MASK) ln &= allow[(size_t)in_rel[j] * W + lw];
-        acc |= ln;
-        ++n_lines;
+    for (uint32_t j0 = lo; j0 < hi; j0 += W) {
+        uint32_t j = j0 + lw;
+        int s = 0, r = 0;
+        bool cand = false;
+        if (j < hi) {
+            s = in_sub[j];
+            cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+            if (MASK && cand) r = in_rel[j];
+        }
+        unsigned gm = group_ballot<W>(cand);
+        n_edges += min((uint32_t)W, hi - j0);
+        n_lines += __popc(gm);
+        while (gm) {
+            int c0 = __ffs((int)gm) - 1;
+            gm &= gm - 1;
+            int c1 = -1;
+            if (gm) {
+                c1 = __ffs((int)gm) - 1;
+                gm &= gm - 1;
+            }
+            int s0 = __shfl(s, g0 + c0), s1 = __shfl(s, g0 + (c1 < 0 ? c0 : c1));
+            unsigned long long l0 = prev[(size_t)s0 * W + lw], l1 = 0;
+            if (c1 >= 0) l1 = prev[(size_t)s1 * W + lw];
+            if (MASK) {
+                int r0 = __shfl(r, g0 + c0), r1 = __shfl(r, g0 + (c1 < 0 ? c0 : c1));
+                l0 &= allow[(size_t)r0 * W + lw];
+                if (c1 >= 0) l1 &= allow[(size_t)r1 * W + lw];
+            }
+            acc |= l0 | l1;
+        }
         if (!group_any<W>((need & ~acc) != 0)) break;
     }
     unsigned long long nw = acc & need;
@@ -352,69 +424,90 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, int Q, const uint32_t
     }
 }
 
-// One wavefront per object row (mid class) or one block per row (hubs).
-template <int W, bool MASK, bool HUB>
-__global__ void __launch_bounds__(512)
-k_pull_coop(const int32_t *__restrict__ rows, long long n, int Q, const uint32_t *__restrict__ off,
-            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
-            const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
-            const unsigned long long *__restrict__ prev, unsigned long long *visited,
-            unsigned long long *cur, uint32_t *act_cur, unsigned long long *stats) {
-    __shared__ unsigned long long sacc[16];
-    int nw = blockDim.x >> 6, wave = threadIdx.x >> 6;
-    long long row = HUB ? (long long)blockIdx.x : (long long)blockIdx.x * nw + wave;
-    bool live = row < n;  // wave-uniform; block-uniform when HUB
-    int lw = lane() & (W - 1);
-    int v = live ? rows[row] : 0;
+// One wavefront per segment (<= 1024 entries) of a longer object row.  A row
+// with one segment is finished here; segments of a multi-segment row merge
+// through atomicOr on level[h] and look at what the others have found so far
+// to stop early; k_pull_finish then folds those rows into visited.
+template <int W, bool MASK>
+__global__ void __launch_bounds__(256)
+k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__restrict__ off,
+           const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
+           const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
+           const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
+           unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
+           unsigned long long *stats) {
+    long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const bool have = item < n;  // wave-uniform
+    const int lw = lane() & (W - 1);
+    int v = 0;
+    uint32_t lo = 0, hi = 0;
+    bool multi = false;
     unsigned long long vis = 0, need = 0, acc = 0;
-    if (live) {
+    if (have) {
+        RowSegment sg = segs[item];
+        v = sg.row;
+        lo = sg.begin;
+        uint32_t row_lo = off[v], row_hi = off[v + 1];
+        hi = min(lo + (uint32_t)kPullSegment, row_hi);
+        multi = (row_hi - row_lo) > (uint32_t)kPullSegment;
         vis = visited[(size_t)v * W + lw];
-        need = ~vis & query_bits(Q, lw);
+        need = ~vis & live[lw];
+        if (multi) need &= ~__atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
     }
-    bool work = wave_any(need != 0);  // same on every wave of a hub block
-    if (HUB) {
-        if (threadIdx.x < 16) sacc[threadIdx.x] = 0;
-        __syncthreads();
-    }
+    const bool work = wave_any(need != 0);
     long long n_edges = 0, n_lines = 0;
     if (work) {
-        uint32_t lo = off[v], hi = off[v + 1];
-        uint32_t step = HUB ? 64u * nw : 64u;
         int it = 0;
-        for (uint32_t j0 = lo + (HUB ? 64u * wave : 0u); j0 < hi; j0 += step, ++it) {
+        for (uint32_t j0 = lo; j0 < hi; j0 += 64, ++it) {
             n_lines += pull_chunk<W, MASK>(j0, hi, in_sub, in_rel, act_prev, prev, allow, acc);
             n_edges += min((uint32_t)64, hi - j0);
             acc = or_across_groups<W>(acc);
-            if (HUB && (it & 3) == 3) {  // fold what the other waves found
-                if (lane() < W) acc |= atomicOr(&sacc[lane()], acc);
-                acc = shfl64(acc, lw);
-            }
+            if (multi && (it & 3) == 3) acc |= __atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
             if (!wave_any((need & ~acc) != 0)) break;
         }
-    }
-    if (HUB) {
-        if (work && lane() < W) atomicOr(&sacc[lane()], acc);
-        __syncthreads();
-        acc = sacc[lw];
-    }
-    if (work && (!HUB || wave == 0)) {
         unsigned long long nb = acc & need;
         if (wave_any(nb != 0)) {
-            if (lane() < W) {
-                cur[(size_t)v * W + lane()] = nb;
-                visited[(size_t)v * W + lane()] = vis | nb;
+            if (!multi) {
+                if (lane() < W) {
+                    cur[(size_t)v * W + lane()] = nb;
+                    visited[(size_t)v * W + lane()] = vis | nb;
+                }
+                if (lane() == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
+            } else if (lane() < W && nb) {
+                atomicOr(&cur[(size_t)v * W + lane()], nb);
             }
-            if (lane() == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
         }
     }
     if (stats) {
         bool lead = lane() == 0;
-        add_stats(stats, (lead && work && (!HUB || wave == 0)) ? 1 : 0, lead ? n_edges : 0,
-                  lead ? n_lines : 0);
+        add_stats(stats, (lead && work) ? 1 : 0, lead ? n_edges : 0, lead ? n_lines : 0);
+    }
+}
+
+// Rows that were expanded by several segments: visited |= level[h], mark active.
+template <int W>
+__global__ void __launch_bounds__(256)
+k_pull_finish(const int32_t *__restrict__ rows, long long n, unsigned long long *visited,
+              const unsigned long long *__restrict__ cur, uint32_t *act_cur) {
+    long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
+    const int lw = threadIdx.x & (W - 1);
+    unsigned long long c = 0;
+    int v = 0;
+    if (gidx < n) {
+        v = rows[gidx];
+        c = cur[(size_t)v * W + lw];
+    }
+    if (group_any<W>(c != 0)) {
+        visited[(size_t)v * W + lw] |= c;
+        if (lw == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
     }
 }
 
 // ---------------------------------------------------------------- host side
+static inline unsigned blocks_for(long long threads, int block) {
+    return (unsigned)((threads + block - 1) / block);
+}
+
 template <int W, bool MASK>
 static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
                         hipStream_t st) {
@@ -422,59 +515,57 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     const unsigned long long *prev = r->levels + plane * (h - 1);
     unsigned long long *cur = r->levels + plane * h;
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
-    long long nt = (long long)hc[C_NTAIL], nm = (long long)hc[C_NMID], nh = (long long)hc[C_NHUB];
+    long long nt = (long long)hc[C_NTAIL], ns = (long long)hc[C_NSEG];
+    if (ns > 0) {
+        ProfScope ps(g->prof, KK_PUSH_SEG, st);
+        k_push_seg<W, MASK><<<dim3(blocks_for(ns, 4)), dim3(256), 0, st>>>(
+            g->fr_seg, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+        g->prof.acc[KK_PUSH_SEG].units[0] += g->prof.on ? ns : 0;
+    }
     if (nt > 0) {
         ProfScope ps(g->prof, KK_PUSH_TAIL, st);
-        long long threads = nt * W;
-        k_push_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
+        k_push_tail<W, MASK><<<dim3(blocks_for(nt * W, 256)), dim3(256), 0, st>>>(
             g->fr_tail, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
         g->prof.acc[KK_PUSH_TAIL].units[0] += g->prof.on ? nt : 0;
     }
-    if (nm > 0) {
-        ProfScope ps(g->prof, KK_PUSH_MID, st);
-        k_push_coop<W, MASK, false><<<dim3((unsigned)((nm + 3) / 4)), dim3(256), 0, st>>>(
-            g->fr_mid, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
-        g->prof.acc[KK_PUSH_MID].units[0] += g->prof.on ? nm : 0;
-    }
-    if (nh > 0) {
-        ProfScope ps(g->prof, KK_PUSH_HUB, st);
-        k_push_coop<W, MASK, true><<<dim3((unsigned)nh), dim3(512), 0, st>>>(
-            g->fr_hub, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
-        g->prof.acc[KK_PUSH_HUB].units[0] += g->prof.on ? nh : 0;
-    }
-    long long nwords = (long long)plane;
     ProfScope ps(g->prof, KK_UPDATE, st);
-    k_update_visited<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(nwords, W, act_cur, cur,
-                                                                                  r->visited);
+    k_update_visited<<<dim3(blocks_for((long long)plane, 256)), dim3(256), 0, st>>>((long long)plane, W, act_cur,
+                                                                                    cur, r->visited);
 }
 
 template <int W, bool MASK>
-static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_stats, hipStream_t st) {
+static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_stats,
+                        const unsigned long long *hc, hipStream_t st) {
     const size_t plane = (size_t)r->Epad * W;
     const unsigned long long *prev = r->levels + plane * (h - 1);
     unsigned long long *cur = r->levels + plane * h;
     const uint32_t *act_prev = r->act + (size_t)(r->Epad / 32) * (h - 1);
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
+    unsigned long long *live = r->live + (size_t)16 * (h - 1);
     auto stats = [&](int kind) { return want_stats ? g->d_ctr + C_STATS + 4 * kind : nullptr; };
     const RowClasses &rc = g->in_rows;
-    if (rc.n_hub > 0) {
-        ProfScope ps(g->prof, KK_PULL_HUB, st);
-        k_pull_coop<W, MASK, true><<<dim3((unsigned)rc.n_hub), dim3(512), 0, st>>>(
-            rc.hub, rc.n_hub, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
-            act_cur, stats(KK_PULL_HUB));
+    {
+        ProfScope ps(g->prof, KK_LIVE, st);
+        long long items = (long long)(hc[C_NTAIL] + hc[C_NSEG]);
+        unsigned nb = std::min<unsigned>(1024u, std::max(1u, blocks_for(items * W, 256)));
+        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(g->fr_tail, g->fr_seg, g->d_ctr, g->out_off, prev, live);
     }
-    if (rc.n_mid > 0) {
-        ProfScope ps(g->prof, KK_PULL_MID, st);
-        k_pull_coop<W, MASK, false><<<dim3((unsigned)((rc.n_mid + 3) / 4)), dim3(256), 0, st>>>(
-            rc.mid, rc.n_mid, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
-            act_cur, stats(KK_PULL_MID));
+    if (rc.n_seg > 0) {
+        ProfScope ps(g->prof, KK_PULL_SEG, st);
+        k_pull_seg<W, MASK><<<dim3(blocks_for(rc.n_seg, 4)), dim3(256), 0, st>>>(
+            rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
+            act_cur, stats(KK_PULL_SEG));
     }
     if (rc.n_tail > 0) {
         ProfScope ps(g->prof, KK_PULL_TAIL, st);
-        long long threads = rc.n_tail * W;
-        k_pull_tail<W, MASK><<<dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st>>>(
-            rc.tail, rc.n_tail, r->Q, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, r->visited, cur,
+        k_pull_tail<W, MASK><<<dim3(blocks_for(rc.n_tail * W, 256)), dim3(256), 0, st>>>(
+            rc.tail, rc.n_tail, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
             act_cur, stats(KK_PULL_TAIL));
+    }
+    if (rc.n_multi > 0) {
+        ProfScope ps(g->prof, KK_PULL_FINISH, st);
+        k_pull_finish<W><<<dim3(blocks_for(rc.n_multi * W, 256)), dim3(256), 0, st>>>(rc.multi, rc.n_multi,
+                                                                                      r->visited, cur, act_cur);
     }
 }
 
@@ -482,8 +573,8 @@ template <int W>
 static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
                     const unsigned long long *hc, hipStream_t st) {
     if (pull) {
-        if (r->has_mask) launch_pull<W, true>(g, r, h, want_stats, st);
-        else launch_pull<W, false>(g, r, h, want_stats, st);
+        if (r->has_mask) launch_pull<W, true>(g, r, h, want_stats, hc, st);
+        else launch_pull<W, false>(g, r, h, want_stats, hc, st);
     } else {
         if (r->has_mask) launch_push<W, true>(g, r, h, hc, st);
         else launch_push<W, false>(g, r, h, hc, st);
@@ -505,9 +596,8 @@ static logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, bool wr
     long long nwords = r->Epad / 32;
     {
         ProfScope ps(g->prof, KK_CENSUS, st);
-        k_census<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(
-            r->act + (size_t)nwords * h, nwords, g->out_off, g->hub_min, write_lists ? 1 : 0, g->fr_tail,
-            g->fr_mid, g->fr_hub, g->d_ctr);
+        k_census<<<dim3(blocks_for(nwords, 256)), dim3(256), 0, st>>>(
+            r->act + (size_t)nwords * h, nwords, g->out_off, write_lists ? 1 : 0, g->fr_tail, g->fr_seg, g->d_ctr);
     }
     LKG_HIP(hipGetLastError());
     LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
@@ -525,8 +615,8 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     if (!r) return;
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
-    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->tile_cnt, r->tile_base,
-                    r->super_base, r->d_reached_off, r->hub_slot};
+    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_cnt, r->tile_base,
+                    r->super_base, r->mega_base, r->d_reached_off, r->hub_slot};
     for (void *p : ptrs) g->pool.release(p);
     delete r;
 }
@@ -569,6 +659,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     if ((s = g->pool.alloc((void **)&r->visited, plane * 8)) != LOGOSKG_OK) return fail(s);
     if ((s = g->pool.alloc((void **)&r->levels, plane * 8 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
     if ((s = g->pool.alloc((void **)&r->act, actw * 4 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
+    if ((s = g->pool.alloc((void **)&r->live, (size_t)16 * 8 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
     if (r->has_mask && (s = g->pool.alloc((void **)&r->allow, (size_t)g->R * W * 8)) != LOGOSKG_OK) return fail(s);
 
 #define KH(call)                                  \
@@ -582,6 +673,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
         KH(hipMemsetAsync(r->visited, 0, plane * 8, st));
         KH(hipMemsetAsync(r->levels, 0, plane * 8 * (size_t)(k + 1), st));
         KH(hipMemsetAsync(r->act, 0, actw * 4 * (size_t)(k + 1), st));
+        KH(hipMemsetAsync(r->live, 0, (size_t)16 * 8 * (size_t)(k + 1), st));
         KH(hipMemsetAsync(g->d_ctr, 0, C_TOTAL * sizeof(unsigned long long), st));
         g->prof.acc[KK_CLEAR].units[3] += g->prof.on ? (long long)(plane * (size_t)(k + 2)) : 0;
     }
@@ -606,7 +698,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     }
     for (int h = 1; h <= k; ++h) {
         logoskg_hop_stats &hs = r->stats[h - 1];
-        long long rows = (long long)(g->h_ctr[C_NTAIL] + g->h_ctr[C_NMID] + g->h_ctr[C_NHUB]);
+        long long rows = (long long)g->h_ctr[C_NROWS];
         long long fedges = (long long)g->h_ctr[C_FEDGES];
         if (rows == 0) break;  // nothing can be reached any more: the remaining levels stay empty
         hs.active_rows = rows;
@@ -622,14 +714,15 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
             hs.shards_touched = 1;
             unsigned long long hc[C_TOTAL];
             memcpy(hc, g->h_ctr, sizeof(hc));
-            KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
+            if (want_stats)
+                KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
             launch_resident_hop(g, r, h, pull, want_stats, hc, st);
             KH(hipGetLastError());
         }
         if ((s = census(g, r, h, h < k, st)) != LOGOSKG_OK) return fail(s);
         hs.entities_reached = (long long)g->h_ctr[C_NACTIVE];
         if (hs.direction == LOGOSKG_DIR_PULL) {
-            for (int kind : {KK_PULL_TAIL, KK_PULL_MID, KK_PULL_HUB}) {
+            for (int kind : {KK_PULL_TAIL, KK_PULL_SEG}) {
                 const unsigned long long *c = g->h_ctr + C_STATS + 4 * kind;
                 hs.rows_scanned += (long long)c[0];
                 hs.edges_scanned += (long long)c[1];

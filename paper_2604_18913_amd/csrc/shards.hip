@@ -31,7 +31,7 @@ extern "C" logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg
     o->hub_min_degree = g->hub_min;
     o->num_out_rows = g->n_out_rows;
     o->num_out_hubs = g->n_out_hubs;
-    o->num_in_rows = g->in_rows.n_tail + g->in_rows.n_mid + g->in_rows.n_hub;
+    o->num_in_rows = g->in_rows.n_tail + g->in_rows.n_long;
     o->num_in_hubs = g->in_rows.n_hub;
     o->device_bytes = (int64_t)(g->static_bytes + g->pool.bytes_held());
     o->pinned_host_bytes = (int64_t)g->pinned_bytes;
