@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=32)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch a plain 1 GiB device copy and a 1 GiB fill, so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding across GPUs, no collectives); "
@@ -81,6 +84,15 @@ def main():
     seed_off = torch.from_numpy(w.seed_off).to(dev)
     seeds = torch.from_numpy(w.seeds).to(dev)
     Q, k = w.num_queries, w.k
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 27, dtype=torch.int64, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)        # reads 1 GiB, writes 1 GiB
+            dst.fill_(7)          # writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # sizes are deterministic: one untimed call sizes the output buffers
     res = g.khop(seed_off, seeds, k)
