@@ -18,7 +18,9 @@ MUTATIONS = {
     "mask_bit_index_wrong": ("(mask[r >> 6] >> (r & 63))", "(mask[r >> 6] >> ((r + 1) & 63))"),
     "subject_used_as_target": ("int32_t v = obj[t];\n    if (st->hop[v] == UNREACHED) {",
                                "int32_t v = obj[t > 0 ? t - 1 : t];\n    if (st->hop[v] == UNREACHED) {"),
-    "one_hop_too_many": ("for (int h = 1; h <= k; ++h) {", "for (int h = 1; h <= k + 1; ++h) {"),
+    # (the traversed[] write is kept inside its k entries so the planted bug cannot corrupt the heap)
+    "one_hop_too_many": ("for (int h = 1; h <= k; ++h) {\n        int64_t inspected = 0;",
+                         "for (int h = 1; h <= k + 1; ++h) {\n        int64_t inspected = 0; if (h > k) trav = NULL;"),
     "one_hop_too_few": ("for (int h = 1; h <= k; ++h) {", "for (int h = 1; h < k; ++h) {"),
     "traversed_counts_only_allowed": ("                    ++inspected;\n                    if (!relation_allowed(mask, rel[t])) continue;",
                                       "                    if (!relation_allowed(mask, rel[t])) continue;\n                    ++inspected;"),
