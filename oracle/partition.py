@@ -1,0 +1,76 @@
+"""Oracle side of the scalable-retrieval pieces (paper Sec. 3.4) -- TEST
+INFRASTRUCTURE ONLY, plain Python.
+
+* degree_aware_partition: the partition reading used by this build -- subjects
+  sorted by (out-degree descending, id ascending), each given to the shard with
+  the fewest triples so far, ties to the lowest shard index.  The paper fixes
+  only the properties (disjoint, a subject's triples stay together, high-degree
+  subjects spread evenly, balanced), which `check_partition_properties` tests.
+* lru_counts: the on-demand cache of capacity n sub-graphs under
+  least-recently-used replacement, counting loads, evictions and hits.
+* shard_accesses: the sub-graphs Algorithm 1 touches, hop by hop (those that
+  hold a subject of the current frontier), in ascending shard order.
+"""
+from __future__ import annotations
+
+import heapq
+from collections import OrderedDict
+
+import numpy as np
+
+
+def degree_aware_partition(num_entities: int, subj: np.ndarray, m: int):
+    deg = np.bincount(subj, minlength=num_entities)
+    subjects = [int(e) for e in np.nonzero(deg)[0]]
+    subjects.sort(key=lambda e: (-int(deg[e]), e))
+    heap = [(0, s) for s in range(m)]
+    heapq.heapify(heap)
+    P = np.full(num_entities, -1, dtype=np.int32)
+    loads = np.zeros(m, dtype=np.int64)
+    for e in subjects:
+        load, s = heapq.heappop(heap)
+        P[e] = s
+        load += int(deg[e])
+        loads[s] = load
+        heapq.heappush(heap, (load, s))
+    return P, loads
+
+
+def check_partition_properties(num_entities, subj, P, loads, m):
+    deg = np.bincount(subj, minlength=num_entities)
+    assert np.all((P >= 0) == (deg > 0)), "exactly the subjects are assigned"
+    assert P.max(initial=-1) < m
+    # all triples of a subject are in one shard and the shard sizes add up
+    assert np.array_equal(np.bincount(P[subj], minlength=m), loads)
+    assert loads.sum() == subj.shape[0]
+    # balance: greedy longest-first keeps every shard within one largest row of the mean
+    assert loads.max() - loads.min() <= max(int(deg.max()), 1)
+
+
+def lru_counts(accesses, capacity: int):
+    cache = OrderedDict()
+    loads = evictions = hits = 0
+    for a in accesses:
+        if a in cache:
+            hits += 1
+            cache.move_to_end(a)
+        else:
+            if len(cache) >= capacity:
+                cache.popitem(last=False)
+                evictions += 1
+            cache[a] = True
+            loads += 1
+    return loads, evictions, hits
+
+
+def shard_accesses(P, subj, num_entities, k, entity, hop):
+    """entity / hop: concatenated result lists of all queries of one batch."""
+    deg = np.bincount(subj, minlength=num_entities)
+    seq = []
+    for h in range(1, k + 1):
+        front = np.unique(entity[hop == h - 1])
+        front = front[deg[front] > 0]
+        if front.size == 0:
+            break
+        seq.extend(sorted(set(int(x) for x in P[front])))
+    return seq

@@ -210,6 +210,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         if (g->num_shards > 1) {
             if ((st = build_shards(g, subj, rel, obj, &o)) != LOGOSKG_OK) return fail(st);
         } else {
+            g->row_begin = g->out_off;
             {   // SUB: stable counting sort by subject
                 std::vector<int32_t> oobj((size_t)T);
                 std::vector<uint16_t> orel((size_t)T);

@@ -127,6 +127,9 @@ struct logoskg_graph {
 
     // subject-sorted CSR (SUB): row s -> objects / relations of its triples
     uint32_t *out_off = nullptr;  // [E+1]
+    uint32_t *row_begin = nullptr;    // [E] start of each subject's triples in the edge arrays
+                                      // (== out_off when resident; shard-grouped order otherwise)
+    uint8_t *shard_of_dev = nullptr;  // [Epad] device copy of the map P (255 = no shard)
     int32_t *out_obj = nullptr;   // [T]
     uint16_t *out_rel = nullptr;  // [T]
     // object-sorted CSR (OBJ): row v -> subjects / relations / edge ids of its triples
@@ -231,6 +234,10 @@ __device__ __forceinline__ unsigned long long query_bits(int Q, int w) {
 
 inline int words_for_queries(int Q) { return Q <= 64 ? 1 : (Q <= 256 ? 4 : 16); }
 
+logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
+void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
+                       const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st);
+void shard_info(const logoskg_graph *g, logoskg_graph_info *o);
 logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
                                logoskg_hop_stats *hs);
 void free_shards(logoskg_graph *g);

@@ -79,11 +79,23 @@ __device__ __forceinline__ int wave_excl_scan(int v, int &total) {
 // Turns the active bitmap of a level into the work lists of a push hop (short
 // subject rows; segments of the longer ones) and the counters the host needs
 // to pick the direction.
+//
+// row_begin[e] is where the triples of subject e start in the edge arrays (equal
+// to out_off for a resident graph; shard-grouped order for a sharded one).  With
+// shard_of != NULL only the subjects of `shard` are listed (Algorithm 1, line 6:
+// restriction of the frontier to one sub-graph).
 __global__ void k_census(const uint32_t *__restrict__ act, long long nwords,
-                         const uint32_t *__restrict__ out_off, int write_lists,
+                         const uint32_t *__restrict__ out_off, const uint32_t *__restrict__ row_begin,
+                         const uint8_t *__restrict__ shard_of, int shard, int write_lists,
                          int32_t *list_tail, RowSegment *list_seg, unsigned long long *ctr) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t word = i < nwords ? act[i] : 0u;
+    if (shard_of) {  // drop the entities of other shards
+        for (uint32_t m = word; m; m &= m - 1) {
+            int b = __ffs((int)m) - 1;
+            if (shard_of[i * 32 + b] != (uint8_t)shard) word &= ~(1u << b);
+        }
+    }
     int ct = 0, cs = 0, cr = 0;
     long long deg_sum = 0;
     for (uint32_t m = word; m; m &= m - 1) {
@@ -112,7 +124,7 @@ __global__ void k_census(const uint32_t *__restrict__ act, long long nwords,
     bs = shfl64(bs, 0) + ps;
     for (uint32_t m = word; m; m &= m - 1) {
         int e = (int)(i * 32) + (__ffs((int)m) - 1);
-        uint32_t lo = out_off[e], hi = out_off[e + 1];
+        uint32_t lo = row_begin[e], hi = lo + (out_off[e + 1] - out_off[e]);
         if (hi - lo > (uint32_t)kTailMaxDegree) {
             for (uint32_t j = lo; j < hi; j += kPushSegment) list_seg[bs++] = RowSegment{e, j};
         } else if (hi > lo) {
@@ -134,7 +146,7 @@ __device__ __forceinline__ unsigned long long or_across_groups(unsigned long lon
 template <int W>
 __global__ void __launch_bounds__(256)
 k_live(const int32_t *__restrict__ list_tail, const RowSegment *__restrict__ list_seg,
-       const unsigned long long *__restrict__ ctr, const uint32_t *__restrict__ out_off,
+       const unsigned long long *__restrict__ ctr, const uint32_t *__restrict__ row_begin,
        const unsigned long long *__restrict__ prev, unsigned long long *live) {
     __shared__ unsigned long long sl[16];
     if (threadIdx.x < 16) sl[threadIdx.x] = 0;
@@ -148,7 +160,7 @@ k_live(const int32_t *__restrict__ list_tail, const RowSegment *__restrict__ lis
         if (i < nt) row = list_tail[i];
         else {
             RowSegment sg = list_seg[i - nt];
-            if (sg.begin == out_off[sg.row]) row = sg.row;  // count a long row once
+            if (sg.begin == row_begin[sg.row]) row = sg.row;  // count a long row once
         }
         if (row >= 0) acc |= prev[(size_t)row * W + lw];
     }
@@ -171,7 +183,8 @@ __device__ __forceinline__ void mark_active(uint32_t *act, int e) {
 template <int W, bool MASK>
 __global__ void __launch_bounds__(256)
 k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restrict__ ctr,
-            const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
+            const uint32_t *__restrict__ off, const uint32_t *__restrict__ row_begin,
+            const int32_t *__restrict__ obj,
             const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
             const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
             unsigned long long *cur, uint32_t *act_cur) {
@@ -182,8 +195,8 @@ k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restri
     unsigned long long line = 0;
     if (gidx < n) {
         int s = rows[gidx];
-        lo = off[s];
-        hi = off[s + 1];
+        lo = row_begin[s];
+        hi = lo + (off[s + 1] - off[s]);
         line = prev[(size_t)s * W + lw];
     }
     for (uint32_t j = lo; j < hi; ++j) {
@@ -245,7 +258,8 @@ __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned lo
 template <int W, bool MASK>
 __global__ void __launch_bounds__(256)
 k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__restrict__ ctr,
-           const uint32_t *__restrict__ off, const int32_t *__restrict__ obj,
+           const uint32_t *__restrict__ off, const uint32_t *__restrict__ row_begin,
+           const int32_t *__restrict__ obj,
            const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
            unsigned long long *cur, uint32_t *act_cur) {
@@ -254,7 +268,8 @@ k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__rest
     RowSegment sg = segs[item];
     int lw = lane() & (W - 1);
     unsigned long long line = prev[(size_t)sg.row * W + lw];
-    uint32_t hi = min(sg.begin + (uint32_t)kPushSegment, off[sg.row + 1]);
+    uint32_t row_end = row_begin[sg.row] + (off[sg.row + 1] - off[sg.row]);
+    uint32_t hi = min(sg.begin + (uint32_t)kPushSegment, row_end);
     for (uint32_t j0 = sg.begin; j0 < hi; j0 += 64)
         push_chunk<W, MASK>(j0, hi, line, obj, rel, allow, visited, cur, act_cur);
 }
@@ -510,7 +525,7 @@ static inline unsigned blocks_for(long long threads, int block) {
 
 template <int W, bool MASK>
 static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
-                        hipStream_t st) {
+                        const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st) {
     const size_t plane = (size_t)r->Epad * W;
     const unsigned long long *prev = r->levels + plane * (h - 1);
     unsigned long long *cur = r->levels + plane * h;
@@ -519,15 +534,16 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     if (ns > 0) {
         ProfScope ps(g->prof, KK_PUSH_SEG, st);
         k_push_seg<W, MASK><<<dim3(blocks_for(ns, 4)), dim3(256), 0, st>>>(
-            g->fr_seg, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+            g->fr_seg, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, r->visited, cur, act_cur);
         g->prof.acc[KK_PUSH_SEG].units[0] += g->prof.on ? ns : 0;
     }
     if (nt > 0) {
         ProfScope ps(g->prof, KK_PUSH_TAIL, st);
         k_push_tail<W, MASK><<<dim3(blocks_for(nt * W, 256)), dim3(256), 0, st>>>(
-            g->fr_tail, g->d_ctr, g->out_off, g->out_obj, g->out_rel, r->allow, prev, r->visited, cur, act_cur);
+            g->fr_tail, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, r->visited, cur, act_cur);
         g->prof.acc[KK_PUSH_TAIL].units[0] += g->prof.on ? nt : 0;
     }
+    if (!update) return;
     ProfScope ps(g->prof, KK_UPDATE, st);
     k_update_visited<<<dim3(blocks_for((long long)plane, 256)), dim3(256), 0, st>>>((long long)plane, W, act_cur,
                                                                                     cur, r->visited);
@@ -548,7 +564,7 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
         ProfScope ps(g->prof, KK_LIVE, st);
         long long items = (long long)(hc[C_NTAIL] + hc[C_NSEG]);
         unsigned nb = std::min<unsigned>(1024u, std::max(1u, blocks_for(items * W, 256)));
-        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(g->fr_tail, g->fr_seg, g->d_ctr, g->out_off, prev, live);
+        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(g->fr_tail, g->fr_seg, g->d_ctr, g->row_begin, prev, live);
     }
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
@@ -576,8 +592,28 @@ static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool 
         if (r->has_mask) launch_pull<W, true>(g, r, h, want_stats, hc, st);
         else launch_pull<W, false>(g, r, h, want_stats, hc, st);
     } else {
-        if (r->has_mask) launch_push<W, true>(g, r, h, hc, st);
-        else launch_push<W, false>(g, r, h, hc, st);
+        if (r->has_mask) launch_push<W, true>(g, r, h, hc, g->out_obj, g->out_rel, true, st);
+        else launch_push<W, false>(g, r, h, hc, g->out_obj, g->out_rel, true, st);
+    }
+}
+
+// Push of the lists the last census wrote, reading the edge arrays through the
+// given base pointers (a shard slot, shifted so that grouped edge indices apply).
+void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
+                       const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st) {
+    switch (r->W) {
+        case 1:
+            if (r->has_mask) launch_push<1, true>(g, r, h, hc, obj, rel, update, st);
+            else launch_push<1, false>(g, r, h, hc, obj, rel, update, st);
+            break;
+        case 4:
+            if (r->has_mask) launch_push<4, true>(g, r, h, hc, obj, rel, update, st);
+            else launch_push<4, false>(g, r, h, hc, obj, rel, update, st);
+            break;
+        default:
+            if (r->has_mask) launch_push<16, true>(g, r, h, hc, obj, rel, update, st);
+            else launch_push<16, false>(g, r, h, hc, obj, rel, update, st);
+            break;
     }
 }
 
@@ -590,14 +626,16 @@ void launch_resident_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, 
     }
 }
 
-// Census of level h's active bitmap; leaves the counters in g->h_ctr (stream synchronised).
-static logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, bool write_lists, hipStream_t st) {
+// Census of level h's active bitmap (all subjects, or those of one shard); leaves
+// the counters in g->h_ctr (stream synchronised).
+logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st) {
     LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 5 * sizeof(unsigned long long), st));
     long long nwords = r->Epad / 32;
     {
         ProfScope ps(g->prof, KK_CENSUS, st);
         k_census<<<dim3(blocks_for(nwords, 256)), dim3(256), 0, st>>>(
-            r->act + (size_t)nwords * h, nwords, g->out_off, write_lists ? 1 : 0, g->fr_tail, g->fr_seg, g->d_ctr);
+            r->act + (size_t)nwords * h, nwords, g->out_off, g->row_begin, shard >= 0 ? g->shard_of_dev : nullptr,
+            shard, write_lists ? 1 : 0, g->fr_tail, g->fr_seg, g->d_ctr);
     }
     LKG_HIP(hipGetLastError());
     LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
@@ -691,7 +729,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     g->prof.end(st);
     KH(hipGetLastError());
     const bool want_stats = g->prof.counters;
-    if ((s = census(g, r, 0, k > 0, st)) != LOGOSKG_OK) return fail(s);
+    if ((s = census(g, r, 0, -1, k > 0 && g->num_shards <= 1, st)) != LOGOSKG_OK) return fail(s);
     if (g->h_ctr[C_ERR]) {
         set_error("seed_off / seeds are inconsistent or out of range (device check, code %llu)", g->h_ctr[C_ERR]);
         return fail(LOGOSKG_EINVAL);
@@ -708,6 +746,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
             if ((s = run_sharded_hop(g, r, h, st, &hs)) != LOGOSKG_OK) return fail(s);
             hs.edges_scanned = fedges;
             hs.lines_gathered = fedges;
+            KH(hipGetLastError());
         } else {
             bool pull = dir == LOGOSKG_DIR_PULL || (dir == LOGOSKG_DIR_AUTO && fedges * 12 > g->T);
             hs.direction = pull ? LOGOSKG_DIR_PULL : LOGOSKG_DIR_PUSH;
@@ -719,7 +758,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
             launch_resident_hop(g, r, h, pull, want_stats, hc, st);
             KH(hipGetLastError());
         }
-        if ((s = census(g, r, h, h < k, st)) != LOGOSKG_OK) return fail(s);
+        if ((s = census(g, r, h, -1, h < k && g->num_shards <= 1, st)) != LOGOSKG_OK) return fail(s);
         hs.entities_reached = (long long)g->h_ctr[C_NACTIVE];
         if (hs.direction == LOGOSKG_DIR_PULL) {
             for (int kind : {KK_PULL_TAIL, KK_PULL_SEG}) {

@@ -1,20 +1,295 @@
-// Sharded graphs (paper Sec. 3.4, Algorithm 1): placeholder until the shard
-// cache is built; logoskg_build rejects num_shards > 1 through build_shards.
+// Graphs larger than the HBM budget (paper Sec. 3.4, Algorithm 1).
+//
+// Degree-aware partitioning: the subjects are sorted by (out-degree descending,
+// id ascending) and each is given to the shard that holds the fewest triples so
+// far (ties: lowest shard index), so high-degree subjects spread evenly and all
+// triples of a subject stay together.  The map P (shard of each subject) lives
+// in HBM; the triples (objects, relations) are kept in pinned host memory,
+// grouped by shard, and move into a fixed number of HBM slots on demand under a
+// least-recently-used policy.  One hop = for every shard that has an active
+// subject, in ascending shard order: make it resident (hit, or load and maybe
+// evict), restrict the frontier to its subjects, push, OR into the global next
+// level (object ids are global, so "map back" is free).  The next shard's load
+// is issued on a copy stream while the current one computes.
+#include <algorithm>
+#include <queue>
+
 #include "common.h"
 
 namespace lkg {
 
-logoskg_status build_shards(logoskg_graph *, const int32_t *, const int32_t *, const int32_t *,
-                            const logoskg_build_opts *) {
-    set_error("sharded graphs are not available in this build");
-    return LOGOSKG_EINVAL;
+struct ShardSet {
+    int n = 0;
+    std::vector<int64_t> edge_begin;  // [n+1] positions in the shard-grouped edge arrays
+    int32_t *h_obj = nullptr;         // pinned host, [T] grouped by shard
+    uint16_t *h_rel = nullptr;        // pinned host, [T]
+    // cache
+    int n_slots = 0;
+    size_t slot_edges = 0;  // capacity of a slot = largest shard
+    std::vector<int32_t *> slot_obj;
+    std::vector<uint16_t *> slot_rel;
+    std::vector<int> slot_shard, shard_slot;
+    std::vector<uint64_t> slot_used;
+    std::vector<hipEvent_t> slot_ready, slot_idle;
+    uint64_t tick = 0;
+    hipStream_t copy_stream = nullptr;
+    int64_t loads = 0, evictions = 0, hits = 0, bytes_h2d = 0;
+    unsigned long long *d_route = nullptr, *h_route = nullptr;  // [2*128] rows / edges per shard
+};
+
+// per-shard number of active subjects and of their triples (Algorithm 1, line 2)
+__global__ void k_route(const uint32_t *__restrict__ act, long long nwords,
+                        const uint32_t *__restrict__ out_off, const uint8_t *__restrict__ shard_of,
+                        unsigned long long *route) {
+    __shared__ unsigned int s_rows[128];
+    __shared__ unsigned long long s_edges[128];
+    if (threadIdx.x < 128) {
+        s_rows[threadIdx.x] = 0;
+        s_edges[threadIdx.x] = 0;
+    }
+    __syncthreads();
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t word = i < nwords ? act[i] : 0u;
+    for (uint32_t m = word; m; m &= m - 1) {
+        long long e = i * 32 + (__ffs((int)m) - 1);
+        uint32_t d = out_off[e + 1] - out_off[e];
+        if (d == 0) continue;
+        int s = shard_of[e];
+        atomicAdd(&s_rows[s & 127], 1u);
+        atomicAdd(&s_edges[s & 127], (unsigned long long)d);
+    }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        if (s_rows[threadIdx.x]) atomicAdd(&route[threadIdx.x], (unsigned long long)s_rows[threadIdx.x]);
+        if (s_edges[threadIdx.x]) atomicAdd(&route[128 + threadIdx.x], s_edges[threadIdx.x]);
+    }
 }
 
-void free_shards(logoskg_graph *) {}
+void free_shards(logoskg_graph *g) {
+    ShardSet *ss = (ShardSet *)g->shards;
+    if (!ss) return;
+    if (ss->copy_stream) (void)hipStreamSynchronize(ss->copy_stream);
+    for (auto p : ss->slot_obj) if (p) (void)hipFree(p);
+    for (auto p : ss->slot_rel) if (p) (void)hipFree(p);
+    for (auto e : ss->slot_ready) if (e) (void)hipEventDestroy(e);
+    for (auto e : ss->slot_idle) if (e) (void)hipEventDestroy(e);
+    if (ss->copy_stream) (void)hipStreamDestroy(ss->copy_stream);
+    if (ss->h_obj) (void)hipHostFree(ss->h_obj);
+    if (ss->h_rel) (void)hipHostFree(ss->h_rel);
+    if (ss->d_route) (void)hipFree(ss->d_route);
+    if (ss->h_route) (void)hipHostFree(ss->h_route);
+    if (g->row_begin && g->row_begin != g->out_off) (void)hipFree(g->row_begin);
+    if (g->shard_of_dev) (void)hipFree(g->shard_of_dev);
+    g->row_begin = nullptr;
+    g->shard_of_dev = nullptr;
+    delete ss;
+    g->shards = nullptr;
+}
 
-logoskg_status run_sharded_hop(logoskg_graph *, logoskg_result *, int, hipStream_t, logoskg_hop_stats *) {
-    set_error("sharded graphs are not available in this build");
-    return LOGOSKG_EINTERNAL;
+logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                            const logoskg_build_opts *opts) {
+    const int n = g->num_shards;
+    const int32_t E = g->E;
+    const int64_t T = g->T;
+    ShardSet *ss = new (std::nothrow) ShardSet();
+    if (!ss) { set_error("out of host memory"); return LOGOSKG_ENOMEM; }
+    g->shards = ss;
+    ss->n = n;
+
+    // out-degrees
+    std::vector<uint32_t> deg((size_t)E, 0);
+    for (int64_t t = 0; t < T; ++t) deg[subj[t]]++;
+    // subjects by (degree desc, id asc); counting sort on the degree keeps it O(E + maxdeg)
+    uint32_t maxdeg = 0;
+    for (int32_t e = 0; e < E; ++e) maxdeg = std::max(maxdeg, deg[e]);
+    std::vector<int64_t> first((size_t)maxdeg + 2, 0);
+    for (int32_t e = 0; e < E; ++e) if (deg[e]) first[deg[e]]++;
+    {   // positions for descending degree
+        int64_t run = 0;
+        for (int64_t d = maxdeg; d >= 1; --d) { int64_t c = first[d]; first[d] = run; run += c; }
+    }
+    std::vector<int32_t> order((size_t)g->n_out_rows);
+    for (int32_t e = 0; e < E; ++e) if (deg[e]) order[(size_t)first[deg[e]]++] = e;
+    // greedy: lightest shard so far, ties to the lowest index
+    g->shard_of.assign((size_t)E, -1);
+    g->shard_triples.assign((size_t)n, 0);
+    typedef std::pair<int64_t, int> Load;  // (triples, shard)
+    std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+    for (int s = 0; s < n; ++s) heap.push(Load(0, s));
+    for (int32_t e : order) {
+        Load l = heap.top();
+        heap.pop();
+        g->shard_of[e] = l.second;
+        l.first += deg[e];
+        g->shard_triples[(size_t)l.second] = l.first;
+        heap.push(l);
+    }
+    ss->edge_begin.assign((size_t)n + 1, 0);
+    for (int s = 0; s < n; ++s) ss->edge_begin[(size_t)s + 1] = ss->edge_begin[s] + g->shard_triples[s];
+    // row_begin: subjects of a shard in ascending id inside the shard's range
+    std::vector<uint32_t> row_begin((size_t)E, 0);
+    {
+        std::vector<int64_t> cur(ss->edge_begin.begin(), ss->edge_begin.end() - 1);
+        for (int32_t e = 0; e < E; ++e) {
+            int s = g->shard_of[e];
+            if (s < 0) continue;
+            row_begin[e] = (uint32_t)cur[s];
+            cur[s] += deg[e];
+        }
+    }
+    size_t ob = std::max<int64_t>(T, 1) * sizeof(int32_t), rb = std::max<int64_t>(T, 1) * sizeof(uint16_t);
+    if (hipHostMalloc((void **)&ss->h_obj, ob, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc((void **)&ss->h_rel, rb, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("pinned host allocation of %zu bytes failed", ob + rb);
+        return LOGOSKG_ENOMEM;
+    }
+    g->pinned_bytes += ob + rb;
+    {
+        std::vector<uint32_t> cur(row_begin);
+        for (int64_t t = 0; t < T; ++t) {
+            uint32_t p = cur[subj[t]]++;
+            ss->h_obj[p] = obj[t];
+            ss->h_rel[p] = (uint16_t)rel[t];
+        }
+    }
+    // device metadata: row_begin and the map P
+    LKG_HIP(hipMalloc((void **)&g->row_begin, (size_t)E * sizeof(uint32_t)));
+    LKG_HIP(hipMemcpy(g->row_begin, row_begin.data(), (size_t)E * sizeof(uint32_t), hipMemcpyHostToDevice));
+    g->static_bytes += (size_t)E * sizeof(uint32_t);
+    {
+        std::vector<uint8_t> p8((size_t)g->Epad, 255);
+        for (int32_t e = 0; e < E; ++e) if (g->shard_of[e] >= 0) p8[e] = (uint8_t)g->shard_of[e];
+        LKG_HIP(hipMalloc((void **)&g->shard_of_dev, (size_t)g->Epad));
+        LKG_HIP(hipMemcpy(g->shard_of_dev, p8.data(), (size_t)g->Epad, hipMemcpyHostToDevice));
+        g->static_bytes += (size_t)g->Epad;
+    }
+    // cache slots
+    int64_t largest = 1;
+    for (int s = 0; s < n; ++s) largest = std::max(largest, g->shard_triples[s]);
+    ss->slot_edges = (size_t)largest;
+    size_t slot_bytes = ss->slot_edges * (sizeof(int32_t) + sizeof(uint16_t));
+    int slots = n;
+    if (opts->max_resident_shards > 0) slots = std::min(slots, opts->max_resident_shards);
+    if (opts->hbm_shard_budget_bytes > 0) {
+        uint64_t fit = opts->hbm_shard_budget_bytes / slot_bytes;
+        if (fit == 0) {
+            set_error("hbm_shard_budget_bytes = %llu is smaller than one shard (%zu bytes)",
+                      (unsigned long long)opts->hbm_shard_budget_bytes, slot_bytes);
+            return LOGOSKG_ENOMEM;
+        }
+        slots = (int)std::min<uint64_t>((uint64_t)slots, fit);
+    }
+    ss->n_slots = slots;
+    ss->slot_obj.assign((size_t)slots, nullptr);
+    ss->slot_rel.assign((size_t)slots, nullptr);
+    ss->slot_shard.assign((size_t)slots, -1);
+    ss->shard_slot.assign((size_t)n, -1);
+    ss->slot_used.assign((size_t)slots, 0);
+    ss->slot_ready.assign((size_t)slots, nullptr);
+    ss->slot_idle.assign((size_t)slots, nullptr);
+    for (int i = 0; i < slots; ++i) {
+        LKG_HIP(hipMalloc((void **)&ss->slot_obj[i], ss->slot_edges * sizeof(int32_t)));
+        LKG_HIP(hipMalloc((void **)&ss->slot_rel[i], ss->slot_edges * sizeof(uint16_t)));
+        g->static_bytes += slot_bytes;
+        LKG_HIP(hipEventCreateWithFlags(&ss->slot_ready[i], hipEventDisableTiming));
+        LKG_HIP(hipEventCreateWithFlags(&ss->slot_idle[i], hipEventDisableTiming));
+    }
+    LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
+    LKG_HIP(hipMalloc((void **)&ss->d_route, 256 * sizeof(unsigned long long)));
+    if (hipHostMalloc((void **)&ss->h_route, 256 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
+        set_error("hipHostMalloc failed");
+        return LOGOSKG_ENOMEM;
+    }
+    return LOGOSKG_OK;
+}
+
+// Makes `shard` resident and returns its slot: a hit refreshes its use stamp; a
+// miss takes an empty slot or evicts the least recently used one and starts the
+// copy on the copy stream (after the kernels that last read the slot).
+static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStream_t compute, int *slot_out) {
+    int slot = ss->shard_slot[shard];
+    if (slot >= 0) {
+        ss->hits++;
+    } else {
+        slot = -1;
+        for (int i = 0; i < ss->n_slots; ++i)
+            if (ss->slot_shard[i] < 0) { slot = i; break; }
+        if (slot < 0) {
+            slot = 0;
+            for (int i = 1; i < ss->n_slots; ++i)
+                if (ss->slot_used[i] < ss->slot_used[slot]) slot = i;
+            ss->shard_slot[ss->slot_shard[slot]] = -1;
+            ss->evictions++;
+        }
+        int64_t b = ss->edge_begin[shard], cnt = ss->edge_begin[(size_t)shard + 1] - b;
+        LKG_HIP(hipStreamWaitEvent(ss->copy_stream, ss->slot_idle[slot], 0));
+        if (cnt > 0) {
+            g->prof.begin(KK_SHARD_COPY, ss->copy_stream);
+            LKG_HIP(hipMemcpyAsync(ss->slot_obj[slot], ss->h_obj + b, (size_t)cnt * sizeof(int32_t),
+                                   hipMemcpyHostToDevice, ss->copy_stream));
+            LKG_HIP(hipMemcpyAsync(ss->slot_rel[slot], ss->h_rel + b, (size_t)cnt * sizeof(uint16_t),
+                                   hipMemcpyHostToDevice, ss->copy_stream));
+            g->prof.end(ss->copy_stream);
+        }
+        LKG_HIP(hipEventRecord(ss->slot_ready[slot], ss->copy_stream));
+        ss->slot_shard[slot] = shard;
+        ss->shard_slot[shard] = slot;
+        ss->loads++;
+        ss->bytes_h2d += cnt * (int64_t)(sizeof(int32_t) + sizeof(uint16_t));
+    }
+    ss->slot_used[slot] = ++ss->tick;
+    (void)compute;
+    *slot_out = slot;
+    return LOGOSKG_OK;
+}
+
+logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
+                               logoskg_hop_stats *hs) {
+    ShardSet *ss = (ShardSet *)g->shards;
+    if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
+    const long long nwords = r->Epad / 32;
+    const uint32_t *act_prev = r->act + (size_t)nwords * (h - 1);
+    // routing: which shards have an active subject
+    LKG_HIP(hipMemsetAsync(ss->d_route, 0, 256 * sizeof(unsigned long long), st));
+    k_route<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(act_prev, nwords, g->out_off,
+                                                                          g->shard_of_dev, ss->d_route);
+    LKG_HIP(hipGetLastError());
+    LKG_HIP(hipMemcpyAsync(ss->h_route, ss->d_route, 256 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    LKG_HIP(hipStreamSynchronize(st));
+    std::vector<int> active;
+    for (int s = 0; s < ss->n; ++s)
+        if (ss->h_route[s] > 0) active.push_back(s);
+    hs->shards_touched = (int)active.size();
+    std::vector<int> slot_of((size_t)active.size(), -1);
+    for (size_t i = 0; i < active.size(); ++i) {
+        const int shard = active[i];
+        if (slot_of[i] < 0) LKG_TRY(acquire(g, ss, shard, st, &slot_of[i]));
+        // with at least two slots the next shard's access can be issued now: it never
+        // evicts the shard in use (that one is the most recently used)
+        if (i + 1 < active.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
+            LKG_TRY(acquire(g, ss, active[i + 1], st, &slot_of[i + 1]));
+        const int slot = slot_of[i];
+        LKG_TRY(census(g, r, h - 1, shard, true, st));
+        unsigned long long hc[C_TOTAL];
+        memcpy(hc, g->h_ctr, sizeof(hc));
+        LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[slot], 0));
+        const int64_t b = ss->edge_begin[shard];
+        launch_push_lists(g, r, h, hc, ss->slot_obj[slot] - b, ss->slot_rel[slot] - b,
+                          i + 1 == active.size(), st);
+        LKG_HIP(hipGetLastError());
+        LKG_HIP(hipEventRecord(ss->slot_idle[slot], st));
+    }
+    return LOGOSKG_OK;
+}
+
+void shard_info(const logoskg_graph *g, logoskg_graph_info *o) {
+    const ShardSet *ss = (const ShardSet *)g->shards;
+    if (!ss) return;
+    o->shard_loads = ss->loads;
+    o->shard_evictions = ss->evictions;
+    o->shard_hits = ss->hits;
+    o->shard_bytes_h2d = ss->bytes_h2d;
 }
 
 }  // namespace lkg
@@ -35,6 +310,7 @@ extern "C" logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg
     o->num_in_hubs = g->in_rows.n_hub;
     o->device_bytes = (int64_t)(g->static_bytes + g->pool.bytes_held());
     o->pinned_host_bytes = (int64_t)g->pinned_bytes;
+    shard_info(g, o);
     return LOGOSKG_OK;
 }
 

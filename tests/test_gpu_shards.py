@@ -1,0 +1,83 @@
+"""GPU parity for graphs kept in pinned host memory and cached shard by shard
+(paper Sec. 3.4, Algorithm 1): results must not depend on the number of shards
+or on the cache capacity, the partition must equal the oracle's, and loads /
+evictions / hits must equal an LRU simulation of the shard access sequence."""
+import numpy as np
+import pytest
+
+import kggen
+import oracle
+from oracle import partition as part
+
+pytestmark = pytest.mark.gpu
+
+
+def lkg():
+    import paper_2604_18913_amd as m
+    return m
+
+
+def run_sharded(w, num_shards, max_resident=0, budget=0, repeat=1):
+    m = lkg()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=num_shards,
+                max_resident_shards=max_resident, hbm_shard_budget_bytes=budget)
+    outs = []
+    for _ in range(repeat):
+        res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+        off = res.offsets()
+        ent, hop, _ = res.fetch(want_pred=False)
+        trav = res.traversed().cpu().numpy()
+        outs.append((off, ent.cpu().numpy(), hop.cpu().numpy(), trav, res.hop_stats()))
+        res.close()
+    info = g.info()
+    P, per = g.partition()
+    g.close()
+    return outs, info, P, per
+
+
+@pytest.mark.parametrize("make", [lambda: kggen.config5(0.0005), lambda: kggen.config3(0.005, k=3),
+                                  lambda: kggen.config1()])
+@pytest.mark.parametrize("num_shards,max_resident", [(2, 0), (8, 0), (8, 1), (8, 2), (8, 3)])
+def test_sharded_results_and_cache_counters(make, num_shards, max_resident):
+    w = make()
+    print("case", w.name, num_shards, max_resident, flush=True)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
+    outs, info, P, per = run_sharded(w, num_shards, max_resident, repeat=2)
+    for off, ent, hop, trav, stats in outs:
+        assert np.array_equal(off, want[0])
+        assert np.array_equal(ent, want[1])
+        assert np.array_equal(hop, want[2])
+        assert np.array_equal(trav, want[4])
+    P_o, loads_o = part.degree_aware_partition(w.num_entities, w.subj, num_shards)
+    assert np.array_equal(P, P_o)
+    assert np.array_equal(per, loads_o)
+    seq = part.shard_accesses(P_o, w.subj, w.num_entities, w.k, want[1], want[2])
+    cap = num_shards if max_resident == 0 else min(max_resident, num_shards)
+    loads, ev, hits = part.lru_counts(seq + seq, cap)   # two identical batches on one graph
+    assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == (loads, ev, hits)
+    touched = [s["shards_touched"] for s in outs[0][4]]
+    assert sum(touched) == len(seq)
+    assert info["pinned_host_bytes"] == 6 * max(w.num_triples, 1)
+
+
+def test_byte_budget_and_errors():
+    m = lkg()
+    w = kggen.config5(0.0005)
+    # a budget of 2.5 slots gives 2 resident shards
+    P_o, loads_o = part.degree_aware_partition(w.num_entities, w.subj, 8)
+    slot_bytes = int(loads_o.max()) * 6
+    outs, info, _, _ = run_sharded(w, 8, budget=int(2.5 * slot_bytes))
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k)
+    seq = part.shard_accesses(P_o, w.subj, w.num_entities, w.k, want[1], want[2])
+    assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == part.lru_counts(seq, 2)
+    with pytest.raises(m.LogosKGError):
+        m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8,
+                hbm_shard_budget_bytes=slot_bytes // 2)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=4)
+    with pytest.raises(m.LogosKGError):
+        g.khop(w.seed_off, w.seeds, w.k, direction="pull")
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    with pytest.raises(m.LogosKGError):
+        res.fetch()  # predecessor edges need a resident graph
+    res.close()
+    g.close()

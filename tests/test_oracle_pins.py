@@ -340,3 +340,31 @@ def test_oracle_rejects_bad_arguments():
         one_query(3, [[0, 0, 1]], [7], 1)
     with pytest.raises(RuntimeError):
         one_query(3, [[0, 0, 1]], [0], 255)
+
+
+# ---------------------------------------------------------------- Sec. 3.4: partition and cache accounting
+def test_partition_properties_and_lru_accounting():
+    from oracle import partition as part
+    w = kggen.config5(0.0005, num_queries=64)
+    for m in (2, 8):
+        P, loads = part.degree_aware_partition(w.num_entities, w.subj, m)
+        part.check_partition_properties(w.num_entities, w.subj, P, loads, m)
+    # the heaviest subjects land in different shards
+    deg = np.bincount(w.subj, minlength=w.num_entities)
+    top = np.argsort(-deg, kind="stable")[:8]
+    P, _ = part.degree_aware_partition(w.num_entities, w.subj, 8)
+    assert len(set(P[top].tolist())) == 8
+    # LRU: textbook traces
+    assert part.lru_counts([0, 1, 2, 0, 1, 2], 3) == (3, 0, 3)
+    assert part.lru_counts([0, 1, 2, 0, 1, 2], 2) == (6, 4, 0)
+    assert part.lru_counts([0, 1, 0, 2, 0, 3], 2) == (4, 2, 2)
+    assert part.lru_counts([], 1) == (0, 0, 0)
+    # capacity >= number of shards: loads = distinct shards touched, no eviction (the paper's
+    # scalability table shows 16 loads / 0 evictions with 16 sub-graphs cached)
+    ro, ent, hop, pred, _ = run_oracle(w)
+    seq = part.shard_accesses(P, w.subj, w.num_entities, w.k, ent, hop)
+    loads, ev, hits = part.lru_counts(seq, 8)
+    assert loads == len(set(seq)) and ev == 0 and loads + hits == len(seq)
+    for cap in (1, 2, 4):
+        l2, e2, h2 = part.lru_counts(seq, cap)
+        assert l2 - e2 <= cap and l2 >= loads and l2 + h2 == len(seq)
