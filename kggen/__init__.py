@@ -95,25 +95,18 @@ def choose_dmin(alpha: float, cap: int, n: int, total: int) -> int:
 # triple assembly
 # --------------------------------------------------------------------------
 
-def _unique_keys(s, r, o, E, R):
-    """Sorted unique (s, r, o) triples as int64 arrays."""
-    s = s.astype(np.int64)
-    o = o.astype(np.int64)
-    r = r.astype(np.int64)
-    if float(E) * float(E) * float(R) < 2.0 ** 63:
-        key = np.unique((s * R + r) * E + o)
-        o2 = key % E
-        key //= E
-        return key // R, key % R, o2
-    # keys do not fit one word: sort (s, o) keys, then r inside equal runs
-    so = s * E + o
-    order = np.lexsort((r, so))
-    so = so[order]
-    rr = r[order]
-    keep = np.ones(so.shape[0], dtype=bool)
-    keep[1:] = (so[1:] != so[:-1]) | (rr[1:] != rr[:-1])
-    so = so[keep]
-    return so // E, rr[keep], so % E
+def _pack_keys(s, r, o, E, R):
+    """(s, r, o) -> one uint64 key per triple; needs E*E*R < 2^64."""
+    assert float(E) * float(E) * float(R) < 2.0 ** 64 * 0.999, "key does not fit 64 bits"
+    E64, R64 = np.uint64(E), np.uint64(R)
+    return (s.astype(np.uint64) * R64 + r.astype(np.uint64)) * E64 + o.astype(np.uint64)
+
+
+def _unpack_keys(key, E, R):
+    E64, R64 = np.uint64(E), np.uint64(R)
+    o = key % E64
+    key = key // E64
+    return (key // R64).astype(np.int64), (key % R64).astype(np.int64), o.astype(np.int64)
 
 
 def _assemble(rng, T, E, R, s_stubs, o_stubs, draw_rel):
@@ -122,25 +115,26 @@ def _assemble(rng, T, E, R, s_stubs, o_stubs, draw_rel):
     two hubs) are topped up by re-drawing pairs from the same stub lists, so
     the degree shape is kept, until T distinct triples exist or five rounds
     have passed.  The triples are finally shuffled so that edge ids carry no
-    locality."""
+    locality.  Ids are whatever the stub lists hold (callers may pass dense
+    ranks and map them back)."""
     n = int(min(s_stubs.shape[0], o_stubs.shape[0], T))
-    s = s_stubs[:n]
-    o = o_stubs[rng.permutation(o_stubs.shape[0])[:n]]
-    r = draw_rel(n)
-    s, r, o = _unique_keys(s, r, o, E, R)
+    keys = np.unique(_pack_keys(s_stubs[:n], draw_rel(n),
+                                o_stubs[rng.permutation(o_stubs.shape[0])[:n]], E, R))
     for _ in range(5):
-        missing = T - s.shape[0]
+        missing = T - keys.shape[0]
         if missing <= 0:
             break
         m = int(missing * 1.25) + 16
-        s_new = s_stubs[rng.integers(0, s_stubs.shape[0], size=m)]
-        o_new = o_stubs[rng.integers(0, o_stubs.shape[0], size=m)]
-        s, r, o = _unique_keys(np.concatenate([s, s_new]),
-                               np.concatenate([r, draw_rel(m)]),
-                               np.concatenate([o, o_new]), E, R)
-    perm = rng.permutation(s.shape[0])[:T]
-    return (s[perm].astype(np.int32), r[perm].astype(np.int32),
-            o[perm].astype(np.int32))
+        new = np.unique(_pack_keys(s_stubs[rng.integers(0, s_stubs.shape[0], size=m)], draw_rel(m),
+                                   o_stubs[rng.integers(0, o_stubs.shape[0], size=m)], E, R))
+        merged = np.sort(np.concatenate([keys, new]), kind="stable")  # two sorted runs: a linear merge
+        keep = np.ones(merged.shape[0], dtype=bool)
+        keep[1:] = merged[1:] != merged[:-1]
+        keys = merged[keep]
+        del merged, keep, new
+    perm = rng.permutation(keys.shape[0])[:T]
+    s, r, o = _unpack_keys(keys[perm], E, R)
+    return s, r, o
 
 
 def _zipf_rank_relations(rng, n, R, alpha):
@@ -195,9 +189,14 @@ def _correlated_powerlaw_graph(rng, E, T, R, alpha, cap, rel_alpha):
         draw_rel = lambda n: rng.integers(0, R, size=n)
     else:
         draw_rel = lambda n: _zipf_rank_relations(rng, n, R, rel_alpha)
-    s, r, o = _assemble(rng, T, E, R, np.repeat(perm, dout), np.repeat(perm, din),
+    # work on ranks (positions in `perm`): only the first `used` ranks carry edges, which keeps
+    # the 63-bit triple keys of the duplicate check small enough even for 10^8 entities
+    used = int(max((dout > 0).sum(), (din > 0).sum()))
+    ranks = np.arange(used, dtype=np.int64)
+    s, r, o = _assemble(rng, T, used, R, np.repeat(ranks, dout[:used]), np.repeat(ranks, din[:used]),
                         draw_rel)
-    return s, r, o, dict(dmin=dmin, cap=cap, alpha=alpha)
+    return (perm[s].astype(np.int32), r.astype(np.int32), perm[o].astype(np.int32),
+            dict(dmin=dmin, cap=cap, alpha=alpha))
 
 
 def _finish_manifest(w: Workload, extra: dict) -> Workload:
@@ -234,6 +233,7 @@ def config1(scale: float = 1.0) -> Workload:
     s, r, o = _assemble(rng, T, E, R, np.repeat(perm, dout),
                         np.arange(E, dtype=np.int64).repeat(-(-T // E)),
                         lambda n: rng.integers(0, R, size=n))
+    s, r, o = s.astype(np.int32), r.astype(np.int32), o.astype(np.int32)
     off, seeds = random_seed_sets(rng, 64, E, 1, 1)
     w = Workload("config1_tiny", E, R, s, r, o, off, seeds, k=2)
     return _finish_manifest(w, dict(dmin=dmin, cap=cap, alpha=2.0, scale=scale))
@@ -308,6 +308,7 @@ def config4(scale: float = 1.0, num_queries: int = 4096) -> Workload:
         rest[rng.integers(0, rest.shape[0], size=n_edges - n_obj_hub)]])
     s, r, o = _assemble(rng, T, E, R, s_stubs, o_stubs,
                         lambda n: rng.integers(0, R, size=n))
+    s, r, o = s.astype(np.int32), r.astype(np.int32), o.astype(np.int32)
     Q = num_queries
     seeds = np.empty(Q, dtype=np.int32)
     seeds[0::2] = hubs[rng.integers(0, n_hub, size=seeds[0::2].shape[0])]
@@ -342,7 +343,7 @@ def random_tiny(seed: int, E: int, T: int, R: int, Q: int, k: int,
     s = rng.integers(0, E, size=T)
     o = rng.integers(0, E, size=T)
     r = rng.integers(0, R, size=T)
-    s, r, o = _unique_keys(s, r, o, E, R)
+    s, r, o = _unpack_keys(np.unique(_pack_keys(s, r, o, E, R)), E, R)
     perm = rng.permutation(s.shape[0])
     s, r, o = (s[perm].astype(np.int32), r[perm].astype(np.int32),
                o[perm].astype(np.int32))

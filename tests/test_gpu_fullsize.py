@@ -1,0 +1,166 @@
+"""Full-size parity on the workloads of the benchmark spec, in the launch
+configuration bench.py times.  The oracle cannot list 10^9 (query, entity)
+pairs in seconds, so it runs on a seeded sample of the queries of the batch and
+every output integer of those queries is compared; invariants that hold at any
+size are checked on further queries.
+
+configs 2 and 3 always run.  configs 4 (300 M triples) and 5 (1 G triples)
+need minutes of input generation and tens of GB of host memory; they run when
+LOGOSKG_FULLSIZE names them, e.g. LOGOSKG_FULLSIZE=4,5."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+import kggen
+import oracle
+from helpers import check_invariants
+
+pytestmark = pytest.mark.gpu
+FULL = {int(x) for x in os.environ.get("LOGOSKG_FULLSIZE", "").split(",") if x.strip()}
+
+
+def lkg():
+    import paper_2604_18913_amd as m
+    return m
+
+
+def log(*a):
+    print(time.strftime("%H:%M:%S"), *a, flush=True)
+
+
+def sampled_queries(Q, n, seed, counts=None):
+    """Seeded sample of query indices; when the per-query reached counts are given, half of the
+    sample is drawn from the queries that reach more than their seeds (live queries)."""
+    rng = np.random.default_rng(seed)
+    n = min(n, Q)
+    if counts is None:
+        return np.sort(rng.choice(Q, size=n, replace=False))
+    live = np.nonzero(counts > np.median(counts))[0]
+    pick = set(rng.choice(live, size=min(n // 2, live.size), replace=False).tolist()) if live.size else set()
+    rest = [q for q in rng.permutation(Q).tolist() if q not in pick]
+    pick.update(rest[: n - len(pick)])
+    return np.array(sorted(pick))
+
+
+def sub_batch(w, qs):
+    lens = np.diff(w.seed_off)[qs]
+    off = np.zeros(len(qs) + 1, dtype=np.int64)
+    np.cumsum(lens, out=off[1:])
+    seeds = np.concatenate([w.seeds[w.seed_off[q]:w.seed_off[q + 1]] for q in qs]).astype(np.int32)
+    mask = None if w.rel_mask is None else w.rel_mask[qs]
+    return off, seeds, mask
+
+
+def compare_sample(w, res, qs, k, with_pred=True, n_invariants=2):
+    off = res.offsets()
+    so, sd, sm = sub_batch(w, qs)
+    t0 = time.time()
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, sm)
+    log(f"oracle on {len(qs)} queries: {time.time() - t0:.1f}s, {want[0][-1]} pairs")
+    trav = res.traversed().cpu().numpy()
+    for i, q in enumerate(qs):
+        a, b = int(want[0][i]), int(want[0][i + 1])
+        assert off[q + 1] - off[q] == b - a, f"query {q}: reached count"
+        ent, hop, pred = res.fetch(int(q), int(q) + 1, want_pred=with_pred)
+        assert np.array_equal(ent.cpu().numpy(), want[1][a:b]), f"query {q}: entities"
+        assert np.array_equal(hop.cpu().numpy(), want[2][a:b]), f"query {q}: hops"
+        if with_pred:
+            assert np.array_equal(pred.cpu().numpy(), want[3][a:b]), f"query {q}: predecessor edges"
+        assert np.array_equal(trav[q], want[4][i]), f"query {q}: traversed"
+    return want
+
+
+def test_config2_full_size():
+    m = lkg()
+    w = kggen.config2()
+    log("generated", w.manifest)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    qs = sampled_queries(w.num_queries, 24, 2, np.diff(res.offsets()))
+    compare_sample(w, res, qs, w.k)
+    # invariants on queries the oracle did not see
+    others = [int(q) for q in sampled_queries(w.num_queries, 40, 3) if q not in set(qs.tolist())][:3]
+    off = res.offsets()
+    for q in others:
+        ent, hop, pred = res.fetch(q, q + 1)
+        ro = np.array([0, ent.numel()], dtype=np.int64)
+        so, sd, sm = sub_batch(w, np.array([q]))
+        check_invariants(w.subj, w.rel, w.obj, so, sd, w.k, sm, ro, ent.cpu().numpy(), hop.cpu().numpy(),
+                         pred.cpu().numpy())
+    # forced directions give the same planes: compare counts and one query's lists
+    for direction in ("push", "pull"):
+        r2 = g.khop(w.seed_off, w.seeds, w.k, direction=direction)
+        assert np.array_equal(r2.offsets(), off), direction
+        q = int(qs[-1])
+        a = [t.cpu().numpy() for t in res.fetch(q, q + 1)]
+        b = [t.cpu().numpy() for t in r2.fetch(q, q + 1)]
+        assert all(np.array_equal(x, y) for x, y in zip(a, b)), direction
+        r2.close()
+    res.close()
+    g.close()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_config3_full_size_masks_and_paths(k):
+    m = lkg()
+    w = kggen.config3(k=k)
+    log("generated", w.name, "k", k)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    res = g.khop(w.seed_off, w.seeds, k, w.rel_mask)
+    qs = sampled_queries(w.num_queries, 12, 10 + k, np.diff(res.offsets()))
+    want = compare_sample(w, res, qs, k)
+    # up to 16 shortest paths for a seeded sample of 4,096 reached (query, entity) pairs
+    so, sd, sm = sub_batch(w, qs)
+    pq_local, pt = kggen.sample_reached_pairs(k, want[0], want[1], 4096)
+    t0 = time.time()
+    cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, pq_local, pt, 16, sm)
+    log(f"oracle paths: {time.time() - t0:.1f}s, {int(cnt_o.sum())} paths")
+    cnt, edges = g.paths(res, qs[pq_local].astype(np.int32), pt, 16)
+    assert np.array_equal(cnt.cpu().numpy(), cnt_o)
+    assert np.array_equal(edges.cpu().numpy(), edges_o)
+    res.close()
+    g.close()
+
+
+@pytest.mark.skipif(4 not in FULL, reason="set LOGOSKG_FULLSIZE=4 (300 M triples; minutes of generation)")
+def test_config4_full_size():
+    m = lkg()
+    t0 = time.time()
+    w = kggen.config4()
+    log(f"generated in {time.time() - t0:.0f}s", w.manifest)
+    t0 = time.time()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    log(f"built in {time.time() - t0:.0f}s", g.info())
+    for b in range(4):  # 4,096 queries as 4 batches of 1,024
+        lo, hi = b * 1024, (b + 1) * 1024
+        off = w.seed_off[lo:hi + 1] - w.seed_off[lo]
+        seeds = w.seeds[w.seed_off[lo]:w.seed_off[hi]]
+        sub = kggen.Workload(w.name, w.num_entities, w.num_relations, w.subj, w.rel, w.obj, off, seeds, w.k)
+        t0 = time.time()
+        res = g.khop(off, seeds, w.k)
+        log(f"batch {b}: khop {time.time() - t0:.2f}s total_reached {res.total_reached}", res.hop_stats())
+        qs = sampled_queries(1024, 6, 40 + b, np.diff(res.offsets()))
+        compare_sample(sub, res, qs, w.k)
+        res.close()
+    g.close()
+
+
+@pytest.mark.skipif(5 not in FULL, reason="set LOGOSKG_FULLSIZE=5 (1 G triples; ~100 GB of host memory)")
+def test_config5_full_size_sharded():
+    m = lkg()
+    t0 = time.time()
+    w = kggen.config5()
+    log(f"generated in {time.time() - t0:.0f}s", w.manifest)
+    t0 = time.time()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8,
+                hbm_shard_budget_bytes=64 << 30)
+    log(f"built in {time.time() - t0:.0f}s", g.info())
+    t0 = time.time()
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    log(f"khop {time.time() - t0:.2f}s total_reached {res.total_reached}", res.hop_stats(), g.info())
+    qs = sampled_queries(w.num_queries, 8, 50, np.diff(res.offsets()))
+    compare_sample(w, res, qs, w.k, with_pred=False)
+    res.close()
+    g.close()
