@@ -234,6 +234,35 @@ __device__ __forceinline__ unsigned long long query_bits(int Q, int w) {
 
 inline int words_for_queries(int Q) { return Q <= 64 ? 1 : (Q <= 256 ? 4 : 16); }
 
+// arguments of the list / predecessor kernels (result.hip)
+struct FillArgs {
+    int32_t E;
+    int Q, k, q0, q1, hub_min;
+    long long ntiles;
+    long long tile_begin, tile_count;  // tiles this predecessor launch covers
+    long long hub_begin;               // first hub row of this predecessor launch
+    long long plane;   // words per plane
+    long long actw;    // uint32 words per active bitmap
+    const unsigned long long *visited, *levels, *allow;
+    const uint32_t *act;
+    const uint16_t *tile_base;
+    const uint32_t *super_base, *mega_base;
+    const long long *reached_off;
+    const uint32_t *in_off;
+    const int32_t *in_sub, *in_eid;
+    const uint16_t *in_rel;
+    const int32_t *hubs;
+    long long n_hubs;
+    int32_t *entity;
+    uint8_t *hop;
+    int32_t *pred;
+    long long *hub_slot;
+    unsigned long long *stats_pred, *stats_hub;  // rows / edges / lines counters or NULL
+};
+
+void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
+void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hubs_here, bool mask, hipStream_t st);
+logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
                        const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st);

@@ -117,29 +117,6 @@ __device__ __forceinline__ unsigned long long range_bits(int q0, int q1, int w) 
     return query_bits(q1, w) & ~query_bits(q0, w);
 }
 
-struct FillArgs {
-    int32_t E;
-    int Q, k, q0, q1, hub_min;
-    long long ntiles;
-    long long plane;   // words per plane
-    long long actw;    // uint32 words per active bitmap
-    const unsigned long long *visited, *levels, *allow;
-    const uint32_t *act;
-    const uint16_t *tile_base;
-    const uint32_t *super_base, *mega_base;
-    const long long *reached_off;
-    const uint32_t *in_off;
-    const int32_t *in_sub, *in_eid;
-    const uint16_t *in_rel;
-    const int32_t *hubs;
-    long long n_hubs;
-    int32_t *entity;
-    uint8_t *hop;
-    int32_t *pred;
-    long long *hub_slot;
-    unsigned long long *stats_pred, *stats_hub;  // rows / edges / lines counters or NULL
-};
-
 // position of a super tile's first entry in the list of query q (relative to query q0's start)
 __device__ __forceinline__ long long super_start(const FillArgs &a, long long st, int Qp, int q) {
     return a.reached_off[q] - a.reached_off[a.q0] + a.mega_base[(size_t)(st / kMegaSupers) * Qp + q] +
@@ -306,8 +283,9 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     __shared__ unsigned long long stage[64][W + 1];
     __shared__ unsigned long long mT[Qp];
     __shared__ long long base[Qp];
-    const long long tile = xcd_contiguous(blockIdx.x, gridDim.x);
-    if (tile >= a.ntiles) return;
+    const long long tile_rel = xcd_contiguous(blockIdx.x, gridDim.x);
+    if (tile_rel >= a.tile_count) return;
+    const long long tile = a.tile_begin + tile_rel;
     const int t = threadIdx.x, wave = t >> 6, v = lane();
     {
         int q = t;
@@ -392,7 +370,7 @@ template <int W, bool MASK>
 __global__ void __launch_bounds__(1024) k_pred_hub(FillArgs a) {
     constexpr int Qp = 64 * W;
     __shared__ unsigned long long srem[16];
-    const long long hidx = blockIdx.x;
+    const long long hidx = a.hub_begin + blockIdx.x;
     const int ev = a.hubs[hidx];
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, lw = lane() & (W - 1);
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
@@ -497,28 +475,47 @@ logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
 }
 
 template <int W>
-static void launch_fill_w(Profiler &prof, const FillArgs &a, bool mask, hipStream_t st) {
+static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
     const long long nsuper = (a.ntiles + kSuperTiles - 1) / kSuperTiles;
-    {
-        ProfScope ps(prof, KK_LISTS, st);
-        int nb = 1;
-        while ((1 << nb) <= a.k) ++nb;
-        dim3 grid((unsigned)nsuper), block(64 * W);
-        if (nb <= 2) k_lists<W, 2><<<grid, block, 0, st>>>(a);
-        else if (nb <= 4) k_lists<W, 4><<<grid, block, 0, st>>>(a);
-        else k_lists<W, 8><<<grid, block, 0, st>>>(a);
-    }
-    if (!a.pred) return;
-    {
+    ProfScope ps(prof, KK_LISTS, st);
+    int nb = 1;
+    while ((1 << nb) <= a.k) ++nb;
+    dim3 grid((unsigned)nsuper), block(64 * W);
+    if (nb <= 2) k_lists<W, 2><<<grid, block, 0, st>>>(a);
+    else if (nb <= 4) k_lists<W, 4><<<grid, block, 0, st>>>(a);
+    else k_lists<W, 8><<<grid, block, 0, st>>>(a);
+}
+
+// predecessor kernels over the tiles [a.tile_begin, +a.tile_count) and `n_hubs_here` hub rows
+// starting at a.hub_begin
+template <int W>
+static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hubs_here, bool mask, hipStream_t st) {
+    if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st);
-        dim3 grid((unsigned)((a.ntiles + 7) / 8 * 8)), block(64 * W);
+        dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
         if (mask) k_pred<W, true><<<grid, block, 0, st>>>(a);
         else k_pred<W, false><<<grid, block, 0, st>>>(a);
     }
-    if (a.n_hubs > 0) {
+    if (n_hubs_here > 0) {
         ProfScope ps(prof, KK_PRED_HUB, st);
-        if (mask) k_pred_hub<W, true><<<dim3((unsigned)a.n_hubs), dim3(1024), 0, st>>>(a);
-        else k_pred_hub<W, false><<<dim3((unsigned)a.n_hubs), dim3(1024), 0, st>>>(a);
+        if (mask) k_pred_hub<W, true><<<dim3((unsigned)n_hubs_here), dim3(1024), 0, st>>>(a);
+        else k_pred_hub<W, false><<<dim3((unsigned)n_hubs_here), dim3(1024), 0, st>>>(a);
+    }
+}
+
+void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st) {
+    switch (W) {
+        case 1: launch_lists_w<1>(prof, a, st); break;
+        case 4: launch_lists_w<4>(prof, a, st); break;
+        default: launch_lists_w<16>(prof, a, st); break;
+    }
+}
+
+void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hubs_here, bool mask, hipStream_t st) {
+    switch (W) {
+        case 1: launch_pred_w<1>(prof, a, n_hubs_here, mask, st); break;
+        case 4: launch_pred_w<4>(prof, a, n_hubs_here, mask, st); break;
+        default: launch_pred_w<16>(prof, a, n_hubs_here, mask, st); break;
     }
 }
 
@@ -546,10 +543,6 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     if (need == 0) return LOGOSKG_OK;
     if (!entity) { set_error("entity buffer is NULL"); return LOGOSKG_EINVAL; }
     logoskg_graph *g = r->g;
-    if (pred && g->num_shards > 1) {
-        set_error("predecessor edges need a resident graph");
-        return LOGOSKG_EINVAL;
-    }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
     const int W = r->W, Qp = 64 * W;
@@ -558,6 +551,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     FillArgs a;
     a.E = g->E; a.Q = r->Q; a.k = r->k; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
     a.ntiles = r->Epad / kTileEntities;
+    a.tile_begin = 0; a.tile_count = a.ntiles; a.hub_begin = 0;
     a.plane = r->Epad * W; a.actw = r->Epad / 32;
     a.visited = r->visited; a.levels = r->levels; a.allow = r->allow;
     a.act = r->act; a.tile_base = r->tile_base; a.super_base = r->super_base; a.mega_base = r->mega_base;
@@ -569,10 +563,10 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
     if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
-    switch (W) {
-        case 1: launch_fill_w<1>(g->prof, a, r->has_mask, st); break;
-        case 4: launch_fill_w<4>(g->prof, a, r->has_mask, st); break;
-        default: launch_fill_w<16>(g->prof, a, r->has_mask, st); break;
+    launch_lists(g->prof, a, W, st);
+    if (pred) {
+        if (g->num_shards > 1) LKG_TRY(sharded_pred(g, &a, W, r->has_mask, st));
+        else launch_pred(g->prof, a, W, a.n_hubs, r->has_mask, st);
     }
     LKG_HIP(hipGetLastError());
     if (g->prof.on) {

@@ -35,6 +35,17 @@ struct ShardSet {
     hipStream_t copy_stream = nullptr;
     int64_t loads = 0, evictions = 0, hits = 0, bytes_h2d = 0;
     unsigned long long *d_route = nullptr, *h_route = nullptr;  // [2*128] rows / edges per shard
+    // object-sorted triples (for predecessor edges): pinned host arrays, streamed through two
+    // staging buffers in chunks of whole 64-entity tiles
+    int32_t *h_in_sub = nullptr, *h_in_eid = nullptr;
+    uint16_t *h_in_rel = nullptr;
+    struct Chunk { long long tile_begin, tile_count; int64_t edge_begin, edge_count; long long hub_begin, hub_count; };
+    std::vector<Chunk> chunks;
+    size_t stage_edges = 0;
+    int32_t *stage_sub[2] = {nullptr, nullptr}, *stage_eid[2] = {nullptr, nullptr};
+    uint16_t *stage_rel[2] = {nullptr, nullptr};
+    hipEvent_t stage_ready[2] = {nullptr, nullptr}, stage_idle[2] = {nullptr, nullptr};
+    int64_t in_bytes_h2d = 0;
 };
 
 // per-shard number of active subjects and of their triples (Algorithm 1, line 2)
@@ -74,6 +85,16 @@ void free_shards(logoskg_graph *g) {
     for (auto e : ss->slot_ready) if (e) (void)hipEventDestroy(e);
     for (auto e : ss->slot_idle) if (e) (void)hipEventDestroy(e);
     if (ss->copy_stream) (void)hipStreamDestroy(ss->copy_stream);
+    for (int i = 0; i < 2; ++i) {
+        if (ss->stage_sub[i]) (void)hipFree(ss->stage_sub[i]);
+        if (ss->stage_eid[i]) (void)hipFree(ss->stage_eid[i]);
+        if (ss->stage_rel[i]) (void)hipFree(ss->stage_rel[i]);
+        if (ss->stage_ready[i]) (void)hipEventDestroy(ss->stage_ready[i]);
+        if (ss->stage_idle[i]) (void)hipEventDestroy(ss->stage_idle[i]);
+    }
+    if (ss->h_in_sub) (void)hipHostFree(ss->h_in_sub);
+    if (ss->h_in_eid) (void)hipHostFree(ss->h_in_eid);
+    if (ss->h_in_rel) (void)hipHostFree(ss->h_in_rel);
     if (ss->h_obj) (void)hipHostFree(ss->h_obj);
     if (ss->h_rel) (void)hipHostFree(ss->h_rel);
     if (ss->d_route) (void)hipFree(ss->d_route);
@@ -84,6 +105,124 @@ void free_shards(logoskg_graph *g) {
     g->shard_of_dev = nullptr;
     delete ss;
     g->shards = nullptr;
+}
+
+// Object-sorted triples for the predecessor pass of a sharded graph: offsets and
+// the hub list stay in HBM, the per-triple arrays go to pinned host memory and
+// are cut into chunks of whole tiles holding about T / num_shards triples each.
+static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int32_t *subj, const int32_t *rel,
+                                      const int32_t *obj) {
+    const int32_t E = g->E;
+    const int64_t T = g->T;
+    std::vector<uint32_t> ioff((size_t)E + 1, 0);
+    for (int64_t t = 0; t < T; ++t) ioff[(size_t)obj[t] + 1]++;
+    std::vector<int32_t> hubs;
+    for (int32_t e = 0; e < E; ++e) {
+        if (ioff[(size_t)e + 1] >= (uint32_t)g->hub_min) hubs.push_back(e);
+        ioff[(size_t)e + 1] += ioff[e];
+    }
+    size_t n4 = std::max<int64_t>(T, 1) * sizeof(int32_t), n2 = std::max<int64_t>(T, 1) * sizeof(uint16_t);
+    if (hipHostMalloc((void **)&ss->h_in_sub, n4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc((void **)&ss->h_in_eid, n4, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc((void **)&ss->h_in_rel, n2, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("pinned host allocation of %zu bytes failed", 2 * n4 + n2);
+        return LOGOSKG_ENOMEM;
+    }
+    g->pinned_bytes += 2 * n4 + n2;
+    {
+        std::vector<uint32_t> cur(ioff.begin(), ioff.end() - 1);
+        for (int64_t t = 0; t < T; ++t) {
+            uint32_t p = cur[obj[t]]++;
+            ss->h_in_sub[p] = subj[t];
+            ss->h_in_rel[p] = (uint16_t)rel[t];
+            ss->h_in_eid[p] = (int32_t)t;
+        }
+    }
+    LKG_HIP(hipMalloc((void **)&g->in_off, ((size_t)E + 1) * sizeof(uint32_t)));
+    LKG_HIP(hipMemcpy(g->in_off, ioff.data(), ((size_t)E + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
+    g->static_bytes += ((size_t)E + 1) * sizeof(uint32_t);
+    g->in_rows.n_hub = (int64_t)hubs.size();
+    LKG_HIP(hipMalloc((void **)&g->in_rows.hub, std::max<size_t>(hubs.size(), 1) * sizeof(int32_t)));
+    if (!hubs.empty())
+        LKG_HIP(hipMemcpy(g->in_rows.hub, hubs.data(), hubs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    // chunks of whole tiles
+    const long long ntiles = g->Epad / kTileEntities;
+    const int64_t target = std::max<int64_t>(1, (T + g->num_shards - 1) / g->num_shards);
+    size_t hub_pos = 0;
+    long long t0 = 0;
+    while (t0 < ntiles) {
+        long long t1 = t0;
+        int64_t e_begin = ioff[(size_t)std::min<long long>(t0 * 64, E)], e_end = e_begin;
+        while (t1 < ntiles) {
+            int64_t nxt = ioff[(size_t)std::min<long long>((t1 + 1) * 64, E)];
+            if (t1 > t0 && nxt - e_begin > target) break;
+            e_end = nxt;
+            ++t1;
+        }
+        ShardSet::Chunk c;
+        c.tile_begin = t0; c.tile_count = t1 - t0; c.edge_begin = e_begin; c.edge_count = e_end - e_begin;
+        c.hub_begin = (long long)hub_pos;
+        while (hub_pos < hubs.size() && hubs[hub_pos] < t1 * 64) ++hub_pos;
+        c.hub_count = (long long)hub_pos - c.hub_begin;
+        ss->chunks.push_back(c);
+        ss->stage_edges = std::max(ss->stage_edges, (size_t)c.edge_count);
+        t0 = t1;
+    }
+    ss->stage_edges = std::max<size_t>(ss->stage_edges, 1);
+    for (int i = 0; i < 2; ++i) {
+        LKG_HIP(hipMalloc((void **)&ss->stage_sub[i], ss->stage_edges * sizeof(int32_t)));
+        LKG_HIP(hipMalloc((void **)&ss->stage_eid[i], ss->stage_edges * sizeof(int32_t)));
+        LKG_HIP(hipMalloc((void **)&ss->stage_rel[i], ss->stage_edges * sizeof(uint16_t)));
+        g->static_bytes += ss->stage_edges * 10;
+        LKG_HIP(hipEventCreateWithFlags(&ss->stage_ready[i], hipEventDisableTiming));
+        LKG_HIP(hipEventCreateWithFlags(&ss->stage_idle[i], hipEventDisableTiming));
+    }
+    return LOGOSKG_OK;
+}
+
+// Predecessor pass of a sharded graph: the object-sorted triples are streamed
+// chunk by chunk (double buffered: the next chunk copies while this one runs).
+logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st) {
+    ShardSet *ss = (ShardSet *)g->shards;
+    if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
+    auto issue = [&](size_t ci) -> logoskg_status {
+        const ShardSet::Chunk &c = ss->chunks[ci];
+        const int b = (int)(ci & 1);
+        LKG_HIP(hipStreamWaitEvent(ss->copy_stream, ss->stage_idle[b], 0));
+        if (c.edge_count > 0) {
+            g->prof.begin(KK_SHARD_COPY, ss->copy_stream);
+            LKG_HIP(hipMemcpyAsync(ss->stage_sub[b], ss->h_in_sub + c.edge_begin, (size_t)c.edge_count * 4,
+                                   hipMemcpyHostToDevice, ss->copy_stream));
+            LKG_HIP(hipMemcpyAsync(ss->stage_eid[b], ss->h_in_eid + c.edge_begin, (size_t)c.edge_count * 4,
+                                   hipMemcpyHostToDevice, ss->copy_stream));
+            if (mask)
+                LKG_HIP(hipMemcpyAsync(ss->stage_rel[b], ss->h_in_rel + c.edge_begin, (size_t)c.edge_count * 2,
+                                       hipMemcpyHostToDevice, ss->copy_stream));
+            g->prof.end(ss->copy_stream);
+            ss->in_bytes_h2d += c.edge_count * (mask ? 10 : 8);
+        }
+        LKG_HIP(hipEventRecord(ss->stage_ready[b], ss->copy_stream));
+        return LOGOSKG_OK;
+    };
+    if (!ss->chunks.empty()) LKG_TRY(issue(0));
+    for (size_t ci = 0; ci < ss->chunks.size(); ++ci) {
+        const ShardSet::Chunk &c = ss->chunks[ci];
+        const int b = (int)(ci & 1);
+        if (ci + 1 < ss->chunks.size()) LKG_TRY(issue(ci + 1));
+        LKG_HIP(hipStreamWaitEvent(st, ss->stage_ready[b], 0));
+        FillArgs x = *a;
+        x.in_sub = ss->stage_sub[b] - c.edge_begin;
+        x.in_eid = ss->stage_eid[b] - c.edge_begin;
+        x.in_rel = ss->stage_rel[b] - c.edge_begin;
+        x.tile_begin = c.tile_begin;
+        x.tile_count = c.tile_count;
+        x.hub_begin = c.hub_begin;
+        launch_pred(g->prof, x, W, c.hub_count, mask, st);
+        LKG_HIP(hipGetLastError());
+        LKG_HIP(hipEventRecord(ss->stage_idle[b], st));
+    }
+    return LOGOSKG_OK;
 }
 
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
@@ -196,6 +335,7 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         LKG_HIP(hipEventCreateWithFlags(&ss->slot_idle[i], hipEventDisableTiming));
     }
     LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
+    LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
     LKG_HIP(hipMalloc((void **)&ss->d_route, 256 * sizeof(unsigned long long)));
     if (hipHostMalloc((void **)&ss->h_route, 256 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
@@ -289,7 +429,7 @@ void shard_info(const logoskg_graph *g, logoskg_graph_info *o) {
     o->shard_loads = ss->loads;
     o->shard_evictions = ss->evictions;
     o->shard_hits = ss->hits;
-    o->shard_bytes_h2d = ss->bytes_h2d;
+    o->shard_bytes_h2d = ss->bytes_h2d + ss->in_bytes_h2d;
 }
 
 }  // namespace lkg

@@ -161,6 +161,7 @@ def test_config5_full_size_sharded():
     res = g.khop(w.seed_off, w.seeds, w.k)
     log(f"khop {time.time() - t0:.2f}s total_reached {res.total_reached}", res.hop_stats(), g.info())
     qs = sampled_queries(w.num_queries, 8, 50, np.diff(res.offsets()))
-    compare_sample(w, res, qs, w.k, with_pred=False)
+    compare_sample(w, res, qs, w.k)
+    log(g.info())
     res.close()
     g.close()

@@ -25,9 +25,9 @@ def run_sharded(w, num_shards, max_resident=0, budget=0, repeat=1):
     for _ in range(repeat):
         res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
         off = res.offsets()
-        ent, hop, _ = res.fetch(want_pred=False)
+        ent, hop, pred = res.fetch()
         trav = res.traversed().cpu().numpy()
-        outs.append((off, ent.cpu().numpy(), hop.cpu().numpy(), trav, res.hop_stats()))
+        outs.append((off, ent.cpu().numpy(), hop.cpu().numpy(), trav, res.hop_stats(), pred.cpu().numpy()))
         res.close()
     info = g.info()
     P, per = g.partition()
@@ -43,10 +43,11 @@ def test_sharded_results_and_cache_counters(make, num_shards, max_resident):
     print("case", w.name, num_shards, max_resident, flush=True)
     want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
     outs, info, P, per = run_sharded(w, num_shards, max_resident, repeat=2)
-    for off, ent, hop, trav, stats in outs:
+    for off, ent, hop, trav, stats, pred in outs:
         assert np.array_equal(off, want[0])
         assert np.array_equal(ent, want[1])
         assert np.array_equal(hop, want[2])
+        assert np.array_equal(pred, want[3])
         assert np.array_equal(trav, want[4])
     P_o, loads_o = part.degree_aware_partition(w.num_entities, w.subj, num_shards)
     assert np.array_equal(P, P_o)
@@ -57,7 +58,7 @@ def test_sharded_results_and_cache_counters(make, num_shards, max_resident):
     assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == (loads, ev, hits)
     touched = [s["shards_touched"] for s in outs[0][4]]
     assert sum(touched) == len(seq)
-    assert info["pinned_host_bytes"] == 6 * max(w.num_triples, 1)
+    assert info["pinned_host_bytes"] == 16 * max(w.num_triples, 1)  # 6 B subject-sorted + 10 B object-sorted
 
 
 def test_byte_budget_and_errors():
@@ -78,6 +79,11 @@ def test_byte_budget_and_errors():
         g.khop(w.seed_off, w.seeds, w.k, direction="pull")
     res = g.khop(w.seed_off, w.seeds, w.k)
     with pytest.raises(m.LogosKGError):
-        res.fetch()  # predecessor edges need a resident graph
+        g.paths(res, [0], [0], 4)  # path listing needs a resident graph
+    # sub-ranges of queries stream the object-sorted chunks again and give the same lists
+    ent, hop, pred = res.fetch(100, 164)
+    off = res.offsets()
+    a, b = want[0][100], want[0][164]
+    assert np.array_equal(pred.cpu().numpy(), want[3][a:b]) and np.array_equal(ent.cpu().numpy(), want[1][a:b])
     res.close()
     g.close()
