@@ -41,7 +41,7 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
     if kernel == "pred":
         # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked
         return n * 2 * plane_bytes + items * 4 + edges * 4
-    if kernel == "pred_hub":
+    if kernel == "pred_rows":
         return edges * 4
     if kernel == "clear_planes":
         return items * 8

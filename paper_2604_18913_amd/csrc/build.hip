@@ -68,7 +68,7 @@ void DevPool::trim() {
 const char *const kKernelNames[KK_NUM] = {
     "clear_planes", "seed_scatter", "frontier_census", "live_queries", "push_tail", "push_seg",
     "update_visited", "pull_tail", "pull_seg", "pull_finish", "count_tiles", "scan_counts",
-    "lists", "pred", "pred_hub", "traversed", "paths", "shard_copy"};
+    "lists", "pred", "pred_rows", "traversed", "paths", "shard_copy"};
 
 void Profiler::begin(int kind, hipStream_t st) {
     if (!on) return;
@@ -123,13 +123,13 @@ static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
 // rows first), rows with several segments, and the hub rows.
 static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_min,
                           std::vector<int32_t> &tail, std::vector<RowSegment> &seg,
-                          std::vector<int32_t> &multi, std::vector<int32_t> &hub, int64_t *n_long) {
+                          std::vector<int32_t> &multi, std::vector<int32_t> &longer, int64_t *n_hub) {
     std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
-    std::vector<int32_t> longer;
+    *n_hub = 0;
     for (int32_t v = 0; v < E; ++v) {
         uint32_t d = off[v + 1] - off[v];
         if (d == 0) continue;
-        if (d >= (uint32_t)hub_min) hub.push_back(v);
+        if (d >= (uint32_t)hub_min) ++*n_hub;
         if (d > (uint32_t)kTailMaxDegree) longer.push_back(v);
         else bucket[d].push_back(v);
     }
@@ -141,7 +141,6 @@ static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_m
         if (off[v + 1] - off[v] > (uint32_t)kPullSegment) multi.push_back(v);
         for (uint32_t j = off[v]; j < off[v + 1]; j += kPullSegment) seg.push_back({v, j});
     }
-    *n_long = (int64_t)longer.size();
 }
 
 }  // namespace lkg
@@ -240,17 +239,17 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
                 if ((st = upload(&g->in_sub, isub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rel, irel, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_eid, ieid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                std::vector<int32_t> tail, multi, hub;
+                std::vector<int32_t> tail, multi, longer;
                 std::vector<RowSegment> seg;
-                classify_rows(ioff, E, g->hub_min, tail, seg, multi, hub, &g->in_rows.n_long);
+                classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
                 g->in_rows.n_tail = (int64_t)tail.size();
                 g->in_rows.n_seg = (int64_t)seg.size();
                 g->in_rows.n_multi = (int64_t)multi.size();
-                g->in_rows.n_hub = (int64_t)hub.size();
+                g->in_rows.n_long = (int64_t)longer.size();
                 if ((st = upload(&g->in_rows.tail, tail, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rows.seg, seg, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rows.multi, multi, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                if ((st = upload(&g->in_rows.hub, hub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = upload(&g->in_rows.longrows, longer, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
             }
         }
     } catch (const std::bad_alloc &) {
@@ -281,7 +280,7 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     free_shards(g);
     g->prof.release();
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
-                    g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.hub, g->fr_tail,
+                    g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,
                     g->fr_seg, g->d_ctr};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);

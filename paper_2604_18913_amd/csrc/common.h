@@ -74,8 +74,10 @@ struct RowClasses {             // device work lists over the object rows, split
     int32_t *tail = nullptr;    // rows with 1 .. kTailMaxDegree entries, descending degree
     RowSegment *seg = nullptr;  // segments of the longer rows, longest rows first
     int32_t *multi = nullptr;   // rows cut into more than one segment
-    int32_t *hub = nullptr;     // rows with >= hub_min entries, ascending row id
-    int64_t n_tail = 0, n_seg = 0, n_multi = 0, n_hub = 0, n_long = 0;  // n_long: rows behind seg
+    int32_t *longrows = nullptr;  // rows with more than kTailMaxDegree entries, descending degree
+                                  // (per streamed chunk when sharded); the first n_hub of them
+                                  // have >= hub_min entries
+    int64_t n_tail = 0, n_seg = 0, n_multi = 0, n_hub = 0, n_long = 0;
 };
 
 // ---------------------------------------------------------------- profiling
@@ -177,7 +179,6 @@ struct logoskg_result {
     long long *d_reached_off = nullptr;  // [64W+1]
     std::vector<int64_t> reached_off;  // host copy [Q+1]
     std::vector<logoskg_hop_stats> stats;
-    long long *hub_slot = nullptr;    // [n_in_hub][64W] scratch of the last fetch
 };
 
 namespace lkg {
@@ -224,6 +225,24 @@ __device__ __forceinline__ long long wave_sum(long long v) {
     return v;
 }
 
+// 64x64 bit-matrix transpose across a wavefront: on entry lane r holds row r
+// (bit c = M[r][c]); on return lane c holds column c (bit r = M[r][c]).  Six
+// butterfly steps; in step j the off-diagonal j x j blocks of every 2j x 2j block
+// change places.
+__device__ __forceinline__ unsigned long long transpose64(unsigned long long x) {
+    const unsigned long long lowmask[6] = {0x00000000FFFFFFFFull, 0x0000FFFF0000FFFFull, 0x00FF00FF00FF00FFull,
+                                           0x0F0F0F0F0F0F0F0Full, 0x3333333333333333ull, 0x5555555555555555ull};
+#pragma unroll
+    for (int s = 0; s < 6; ++s) {
+        const int j = 32 >> s;
+        const unsigned long long m = lowmask[s];
+        unsigned long long y = shfl_xor64(x, j);
+        if (lane() & j) x = ((y >> j) & m) | (x & ~m);
+        else x = (x & m) | ((y & m) << j);
+    }
+    return x;
+}
+
 // bits of word w (0..W-1) that belong to queries < Q
 __device__ __forceinline__ unsigned long long query_bits(int Q, int w) {
     int lo = w * 64;
@@ -240,7 +259,6 @@ struct FillArgs {
     int Q, k, q0, q1, hub_min;
     long long ntiles;
     long long tile_begin, tile_count;  // tiles this predecessor launch covers
-    long long hub_begin;               // first hub row of this predecessor launch
     long long plane;   // words per plane
     long long actw;    // uint32 words per active bitmap
     const unsigned long long *visited, *levels, *allow;
@@ -251,17 +269,16 @@ struct FillArgs {
     const uint32_t *in_off;
     const int32_t *in_sub, *in_eid;
     const uint16_t *in_rel;
-    const int32_t *hubs;
-    long long n_hubs;
+    const int32_t *rows;  // long object rows of this predecessor launch
     int32_t *entity;
     uint8_t *hop;
     int32_t *pred;
-    long long *hub_slot;
     unsigned long long *stats_pred, *stats_hub;  // rows / edges / lines counters or NULL
 };
 
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
-void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hubs_here, bool mask, hipStream_t st);
+void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
+                 hipStream_t st);
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,

@@ -654,7 +654,7 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
     void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_cnt, r->tile_base,
-                    r->super_base, r->mega_base, r->d_reached_off, r->hub_slot};
+                    r->super_base, r->mega_base, r->d_reached_off};
     for (void *p : ptrs) g->pool.release(p);
     delete r;
 }

@@ -63,12 +63,7 @@ __global__ void k_count(const unsigned long long *__restrict__ visited, long lon
         unsigned long long x = stage_word<W>(stage, visited + (size_t)tile * 64 * W, wave);
         tile_base[(size_t)tile * Qp + threadIdx.x] = (uint16_t)run;
         int mine = 0;
-        if (wave_any(x != 0)) {
-            for (int qq = 0; qq < 64; ++qq) {
-                unsigned long long m = __ballot((x >> qq) & 1ull);
-                if (lane() == qq) mine = __popcll(m);
-            }
-        }
+        if (wave_any(x != 0)) mine = __popcll(transpose64(x));  // lane qq: entities of the tile query qq reached
         run += mine;
     }
     super_sum[(size_t)st * Qp + threadIdx.x] = (uint32_t)run;
@@ -257,26 +252,34 @@ __device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillAr
     }
     unsigned long long cm = __ballot(cand);
     int gathered = 0;
-    while (cm) {
-        gathered += min(__popcll(cm), 64 / W);
-        int p = next_candidates<W>(cm);
-        int sc = __shfl(s, p < 0 ? 0 : p);
-        unsigned long long ln = 0;
-        if (p >= 0) {
-            ln = prev[(size_t)sc * W + lw];
-            if (MASK) ln &= a.allow[(size_t)a.in_rel[j0 + p] * W + lw];
+    while (cm) {  // two rounds of 64/W candidates each, both loads in flight before either is resolved
+        gathered += min(__popcll(cm), 2 * (64 / W));
+        int p0 = next_candidates<W>(cm);
+        int p1 = next_candidates<W>(cm);
+        int s0 = __shfl(s, p0 < 0 ? 0 : p0), s1 = __shfl(s, p1 < 0 ? 0 : p1);
+        unsigned long long l0 = 0, l1 = 0;
+        if (p0 >= 0) l0 = prev[(size_t)s0 * W + lw];
+        if (p1 >= 0) l1 = prev[(size_t)s1 * W + lw];
+        if (MASK) {
+            if (p0 >= 0) l0 &= a.allow[(size_t)a.in_rel[j0 + p0] * W + lw];
+            if (p1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + p1] * W + lw];
         }
-        unsigned long long hit = ln & rem & ~groups_before<W>(ln);
-        rem &= ~or_groups<W>(ln);
-        if (hit) emit(hit, a.in_eid[j0 + p]);
+        unsigned long long hit0 = l0 & rem & ~groups_before<W>(l0);
+        rem &= ~or_groups<W>(l0);
+        unsigned long long hit1 = l1 & rem & ~groups_before<W>(l1);
+        rem &= ~or_groups<W>(l1);
+        if (hit0) emit(hit0, a.in_eid[j0 + p0]);
+        if (hit1) emit(hit1, a.in_eid[j0 + p1]);
         if (!wave_any(rem != 0)) break;
     }
     return gathered;
 }
 
-// One block per tile of 64 entities.  Phase 1: per query, the mask of tile
-// entities it reached (for ranks) and the list position of the tile's run;
-// seeds get -1.  Phase 2: one wavefront per entity walks its object row.
+// One block per tile of 64 entities.  Phase 1: per query of the fetched range, the
+// mask of tile entities it reached (for ranks) and the list position of the
+// tile's run; seeds get -1.  Phase 2: every entity whose object row has at most
+// 32 entries is walked by one W-lane group, two candidate lines in flight.
+// Longer rows are left to k_pred_row.
 template <int W, bool MASK>
 __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     constexpr int Qp = 64 * W;
@@ -286,7 +289,7 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     const long long tile_rel = xcd_contiguous(blockIdx.x, gridDim.x);
     if (tile_rel >= a.tile_count) return;
     const long long tile = a.tile_begin + tile_rel;
-    const int t = threadIdx.x, wave = t >> 6, v = lane();
+    const int t = threadIdx.x, wave = t >> 6, v = lane(), lw = t & (W - 1);
     {
         int q = t;
         long long b = 0;
@@ -294,116 +297,165 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
             b = super_start(a, tile / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile * Qp + q];
         base[q] = b;
     }
-    unsigned long long visw = stage_word<W>(stage, a.visited + (size_t)tile * 64 * W, wave);
-    unsigned long long seedw = stage_word<W>(stage, a.levels + (size_t)tile * 64 * W, wave);
+    const unsigned long long range_w = range_bits(a.q0, a.q1, wave);
+    unsigned long long visw = stage_word<W>(stage, a.visited + (size_t)tile * 64 * W, wave) & range_w;
+    unsigned long long seedw = stage_word<W>(stage, a.levels + (size_t)tile * 64 * W, wave) & range_w;
     unsigned long long mine = 0;
-    unsigned long long todo = range_bits(a.q0, a.q1, wave);
-    if (!wave_any(visw != 0)) todo = 0;
-    for (int qq = 0; qq < 64; ++qq) {
-        if (!((todo >> qq) & 1ull)) continue;
-        bool bit = (visw >> qq) & 1ull;
-        unsigned long long m = __ballot(bit);
-        if (v == qq) mine = m;
-        if ((seedw >> qq) & 1ull) a.pred[base[wave * 64 + qq] + __popcll(m & ((1ull << v) - 1ull))] = -1;
-    }
+    if (wave_any(visw != 0)) mine = transpose64(visw);  // lane qq: mask of tile entities query qq reached
     mT[t] = mine;
     __syncthreads();
-
-    const int nwaves = blockDim.x >> 6, lw = v & (W - 1);
+    auto slot = [&](int q, unsigned long long below) -> long long {
+        return base[q] + __popcll(mT[q] & below);
+    };
+    {   // seeds have no predecessor
+        const unsigned long long below_v = (1ull << v) - 1ull;
+        for (unsigned long long m = seedw; m; m &= m - 1)
+            a.pred[slot(wave * 64 + (__ffsll((long long)m) - 1), below_v)] = -1;
+    }
+    const int vi = t / W, g0 = v & ~(W - 1);
+    const long long ev = tile * 64 + vi;
+    uint32_t lo = 0, hi = 0;
+    if (ev < a.E) {
+        lo = a.in_off[ev];
+        hi = a.in_off[ev + 1];
+    }
+    const bool longrow = hi - lo > (uint32_t)kTailMaxDegree;
+    const unsigned long long below = (1ull << vi) - 1ull;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
-    for (int vi = wave; vi < 64; vi += nwaves) {
-        int ev = (int)(tile * 64) + vi;
-        if (ev >= a.E) break;
-        uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
-        if (lo == hi) continue;
-        bool hubrow = (hi - lo) >= (uint32_t)a.hub_min;
-        long long hidx = 0;
-        if (hubrow) {  // position of ev in the ascending hub list
-            long long l = 0, r = a.n_hubs - 1;
-            while (l < r) {
-                long long mid = (l + r) >> 1;
-                if (a.hubs[mid] < ev) l = mid + 1; else r = mid;
-            }
-            hidx = l;
-        }
-        const unsigned long long below = (1ull << vi) - 1ull;
+    if (hi > lo && !longrow)
         for (int h = 1; h <= a.k; ++h) {
-            unsigned long long rem = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
-            if (!wave_any(rem != 0)) continue;
-            if (hubrow) {  // the block-per-row kernel resolves these; give it the slots
-                if (v < W)
-                    for (unsigned long long m = rem; m; m &= m - 1) {
-                        int q = v * 64 + (__ffsll((long long)m) - 1);
-                        long long pos = base[q] + __popcll(mT[q] & below);
-                        a.pred[pos] = INT_MAX;
-                        a.hub_slot[(size_t)hidx * Qp + q] = pos;
-                    }
-                continue;
-            }
+            unsigned long long rem =
+                a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
+            if (!group_any<W>(rem != 0)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
-            ++n_rows;
-            for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
-                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1) {
-                        int q = lw * 64 + (__ffsll((long long)m) - 1);
-                        a.pred[base[q] + __popcll(mT[q] & below)] = eid;
+            if (lw == 0) ++n_rows;
+            for (uint32_t j0 = lo; j0 < hi; j0 += W) {
+                uint32_t j = j0 + lw;
+                int s = 0;
+                bool cand = false;
+                if (j < hi) {
+                    s = a.in_sub[j];
+                    cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+                }
+                unsigned gm = 0;
+                if constexpr (W == 1) gm = cand ? 1u : 0u;
+                else gm = (unsigned)((__ballot(cand) >> g0) & ((1ull << W) - 1ull));
+                if (lw == 0) {
+                    n_edges += min((uint32_t)W, hi - j0);
+                    n_lines += __popc(gm);
+                }
+                while (gm) {  // two candidate lines in flight, resolved in edge order
+                    int c0 = __ffs((int)gm) - 1;
+                    gm &= gm - 1;
+                    int c1 = -1;
+                    if (gm) {
+                        c1 = __ffs((int)gm) - 1;
+                        gm &= gm - 1;
                     }
-                });
-                n_edges += min((uint32_t)64, hi - j0);
-                if (!wave_any(rem != 0)) break;
+                    int s0 = __shfl(s, g0 + c0), s1 = __shfl(s, g0 + (c1 < 0 ? c0 : c1));
+                    unsigned long long l0 = prev[(size_t)s0 * W + lw], l1 = 0;
+                    if (c1 >= 0) l1 = prev[(size_t)s1 * W + lw];
+                    if (MASK) {
+                        l0 &= a.allow[(size_t)a.in_rel[j0 + c0] * W + lw];
+                        if (c1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + c1] * W + lw];
+                    }
+                    unsigned long long hit0 = l0 & rem, hit1 = l1 & rem & ~l0;
+                    rem &= ~(l0 | l1);
+                    if (hit0) {
+                        int eid = a.in_eid[j0 + c0];
+                        for (unsigned long long m = hit0; m; m &= m - 1)
+                            a.pred[slot(lw * 64 + (__ffsll((long long)m) - 1), below)] = eid;
+                    }
+                    if (hit1) {
+                        int eid = a.in_eid[j0 + c1];
+                        for (unsigned long long m = hit1; m; m &= m - 1)
+                            a.pred[slot(lw * 64 + (__ffsll((long long)m) - 1), below)] = eid;
+                    }
+                    if (!group_any<W>(rem != 0)) break;
+                }
+                if (!group_any<W>(rem != 0)) break;
             }
         }
-    }
-    if (a.stats_pred && v == 0) {
-        if (n_rows) atomicAdd(&a.stats_pred[0], (unsigned long long)n_rows);
-        if (n_edges) atomicAdd(&a.stats_pred[1], (unsigned long long)n_edges);
-        if (n_lines) atomicAdd(&a.stats_pred[2], (unsigned long long)n_lines);
+    if (a.stats_pred) {
+        n_rows = wave_sum(n_rows);
+        n_edges = wave_sum(n_edges);
+        n_lines = wave_sum(n_lines);
+        if (v == 0) {
+            if (n_rows) atomicAdd(&a.stats_pred[0], (unsigned long long)n_rows);
+            if (n_edges) atomicAdd(&a.stats_pred[1], (unsigned long long)n_edges);
+            if (n_lines) atomicAdd(&a.stats_pred[2], (unsigned long long)n_lines);
+        }
     }
 }
 
-// Hub object rows: one block per row.  The row is walked in steps of
-// (waves x 64) edges; inside a step the waves work on disjoint edge ranges in
-// parallel and merge with atomicMin, between steps the resolved bits are
-// removed, so later steps never override earlier (smaller) edge ids.
+// Object rows of more than 32 entries: one block per row (4 waves; 16 for hub
+// rows).  Phase 1 rebuilds the list positions of the row's entity (ranks inside
+// its tile).  Phase 2 walks the row in steps of (waves x 64) entries: inside a
+// step the waves take disjoint 64-entry chunks and keep, per query, the smallest
+// edge id any of them found (LDS atomicMin); after the step the resolved queries
+// are removed from the shared mask, so a later step (larger edge ids) never
+// touches them.  Each predecessor is then written once.
 template <int W, bool MASK>
-__global__ void __launch_bounds__(1024) k_pred_hub(FillArgs a) {
+__global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
     constexpr int Qp = 64 * W;
-    __shared__ unsigned long long srem[16];
-    const long long hidx = a.hub_begin + blockIdx.x;
-    const int ev = a.hubs[hidx];
-    const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, lw = lane() & (W - 1);
+    __shared__ long long slot[Qp];
+    __shared__ int smin[Qp];
+    __shared__ unsigned long long srem[16], slevel[16];
+    const int ev = a.rows[first_row + blockIdx.x];
+    const long long tile = ev >> 6;
+    const int vi = ev & 63;
+    const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, v = lane(), lw = v & (W - 1);
+    const unsigned long long below = (1ull << vi) - 1ull;
+    for (int w = wave; w < W; w += nw) {  // lane v = entity v of the tile, one word at a time
+        unsigned long long x = a.visited[((size_t)tile * 64 + v) * W + w] & range_bits(a.q0, a.q1, w);
+        int rank = 0;
+        if (shfl64(x, vi) != 0ull)  // only queries that reached this entity matter
+            rank = __popcll(transpose64(x) & below);
+        int q = w * 64 + v;
+        long long b = 0;
+        if (q >= a.q0 && q < a.q1)
+            b = super_start(a, tile / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile * Qp + q] + rank;
+        slot[q] = b;
+    }
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int h = 1; h <= a.k; ++h) {
         __syncthreads();
-        if (t < 16)
-            srem[t] = t < W ? a.levels[(size_t)h * a.plane + (size_t)ev * W + t] & range_bits(a.q0, a.q1, t) : 0ull;
+        if (t < 16) {
+            unsigned long long x =
+                t < W ? a.levels[(size_t)h * a.plane + (size_t)ev * W + t] & range_bits(a.q0, a.q1, t) : 0ull;
+            srem[t] = x;
+            slevel[t] = x;
+        }
+        for (int q = t; q < Qp; q += blockDim.x) smin[q] = INT_MAX;
         __syncthreads();
+        if (!wave_any(slevel[lw] != 0)) continue;  // block-uniform
         const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
         const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+        if (wave == 0) ++n_rows;
         for (uint32_t s0 = lo; s0 < hi; s0 += 64u * nw) {
             unsigned long long rem = srem[lw];
             if (!wave_any(rem != 0)) break;  // same decision in every wave
-            if (s0 == lo && wave == 0) ++n_rows;
             const unsigned long long before = rem;
             uint32_t j0 = s0 + 64u * wave;
             if (j0 < hi) {
                 n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1) {
-                        int q = lw * 64 + (__ffsll((long long)m) - 1);
-                        atomicMin(&a.pred[a.hub_slot[(size_t)hidx * Qp + q]], eid);
-                    }
+                    for (unsigned long long m = hit; m; m &= m - 1)
+                        atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
                 });
                 n_edges += min((uint32_t)64, hi - j0);
             }
             unsigned long long resolved = before & ~rem;
             __syncthreads();
-            if (lane() < W && resolved) atomicAnd(&srem[lane()], ~resolved);
+            if (v < W && resolved) atomicAnd(&srem[v], ~resolved);
             __syncthreads();
         }
+        __syncthreads();
+        for (int q = t; q < Qp; q += blockDim.x)
+            if ((slevel[q >> 6] >> (q & 63)) & 1ull) a.pred[slot[q]] = smin[q];
     }
-    if (a.stats_hub && lane() == 0) {
+    if (a.stats_hub && v == 0) {
         if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
         if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
         if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
@@ -486,20 +538,27 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
     else k_lists<W, 8><<<grid, block, 0, st>>>(a);
 }
 
-// predecessor kernels over the tiles [a.tile_begin, +a.tile_count) and `n_hubs_here` hub rows
-// starting at a.hub_begin
+// predecessor kernels over the tiles [a.tile_begin, +a.tile_count) and the long rows a.rows[0 ..
+// n_hub_rows + n_other_rows): the hub rows first (16 waves per row), then the others (4 waves)
 template <int W>
-static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hubs_here, bool mask, hipStream_t st) {
+static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
+                          bool mask, hipStream_t st) {
+    if (n_hub_rows + n_other_rows > 0) {
+        ProfScope ps(prof, KK_PRED_HUB, st);
+        if (n_hub_rows > 0) {
+            if (mask) k_pred_row<W, true><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
+            else k_pred_row<W, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
+        }
+        if (n_other_rows > 0) {
+            if (mask) k_pred_row<W, true><<<dim3((unsigned)n_other_rows), dim3(256), 0, st>>>(a, n_hub_rows);
+            else k_pred_row<W, false><<<dim3((unsigned)n_other_rows), dim3(256), 0, st>>>(a, n_hub_rows);
+        }
+    }
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st);
         dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
         if (mask) k_pred<W, true><<<grid, block, 0, st>>>(a);
         else k_pred<W, false><<<grid, block, 0, st>>>(a);
-    }
-    if (n_hubs_here > 0) {
-        ProfScope ps(prof, KK_PRED_HUB, st);
-        if (mask) k_pred_hub<W, true><<<dim3((unsigned)n_hubs_here), dim3(1024), 0, st>>>(a);
-        else k_pred_hub<W, false><<<dim3((unsigned)n_hubs_here), dim3(1024), 0, st>>>(a);
     }
 }
 
@@ -511,11 +570,12 @@ void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st) {
     }
 }
 
-void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hubs_here, bool mask, hipStream_t st) {
+void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
+                 hipStream_t st) {
     switch (W) {
-        case 1: launch_pred_w<1>(prof, a, n_hubs_here, mask, st); break;
-        case 4: launch_pred_w<4>(prof, a, n_hubs_here, mask, st); break;
-        default: launch_pred_w<16>(prof, a, n_hubs_here, mask, st); break;
+        case 1: launch_pred_w<1>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
+        case 4: launch_pred_w<4>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
+        default: launch_pred_w<16>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
     }
 }
 
@@ -545,20 +605,18 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
-    const int W = r->W, Qp = 64 * W;
-    if (pred && g->in_rows.n_hub > 0 && !r->hub_slot)
-        LKG_TRY(g->pool.alloc((void **)&r->hub_slot, (size_t)g->in_rows.n_hub * Qp * 8));
+    const int W = r->W;
     FillArgs a;
     a.E = g->E; a.Q = r->Q; a.k = r->k; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
     a.ntiles = r->Epad / kTileEntities;
-    a.tile_begin = 0; a.tile_count = a.ntiles; a.hub_begin = 0;
+    a.tile_begin = 0; a.tile_count = a.ntiles;
     a.plane = r->Epad * W; a.actw = r->Epad / 32;
     a.visited = r->visited; a.levels = r->levels; a.allow = r->allow;
     a.act = r->act; a.tile_base = r->tile_base; a.super_base = r->super_base; a.mega_base = r->mega_base;
     a.reached_off = r->d_reached_off;
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
-    a.hubs = g->in_rows.hub; a.n_hubs = g->in_rows.n_hub;
-    a.entity = entity; a.hop = hop; a.pred = pred; a.hub_slot = r->hub_slot;
+    a.rows = g->in_rows.longrows;
+    a.entity = entity; a.hop = hop; a.pred = pred;
     const bool counting = g->prof.counters;
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
@@ -566,7 +624,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     launch_lists(g->prof, a, W, st);
     if (pred) {
         if (g->num_shards > 1) LKG_TRY(sharded_pred(g, &a, W, r->has_mask, st));
-        else launch_pred(g->prof, a, W, a.n_hubs, r->has_mask, st);
+        else launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, st);
     }
     LKG_HIP(hipGetLastError());
     if (g->prof.on) {

@@ -39,7 +39,7 @@ struct ShardSet {
     // staging buffers in chunks of whole 64-entity tiles
     int32_t *h_in_sub = nullptr, *h_in_eid = nullptr;
     uint16_t *h_in_rel = nullptr;
-    struct Chunk { long long tile_begin, tile_count; int64_t edge_begin, edge_count; long long hub_begin, hub_count; };
+    struct Chunk { long long tile_begin, tile_count; int64_t edge_begin, edge_count; long long row_begin, hub_count, row_count; };
     std::vector<Chunk> chunks;
     size_t stage_edges = 0;
     int32_t *stage_sub[2] = {nullptr, nullptr}, *stage_eid[2] = {nullptr, nullptr};
@@ -116,11 +116,8 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
     const int64_t T = g->T;
     std::vector<uint32_t> ioff((size_t)E + 1, 0);
     for (int64_t t = 0; t < T; ++t) ioff[(size_t)obj[t] + 1]++;
-    std::vector<int32_t> hubs;
-    for (int32_t e = 0; e < E; ++e) {
-        if (ioff[(size_t)e + 1] >= (uint32_t)g->hub_min) hubs.push_back(e);
-        ioff[(size_t)e + 1] += ioff[e];
-    }
+    for (int32_t e = 0; e < E; ++e) ioff[(size_t)e + 1] += ioff[e];
+    std::vector<int32_t> longrows;  // rows of more than kTailMaxDegree entries, chunk by chunk
     size_t n4 = std::max<int64_t>(T, 1) * sizeof(int32_t), n2 = std::max<int64_t>(T, 1) * sizeof(uint16_t);
     if (hipHostMalloc((void **)&ss->h_in_sub, n4, hipHostMallocDefault) != hipSuccess ||
         hipHostMalloc((void **)&ss->h_in_eid, n4, hipHostMallocDefault) != hipSuccess ||
@@ -142,14 +139,9 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
     LKG_HIP(hipMalloc((void **)&g->in_off, ((size_t)E + 1) * sizeof(uint32_t)));
     LKG_HIP(hipMemcpy(g->in_off, ioff.data(), ((size_t)E + 1) * sizeof(uint32_t), hipMemcpyHostToDevice));
     g->static_bytes += ((size_t)E + 1) * sizeof(uint32_t);
-    g->in_rows.n_hub = (int64_t)hubs.size();
-    LKG_HIP(hipMalloc((void **)&g->in_rows.hub, std::max<size_t>(hubs.size(), 1) * sizeof(int32_t)));
-    if (!hubs.empty())
-        LKG_HIP(hipMemcpy(g->in_rows.hub, hubs.data(), hubs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     // chunks of whole tiles
     const long long ntiles = g->Epad / kTileEntities;
     const int64_t target = std::max<int64_t>(1, (T + g->num_shards - 1) / g->num_shards);
-    size_t hub_pos = 0;
     long long t0 = 0;
     while (t0 < ntiles) {
         long long t1 = t0;
@@ -162,13 +154,27 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
         }
         ShardSet::Chunk c;
         c.tile_begin = t0; c.tile_count = t1 - t0; c.edge_begin = e_begin; c.edge_count = e_end - e_begin;
-        c.hub_begin = (long long)hub_pos;
-        while (hub_pos < hubs.size() && hubs[hub_pos] < t1 * 64) ++hub_pos;
-        c.hub_count = (long long)hub_pos - c.hub_begin;
+        c.row_begin = (long long)longrows.size();
+        c.hub_count = 0;
+        for (long long e = t0 * 64; e < std::min<long long>(t1 * 64, E); ++e) {
+            uint32_t d = ioff[(size_t)e + 1] - ioff[(size_t)e];
+            if (d > (uint32_t)kTailMaxDegree) longrows.push_back((int32_t)e);
+            if (d >= (uint32_t)g->hub_min) c.hub_count++;
+        }
+        std::stable_sort(longrows.begin() + c.row_begin, longrows.end(), [&](int32_t x, int32_t y) {
+            return ioff[(size_t)x + 1] - ioff[x] > ioff[(size_t)y + 1] - ioff[y];
+        });
+        c.row_count = (long long)longrows.size() - c.row_begin;
+        g->in_rows.n_hub += c.hub_count;
         ss->chunks.push_back(c);
         ss->stage_edges = std::max(ss->stage_edges, (size_t)c.edge_count);
         t0 = t1;
     }
+    g->in_rows.n_long = (int64_t)longrows.size();
+    LKG_HIP(hipMalloc((void **)&g->in_rows.longrows, std::max<size_t>(longrows.size(), 1) * sizeof(int32_t)));
+    if (!longrows.empty())
+        LKG_HIP(hipMemcpy(g->in_rows.longrows, longrows.data(), longrows.size() * sizeof(int32_t),
+                          hipMemcpyHostToDevice));
     ss->stage_edges = std::max<size_t>(ss->stage_edges, 1);
     for (int i = 0; i < 2; ++i) {
         LKG_HIP(hipMalloc((void **)&ss->stage_sub[i], ss->stage_edges * sizeof(int32_t)));
@@ -217,8 +223,8 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
         x.in_rel = ss->stage_rel[b] - c.edge_begin;
         x.tile_begin = c.tile_begin;
         x.tile_count = c.tile_count;
-        x.hub_begin = c.hub_begin;
-        launch_pred(g->prof, x, W, c.hub_count, mask, st);
+        x.rows = g->in_rows.longrows + c.row_begin;
+        launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->stage_idle[b], st));
     }
