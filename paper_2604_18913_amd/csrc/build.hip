@@ -270,6 +270,17 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         set_error("hipHostMalloc failed");
         return fail(LOGOSKG_ENOMEM);
     }
+    for (int i = 0; i < 2; ++i) {
+        if (hipStreamCreateWithFlags(&g->side[i], hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&g->ev_join[i], hipEventDisableTiming) != hipSuccess) {
+            set_error("could not create side streams");
+            return fail(LOGOSKG_EDEVICE);
+        }
+    }
+    if (hipEventCreateWithFlags(&g->ev_fork, hipEventDisableTiming) != hipSuccess) {
+        set_error("could not create events");
+        return fail(LOGOSKG_EDEVICE);
+    }
     *out = g;
     return LOGOSKG_OK;
 }
@@ -279,6 +290,11 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     (void)hipSetDevice(g->device);
     free_shards(g);
     g->prof.release();
+    for (int i = 0; i < 2; ++i) {
+        if (g->side[i]) { (void)hipStreamSynchronize(g->side[i]); (void)hipStreamDestroy(g->side[i]); }
+        if (g->ev_join[i]) (void)hipEventDestroy(g->ev_join[i]);
+    }
+    if (g->ev_fork) (void)hipEventDestroy(g->ev_fork);
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
                     g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,
                     g->fr_seg, g->d_ctr};

@@ -153,6 +153,10 @@ struct logoskg_graph {
     std::vector<int64_t> shard_triples;
     void *shards = nullptr;  // lkg::ShardSet* when num_shards > 1
 
+    // side streams (default priority) so that the independent result kernels of a fetch overlap
+    hipStream_t side[2] = {nullptr, nullptr};
+    hipEvent_t ev_fork = nullptr, ev_join[2] = {nullptr, nullptr};
+
     lkg::DevPool pool;
     lkg::Profiler prof;
     size_t static_bytes = 0;
@@ -219,6 +223,18 @@ __device__ __forceinline__ unsigned long long shfl_up64(unsigned long long v, in
     return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
 }
 
+// exclusive prefix sum over the lanes of a wavefront; `total` receives the sum
+__device__ __forceinline__ int wave_excl_scan(int v, int &total) {
+    int x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d);
+        if (lane() >= d) x += y;
+    }
+    total = __shfl(x, 63);
+    return x - v;
+}
+
 __device__ __forceinline__ long long wave_sum(long long v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += (long long)shfl_xor64((unsigned long long)v, m);
@@ -278,7 +294,7 @@ struct FillArgs {
 
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
-                 hipStream_t st);
+                 hipStream_t st_tiles, hipStream_t st_rows);
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,

@@ -65,17 +65,6 @@ __global__ void k_allow(int Q, int R, int W, int rel_words, const unsigned long 
 }
 
 // ---------------------------------------------------------------- frontier census
-__device__ __forceinline__ int wave_excl_scan(int v, int &total) {
-    int x = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        int y = __shfl_up(x, d);
-        if (lane() >= d) x += y;
-    }
-    total = __shfl(x, 63);
-    return x - v;
-}
-
 // Turns the active bitmap of a level into the work lists of a push hop (short
 // subject rows; segments of the longer ones) and the counters the host needs
 // to pick the direction.

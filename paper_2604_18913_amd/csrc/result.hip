@@ -20,6 +20,7 @@
 //           unresolved queries, so every (query, entity) pair is written once.
 #include <algorithm>
 #include <climits>
+#include <cstdlib>
 
 #include "common.h"
 
@@ -542,7 +543,7 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
 // n_hub_rows + n_other_rows): the hub rows first (16 waves per row), then the others (4 waves)
 template <int W>
 static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
-                          bool mask, hipStream_t st) {
+                          bool mask, hipStream_t st_tiles, hipStream_t st) {
     if (n_hub_rows + n_other_rows > 0) {
         ProfScope ps(prof, KK_PRED_HUB, st);
         if (n_hub_rows > 0) {
@@ -555,10 +556,10 @@ static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_row
         }
     }
     if (a.tile_count > 0) {
-        ProfScope ps(prof, KK_PRED, st);
+        ProfScope ps(prof, KK_PRED, st_tiles);
         dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
-        if (mask) k_pred<W, true><<<grid, block, 0, st>>>(a);
-        else k_pred<W, false><<<grid, block, 0, st>>>(a);
+        if (mask) k_pred<W, true><<<grid, block, 0, st_tiles>>>(a);
+        else k_pred<W, false><<<grid, block, 0, st_tiles>>>(a);
     }
 }
 
@@ -570,12 +571,14 @@ void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st) {
     }
 }
 
+// The tile kernel and the row kernels write disjoint list entries, so they may run on
+// different streams.
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
-                 hipStream_t st) {
+                 hipStream_t st_tiles, hipStream_t st_rows) {
     switch (W) {
-        case 1: launch_pred_w<1>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
-        case 4: launch_pred_w<4>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
-        default: launch_pred_w<16>(prof, a, n_hub_rows, n_other_rows, mask, st); break;
+        case 1: launch_pred_w<1>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
+        case 4: launch_pred_w<4>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
+        default: launch_pred_w<16>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
     }
 }
 
@@ -621,10 +624,25 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
     if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
-    launch_lists(g->prof, a, W, st);
-    if (pred) {
-        if (g->num_shards > 1) LKG_TRY(sharded_pred(g, &a, W, r->has_mask, st));
-        else launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, st);
+    // lists, the per-tile predecessor kernel and the per-row predecessor kernels are independent:
+    // on a resident graph they run on three streams and join on the caller's
+    static const bool serial = getenv("LOGOSKG_SERIAL_FETCH") != nullptr;
+    if (pred && g->num_shards <= 1 && !serial) {
+        LKG_HIP(hipEventRecord(g->ev_fork, st));
+        for (int i = 0; i < 2; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
+        launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, g->side[0],
+                    g->side[1]);
+        launch_lists(g->prof, a, W, st);
+        for (int i = 0; i < 2; ++i) {
+            LKG_HIP(hipEventRecord(g->ev_join[i], g->side[i]));
+            LKG_HIP(hipStreamWaitEvent(st, g->ev_join[i], 0));
+        }
+    } else {
+        launch_lists(g->prof, a, W, st);
+        if (pred) {
+            if (g->num_shards > 1) LKG_TRY(sharded_pred(g, &a, W, r->has_mask, st));
+            else launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, st, st);
+        }
     }
     LKG_HIP(hipGetLastError());
     if (g->prof.on) {

@@ -224,7 +224,7 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
         x.tile_begin = c.tile_begin;
         x.tile_count = c.tile_count;
         x.rows = g->in_rows.longrows + c.row_begin;
-        launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st);
+        launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st, st);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->stage_idle[b], st));
     }
