@@ -60,7 +60,8 @@ constexpr int kTailMaxDegree = 32;      // rows up to this degree: one W-lane gr
 constexpr int kPullSegment = 1024;      // longer object rows are cut into segments of this many
                                         // entries, one wavefront each
 constexpr int kPushSegment = 256;       // same for the subject rows of a push frontier
-constexpr int kDefaultHubMin = 4096;    // object rows from this degree: block-per-row predecessor kernel
+constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
+                                        // (shorter long rows: one wavefront per row)
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
 constexpr int kSuperTiles = 16;         // tiles per super tile (1024 entities)
 constexpr int kMegaSupers = 64;         // super tiles per mega tile (65536 entities)

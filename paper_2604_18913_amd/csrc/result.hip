@@ -239,18 +239,10 @@ __device__ __forceinline__ int next_candidates(unsigned long long &rest) {
 // sequential walk in ascending edge id.  emit(hit, eid) runs on lanes whose word
 // has newly resolved bits; returns the number of lines gathered.
 template <int W, bool MASK, typename Emit>
-__device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
-                                          const uint32_t *__restrict__ act_prev,
-                                          const unsigned long long *__restrict__ prev,
-                                          unsigned long long &rem, Emit emit) {
+__device__ __forceinline__ int pred_resolve(uint32_t j0, int s, bool cand, const FillArgs &a,
+                                            const unsigned long long *__restrict__ prev,
+                                            unsigned long long &rem, Emit emit) {
     const int lw = lane() & (W - 1);
-    uint32_t j = j0 + lane();
-    int s = 0;
-    bool cand = false;
-    if (j < hi) {
-        s = a.in_sub[j];
-        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
-    }
     unsigned long long cm = __ballot(cand);
     int gathered = 0;
     while (cm) {  // two rounds of 64/W candidates each, both loads in flight before either is resolved
@@ -274,6 +266,80 @@ __device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillAr
         if (!wave_any(rem != 0)) break;
     }
     return gathered;
+}
+
+template <int W, bool MASK, typename Emit>
+__device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
+                                          const uint32_t *__restrict__ act_prev,
+                                          const unsigned long long *__restrict__ prev,
+                                          unsigned long long &rem, Emit emit) {
+    uint32_t j = j0 + lane();
+    int s = 0;
+    bool cand = false;
+    if (j < hi) {
+        s = a.in_sub[j];
+        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+    }
+    return pred_resolve<W, MASK>(j0, s, cand, a, prev, rem, emit);
+}
+
+// List positions of entity `ev` for every query: slot[q] = start of the tile's run in query q's
+// list + rank of the entity inside the tile.  Called by a whole wavefront for the words
+// w = w_first, w_first + w_step, ..
+template <int W>
+__device__ __forceinline__ void row_slots(const FillArgs &a, int ev, int w_first, int w_step, long long *slot) {
+    constexpr int Qp = 64 * W;
+    const long long tile = ev >> 6;
+    const int vi = ev & 63, v = lane();
+    const unsigned long long below = (1ull << vi) - 1ull;
+    for (int w = w_first; w < W; w += w_step) {  // lane v = entity v of the tile
+        unsigned long long x = a.visited[((size_t)tile * 64 + v) * W + w] & range_bits(a.q0, a.q1, w);
+        int rank = 0;
+        if (shfl64(x, vi) != 0ull)  // only queries that reached this entity matter
+            rank = __popcll(transpose64(x) & below);
+        int q = w * 64 + v;
+        long long b = 0;
+        if (q >= a.q0 && q < a.q1)
+            b = super_start(a, tile / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile * Qp + q] + rank;
+        slot[q] = b;
+    }
+}
+
+// Object rows of 33 .. hub_min-1 entries: one wavefront per row, four rows per block.  A single
+// wavefront walks the row in order, so every predecessor is final when it is found.
+template <int W, bool MASK>
+__global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_row, long long n_rows_total) {
+    constexpr int Qp = 64 * W;
+    __shared__ long long slots[4][Qp];
+    const int wave = threadIdx.x >> 6, v = lane(), lw = v & (W - 1);
+    const long long idx = (long long)blockIdx.x * 4 + wave;
+    long long n_rows = 0, n_edges = 0, n_lines = 0;
+    if (idx < n_rows_total) {  // wave-uniform
+        const int ev = a.rows[first_row + idx];
+        long long *slot = slots[wave];
+        row_slots<W>(a, ev, 0, 1, slot);
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
+        for (int h = 1; h <= a.k; ++h) {
+            unsigned long long rem = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
+            if (!wave_any(rem != 0)) continue;
+            const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
+            const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+            ++n_rows;
+            for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
+                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
+                    for (unsigned long long m = hit; m; m &= m - 1) a.pred[slot[lw * 64 + (__ffsll((long long)m) - 1)]] = eid;
+                });
+                n_edges += min((uint32_t)64, hi - j0);
+                if (!wave_any(rem != 0)) break;
+            }
+        }
+    }
+    if (a.stats_hub && v == 0) {
+        if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
+        if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
+        if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
+    }
 }
 
 // One block per tile of 64 entities.  Phase 1: per query of the fetched range, the
@@ -400,25 +466,13 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
 template <int W, bool MASK>
 __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
     constexpr int Qp = 64 * W;
+    constexpr int C = 4;  // 64-entry chunks per wavefront and step, loaded together
     __shared__ long long slot[Qp];
     __shared__ int smin[Qp];
     __shared__ unsigned long long srem[16], slevel[16];
     const int ev = a.rows[first_row + blockIdx.x];
-    const long long tile = ev >> 6;
-    const int vi = ev & 63;
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, v = lane(), lw = v & (W - 1);
-    const unsigned long long below = (1ull << vi) - 1ull;
-    for (int w = wave; w < W; w += nw) {  // lane v = entity v of the tile, one word at a time
-        unsigned long long x = a.visited[((size_t)tile * 64 + v) * W + w] & range_bits(a.q0, a.q1, w);
-        int rank = 0;
-        if (shfl64(x, vi) != 0ull)  // only queries that reached this entity matter
-            rank = __popcll(transpose64(x) & below);
-        int q = w * 64 + v;
-        long long b = 0;
-        if (q >= a.q0 && q < a.q1)
-            b = super_start(a, tile / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile * Qp + q] + rank;
-        slot[q] = b;
-    }
+    row_slots<W>(a, ev, wave, nw, slot);
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int h = 1; h <= a.k; ++h) {
@@ -435,17 +489,33 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
         const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
         if (wave == 0) ++n_rows;
-        for (uint32_t s0 = lo; s0 < hi; s0 += 64u * nw) {
+        for (uint32_t s0 = lo; s0 < hi; s0 += 64u * C * nw) {
             unsigned long long rem = srem[lw];
             if (!wave_any(rem != 0)) break;  // same decision in every wave
             const unsigned long long before = rem;
-            uint32_t j0 = s0 + 64u * wave;
-            if (j0 < hi) {
-                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1)
-                        atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
-                });
-                n_edges += min((uint32_t)64, hi - j0);
+            const uint32_t w0 = s0 + 64u * C * wave;
+            int sj[C];
+            bool cj[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c) {  // all loads of the step first
+                uint32_t j = w0 + 64u * c + v;
+                sj[c] = 0;
+                cj[c] = false;
+                if (j < hi) {
+                    sj[c] = a.in_sub[j];
+                    cj[c] = (act_prev[sj[c] >> 5] >> (sj[c] & 31)) & 1u;
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                uint32_t j0 = w0 + 64u * c;
+                if (j0 < hi && wave_any(rem != 0)) {
+                    n_lines += pred_resolve<W, MASK>(j0, sj[c], cj[c], a, prev, rem, [&](unsigned long long hit, int eid) {
+                        for (unsigned long long m = hit; m; m &= m - 1)
+                            atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
+                    });
+                    n_edges += min((uint32_t)64, hi - j0);
+                }
             }
             unsigned long long resolved = before & ~rem;
             __syncthreads();
@@ -551,8 +621,9 @@ static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_row
             else k_pred_row<W, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
         }
         if (n_other_rows > 0) {
-            if (mask) k_pred_row<W, true><<<dim3((unsigned)n_other_rows), dim3(256), 0, st>>>(a, n_hub_rows);
-            else k_pred_row<W, false><<<dim3((unsigned)n_other_rows), dim3(256), 0, st>>>(a, n_hub_rows);
+            dim3 grid((unsigned)((n_other_rows + 3) / 4));
+            if (mask) k_pred_wave<W, true><<<grid, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+            else k_pred_wave<W, false><<<grid, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
         }
     }
     if (a.tile_count > 0) {
