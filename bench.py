@@ -35,6 +35,10 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
         # offsets (the visited write-back is not counted); per edge: subject id (+ relation);
         # per DISTINCT frontier line gathered: one line (caches are assumed to absorb repeats)
         return rows * (2 * line + 8) + edges * e_bytes + items * line
+    if kernel.startswith("push_"):
+        return 0.0  # frontier of hop 1 only: a few hundred KB, not priced
+    if kernel == "frontier_census":
+        return n * plane_bytes / (64.0 * W)  # the 1-bit-per-entity active bitmap
     if kernel == "lists":
         # visited + levels 1..k streamed once; 4 B entity + 1 B hop written per list entry
         return n * (k + 1) * plane_bytes + items * 5
@@ -58,6 +62,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=32)
+    ap.add_argument("--serial-fetch", action="store_true",
+                    help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch a plain 1 GiB device copy and a 1 GiB fill, so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
@@ -113,6 +119,17 @@ def main():
         r.fetch(out=(ent, hop, pred))
         return r
 
+    def run_steps(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step().close()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    if args.serial_fetch:
+        os.environ["LOGOSKG_SERIAL_FETCH"] = "1"
+
     # work units of every kernel (counting mode; not timed)
     g.profile_enable(2)
     r = step()
@@ -123,26 +140,21 @@ def main():
     r.close()
     g.profile_enable(0)
 
-    for _ in range(args.warmup):
-        step().close()
-    torch.cuda.synchronize()
+    run_steps(args.warmup)
+    # timed region: the default path (list / predecessor kernels of a fetch overlap on side
+    # streams), every launch bracketed by HIP events on its own stream
     g.profile_enable(1)
     g.profile_read()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step().close()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt = run_steps(args.steps)
+    prof_overlapped = g.profile_read()
+    # the same steps with the kernels of a fetch issued back to back, so that each event pair
+    # times one kernel alone: these durations feed the roofline figures
+    os.environ["LOGOSKG_SERIAL_FETCH"] = "1"
+    dt_serial = run_steps(args.steps)
     prof = g.profile_read()
     g.profile_enable(0)
-
-    # un-instrumented timing of the same loop (no events at all)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step().close()
-    torch.cuda.synchronize()
-    dt_plain = time.perf_counter() - t0
+    if not args.serial_fetch:
+        os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
 
     ms_per_step = dt / args.steps * 1e3
     qps = Q / (dt / args.steps)
@@ -154,18 +166,28 @@ def main():
         per_step = {x: u.get(x, 0) for x in ("rows", "edges", "lines", "items")}
         kernels[name] = dict(launches_per_step=p["launches"] / args.steps,
                              ms_per_step=p["total_ms"] / args.steps,
-                             avg_ms=p["total_ms"] / p["launches"], **per_step)
-    expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items()
-                       if n.startswith(("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")))
+                             avg_ms=p["total_ms"] / p["launches"],
+                             ms_per_step_overlapped=prof_overlapped.get(name, {}).get("total_ms", 0.0) / args.steps,
+                             **per_step)
+    expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")
+    expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith(expansion_names))
+    plane_bytes = float(res_epad * W * 8)
+    expansion_bytes = sum(algorithmic_bytes(n, v, W, k, False, plane_bytes) for n, v in kernels.items()
+                          if n.startswith(expansion_names))
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
-    plane_bytes = float(res_epad * W * 8)
     alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
+    traffic = None
+    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_traffic.json")
+    if os.path.exists(tfile) and args.scale == 1.0:
+        tj = json.load(open(tfile))
+        traffic = tj.get("kernels", {}).get(dom, {}).get("hbm_bytes_per_launch")
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
-                    algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4))
-    # the same figure for every expansion kernel of the 3-hop batched expansion
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
+                    algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4),
+                    measured="HIP events around every launch, fetch kernels serialized")
+    # the same figure for every kernel that has a byte model
     exp = {}
     for n, v in kernels.items():
         b = algorithmic_bytes(n, v, W, k, False, plane_bytes)
@@ -188,9 +210,12 @@ def main():
         "gteps_logical": round(logical_edges / (dt / args.steps) / 1e9, 2),
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
         "logical_edges_per_step": logical_edges, "physical_edges_per_step": physical_edges,
-        "expansion_ms_per_step": round(expansion_ms, 4),
-        "expansion_queries_per_s": round(Q / (expansion_ms * 1e-3), 1) if expansion_ms > 0 else None,
-        "ms_per_step_without_events": round(dt_plain / args.steps * 1e3, 4),
+        "ms_per_step_serialized": round(dt_serial / args.steps * 1e3, 4),
+        "expansion": {"ms_per_step": round(expansion_ms, 4),
+                      "queries_per_s": round(Q / (expansion_ms * 1e-3), 1) if expansion_ms > 0 else None,
+                      "algorithmic_GBps": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
+                      "hbm_frac": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if expansion_ms else None,
+                      "gteps_logical": round(logical_edges / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None},
         "roofline": roofline,
         "kernels": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for n, v in kernels.items()},

@@ -697,7 +697,8 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
     // lists, the per-tile predecessor kernel and the per-row predecessor kernels are independent:
     // on a resident graph they run on three streams and join on the caller's
-    static const bool serial = getenv("LOGOSKG_SERIAL_FETCH") != nullptr;
+    const char *serial_env = getenv("LOGOSKG_SERIAL_FETCH");  // measurement aid: one kernel at a time
+    const bool serial = serial_env && serial_env[0] == '1';
     if (pred && g->num_shards <= 1 && !serial) {
         LKG_HIP(hipEventRecord(g->ev_fork, st));
         for (int i = 0; i < 2; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
