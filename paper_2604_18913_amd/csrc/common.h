@@ -64,6 +64,8 @@ constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-p
                                         // (shorter long rows: one wavefront per row)
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
 constexpr int kSuperTiles = 16;         // tiles per super tile (1024 entities)
+constexpr int kPredTiles = 4;           // tiles per block of the 16-word predecessor kernel
+constexpr int kPredGroup = 4;           // lanes (= words) per entity in that kernel
 constexpr int kMegaSupers = 64;         // super tiles per mega tile (65536 entities)
 
 struct RowSegment {  // part [begin, min(begin + segment, row end)) of one CSR row

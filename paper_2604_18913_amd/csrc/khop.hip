@@ -361,7 +361,7 @@ __device__ __forceinline__ unsigned group_ballot(bool p) {
 
 // One W-lane group per short object row (<= 32 entries): the group's lanes load
 // W entries at once, then gather the frontier lines of the candidates.
-template <int W, bool MASK>
+template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(256)
 k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__restrict__ off,
             const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
@@ -422,7 +422,7 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
         visited[(size_t)v * W + lw] = vis | nw;
         if (lw == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
     }
-    if (stats) {
+    if (STATS) {
         bool lead = (lw == 0);
         add_stats(stats, (lead && hi > lo) ? 1 : 0, lead ? n_edges : 0, lead ? n_lines : 0);
     }
@@ -432,7 +432,7 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
 // with one segment is finished here; segments of a multi-segment row merge
 // through atomicOr on level[h] and look at what the others have found so far
 // to stop early; k_pull_finish then folds those rows into visited.
-template <int W, bool MASK>
+template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(256)
 k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__restrict__ off,
            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
@@ -482,7 +482,7 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
             }
         }
     }
-    if (stats) {
+    if (STATS) {
         bool lead = lane() == 0;
         add_stats(stats, (lead && work) ? 1 : 0, lead ? n_edges : 0, lead ? n_lines : 0);
     }
@@ -538,7 +538,9 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
                                                                                     cur, r->visited);
 }
 
-template <int W, bool MASK>
+// STATS: the counting mode runs instantiations of its own, so that kernel statistics of the
+// ordinary ones are not mixed with it
+template <int W, bool MASK, bool STATS>
 static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_stats,
                         const unsigned long long *hc, hipStream_t st) {
     const size_t plane = (size_t)r->Epad * W;
@@ -557,13 +559,13 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
     }
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
-        k_pull_seg<W, MASK><<<dim3(blocks_for(rc.n_seg, 4)), dim3(256), 0, st>>>(
+        k_pull_seg<W, MASK, STATS><<<dim3(blocks_for(rc.n_seg, 4)), dim3(256), 0, st>>>(
             rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
             act_cur, stats(KK_PULL_SEG));
     }
     if (rc.n_tail > 0) {
         ProfScope ps(g->prof, KK_PULL_TAIL, st);
-        k_pull_tail<W, MASK><<<dim3(blocks_for(rc.n_tail * W, 256)), dim3(256), 0, st>>>(
+        k_pull_tail<W, MASK, STATS><<<dim3(blocks_for(rc.n_tail * W, 256)), dim3(256), 0, st>>>(
             rc.tail, rc.n_tail, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
             act_cur, stats(KK_PULL_TAIL));
     }
@@ -578,8 +580,13 @@ template <int W>
 static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
                     const unsigned long long *hc, hipStream_t st) {
     if (pull) {
-        if (r->has_mask) launch_pull<W, true>(g, r, h, want_stats, hc, st);
-        else launch_pull<W, false>(g, r, h, want_stats, hc, st);
+        if (r->has_mask) {
+            if (want_stats) launch_pull<W, true, true>(g, r, h, true, hc, st);
+            else launch_pull<W, true, false>(g, r, h, false, hc, st);
+        } else {
+            if (want_stats) launch_pull<W, false, true>(g, r, h, true, hc, st);
+            else launch_pull<W, false, false>(g, r, h, false, hc, st);
+        }
     } else {
         if (r->has_mask) launch_push<W, true>(g, r, h, hc, g->out_obj, g->out_rel, true, st);
         else launch_push<W, false>(g, r, h, hc, g->out_obj, g->out_rel, true, st);

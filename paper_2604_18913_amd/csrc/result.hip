@@ -307,7 +307,7 @@ __device__ __forceinline__ void row_slots(const FillArgs &a, int ev, int w_first
 
 // Object rows of 33 .. hub_min-1 entries: one wavefront per row, four rows per block.  A single
 // wavefront walks the row in order, so every predecessor is final when it is found.
-template <int W, bool MASK>
+template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_row, long long n_rows_total) {
     constexpr int Qp = 64 * W;
     __shared__ long long slots[4][Qp];
@@ -335,7 +335,7 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
             }
         }
     }
-    if (a.stats_hub && v == 0) {
+    if (STATS && v == 0) {
         if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
         if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
         if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
@@ -347,7 +347,7 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
 // tile's run; seeds get -1.  Phase 2: every entity whose object row has at most
 // 32 entries is walked by one W-lane group, two candidate lines in flight.
 // Longer rows are left to k_pred_row.
-template <int W, bool MASK>
+template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     constexpr int Qp = 64 * W;
     __shared__ unsigned long long stage[64][W + 1];
@@ -444,7 +444,201 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
                 if (!group_any<W>(rem != 0)) break;
             }
         }
-    if (a.stats_pred) {
+    if (STATS) {
+        n_rows = wave_sum(n_rows);
+        n_edges = wave_sum(n_edges);
+        n_lines = wave_sum(n_lines);
+        if (v == 0) {
+            if (n_rows) atomicAdd(&a.stats_pred[0], (unsigned long long)n_rows);
+            if (n_edges) atomicAdd(&a.stats_pred[1], (unsigned long long)n_edges);
+            if (n_lines) atomicAdd(&a.stats_pred[2], (unsigned long long)n_lines);
+        }
+    }
+}
+
+// Predecessor kernel for 16-word planes.  One block = a macro tile of 256
+// entities (4 tiles) x 4 words (256 queries); one 4-lane group per entity, lane
+// lw owns word 4*slab + lw.  A (query, entity) pair found during the row walk is
+// not stored to its scattered list position: a 16-bit code (entity, position in
+// its object row) goes to the block's staging buffer at the pair's place in the
+// query's run, and afterwards every query's run (up to 256 consecutive list
+// entries) leaves with full-width stores, which keeps the lines that reach HBM
+// whole.  Codes: 0xFFFF = seed (-1), 0xFFFE = not produced here (rows of more
+// than 32 entries, written by the row kernels).  When a macro tile has more
+// pairs than the staging buffer holds, its words are processed in several
+// passes.
+constexpr int kMtCap = 16384;   // staged codes per pass (>= 256 entities x 64 queries)
+constexpr int kMtEids = 3072;   // staged edge ids of the short rows
+constexpr unsigned kCodeSeed = 0xFFFFu, kCodeNone = 0xFFFEu;
+
+template <bool MASK, bool STATS>
+__global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
+    constexpr int W = 16, Qp = 1024, G = kPredGroup;
+    __shared__ unsigned long long mT[4][256];  // [tile][query]: tile entities the query reached
+    __shared__ uint32_t pos0[4][256];          // start of the tile's part of the query's staged run
+    __shared__ uint32_t lbase[257];            // start of the query's staged run
+    __shared__ long long base[256];            // list position of the query's run
+    __shared__ union {
+        unsigned long long stage[256][5];
+        uint16_t code[kMtCap];
+    } u;
+    __shared__ int eid_tab[kMtEids + 32];
+    __shared__ uint16_t roff[256];
+    __shared__ uint32_t in_lo[256];
+    __shared__ int wsum[8];
+    const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
+    if (L >= mt_count * 4) return;
+    const long long mt = mt_begin + (L >> 2);
+    const int slab = (int)(L & 3);
+    const int t = threadIdx.x, wave = t >> 6, v = lane();
+    const int vi = t / G, lw = t % G, wq = G * slab + lw, g0 = v & ~(G - 1);
+    const int tt = vi >> 6;
+    const long long tile0 = mt * kPredTiles;
+    const long long ev = tile0 * 64 + vi;
+    const bool valid = tile0 + tt < a.tile_begin + a.tile_count;
+    const unsigned long long range_w = range_bits(a.q0, a.q1, wq);
+    unsigned long long visw = 0, seedw = 0;
+    uint32_t lo = 0, hi = 0;
+    if (valid) {
+        visw = a.visited[(size_t)ev * W + wq] & range_w;
+        seedw = a.levels[(size_t)ev * W + wq] & range_w;
+        if (ev < a.E) {
+            lo = a.in_off[ev];
+            hi = a.in_off[ev + 1];
+        }
+    }
+    const uint32_t deg = hi - lo;
+    const bool shortrow = deg > 0 && deg <= (uint32_t)kTailMaxDegree;
+    u.stage[vi][lw] = visw;
+    if (lw == 0) {
+        roff[vi] = shortrow ? (uint16_t)deg : (uint16_t)0;
+        in_lo[vi] = lo;
+    }
+    __syncthreads();
+    {   // wave = (tile, word): lane qq gets the mask of tile entities query qq reached
+        const int wt = wave >> 2, wj = wave & 3;
+        unsigned long long x = u.stage[wt * 64 + v][wj], m = 0;
+        if (wave_any(x != 0)) m = transpose64(x);
+        mT[wt][wj * 64 + v] = m;
+    }
+    __syncthreads();
+    // staged layout: query-major, inside a query tile by tile; offsets into the edge-id table
+    int c0 = 0, c1 = 0, c2 = 0, tot = 0, ex = 0, dx = 0;
+    if (t < 256) {
+        c0 = __popcll(mT[0][t]);
+        c1 = __popcll(mT[1][t]);
+        c2 = __popcll(mT[2][t]);
+        tot = c0 + c1 + c2 + __popcll(mT[3][t]);
+        int wtot, dtot;
+        ex = wave_excl_scan(tot, wtot);
+        dx = wave_excl_scan((int)roff[t], dtot);
+        if (v == 0) {
+            wsum[wave] = wtot;
+            wsum[4 + wave] = dtot;
+        }
+    }
+    __syncthreads();
+    if (t < 256) {
+        for (int w2 = 0; w2 < wave; ++w2) {
+            ex += wsum[w2];
+            dx += wsum[4 + w2];
+        }
+        lbase[t] = (uint32_t)ex;
+        if (t == 255) lbase[256] = (uint32_t)(ex + tot);
+        pos0[0][t] = (uint32_t)ex;
+        pos0[1][t] = (uint32_t)(ex + c0);
+        pos0[2][t] = (uint32_t)(ex + c0 + c1);
+        pos0[3][t] = (uint32_t)(ex + c0 + c1 + c2);
+        roff[t] = (uint16_t)dx;
+        const int q = slab * 256 + t;
+        long long b = 0;
+        if (q >= a.q0 && q < a.q1) b = super_start(a, tile0 / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile0 * Qp + q];
+        base[t] = b;
+    }
+    __syncthreads();
+    const int my_roff = roff[vi];
+    if (shortrow && my_roff + kTailMaxDegree <= kMtEids)
+        for (uint32_t j = lw; j < deg; j += G) eid_tab[my_roff + j] = a.in_eid[lo + j];
+    const unsigned long long below = (1ull << (vi & 63)) - 1ull;
+    long long n_rows = 0, n_edges = 0, n_lines = 0;
+    for (int ja = 0; ja < 4;) {  // pass over the words [ja, jb)
+        int jb = ja + 1;
+        while (jb < 4 && lbase[64 * (jb + 1)] - lbase[64 * ja] <= (uint32_t)kMtCap) ++jb;
+        const uint32_t goff = lbase[64 * ja], gcount = lbase[64 * jb] - goff;
+        for (uint32_t i = t; i * 4 < gcount; i += 1024)
+            reinterpret_cast<uint2 *>(u.code)[i] = make_uint2(kCodeNone * 0x10001u, kCodeNone * 0x10001u);
+        __syncthreads();
+        const bool mine = lw >= ja && lw < jb;
+        auto emit = [&](unsigned long long bits, unsigned code) {
+            for (unsigned long long m = bits; m; m &= m - 1) {
+                const int ql = lw * 64 + (__ffsll((long long)m) - 1);
+                u.code[pos0[tt][ql] + __popcll(mT[tt][ql] & below) - goff] = (uint16_t)code;
+            }
+        };
+        if (mine && seedw) emit(seedw, kCodeSeed);
+        if (shortrow)
+            for (int h = 1; h <= a.k; ++h) {
+                unsigned long long rem = mine ? a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w : 0ull;
+                if (!group_any<G>(rem != 0)) continue;
+                const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
+                const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+                if (STATS && lw == 0) ++n_rows;
+                for (uint32_t j0 = lo; j0 < hi; j0 += G) {
+                    uint32_t j = j0 + lw;
+                    int s = 0;
+                    bool cand = false;
+                    if (j < hi) {
+                        s = a.in_sub[j];
+                        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+                    }
+                    unsigned gm = (unsigned)((__ballot(cand) >> g0) & ((1u << G) - 1u));
+                    if (STATS && lw == 0) {
+                        n_edges += min((uint32_t)G, hi - j0);
+                        n_lines += __popc(gm);
+                    }
+                    while (gm) {  // two candidate lines in flight, resolved in edge order
+                        int d0 = __ffs((int)gm) - 1;
+                        gm &= gm - 1;
+                        int d1 = -1;
+                        if (gm) {
+                            d1 = __ffs((int)gm) - 1;
+                            gm &= gm - 1;
+                        }
+                        int s0 = __shfl(s, g0 + d0), s1 = __shfl(s, g0 + (d1 < 0 ? d0 : d1));
+                        unsigned long long l0 = prev[(size_t)s0 * W + wq], l1 = 0;
+                        if (d1 >= 0) l1 = prev[(size_t)s1 * W + wq];
+                        if (MASK) {
+                            l0 &= a.allow[(size_t)a.in_rel[j0 + d0] * W + wq];
+                            if (d1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + d1] * W + wq];
+                        }
+                        unsigned long long hit0 = l0 & rem, hit1 = l1 & rem & ~l0;
+                        rem &= ~(l0 | l1);
+                        if (hit0) emit(hit0, ((unsigned)vi << 5) | (j0 + d0 - lo));
+                        if (hit1) emit(hit1, ((unsigned)vi << 5) | (j0 + d1 - lo));
+                        if (!group_any<G>(rem != 0)) break;
+                    }
+                    if (!group_any<G>(rem != 0)) break;
+                }
+            }
+        __syncthreads();
+        for (int ql = 64 * ja + wave; ql < 64 * jb; ql += 16) {  // one wavefront per query's run
+            const uint32_t src = lbase[ql] - goff, n = lbase[ql + 1] - lbase[ql];
+            const long long dst = base[ql];
+            for (uint32_t i = v; i < n; i += 64) {
+                const unsigned code = u.code[src + i];
+                if (code == kCodeNone) continue;
+                int val = -1;
+                if (code != kCodeSeed) {
+                    const int e = code >> 5, jp = code & 31, ro = roff[e];
+                    val = ro + kTailMaxDegree <= kMtEids ? eid_tab[ro + jp] : a.in_eid[in_lo[e] + jp];
+                }
+                a.pred[dst + i] = val;
+            }
+        }
+        __syncthreads();
+        ja = jb;
+    }
+    if (STATS && slab == 0) {  // work counters on one quarter of the words
         n_rows = wave_sum(n_rows);
         n_edges = wave_sum(n_edges);
         n_lines = wave_sum(n_lines);
@@ -463,7 +657,7 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
 // edge id any of them found (LDS atomicMin); after the step the resolved queries
 // are removed from the shared mask, so a later step (larger edge ids) never
 // touches them.  Each predecessor is then written once.
-template <int W, bool MASK>
+template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
     constexpr int Qp = 64 * W;
     constexpr int C = 4;  // 64-entry chunks per wavefront and step, loaded together
@@ -526,7 +720,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         for (int q = t; q < Qp; q += blockDim.x)
             if ((slevel[q >> 6] >> (q & 63)) & 1ull) a.pred[slot[q]] = smin[q];
     }
-    if (a.stats_hub && v == 0) {
+    if (STATS && v == 0) {
         if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
         if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
         if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
@@ -609,28 +803,43 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
     else k_lists<W, 8><<<grid, block, 0, st>>>(a);
 }
 
-// predecessor kernels over the tiles [a.tile_begin, +a.tile_count) and the long rows a.rows[0 ..
-// n_hub_rows + n_other_rows): the hub rows first (16 waves per row), then the others (4 waves)
-template <int W>
-static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
-                          bool mask, hipStream_t st_tiles, hipStream_t st) {
+template <int W, bool MASK, bool STATS>
+static void launch_pred_wms(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
+                            hipStream_t st_tiles, hipStream_t st) {
     if (n_hub_rows + n_other_rows > 0) {
         ProfScope ps(prof, KK_PRED_HUB, st);
-        if (n_hub_rows > 0) {
-            if (mask) k_pred_row<W, true><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
-            else k_pred_row<W, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
-        }
-        if (n_other_rows > 0) {
-            dim3 grid((unsigned)((n_other_rows + 3) / 4));
-            if (mask) k_pred_wave<W, true><<<grid, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
-            else k_pred_wave<W, false><<<grid, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
-        }
+        if (n_hub_rows > 0) k_pred_row<W, MASK, STATS><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
+        if (n_other_rows > 0)
+            k_pred_wave<W, MASK, STATS><<<dim3((unsigned)((n_other_rows + 3) / 4)), dim3(256), 0, st>>>(a, n_hub_rows,
+                                                                                                     n_other_rows);
     }
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st_tiles);
-        dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
-        if (mask) k_pred<W, true><<<grid, block, 0, st_tiles>>>(a);
-        else k_pred<W, false><<<grid, block, 0, st_tiles>>>(a);
+        if (W == 16 && a.tile_begin % kPredTiles == 0) {
+            const long long mt_count = (a.tile_count + kPredTiles - 1) / kPredTiles;
+            dim3 grid((unsigned)((mt_count * 4 + 7) / 8 * 8));
+            k_pred_mt<MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a, a.tile_begin / kPredTiles, mt_count);
+        } else {
+            dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
+            k_pred<W, MASK, STATS><<<grid, block, 0, st_tiles>>>(a);
+        }
+    }
+}
+
+// predecessor kernels over the tiles [a.tile_begin, +a.tile_count) and the long rows a.rows[0 ..
+// n_hub_rows + n_other_rows): the hub rows first (16 waves per row), then the others (one wave
+// each).  The counting mode runs instantiations of its own, so that kernel statistics of the
+// ordinary ones are not mixed with it.
+template <int W>
+static void launch_pred_w(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
+                          bool mask, hipStream_t st_tiles, hipStream_t st) {
+    const bool stats = a.stats_pred != nullptr;
+    if (mask) {
+        if (stats) launch_pred_wms<W, true, true>(prof, a, n_hub_rows, n_other_rows, st_tiles, st);
+        else launch_pred_wms<W, true, false>(prof, a, n_hub_rows, n_other_rows, st_tiles, st);
+    } else {
+        if (stats) launch_pred_wms<W, false, true>(prof, a, n_hub_rows, n_other_rows, st_tiles, st);
+        else launch_pred_wms<W, false, false>(prof, a, n_hub_rows, n_other_rows, st_tiles, st);
     }
 }
 

@@ -146,11 +146,12 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
     while (t0 < ntiles) {
         long long t1 = t0;
         int64_t e_begin = ioff[(size_t)std::min<long long>(t0 * 64, E)], e_end = e_begin;
-        while (t1 < ntiles) {
-            int64_t nxt = ioff[(size_t)std::min<long long>((t1 + 1) * 64, E)];
+        while (t1 < ntiles) {  // chunks begin on a multiple of kPredTiles tiles
+            const long long t2 = std::min<long long>(t1 + kPredTiles, ntiles);
+            int64_t nxt = ioff[(size_t)std::min<long long>(t2 * 64, E)];
             if (t1 > t0 && nxt - e_begin > target) break;
             e_end = nxt;
-            ++t1;
+            t1 = t2;
         }
         ShardSet::Chunk c;
         c.tile_begin = t0; c.tile_count = t1 - t0; c.edge_begin = e_begin; c.edge_count = e_end - e_begin;
