@@ -297,7 +297,7 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     if (g->ev_fork) (void)hipEventDestroy(g->ev_fork);
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
                     g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,
-                    g->fr_seg, g->d_ctr};
+                    g->fr_seg, g->d_ctr, g->long_index, g->row_pred};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (g->h_ctr) (void)hipHostFree(g->h_ctr);

@@ -156,6 +156,13 @@ struct logoskg_graph {
     std::vector<int64_t> shard_triples;
     void *shards = nullptr;  // lkg::ShardSet* when num_shards > 1
 
+    // predecessor pass with 16-word planes: the kernels of the long object rows leave their
+    // results in row_pred[row index][query] and the tile kernel moves them into the lists
+    int32_t *long_index = nullptr;  // [E] position of a long row's entity in in_rows.longrows
+    int32_t *row_pred = nullptr;    // [row_pred_rows][1024]
+    int64_t row_pred_rows = 0;
+    bool row_pred_tried = false;
+
     // side streams (default priority) so that the independent result kernels of a fetch overlap
     hipStream_t side[2] = {nullptr, nullptr};
     hipEvent_t ev_fork = nullptr, ev_join[2] = {nullptr, nullptr};
@@ -289,6 +296,10 @@ struct FillArgs {
     const int32_t *in_sub, *in_eid;
     const uint16_t *in_rel;
     const int32_t *rows;  // long object rows of this predecessor launch
+    long long row_base;   // position of rows[0] in the graph's list of long rows
+    const int32_t *long_index;  // entity -> position in that list (long rows only)
+    int32_t *row_pred;    // [rows of the launch][1024] results of the row kernels, or NULL: they
+                          // write the lists themselves
     int32_t *entity;
     uint8_t *hop;
     int32_t *pred;
@@ -299,6 +310,7 @@ void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
                  hipStream_t st_tiles, hipStream_t st_rows);
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
+long long max_chunk_rows(const logoskg_graph *g);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
                        const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st);

@@ -307,18 +307,21 @@ __device__ __forceinline__ void row_slots(const FillArgs &a, int ev, int w_first
 
 // Object rows of 33 .. hub_min-1 entries: one wavefront per row, four rows per block.  A single
 // wavefront walks the row in order, so every predecessor is final when it is found.
-template <int W, bool MASK, bool STATS>
+template <int W, bool MASK, bool STATS, bool BUF>
 __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_row, long long n_rows_total) {
     constexpr int Qp = 64 * W;
-    __shared__ long long slots[4][Qp];
+    __shared__ long long slots[BUF ? 1 : 4][BUF ? 1 : Qp];
     const int wave = threadIdx.x >> 6, v = lane(), lw = v & (W - 1);
     const long long idx = (long long)blockIdx.x * 4 + wave;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     if (idx < n_rows_total) {  // wave-uniform
         const int ev = a.rows[first_row + idx];
-        long long *slot = slots[wave];
-        row_slots<W>(a, ev, 0, 1, slot);
-        __builtin_amdgcn_wave_barrier();
+        long long *slot = slots[BUF ? 0 : wave];
+        int32_t *out = BUF ? a.row_pred + (size_t)(first_row + idx) * Qp : a.pred;
+        if (!BUF) {
+            row_slots<W>(a, ev, 0, 1, slot);
+            __builtin_amdgcn_wave_barrier();
+        }
         const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
         for (int h = 1; h <= a.k; ++h) {
             unsigned long long rem = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
@@ -328,7 +331,10 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
             ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
                 n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1) a.pred[slot[lw * 64 + (__ffsll((long long)m) - 1)]] = eid;
+                    for (unsigned long long m = hit; m; m &= m - 1) {
+                        const int q = lw * 64 + (__ffsll((long long)m) - 1);
+                        out[BUF ? (long long)q : slot[q]] = eid;
+                    }
                 });
                 n_edges += min((uint32_t)64, hi - j0);
                 if (!wave_any(rem != 0)) break;
@@ -463,13 +469,15 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
 // its object row) goes to the block's staging buffer at the pair's place in the
 // query's run, and afterwards every query's run (up to 256 consecutive list
 // entries) leaves with full-width stores, which keeps the lines that reach HBM
-// whole.  Codes: 0xFFFF = seed (-1), 0xFFFE = not produced here (rows of more
-// than 32 entries, written by the row kernels).  When a macro tile has more
+// whole.  Rows of more than 32 entries belong to the row kernels: when those
+// ran before and left their results in row_pred, the pairs of such an entity are
+// staged as (kCodeRow | entity) and fetched from there; otherwise they stay
+// 0xFFFE = not produced here.  0xFFFF = seed (-1).  When a macro tile has more
 // pairs than the staging buffer holds, its words are processed in several
 // passes.
 constexpr int kMtCap = 16384;   // staged codes per pass (>= 256 entities x 64 queries)
 constexpr int kMtEids = 3072;   // staged edge ids of the short rows
-constexpr unsigned kCodeSeed = 0xFFFFu, kCodeNone = 0xFFFEu;
+constexpr unsigned kCodeSeed = 0xFFFFu, kCodeNone = 0xFFFEu, kCodeRow = 0x4000u;  // kCodeRow | entity: a long row
 
 template <bool MASK, bool STATS>
 __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
@@ -485,6 +493,7 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     __shared__ int eid_tab[kMtEids + 32];
     __shared__ uint16_t roff[256];
     __shared__ uint32_t in_lo[256];
+    __shared__ int long_li[256];
     __shared__ int wsum[8];
     const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
     if (L >= mt_count * 4) return;
@@ -510,9 +519,11 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     const uint32_t deg = hi - lo;
     const bool shortrow = deg > 0 && deg <= (uint32_t)kTailMaxDegree;
     u.stage[vi][lw] = visw;
+    const bool longrow = deg > (uint32_t)kTailMaxDegree && a.row_pred != nullptr;
     if (lw == 0) {
         roff[vi] = shortrow ? (uint16_t)deg : (uint16_t)0;
         in_lo[vi] = lo;
+        long_li[vi] = longrow ? (int)(a.long_index[ev] - a.row_base) : 0;
     }
     __syncthreads();
     {   // wave = (tile, word): lane qq gets the mask of tile entities query qq reached
@@ -576,6 +587,7 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
             }
         };
         if (mine && seedw) emit(seedw, kCodeSeed);
+        if (mine && longrow && (visw & ~seedw)) emit(visw & ~seedw, kCodeRow | (unsigned)vi);
         if (shortrow)
             for (int h = 1; h <= a.k; ++h) {
                 unsigned long long rem = mine ? a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w : 0ull;
@@ -628,7 +640,9 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
                 const unsigned code = u.code[src + i];
                 if (code == kCodeNone) continue;
                 int val = -1;
-                if (code != kCodeSeed) {
+                if (code & kCodeRow) {
+                    if (code != kCodeSeed) val = a.row_pred[(size_t)long_li[code & 255] * Qp + slab * 256 + ql];
+                } else {
                     const int e = code >> 5, jp = code & 31, ro = roff[e];
                     val = ro + kTailMaxDegree <= kMtEids ? eid_tab[ro + jp] : a.in_eid[in_lo[e] + jp];
                 }
@@ -657,16 +671,17 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
 // edge id any of them found (LDS atomicMin); after the step the resolved queries
 // are removed from the shared mask, so a later step (larger edge ids) never
 // touches them.  Each predecessor is then written once.
-template <int W, bool MASK, bool STATS>
+template <int W, bool MASK, bool STATS, bool BUF>
 __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
     constexpr int Qp = 64 * W;
     constexpr int C = 4;  // 64-entry chunks per wavefront and step, loaded together
-    __shared__ long long slot[Qp];
+    __shared__ long long slot[BUF ? 1 : Qp];
     __shared__ int smin[Qp];
     __shared__ unsigned long long srem[16], slevel[16];
     const int ev = a.rows[first_row + blockIdx.x];
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, v = lane(), lw = v & (W - 1);
-    row_slots<W>(a, ev, wave, nw, slot);
+    if (!BUF) row_slots<W>(a, ev, wave, nw, slot);
+    int32_t *out = BUF ? a.row_pred + (size_t)(first_row + blockIdx.x) * Qp : a.pred;
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int h = 1; h <= a.k; ++h) {
@@ -718,7 +733,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         }
         __syncthreads();
         for (int q = t; q < Qp; q += blockDim.x)
-            if ((slevel[q >> 6] >> (q & 63)) & 1ull) a.pred[slot[q]] = smin[q];
+            if ((slevel[q >> 6] >> (q & 63)) & 1ull) out[BUF ? (long long)q : slot[q]] = smin[q];
     }
     if (STATS && v == 0) {
         if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
@@ -791,6 +806,32 @@ logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
     return LOGOSKG_OK;
 }
 
+__global__ void k_long_index(const int32_t *__restrict__ rows, long long n, int32_t *index) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) index[rows[i]] = (int32_t)i;
+}
+
+// First predecessor fetch with 16-word planes: the entity -> long-row position map and the
+// buffer the row kernels write to (one 1024-query line per long row of a launch).  A graph whose
+// buffer would pass 8 GiB keeps the direct path.
+logoskg_status prepare_row_pred(logoskg_graph *g, hipStream_t st) {
+    if (g->row_pred_tried) return LOGOSKG_OK;
+    g->row_pred_tried = true;
+    const long long rows = g->num_shards > 1 ? max_chunk_rows(g) : (long long)g->in_rows.n_long;
+    if (rows <= 0 || (size_t)rows * 4096 > ((size_t)8 << 30)) return LOGOSKG_OK;
+    LKG_HIP(hipMalloc((void **)&g->long_index, (size_t)g->E * sizeof(int32_t)));
+    if (hipMalloc((void **)&g->row_pred, (size_t)rows * 4096) != hipSuccess) {
+        (void)hipGetLastError();
+        g->row_pred = nullptr;
+        return LOGOSKG_OK;
+    }
+    g->row_pred_rows = rows;
+    k_long_index<<<dim3((unsigned)((g->in_rows.n_long + 255) / 256)), dim3(256), 0, st>>>(g->in_rows.longrows,
+                                                                                         g->in_rows.n_long, g->long_index);
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}
+
 template <int W>
 static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
     const long long nsuper = (a.ntiles + kSuperTiles - 1) / kSuperTiles;
@@ -804,18 +845,25 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
 }
 
 template <int W, bool MASK, bool STATS>
-static void launch_pred_wms(Profiler &prof, const FillArgs &a, long long n_hub_rows, long long n_other_rows,
+static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_rows, long long n_other_rows,
                             hipStream_t st_tiles, hipStream_t st) {
+    FillArgs a = a0;
+    const bool mt = W == 16 && a.tile_begin % kPredTiles == 0;
+    if (!mt) a.row_pred = nullptr;
     if (n_hub_rows + n_other_rows > 0) {
         ProfScope ps(prof, KK_PRED_HUB, st);
-        if (n_hub_rows > 0) k_pred_row<W, MASK, STATS><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
-        if (n_other_rows > 0)
-            k_pred_wave<W, MASK, STATS><<<dim3((unsigned)((n_other_rows + 3) / 4)), dim3(256), 0, st>>>(a, n_hub_rows,
-                                                                                                     n_other_rows);
+        const dim3 gw((unsigned)((n_other_rows + 3) / 4));
+        if (a.row_pred) {
+            if (n_hub_rows > 0) k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
+            if (n_other_rows > 0) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+        } else {
+            if (n_hub_rows > 0) k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
+            if (n_other_rows > 0) k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+        }
     }
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st_tiles);
-        if (W == 16 && a.tile_begin % kPredTiles == 0) {
+        if (mt) {
             const long long mt_count = (a.tile_count + kPredTiles - 1) / kPredTiles;
             dim3 grid((unsigned)((mt_count * 4 + 7) / 8 * 8));
             k_pred_mt<MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a, a.tile_begin / kPredTiles, mt_count);
@@ -851,8 +899,9 @@ void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st) {
     }
 }
 
-// The tile kernel and the row kernels write disjoint list entries, so they may run on
-// different streams.
+// Without a.row_pred the tile kernel and the row kernels write disjoint list entries and may
+// run on different streams; with it the tile kernel reads what the row kernels wrote and both
+// streams must be the same.
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
                  hipStream_t st_tiles, hipStream_t st_rows) {
     switch (W) {
@@ -899,6 +948,12 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.reached_off = r->d_reached_off;
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.rows = g->in_rows.longrows;
+    a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr;
+    if (pred && W == 16) {
+        LKG_TRY(prepare_row_pred(g, st));
+        a.long_index = g->long_index;
+        a.row_pred = g->row_pred;
+    }
     a.entity = entity; a.hop = hop; a.pred = pred;
     const bool counting = g->prof.counters;
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
@@ -909,12 +964,13 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     const char *serial_env = getenv("LOGOSKG_SERIAL_FETCH");  // measurement aid: one kernel at a time
     const bool serial = serial_env && serial_env[0] == '1';
     if (pred && g->num_shards <= 1 && !serial) {
+        const int n_side = a.row_pred ? 1 : 2;  // with row_pred the row kernels precede the tile kernel
         LKG_HIP(hipEventRecord(g->ev_fork, st));
-        for (int i = 0; i < 2; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
+        for (int i = 0; i < n_side; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
         launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, g->side[0],
-                    g->side[1]);
+                    g->side[n_side - 1]);
         launch_lists(g->prof, a, W, st);
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < n_side; ++i) {
             LKG_HIP(hipEventRecord(g->ev_join[i], g->side[i]));
             LKG_HIP(hipStreamWaitEvent(st, g->ev_join[i], 0));
         }

@@ -188,6 +188,14 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
     return LOGOSKG_OK;
 }
 
+long long max_chunk_rows(const logoskg_graph *g) {
+    const ShardSet *ss = (const ShardSet *)g->shards;
+    long long m = 0;
+    if (ss)
+        for (const ShardSet::Chunk &c : ss->chunks) m = std::max(m, c.row_count);
+    return m;
+}
+
 // Predecessor pass of a sharded graph: the object-sorted triples are streamed
 // chunk by chunk (double buffered: the next chunk copies while this one runs).
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st) {
@@ -225,6 +233,7 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
         x.tile_begin = c.tile_begin;
         x.tile_count = c.tile_count;
         x.rows = g->in_rows.longrows + c.row_begin;
+        x.row_base = c.row_begin;
         launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st, st);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->stage_idle[b], st));
