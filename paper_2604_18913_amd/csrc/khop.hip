@@ -73,52 +73,65 @@ __global__ void k_allow(int Q, int R, int W, int rel_words, const unsigned long 
 // to out_off for a resident graph; shard-grouped order for a sharded one).  With
 // shard_of != NULL only the subjects of `shard` are listed (Algorithm 1, line 6:
 // restriction of the frontier to one sub-graph).
-__global__ void k_census(const uint32_t *__restrict__ act, long long nwords,
-                         const uint32_t *__restrict__ out_off, const uint32_t *__restrict__ row_begin,
-                         const uint8_t *__restrict__ shard_of, int shard, int write_lists,
-                         int32_t *list_tail, RowSegment *list_seg, unsigned long long *ctr) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    uint32_t word = i < nwords ? act[i] : 0u;
-    if (shard_of) {  // drop the entities of other shards
-        for (uint32_t m = word; m; m &= m - 1) {
-            int b = __ffs((int)m) - 1;
-            if (shard_of[i * 32 + b] != (uint8_t)shard) word &= ~(1u << b);
+__global__ void __launch_bounds__(256)
+k_census(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__ out_off,
+         const uint32_t *__restrict__ row_begin, const uint8_t *__restrict__ shard_of, int shard, int write_lists,
+         int32_t *list_tail, RowSegment *list_seg, unsigned long long *ctr) {
+    // one thread per entity and step (coalesced offsets); mode 0 counts, mode 1 appends the
+    // lists (C_NTAIL / C_NSEG are then the append cursors)
+    __shared__ long long part[4][5];
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    long long ct = 0, cs = 0, cr = 0, na = 0, deg_sum = 0;
+    for (long long base = (long long)blockIdx.x * blockDim.x; base < E; base += stride) {  // block-uniform trip count
+        const long long e = base + threadIdx.x;
+        bool on = false;
+        uint32_t d = 0;
+        if (e < E) {
+            on = (act[e >> 5] >> (e & 31)) & 1u;
+            if (on && shard_of && shard_of[e] != (uint8_t)shard) on = false;
+            if (on) d = out_off[e + 1] - out_off[e];
+        }
+        const bool tail = d > 0 && d <= (uint32_t)kTailMaxDegree;
+        const int segs = d > (uint32_t)kTailMaxDegree ? (int)((d + kPushSegment - 1) / kPushSegment) : 0;
+        if (!write_lists) {
+            na += on;
+            cr += d > 0;
+            ct += tail;
+            cs += segs;
+            deg_sum += d;
+            continue;
+        }
+        const unsigned long long tmask = __ballot(tail);
+        int ts;
+        const int ps = wave_excl_scan(segs, ts);
+        unsigned long long bt = 0, bs = 0;
+        if (lane() == 0) {
+            if (tmask) bt = atomicAdd(&ctr[C_NTAIL], (unsigned long long)__popcll(tmask));
+            if (ts) bs = atomicAdd(&ctr[C_NSEG], (unsigned long long)ts);
+        }
+        bt = shfl64(bt, 0);
+        bs = shfl64(bs, 0);
+        if (tail) list_tail[bt + __popcll(tmask & ((1ull << lane()) - 1ull))] = (int32_t)e;
+        if (segs) {
+            const uint32_t lo = row_begin[e];
+            for (int i = 0; i < segs; ++i) list_seg[bs + ps + i] = RowSegment{(int32_t)e, lo + (uint32_t)i * kPushSegment};
         }
     }
-    int ct = 0, cs = 0, cr = 0;
-    long long deg_sum = 0;
-    for (uint32_t m = word; m; m &= m - 1) {
-        int e = (int)(i * 32) + (__ffs((int)m) - 1);
-        uint32_t d = out_off[e + 1] - out_off[e];
-        deg_sum += d;
-        if (d > 0) ++cr;
-        if (d > (uint32_t)kTailMaxDegree) cs += (int)((d + kPushSegment - 1) / kPushSegment);
-        else if (d > 0) ++ct;
-    }
-    int tt, ts;
-    int pt = wave_excl_scan(ct, tt), ps = wave_excl_scan(cs, ts);
-    long long es = wave_sum(deg_sum);
-    long long na = wave_sum((long long)__popc(word));
-    long long nr = wave_sum((long long)cr);
-    unsigned long long bt = 0, bs = 0;
+    if (write_lists) return;
+    ct = wave_sum(ct);
+    cs = wave_sum(cs);
+    cr = wave_sum(cr);
+    na = wave_sum(na);
+    deg_sum = wave_sum(deg_sum);
+    const int wave = threadIdx.x >> 6;
     if (lane() == 0) {
-        if (tt) bt = atomicAdd(&ctr[C_NTAIL], (unsigned long long)tt);
-        if (ts) bs = atomicAdd(&ctr[C_NSEG], (unsigned long long)ts);
-        if (nr) atomicAdd(&ctr[C_NROWS], (unsigned long long)nr);
-        if (es) atomicAdd(&ctr[C_FEDGES], (unsigned long long)es);
-        if (na) atomicAdd(&ctr[C_NACTIVE], (unsigned long long)na);
+        part[wave][0] = ct; part[wave][1] = cs; part[wave][2] = cr; part[wave][3] = deg_sum; part[wave][4] = na;
     }
-    if (!write_lists) return;
-    bt = shfl64(bt, 0) + pt;
-    bs = shfl64(bs, 0) + ps;
-    for (uint32_t m = word; m; m &= m - 1) {
-        int e = (int)(i * 32) + (__ffs((int)m) - 1);
-        uint32_t lo = row_begin[e], hi = lo + (out_off[e + 1] - out_off[e]);
-        if (hi - lo > (uint32_t)kTailMaxDegree) {
-            for (uint32_t j = lo; j < hi; j += kPushSegment) list_seg[bs++] = RowSegment{e, j};
-        } else if (hi > lo) {
-            list_tail[bt++] = e;
-        }
+    __syncthreads();
+    if (threadIdx.x < 5) {
+        long long x = part[0][threadIdx.x] + part[1][threadIdx.x] + part[2][threadIdx.x] + part[3][threadIdx.x];
+        const int slot[5] = {C_NTAIL, C_NSEG, C_NROWS, C_FEDGES, C_NACTIVE};
+        if (x) atomicAdd(&ctr[slot[threadIdx.x]], (unsigned long long)x);
     }
 }
 
@@ -133,25 +146,33 @@ __device__ __forceinline__ unsigned long long or_across_groups(unsigned long lon
 // the queries for which this hop can still reach something.  A pull row stops
 // as soon as it has all of them.
 template <int W>
+__device__ __forceinline__ int take_candidates(unsigned long long &rest);
+
+template <int W>
 __global__ void __launch_bounds__(256)
-k_live(const int32_t *__restrict__ list_tail, const RowSegment *__restrict__ list_seg,
-       const unsigned long long *__restrict__ ctr, const uint32_t *__restrict__ row_begin,
+k_live(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__ out_off,
        const unsigned long long *__restrict__ prev, unsigned long long *live) {
     __shared__ unsigned long long sl[16];
     if (threadIdx.x < 16) sl[threadIdx.x] = 0;
     __syncthreads();
-    const long long nt = (long long)ctr[C_NTAIL], total = nt + (long long)ctr[C_NSEG];
-    const long long ngroups = (long long)gridDim.x * blockDim.x / W;
+    // a wavefront tests 64 consecutive entities (coalesced), then its groups fetch the lines of
+    // the frontier rows among them, two at a time
+    const long long nwaves = (long long)gridDim.x * (blockDim.x >> 6);
     const int lw = threadIdx.x & (W - 1);
     unsigned long long acc = 0;
-    for (long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W; i < total; i += ngroups) {
-        int row = -1;
-        if (i < nt) row = list_tail[i];
-        else {
-            RowSegment sg = list_seg[i - nt];
-            if (sg.begin == row_begin[sg.row]) row = sg.row;  // count a long row once
+    for (long long base = ((long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64; base < E;
+         base += nwaves * 64) {
+        const long long e = base + lane();
+        bool on = false;
+        if (e < E) on = ((act[e >> 5] >> (e & 31)) & 1u) && out_off[e + 1] > out_off[e];
+        unsigned long long m = __ballot(on);
+        while (m) {
+            const int p0 = take_candidates<W>(m), p1 = take_candidates<W>(m);
+            unsigned long long l0 = 0, l1 = 0;
+            if (p0 >= 0) l0 = prev[(size_t)(base + p0) * W + lw];
+            if (p1 >= 0) l1 = prev[(size_t)(base + p1) * W + lw];
+            acc |= l0 | l1;
         }
-        if (row >= 0) acc |= prev[(size_t)row * W + lw];
     }
     acc = or_across_groups<W>(acc);
     if (lane() < W && acc) atomicOr(&sl[lane()], acc);
@@ -553,9 +574,8 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
     const RowClasses &rc = g->in_rows;
     {
         ProfScope ps(g->prof, KK_LIVE, st);
-        long long items = (long long)(hc[C_NTAIL] + hc[C_NSEG]);
-        unsigned nb = std::min<unsigned>(1024u, std::max(1u, blocks_for(items * W, 256)));
-        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(g->fr_tail, g->fr_seg, g->d_ctr, g->row_begin, prev, live);
+        unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
+        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, prev, live);
     }
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
@@ -622,19 +642,31 @@ void launch_resident_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, 
     }
 }
 
-// Census of level h's active bitmap (all subjects, or those of one shard); leaves
-// the counters in g->h_ctr (stream synchronised).
+// Census of level h's active bitmap (all subjects, or those of one shard): counts the rows,
+// edges and list entries into g->h_ctr (stream synchronised); with write_lists a second pass
+// appends the push work lists.
+static void launch_census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool lists, hipStream_t st) {
+    const long long nwords = r->Epad / 32;
+    ProfScope ps(g->prof, KK_CENSUS, st);
+    const unsigned nb = std::min<unsigned>(1024u, std::max(1u, blocks_for(g->E, 256)));
+    k_census<<<dim3(nb), dim3(256), 0, st>>>(r->act + (size_t)nwords * h, g->E, g->out_off, g->row_begin,
+                                             shard >= 0 ? g->shard_of_dev : nullptr, shard, lists ? 1 : 0,
+                                             g->fr_tail, g->fr_seg, g->d_ctr);
+}
+
+logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st) {
+    LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 2 * sizeof(unsigned long long), st));  // C_NTAIL, C_NSEG: append cursors
+    launch_census(g, r, h, shard, true, st);
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}
+
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st) {
     LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 5 * sizeof(unsigned long long), st));
-    long long nwords = r->Epad / 32;
-    {
-        ProfScope ps(g->prof, KK_CENSUS, st);
-        k_census<<<dim3(blocks_for(nwords, 256)), dim3(256), 0, st>>>(
-            r->act + (size_t)nwords * h, nwords, g->out_off, g->row_begin, shard >= 0 ? g->shard_of_dev : nullptr,
-            shard, write_lists ? 1 : 0, g->fr_tail, g->fr_seg, g->d_ctr);
-    }
+    launch_census(g, r, h, shard, false, st);
     LKG_HIP(hipGetLastError());
     LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    if (write_lists) LKG_TRY(census_lists(g, r, h, shard, st));
     LKG_HIP(hipStreamSynchronize(st));
     return LOGOSKG_OK;
 }
@@ -725,7 +757,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     g->prof.end(st);
     KH(hipGetLastError());
     const bool want_stats = g->prof.counters;
-    if ((s = census(g, r, 0, -1, k > 0 && g->num_shards <= 1, st)) != LOGOSKG_OK) return fail(s);
+    if ((s = census(g, r, 0, -1, false, st)) != LOGOSKG_OK) return fail(s);
     if (g->h_ctr[C_ERR]) {
         set_error("seed_off / seeds are inconsistent or out of range (device check, code %llu)", g->h_ctr[C_ERR]);
         return fail(LOGOSKG_EINVAL);
@@ -751,10 +783,11 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
             memcpy(hc, g->h_ctr, sizeof(hc));
             if (want_stats)
                 KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
+            if (!pull && (s = census_lists(g, r, h - 1, -1, st)) != LOGOSKG_OK) return fail(s);
             launch_resident_hop(g, r, h, pull, want_stats, hc, st);
             KH(hipGetLastError());
         }
-        if ((s = census(g, r, h, -1, h < k && g->num_shards <= 1, st)) != LOGOSKG_OK) return fail(s);
+        if ((s = census(g, r, h, -1, false, st)) != LOGOSKG_OK) return fail(s);
         hs.entities_reached = (long long)g->h_ctr[C_NACTIVE];
         if (hs.direction == LOGOSKG_DIR_PULL) {
             for (int kind : {KK_PULL_TAIL, KK_PULL_SEG}) {
