@@ -311,48 +311,60 @@ __device__ __forceinline__ int take_candidates(unsigned long long &rest) {
     return mine;
 }
 
-// 64 consecutive in-edges of one object row: lanes test whether their edge's
-// subject is in the frontier, then the groups gather the frontier lines of the
-// candidates, two rounds of loads in flight.  acc collects (per group) the OR
-// of the gathered words; returns the number of lines gathered.
-template <int W, bool MASK>
-__device__ __forceinline__ int pull_chunk(uint32_t j0, uint32_t hi, const int32_t *__restrict__ in_sub,
-                                          const uint16_t *__restrict__ in_rel,
-                                          const uint32_t *__restrict__ act_prev,
-                                          const unsigned long long *__restrict__ prev,
-                                          const unsigned long long *__restrict__ allow,
-                                          unsigned long long &acc) {
+// 64 consecutive in-edges of one object row, in three stages so that a caller can
+// keep the loads of later chunks in flight: subject (and relation) ids, the
+// frontier bit of every subject, then the gather of the frontier lines of the
+// candidates (64/W per round, four rounds of loads in flight).  acc collects
+// (per group) the OR of the gathered words; gather returns the number of lines.
+struct PullEdges {
+    int s, r;
+};
+
+template <bool MASK>
+__device__ __forceinline__ PullEdges pull_load_edges(uint32_t j0, uint32_t hi, const int32_t *__restrict__ in_sub,
+                                                     const uint16_t *__restrict__ in_rel) {
+    PullEdges e{-1, 0};
     uint32_t j = j0 + lane();
-    int s = 0, r = 0;
-    bool cand = false;
     if (j < hi) {
-        s = in_sub[j];
-        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
-        if (MASK && cand) r = in_rel[j];
+        e.s = in_sub[j];
+        if (MASK) e.r = in_rel[j];
     }
+    return e;
+}
+
+__device__ __forceinline__ bool pull_test(const PullEdges &e, const uint32_t *__restrict__ act_prev) {
+    return e.s >= 0 && ((act_prev[e.s >> 5] >> (e.s & 31)) & 1u);
+}
+
+template <int W, bool MASK>
+__device__ __forceinline__ int pull_gather(const PullEdges &e, bool cand, const unsigned long long *__restrict__ prev,
+                                           const unsigned long long *__restrict__ allow, unsigned long long &acc) {
     unsigned long long cm = __ballot(cand);
-    int ncand = __popcll(cm);
+    const int ncand = __popcll(cm);
     if constexpr (W == 1) {
         if (cand) {
-            unsigned long long ln = prev[s];
-            if (MASK) ln &= allow[r];
+            unsigned long long ln = prev[e.s];
+            if (MASK) ln &= allow[e.r];
             acc |= ln;
         }
     } else {
-        int lw = lane() & (W - 1);
+        const int lw = lane() & (W - 1);
         while (cm) {
-            int p0 = take_candidates<W>(cm);
-            int p1 = take_candidates<W>(cm);
-            int s0 = __shfl(s, p0 < 0 ? 0 : p0), s1 = __shfl(s, p1 < 0 ? 0 : p1);
-            int r0 = MASK ? __shfl(r, p0 < 0 ? 0 : p0) : 0, r1 = MASK ? __shfl(r, p1 < 0 ? 0 : p1) : 0;
-            unsigned long long l0 = 0, l1 = 0;
-            if (p0 >= 0) l0 = prev[(size_t)s0 * W + lw];
-            if (p1 >= 0) l1 = prev[(size_t)s1 * W + lw];
-            if (MASK) {
-                if (p0 >= 0) l0 &= allow[(size_t)r0 * W + lw];
-                if (p1 >= 0) l1 &= allow[(size_t)r1 * W + lw];
+            int p[4];
+            unsigned long long l[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) p[x] = take_candidates<W>(cm);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int sx = __shfl(e.s, p[x] < 0 ? 0 : p[x]);
+                l[x] = 0;
+                if (p[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
+                if (MASK) {
+                    const int rx = __shfl(e.r, p[x] < 0 ? 0 : p[x]);
+                    if (p[x] >= 0) l[x] &= allow[(size_t)rx * W + lw];
+                }
             }
-            acc |= l0 | l1;
+            acc |= (l[0] | l[1]) | (l[2] | l[3]);
         }
     }
     return ncand;
@@ -395,15 +407,14 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
     uint32_t lo = 0, hi = 0;
     int v = 0;
     unsigned long long vis = 0, need = 0, acc = 0;
-    if (gidx < n) {
+    if (gidx < n) {  // offsets and the visited line are requested together
         v = rows[gidx];
         vis = visited[(size_t)v * W + lw];
-        need = ~vis & live[lw];
-    }
-    if (group_any<W>(need != 0)) {
         lo = off[v];
         hi = off[v + 1];
+        need = ~vis & live[lw];
     }
+    if (!group_any<W>(need != 0)) hi = lo;
     long long n_edges = 0, n_lines = 0;
     for (uint32_t j0 = lo; j0 < hi; j0 += W) {
         uint32_t j = j0 + lw;
@@ -417,23 +428,28 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
         unsigned gm = group_ballot<W>(cand);
         n_edges += min((uint32_t)W, hi - j0);
         n_lines += __popc(gm);
-        while (gm) {
-            int c0 = __ffs((int)gm) - 1;
-            gm &= gm - 1;
-            int c1 = -1;
-            if (gm) {
-                c1 = __ffs((int)gm) - 1;
-                gm &= gm - 1;
+        while (gm) {  // up to four candidate lines in flight
+            int c[4];
+            unsigned long long l[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                c[x] = -1;
+                if (gm) {
+                    c[x] = __ffs((int)gm) - 1;
+                    gm &= gm - 1;
+                }
             }
-            int s0 = __shfl(s, g0 + c0), s1 = __shfl(s, g0 + (c1 < 0 ? c0 : c1));
-            unsigned long long l0 = prev[(size_t)s0 * W + lw], l1 = 0;
-            if (c1 >= 0) l1 = prev[(size_t)s1 * W + lw];
-            if (MASK) {
-                int r0 = __shfl(r, g0 + c0), r1 = __shfl(r, g0 + (c1 < 0 ? c0 : c1));
-                l0 &= allow[(size_t)r0 * W + lw];
-                if (c1 >= 0) l1 &= allow[(size_t)r1 * W + lw];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int sx = __shfl(s, g0 + (c[x] < 0 ? 0 : c[x]));
+                l[x] = 0;
+                if (c[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
+                if (MASK) {
+                    const int rx = __shfl(r, g0 + (c[x] < 0 ? 0 : c[x]));
+                    if (c[x] >= 0) l[x] &= allow[(size_t)rx * W + lw];
+                }
             }
-            acc |= l0 | l1;
+            acc |= (l[0] | l[1]) | (l[2] | l[3]);
         }
         if (!group_any<W>((need & ~acc) != 0)) break;
     }
@@ -482,14 +498,27 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
     const bool work = wave_any(need != 0);
     long long n_edges = 0, n_lines = 0;
     if (work) {
+        // software pipeline: ids of chunk i+2 and frontier bits of chunk i+1 are requested
+        // before the lines of chunk i are gathered
+        PullEdges e0 = pull_load_edges<MASK>(lo, hi, in_sub, in_rel);
+        PullEdges e1 = pull_load_edges<MASK>(lo + 64, hi, in_sub, in_rel);
+        bool c0 = pull_test(e0, act_prev);
         int it = 0;
         for (uint32_t j0 = lo; j0 < hi; j0 += 64, ++it) {
-            n_lines += pull_chunk<W, MASK>(j0, hi, in_sub, in_rel, act_prev, prev, allow, acc);
+            PullEdges e2 = pull_load_edges<MASK>(j0 + 128, hi, in_sub, in_rel);
+            const bool c1 = pull_test(e1, act_prev);
+            n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, acc);
             n_edges += min((uint32_t)64, hi - j0);
-            acc = or_across_groups<W>(acc);
-            if (multi && (it & 3) == 3) acc |= __atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
-            if (!wave_any((need & ~acc) != 0)) break;
+            e0 = e1;
+            c0 = c1;
+            e1 = e2;
+            if ((it & 3) == 3) {  // early exit is rare: test it every fourth chunk
+                acc = or_across_groups<W>(acc);
+                if (multi) acc |= __atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
+                if (!wave_any((need & ~acc) != 0)) break;
+            }
         }
+        acc = or_across_groups<W>(acc);
         unsigned long long nb = acc & need;
         if (wave_any(nb != 0)) {
             if (!multi) {
