@@ -178,11 +178,17 @@ def main():
     dk = kernels[dom]
     alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
+    # calibrated); counters cannot be read from inside this process
     traffic = None
+    expansion_measured = None
     tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_traffic.json")
     if os.path.exists(tfile) and args.scale == 1.0:
-        tj = json.load(open(tfile))
-        traffic = tj.get("kernels", {}).get(dom, {}).get("hbm_bytes_per_launch")
+        tk = json.load(open(tfile)).get("kernels", {})
+        traffic = tk.get(dom, {}).get("hbm_bytes_per_launch")
+        expansion_measured = sum(tk[n]["hbm_read_bytes_per_step"] + tk[n]["hbm_write_bytes_per_step"]
+                                 for n in kernels if n.startswith(expansion_names) and n in tk)
+        expansion_measured += kernels.get("clear_planes", {}).get("items", 0) * 8  # a memset: its own size
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                     algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4),
@@ -215,7 +221,11 @@ def main():
                       "queries_per_s": round(Q / (expansion_ms * 1e-3), 1) if expansion_ms > 0 else None,
                       "algorithmic_GBps": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
                       "hbm_frac": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if expansion_ms else None,
-                      "gteps_logical": round(logical_edges / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None},
+                      "gteps_logical": round(logical_edges / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
+                      "counter_GBps": round(expansion_measured / (expansion_ms * 1e-3) / 1e9, 1)
+                      if expansion_measured and expansion_ms else None,
+                      "counter_hbm_frac": round(expansion_measured / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                      if expansion_measured and expansion_ms else None},
         "roofline": roofline,
         "kernels": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for n, v in kernels.items()},

@@ -59,7 +59,7 @@ typedef struct {
     int32_t max_resident_shards;     /* cache capacity in shards (the paper's n); 0 = no cap     */
     uint64_t hbm_shard_budget_bytes; /* cache capacity in bytes; 0 = no cap                      */
     int32_t hub_min_degree;          /* rows with at least this many edges take the
-                                        block-per-row kernels; 0 = default.  Never changes
+                                        block-per-row kernels; 0 = default (1024).  Never changes
                                         results.                                                 */
     int32_t reserved;
 } logoskg_build_opts;
@@ -202,7 +202,12 @@ logoskg_status logoskg_result_offsets(const logoskg_result *r, int64_t *reached_
  *   pred_edge = the smallest edge id t with o_t = v, r_t allowed for the query
  *   and hop(s_t) = hop(v) - 1 (the active triple of Eq. 5-7 that reaches v
  *   first in edge-id order); -1 for seeds.
- * Asynchronous on `stream`.
+ * Asynchronous on `stream`; the list kernel and the predecessor kernels run on
+ * side streams of the graph and join `stream` before the call returns.  The
+ * first call on a graph that asks for pred_edge with more than 256 queries
+ * allocates a buffer of 4 KiB per object row of more than 32 entries (not
+ * above 8 GiB; freed with the graph).  On a sharded graph pred_edge streams the
+ * object-sorted triples from pinned host memory.
  */
 logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q_begin, int32_t q_end,
                                     int64_t capacity, int32_t *entity, uint8_t *hop,
