@@ -23,7 +23,8 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_bytes: float) -> float:
+def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_bytes: float,
+                      lists_fused: bool = False) -> float:
     """Bytes the named kernel has to move per step for the work units it reported
     (rows / edges / lines / items), per the per-unit figures of the design doc."""
     line = 8 * W
@@ -43,9 +44,12 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
         # visited + levels 1..k streamed once; 4 B entity + 1 B hop written per list entry
         return n * (k + 1) * plane_bytes + items * 5
     if kernel == "pred":
-        # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked
+        # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked;
+        # when the kernel also writes the entity / hop lists: all k+1 levels read, 9 B per entry
+        if lists_fused:
+            return n * (k + 2) * plane_bytes + items * 9 + edges * 4
         return n * 2 * plane_bytes + items * 4 + edges * 4
-    if kernel == "pred_rows":
+    if kernel in ("pred_rows", "pred_mid_rows"):
         return edges * 4
     if kernel == "clear_planes":
         return items * 8
@@ -174,9 +178,10 @@ def main():
     plane_bytes = float(res_epad * W * 8)
     expansion_bytes = sum(algorithmic_bytes(n, v, W, k, False, plane_bytes) for n, v in kernels.items()
                           if n.startswith(expansion_names))
+    lists_fused = "lists" not in kernels  # the predecessor tile kernel wrote the entity / hop lists too
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
-    alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes) / max(dk["launches_per_step"], 1)
+    alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes, lists_fused) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     # calibrated); counters cannot be read from inside this process
@@ -196,7 +201,7 @@ def main():
     # the same figure for every kernel that has a byte model
     exp = {}
     for n, v in kernels.items():
-        b = algorithmic_bytes(n, v, W, k, False, plane_bytes)
+        b = algorithmic_bytes(n, v, W, k, False, plane_bytes, lists_fused)
         if b > 0 and v["ms_per_step"] > 0:
             exp[n] = dict(GBps=round(b / (v["ms_per_step"] * 1e-3) / 1e9, 1),
                           frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -68,7 +68,7 @@ void DevPool::trim() {
 const char *const kKernelNames[KK_NUM] = {
     "clear_planes", "seed_scatter", "frontier_census", "live_queries", "push_tail", "push_seg",
     "update_visited", "pull_tail", "pull_seg", "pull_finish", "count_tiles", "scan_counts",
-    "lists", "pred", "pred_rows", "traversed", "paths", "shard_copy"};
+    "lists", "pred", "pred_rows", "pred_mid_rows", "traversed", "paths", "shard_copy"};
 
 void Profiler::begin(int kind, hipStream_t st) {
     if (!on) return;

@@ -86,7 +86,7 @@ struct RowClasses {             // device work lists over the object rows, split
 // ---------------------------------------------------------------- profiling
 enum KernelKind {
     KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_LIVE, KK_PUSH_TAIL, KK_PUSH_SEG, KK_UPDATE, KK_PULL_TAIL,
-    KK_PULL_SEG, KK_PULL_FINISH, KK_COUNT, KK_SCAN, KK_LISTS, KK_PRED, KK_PRED_HUB, KK_TRAVERSED,
+    KK_PULL_SEG, KK_PULL_FINISH, KK_COUNT, KK_SCAN, KK_LISTS, KK_PRED, KK_PRED_HUB, KK_PRED_MID, KK_TRAVERSED,
     KK_PATHS, KK_SHARD_COPY, KK_NUM
 };
 extern const char *const kKernelNames[KK_NUM];
@@ -303,7 +303,8 @@ struct FillArgs {
     int32_t *entity;
     uint8_t *hop;
     int32_t *pred;
-    unsigned long long *stats_pred, *stats_hub;  // rows / edges / lines counters or NULL
+    unsigned long long *stats_pred, *stats_hub, *stats_mid;  // rows / edges / lines counters or NULL
+    int fuse_lists;  // the 16-word tile kernel also writes the entity and hop lists
 };
 
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);

@@ -342,9 +342,9 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
         }
     }
     if (STATS && v == 0) {
-        if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
-        if (n_edges) atomicAdd(&a.stats_hub[1], (unsigned long long)n_edges);
-        if (n_lines) atomicAdd(&a.stats_hub[2], (unsigned long long)n_lines);
+        if (n_rows) atomicAdd(&a.stats_mid[0], (unsigned long long)n_rows);
+        if (n_edges) atomicAdd(&a.stats_mid[1], (unsigned long long)n_edges);
+        if (n_lines) atomicAdd(&a.stats_mid[2], (unsigned long long)n_lines);
     }
 }
 
@@ -469,15 +469,19 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
 // its object row) goes to the block's staging buffer at the pair's place in the
 // query's run, and afterwards every query's run (up to 256 consecutive list
 // entries) leaves with full-width stores, which keeps the lines that reach HBM
-// whole.  Rows of more than 32 entries belong to the row kernels: when those
-// ran before and left their results in row_pred, the pairs of such an entity are
-// staged as (kCodeRow | entity) and fetched from there; otherwise they stay
-// 0xFFFE = not produced here.  0xFFFF = seed (-1).  When a macro tile has more
-// pairs than the staging buffer holds, its words are processed in several
-// passes.
+// whole.  A code is (hop << 13) | (entity << 5) | position, so k <= 6 (0xFFFF
+// marks a place nothing was staged for).  Hop 0 = seed (-1).  Rows of more than
+// 32 entries belong to the row kernels: the pairs of such an entity are staged
+// with their hop only, and their predecessor is either fetched from row_pred
+// (rows below hub_min, whose kernel ran before on the same stream) or left to
+// the block-per-row kernel, which writes the lists itself.  With a.fuse_lists
+// the run's entity ids and hop numbers are written as well, which replaces the
+// list kernel.  When a macro tile has more pairs than the staging buffer
+// holds, its words are processed in several passes.
 constexpr int kMtCap = 16384;   // staged codes per pass (>= 256 entities x 64 queries)
 constexpr int kMtEids = 3072;   // staged edge ids of the short rows
-constexpr unsigned kCodeSeed = 0xFFFFu, kCodeNone = 0xFFFEu, kCodeRow = 0x4000u;  // kCodeRow | entity: a long row
+constexpr unsigned kCodeNone = 0xFFFFu;
+constexpr int kMtMaxK = 6;       // hop numbers 0..6 fit the code's three bits beside kCodeNone
 
 template <bool MASK, bool STATS>
 __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
@@ -519,11 +523,14 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     const uint32_t deg = hi - lo;
     const bool shortrow = deg > 0 && deg <= (uint32_t)kTailMaxDegree;
     u.stage[vi][lw] = visw;
-    const bool longrow = deg > (uint32_t)kTailMaxDegree && a.row_pred != nullptr;
+    const bool longrow = deg > (uint32_t)kTailMaxDegree;
     if (lw == 0) {
         roff[vi] = shortrow ? (uint16_t)deg : (uint16_t)0;
         in_lo[vi] = lo;
-        long_li[vi] = longrow ? (int)(a.long_index[ev] - a.row_base) : 0;
+        // -1: short row (edge ids staged here), >= 0: line of row_pred, -2: predecessor written elsewhere
+        int li = -1;
+        if (longrow) li = (a.row_pred && deg < (uint32_t)a.hub_min) ? (int)(a.long_index[ev] - a.row_base) : -2;
+        long_li[vi] = li;
     }
     __syncthreads();
     {   // wave = (tile, word): lane qq gets the mask of tile entities query qq reached
@@ -586,8 +593,12 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
                 u.code[pos0[tt][ql] + __popcll(mT[tt][ql] & below) - goff] = (uint16_t)code;
             }
         };
-        if (mine && seedw) emit(seedw, kCodeSeed);
-        if (mine && longrow && (visw & ~seedw)) emit(visw & ~seedw, kCodeRow | (unsigned)vi);
+        if (mine && seedw) emit(seedw, (unsigned)vi << 5);
+        if (mine && longrow && (visw & ~seedw))
+            for (int h = 1; h <= a.k; ++h) {
+                unsigned long long lv = a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
+                if (lv) emit(lv, ((unsigned)h << 13) | ((unsigned)vi << 5));
+            }
         if (shortrow)
             for (int h = 1; h <= a.k; ++h) {
                 unsigned long long rem = mine ? a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w : 0ull;
@@ -625,8 +636,8 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
                         }
                         unsigned long long hit0 = l0 & rem, hit1 = l1 & rem & ~l0;
                         rem &= ~(l0 | l1);
-                        if (hit0) emit(hit0, ((unsigned)vi << 5) | (j0 + d0 - lo));
-                        if (hit1) emit(hit1, ((unsigned)vi << 5) | (j0 + d1 - lo));
+                        if (hit0) emit(hit0, ((unsigned)h << 13) | ((unsigned)vi << 5) | (j0 + d0 - lo));
+                        if (hit1) emit(hit1, ((unsigned)h << 13) | ((unsigned)vi << 5) | (j0 + d1 - lo));
                         if (!group_any<G>(rem != 0)) break;
                     }
                     if (!group_any<G>(rem != 0)) break;
@@ -639,12 +650,20 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
             for (uint32_t i = v; i < n; i += 64) {
                 const unsigned code = u.code[src + i];
                 if (code == kCodeNone) continue;
+                const int e = (code >> 5) & 255, jp = code & 31, hopv = code >> 13, li = long_li[e];
+                if (a.fuse_lists) {
+                    a.entity[dst + i] = (int32_t)(tile0 * 64 + e);
+                    if (a.hop) a.hop[dst + i] = (uint8_t)hopv;
+                }
                 int val = -1;
-                if (code & kCodeRow) {
-                    if (code != kCodeSeed) val = a.row_pred[(size_t)long_li[code & 255] * Qp + slab * 256 + ql];
-                } else {
-                    const int e = code >> 5, jp = code & 31, ro = roff[e];
-                    val = ro + kTailMaxDegree <= kMtEids ? eid_tab[ro + jp] : a.in_eid[in_lo[e] + jp];
+                if (hopv != 0) {
+                    if (li == -2) continue;
+                    if (li >= 0) {
+                        val = a.row_pred[(size_t)li * Qp + slab * 256 + ql];
+                    } else {
+                        const int ro = roff[e];
+                        val = ro + kTailMaxDegree <= kMtEids ? eid_tab[ro + jp] : a.in_eid[in_lo[e] + jp];
+                    }
                 }
                 a.pred[dst + i] = val;
             }
@@ -844,22 +863,31 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
     else k_lists<W, 8><<<grid, block, 0, st>>>(a);
 }
 
+// True when the 16-word tile kernel can serve this launch (it then can also write the entity and
+// hop lists, see FillArgs::fuse_lists).
+bool pred_uses_staged_kernel(const FillArgs &a, int W) {
+    return W == 16 && a.k <= kMtMaxK && a.tile_begin % kPredTiles == 0;
+}
+
 template <int W, bool MASK, bool STATS>
 static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_rows, long long n_other_rows,
-                            hipStream_t st_tiles, hipStream_t st) {
+                            hipStream_t st_tiles, hipStream_t st_hub) {
     FillArgs a = a0;
-    const bool mt = W == 16 && a.tile_begin % kPredTiles == 0;
-    if (!mt) a.row_pred = nullptr;
-    if (n_hub_rows + n_other_rows > 0) {
-        ProfScope ps(prof, KK_PRED_HUB, st);
+    const bool mt = pred_uses_staged_kernel(a, W);
+    if (!mt) {
+        a.row_pred = nullptr;
+        a.fuse_lists = 0;
+    }
+    if (n_hub_rows > 0) {  // writes the lists itself: independent of the other two kernels
+        ProfScope ps(prof, KK_PRED_HUB, st_hub);
+        k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st_hub>>>(a, 0);
+    }
+    if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
+        hipStream_t st = a.row_pred ? st_tiles : st_hub;
+        ProfScope ps(prof, KK_PRED_MID, st);
         const dim3 gw((unsigned)((n_other_rows + 3) / 4));
-        if (a.row_pred) {
-            if (n_hub_rows > 0) k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
-            if (n_other_rows > 0) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
-        } else {
-            if (n_hub_rows > 0) k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st>>>(a, 0);
-            if (n_other_rows > 0) k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
-        }
+        if (a.row_pred) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+        else k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
     }
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st_tiles);
@@ -899,15 +927,15 @@ void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st) {
     }
 }
 
-// Without a.row_pred the tile kernel and the row kernels write disjoint list entries and may
-// run on different streams; with it the tile kernel reads what the row kernels wrote and both
-// streams must be the same.
+// The block-per-row kernel of the hub rows goes to st_hub and may overlap the rest; the kernel of
+// the other long rows goes to st_tiles ahead of the tile kernel when its results pass through
+// a.row_pred, to st_hub otherwise.
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
-                 hipStream_t st_tiles, hipStream_t st_rows) {
+                 hipStream_t st_tiles, hipStream_t st_hub) {
     switch (W) {
-        case 1: launch_pred_w<1>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
-        case 4: launch_pred_w<4>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
-        default: launch_pred_w<16>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_rows); break;
+        case 1: launch_pred_w<1>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_hub); break;
+        case 4: launch_pred_w<4>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_hub); break;
+        default: launch_pred_w<16>(prof, a, n_hub_rows, n_other_rows, mask, st_tiles, st_hub); break;
     }
 }
 
@@ -948,7 +976,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.reached_off = r->d_reached_off;
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.rows = g->in_rows.longrows;
-    a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr;
+    a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
     if (pred && W == 16) {
         LKG_TRY(prepare_row_pred(g, st));
         a.long_index = g->long_index;
@@ -958,38 +986,46 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     const bool counting = g->prof.counters;
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
+    a.stats_mid = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_MID : nullptr;
     if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
     // lists, the per-tile predecessor kernel and the per-row predecessor kernels are independent:
     // on a resident graph they run on three streams and join on the caller's
     const char *serial_env = getenv("LOGOSKG_SERIAL_FETCH");  // measurement aid: one kernel at a time
     const bool serial = serial_env && serial_env[0] == '1';
+    // With predecessors on 16-word planes the tile kernel writes all three lists; otherwise the
+    // list kernel runs beside the predecessor kernels.  The block-per-row kernel of the hub rows is
+    // independent of the rest and overlaps it on a side stream of the graph.
+    a.fuse_lists = pred && pred_uses_staged_kernel(a, W);
+    const long long n_hub = g->in_rows.n_hub, n_mid = g->in_rows.n_long - g->in_rows.n_hub;
     if (pred && g->num_shards <= 1 && !serial) {
-        const int n_side = a.row_pred ? 1 : 2;  // with row_pred the row kernels precede the tile kernel
         LKG_HIP(hipEventRecord(g->ev_fork, st));
-        for (int i = 0; i < n_side; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
-        launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, g->side[0],
-                    g->side[n_side - 1]);
-        launch_lists(g->prof, a, W, st);
-        for (int i = 0; i < n_side; ++i) {
+        for (int i = 0; i < 2; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
+        if (a.fuse_lists) {
+            launch_pred(g->prof, a, W, n_hub, n_mid, r->has_mask, st, g->side[0]);
+        } else {
+            launch_pred(g->prof, a, W, n_hub, n_mid, r->has_mask, g->side[0], g->side[1]);
+            launch_lists(g->prof, a, W, st);
+        }
+        for (int i = 0; i < 2; ++i) {
             LKG_HIP(hipEventRecord(g->ev_join[i], g->side[i]));
             LKG_HIP(hipStreamWaitEvent(st, g->ev_join[i], 0));
         }
     } else {
-        launch_lists(g->prof, a, W, st);
+        if (!a.fuse_lists) launch_lists(g->prof, a, W, st);
         if (pred) {
             if (g->num_shards > 1) LKG_TRY(sharded_pred(g, &a, W, r->has_mask, st));
-            else launch_pred(g->prof, a, W, g->in_rows.n_hub, g->in_rows.n_long - g->in_rows.n_hub, r->has_mask, st, st);
+            else launch_pred(g->prof, a, W, n_hub, n_mid, r->has_mask, st, st);
         }
     }
     LKG_HIP(hipGetLastError());
     if (g->prof.on) {
-        g->prof.acc[KK_LISTS].units[3] += need;
+        if (!a.fuse_lists) g->prof.acc[KK_LISTS].units[3] += need;
         if (pred) g->prof.acc[KK_PRED].units[3] += need;
     }
     if (counting) {  // measurement mode only: wait for the counters
         LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         LKG_HIP(hipStreamSynchronize(st));
-        for (int kind : {KK_PRED, KK_PRED_HUB})
+        for (int kind : {KK_PRED, KK_PRED_HUB, KK_PRED_MID})
             for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)g->h_ctr[C_STATS + 4 * kind + u];
     }
     return LOGOSKG_OK;
