@@ -144,6 +144,30 @@ def test_fetch_subranges_and_optional_outputs():
     g.close()
 
 
+def test_sixteen_word_planes_deep_hops_serial_fetch_and_no_hop_output(monkeypatch):
+    # more than 256 queries: k <= 6 takes the staged predecessor kernel that also writes the
+    # entity / hop lists, deeper searches take the tile kernel with scattered stores plus the
+    # list kernel; both must agree with the oracle, also when a fetch is issued on one stream
+    m = lkg()
+    w = kggen.config2(0.004, num_queries=300)
+    for k in (6, 7, 9):
+        want = run_oracle(w, k=k)
+        got, _ = run_gpu(w, "auto", hub_min_degree=100, k=k)
+        assert_same(got, want, f"k={k}")
+    monkeypatch.setenv("LOGOSKG_SERIAL_FETCH", "1")
+    want = run_oracle(w)
+    got, _ = run_gpu(w, "auto", hub_min_degree=100)
+    assert_same(got, want, "serial fetch")
+    monkeypatch.delenv("LOGOSKG_SERIAL_FETCH")
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=100)
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    ent, hop, pred = res.fetch(want_hop=False)
+    assert hop is None
+    assert np.array_equal(ent.cpu().numpy(), want[1]) and np.array_equal(pred.cpu().numpy(), want[3])
+    res.close()
+    g.close()
+
+
 def test_two_runs_are_bit_identical():
     w = kggen.config3(0.01, k=3)
     a, _ = run_gpu(w, "auto", hub_min_degree=100)
