@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-queries", type=int, default=32)
+    ap.add_argument("--cpu-queries", type=int, default=384)
     ap.add_argument("--serial-fetch", action="store_true",
                     help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
     ap.add_argument("--pmc-calibration", action="store_true",

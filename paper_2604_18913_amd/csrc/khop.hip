@@ -336,10 +336,16 @@ __device__ __forceinline__ bool pull_test(const PullEdges &e, const uint32_t *__
     return e.s >= 0 && ((act_prev[e.s >> 5] >> (e.s & 31)) & 1u);
 }
 
+// Gather stage.  The candidates' subject ids are compacted into a per-wavefront
+// LDS queue (position = number of candidates in lower lanes); group g of round r
+// then reads entry r * (64/W) + g, so picking a candidate costs one LDS read
+// instead of a search in the ballot mask and a cross-lane move.  Four rounds of
+// loads are in flight; only the last, partly filled batch is predicated.
 template <int W, bool MASK>
 __device__ __forceinline__ int pull_gather(const PullEdges &e, bool cand, const unsigned long long *__restrict__ prev,
-                                           const unsigned long long *__restrict__ allow, unsigned long long &acc) {
-    unsigned long long cm = __ballot(cand);
+                                           const unsigned long long *__restrict__ allow, unsigned long long &acc,
+                                           int *queue_s, uint16_t *queue_r) {
+    const unsigned long long cm = __ballot(cand);
     const int ncand = __popcll(cm);
     if constexpr (W == 1) {
         if (cand) {
@@ -348,24 +354,40 @@ __device__ __forceinline__ int pull_gather(const PullEdges &e, bool cand, const 
             acc |= ln;
         }
     } else {
-        const int lw = lane() & (W - 1);
-        while (cm) {
-            int p[4];
+        constexpr int GPW = 64 / W, B = 4 * GPW;  // candidates per batch
+        if (ncand == 0) return 0;
+        if (cand) {
+            const int pos = __popcll(cm & ((1ull << lane()) - 1ull));
+            queue_s[pos] = e.s;
+            if (MASK) queue_r[pos] = (uint16_t)e.r;
+        }
+        __builtin_amdgcn_wave_barrier();
+        const int lw = lane() & (W - 1), g = lane() / W;
+        int base = 0;
+        for (; base + B <= ncand; base += B) {  // full batches
             unsigned long long l[4];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) p[x] = take_candidates<W>(cm);
+            for (int x = 0; x < 4; ++x) {
+                const int i = base + x * GPW + g;
+                l[x] = prev[(size_t)queue_s[i] * W + lw];
+                if (MASK) l[x] &= allow[(size_t)queue_r[i] * W + lw];
+            }
+            acc |= (l[0] | l[1]) | (l[2] | l[3]);
+        }
+        if (base < ncand) {
+            unsigned long long l[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const int sx = __shfl(e.s, p[x] < 0 ? 0 : p[x]);
+                const int i = base + x * GPW + g;
                 l[x] = 0;
-                if (p[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
-                if (MASK) {
-                    const int rx = __shfl(e.r, p[x] < 0 ? 0 : p[x]);
-                    if (p[x] >= 0) l[x] &= allow[(size_t)rx * W + lw];
+                if (i < ncand) {
+                    l[x] = prev[(size_t)queue_s[i] * W + lw];
+                    if (MASK) l[x] &= allow[(size_t)queue_r[i] * W + lw];
                 }
             }
             acc |= (l[0] | l[1]) | (l[2] | l[3]);
         }
+        __builtin_amdgcn_wave_barrier();  // the queue is rewritten by the next chunk
     }
     return ncand;
 }
@@ -477,6 +499,8 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
            unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
            unsigned long long *stats) {
+    __shared__ int queue_s[4][64];
+    __shared__ uint16_t queue_r[4][64];
     long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const bool have = item < n;  // wave-uniform
     const int lw = lane() & (W - 1);
@@ -507,7 +531,7 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
         for (uint32_t j0 = lo; j0 < hi; j0 += 64, ++it) {
             PullEdges e2 = pull_load_edges<MASK>(j0 + 128, hi, in_sub, in_rel);
             const bool c1 = pull_test(e1, act_prev);
-            n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, acc);
+            n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, acc, queue_s[threadIdx.x >> 6], queue_r[threadIdx.x >> 6]);
             n_edges += min((uint32_t)64, hi - j0);
             e0 = e1;
             c0 = c1;
