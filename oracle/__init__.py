@@ -44,6 +44,10 @@ def _load():
         lib.oracle_paths.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, P, ctypes.c_int32,
                                      P, P, ctypes.c_int32, P, ctypes.c_int32, ctypes.c_int64,
                                      P, P, ctypes.c_int32, P, P]
+        lib.oracle_walk_levels.restype = ctypes.c_int
+        lib.oracle_walk_levels.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, P, ctypes.c_int32,
+                                           P, P, ctypes.c_int32, P, ctypes.c_int32, ctypes.c_int32,
+                                           P, ctypes.POINTER(P)]
         lib.oracle_free.argtypes = [P]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -134,3 +138,39 @@ def paths(num_entities: int, subj, rel, obj, seed_off, seeds, k: int, pair_query
     if rc != 0:
         raise RuntimeError("oracle_paths failed")
     return count, edges
+
+
+def walk_levels(num_entities: int, subj, rel, obj, seed_off, seeds, k: int,
+                rel_mask: Optional[np.ndarray] = None, nthreads: int = 0):
+    """Walk-exact levels: Eq. 4 iterated without a visited set.
+
+    Returns ``(level_off int64[(k+1)*Q + 1], entity int32[N])``: the entities that
+    end a walk of exactly ``h`` allowed triples from a seed of query ``q`` are
+    ``entity[level_off[h*Q+q] : level_off[h*Q+q+1]]``, ascending.
+    """
+    lib = _load()
+    subj, p_s = _c(subj, np.int32)
+    rel, p_r = _c(rel, np.int32)
+    obj, p_o = _c(obj, np.int32)
+    seed_off, p_so = _c(seed_off, np.int64)
+    seeds, p_sd = _c(seeds, np.int32)
+    Q = seed_off.shape[0] - 1
+    if rel_mask is not None:
+        rel_mask, p_m = _c(rel_mask, np.uint64)
+        rw = rel_mask.shape[1]
+    else:
+        p_m, rw = None, 0
+    level_off = np.zeros((k + 1) * Q + 1, dtype=np.int64)
+    ent = ctypes.c_void_p()
+    rc = lib.oracle_walk_levels(subj.shape[0], num_entities, p_s, p_r, p_o, Q, p_so, p_sd, k,
+                                p_m, rw, nthreads, level_off.ctypes.data_as(ctypes.c_void_p),
+                                ctypes.byref(ent))
+    if rc != 0:
+        raise RuntimeError("oracle_walk_levels failed (bad arguments or out of memory)")
+    n = int(level_off[-1])
+    if n == 0:
+        out = np.zeros(0, dtype=np.int32)
+    else:
+        out = np.ctypeslib.as_array(ctypes.cast(ent, ctypes.POINTER(ctypes.c_int32)), shape=(n,)).copy()
+    lib.oracle_free(ent)
+    return level_off, out

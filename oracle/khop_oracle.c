@@ -35,6 +35,14 @@
  * They are ordered lexicographically by (t_d, t_{d-1}, .., t_1) and the first
  * max_paths are returned, each written seed -> target.
  *
+ * Walk-exact levels (oracle_walk_levels): the iteration of Eq. 4 taken
+ * literally, without a visited set: level h holds the entities that end a walk
+ * of exactly h allowed triples from a seed, q^(h) = q^(h-1) . SUB . OBJ with
+ * the whitelist applied to the active triples.  An entity may appear in several
+ * levels.  Pins: dense boolean matrix powers, brute-force walk enumeration,
+ * closed forms on cycles / paths / self loops, and against oracle_khop itself
+ * (union over h = reached set, first h = hop).
+ *
  * Parity pins (see tests/test_oracle_pins.py): boolean products of dense
  * SUB / REL / OBJ matrices, brute-force walk enumeration, closed forms on
  * paths / cycles / stars / trees, networkx and scipy shortest-path lengths,
@@ -341,4 +349,87 @@ int oracle_paths(int64_t T, int32_t E, const int32_t *subj, const int32_t *rel,
     state_free(&st);
     free(sfirst); free(sids); free(ofirst); free(oids);
     return 0;
+}
+
+/*
+ * Walk-exact levels, Eq. 4 iterated without a visited set.
+ *
+ *   level_off : int64[(k+1) * Q + 1]; the list of level h of query q is
+ *               entity[level_off[h * Q + q] .. level_off[h * Q + q + 1]),
+ *               ascending entity id.  Level 0 = the distinct seeds.
+ *   entity    : malloc'ed by the callee (oracle_free).
+ */
+int oracle_walk_levels(int64_t T, int32_t E, const int32_t *subj, const int32_t *rel,
+                       const int32_t *obj, int32_t Q, const int64_t *seed_off,
+                       const int32_t *seeds, int32_t k, const uint64_t *rel_mask,
+                       int32_t rel_words, int32_t nthreads, int64_t *level_off,
+                       int32_t **entity)
+{
+    if (k < 0 || k > 254 || E <= 0 || T < 0 || Q < 0) return -1;
+    for (int64_t i = 0; i < seed_off[Q]; ++i)
+        if (seeds[i] < 0 || seeds[i] >= E) return -1;
+    int64_t *first = NULL;
+    int32_t *ids = NULL;
+    if (build_index(subj, T, E, &first, &ids) != 0) return -1;
+    const int64_t cells = (int64_t)(k + 1) * Q;
+    int32_t **lists = (int32_t **)calloc((size_t)cells + 1, sizeof(*lists));
+    int64_t *counts = (int64_t *)calloc((size_t)cells + 1, sizeof(int64_t));
+    int failed = !lists || !counts;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#endif
+#pragma omp parallel
+    {
+        /* stamp[v] == mark  <=>  v is in the level being built */
+        int32_t *stamp = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+        int32_t *cur = (int32_t *)malloc((size_t)E * sizeof(int32_t));
+        int32_t *nxt = (int32_t *)malloc((size_t)E * sizeof(int32_t));
+        int32_t mark = 0;
+        int ok = stamp && cur && nxt && !failed;
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t q = 0; q < Q; ++q) {
+            if (!ok) { failed = 1; continue; }
+            const uint64_t *mask = rel_mask ? rel_mask + (size_t)q * rel_words : NULL;
+            int64_t n_cur = 0;
+            ++mark;
+            for (int64_t i = seed_off[q]; i < seed_off[q + 1]; ++i)
+                if (stamp[seeds[i]] != mark) { stamp[seeds[i]] = mark; cur[n_cur++] = seeds[i]; }
+            for (int h = 0; h <= k; ++h) {
+                qsort(cur, (size_t)n_cur, sizeof(int32_t), cmp_i32);
+                int32_t *keep = (int32_t *)malloc((size_t)(n_cur > 0 ? n_cur : 1) * sizeof(int32_t));
+                if (!keep) { failed = 1; break; }
+                memcpy(keep, cur, (size_t)n_cur * sizeof(int32_t));
+                lists[(int64_t)h * Q + q] = keep;
+                counts[(int64_t)h * Q + q] = n_cur;
+                if (h == k) break;
+                /* next level: objects of the allowed triples whose subject is in this level */
+                int64_t n_nxt = 0;
+                ++mark;
+                for (int64_t i = 0; i < n_cur; ++i) {
+                    int32_t s = cur[i];
+                    for (int64_t p = first[s]; p < first[s + 1]; ++p) {
+                        int32_t t = ids[p];
+                        if (!relation_allowed(mask, rel[t])) continue;
+                        int32_t v = obj[t];
+                        if (stamp[v] != mark) { stamp[v] = mark; nxt[n_nxt++] = v; }
+                    }
+                }
+                int32_t *swap = cur; cur = nxt; nxt = swap;
+                n_cur = n_nxt;
+            }
+            if (mark > 0x7ffffff0) { memset(stamp, 0, (size_t)E * sizeof(int32_t)); mark = 0; }
+        }
+        free(stamp); free(cur); free(nxt);
+    }
+    level_off[0] = 0;
+    for (int64_t c = 0; c < cells; ++c) level_off[c + 1] = level_off[c] + counts[c];
+    int64_t N = level_off[cells];
+    *entity = (int32_t *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int32_t));
+    if (!*entity) failed = 1;
+    for (int64_t c = 0; c < cells; ++c) {
+        if (!failed && lists[c]) memcpy(*entity + level_off[c], lists[c], (size_t)counts[c] * sizeof(int32_t));
+        free(lists[c]);
+    }
+    free(lists); free(counts); free(first); free(ids);
+    return failed ? -1 : 0;
 }

@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 import test_oracle_pins as pins
+import test_oracle_walk_pins as wpins
 
 MUTATIONS = {
     "tie_break_dropped": ("} else if (st->hop[v] == h && t < st->pred[v]) {",
@@ -28,6 +29,13 @@ MUTATIONS = {
     "paths_forward_order": ("row[i] = c->stack[c->d - 1 - i];", "row[i] = c->stack[i];"),
     "paths_wrong_level": ("if (c->hop[c->subj[t]] != level - 1) continue;", "if (c->hop[c->subj[t]] != level) continue;"),
     "paths_ignore_mask": ("        if (!relation_allowed(c->mask, c->rel[t])) continue;\n", ""),
+    # walk-exact levels
+    "walk_keeps_a_visited_set": ("                int64_t n_nxt = 0;\n                ++mark;", "                int64_t n_nxt = 0;"),
+    "walk_mask_dropped": ("                        if (!relation_allowed(mask, rel[t])) continue;\n                        int32_t v = obj[t];",
+                          "                        int32_t v = obj[t];"),
+    "walk_sets_the_subject": ("                        int32_t v = obj[t];\n                        if (stamp[v] != mark)",
+                              "                        int32_t v = subj[t];\n                        if (stamp[v] != mark)"),
+    "walk_last_level_missing": ("                if (h == k) break;", "                if (h >= k - 1) break;"),
 }
 
 PIN_CALLS = [
@@ -37,6 +45,8 @@ PIN_CALLS = [
     lambda: pins.test_tie_break_smallest_edge_id_and_mask_selects_other_edge(),
     lambda: pins.test_directed_cycle_never_lowers_the_seed(0),
     lambda: pins.test_first_path_is_the_pred_chain(),
+    lambda: [wpins.test_against_boolean_matrix_powers(s, m) for s in range(3) for m in (False, True)],
+    lambda: wpins.test_cycle_path_self_loop_and_bipartite(),
 ]
 
 
@@ -52,7 +62,7 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
                            str(mutated)])
     good = oracle._load()
     lib = ctypes.CDLL(lib_path)
-    for fn in ("oracle_khop", "oracle_paths", "oracle_free", "oracle_num_threads"):
+    for fn in ("oracle_khop", "oracle_paths", "oracle_walk_levels", "oracle_free", "oracle_num_threads"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
