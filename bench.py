@@ -13,6 +13,7 @@ Prints one JSON line.
 from __future__ import annotations
 
 import argparse
+import functools
 import json
 import os
 import sys
@@ -24,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 
 
 def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_bytes: float,
-                      lists_fused: bool = False) -> float:
+                      lists_fused: bool = False, level_lists: bool = False) -> float:
     """Bytes the named kernel has to move per step for the work units it reported
     (rows / edges / lines / items), per the per-unit figures of the design doc."""
     line = 8 * W
@@ -42,6 +43,9 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
         return n * plane_bytes / (64.0 * W)  # the 1-bit-per-entity active bitmap
     if kernel == "lists":
         # visited + levels 1..k streamed once; 4 B entity + 1 B hop written per list entry
+        # (the list of one level: that level's plane, 4 B per entry)
+        if level_lists:
+            return n * plane_bytes + items * 4
         return n * (k + 1) * plane_bytes + items * 5
     if kernel == "pred":
         # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked;
@@ -68,6 +72,9 @@ def main():
     ap.add_argument("--cpu-queries", type=int, default=384)
     ap.add_argument("--serial-fetch", action="store_true",
                     help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
+    ap.add_argument("--mode", choices=["minhop", "walk"], default="minhop",
+                    help="minhop (default): the headline path; walk: Eq. 4 iterated without the visited set "
+                         "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch a plain 1 GiB device copy and a 1 GiB fill, so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
@@ -105,22 +112,28 @@ def main():
         del src, dst
 
     # sizes are deterministic: one untimed call sizes the output buffers
-    res = g.khop(seed_off, seeds, k)
+    walk = args.mode == "walk"
+    res = g.khop(seed_off, seeds, k, walk_exact=walk)
     off = res.offsets()
-    total = int(off[-1])
+    total = int(res.level(k, 0, 0)[0][-1]) if walk else int(off[-1])
     W = res.words_per_entity
     res_epad = res.padded_entities
-    ent = torch.empty(total, dtype=torch.int32, device=dev)
-    hop = torch.empty(total, dtype=torch.uint8, device=dev)
-    pred = torch.empty(total, dtype=torch.int32, device=dev)
+    if not walk:
+        ent = torch.empty(total, dtype=torch.int32, device=dev)
+        hop = torch.empty(total, dtype=torch.uint8, device=dev)
+        pred = torch.empty(total, dtype=torch.int32, device=dev)
     trav = res.traversed().cpu().numpy()
     hop_stats = res.hop_stats()
     res.close()
     logical_edges = int(trav.sum())
 
     def step():
-        r = g.khop(seed_off, seeds, k)
-        r.fetch(out=(ent, hop, pred))
+        if walk:
+            r = g.khop(seed_off, seeds, k, walk_exact=True)
+            r.level(k)
+        else:
+            r = g.khop(seed_off, seeds, k)
+            r.fetch(out=(ent, hop, pred))
         return r
 
     def run_steps(n):
@@ -160,6 +173,7 @@ def main():
     if not args.serial_fetch:
         os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
 
+    ab = functools.partial(algorithmic_bytes, level_lists=walk)
     ms_per_step = dt / args.steps * 1e3
     qps = Q / (dt / args.steps)
     kernels = {}
@@ -176,12 +190,12 @@ def main():
     expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")
     expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith(expansion_names))
     plane_bytes = float(res_epad * W * 8)
-    expansion_bytes = sum(algorithmic_bytes(n, v, W, k, False, plane_bytes) for n, v in kernels.items()
+    expansion_bytes = sum(ab(n, v, W, k, False, plane_bytes) for n, v in kernels.items()
                           if n.startswith(expansion_names))
     lists_fused = "lists" not in kernels  # the predecessor tile kernel wrote the entity / hop lists too
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
-    alg = algorithmic_bytes(dom, dk, W, k, False, plane_bytes, lists_fused) / max(dk["launches_per_step"], 1)
+    alg = ab(dom, dk, W, k, False, plane_bytes, lists_fused) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     # calibrated); counters cannot be read from inside this process
@@ -201,14 +215,17 @@ def main():
     # the same figure for every kernel that has a byte model
     exp = {}
     for n, v in kernels.items():
-        b = algorithmic_bytes(n, v, W, k, False, plane_bytes, lists_fused)
+        b = ab(n, v, W, k, False, plane_bytes, lists_fused)
         if b > 0 and v["ms_per_step"] > 0:
             exp[n] = dict(GBps=round(b / (v["ms_per_step"] * 1e-3) / 1e9, 1),
                           frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           ms_per_step=round(v["ms_per_step"], 4), bytes_per_step=int(b))
 
     out = {
-        "metric": "queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)",
+        "metric": ("queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)"
+                   if not walk else
+                   "queries/s, walk-exact 3-hop batch-1024 on 30M-edge synthetic KG (khop without the visited set + "
+                   "the level-3 list of every query)"),
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
@@ -216,7 +233,7 @@ def main():
                                "1,024 queries x 1-5 seeds, k=3, no relation mask" +
                                ("" if args.scale == 1.0 else f" (scaled by {args.scale})"),
                    "num_entities": w.num_entities, "num_triples": w.num_triples, "num_queries": Q, "k": k,
-                   "words_per_entity": W, "reached_pairs": total,
+                   "mode": args.mode, "words_per_entity": W, "reached_pairs": total,
                    "directions": [h["direction"] for h in hop_stats]},
         "gteps_logical": round(logical_edges / (dt / args.steps) / 1e9, 2),
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
@@ -245,12 +262,21 @@ def main():
         so = w.seed_off[: nq + 1]
         sd = w.seeds[: so[-1]]
         t0 = time.perf_counter()
-        o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
+        if walk:
+            o_off, o_ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
+        else:
+            o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
         t_cpu = time.perf_counter() - t0
-        got = g.khop(seed_off, seeds, k)
-        e2, h2, p2 = got.fetch(0, nq)
-        same = (np.array_equal(off[: nq + 1], o[0]) and np.array_equal(e2.cpu().numpy(), o[1])
-                and np.array_equal(h2.cpu().numpy(), o[2]) and np.array_equal(p2.cpu().numpy(), o[3]))
+        got = g.khop(seed_off, seeds, k, walk_exact=walk)
+        if walk:
+            l_off, l_ent = got.level(k, 0, nq)
+            a = o_off[k * nq:(k + 1) * nq + 1]
+            same = (np.array_equal(l_off[: nq + 1], a - a[0]) and
+                    np.array_equal(l_ent.cpu().numpy(), o_ent[a[0]:a[-1]]))
+        else:
+            e2, h2, p2 = got.fetch(0, nq)
+            same = (np.array_equal(off[: nq + 1], o[0]) and np.array_equal(e2.cpu().numpy(), o[1])
+                    and np.array_equal(h2.cpu().numpy(), o[2]) and np.array_equal(p2.cpu().numpy(), o[3]))
         got.close()
         out["cpu_baseline"] = {"value": round(nq / t_cpu, 2), "unit": "queries/s", "cores": oracle.num_threads(),
                                "kind": "oracle",

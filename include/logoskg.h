@@ -135,6 +135,12 @@ logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_t *shard_of
 #define LOGOSKG_DIR_PULL 2u       /* always gather over the object rows (resident graphs only)  */
 #define LOGOSKG_DIR_MASK 3u
 #define LOGOSKG_NO_COUNTS 4u      /* skip the per-query reached counts (planes only)            */
+#define LOGOSKG_WALK_EXACT 8u     /* Eq. 4 iterated literally, without the visited set: level h
+                                     = the entities that end a walk of exactly h allowed triples
+                                     (an entity may be in several levels).  The reached set and
+                                     its offsets are unchanged; hop, pred_edge and paths are not
+                                     defined for such a result (LOGOSKG_EINVAL): read the levels
+                                     with logoskg_result_level_offsets / _level_fetch.          */
 
 typedef struct {
     uint32_t struct_size;     /* sizeof(logoskg_query_batch)                                  */
@@ -212,6 +218,21 @@ logoskg_status logoskg_result_offsets(const logoskg_result *r, int64_t *reached_
 logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q_begin, int32_t q_end,
                                     int64_t capacity, int32_t *entity, uint8_t *hop,
                                     int32_t *pred_edge, void *stream);
+
+/*
+ * Level h of every query, h in [0, k] (Sec. 3.3, the support of q^(h)): with the
+ * default search the entities whose minimum hop is exactly h ("at a specific
+ * hop"), with LOGOSKG_WALK_EXACT the ends of the walks of exactly h triples.
+ * logoskg_result_level_offsets counts the level (level_off: host int64[Q+1],
+ * synchronises `stream`); logoskg_result_level_fetch then writes the lists of
+ * the queries [q_begin, q_end) of that same level, query-major and ascending in
+ * entity id, to the device buffer `entity` (capacity checked: LOGOSKG_ERANGE),
+ * asynchronously on `stream`.  One level at a time per result.
+ */
+logoskg_status logoskg_result_level_offsets(logoskg_result *r, int32_t h, int64_t *level_off,
+                                            void *stream);
+logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t h, int32_t q_begin, int32_t q_end,
+                                          int64_t capacity, int32_t *entity, void *stream);
 
 /*
  * traversed[q][h-1] = number of triples whose subject has hop h-1 for query q

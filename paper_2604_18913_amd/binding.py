@@ -18,6 +18,7 @@ _lib = None
 
 DIRECTIONS = {"auto": 0, "push": 1, "pull": 2}
 NO_COUNTS = 4
+WALK_EXACT = 8
 STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EDEVICE", 4: "ERANGE", 5: "EINTERNAL"}
 
 
@@ -106,6 +107,10 @@ def _load():
     lib.logoskg_result_offsets.argtypes = [P, P]
     lib.logoskg_result_fetch.restype = ctypes.c_int
     lib.logoskg_result_fetch.argtypes = [P, I32, I32, I64, P, P, P, P]
+    lib.logoskg_result_level_offsets.restype = ctypes.c_int
+    lib.logoskg_result_level_offsets.argtypes = [P, I32, P, P]
+    lib.logoskg_result_level_fetch.restype = ctypes.c_int
+    lib.logoskg_result_level_fetch.argtypes = [P, I32, I32, I32, I64, P, P]
     lib.logoskg_result_traversed.restype = ctypes.c_int
     lib.logoskg_result_traversed.argtypes = [P, P, P]
     lib.logoskg_result_free.restype = None
@@ -205,6 +210,21 @@ class Result:
             pred.data_ptr() if pred is not None else None, _stream_handle(stream)))
         return entity[:n], (hop[:n] if hop is not None else None), (pred[:n] if pred is not None else None)
 
+    def level(self, h: int, q_begin: int = 0, q_end: Optional[int] = None, stream=None):
+        """``logoskg_result_level_offsets`` + ``logoskg_result_level_fetch``: the entities of level
+        ``h`` of the queries [q_begin, q_end) as (offsets int64[Q+1] of the whole level, entity
+        int32 device tensor)."""
+        torch = _torch()
+        q_end = self.num_queries if q_end is None else q_end
+        off = np.zeros(self.num_queries + 1, dtype=np.int64)
+        _check(_load().logoskg_result_level_offsets(self._h, h, off.ctypes.data_as(ctypes.c_void_p),
+                                                    _stream_handle(stream)))
+        n = int(off[q_end] - off[q_begin])
+        entity = torch.empty(n, dtype=torch.int32, device=self._g.device)
+        _check(_load().logoskg_result_level_fetch(self._h, h, q_begin, q_end, n, entity.data_ptr(),
+                                                  _stream_handle(stream)))
+        return off, entity
+
     def traversed(self, stream=None):
         torch = _torch()
         t = torch.empty((self.num_queries, self.k), dtype=torch.int64, device=self._g.device)
@@ -283,7 +303,7 @@ class Graph:
         return shard_of, per
 
     def khop(self, seed_off, seeds, k: int, rel_mask=None, direction: str = "auto", counts: bool = True,
-             stream=None) -> Result:
+             stream=None, walk_exact: bool = False) -> Result:
         """``logoskg_khop`` for up to 1024 queries; inputs may be numpy arrays
         or device tensors (they are placed in HBM before the call)."""
         torch = _torch()
@@ -299,7 +319,7 @@ class Graph:
                 raise ValueError("rel_mask must be [Q, ceil(R/64)] 64-bit words")
         batch = _QueryBatch(ctypes.sizeof(_QueryBatch), seed_off_d.numel() - 1, seeds_d.numel(),
                             seed_off_d.data_ptr(), seeds_d.data_ptr() if seeds_d.numel() else None, k,
-                            DIRECTIONS[direction] | (0 if counts else NO_COUNTS),
+                            DIRECTIONS[direction] | (0 if counts else NO_COUNTS) | (WALK_EXACT if walk_exact else 0),
                             mask_d.data_ptr() if mask_d is not None else None, _stream_handle(stream))
         h = ctypes.c_void_p()
         _check(_load().logoskg_khop(self._h, ctypes.byref(batch), ctypes.byref(h)))

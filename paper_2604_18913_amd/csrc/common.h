@@ -179,6 +179,7 @@ struct logoskg_result {
     int64_t Epad = 0;
     bool has_mask = false;
     bool has_counts = false;
+    bool walk_exact = false;  // levels hold q^(h) of the plain iteration (no visited filter)
     unsigned long long *visited = nullptr;  // [Epad][W]
     unsigned long long *levels = nullptr;   // [k+1][Epad][W]
     uint32_t *act = nullptr;      // [k+1][Epad/32]: entity has a non-zero line in that level
@@ -192,6 +193,12 @@ struct logoskg_result {
     uint32_t *mega_base = nullptr;  // [nmega][64W]   mega tiles (65536 entities)
     long long *d_reached_off = nullptr;  // [64W+1]
     std::vector<int64_t> reached_off;  // host copy [Q+1]
+    // the same bookkeeping for one level plane (logoskg_result_level_offsets)
+    int level_counted = -1;
+    uint16_t *lvl_tile_base = nullptr;
+    uint32_t *lvl_super_base = nullptr, *lvl_mega_base = nullptr;
+    long long *d_level_off = nullptr;
+    std::vector<int64_t> level_off;
     std::vector<logoskg_hop_stats> stats;
 };
 

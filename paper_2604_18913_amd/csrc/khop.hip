@@ -189,6 +189,8 @@ __device__ __forceinline__ void mark_active(uint32_t *act, int e) {
     if (!(act[e >> 5] & bit)) atomicOr(&act[e >> 5], bit);
 }
 
+// `known` = the bits that need not be set again: the visited plane (minimum-hop search: an entity
+// keeps its first level) or, for walk-exact levels, the level under construction itself.
 // One W-lane group per short frontier row; its edges are walked one after another.
 template <int W, bool MASK>
 __global__ void __launch_bounds__(256)
@@ -196,7 +198,7 @@ k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restri
             const uint32_t *__restrict__ off, const uint32_t *__restrict__ row_begin,
             const int32_t *__restrict__ obj,
             const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
-            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
+            const unsigned long long *__restrict__ prev, const unsigned long long *known,
             unsigned long long *cur, uint32_t *act_cur) {
     long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
     int lw = threadIdx.x & (W - 1);
@@ -213,7 +215,7 @@ k_push_tail(const int32_t *__restrict__ rows, const unsigned long long *__restri
         int o = obj[j];
         unsigned long long m = line;
         if (MASK) m &= allow[(size_t)rel[j] * W + lw];
-        if (m) m &= ~visited[(size_t)o * W + lw];
+        if (m) m &= ~known[(size_t)o * W + lw];
         if (m) atomicOr(&cur[(size_t)o * W + lw], m);
         bool any = group_any<W>(m != 0);
         if (any && lw == 0) mark_active(act_cur, o);
@@ -226,7 +228,7 @@ template <int W, bool MASK>
 __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned long long line,
                                            const int32_t *__restrict__ obj, const uint16_t *__restrict__ rel,
                                            const unsigned long long *__restrict__ allow,
-                                           const unsigned long long *__restrict__ visited,
+                                           const unsigned long long *known,
                                            unsigned long long *cur, uint32_t *act_cur) {
     constexpr int GPW = 64 / W;
     int lw = lane() & (W - 1), g = lane() / W;
@@ -241,7 +243,7 @@ __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned lo
         if (o >= 0) {
             unsigned long long m = line;
             if (MASK) m &= allow[r];
-            if (m) m &= ~visited[o];
+            if (m) m &= ~known[o];
             if (m) {
                 atomicOr(&cur[o], m);
                 mark_active(act_cur, o);
@@ -255,7 +257,7 @@ __device__ __forceinline__ void push_chunk(uint32_t j0, uint32_t hi, unsigned lo
             if (idx < n) {
                 unsigned long long m = line;
                 if (MASK) m &= allow[(size_t)rc * W + lw];
-                if (m) m &= ~visited[(size_t)oc * W + lw];
+                if (m) m &= ~known[(size_t)oc * W + lw];
                 if (m) atomicOr(&cur[(size_t)oc * W + lw], m);
                 bool any = group_any<W>(m != 0);
                 if (any && lw == 0) mark_active(act_cur, oc);
@@ -271,7 +273,7 @@ k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__rest
            const uint32_t *__restrict__ off, const uint32_t *__restrict__ row_begin,
            const int32_t *__restrict__ obj,
            const uint16_t *__restrict__ rel, const unsigned long long *__restrict__ allow,
-           const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ visited,
+           const unsigned long long *__restrict__ prev, const unsigned long long *known,
            unsigned long long *cur, uint32_t *act_cur) {
     long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (item >= (long long)ctr[C_NSEG]) return;
@@ -281,7 +283,7 @@ k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__rest
     uint32_t row_end = row_begin[sg.row] + (off[sg.row + 1] - off[sg.row]);
     uint32_t hi = min(sg.begin + (uint32_t)kPushSegment, row_end);
     for (uint32_t j0 = sg.begin; j0 < hi; j0 += 64)
-        push_chunk<W, MASK>(j0, hi, line, obj, rel, allow, visited, cur, act_cur);
+        push_chunk<W, MASK>(j0, hi, line, obj, rel, allow, known, cur, act_cur);
 }
 
 // visited |= level[h] on the lines the push kernels touched.
@@ -423,7 +425,7 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
             const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
             const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
             unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
-            unsigned long long *stats) {
+            unsigned long long *stats, int walk_exact) {
     long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
     const int lw = threadIdx.x & (W - 1), g0 = lane() & ~(W - 1);
     uint32_t lo = 0, hi = 0;
@@ -434,7 +436,7 @@ k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__res
         vis = visited[(size_t)v * W + lw];
         lo = off[v];
         hi = off[v + 1];
-        need = ~vis & live[lw];
+        need = (walk_exact ? ~0ull : ~vis) & live[lw];
     }
     if (!group_any<W>(need != 0)) hi = lo;
     long long n_edges = 0, n_lines = 0;
@@ -498,7 +500,7 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
            const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
            unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
-           unsigned long long *stats) {
+           unsigned long long *stats, int walk_exact) {
     __shared__ int queue_s[4][64];
     __shared__ uint16_t queue_r[4][64];
     long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -516,7 +518,7 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
         hi = min(lo + (uint32_t)kPullSegment, row_hi);
         multi = (row_hi - row_lo) > (uint32_t)kPullSegment;
         vis = visited[(size_t)v * W + lw];
-        need = ~vis & live[lw];
+        need = (walk_exact ? ~0ull : ~vis) & live[lw];
         if (multi) need &= ~__atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
     }
     const bool work = wave_any(need != 0);
@@ -594,16 +596,17 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     unsigned long long *cur = r->levels + plane * h;
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
     long long nt = (long long)hc[C_NTAIL], ns = (long long)hc[C_NSEG];
+    const unsigned long long *known = r->walk_exact ? cur : r->visited;
     if (ns > 0) {
         ProfScope ps(g->prof, KK_PUSH_SEG, st);
         k_push_seg<W, MASK><<<dim3(blocks_for(ns, 4)), dim3(256), 0, st>>>(
-            g->fr_seg, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, r->visited, cur, act_cur);
+            g->fr_seg, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
         g->prof.acc[KK_PUSH_SEG].units[0] += g->prof.on ? ns : 0;
     }
     if (nt > 0) {
         ProfScope ps(g->prof, KK_PUSH_TAIL, st);
         k_push_tail<W, MASK><<<dim3(blocks_for(nt * W, 256)), dim3(256), 0, st>>>(
-            g->fr_tail, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, r->visited, cur, act_cur);
+            g->fr_tail, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
         g->prof.acc[KK_PUSH_TAIL].units[0] += g->prof.on ? nt : 0;
     }
     if (!update) return;
@@ -634,13 +637,13 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
         ProfScope ps(g->prof, KK_PULL_SEG, st);
         k_pull_seg<W, MASK, STATS><<<dim3(blocks_for(rc.n_seg, 4)), dim3(256), 0, st>>>(
             rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
-            act_cur, stats(KK_PULL_SEG));
+            act_cur, stats(KK_PULL_SEG), r->walk_exact ? 1 : 0);
     }
     if (rc.n_tail > 0) {
         ProfScope ps(g->prof, KK_PULL_TAIL, st);
         k_pull_tail<W, MASK, STATS><<<dim3(blocks_for(rc.n_tail * W, 256)), dim3(256), 0, st>>>(
             rc.tail, rc.n_tail, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
-            act_cur, stats(KK_PULL_TAIL));
+            act_cur, stats(KK_PULL_TAIL), r->walk_exact ? 1 : 0);
     }
     if (rc.n_multi > 0) {
         ProfScope ps(g->prof, KK_PULL_FINISH, st);
@@ -735,7 +738,8 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
     void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_cnt, r->tile_base,
-                    r->super_base, r->mega_base, r->d_reached_off};
+                    r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
+                    r->lvl_mega_base, r->d_level_off};
     for (void *p : ptrs) g->pool.release(p);
     delete r;
 }
@@ -753,6 +757,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
         return LOGOSKG_EINVAL;
     }
     uint32_t dir = b->flags & LOGOSKG_DIR_MASK;
+    const bool walk_exact = (b->flags & LOGOSKG_WALK_EXACT) != 0;
     if (dir == 3u) { set_error("bad direction flags"); return LOGOSKG_EINVAL; }
     if (g->num_shards > 1 && dir == LOGOSKG_DIR_PULL) {
         set_error("pull is only available on resident graphs");
@@ -769,6 +774,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     r->W = words_for_queries(r->Q);
     r->Epad = g->Epad;
     r->has_mask = b->rel_mask != nullptr;
+    r->walk_exact = walk_exact;
     r->stats.assign((size_t)r->k, logoskg_hop_stats{});
     const int W = r->W, k = r->k;
     const size_t plane = (size_t)r->Epad * W;

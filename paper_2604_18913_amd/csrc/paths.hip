@@ -84,6 +84,7 @@ extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *
         return LOGOSKG_EINVAL;
     }
     if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
+    if (r->walk_exact) { set_error("shortest paths are not defined for a LOGOSKG_WALK_EXACT result"); return LOGOSKG_EINVAL; }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
     const int k = r->k;

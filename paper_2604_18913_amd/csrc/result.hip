@@ -790,37 +790,46 @@ __global__ void k_traversed(int32_t E, int Q, int k, long long plane, long long 
     }
 }
 
-logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
+// Per-query counts of the set bits of one plane (visited, or a level) as three nested exclusive
+// prefixes plus the offsets of the query-major lists; the tables are allocated on first use.
+static logoskg_status count_plane(logoskg_result *r, const unsigned long long *plane_bits, uint16_t **tile_base,
+                                  uint32_t **super_base, uint32_t **mega_base, long long **d_off,
+                                  std::vector<int64_t> *off, hipStream_t st) {
     logoskg_graph *g = r->g;
     const int W = r->W, Qp = 64 * W;
     const long long ntiles = r->Epad / kTileEntities;
     const long long nsuper = (ntiles + kSuperTiles - 1) / kSuperTiles;
     const long long nmega = (nsuper + kMegaSupers - 1) / kMegaSupers;
-    LKG_TRY(g->pool.alloc((void **)&r->tile_base, (size_t)ntiles * Qp * 2));
-    LKG_TRY(g->pool.alloc((void **)&r->super_base, (size_t)nsuper * Qp * 4));
-    LKG_TRY(g->pool.alloc((void **)&r->mega_base, (size_t)nmega * Qp * 4));
-    LKG_TRY(g->pool.alloc((void **)&r->d_reached_off, (size_t)(Qp + 1) * 8));
+    if (!*tile_base) LKG_TRY(g->pool.alloc((void **)tile_base, (size_t)ntiles * Qp * 2));
+    if (!*super_base) LKG_TRY(g->pool.alloc((void **)super_base, (size_t)nsuper * Qp * 4));
+    if (!*mega_base) LKG_TRY(g->pool.alloc((void **)mega_base, (size_t)nmega * Qp * 4));
+    if (!*d_off) LKG_TRY(g->pool.alloc((void **)d_off, (size_t)(Qp + 1) * 8));
     {
         ProfScope ps(g->prof, KK_COUNT, st);
         dim3 grid((unsigned)nsuper), block(Qp);
         switch (W) {
-            case 1: k_count<1><<<grid, block, 0, st>>>(r->visited, ntiles, r->tile_base, r->super_base); break;
-            case 4: k_count<4><<<grid, block, 0, st>>>(r->visited, ntiles, r->tile_base, r->super_base); break;
-            default: k_count<16><<<grid, block, 0, st>>>(r->visited, ntiles, r->tile_base, r->super_base); break;
+            case 1: k_count<1><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
+            case 4: k_count<4><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
+            default: k_count<16><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
         }
         g->prof.acc[KK_COUNT].units[3] += g->prof.on ? r->Epad * W : 0;
     }
     {
         ProfScope ps(g->prof, KK_SCAN, st);
-        k_scan_level<<<dim3((unsigned)nmega), dim3(std::min(Qp, 256)), 0, st>>>(nsuper, kMegaSupers, Qp,
-                                                                              r->super_base, r->mega_base);
-        k_scan_top<<<dim3(1), dim3(Qp), 0, st>>>(nmega, r->Q, Qp, r->mega_base, r->d_reached_off);
+        k_scan_level<<<dim3((unsigned)nmega), dim3(std::min(Qp, 256)), 0, st>>>(nsuper, kMegaSupers, Qp, *super_base,
+                                                                              *mega_base);
+        k_scan_top<<<dim3(1), dim3(Qp), 0, st>>>(nmega, r->Q, Qp, *mega_base, *d_off);
     }
     LKG_HIP(hipGetLastError());
-    r->reached_off.assign((size_t)r->Q + 1, 0);
-    LKG_HIP(hipMemcpyAsync(r->reached_off.data(), r->d_reached_off, (size_t)(r->Q + 1) * 8,
-                           hipMemcpyDeviceToHost, st));
+    off->assign((size_t)r->Q + 1, 0);
+    LKG_HIP(hipMemcpyAsync(off->data(), *d_off, (size_t)(r->Q + 1) * 8, hipMemcpyDeviceToHost, st));
     LKG_HIP(hipStreamSynchronize(st));
+    return LOGOSKG_OK;
+}
+
+logoskg_status count_reached(logoskg_result *r, hipStream_t st) {
+    LKG_TRY(count_plane(r, r->visited, &r->tile_base, &r->super_base, &r->mega_base, &r->d_reached_off,
+                        &r->reached_off, st));
     r->has_counts = true;
     return LOGOSKG_OK;
 }
@@ -954,6 +963,10 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
                                                int32_t *entity, uint8_t *hop, int32_t *pred, void *stream) {
     if (!r) { set_error("NULL result"); return LOGOSKG_EINVAL; }
     if (!r->has_counts) { set_error("result was computed with LOGOSKG_NO_COUNTS"); return LOGOSKG_EINVAL; }
+    if (r->walk_exact) {
+        set_error("hop and predecessor are not defined for a LOGOSKG_WALK_EXACT result: use logoskg_result_level_fetch");
+        return LOGOSKG_EINVAL;
+    }
     if (q0 < 0 || q1 > r->Q || q0 > q1) { set_error("bad query range [%d, %d)", q0, q1); return LOGOSKG_EINVAL; }
     int64_t need = r->reached_off[(size_t)q1] - r->reached_off[(size_t)q0];
     if (capacity < need) {
@@ -1028,6 +1041,53 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
         for (int kind : {KK_PRED, KK_PRED_HUB, KK_PRED_MID})
             for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)g->h_ctr[C_STATS + 4 * kind + u];
     }
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_result_level_offsets(logoskg_result *r, int32_t h, int64_t *level_off,
+                                                       void *stream) {
+    if (!r || !level_off) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    if (h < 0 || h > r->k) { set_error("level %d outside [0, %d]", h, r->k); return LOGOSKG_EINVAL; }
+    LKG_HIP(hipSetDevice(r->g->device));
+    r->level_counted = -1;
+    LKG_TRY(count_plane(r, r->levels + (size_t)h * r->Epad * r->W, &r->lvl_tile_base, &r->lvl_super_base,
+                        &r->lvl_mega_base, &r->d_level_off, &r->level_off, (hipStream_t)stream));
+    r->level_counted = h;
+    memcpy(level_off, r->level_off.data(), (size_t)(r->Q + 1) * sizeof(int64_t));
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t h, int32_t q0, int32_t q1,
+                                                     int64_t capacity, int32_t *entity, void *stream) {
+    if (!r) { set_error("NULL result"); return LOGOSKG_EINVAL; }
+    if (h < 0 || h > r->k || r->level_counted != h) {
+        set_error("level %d was not counted: call logoskg_result_level_offsets for it first", h);
+        return LOGOSKG_EINVAL;
+    }
+    if (q0 < 0 || q1 > r->Q || q0 > q1) { set_error("bad query range [%d, %d)", q0, q1); return LOGOSKG_EINVAL; }
+    const int64_t need = r->level_off[(size_t)q1] - r->level_off[(size_t)q0];
+    if (capacity < need) {
+        set_error("capacity %lld < %lld entries", (long long)capacity, (long long)need);
+        return LOGOSKG_ERANGE;
+    }
+    if (need == 0) return LOGOSKG_OK;
+    if (!entity) { set_error("entity buffer is NULL"); return LOGOSKG_EINVAL; }
+    logoskg_graph *g = r->g;
+    LKG_HIP(hipSetDevice(g->device));
+    const int W = r->W;
+    FillArgs a = {};
+    // the level plane plays the part of the visited plane; no hop numbers are asked for
+    a.E = g->E; a.Q = r->Q; a.k = 0; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
+    a.ntiles = r->Epad / kTileEntities;
+    a.tile_begin = 0; a.tile_count = a.ntiles;
+    a.plane = r->Epad * W; a.actw = r->Epad / 32;
+    a.visited = r->levels + (size_t)h * r->Epad * W; a.levels = a.visited; a.allow = r->allow;
+    a.act = r->act; a.tile_base = r->lvl_tile_base; a.super_base = r->lvl_super_base; a.mega_base = r->lvl_mega_base;
+    a.reached_off = r->d_level_off;
+    a.entity = entity;
+    launch_lists(g->prof, a, W, (hipStream_t)stream);
+    LKG_HIP(hipGetLastError());
+    if (g->prof.on) g->prof.acc[KK_LISTS].units[3] += need;
     return LOGOSKG_OK;
 }
 

@@ -102,6 +102,33 @@ def test_config2_full_size():
     g.close()
 
 
+def test_config2_full_size_walk_exact_levels():
+    # Eq. 4 iterated without the visited set, at full size: sampled queries against the oracle,
+    # every level; the reached counts of all queries against the minimum-hop run
+    m = lkg()
+    w = kggen.config2()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    base = g.khop(w.seed_off, w.seeds, w.k)
+    res = g.khop(w.seed_off, w.seeds, w.k, walk_exact=True)
+    assert np.array_equal(res.offsets(), base.offsets())
+    qs = sampled_queries(w.num_queries, 16, 5, np.diff(base.offsets()))
+    base.close()
+    so, sd, sm = sub_batch(w, qs)
+    t0 = time.time()
+    want_off, want_ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, so, sd, w.k, sm)
+    log(f"oracle walk levels on {len(qs)} queries: {time.time() - t0:.1f}s, {want_off[-1]} entries")
+    n = len(qs)
+    for h in range(w.k + 1):
+        off, _ = res.level(h, 0, 0)
+        for i, q in enumerate(qs):
+            a, b = int(want_off[h * n + i]), int(want_off[h * n + i + 1])
+            assert off[q + 1] - off[q] == b - a, f"level {h} query {q}: count"
+            _, ent = res.level(h, int(q), int(q) + 1)
+            assert np.array_equal(ent.cpu().numpy(), want_ent[a:b]), f"level {h} query {q}: entities"
+    res.close()
+    g.close()
+
+
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 def test_config3_full_size_masks_and_paths(k):
     m = lkg()
