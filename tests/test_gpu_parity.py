@@ -201,6 +201,45 @@ def test_paths_against_oracle(masked):
     g.close()
 
 
+@pytest.mark.parametrize("Q", [3, 300])
+def test_degenerate_graphs_and_the_deepest_search(Q):
+    # a 300-entity chain searched to the largest k (hop numbers up to 254), a graph without
+    # triples, a single entity with a self loop, and relation ids at the top of the 16-bit range
+    m = lkg()
+    n = 300
+    chain = np.arange(n - 1, dtype=np.int32)
+    rel = (np.arange(n - 1, dtype=np.int32) * 7919) % 65536
+    seed_off = np.arange(Q + 1, dtype=np.int64)
+    seeds = (np.arange(Q, dtype=np.int32) * 5) % n
+    for k in (254, 6, 1):
+        g = m.Graph(chain, rel, chain + 1, n, 65536)
+        res = g.khop(seed_off, seeds, k)
+        want = oracle.khop(n, chain, rel, chain + 1, seed_off, seeds, k)
+        ent, hop, pred = res.fetch()
+        got = (res.offsets(), ent.cpu().numpy(), hop.cpu().numpy(), pred.cpu().numpy(),
+               res.traversed().cpu().numpy())
+        assert_same(got, want, f"chain k={k}")
+        res.close()
+        g.close()
+    empty = np.zeros(0, dtype=np.int32)
+    g = m.Graph(empty, empty, empty, 70, 3)
+    res = g.khop(seed_off, seeds % 70, 3)
+    want = oracle.khop(70, empty, empty, empty, seed_off, seeds % 70, 3)
+    ent, hop, pred = res.fetch()
+    assert_same((res.offsets(), ent.cpu().numpy(), hop.cpu().numpy(), pred.cpu().numpy(), None), want, "no triples")
+    res.close()
+    g.close()
+    one = np.zeros(1, dtype=np.int32)
+    g = m.Graph(one, one, one, 1, 1)
+    res = g.khop(seed_off, np.zeros(Q, dtype=np.int32), 4)
+    want = oracle.khop(1, one, one, one, seed_off, np.zeros(Q, dtype=np.int32), 4)
+    ent, hop, pred = res.fetch()
+    assert_same((res.offsets(), ent.cpu().numpy(), hop.cpu().numpy(), pred.cpu().numpy(),
+                 res.traversed().cpu().numpy()), want, "self loop")
+    res.close()
+    g.close()
+
+
 def test_bad_inputs_are_reported_not_faulted():
     m = lkg()
     w = kggen.config1()
