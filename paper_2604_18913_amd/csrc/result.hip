@@ -499,6 +499,7 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     __shared__ uint32_t in_lo[256];
     __shared__ int long_li[256];
     __shared__ int wsum[8];
+    __shared__ int short_entries;  // entries of all short rows of the block
     const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
     if (L >= mt_count * 4) return;
     const long long mt = mt_begin + (L >> 2);
@@ -541,15 +542,16 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     }
     __syncthreads();
     // staged layout: query-major, inside a query tile by tile; offsets into the edge-id table
-    int c0 = 0, c1 = 0, c2 = 0, tot = 0, ex = 0, dx = 0;
+    int c0 = 0, c1 = 0, c2 = 0, tot = 0, ex = 0, dx = 0, my_deg = 0;
     if (t < 256) {
+        my_deg = roff[t];
         c0 = __popcll(mT[0][t]);
         c1 = __popcll(mT[1][t]);
         c2 = __popcll(mT[2][t]);
         tot = c0 + c1 + c2 + __popcll(mT[3][t]);
         int wtot, dtot;
         ex = wave_excl_scan(tot, wtot);
-        dx = wave_excl_scan((int)roff[t], dtot);
+        dx = wave_excl_scan(my_deg, dtot);
         if (v == 0) {
             wsum[wave] = wtot;
             wsum[4 + wave] = dtot;
@@ -568,6 +570,7 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
         pos0[2][t] = (uint32_t)(ex + c0 + c1);
         pos0[3][t] = (uint32_t)(ex + c0 + c1 + c2);
         roff[t] = (uint16_t)dx;
+        if (t == 255) short_entries = dx + my_deg;
         const int q = slab * 256 + t;
         long long b = 0;
         if (q >= a.q0 && q < a.q1) b = super_start(a, tile0 / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile0 * Qp + q];
@@ -575,7 +578,8 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
     }
     __syncthreads();
     const int my_roff = roff[vi];
-    if (shortrow && my_roff + kTailMaxDegree <= kMtEids)
+    const bool eids_staged = short_entries <= kMtEids;  // block-uniform: the table holds every short row
+    if (shortrow && eids_staged)
         for (uint32_t j = lw; j < deg; j += G) eid_tab[my_roff + j] = a.in_eid[lo + j];
     const unsigned long long below = (1ull << (vi & 63)) - 1ull;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
@@ -660,9 +664,10 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
                     if (li == -2) continue;
                     if (li >= 0) {
                         val = a.row_pred[(size_t)li * Qp + slab * 256 + ql];
+                    } else if (eids_staged) {
+                        val = eid_tab[roff[e] + jp];
                     } else {
-                        const int ro = roff[e];
-                        val = ro + kTailMaxDegree <= kMtEids ? eid_tab[ro + jp] : a.in_eid[in_lo[e] + jp];
+                        val = a.in_eid[in_lo[e] + jp];
                     }
                 }
                 a.pred[dst + i] = val;
