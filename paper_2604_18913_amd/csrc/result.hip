@@ -653,24 +653,20 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
             const long long dst = base[ql];
             for (uint32_t i = v; i < n; i += 64) {
                 const unsigned code = u.code[src + i];
-                if (code == kCodeNone) continue;
+                const bool have = code != kCodeNone;
                 const int e = (code >> 5) & 255, jp = code & 31, hopv = code >> 13, li = long_li[e];
-                if (a.fuse_lists) {
-                    a.entity[dst + i] = (int32_t)(tile0 * 64 + e);
-                    if (a.hop) a.hop[dst + i] = (uint8_t)hopv;
-                }
-                int val = -1;
-                if (hopv != 0) {
-                    if (li == -2) continue;
-                    if (li >= 0) {
-                        val = a.row_pred[(size_t)li * Qp + slab * 256 + ql];
-                    } else if (eids_staged) {
-                        val = eid_tab[roff[e] + jp];
-                    } else {
-                        val = a.in_eid[in_lo[e] + jp];
+                int val;
+                if (eids_staged) val = eid_tab[min((int)roff[e] + jp, kMtEids + 31)];  // unused for long rows
+                else val = have && li == -1 && hopv != 0 ? a.in_eid[in_lo[e] + jp] : -1;
+                if (have && li >= 0 && hopv != 0) val = a.row_pred[(size_t)li * Qp + slab * 256 + ql];
+                if (hopv == 0) val = -1;
+                if (have) {
+                    if (a.fuse_lists) {
+                        a.entity[dst + i] = (int32_t)(tile0 * 64 + e);
+                        if (a.hop) a.hop[dst + i] = (uint8_t)hopv;
                     }
+                    if (li != -2 || hopv == 0) a.pred[dst + i] = val;
                 }
-                a.pred[dst + i] = val;
             }
         }
         __syncthreads();
