@@ -483,8 +483,12 @@ constexpr int kMtEids = 3072;   // staged edge ids of the short rows
 constexpr unsigned kCodeNone = 0xFFFFu;
 constexpr int kMtMaxK = 6;       // hop numbers 0..6 fit the code's three bits beside kCodeNone
 
+// Two blocks per CU need 8 wavefronts per SIMD; measured, the second block is only co-resident
+// while a wavefront asks for at most 80 scalar registers (SQ_WAVE_CYCLES / SQ_BUSY_CYCLES halves
+// above that), hence the cap: spilling a few scalars costs far less than half the occupancy.
 template <bool MASK, bool STATS>
-__global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(72)))
+k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
     constexpr int W = 16, Qp = 1024, G = kPredGroup;
     __shared__ unsigned long long mT[4][256];  // [tile][query]: tile entities the query reached
     __shared__ uint32_t pos0[4][256];          // start of the tile's part of the query's staged run
@@ -591,11 +595,17 @@ __global__ void __launch_bounds__(1024) k_pred_mt(FillArgs a, long long mt_begin
             reinterpret_cast<uint2 *>(u.code)[i] = make_uint2(kCodeNone * 0x10001u, kCodeNone * 0x10001u);
         __syncthreads();
         const bool mine = lw >= ja && lw < jb;
+        // the two 32-bit halves of a mask are walked one after the other: 32-bit bit tricks are
+        // half the instructions of their 64-bit forms
+        const uint32_t *const my_pos0 = &pos0[tt][lw * 64];
+        const unsigned long long *const my_mT = &mT[tt][lw * 64];
         auto emit = [&](unsigned long long bits, unsigned code) {
-            for (unsigned long long m = bits; m; m &= m - 1) {
-                const int ql = lw * 64 + (__ffsll((long long)m) - 1);
-                u.code[pos0[tt][ql] + __popcll(mT[tt][ql] & below) - goff] = (uint16_t)code;
-            }
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+                for (uint32_t m = (uint32_t)(bits >> (32 * half)); m; m &= m - 1) {
+                    const int b = 32 * half + __ffs((int)m) - 1;
+                    u.code[my_pos0[b] + __popcll(my_mT[b] & below) - goff] = (uint16_t)code;
+                }
         };
         if (mine && seedw) emit(seedw, (unsigned)vi << 5);
         if (mine && longrow && (visw & ~seedw))
