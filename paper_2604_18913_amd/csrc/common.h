@@ -187,7 +187,6 @@ struct logoskg_result {
     unsigned long long *live = nullptr;     // [k+1][16] queries whose level-h frontier has an out-edge
     // result-list bookkeeping (count pass): for every query, the number of reached
     // entities below a tile, as three nested exclusive prefixes
-    uint8_t *tile_cnt = nullptr;    // unused (kept zero)
     uint16_t *tile_base = nullptr;  // [ntiles][64W]  tiles (64 entities) inside their super tile
     uint32_t *super_base = nullptr; // [nsuper][64W]  super tiles (1024 entities) inside their mega tile
     uint32_t *mega_base = nullptr;  // [nmega][64W]   mega tiles (65536 entities)

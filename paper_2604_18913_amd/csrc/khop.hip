@@ -17,6 +17,10 @@
 // Both give the same level[h].  Rows of up to 32 entries are handled by a
 // W-lane group each; longer rows are cut into fixed-size segments, one
 // wavefront per segment, so a 100,000-entry hub spreads over many CUs.
+//
+// With LOGOSKG_WALK_EXACT the visited filter is dropped (Eq. 4 iterated as
+// written): level[h] = image of level[h-1], an entity may be in several levels;
+// visited still collects their union.
 #include <algorithm>
 
 #include "common.h"
@@ -737,7 +741,7 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     if (!r) return;
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
-    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_cnt, r->tile_base,
+    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_base,
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
                     r->lvl_mega_base, r->d_level_off};
     for (void *p : ptrs) g->pool.release(p);

@@ -11,6 +11,7 @@
 // entity's rank inside the tile's run of the query's list.
 //
 //   count : per (query, tile) counts -> nested exclusive prefixes -> offsets
+//           (of the visited plane, or of one level plane for the per-level lists)
 //   lists : one block per super tile compacts the (entity, hop) entries of each
 //           query in LDS and writes them as whole 64-lane stores
 //   pred  : the predecessor edge (smallest edge id whose subject sits one hop
@@ -18,6 +19,10 @@
 //           triple of Eq. 5-7 in edge-id order) is found by walking the object
 //           row of the entity in ascending edge id with a mask of still
 //           unresolved queries, so every (query, entity) pair is written once.
+//           Object rows of up to 32 entries belong to a tile kernel (k_pred_mt
+//           for 16-word planes and k <= 6, which writes the entity and hop
+//           lists as well; k_pred otherwise), rows of 33 .. hub_min-1 entries to
+//           k_pred_wave, longer ones to k_pred_row.
 #include <algorithm>
 #include <climits>
 #include <cstdlib>
