@@ -69,9 +69,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-queries", type=int, default=384)
+    ap.add_argument("--cpu-queries", type=int, default=0, help="0 = 384 for configs 1-3, 6 for configs 4 and 5")
     ap.add_argument("--serial-fetch", action="store_true",
                     help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
+    ap.add_argument("--config", type=int, choices=[1, 2, 3, 4, 5], default=2,
+                    help="workload: 2 (default) is the one the metric is quoted on; the others are the "
+                         "parity-test shapes, timed the same way for the table in DESIGN.md "
+                         "(4: the first of its four 1,024-query batches; 5: 8 shards, 64 GB shard budget)")
+    ap.add_argument("--k", type=int, default=0, help="hops (config 3 sweeps 1..4; 0 = the workload's own)")
+    ap.add_argument("--fetch-queries", type=int, default=0,
+                    help="fetch the lists of the first N queries only (0 = all; configs 4 and 5 default to 64)")
     ap.add_argument("--mode", choices=["minhop", "walk"], default="minhop",
                     help="minhop (default): the headline path; walk: Eq. 4 iterated without the visited set "
                          "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query")
@@ -92,15 +99,35 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     t0 = time.time()
-    w = kggen.config2(args.scale)
+    cfg = args.config
+    graph_opts = {}
+    if cfg == 1:
+        w = kggen.config1(args.scale)
+    elif cfg == 2:
+        w = kggen.config2(args.scale)
+    elif cfg == 3:
+        w = kggen.config3(args.scale, k=args.k or 3)
+    elif cfg == 4:
+        w = kggen.config4(args.scale)
+        w.seed_off = w.seed_off[: min(w.num_queries, 1024) + 1]     # the first of the four batches
+        w.seeds = w.seeds[: w.seed_off[-1]]
+    else:
+        w = kggen.config5(args.scale)
+        graph_opts = dict(num_shards=8, hbm_shard_budget_bytes=64 << 30)
+    if args.k:
+        w.k = args.k
     t_gen = time.time() - t0
     t0 = time.time()
-    g = lkg.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    g = lkg.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, **graph_opts)
     t_build = time.time() - t0
     dev = g.device
     seed_off = torch.from_numpy(w.seed_off).to(dev)
     seeds = torch.from_numpy(w.seeds).to(dev)
+    rel_mask = None if w.rel_mask is None else torch.from_numpy(w.rel_mask.view(np.int64)).to(dev)
+    masked = rel_mask is not None
     Q, k = w.num_queries, w.k
+    nf = args.fetch_queries or (64 if cfg >= 4 else Q)   # queries whose lists are fetched
+    nf = min(nf, Q)
 
     if args.pmc_calibration:
         src = torch.ones(1 << 27, dtype=torch.int64, device=dev)   # 1 GiB
@@ -113,9 +140,9 @@ def main():
 
     # sizes are deterministic: one untimed call sizes the output buffers
     walk = args.mode == "walk"
-    res = g.khop(seed_off, seeds, k, walk_exact=walk)
+    res = g.khop(seed_off, seeds, k, rel_mask, walk_exact=walk)
     off = res.offsets()
-    total = int(res.level(k, 0, 0)[0][-1]) if walk else int(off[-1])
+    total = int(res.level(k, 0, 0)[0][nf]) if walk else int(off[nf])
     W = res.words_per_entity
     res_epad = res.padded_entities
     if not walk:
@@ -129,11 +156,11 @@ def main():
 
     def step():
         if walk:
-            r = g.khop(seed_off, seeds, k, walk_exact=True)
-            r.level(k)
+            r = g.khop(seed_off, seeds, k, rel_mask, walk_exact=True)
+            r.level(k, 0, nf)
         else:
-            r = g.khop(seed_off, seeds, k)
-            r.fetch(out=(ent, hop, pred))
+            r = g.khop(seed_off, seeds, k, rel_mask)
+            r.fetch(0, nf, out=(ent, hop, pred))
         return r
 
     def run_steps(n):
@@ -174,6 +201,7 @@ def main():
         os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
 
     ab = functools.partial(algorithmic_bytes, level_lists=walk)
+    masked_arg = masked
     ms_per_step = dt / args.steps * 1e3
     qps = Q / (dt / args.steps)
     kernels = {}
@@ -190,19 +218,19 @@ def main():
     expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")
     expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith(expansion_names))
     plane_bytes = float(res_epad * W * 8)
-    expansion_bytes = sum(ab(n, v, W, k, False, plane_bytes) for n, v in kernels.items()
+    expansion_bytes = sum(ab(n, v, W, k, masked_arg, plane_bytes) for n, v in kernels.items()
                           if n.startswith(expansion_names))
     lists_fused = "lists" not in kernels  # the predecessor tile kernel wrote the entity / hop lists too
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
-    alg = ab(dom, dk, W, k, False, plane_bytes, lists_fused) / max(dk["launches_per_step"], 1)
+    alg = ab(dom, dk, W, k, masked_arg, plane_bytes, lists_fused) / max(dk["launches_per_step"], 1)
     achieved = alg / (dk["avg_ms"] * 1e-3) / 1e9 if dk["avg_ms"] > 0 else 0.0
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     # calibrated); counters cannot be read from inside this process
     traffic = None
     expansion_measured = None
     tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_traffic.json")
-    if os.path.exists(tfile) and args.scale == 1.0:
+    if os.path.exists(tfile) and args.scale == 1.0 and cfg == 2 and not walk and nf == Q:
         tk = json.load(open(tfile)).get("kernels", {})
         traffic = tk.get(dom, {}).get("hbm_bytes_per_launch")
         expansion_measured = sum(tk[n]["hbm_read_bytes_per_step"] + tk[n]["hbm_write_bytes_per_step"]
@@ -215,25 +243,39 @@ def main():
     # the same figure for every kernel that has a byte model
     exp = {}
     for n, v in kernels.items():
-        b = ab(n, v, W, k, False, plane_bytes, lists_fused)
+        b = ab(n, v, W, k, masked_arg, plane_bytes, lists_fused)
         if b > 0 and v["ms_per_step"] > 0:
             exp[n] = dict(GBps=round(b / (v["ms_per_step"] * 1e-3) / 1e9, 1),
                           frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           ms_per_step=round(v["ms_per_step"], 4), bytes_per_step=int(b))
 
+    if cfg == 2 and not walk:
+        metric = "queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)"
+    elif cfg == 2:
+        metric = ("queries/s, walk-exact 3-hop batch-1024 on 30M-edge synthetic KG (khop without the visited set + "
+                  "the level-3 list of every query)")
+    else:
+        metric = (f"queries/s, {k}-hop batch-{Q} on configs[{cfg - 1}] (khop + the lists of the first {nf} queries"
+                  + (", walk-exact" if walk else "") + ")")
+    workload = f"configs[{cfg - 1}]: {w.num_entities:,} entities, {w.num_triples:,} triples, {w.num_relations:,} " \
+               f"relations, {Q:,} queries, k={k}, " + ("per-query relation whitelists" if masked else "no relation mask")
+    if cfg == 2:
+        workload = ("configs[1]: 3,000,000 entities, 30,000,000 triples, 500 relations, "
+                    "1,024 queries x 1-5 seeds, k=3, no relation mask")
+    if cfg == 4:
+        workload += " (first of four 1,024-query batches)"
+    if cfg == 5:
+        workload += " (8 shards, 64 GB shard budget, shards cached from pinned host memory)"
     out = {
-        "metric": ("queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)"
-                   if not walk else
-                   "queries/s, walk-exact 3-hop batch-1024 on 30M-edge synthetic KG (khop without the visited set + "
-                   "the level-3 list of every query)"),
+        "metric": metric,
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "configs[1]: 3,000,000 entities, 30,000,000 triples, 500 relations, "
-                               "1,024 queries x 1-5 seeds, k=3, no relation mask" +
+        "config": {"workload": workload +
                                ("" if args.scale == 1.0 else f" (scaled by {args.scale})"),
                    "num_entities": w.num_entities, "num_triples": w.num_triples, "num_queries": Q, "k": k,
-                   "mode": args.mode, "words_per_entity": W, "reached_pairs": total,
+                   "mode": args.mode, "words_per_entity": W, "reached_pairs": total, "queries_fetched": nf,
+                   "reached_pairs_all_queries": int(off[-1]),
                    "directions": [h["direction"] for h in hop_stats]},
         "gteps_logical": round(logical_edges / (dt / args.steps) / 1e9, 2),
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
@@ -256,18 +298,22 @@ def main():
         "setup_s": {"generate": round(t_gen, 1), "build": round(t_build, 1)},
     }
 
+    if cfg == 5:
+        out["shard_cache"] = {kk: vv for kk, vv in g.info().items()
+                              if kk.startswith("shard_") or kk in ("num_shards", "pinned_host_bytes", "device_bytes")}
     if not args.no_cpu_baseline:
         import oracle  # the cpu_baseline leg is the only user of the oracle here
-        nq = min(args.cpu_queries, Q)
+        nq = min(args.cpu_queries or (384 if cfg <= 3 else 6), nf)
         so = w.seed_off[: nq + 1]
         sd = w.seeds[: so[-1]]
+        mk = None if w.rel_mask is None else w.rel_mask[:nq]
         t0 = time.perf_counter()
         if walk:
-            o_off, o_ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
+            o_off, o_ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         else:
-            o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k)
+            o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         t_cpu = time.perf_counter() - t0
-        got = g.khop(seed_off, seeds, k, walk_exact=walk)
+        got = g.khop(seed_off, seeds, k, rel_mask, walk_exact=walk)
         if walk:
             l_off, l_ent = got.level(k, 0, nq)
             a = o_off[k * nq:(k + 1) * nq + 1]

@@ -493,7 +493,7 @@ constexpr int kMtMaxK = 6;       // hop numbers 0..6 fit the code's three bits b
 // above that), hence the cap: spilling a few scalars costs far less than half the occupancy.
 template <bool MASK, bool STATS>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(72)))
-k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
+k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, int slab_count) {
     constexpr int W = 16, Qp = 1024, G = kPredGroup;
     __shared__ unsigned long long mT[4][256];  // [tile][query]: tile entities the query reached
     __shared__ uint32_t pos0[4][256];          // start of the tile's part of the query's staged run
@@ -510,9 +510,9 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
     __shared__ int wsum[8];
     __shared__ int short_entries;  // entries of all short rows of the block
     const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
-    if (L >= mt_count * 4) return;
-    const long long mt = mt_begin + (L >> 2);
-    const int slab = (int)(L & 3);
+    if (L >= mt_count * slab_count) return;
+    const long long mt = mt_begin + L / slab_count;
+    const int slab = slab_first + (int)(L % slab_count);  // slabs without a fetched query are not launched
     const int t = threadIdx.x, wave = t >> 6, v = lane();
     const int vi = t / G, lw = t % G, wq = G * slab + lw, g0 = v & ~(G - 1);
     const int tt = vi >> 6;
@@ -582,13 +582,14 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
         if (t == 255) short_entries = dx + my_deg;
         const int q = slab * 256 + t;
         long long b = 0;
-        if (q >= a.q0 && q < a.q1) b = super_start(a, tile0 / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile0 * Qp + q];
+        if (tot > 0) b = super_start(a, tile0 / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile0 * Qp + q];
         base[t] = b;
     }
     __syncthreads();
     const int my_roff = roff[vi];
     const bool eids_staged = short_entries <= kMtEids;  // block-uniform: the table holds every short row
-    if (shortrow && eids_staged)
+    const bool reached = group_any<G>((visw & ~seedw) != 0);  // by an edge, for some query of the slab
+    if (shortrow && eids_staged && reached)
         for (uint32_t j = lw; j < deg; j += G) eid_tab[my_roff + j] = a.in_eid[lo + j];
     const unsigned long long below = (1ull << (vi & 63)) - 1ull;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
@@ -618,7 +619,7 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
                 unsigned long long lv = a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
                 if (lv) emit(lv, ((unsigned)h << 13) | ((unsigned)vi << 5));
             }
-        if (shortrow)
+        if (shortrow && reached)
             for (int h = 1; h <= a.k; ++h) {
                 unsigned long long rem = mine ? a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w : 0ull;
                 if (!group_any<G>(rem != 0)) continue;
@@ -687,7 +688,7 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count) {
         __syncthreads();
         ja = jb;
     }
-    if (STATS && slab == 0) {  // work counters on one quarter of the words
+    if (STATS && slab == slab_first) {  // work counters on one slab of words
         n_rows = wave_sum(n_rows);
         n_edges = wave_sum(n_edges);
         n_lines = wave_sum(n_lines);
@@ -918,8 +919,10 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         ProfScope ps(prof, KK_PRED, st_tiles);
         if (mt) {
             const long long mt_count = (a.tile_count + kPredTiles - 1) / kPredTiles;
-            dim3 grid((unsigned)((mt_count * 4 + 7) / 8 * 8));
-            k_pred_mt<MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a, a.tile_begin / kPredTiles, mt_count);
+            const int slab_first = a.q0 / 256, slab_count = (a.q1 - 1) / 256 - slab_first + 1;
+            dim3 grid((unsigned)((mt_count * slab_count + 7) / 8 * 8));
+            k_pred_mt<MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a, a.tile_begin / kPredTiles, mt_count, slab_first,
+                                                                      slab_count);
         } else {
             dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
             k_pred<W, MASK, STATS><<<grid, block, 0, st_tiles>>>(a);
