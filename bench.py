@@ -62,6 +62,11 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
     return 0.0
 
 
+def note(*a):
+    """Progress lines go to stderr: stdout carries the one JSON line."""
+    print(time.strftime("%H:%M:%S"), *a, file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,9 +122,11 @@ def main():
     if args.k:
         w.k = args.k
     t_gen = time.time() - t0
+    note(f"generated config {cfg} in {t_gen:.0f} s: {w.num_entities:,} entities, {w.num_triples:,} triples")
     t0 = time.time()
     g = lkg.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, **graph_opts)
     t_build = time.time() - t0
+    note(f"built in {t_build:.0f} s")
     dev = g.device
     seed_off = torch.from_numpy(w.seed_off).to(dev)
     seeds = torch.from_numpy(w.seeds).to(dev)
@@ -184,7 +191,9 @@ def main():
     r.close()
     g.profile_enable(0)
 
+    note("work units counted; warm-up")
     run_steps(args.warmup)
+    note("timed region")
     # timed region: the default path (list / predecessor kernels of a fetch overlap on side
     # streams), every launch bracketed by HIP events on its own stream
     g.profile_enable(1)
@@ -301,7 +310,9 @@ def main():
     if cfg == 5:
         out["shard_cache"] = {kk: vv for kk, vv in g.info().items()
                               if kk.startswith("shard_") or kk in ("num_shards", "pinned_host_bytes", "device_bytes")}
+    note(f"{ms_per_step:.3f} ms per step")
     if not args.no_cpu_baseline:
+        note("oracle on the host cores")
         import oracle  # the cpu_baseline leg is the only user of the oracle here
         nq = min(args.cpu_queries or (384 if cfg <= 3 else 6), nf)
         so = w.seed_off[: nq + 1]

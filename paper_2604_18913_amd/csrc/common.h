@@ -320,7 +320,8 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
 long long max_chunk_rows(const logoskg_graph *g);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
-                       const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st);
+                       const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
+                       const lkg::RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st);
 void shard_info(const logoskg_graph *g, logoskg_graph_info *o);
 logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
                                logoskg_hop_stats *hs);

@@ -594,7 +594,8 @@ static inline unsigned blocks_for(long long threads, int block) {
 
 template <int W, bool MASK>
 static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
-                        const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st) {
+                        const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
+                        const RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st) {
     const size_t plane = (size_t)r->Epad * W;
     const unsigned long long *prev = r->levels + plane * (h - 1);
     unsigned long long *cur = r->levels + plane * h;
@@ -604,13 +605,13 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     if (ns > 0) {
         ProfScope ps(g->prof, KK_PUSH_SEG, st);
         k_push_seg<W, MASK><<<dim3(blocks_for(ns, 4)), dim3(256), 0, st>>>(
-            g->fr_seg, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
+            list_seg, ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
         g->prof.acc[KK_PUSH_SEG].units[0] += g->prof.on ? ns : 0;
     }
     if (nt > 0) {
         ProfScope ps(g->prof, KK_PUSH_TAIL, st);
         k_push_tail<W, MASK><<<dim3(blocks_for(nt * W, 256)), dim3(256), 0, st>>>(
-            g->fr_tail, g->d_ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
+            list_tail, ctr, g->out_off, g->row_begin, obj, rel, r->allow, prev, known, cur, act_cur);
         g->prof.acc[KK_PUSH_TAIL].units[0] += g->prof.on ? nt : 0;
     }
     if (!update) return;
@@ -668,27 +669,29 @@ static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool 
             else launch_pull<W, false, false>(g, r, h, false, hc, st);
         }
     } else {
-        if (r->has_mask) launch_push<W, true>(g, r, h, hc, g->out_obj, g->out_rel, true, st);
-        else launch_push<W, false>(g, r, h, hc, g->out_obj, g->out_rel, true, st);
+        if (r->has_mask) launch_push<W, true>(g, r, h, hc, g->out_obj, g->out_rel, true, g->fr_tail, g->fr_seg, g->d_ctr, st);
+        else launch_push<W, false>(g, r, h, hc, g->out_obj, g->out_rel, true, g->fr_tail, g->fr_seg, g->d_ctr, st);
     }
 }
 
-// Push of the lists the last census wrote, reading the edge arrays through the
-// given base pointers (a shard slot, shifted so that grouped edge indices apply).
+// Push of prepared work lists (short rows, segments; ctr[0], ctr[1] = their lengths on the
+// device), reading the edge arrays through the given base pointers (a shard slot, shifted so
+// that grouped edge indices apply).
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
-                       const int32_t *obj, const uint16_t *rel, bool update, hipStream_t st) {
+                       const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
+                       const RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st) {
     switch (r->W) {
         case 1:
-            if (r->has_mask) launch_push<1, true>(g, r, h, hc, obj, rel, update, st);
-            else launch_push<1, false>(g, r, h, hc, obj, rel, update, st);
+            if (r->has_mask) launch_push<1, true>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
+            else launch_push<1, false>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
             break;
         case 4:
-            if (r->has_mask) launch_push<4, true>(g, r, h, hc, obj, rel, update, st);
-            else launch_push<4, false>(g, r, h, hc, obj, rel, update, st);
+            if (r->has_mask) launch_push<4, true>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
+            else launch_push<4, false>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
             break;
         default:
-            if (r->has_mask) launch_push<16, true>(g, r, h, hc, obj, rel, update, st);
-            else launch_push<16, false>(g, r, h, hc, obj, rel, update, st);
+            if (r->has_mask) launch_push<16, true>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
+            else launch_push<16, false>(g, r, h, hc, obj, rel, update, list_tail, list_seg, ctr, st);
             break;
     }
 }

@@ -542,7 +542,7 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, in
         if (longrow) li = (a.row_pred && deg < (uint32_t)a.hub_min) ? (int)(a.long_index[ev] - a.row_base) : -2;
         long_li[vi] = li;
     }
-    __syncthreads();
+    if (!__syncthreads_or(visw != 0)) return;  // none of the slab's queries reached the macro tile
     {   // wave = (tile, word): lane qq gets the mask of tile entities query qq reached
         const int wt = wave >> 2, wj = wave & 3;
         unsigned long long x = u.stage[wt * 64 + v][wj], m = 0;

@@ -34,7 +34,7 @@ struct ShardSet {
     uint64_t tick = 0;
     hipStream_t copy_stream = nullptr;
     int64_t loads = 0, evictions = 0, hits = 0, bytes_h2d = 0;
-    unsigned long long *d_route = nullptr, *h_route = nullptr;  // [2*128] rows / edges per shard
+    unsigned long long *d_route = nullptr, *h_route = nullptr;  // [kRouteWords], see k_route_count
     // object-sorted triples (for predecessor edges): pinned host arrays, streamed through two
     // staging buffers in chunks of whole 64-entity tiles
     int32_t *h_in_sub = nullptr, *h_in_eid = nullptr;
@@ -48,31 +48,94 @@ struct ShardSet {
     int64_t in_bytes_h2d = 0;
 };
 
-// per-shard number of active subjects and of their triples (Algorithm 1, line 2)
-__global__ void k_route(const uint32_t *__restrict__ act, long long nwords,
-                        const uint32_t *__restrict__ out_off, const uint8_t *__restrict__ shard_of,
-                        unsigned long long *route) {
-    __shared__ unsigned int s_rows[128];
-    __shared__ unsigned long long s_edges[128];
-    if (threadIdx.x < 128) {
-        s_rows[threadIdx.x] = 0;
-        s_edges[threadIdx.x] = 0;
+// Routing of a hop (Algorithm 1, line 2) in two passes over the entities, whatever the number of
+// shards.  Layout of `route` (unsigned long long, kRouteWords entries):
+//   [0,128) active subject rows per shard   [128,256) their triples
+//   [256,384) rows of up to 32 triples       [384,512) 256-triple segments of the longer rows
+//   [512,640) first place of the shard in the short-row list   [640,768) in the segment list
+//   [768,1024) append cursors, two per shard (short rows, segments); after k_route_lists they are
+//              the counts the push kernels read
+constexpr int kRouteWords = 1024, kRouteBase = 512, kRouteCursor = 768;
+
+// The lanes of a wavefront that hold a subject of the same shard, one shard after the other.
+template <typename F>
+__device__ __forceinline__ void for_each_shard(bool has, int shard, F body) {
+    unsigned long long todo = __ballot(has);
+    while (todo) {  // wave-uniform
+        const int leader = __ffsll((long long)todo) - 1;
+        const int s0 = __shfl(shard, leader);
+        const bool mine = has && shard == s0;
+        todo &= ~__ballot(mine);
+        body(s0, mine, leader);
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_route_count(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__ out_off,
+              const uint8_t *__restrict__ shard_of, unsigned long long *route) {
+    __shared__ unsigned long long sh[4][128];
+    for (int i = threadIdx.x; i < 512; i += blockDim.x) sh[i >> 7][i & 127] = 0;
+    __syncthreads();
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long base = (long long)blockIdx.x * blockDim.x; base < E; base += stride) {  // block-uniform trip count
+        const long long e = base + threadIdx.x;
+        uint32_t d = 0;
+        int shard = 0;
+        if (e < E && ((act[e >> 5] >> (e & 31)) & 1u)) {
+            d = out_off[e + 1] - out_off[e];
+            if (d) shard = shard_of[e] & 127;
+        }
+        const bool tail = d > 0 && d <= (uint32_t)kTailMaxDegree;
+        const long long segs = d > (uint32_t)kTailMaxDegree ? (d + kPushSegment - 1) / kPushSegment : 0;
+        for_each_shard(d > 0, shard, [&](int s0, bool mine, int leader) {
+            const long long rows = __popcll(__ballot(mine)), tails = __popcll(__ballot(mine && tail));
+            const long long edges = wave_sum(mine ? (long long)d : 0), sg = wave_sum(mine ? segs : 0);
+            if (lane() == leader) {
+                atomicAdd(&sh[0][s0], (unsigned long long)rows);
+                atomicAdd(&sh[1][s0], (unsigned long long)edges);
+                if (tails) atomicAdd(&sh[2][s0], (unsigned long long)tails);
+                if (sg) atomicAdd(&sh[3][s0], (unsigned long long)sg);
+            }
+        });
     }
     __syncthreads();
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    uint32_t word = i < nwords ? act[i] : 0u;
-    for (uint32_t m = word; m; m &= m - 1) {
-        long long e = i * 32 + (__ffs((int)m) - 1);
-        uint32_t d = out_off[e + 1] - out_off[e];
-        if (d == 0) continue;
-        int s = shard_of[e];
-        atomicAdd(&s_rows[s & 127], 1u);
-        atomicAdd(&s_edges[s & 127], (unsigned long long)d);
-    }
-    __syncthreads();
-    if (threadIdx.x < 128) {
-        if (s_rows[threadIdx.x]) atomicAdd(&route[threadIdx.x], (unsigned long long)s_rows[threadIdx.x]);
-        if (s_edges[threadIdx.x]) atomicAdd(&route[128 + threadIdx.x], s_edges[threadIdx.x]);
+    for (int i = threadIdx.x; i < 512; i += blockDim.x)
+        if (sh[i >> 7][i & 127]) atomicAdd(&route[i], sh[i >> 7][i & 127]);
+}
+
+__global__ void __launch_bounds__(256)
+k_route_lists(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__ out_off,
+              const uint32_t *__restrict__ row_begin, const uint8_t *__restrict__ shard_of,
+              unsigned long long *route, int32_t *list_tail, RowSegment *list_seg) {
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long base = (long long)blockIdx.x * blockDim.x; base < E; base += stride) {
+        const long long e = base + threadIdx.x;
+        uint32_t d = 0;
+        int shard = 0;
+        if (e < E && ((act[e >> 5] >> (e & 31)) & 1u)) {
+            d = out_off[e + 1] - out_off[e];
+            if (d) shard = shard_of[e] & 127;
+        }
+        const bool tail = d > 0 && d <= (uint32_t)kTailMaxDegree;
+        const int segs = d > (uint32_t)kTailMaxDegree ? (int)((d + kPushSegment - 1) / kPushSegment) : 0;
+        for_each_shard(d > 0, shard, [&](int s0, bool mine, int leader) {
+            const unsigned long long tmask = __ballot(mine && tail);
+            int ts;
+            const int ps = wave_excl_scan(mine ? segs : 0, ts);
+            unsigned long long bt = 0, bs = 0;
+            if (lane() == leader) {
+                if (tmask) bt = atomicAdd(&route[kRouteCursor + 2 * s0], (unsigned long long)__popcll(tmask));
+                if (ts) bs = atomicAdd(&route[kRouteCursor + 2 * s0 + 1], (unsigned long long)ts);
+            }
+            bt = shfl64(bt, leader) + route[kRouteBase + s0];
+            bs = shfl64(bs, leader) + route[kRouteBase + 128 + s0];
+            if (mine && tail) list_tail[bt + __popcll(tmask & ((1ull << lane()) - 1ull))] = (int32_t)e;
+            if (mine && segs) {
+                const uint32_t lo = row_begin[e];
+                for (int i = 0; i < segs; ++i)
+                    list_seg[bs + ps + i] = RowSegment{(int32_t)e, lo + (uint32_t)i * kPushSegment};
+            }
+        });
     }
 }
 
@@ -352,8 +415,8 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
     }
     LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
     LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
-    LKG_HIP(hipMalloc((void **)&ss->d_route, 256 * sizeof(unsigned long long)));
-    if (hipHostMalloc((void **)&ss->h_route, 256 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
+    LKG_HIP(hipMalloc((void **)&ss->d_route, 1024 * sizeof(unsigned long long)));
+    if (hipHostMalloc((void **)&ss->h_route, 1024 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
         return LOGOSKG_ENOMEM;
     }
@@ -406,17 +469,36 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
     if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
     const long long nwords = r->Epad / 32;
     const uint32_t *act_prev = r->act + (size_t)nwords * (h - 1);
-    // routing: which shards have an active subject
-    LKG_HIP(hipMemsetAsync(ss->d_route, 0, 256 * sizeof(unsigned long long), st));
-    k_route<<<dim3((unsigned)((nwords + 255) / 256)), dim3(256), 0, st>>>(act_prev, nwords, g->out_off,
-                                                                          g->shard_of_dev, ss->d_route);
+    const unsigned nb = (unsigned)std::min<long long>(1024, std::max<long long>(1, ((long long)g->E + 255) / 256));
+    // routing: rows, triples and list sizes of every shard in one pass
+    LKG_HIP(hipMemsetAsync(ss->d_route, 0, kRouteWords * sizeof(unsigned long long), st));
+    {
+        ProfScope ps(g->prof, KK_CENSUS, st);
+        k_route_count<<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, g->shard_of_dev, ss->d_route);
+    }
     LKG_HIP(hipGetLastError());
-    LKG_HIP(hipMemcpyAsync(ss->h_route, ss->d_route, 256 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    LKG_HIP(hipMemcpyAsync(ss->h_route, ss->d_route, 512 * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     LKG_HIP(hipStreamSynchronize(st));
     std::vector<int> active;
-    for (int s = 0; s < ss->n; ++s)
+    unsigned long long tail_run = 0, seg_run = 0;
+    for (int s = 0; s < ss->n; ++s) {
         if (ss->h_route[s] > 0) active.push_back(s);
+        ss->h_route[kRouteBase + s] = tail_run;
+        ss->h_route[kRouteBase + 128 + s] = seg_run;
+        tail_run += ss->h_route[256 + s];
+        seg_run += ss->h_route[384 + s];
+    }
     hs->shards_touched = (int)active.size();
+    if (active.empty()) return LOGOSKG_OK;
+    // the work lists of all shards, shard after shard, in a second pass
+    LKG_HIP(hipMemcpyAsync(ss->d_route + kRouteBase, ss->h_route + kRouteBase, 256 * sizeof(unsigned long long),
+                           hipMemcpyHostToDevice, st));
+    {
+        ProfScope ps(g->prof, KK_CENSUS, st);
+        k_route_lists<<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, g->row_begin, g->shard_of_dev,
+                                                      ss->d_route, g->fr_tail, g->fr_seg);
+    }
+    LKG_HIP(hipGetLastError());
     std::vector<int> slot_of((size_t)active.size(), -1);
     for (size_t i = 0; i < active.size(); ++i) {
         const int shard = active[i];
@@ -426,13 +508,14 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
         if (i + 1 < active.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
             LKG_TRY(acquire(g, ss, active[i + 1], st, &slot_of[i + 1]));
         const int slot = slot_of[i];
-        LKG_TRY(census(g, r, h - 1, shard, true, st));
-        unsigned long long hc[C_TOTAL];
-        memcpy(hc, g->h_ctr, sizeof(hc));
+        unsigned long long hc[C_TOTAL] = {};
+        hc[C_NTAIL] = ss->h_route[256 + shard];
+        hc[C_NSEG] = ss->h_route[384 + shard];
         LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[slot], 0));
         const int64_t b = ss->edge_begin[shard];
-        launch_push_lists(g, r, h, hc, ss->slot_obj[slot] - b, ss->slot_rel[slot] - b,
-                          i + 1 == active.size(), st);
+        launch_push_lists(g, r, h, hc, ss->slot_obj[slot] - b, ss->slot_rel[slot] - b, i + 1 == active.size(),
+                          g->fr_tail + ss->h_route[kRouteBase + shard], g->fr_seg + ss->h_route[kRouteBase + 128 + shard],
+                          ss->d_route + kRouteCursor + 2 * shard, st);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->slot_idle[slot], st));
     }
