@@ -103,37 +103,76 @@ k_route_count(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__res
         if (sh[i >> 7][i & 127]) atomicAdd(&route[i], sh[i >> 7][i & 127]);
 }
 
+// Every block owns a contiguous run of entities: it counts its list entries per shard, reserves
+// their places with one atomic per shard and list, and then writes them (the run is read twice;
+// an atomic per wavefront and shard on sixteen global cursors would serialise).
 __global__ void __launch_bounds__(256)
 k_route_lists(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__ out_off,
               const uint32_t *__restrict__ row_begin, const uint8_t *__restrict__ shard_of,
               unsigned long long *route, int32_t *list_tail, RowSegment *list_seg) {
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long base = (long long)blockIdx.x * blockDim.x; base < E; base += stride) {
-        const long long e = base + threadIdx.x;
-        uint32_t d = 0;
-        int shard = 0;
-        if (e < E && ((act[e >> 5] >> (e & 31)) & 1u)) {
+    __shared__ unsigned int cnt[2][128];           // entries of this block per shard: short rows, segments
+    __shared__ unsigned long long first[2][128];   // first place of the block's entries in the two lists
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) cnt[i >> 7][i & 127] = 0;
+    __syncthreads();
+    const long long chunk = (((long long)E + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const long long begin = (long long)blockIdx.x * chunk, end = min((long long)E, begin + chunk);
+    auto classify = [&](long long e, uint32_t &d, int &shard) {
+        d = 0;
+        shard = 0;
+        if (e < end && ((act[e >> 5] >> (e & 31)) & 1u)) {
             d = out_off[e + 1] - out_off[e];
             if (d) shard = shard_of[e] & 127;
         }
+    };
+    for (long long base = begin; base < end; base += blockDim.x) {  // block-uniform trip count
+        uint32_t d;
+        int shard;
+        classify(base + threadIdx.x, d, shard);
+        const bool tail = d > 0 && d <= (uint32_t)kTailMaxDegree;
+        const int segs = d > (uint32_t)kTailMaxDegree ? (int)((d + kPushSegment - 1) / kPushSegment) : 0;
+        for_each_shard(d > 0, shard, [&](int s0, bool mine, int leader) {
+            const int tails = __popcll(__ballot(mine && tail));
+            const int sg = (int)wave_sum(mine ? (long long)segs : 0);
+            if (lane() == leader) {
+                if (tails) atomicAdd(&cnt[0][s0], (unsigned)tails);
+                if (sg) atomicAdd(&cnt[1][s0], (unsigned)sg);
+            }
+        });
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) {
+        const int which = i >> 7, s0 = i & 127;
+        unsigned long long f = 0;
+        if (cnt[which][s0])
+            f = route[kRouteBase + 128 * which + s0] +
+                atomicAdd(&route[kRouteCursor + 2 * s0 + which], (unsigned long long)cnt[which][s0]);
+        first[which][s0] = f;
+        cnt[which][s0] = 0;  // from here on: entries written so far
+    }
+    __syncthreads();
+    for (long long base = begin; base < end; base += blockDim.x) {
+        const long long e = base + threadIdx.x;
+        uint32_t d;
+        int shard;
+        classify(e, d, shard);
         const bool tail = d > 0 && d <= (uint32_t)kTailMaxDegree;
         const int segs = d > (uint32_t)kTailMaxDegree ? (int)((d + kPushSegment - 1) / kPushSegment) : 0;
         for_each_shard(d > 0, shard, [&](int s0, bool mine, int leader) {
             const unsigned long long tmask = __ballot(mine && tail);
             int ts;
             const int ps = wave_excl_scan(mine ? segs : 0, ts);
-            unsigned long long bt = 0, bs = 0;
+            unsigned bt = 0, bs = 0;
             if (lane() == leader) {
-                if (tmask) bt = atomicAdd(&route[kRouteCursor + 2 * s0], (unsigned long long)__popcll(tmask));
-                if (ts) bs = atomicAdd(&route[kRouteCursor + 2 * s0 + 1], (unsigned long long)ts);
+                if (tmask) bt = atomicAdd(&cnt[0][s0], (unsigned)__popcll(tmask));
+                if (ts) bs = atomicAdd(&cnt[1][s0], (unsigned)ts);
             }
-            bt = shfl64(bt, leader) + route[kRouteBase + s0];
-            bs = shfl64(bs, leader) + route[kRouteBase + 128 + s0];
-            if (mine && tail) list_tail[bt + __popcll(tmask & ((1ull << lane()) - 1ull))] = (int32_t)e;
+            const unsigned long long at = first[0][s0] + (unsigned)__shfl((int)bt, leader);
+            const unsigned long long as = first[1][s0] + (unsigned)__shfl((int)bs, leader);
+            if (mine && tail) list_tail[at + __popcll(tmask & ((1ull << lane()) - 1ull))] = (int32_t)e;
             if (mine && segs) {
                 const uint32_t lo = row_begin[e];
                 for (int i = 0; i < segs; ++i)
-                    list_seg[bs + ps + i] = RowSegment{(int32_t)e, lo + (uint32_t)i * kPushSegment};
+                    list_seg[as + ps + i] = RowSegment{(int32_t)e, lo + (uint32_t)i * kPushSegment};
             }
         });
     }
