@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--k", type=int, default=0, help="hops (config 3 sweeps 1..4; 0 = the workload's own)")
     ap.add_argument("--fetch-queries", type=int, default=0,
                     help="fetch the lists of the first N queries only (0 = all; configs 4 and 5 default to 64)")
+    ap.add_argument("--resident-shards", type=int, default=0,
+                    help="config 5: capacity of the shard cache in shards (the paper's n); 0 = the byte budget only")
     ap.add_argument("--mode", choices=["minhop", "walk"], default="minhop",
                     help="minhop (default): the headline path; walk: Eq. 4 iterated without the visited set "
                          "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query")
@@ -118,7 +120,7 @@ def main():
         w.seeds = w.seeds[: w.seed_off[-1]]
     else:
         w = kggen.config5(args.scale)
-        graph_opts = dict(num_shards=8, hbm_shard_budget_bytes=64 << 30)
+        graph_opts = dict(num_shards=8, hbm_shard_budget_bytes=64 << 30, max_resident_shards=args.resident_shards)
     if args.k:
         w.k = args.k
     t_gen = time.time() - t0
@@ -274,7 +276,8 @@ def main():
     if cfg == 4:
         workload += " (first of four 1,024-query batches)"
     if cfg == 5:
-        workload += " (8 shards, 64 GB shard budget, shards cached from pinned host memory)"
+        workload += " (8 shards, 64 GB shard budget, shards cached from pinned host memory" + \
+                    (f", at most {args.resident_shards} resident" if args.resident_shards else "") + ")"
     out = {
         "metric": metric,
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

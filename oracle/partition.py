@@ -72,5 +72,11 @@ def shard_accesses(P, subj, num_entities, k, entity, hop):
         front = front[deg[front] > 0]
         if front.size == 0:
             break
-        seq.extend(sorted(set(int(x) for x in P[front])))
+        order = sorted(set(int(x) for x in P[front]))
+        # Alg. 1 does not fix the order in which a hop visits its shards; the reading taken is
+        # ascending on odd hops and descending on even ones, so that consecutive hops share the
+        # shards at the turning point and a small LRU cache does not thrash
+        if h % 2 == 0:
+            order.reverse()
+        seq.extend(order)
     return seq

@@ -529,6 +529,10 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
     }
     hs->shards_touched = (int)active.size();
     if (active.empty()) return LOGOSKG_OK;
+    // Alg. 1 leaves the order of the shards open.  Even hops go down, odd hops up: the shards a
+    // hop ends with are the ones the next hop begins with, so a cache smaller than the graph
+    // still hits (a fixed order would evict every shard just before its next use).
+    if ((h & 1) == 0) std::reverse(active.begin(), active.end());
     // the work lists of all shards, shard after shard, in a second pass
     LKG_HIP(hipMemcpyAsync(ss->d_route + kRouteBase, ss->h_route + kRouteBase, 256 * sizeof(unsigned long long),
                            hipMemcpyHostToDevice, st));
