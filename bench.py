@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-queries", type=int, default=0, help="0 = 384 for configs 1-3, 6 for configs 4 and 5")
+    ap.add_argument("--cpu-queries", type=int, default=0, help="0 = 512 for configs 1-3, 6 for configs 4 and 5")
     ap.add_argument("--serial-fetch", action="store_true",
                     help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
     ap.add_argument("--config", type=int, choices=[1, 2, 3, 4, 5], default=2,
@@ -317,7 +317,7 @@ def main():
     if not args.no_cpu_baseline:
         note("oracle on the host cores")
         import oracle  # the cpu_baseline leg is the only user of the oracle here
-        nq = min(args.cpu_queries or (384 if cfg <= 3 else 6), nf)
+        nq = min(args.cpu_queries or (512 if cfg <= 3 else 6), nf)
         so = w.seed_off[: nq + 1]
         sd = w.seeds[: so[-1]]
         mk = None if w.rel_mask is None else w.rel_mask[:nq]

@@ -129,68 +129,78 @@ __device__ __forceinline__ long long super_start(const FillArgs &a, long long st
 // keeps its word of all 16 tiles in registers (visited and the bit-sliced hop
 // number), and for one query at a time compacts the reached entities into LDS,
 // then streams them out with full-width stores.
-template <int W, int NB>
+// NB = words of the bit-sliced hop number (0: entity ids only); TILES = tiles per block: a
+// whole super tile, or half of one where the registers of a whole one would not leave room for
+// two blocks per CU.
+template <int W, int NB, int TILES>
 __global__ void __launch_bounds__(64 * W) k_lists(FillArgs a) {
-    constexpr int Qp = 64 * W;
+    constexpr int Qp = 64 * W, NBX = NB > 0 ? NB : 1;
     __shared__ unsigned long long stage[64][W + 1];
-    __shared__ uint16_t s_ent[W][kSuperTiles * 64];
-    __shared__ uint8_t s_hop[W][kSuperTiles * 64];
-    const long long st = blockIdx.x;
+    __shared__ uint16_t s_ent[W][TILES * 64];
+    __shared__ uint8_t s_hop[NB > 0 ? W : 1][TILES * 64];
+    const long long first_tile = (long long)blockIdx.x * TILES;
+    const long long st = first_tile / kSuperTiles;
     const int wave = threadIdx.x >> 6, v = lane();
-    unsigned long long visw[kSuperTiles];
-    unsigned long long hb[NB][kSuperTiles];
+    unsigned long long visw[TILES];
+    unsigned long long hb[NBX][TILES];
 #pragma unroll
-    for (int i = 0; i < kSuperTiles; ++i) {
-        long long tile = st * kSuperTiles + i;
+    for (int i = 0; i < TILES; ++i) {
+        long long tile = first_tile + i;
         visw[i] = 0;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) hb[b][i] = 0;
+        for (int b = 0; b < NBX; ++b) hb[b][i] = 0;
         if (tile < a.ntiles) {  // block-uniform
             visw[i] = stage_word<W>(stage, a.visited + (size_t)tile * 64 * W, wave);
-            for (int h = 1; h <= a.k; ++h) {  // hop number of each bit, bit-sliced over NB words
-                unsigned long long x =
-                    stage_word<W>(stage, a.levels + (size_t)h * a.plane + (size_t)tile * 64 * W, wave);
+            if constexpr (NB > 0)
+                for (int h = 1; h <= a.k; ++h) {  // hop number of each bit, bit-sliced over NB words
+                    unsigned long long x =
+                        stage_word<W>(stage, a.levels + (size_t)h * a.plane + (size_t)tile * 64 * W, wave);
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    if ((h >> b) & 1) hb[b][i] |= x;
-            }
+                    for (int b = 0; b < NB; ++b)
+                        if ((h >> b) & 1) hb[b][i] |= x;
+                }
         }
     }
     unsigned long long present = 0;
 #pragma unroll
-    for (int i = 0; i < kSuperTiles; ++i) present |= visw[i];
+    for (int i = 0; i < TILES; ++i) present |= visw[i];
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) present |= shfl_xor64(present, m);
     present &= range_bits(a.q0, a.q1, wave);
-    // lane qq keeps the list position where query 64*wave+qq continues in this super tile
+    // lane qq keeps the list position where query 64*wave+qq continues in this block's tiles
     long long mybase = 0;
-    if ((present >> v) & 1ull) mybase = super_start(a, st, Qp, wave * 64 + v);
+    if ((present >> v) & 1ull) {
+        mybase = super_start(a, st, Qp, wave * 64 + v);
+        if (TILES < kSuperTiles) mybase += a.tile_base[(size_t)first_tile * Qp + wave * 64 + v];
+    }
     uint16_t *ent = s_ent[wave];
-    uint8_t *hp = s_hop[wave];
+    uint8_t *hp = s_hop[NB > 0 ? wave : 0];
     while (present) {
         const int qq = __ffsll((long long)present) - 1;
         present &= present - 1;
         int cnt = 0;
 #pragma unroll
-        for (int i = 0; i < kSuperTiles; ++i) {
+        for (int i = 0; i < TILES; ++i) {
             bool bit = (visw[i] >> qq) & 1ull;
             unsigned long long m = __ballot(bit);
             if (bit) {
                 int pos = cnt + __popcll(m & ((1ull << v) - 1ull));
-                int hv = 0;
-#pragma unroll
-                for (int b = 0; b < NB; ++b) hv |= (int)((hb[b][i] >> qq) & 1ull) << b;
                 ent[pos] = (uint16_t)(i * 64 + v);
-                hp[pos] = (uint8_t)hv;
+                if constexpr (NB > 0) {
+                    int hv = 0;
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) hv |= (int)((hb[b][i] >> qq) & 1ull) << b;
+                    hp[pos] = (uint8_t)hv;
+                }
             }
             cnt += __popcll(m);
         }
         __builtin_amdgcn_wave_barrier();
         const long long base = (long long)shfl64((unsigned long long)mybase, qq);
-        const int e0 = (int)(st * (kSuperTiles * 64));
+        const int e0 = (int)(first_tile * 64);
         for (int p = v; p < cnt; p += 64) {
             a.entity[base + p] = e0 + ent[p];
-            if (a.hop) a.hop[base + p] = hp[p];
+            if constexpr (NB > 0) a.hop[base + p] = hp[p];
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -879,14 +889,16 @@ logoskg_status prepare_row_pred(logoskg_graph *g, hipStream_t st) {
 
 template <int W>
 static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
-    const long long nsuper = (a.ntiles + kSuperTiles - 1) / kSuperTiles;
+    constexpr int TILES = W == 16 ? kSuperTiles / 2 : kSuperTiles;
+    const long long nblocks = (a.ntiles + TILES - 1) / TILES;
     ProfScope ps(prof, KK_LISTS, st);
     int nb = 1;
     while ((1 << nb) <= a.k) ++nb;
-    dim3 grid((unsigned)nsuper), block(64 * W);
-    if (nb <= 2) k_lists<W, 2><<<grid, block, 0, st>>>(a);
-    else if (nb <= 4) k_lists<W, 4><<<grid, block, 0, st>>>(a);
-    else k_lists<W, 8><<<grid, block, 0, st>>>(a);
+    dim3 grid((unsigned)nblocks), block(64 * W);
+    if (!a.hop) k_lists<W, 0, TILES><<<grid, block, 0, st>>>(a);
+    else if (nb <= 2) k_lists<W, 2, TILES><<<grid, block, 0, st>>>(a);
+    else if (nb <= 4) k_lists<W, 4, TILES><<<grid, block, 0, st>>>(a);
+    else k_lists<W, 8, TILES><<<grid, block, 0, st>>>(a);
 }
 
 // True when the 16-word tile kernel can serve this launch (it then can also write the entity and
