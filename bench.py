@@ -138,6 +138,20 @@ def main():
     nf = args.fetch_queries or (64 if cfg >= 4 else Q)   # queries whose lists are fetched
     nf = min(nf, Q)
 
+    # practical HBM ceiling of this machine in this run: a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB)
+    src = torch.ones(1 << 27, dtype=torch.int64, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_copy_gbps = 10 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    note(f"1 GiB device copy: {stream_copy_gbps:.0f} GB/s (read + write)")
+
     if args.pmc_calibration:
         src = torch.ones(1 << 27, dtype=torch.int64, device=dev)   # 1 GiB
         dst = torch.empty_like(src)
@@ -298,10 +312,13 @@ def main():
                       "algorithmic_GBps": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
                       "hbm_frac": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if expansion_ms else None,
                       "gteps_logical": round(logical_edges / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
+                      "frac_of_stream_copy": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9 / stream_copy_gbps, 4)
+                      if expansion_ms else None,
                       "counter_GBps": round(expansion_measured / (expansion_ms * 1e-3) / 1e9, 1)
                       if expansion_measured and expansion_ms else None,
                       "counter_hbm_frac": round(expansion_measured / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
                       if expansion_measured and expansion_ms else None},
+        "stream_copy_GBps": round(stream_copy_gbps, 1),
         "roofline": roofline,
         "kernels": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for n, v in kernels.items()},

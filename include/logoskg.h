@@ -61,7 +61,10 @@ typedef struct {
     int32_t hub_min_degree;          /* rows with at least this many edges take the
                                         block-per-row kernels; 0 = default (1024).  Never changes
                                         results.                                                 */
-    int32_t reserved;
+    int32_t host_build;              /* 0: a resident graph is sorted on the GPU (the triples
+                                        are copied to HBM first).  1: counting sorts on the host.
+                                        Both give the same arrays.  Sharded graphs are always
+                                        sorted on the host.                                      */
 } logoskg_build_opts;
 
 /*

@@ -32,7 +32,7 @@ class _BuildOpts(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("device", ctypes.c_int32),
                 ("num_shards", ctypes.c_int32), ("max_resident_shards", ctypes.c_int32),
                 ("hbm_shard_budget_bytes", ctypes.c_uint64), ("hub_min_degree", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("host_build", ctypes.c_int32)]
 
 
 class _QueryBatch(ctypes.Structure):
@@ -248,7 +248,7 @@ class Graph:
 
     def __init__(self, subj, rel, obj, num_entities: int, num_relations: int, device: int = 0,
                  num_shards: int = 0, max_resident_shards: int = 0, hbm_shard_budget_bytes: int = 0,
-                 hub_min_degree: int = 0):
+                 hub_min_degree: int = 0, host_build: bool = False):
         lib = _load()
         torch = _torch()
         if not _NP:
@@ -261,7 +261,7 @@ class Graph:
         if not (subj.shape == rel.shape == obj.shape and subj.ndim == 1):
             raise ValueError("subj, rel, obj must be 1-D arrays of equal length")
         opts = _BuildOpts(ctypes.sizeof(_BuildOpts), device, num_shards, max_resident_shards,
-                          hbm_shard_budget_bytes, hub_min_degree, 0)
+                          hbm_shard_budget_bytes, hub_min_degree, 1 if host_build else 0)
         h = ctypes.c_void_p()
         _check(lib.logoskg_build(subj.ctypes.data_as(ctypes.c_void_p), rel.ctypes.data_as(ctypes.c_void_p),
                                  obj.ctypes.data_as(ctypes.c_void_p), subj.shape[0], num_entities,

@@ -1,6 +1,8 @@
 // logoskg_build: triple list -> device CSR forms of the SUB and OBJ incidence
-// matrices (paper Sec. 3.2, Eq. 1-3) plus degree classes.  Host-side counting
-// sorts, then one upload.
+// matrices (paper Sec. 3.2, Eq. 1-3) plus degree classes.  A resident graph is
+// sorted on the GPU (build_device.hip); the host counting sorts below serve
+// sharded graphs, whose edge arrays stay in host memory, and the host_build
+// option.
 #include <algorithm>
 #include <numeric>
 
@@ -170,7 +172,8 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         set_error("bad build options");
         return LOGOSKG_EINVAL;
     }
-    for (int64_t t = 0; t < T; ++t) {
+    const bool device_build = o.num_shards <= 1 && !o.host_build;  // else ids are checked here
+    for (int64_t t = 0; !device_build && t < T; ++t) {
         if ((uint32_t)subj[t] >= (uint32_t)E || (uint32_t)obj[t] >= (uint32_t)E ||
             (uint32_t)rel[t] >= (uint32_t)R) {
             set_error("triple %lld = (%d, %d, %d) is out of range", (long long)t, subj[t], rel[t], obj[t]);
@@ -195,15 +198,40 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     logoskg_status st = LOGOSKG_OK;
     auto fail = [&](logoskg_status s) { logoskg_graph_free(g); return s; };
     try {
+        // row classes of the object-sorted CSR (pull and predecessor work lists)
+        auto object_row_classes = [&](const std::vector<uint32_t> &ioff) -> logoskg_status {
+            std::vector<int32_t> tail, multi, longer;
+            std::vector<RowSegment> seg;
+            classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
+            g->in_rows.n_tail = (int64_t)tail.size();
+            g->in_rows.n_seg = (int64_t)seg.size();
+            g->in_rows.n_multi = (int64_t)multi.size();
+            g->in_rows.n_long = (int64_t)longer.size();
+            LKG_TRY(upload(&g->in_rows.tail, tail, &g->static_bytes));
+            LKG_TRY(upload(&g->in_rows.seg, seg, &g->static_bytes));
+            LKG_TRY(upload(&g->in_rows.multi, multi, &g->static_bytes));
+            LKG_TRY(upload(&g->in_rows.longrows, longer, &g->static_bytes));
+            return LOGOSKG_OK;
+        };
+        auto subject_row_counts = [&](const std::vector<uint32_t> &ooff) {
+            for (int32_t e = 0; e < E; ++e) {
+                uint32_t d = ooff[(size_t)e + 1] - ooff[e];
+                if (d > 0) g->n_out_rows++;
+                if (d >= (uint32_t)g->hub_min) g->n_out_hubs++;
+            }
+        };
+        if (device_build) {
+            std::vector<uint32_t> ooff, ioff;
+            if ((st = build_csr_on_device(g, subj, rel, obj, &ooff, &ioff)) != LOGOSKG_OK) return fail(st);
+            g->row_begin = g->out_off;
+            subject_row_counts(ooff);
+            if ((st = object_row_classes(ioff)) != LOGOSKG_OK) return fail(st);
+        } else {
         // out-degrees are needed by both the resident and the sharded form
         std::vector<uint32_t> ooff((size_t)E + 1, 0);
         for (int64_t t = 0; t < T; ++t) ooff[(size_t)subj[t] + 1]++;
-        for (int32_t e = 0; e < E; ++e) {
-            uint32_t d = ooff[(size_t)e + 1];
-            if (d > 0) g->n_out_rows++;
-            if (d >= (uint32_t)g->hub_min) g->n_out_hubs++;
-            ooff[(size_t)e + 1] += ooff[e];
-        }
+        for (int32_t e = 0; e < E; ++e) ooff[(size_t)e + 1] += ooff[e];
+        subject_row_counts(ooff);
         if ((st = upload(&g->out_off, ooff, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
 
         if (g->num_shards > 1) {
@@ -239,18 +267,9 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
                 if ((st = upload(&g->in_sub, isub, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_rel, irel, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
                 if ((st = upload(&g->in_eid, ieid, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                std::vector<int32_t> tail, multi, longer;
-                std::vector<RowSegment> seg;
-                classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
-                g->in_rows.n_tail = (int64_t)tail.size();
-                g->in_rows.n_seg = (int64_t)seg.size();
-                g->in_rows.n_multi = (int64_t)multi.size();
-                g->in_rows.n_long = (int64_t)longer.size();
-                if ((st = upload(&g->in_rows.tail, tail, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                if ((st = upload(&g->in_rows.seg, seg, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                if ((st = upload(&g->in_rows.multi, multi, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
-                if ((st = upload(&g->in_rows.longrows, longer, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+                if ((st = object_row_classes(ioff)) != LOGOSKG_OK) return fail(st);
             }
+        }
         }
     } catch (const std::bad_alloc &) {
         set_error("out of host memory while sorting %lld triples", (long long)T);

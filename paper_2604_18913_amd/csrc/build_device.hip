@@ -1,0 +1,170 @@
+// Device-side part of logoskg_build for a resident graph: the two stable sorts
+// of the triple list (by subject for SUB, by object for OBJ, Sec. 3.2, Eq. 1-3)
+// run on the GPU.  A least-significant-digit radix sort of (key, triple index)
+// pairs is stable, so triple indices ascend inside a row exactly as in the host
+// counting sort; the row offsets come from a histogram and a prefix sum.  The
+// sort and the scan are rocPRIM's device-wide primitives; everything else is a
+// handful of streaming kernels.
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
+
+#include "common.h"
+
+namespace lkg {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+inline unsigned grid_for(int64_t n) { return (unsigned)std::max<int64_t>(1, (n + kBlock - 1) / kBlock); }
+
+// index of the first triple with an id out of range (INT64_MAX-like sentinel = none)
+__global__ void k_check_triples(const int32_t *__restrict__ subj, const int32_t *__restrict__ rel,
+                                const int32_t *__restrict__ obj, long long T, int32_t E, int32_t R,
+                                unsigned long long *first_bad) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    if ((uint32_t)subj[t] >= (uint32_t)E || (uint32_t)obj[t] >= (uint32_t)E || (uint32_t)rel[t] >= (uint32_t)R)
+        atomicMin(first_bad, (unsigned long long)t);
+}
+
+__global__ void k_iota(uint32_t *v, long long n) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) v[i] = (uint32_t)i;
+}
+
+// cnt[key + 1] += 1: after an inclusive prefix sum cnt[e] is the first place of row e
+__global__ void k_degrees(const int32_t *__restrict__ key, long long T, uint32_t *cnt) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) atomicAdd(&cnt[key[t] + 1], 1u);
+}
+
+__global__ void k_gather_sub_rows(const uint32_t *__restrict__ eid, long long T, const int32_t *__restrict__ obj,
+                                  const int32_t *__restrict__ rel, int32_t *out_obj, uint16_t *out_rel) {
+    long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= T) return;
+    const uint32_t t = eid[p];
+    out_obj[p] = obj[t];
+    out_rel[p] = (uint16_t)rel[t];
+}
+
+__global__ void k_gather_obj_rows(const uint32_t *__restrict__ eid, long long T, const int32_t *__restrict__ subj,
+                                  const int32_t *__restrict__ rel, int32_t *in_sub, uint16_t *in_rel,
+                                  int32_t *in_eid) {
+    long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= T) return;
+    const uint32_t t = eid[p];
+    in_sub[p] = subj[t];
+    in_rel[p] = (uint16_t)rel[t];
+    in_eid[p] = (int32_t)t;
+}
+
+struct Scratch {  // device temporaries, freed on every way out
+    std::vector<void *> ptrs;
+    ~Scratch() {
+        for (void *p : ptrs)
+            if (p) (void)hipFree(p);
+    }
+    template <typename T>
+    logoskg_status get(T **p, size_t n) {
+        LKG_HIP(hipMalloc((void **)p, std::max<size_t>(n, 1) * sizeof(T)));
+        ptrs.push_back(*p);
+        return LOGOSKG_OK;
+    }
+};
+
+// sorted_eid = triple indices in (key, index) order; off = row offsets of that order
+logoskg_status sort_by(const int32_t *d_key, int64_t T, int32_t E, unsigned key_bits, uint32_t *d_iota,
+                       uint32_t *d_keys_out, uint32_t *d_sorted_eid, uint32_t *d_off, void *d_tmp, size_t tmp_bytes) {
+    LKG_HIP(hipMemsetAsync(d_off, 0, ((size_t)E + 1) * sizeof(uint32_t), nullptr));
+    if (T > 0) {
+        k_degrees<<<dim3(grid_for(T)), dim3(kBlock)>>>(d_key, T, d_off);
+        size_t need = tmp_bytes;
+        LKG_HIP(rocprim::radix_sort_pairs(d_tmp, need, reinterpret_cast<const uint32_t *>(d_key), d_keys_out, d_iota,
+                                          d_sorted_eid, (size_t)T, 0u, key_bits));
+    }
+    size_t need = tmp_bytes;
+    LKG_HIP(rocprim::inclusive_scan(d_tmp, need, d_off, d_off, (size_t)E + 1, rocprim::plus<uint32_t>()));
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}
+
+}  // namespace
+
+// Fills g->out_off/out_obj/out_rel and g->in_off/in_sub/in_rel/in_eid from host triple arrays;
+// returns the two offset arrays to the host as well (row classes are built there).
+logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                                   std::vector<uint32_t> *ooff, std::vector<uint32_t> *ioff) {
+    const int64_t T = g->T;
+    const int32_t E = g->E;
+    Scratch tmp;
+    int32_t *d_subj = nullptr, *d_rel = nullptr, *d_obj = nullptr;
+    uint32_t *d_iota = nullptr, *d_keys = nullptr, *d_eid = nullptr;
+    unsigned long long *d_bad = nullptr;
+    LKG_TRY(tmp.get(&d_subj, (size_t)T));
+    LKG_TRY(tmp.get(&d_rel, (size_t)T));
+    LKG_TRY(tmp.get(&d_obj, (size_t)T));
+    LKG_TRY(tmp.get(&d_iota, (size_t)T));
+    LKG_TRY(tmp.get(&d_keys, (size_t)T));
+    LKG_TRY(tmp.get(&d_eid, (size_t)T));
+    LKG_TRY(tmp.get(&d_bad, 1));
+    if (T > 0) {
+        LKG_HIP(hipMemcpy(d_subj, subj, (size_t)T * 4, hipMemcpyHostToDevice));
+        LKG_HIP(hipMemcpy(d_rel, rel, (size_t)T * 4, hipMemcpyHostToDevice));
+        LKG_HIP(hipMemcpy(d_obj, obj, (size_t)T * 4, hipMemcpyHostToDevice));
+    }
+    const unsigned long long none = ~0ull;
+    LKG_HIP(hipMemcpy(d_bad, &none, sizeof(none), hipMemcpyHostToDevice));
+    if (T > 0) {
+        k_check_triples<<<dim3(grid_for(T)), dim3(kBlock)>>>(d_subj, d_rel, d_obj, T, E, g->R, d_bad);
+        k_iota<<<dim3(grid_for(T)), dim3(kBlock)>>>(d_iota, T);
+    }
+    unsigned long long bad = none;
+    LKG_HIP(hipMemcpy(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost));
+    if (bad != none) {
+        set_error("triple %llu = (%d, %d, %d) is out of range", bad, subj[bad], rel[bad], obj[bad]);
+        return LOGOSKG_EINVAL;
+    }
+    unsigned key_bits = 1;
+    while (key_bits < 32 && (1ull << key_bits) < (unsigned long long)E) ++key_bits;
+    // one temporary buffer that serves the sort and the scan
+    size_t sort_bytes = 0, scan_bytes = 0;
+    LKG_HIP(rocprim::radix_sort_pairs(nullptr, sort_bytes, reinterpret_cast<const uint32_t *>(d_subj), d_keys, d_iota,
+                                      d_eid, (size_t)std::max<int64_t>(T, 1), 0u, key_bits));
+    LKG_HIP(rocprim::inclusive_scan(nullptr, scan_bytes, (uint32_t *)nullptr, (uint32_t *)nullptr, (size_t)E + 1,
+                                    rocprim::plus<uint32_t>()));
+    const size_t tmp_bytes = std::max(sort_bytes, scan_bytes);
+    char *d_tmp = nullptr;
+    LKG_TRY(tmp.get(&d_tmp, tmp_bytes));
+
+    auto keep = [&](void **p, size_t bytes) -> logoskg_status {
+        LKG_HIP(hipMalloc(p, std::max<size_t>(bytes, 4)));
+        g->static_bytes += std::max<size_t>(bytes, 4);
+        return LOGOSKG_OK;
+    };
+    // SUB: rows by subject
+    LKG_TRY(keep((void **)&g->out_off, ((size_t)E + 1) * 4));
+    LKG_TRY(keep((void **)&g->out_obj, (size_t)T * 4));
+    LKG_TRY(keep((void **)&g->out_rel, (size_t)T * 2));
+    LKG_TRY(sort_by(d_subj, T, E, key_bits, d_iota, d_keys, d_eid, g->out_off, d_tmp, tmp_bytes));
+    if (T > 0) k_gather_sub_rows<<<dim3(grid_for(T)), dim3(kBlock)>>>(d_eid, T, d_obj, d_rel, g->out_obj, g->out_rel);
+    // OBJ: rows by object, triple indices kept as edge ids
+    LKG_TRY(keep((void **)&g->in_off, ((size_t)E + 1) * 4));
+    LKG_TRY(keep((void **)&g->in_sub, (size_t)T * 4));
+    LKG_TRY(keep((void **)&g->in_rel, (size_t)T * 2));
+    LKG_TRY(keep((void **)&g->in_eid, (size_t)T * 4));
+    LKG_TRY(sort_by(d_obj, T, E, key_bits, d_iota, d_keys, d_eid, g->in_off, d_tmp, tmp_bytes));
+    if (T > 0)
+        k_gather_obj_rows<<<dim3(grid_for(T)), dim3(kBlock)>>>(d_eid, T, d_subj, d_rel, g->in_sub, g->in_rel, g->in_eid);
+    LKG_HIP(hipGetLastError());
+    ooff->resize((size_t)E + 1);
+    ioff->resize((size_t)E + 1);
+    LKG_HIP(hipMemcpy(ooff->data(), g->out_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
+    LKG_HIP(hipMemcpy(ioff->data(), g->in_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
+    LKG_HIP(hipDeviceSynchronize());
+    return LOGOSKG_OK;
+}
+
+}  // namespace lkg

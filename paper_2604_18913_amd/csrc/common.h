@@ -313,6 +313,8 @@ struct FillArgs {
     int fuse_lists;  // the 16-word tile kernel also writes the entity and hop lists
 };
 
+logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                                   std::vector<uint32_t> *ooff, std::vector<uint32_t> *ioff);
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
                  hipStream_t st_tiles, hipStream_t st_rows);

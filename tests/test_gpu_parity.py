@@ -240,6 +240,28 @@ def test_degenerate_graphs_and_the_deepest_search(Q):
     g.close()
 
 
+def test_device_build_equals_host_build():
+    # the GPU sort and the host counting sort must give the same CSR: predecessor edges and path
+    # listings depend on the order of the entries inside a row
+    m = lkg()
+    cases = [kggen.config1(), kggen.config2(0.01), kggen.config3(0.005, k=3),
+             kggen.random_tiny(900, E=50, T=400, R=3, Q=70, k=4, masked=True)]
+    for w in cases:
+        outs = []
+        for host_build in (False, True):
+            g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, host_build=host_build)
+            res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+            ent, hop, pred = res.fetch()
+            info = {k: v for k, v in g.info().items() if k.startswith("num_")}
+            outs.append((res.offsets(), ent.cpu().numpy(), hop.cpu().numpy(), pred.cpu().numpy(),
+                         res.traversed().cpu().numpy(), info))
+            res.close()
+            g.close()
+        assert outs[0][5] == outs[1][5], w.name
+        assert_same(outs[0][:5], outs[1][:5], w.name)
+        assert_same(outs[0][:5], run_oracle(w), w.name)
+
+
 def test_bad_inputs_are_reported_not_faulted():
     m = lkg()
     w = kggen.config1()
