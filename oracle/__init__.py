@@ -48,6 +48,9 @@ def _load():
         lib.oracle_walk_levels.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, P, ctypes.c_int32,
                                            P, P, ctypes.c_int32, P, ctypes.c_int32, ctypes.c_int32,
                                            P, ctypes.POINTER(P)]
+        lib.oracle_active_triples.restype = ctypes.c_int64
+        lib.oracle_active_triples.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, ctypes.c_int64, P, P,
+                                              ctypes.POINTER(P)]
         lib.oracle_free.argtypes = [P]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -174,3 +177,29 @@ def walk_levels(num_entities: int, subj, rel, obj, seed_off, seeds, k: int,
         out = np.ctypeslib.as_array(ctypes.cast(ent, ctypes.POINTER(ctypes.c_int32)), shape=(n,)).copy()
     lib.oracle_free(ent)
     return level_off, out
+
+
+def active_triples(num_entities: int, subj, rel, frontier, rel_mask_row: Optional[np.ndarray] = None):
+    """T_h of one query (Eq. 5-6): indices of the triples whose subject is in
+    ``frontier`` (the support of q^(h-1)) and whose relation the query's
+    whitelist ``rel_mask_row`` (uint64 words, or None = all) allows, ordered by
+    (subject, triple index).  Returns int32[n]."""
+    lib = _load()
+    subj, p_s = _c(subj, np.int32)
+    rel, p_r = _c(rel, np.int32)
+    frontier, p_f = _c(frontier, np.int32)
+    if rel_mask_row is not None:
+        rel_mask_row, p_m = _c(rel_mask_row, np.uint64)
+    else:
+        p_m = None
+    out = ctypes.c_void_p()
+    n = lib.oracle_active_triples(subj.shape[0], num_entities, p_s, p_r, frontier.shape[0], p_f, p_m,
+                                  ctypes.byref(out))
+    if n < 0:
+        raise RuntimeError("oracle_active_triples failed (bad arguments or out of memory)")
+    if n == 0:
+        res = np.zeros(0, dtype=np.int32)
+    else:
+        res = np.ctypeslib.as_array(ctypes.cast(out, ctypes.POINTER(ctypes.c_int32)), shape=(n,)).copy()
+    lib.oracle_free(out)
+    return res

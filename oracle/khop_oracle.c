@@ -43,6 +43,16 @@
  * closed forms on cycles / paths / self loops, and against oracle_khop itself
  * (union over h = reached set, first h = hop).
  *
+ * Active-triple sets (oracle_active_triples): T_h of Eq. 5-6 for one query,
+ * given the support of q^(h-1) as an entity list: every triple whose subject
+ * is in that list and whose relation is in M, written out with the triple list
+ * scanned once in index order and then ordered by (subject, triple index) -
+ * the order of SUB's rows, with triple indices ascending inside a subject.
+ * The caller takes (s_t, r_t, o_t) of Eq. 7 from the input arrays.  Pins
+ * (tests/test_oracle_triples_pins.py): the dense product q . SUB of Eq. 5,
+ * t^(h) . OBJ = q^(h) against oracle_walk_levels, |T_h| against trav(h),
+ * closed forms and the hand-worked example.
+ *
  * Parity pins (see tests/test_oracle_pins.py): boolean products of dense
  * SUB / REL / OBJ matrices, brute-force walk enumeration, closed forms on
  * paths / cycles / stars / trees, networkx and scipy shortest-path lengths,
@@ -432,4 +442,51 @@ int oracle_walk_levels(int64_t T, int32_t E, const int32_t *subj, const int32_t 
     }
     free(lists); free(counts); free(first); free(ids);
     return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Active triples of one hop of one query (Sec. 3.3, Eq. 5-6).
+ *
+ *   frontier  : the n_frontier entities with q^(h-1)[e] = 1 (any order, may
+ *               repeat)
+ *   mask      : the query's relation whitelist (rel_words 64-bit words) or NULL
+ *   triple    : malloc'ed by the callee (oracle_free): the indices t with
+ *               subj[t] in frontier and rel[t] allowed, ordered by
+ *               (subj[t], t)
+ * Returns the number of triples, or -1.
+ */
+typedef struct { int32_t s, t; } subject_triple;
+
+static int cmp_subject_triple(const void *a, const void *b)
+{
+    const subject_triple *x = (const subject_triple *)a, *y = (const subject_triple *)b;
+    if (x->s != y->s) return x->s < y->s ? -1 : 1;
+    return (x->t > y->t) - (x->t < y->t);
+}
+
+int64_t oracle_active_triples(int64_t T, int32_t E, const int32_t *subj, const int32_t *rel,
+                              int64_t n_frontier, const int32_t *frontier, const uint64_t *mask,
+                              int32_t **triple)
+{
+    if (E <= 0 || T < 0 || T > 0x7fffffff || n_frontier < 0) return -1;
+    uint8_t *in_q = (uint8_t *)calloc((size_t)E, 1);   /* q^(h-1) as an indicator vector */
+    if (!in_q) return -1;
+    for (int64_t i = 0; i < n_frontier; ++i) {
+        if (frontier[i] < 0 || frontier[i] >= E) { free(in_q); return -1; }
+        in_q[frontier[i]] = 1;
+    }
+    int64_t n = 0;
+    for (int64_t t = 0; t < T; ++t)                     /* t^(h)[t] = q^(h-1)[s_t], whitelist applied */
+        if (in_q[subj[t]] && relation_allowed(mask, rel[t])) ++n;
+    subject_triple *act = (subject_triple *)malloc((size_t)(n > 0 ? n : 1) * sizeof(*act));
+    *triple = (int32_t *)malloc((size_t)(n > 0 ? n : 1) * sizeof(int32_t));
+    if (!act || !*triple) { free(in_q); free(act); free(*triple); *triple = NULL; return -1; }
+    int64_t m = 0;
+    for (int64_t t = 0; t < T; ++t)
+        if (in_q[subj[t]] && relation_allowed(mask, rel[t])) { act[m].s = subj[t]; act[m].t = (int32_t)t; ++m; }
+    qsort(act, (size_t)n, sizeof(*act), cmp_subject_triple);
+    for (int64_t i = 0; i < n; ++i) (*triple)[i] = act[i].t;
+    free(act);
+    free(in_q);
+    return n;
 }

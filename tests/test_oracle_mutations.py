@@ -10,6 +10,7 @@ import pytest
 import oracle
 import test_oracle_pins as pins
 import test_oracle_walk_pins as wpins
+import test_oracle_triples_pins as tpins
 
 MUTATIONS = {
     "tie_break_dropped": ("} else if (st->hop[v] == h && t < st->pred[v]) {",
@@ -36,6 +37,11 @@ MUTATIONS = {
     "walk_sets_the_subject": ("                        int32_t v = obj[t];\n                        if (stamp[v] != mark)",
                               "                        int32_t v = subj[t];\n                        if (stamp[v] != mark)"),
     "walk_last_level_missing": ("                if (h == k) break;", "                if (h >= k - 1) break;"),
+    # active-triple sets
+    "triples_ignore_whitelist": ("in_q[subj[t]] && relation_allowed(mask, rel[t])", "in_q[subj[t]]"),
+    "triples_ordered_by_index_only": ("    if (x->s != y->s) return x->s < y->s ? -1 : 1;\n", ""),
+    "triples_subjects_descending": ("return x->s < y->s ? -1 : 1;", "return x->s > y->s ? -1 : 1;"),
+    "triples_frontier_shifted": ("        in_q[frontier[i]] = 1;", "        in_q[frontier[i] > 0 ? frontier[i] - 1 : 0] = 1;"),
 }
 
 PIN_CALLS = [
@@ -47,6 +53,9 @@ PIN_CALLS = [
     lambda: pins.test_first_path_is_the_pred_chain(),
     lambda: [wpins.test_against_boolean_matrix_powers(s, m) for s in range(3) for m in (False, True)],
     lambda: wpins.test_cycle_path_self_loop_and_bipartite(),
+    lambda: tpins.test_hand_worked_example(),
+    lambda: [tpins.test_against_dense_incidence_product(s, m) for s in range(3) for m in (False, True)],
+    lambda: tpins.test_closed_forms(),
 ]
 
 
@@ -62,7 +71,8 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
                            str(mutated)])
     good = oracle._load()
     lib = ctypes.CDLL(lib_path)
-    for fn in ("oracle_khop", "oracle_paths", "oracle_walk_levels", "oracle_free", "oracle_num_threads"):
+    for fn in ("oracle_khop", "oracle_paths", "oracle_walk_levels", "oracle_active_triples", "oracle_free",
+               "oracle_num_threads"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
     monkeypatch.setattr(oracle, "_lib", lib)
