@@ -253,18 +253,26 @@ def main():
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     # calibrated); counters cannot be read from inside this process
     traffic = None
+    valu_view = None
     expansion_measured = None
     tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_traffic.json")
     if os.path.exists(tfile) and args.scale == 1.0 and cfg == 2 and not walk and nf == Q:
         tk = json.load(open(tfile)).get("kernels", {})
         traffic = tk.get(dom, {}).get("hbm_bytes_per_launch")
+        sq = tk.get(dom, {}).get("sq_counters")
+        if sq and dk["avg_ms"] > 0:  # how busy the vector ALUs are: the kernel may be bound by instruction issue
+            simd_cycles = 1024 * dk["avg_ms"] * 1e-3 * 2.4e9
+            valu_view = {"wave_instructions_per_launch": sq["SQ_INSTS_VALU"],
+                         "issue_busy_frac": round(sq["SQ_INSTS_VALU"] * 4 / simd_cycles, 3),
+                         "lanes_active_per_instruction": round(sq["SQ_THREAD_CYCLES_VALU"] / sq["SQ_ACTIVE_INST_VALU"], 1),
+                         "source": "rocprofv3 --pmc SQ_* of the same kernel (profiles/)"}
         expansion_measured = sum(tk[n]["hbm_read_bytes_per_step"] + tk[n]["hbm_write_bytes_per_step"]
                                  for n in kernels if n.startswith(expansion_names) and n in tk)
         expansion_measured += kernels.get("clear_planes", {}).get("items", 0) * 8  # a memset: its own size
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                     algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4),
-                    measured="HIP events around every launch, fetch kernels serialized")
+                    measured="HIP events around every launch, fetch kernels serialized", valu=valu_view)
     # the same figure for every kernel that has a byte model
     exp = {}
     for n, v in kernels.items():

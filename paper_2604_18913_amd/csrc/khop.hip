@@ -320,8 +320,7 @@ __device__ __forceinline__ int take_candidates(unsigned long long &rest) {
 // 64 consecutive in-edges of one object row, in three stages so that a caller can
 // keep the loads of later chunks in flight: subject (and relation) ids, the
 // frontier bit of every subject, then the gather of the frontier lines of the
-// candidates (64/W per round, four rounds of loads in flight).  acc collects
-// (per group) the OR of the gathered words; gather returns the number of lines.
+// candidates (pull_gather).
 struct PullEdges {
     int s, r;
 };
@@ -344,23 +343,30 @@ __device__ __forceinline__ bool pull_test(const PullEdges &e, const uint32_t *__
 
 // Gather stage.  The candidates' subject ids are compacted into a per-wavefront
 // LDS queue (position = number of candidates in lower lanes); group g of round r
-// then reads entry r * (64/W) + g, so picking a candidate costs one LDS read
-// instead of a search in the ballot mask and a cross-lane move.  Four rounds of
+// then reads entry r * (groups per round) + g, so picking a candidate costs one
+// LDS read instead of a search in the ballot mask and a cross-lane move.  A lane
+// loads two plane words (16 bytes): W/2 lanes cover a line and one load
+// instruction of a wavefront fetches 128/W lines, which halves the number of
+// vector memory instructions against one word per lane.  Up to four rounds of
 // loads are in flight; only the last, partly filled batch is predicated.
+// a0 / a1 collect words 2*(lane % (W/2)) and 2*(lane % (W/2)) + 1 (W = 1: a0 only).
 template <int W, bool MASK>
 __device__ __forceinline__ int pull_gather(const PullEdges &e, bool cand, const unsigned long long *__restrict__ prev,
-                                           const unsigned long long *__restrict__ allow, unsigned long long &acc,
-                                           int *queue_s, uint16_t *queue_r) {
+                                           const unsigned long long *__restrict__ allow, unsigned long long &a0,
+                                           unsigned long long &a1, int *queue_s, uint16_t *queue_r) {
     const unsigned long long cm = __ballot(cand);
     const int ncand = __popcll(cm);
     if constexpr (W == 1) {
         if (cand) {
             unsigned long long ln = prev[e.s];
             if (MASK) ln &= allow[e.r];
-            acc |= ln;
+            a0 |= ln;
         }
     } else {
-        constexpr int GPW = 64 / W, B = 4 * GPW;  // candidates per batch
+        constexpr int LW = W / 2, GPW = 64 / LW;            // lanes per line, lines per load instruction
+        constexpr int NR = GPW >= 32 ? 64 / GPW : 4, B = NR * GPW;  // rounds and candidates per batch
+        const ulonglong2 *prev2 = reinterpret_cast<const ulonglong2 *>(prev);
+        const ulonglong2 *allow2 = reinterpret_cast<const ulonglong2 *>(allow);
         if (ncand == 0) return 0;
         if (cand) {
             const int pos = __popcll(cm & ((1ull << lane()) - 1ull));
@@ -368,34 +374,65 @@ __device__ __forceinline__ int pull_gather(const PullEdges &e, bool cand, const 
             if (MASK) queue_r[pos] = (uint16_t)e.r;
         }
         __builtin_amdgcn_wave_barrier();
-        const int lw = lane() & (W - 1), g = lane() / W;
+        const int lw = lane() & (LW - 1), g = lane() / LW;
         int base = 0;
         for (; base + B <= ncand; base += B) {  // full batches
-            unsigned long long l[4];
+            ulonglong2 l[NR];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
+            for (int x = 0; x < NR; ++x) {
                 const int i = base + x * GPW + g;
-                l[x] = prev[(size_t)queue_s[i] * W + lw];
-                if (MASK) l[x] &= allow[(size_t)queue_r[i] * W + lw];
-            }
-            acc |= (l[0] | l[1]) | (l[2] | l[3]);
-        }
-        if (base < ncand) {
-            unsigned long long l[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int i = base + x * GPW + g;
-                l[x] = 0;
-                if (i < ncand) {
-                    l[x] = prev[(size_t)queue_s[i] * W + lw];
-                    if (MASK) l[x] &= allow[(size_t)queue_r[i] * W + lw];
+                l[x] = prev2[(size_t)queue_s[i] * LW + lw];
+                if (MASK) {
+                    const ulonglong2 m = allow2[(size_t)queue_r[i] * LW + lw];
+                    l[x].x &= m.x;
+                    l[x].y &= m.y;
                 }
             }
-            acc |= (l[0] | l[1]) | (l[2] | l[3]);
+#pragma unroll
+            for (int x = 0; x < NR; ++x) {
+                a0 |= l[x].x;
+                a1 |= l[x].y;
+            }
+        }
+        if (base < ncand) {
+            ulonglong2 l[NR];
+#pragma unroll
+            for (int x = 0; x < NR; ++x) {
+                const int i = base + x * GPW + g;
+                l[x] = make_ulonglong2(0, 0);
+                if (i < ncand) {
+                    l[x] = prev2[(size_t)queue_s[i] * LW + lw];
+                    if (MASK) {
+                        const ulonglong2 m = allow2[(size_t)queue_r[i] * LW + lw];
+                        l[x].x &= m.x;
+                        l[x].y &= m.y;
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < NR; ++x) {
+                a0 |= l[x].x;
+                a1 |= l[x].y;
+            }
         }
         __builtin_amdgcn_wave_barrier();  // the queue is rewritten by the next chunk
     }
     return ncand;
+}
+
+// Folds the accumulators of pull_gather into one word per lane (word lane % W),
+// the union over the whole wavefront.
+template <int W>
+__device__ __forceinline__ unsigned long long fold_gathered(unsigned long long a0, unsigned long long a1) {
+    if constexpr (W == 1) {
+        return or_across_groups<1>(a0);
+    } else {
+        a0 = or_across_groups<W / 2>(a0);
+        a1 = or_across_groups<W / 2>(a1);
+        const int lw = lane() & (W - 1);
+        const unsigned long long x = shfl64(a0, lw >> 1), y = shfl64(a1, lw >> 1);
+        return (lw & 1) ? y : x;
+    }
 }
 
 __device__ __forceinline__ void add_stats(unsigned long long *stats, long long rows, long long edges,
@@ -527,6 +564,7 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
     }
     const bool work = wave_any(need != 0);
     long long n_edges = 0, n_lines = 0;
+    unsigned long long a0 = 0, a1 = 0;
     if (work) {
         // software pipeline: ids of chunk i+2 and frontier bits of chunk i+1 are requested
         // before the lines of chunk i are gathered
@@ -537,18 +575,18 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
         for (uint32_t j0 = lo; j0 < hi; j0 += 64, ++it) {
             PullEdges e2 = pull_load_edges<MASK>(j0 + 128, hi, in_sub, in_rel);
             const bool c1 = pull_test(e1, act_prev);
-            n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, acc, queue_s[threadIdx.x >> 6], queue_r[threadIdx.x >> 6]);
+            n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, a0, a1, queue_s[threadIdx.x >> 6], queue_r[threadIdx.x >> 6]);
             n_edges += min((uint32_t)64, hi - j0);
             e0 = e1;
             c0 = c1;
             e1 = e2;
             if ((it & 3) == 3) {  // early exit is rare: test it every fourth chunk
-                acc = or_across_groups<W>(acc);
+                acc = fold_gathered<W>(a0, a1);
                 if (multi) acc |= __atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
                 if (!wave_any((need & ~acc) != 0)) break;
             }
         }
-        acc = or_across_groups<W>(acc);
+        acc |= fold_gathered<W>(a0, a1);
         unsigned long long nb = acc & need;
         if (wave_any(nb != 0)) {
             if (!multi) {
