@@ -238,6 +238,33 @@ logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t h, int32_t 
                                           int64_t capacity, int32_t *entity, void *stream);
 
 /*
+ * Active triples of hop h, h in [1, k] (Sec. 3.3 "Path reconstruction", Eq. 5-7):
+ * T_h of query q holds the triples t whose subject is in level h-1 of q (the
+ * support of q^(h-1): minimum hop h-1 with the default search, walks of h-1
+ * triples with LOGOSKG_WALK_EXACT) and whose relation the query's whitelist
+ * allows.  Lists are query-major; inside a query they follow SUB's rows:
+ * ascending subject, ascending triple index inside a subject.
+ * logoskg_result_triples_offsets prepares the queries [q_begin, q_end) and
+ * returns triple_off (host int64[q_end - q_begin + 1], prefix sums of |T_h|;
+ * synchronises `stream`); logoskg_result_triples_fetch, called with the same
+ * h and range, then writes for position triple_off[q - q_begin] + i the triple
+ * index and its components (s_h, r_h, e_h of Eq. 7) to the device buffers
+ * triple / subject / relation / object (each int32[capacity] or NULL;
+ * capacity checked: LOGOSKG_ERANGE), asynchronously on `stream`.  The calls
+ * count level h-1 (they replace the level counted by
+ * logoskg_result_level_offsets) and keep the level's entity list and one
+ * int64 per entry in device memory until the result is freed or another range
+ * is prepared.  The first call on a graph builds the triple indices of SUB's
+ * rows (4 bytes per triple, freed with the graph).  Needs a resident
+ * (unsharded) graph: LOGOSKG_EINVAL otherwise.
+ */
+logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int32_t h, int32_t q_begin, int32_t q_end,
+                                              int64_t *triple_off, void *stream);
+logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_t h, int32_t q_begin, int32_t q_end,
+                                            int64_t capacity, int32_t *triple, int32_t *subject,
+                                            int32_t *relation, int32_t *object, void *stream);
+
+/*
  * traversed[q][h-1] = number of triples whose subject has hop h-1 for query q
  * (the triples hop h inspects, whatever their relation): the numerator of the
  * per-query "traversed edges per second" figure.  device int64[Q][k].

@@ -111,6 +111,10 @@ def _load():
     lib.logoskg_result_level_offsets.argtypes = [P, I32, P, P]
     lib.logoskg_result_level_fetch.restype = ctypes.c_int
     lib.logoskg_result_level_fetch.argtypes = [P, I32, I32, I32, I64, P, P]
+    lib.logoskg_result_triples_offsets.restype = ctypes.c_int
+    lib.logoskg_result_triples_offsets.argtypes = [P, I32, I32, I32, P, P]
+    lib.logoskg_result_triples_fetch.restype = ctypes.c_int
+    lib.logoskg_result_triples_fetch.argtypes = [P, I32, I32, I32, I64, P, P, P, P, P]
     lib.logoskg_result_traversed.restype = ctypes.c_int
     lib.logoskg_result_traversed.argtypes = [P, P, P]
     lib.logoskg_result_free.restype = None
@@ -224,6 +228,23 @@ class Result:
         _check(_load().logoskg_result_level_fetch(self._h, h, q_begin, q_end, n, entity.data_ptr(),
                                                   _stream_handle(stream)))
         return off, entity
+
+    def active_triples(self, h: int, q_begin: int = 0, q_end: Optional[int] = None, components: bool = True,
+                       stream=None):
+        """``logoskg_result_triples_offsets`` + ``logoskg_result_triples_fetch``: T_h of the queries
+        [q_begin, q_end) as (offsets int64[q_end - q_begin + 1], triple, subject, relation, object)
+        int32 device tensors (the last three None without ``components``)."""
+        torch = _torch()
+        q_end = self.num_queries if q_end is None else q_end
+        off = np.zeros(max(q_end - q_begin, 0) + 1, dtype=np.int64)
+        _check(_load().logoskg_result_triples_offsets(self._h, h, q_begin, q_end,
+                                                      off.ctypes.data_as(ctypes.c_void_p), _stream_handle(stream)))
+        n = int(off[-1])
+        bufs = [torch.empty(n, dtype=torch.int32, device=self._g.device) for _ in range(4 if components else 1)]
+        ptrs = [b.data_ptr() for b in bufs] + [None] * (4 - len(bufs))
+        _check(_load().logoskg_result_triples_fetch(self._h, h, q_begin, q_end, n, *ptrs, _stream_handle(stream)))
+        bufs += [None] * (4 - len(bufs))
+        return (off, *bufs)
 
     def traversed(self, stream=None):
         torch = _torch()

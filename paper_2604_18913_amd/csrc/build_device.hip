@@ -61,6 +61,13 @@ __global__ void k_gather_obj_rows(const uint32_t *__restrict__ eid, long long T,
     in_eid[p] = (int32_t)t;
 }
 
+// subject_of[t] = subject of triple t, from the object-sorted arrays (which keep the triple index)
+__global__ void k_subject_of_triple(const int32_t *__restrict__ in_sub, const int32_t *__restrict__ in_eid,
+                                    long long T, uint32_t *subject_of) {
+    long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < T) subject_of[in_eid[p]] = (uint32_t)in_sub[p];
+}
+
 struct Scratch {  // device temporaries, freed on every way out
     std::vector<void *> ptrs;
     ~Scratch() {
@@ -164,6 +171,45 @@ logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const 
     LKG_HIP(hipMemcpy(ooff->data(), g->out_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
     LKG_HIP(hipMemcpy(ioff->data(), g->in_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
     LKG_HIP(hipDeviceSynchronize());
+    return LOGOSKG_OK;
+}
+
+// g->out_eid[p] = index of the triple behind entry p of the subject-sorted CSR (SUB's rows, Eq. 1).
+// The build keeps triple indices only with the object-sorted arrays; this repeats the stable sort
+// by subject on (subject, triple index) pairs, so the order is the one of out_obj / out_rel.
+logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st) {
+    if (g->out_eid) return LOGOSKG_OK;
+    if (g->num_shards > 1) { set_error("needs a resident (unsharded) graph"); return LOGOSKG_EINVAL; }
+    const int64_t T = g->T;
+    Scratch tmp;
+    uint32_t *d_subject = nullptr, *d_iota = nullptr, *d_keys = nullptr;
+    LKG_TRY(tmp.get(&d_subject, (size_t)T));
+    LKG_TRY(tmp.get(&d_iota, (size_t)T));
+    LKG_TRY(tmp.get(&d_keys, (size_t)T));
+    int32_t *eid = nullptr;
+    LKG_HIP(hipMalloc((void **)&eid, std::max<size_t>((size_t)T, 1) * 4));
+    auto fail = [&](logoskg_status s) { (void)hipFree(eid); return s; };
+    if (T > 0) {
+        unsigned key_bits = 1;
+        while (key_bits < 32 && (1ull << key_bits) < (unsigned long long)g->E) ++key_bits;
+        k_subject_of_triple<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(g->in_sub, g->in_eid, T, d_subject);
+        k_iota<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(d_iota, T);
+        size_t bytes = 0;
+        hipError_t e = rocprim::radix_sort_pairs(nullptr, bytes, d_subject, d_keys, d_iota, (uint32_t *)eid, (size_t)T,
+                                                 0u, key_bits, st);
+        char *d_tmp = nullptr;
+        if (e == hipSuccess && tmp.get(&d_tmp, bytes) != LOGOSKG_OK) return fail(LOGOSKG_ENOMEM);
+        if (e == hipSuccess)
+            e = rocprim::radix_sort_pairs(d_tmp, bytes, d_subject, d_keys, d_iota, (uint32_t *)eid, (size_t)T, 0u,
+                                          key_bits, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);  // the temporaries are freed on return
+        if (e != hipSuccess) {
+            set_error("sort of the triple indices failed: %s", hipGetErrorString(e));
+            return fail(LOGOSKG_EDEVICE);
+        }
+    }
+    g->out_eid = eid;
+    g->static_bytes += std::max<size_t>((size_t)T, 1) * 4;
     return LOGOSKG_OK;
 }
 

@@ -87,7 +87,7 @@ struct RowClasses {             // device work lists over the object rows, split
 enum KernelKind {
     KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_LIVE, KK_PUSH_TAIL, KK_PUSH_SEG, KK_UPDATE, KK_PULL_TAIL,
     KK_PULL_SEG, KK_PULL_FINISH, KK_COUNT, KK_SCAN, KK_LISTS, KK_PRED, KK_PRED_HUB, KK_PRED_MID, KK_TRAVERSED,
-    KK_PATHS, KK_SHARD_COPY, KK_NUM
+    KK_PATHS, KK_SHARD_COPY, KK_TRIPLES, KK_NUM
 };
 extern const char *const kKernelNames[KK_NUM];
 
@@ -142,6 +142,8 @@ struct logoskg_graph {
     int32_t *in_sub = nullptr;   // [T]
     uint16_t *in_rel = nullptr;  // [T]
     int32_t *in_eid = nullptr;   // [T]
+    int32_t *out_eid = nullptr;  // [T] triple index of every entry of the subject-sorted CSR; built on
+                                 // first use by the active-triple export
     lkg::RowClasses in_rows;     // static row lists for the pull kernels
     int64_t n_out_rows = 0, n_out_hubs = 0;
 
@@ -198,6 +200,12 @@ struct logoskg_result {
     uint32_t *lvl_super_base = nullptr, *lvl_mega_base = nullptr;
     long long *d_level_off = nullptr;
     std::vector<int64_t> level_off;
+    // active triples of one hop for one query range (logoskg_result_triples_offsets)
+    int trip_h = -1, trip_q0 = 0, trip_q1 = 0;
+    int64_t trip_n = 0;            // entries of level trip_h - 1 over the range
+    int32_t *trip_ent = nullptr;   // [trip_n] those entities, query-major
+    long long *trip_off = nullptr; // [trip_n + 1] first output position of every entry's triples
+    std::vector<int64_t> trip_off_host;  // [trip_q1 - trip_q0 + 1]
     std::vector<logoskg_hop_stats> stats;
 };
 
@@ -315,6 +323,7 @@ struct FillArgs {
 
 logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
                                    std::vector<uint32_t> *ooff, std::vector<uint32_t> *ioff);
+logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st);
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
                  hipStream_t st_tiles, hipStream_t st_rows);
