@@ -57,6 +57,10 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
         return edges * 4
     if kernel == "clear_planes":
         return items * 8
+    if kernel == "active_triples":
+        # per list entry (one row of SUB): entity id, output position, two row offsets; per triple:
+        # triple index + object + relation read (10 B), four int32 columns written
+        return rows * 20 + items * 26
     if kernel == "count_tiles":
         return items * 8 * 1.25  # plane read + uint16 per (tile, query) written
     return 0.0
@@ -86,9 +90,11 @@ def main():
                     help="fetch the lists of the first N queries only (0 = all; configs 4 and 5 default to 64)")
     ap.add_argument("--resident-shards", type=int, default=0,
                     help="config 5: capacity of the shard cache in shards (the paper's n); 0 = the byte budget only")
-    ap.add_argument("--mode", choices=["minhop", "walk"], default="minhop",
+    ap.add_argument("--mode", choices=["minhop", "walk", "triples"], default="minhop",
                     help="minhop (default): the headline path; walk: Eq. 4 iterated without the visited set "
-                         "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query")
+                         "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query; "
+                         "triples: one step = khop + the active triples T_k (Eq. 5-7, four columns) of the "
+                         "first --fetch-queries queries (default 16)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch a plain 1 GiB device copy and a 1 GiB fill, so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known size")
@@ -135,7 +141,8 @@ def main():
     rel_mask = None if w.rel_mask is None else torch.from_numpy(w.rel_mask.view(np.int64)).to(dev)
     masked = rel_mask is not None
     Q, k = w.num_queries, w.k
-    nf = args.fetch_queries or (64 if cfg >= 4 else Q)   # queries whose lists are fetched
+    triples = args.mode == "triples"
+    nf = args.fetch_queries or (16 if triples else 64 if cfg >= 4 else Q)   # queries whose lists are fetched
     nf = min(nf, Q)
 
     # practical HBM ceiling of this machine in this run: a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB)
@@ -168,7 +175,13 @@ def main():
     total = int(res.level(k, 0, 0)[0][nf]) if walk else int(off[nf])
     W = res.words_per_entity
     res_epad = res.padded_entities
-    if not walk:
+    n_triples = 0
+    if triples:
+        first = res.active_triples(k, 0, nf)
+        n_triples = int(first[0][-1])
+        cols = tuple(first[1:])
+        del first
+    elif not walk:
         ent = torch.empty(total, dtype=torch.int32, device=dev)
         hop = torch.empty(total, dtype=torch.uint8, device=dev)
         pred = torch.empty(total, dtype=torch.int32, device=dev)
@@ -181,6 +194,9 @@ def main():
         if walk:
             r = g.khop(seed_off, seeds, k, rel_mask, walk_exact=True)
             r.level(k, 0, nf)
+        elif triples:
+            r = g.khop(seed_off, seeds, k, rel_mask)
+            r.active_triples(k, 0, nf, out=cols)
         else:
             r = g.khop(seed_off, seeds, k, rel_mask)
             r.fetch(0, nf, out=(ent, hop, pred))
@@ -225,7 +241,7 @@ def main():
     if not args.serial_fetch:
         os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
 
-    ab = functools.partial(algorithmic_bytes, level_lists=walk)
+    ab = functools.partial(algorithmic_bytes, level_lists=walk or triples)
     masked_arg = masked
     ms_per_step = dt / args.steps * 1e3
     qps = Q / (dt / args.steps)
@@ -282,7 +298,10 @@ def main():
                           frac=round(b / (v["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           ms_per_step=round(v["ms_per_step"], 4), bytes_per_step=int(b))
 
-    if cfg == 2 and not walk:
+    if triples:
+        metric = (f"queries/s, {k}-hop batch-{Q} on configs[{cfg - 1}] (khop + the active triples T_{k} of the first "
+                  f"{nf} queries: {n_triples:,} triples with subject, relation and object)")
+    elif cfg == 2 and not walk:
         metric = "queries/s, 3-hop batch-1024 on 30M-edge synthetic KG (whole hot path: khop + result lists)"
     elif cfg == 2:
         metric = ("queries/s, walk-exact 3-hop batch-1024 on 30M-edge synthetic KG (khop without the visited set + "
@@ -309,7 +328,7 @@ def main():
                                ("" if args.scale == 1.0 else f" (scaled by {args.scale})"),
                    "num_entities": w.num_entities, "num_triples": w.num_triples, "num_queries": Q, "k": k,
                    "mode": args.mode, "words_per_entity": W, "reached_pairs": total, "queries_fetched": nf,
-                   "reached_pairs_all_queries": int(off[-1]),
+                   "reached_pairs_all_queries": int(off[-1]), "active_triples": n_triples,
                    "directions": [h["direction"] for h in hop_stats]},
         "gteps_logical": round(logical_edges / (dt / args.steps) / 1e9, 2),
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
@@ -346,14 +365,32 @@ def main():
         so = w.seed_off[: nq + 1]
         sd = w.seeds[: so[-1]]
         mk = None if w.rel_mask is None else w.rel_mask[:nq]
+        if triples:
+            nq = min(nq, 8)
+            so = w.seed_off[: nq + 1]
+            sd = w.seeds[: so[-1]]
+            mk = None if w.rel_mask is None else w.rel_mask[:nq]
         t0 = time.perf_counter()
-        if walk:
+        if triples:
+            o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
+            o_t = []
+            for q in range(nq):
+                a, b = o[0][q], o[0][q + 1]
+                o_t.append(oracle.active_triples(w.num_entities, w.subj, w.rel, o[1][a:b][o[2][a:b] == k - 1],
+                                                 None if mk is None else mk[q]))
+        elif walk:
             o_off, o_ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         else:
             o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         t_cpu = time.perf_counter() - t0
         got = g.khop(seed_off, seeds, k, rel_mask, walk_exact=walk)
-        if walk:
+        if triples:
+            t_off, t_id, t_s, t_r, t_o = got.active_triples(k, 0, nq)
+            want = np.concatenate(o_t) if o_t else np.zeros(0, dtype=np.int32)
+            same = (np.array_equal(t_off, np.concatenate([[0], np.cumsum([len(x) for x in o_t])])) and
+                    np.array_equal(t_id.cpu().numpy(), want) and np.array_equal(t_s.cpu().numpy(), w.subj[want]) and
+                    np.array_equal(t_r.cpu().numpy(), w.rel[want]) and np.array_equal(t_o.cpu().numpy(), w.obj[want]))
+        elif walk:
             l_off, l_ent = got.level(k, 0, nq)
             a = o_off[k * nq:(k + 1) * nq + 1]
             same = (np.array_equal(l_off[: nq + 1], a - a[0]) and

@@ -252,9 +252,9 @@ logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t h, int32_t 
  * triple / subject / relation / object (each int32[capacity] or NULL;
  * capacity checked: LOGOSKG_ERANGE), asynchronously on `stream`.  The calls
  * count level h-1 (they replace the level counted by
- * logoskg_result_level_offsets) and keep the level's entity list and one
- * int64 per entry in device memory until the result is freed or another range
- * is prepared.  The first call on a graph builds the triple indices of SUB's
+ * logoskg_result_level_offsets) and keep the level's entity list, one int64
+ * per entry and one or two int64 per 256 triples in device memory until the
+ * result is freed or another range is prepared.  The first call on a graph builds the triple indices of SUB's
  * rows (4 bytes per triple, freed with the graph).  Needs a resident
  * (unsharded) graph: LOGOSKG_EINVAL otherwise.
  */

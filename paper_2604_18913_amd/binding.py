@@ -230,21 +230,27 @@ class Result:
         return off, entity
 
     def active_triples(self, h: int, q_begin: int = 0, q_end: Optional[int] = None, components: bool = True,
-                       stream=None):
+                       out=None, stream=None):
         """``logoskg_result_triples_offsets`` + ``logoskg_result_triples_fetch``: T_h of the queries
         [q_begin, q_end) as (offsets int64[q_end - q_begin + 1], triple, subject, relation, object)
-        int32 device tensors (the last three None without ``components``)."""
+        int32 device tensors (the last three None without ``components``).  ``out`` = four int32
+        device tensors (or None entries) to write into instead of new ones."""
         torch = _torch()
         q_end = self.num_queries if q_end is None else q_end
         off = np.zeros(max(q_end - q_begin, 0) + 1, dtype=np.int64)
         _check(_load().logoskg_result_triples_offsets(self._h, h, q_begin, q_end,
                                                       off.ctypes.data_as(ctypes.c_void_p), _stream_handle(stream)))
         n = int(off[-1])
-        bufs = [torch.empty(n, dtype=torch.int32, device=self._g.device) for _ in range(4 if components else 1)]
-        ptrs = [b.data_ptr() for b in bufs] + [None] * (4 - len(bufs))
-        _check(_load().logoskg_result_triples_fetch(self._h, h, q_begin, q_end, n, *ptrs, _stream_handle(stream)))
-        bufs += [None] * (4 - len(bufs))
-        return (off, *bufs)
+        if out is not None:
+            bufs = list(out)
+            cap = min(int(b.numel()) for b in bufs if b is not None)
+        else:
+            bufs = [torch.empty(n, dtype=torch.int32, device=self._g.device) for _ in range(4 if components else 1)]
+            bufs += [None] * (4 - len(bufs))
+            cap = n
+        ptrs = [None if b is None else b.data_ptr() for b in bufs]
+        _check(_load().logoskg_result_triples_fetch(self._h, h, q_begin, q_end, cap, *ptrs, _stream_handle(stream)))
+        return (off, *[None if b is None else b[:n] for b in bufs])
 
     def traversed(self, stream=None):
         torch = _torch()

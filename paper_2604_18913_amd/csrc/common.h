@@ -203,8 +203,11 @@ struct logoskg_result {
     // active triples of one hop for one query range (logoskg_result_triples_offsets)
     int trip_h = -1, trip_q0 = 0, trip_q1 = 0;
     int64_t trip_n = 0;            // entries of level trip_h - 1 over the range
+    int64_t trip_total = 0;        // length of the concatenation of their rows of SUB
     int32_t *trip_ent = nullptr;   // [trip_n] those entities, query-major
-    long long *trip_off = nullptr; // [trip_n + 1] first output position of every entry's triples
+    long long *trip_off = nullptr; // [trip_n + 1] where every entry's row starts in that concatenation
+    long long *trip_chunk_entry = nullptr;  // [chunks + 1] entry behind the first position of every 256-position chunk
+    long long *trip_chunk_first = nullptr;  // [chunks + 1] with a whitelist: allowed triples before the chunk
     std::vector<int64_t> trip_off_host;  // [trip_q1 - trip_q0 + 1]
     std::vector<logoskg_hop_stats> stats;
 };

@@ -784,7 +784,8 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     (void)hipSetDevice(g->device);
     void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_base,
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
-                    r->lvl_mega_base, r->d_level_off, r->trip_ent, r->trip_off};
+                    r->lvl_mega_base, r->d_level_off, r->trip_ent, r->trip_off,
+                    r->trip_chunk_entry, r->trip_chunk_first};
     for (void *p : ptrs) g->pool.release(p);
     delete r;
 }

@@ -3,12 +3,21 @@
 // query's whitelist allows, written out with their components.
 //
 // The level's entity lists (query-major, ascending entity id) come from the
-// level-list path; every list entry then stands for one row of SUB.  A degree
-// kernel counts the allowed triples of every entry, a device-wide exclusive
-// prefix sum (rocPRIM) turns the counts into output positions, and an expansion
-// kernel copies the rows: one wavefront per entry, 64 triples per step,
-// compacted with a ballot when a whitelist removes some.  The output order is
-// therefore (query, subject, triple index).
+// level-list path; every list entry stands for one row of SUB, and the output
+// is the concatenation of those rows with the entries a whitelist forbids
+// removed: a stream compaction over the concatenated rows.  So the work is cut
+// by position, not by row, and a hub row of 100,000 triples costs as much per
+// triple as a row of three:
+//   1. row_first[i] = exclusive prefix sum of the row lengths (rocPRIM);
+//   2. chunk_entry[c] = the list entry that holds concatenated position
+//      c * 256 (written by the entries themselves);
+//   3. with a whitelist: every 256-position chunk counts its allowed triples,
+//      a second prefix sum gives the chunk's first output position;
+//   4. one block per chunk: a thread finds its entry by a binary search between
+//      chunk_entry[c] and chunk_entry[c + 1], reads its triple and writes it at
+//      its output position (its own position without a whitelist).
+// Reads of a row and all writes are contiguous across the lanes of a wavefront.
+// The output order is (query, subject, triple index).
 #include <cstring>
 
 #include <rocprim/device/device_scan.hpp>
@@ -19,14 +28,14 @@ namespace lkg {
 
 namespace {
 
-constexpr int kBlock = 256;
-constexpr long long kMaxBlocks = 1 << 16;
+constexpr int kBlock = 256;               // threads per block = concatenated positions per chunk
+constexpr long long kMaxBlocks = 1 << 20;
 
 // The query whose list holds position pos of the concatenated level lists: the
-// last q in [q0, q1) with level_off[q] <= pos (queries with empty lists share
+// last q in [qa, qb] with level_off[q] <= pos (queries with empty lists share
 // their offset with the next one and are skipped that way).
-__device__ __forceinline__ int query_of(const long long *__restrict__ level_off, int q0, int q1, long long pos) {
-    int lo = q0, hi = q1 - 1;
+__device__ __forceinline__ int query_of(const long long *__restrict__ level_off, int qa, int qb, long long pos) {
+    int lo = qa, hi = qb;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (level_off[mid] <= pos) lo = mid;
@@ -39,9 +48,9 @@ __device__ __forceinline__ bool allowed(const unsigned long long *__restrict__ a
     return (allow[(size_t)r * W + (q >> 6)] >> (q & 63)) & 1ull;
 }
 
-// deg[i] = number of triples of entry i's subject (no whitelist): one thread per entry
-__global__ void k_triple_degree(const int32_t *__restrict__ ent, long long n, const uint32_t *__restrict__ out_off,
-                                long long *deg) {
+// len[i] = number of triples of entry i's subject; len[n] = 0 (the prefix sum leaves the total there)
+__global__ void k_row_length(const int32_t *__restrict__ ent, long long n, const uint32_t *__restrict__ out_off,
+                             long long *len) {
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i <= n;
          i += (long long)gridDim.x * blockDim.x) {
         long long d = 0;
@@ -49,68 +58,147 @@ __global__ void k_triple_degree(const int32_t *__restrict__ ent, long long n, co
             const int32_t s = ent[i];
             d = (long long)(out_off[s + 1] - out_off[s]);
         }
-        deg[i] = d;  // deg[n] = 0: the prefix sum leaves the total there
+        len[i] = d;
     }
 }
 
-// the same with a whitelist: one wavefront per entry counts the allowed triples of the row
-__global__ void k_triple_degree_masked(const int32_t *__restrict__ ent, long long n,
-                                       const uint32_t *__restrict__ out_off, const uint16_t *__restrict__ out_rel,
-                                       const unsigned long long *__restrict__ allow, int W,
-                                       const long long *__restrict__ level_off, int q0, int q1, long long *deg) {
-    const long long waves = (long long)gridDim.x * (blockDim.x >> 6);
-    for (long long i = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); i <= n; i += waves) {
-        long long cnt = 0;
-        if (i < n) {
-            const int32_t s = ent[i];
-            const int q = query_of(level_off, q0, q1, level_off[q0] + i);
-            const uint32_t lo = out_off[s], hi = out_off[s + 1];
-            for (uint32_t p = lo + (uint32_t)lane(); p < hi; p += 64) cnt += allowed(allow, W, out_rel[p], q) ? 1 : 0;
-            cnt = wave_sum(cnt);
+// chunk_entry[c] = the entry whose row holds concatenated position c * kBlock, c = 0 .. nchunks - 1;
+// every such position lies in exactly one non-empty row.  chunk_entry[nchunks] = n - 1.
+__global__ void k_chunk_entry(const long long *__restrict__ row_first, long long n, long long nchunks,
+                              long long *chunk_entry) {
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long a = row_first[i], b = row_first[i + 1];
+        for (long long c = (a + kBlock - 1) / kBlock; c * kBlock < b; ++c) chunk_entry[c] = i;
+        if (i == n - 1) chunk_entry[nchunks] = n - 1;
+    }
+}
+
+// What the thread at concatenated position x has to copy.
+struct Position {
+    long long entry;  // list entry, -1 beyond the end
+    int32_t s;        // its subject
+    uint32_t p;       // index into the arrays of SUB's rows
+};
+
+__device__ __forceinline__ Position locate(long long x, long long total, long long c,
+                                           const long long *__restrict__ chunk_entry,
+                                           const long long *__restrict__ row_first,
+                                           const int32_t *__restrict__ ent, const uint32_t *__restrict__ out_off) {
+    Position r{-1, 0, 0};
+    if (x >= total) return r;
+    // the last entry in [chunk_entry[c], chunk_entry[c + 1]] whose row starts at or before x
+    long long lo = chunk_entry[c], hi = chunk_entry[c + 1];
+    while (lo < hi) {
+        const long long mid = (lo + hi + 1) >> 1;
+        if (row_first[mid] <= x) lo = mid;
+        else hi = mid - 1;
+    }
+    r.entry = lo;
+    r.s = ent[lo];
+    r.p = out_off[r.s] + (uint32_t)(x - row_first[lo]);
+    return r;
+}
+
+// Whitelist test of the triple at position x: the query comes from the entry's place in the level lists.
+__device__ __forceinline__ bool position_allowed(const Position &r, const uint16_t *__restrict__ out_rel,
+                                                 const unsigned long long *__restrict__ allow, int W,
+                                                 const long long *__restrict__ level_off, int q0, int q1) {
+    if (r.entry < 0) return false;
+    const int q = query_of(level_off, q0, q1 - 1, level_off[q0] + r.entry);
+    return allowed(allow, W, out_rel[r.p], q);
+}
+
+// chunk_count[c] = allowed triples among the positions of chunk c; chunk_count[nchunks] = 0
+__global__ void __launch_bounds__(kBlock)
+k_chunk_count(long long total, long long nchunks, const long long *__restrict__ chunk_entry,
+              const long long *__restrict__ row_first, const int32_t *__restrict__ ent,
+              const uint32_t *__restrict__ out_off, const uint16_t *__restrict__ out_rel,
+              const unsigned long long *__restrict__ allow, int W, const long long *__restrict__ level_off, int q0,
+              int q1, long long *chunk_count) {
+    __shared__ int wave_count[kBlock / 64];
+    for (long long c = blockIdx.x; c <= nchunks; c += gridDim.x) {
+        bool ok = false;
+        if (c < nchunks) {
+            const Position r = locate(c * kBlock + threadIdx.x, total, c, chunk_entry, row_first, ent, out_off);
+            ok = position_allowed(r, out_rel, allow, W, level_off, q0, q1);
         }
-        if (lane() == 0) deg[i] = cnt;
+        const unsigned long long b = __ballot(ok);
+        if (lane() == 0) wave_count[threadIdx.x >> 6] = __popcll(b);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int sum = 0;
+            for (int w = 0; w < kBlock / 64; ++w) sum += wave_count[w];
+            chunk_count[c] = sum;
+        }
+        __syncthreads();
     }
 }
 
-// picked[j] = first[level_off[q0 + j] - level_off[q0]], j = 0 .. q1 - q0
-__global__ void k_pick_offsets(const long long *__restrict__ first, const long long *__restrict__ level_off, int q0,
-                               int q1, long long *picked) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j <= q1 - q0) picked[j] = first[level_off[q0 + j] - level_off[q0]];
-}
-
-// One wavefront per list entry: copy the (allowed) triples of the subject's row to first[i]..
+// picked[j] = output position of the first triple of query q0 + j (j = q1 - q0: the total).  Without a
+// whitelist that is row_first of the query's first entry; with one, the allowed triples before it.
 template <bool MASK>
 __global__ void __launch_bounds__(kBlock)
-k_triple_expand(const int32_t *__restrict__ ent, long long n, const long long *__restrict__ first,
-                const uint32_t *__restrict__ out_off, const int32_t *__restrict__ out_obj,
-                const uint16_t *__restrict__ out_rel, const int32_t *__restrict__ out_eid,
-                const unsigned long long *__restrict__ allow, int W, const long long *__restrict__ level_off, int q0,
-                int q1, int32_t *triple, int32_t *subject, int32_t *relation, int32_t *object) {
-    const long long waves = (long long)gridDim.x * (blockDim.x >> 6);
-    for (long long i = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); i < n; i += waves) {
-        const int32_t s = ent[i];
-        const uint32_t lo = out_off[s], hi = out_off[s + 1];
-        long long w = first[i];
-        int q = 0;
-        if (MASK) q = query_of(level_off, q0, q1, level_off[q0] + i);
-        for (uint32_t p0 = lo; p0 < hi; p0 += 64) {
-            const uint32_t p = p0 + (uint32_t)lane();
-            bool ok = p < hi;
-            int rr = 0;
-            if (ok) {
-                rr = out_rel[p];
-                if (MASK) ok = allowed(allow, W, rr, q);
-            }
+k_pick_offsets(long long total, long long nchunks, const long long *__restrict__ chunk_entry,
+               const long long *__restrict__ row_first, const long long *__restrict__ chunk_first,
+               const int32_t *__restrict__ ent, const uint32_t *__restrict__ out_off,
+               const uint16_t *__restrict__ out_rel, const unsigned long long *__restrict__ allow, int W,
+               const long long *__restrict__ level_off, int q0, int q1, long long *picked) {
+    __shared__ int wave_count[kBlock / 64];
+    const int j = blockIdx.x;  // one block per boundary
+    const long long x = row_first[level_off[q0 + j] - level_off[q0]];
+    if (!MASK) {
+        if (threadIdx.x == 0) picked[j] = x;
+        return;
+    }
+    const long long c = x / kBlock;  // allowed triples of the chunk's positions below x are added
+    bool ok = false;
+    if (c < nchunks && c * kBlock + threadIdx.x < x) {
+        const Position r = locate(c * kBlock + threadIdx.x, total, c, chunk_entry, row_first, ent, out_off);
+        ok = position_allowed(r, out_rel, allow, W, level_off, q0, q1);
+    }
+    const unsigned long long b = __ballot(ok);
+    if (lane() == 0) wave_count[threadIdx.x >> 6] = __popcll(b);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long sum = chunk_first[c < nchunks ? c : nchunks];
+        for (int w = 0; w < kBlock / 64; ++w) sum += wave_count[w];
+        picked[j] = sum;
+    }
+}
+
+// One block per chunk of kBlock concatenated positions: every thread copies its triple.
+template <bool MASK>
+__global__ void __launch_bounds__(kBlock)
+k_triple_expand(long long total, long long nchunks, const long long *__restrict__ chunk_entry,
+                const long long *__restrict__ row_first, const long long *__restrict__ chunk_first,
+                const int32_t *__restrict__ ent, const uint32_t *__restrict__ out_off,
+                const int32_t *__restrict__ out_obj, const uint16_t *__restrict__ out_rel,
+                const int32_t *__restrict__ out_eid, const unsigned long long *__restrict__ allow, int W,
+                const long long *__restrict__ level_off, int q0, int q1, int32_t *__restrict__ triple,
+                int32_t *__restrict__ subject, int32_t *__restrict__ relation, int32_t *__restrict__ object) {
+    __shared__ int wave_count[kBlock / 64];
+    for (long long c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const long long x = c * kBlock + threadIdx.x;
+        const Position r = locate(x, total, c, chunk_entry, row_first, ent, out_off);
+        bool ok = r.entry >= 0;
+        int rr = 0;
+        if (ok) rr = out_rel[r.p];
+        long long pos = x;
+        if (MASK) {
+            if (ok) ok = allowed(allow, W, rr, query_of(level_off, q0, q1 - 1, level_off[q0] + r.entry));
             const unsigned long long b = __ballot(ok);
-            if (ok) {
-                const long long pos = w + __popcll(b & ((1ull << lane()) - 1ull));
-                if (triple) triple[pos] = out_eid[p];
-                if (subject) subject[pos] = s;
-                if (relation) relation[pos] = rr;
-                if (object) object[pos] = out_obj[p];
-            }
-            w += __popcll(b);
+            if (lane() == 0) wave_count[threadIdx.x >> 6] = __popcll(b);
+            __syncthreads();
+            pos = chunk_first[c] + __popcll(b & ((1ull << lane()) - 1ull));
+            for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pos += wave_count[w];
+            __syncthreads();
+        }
+        if (ok) {
+            if (triple) triple[pos] = out_eid[r.p];
+            if (subject) subject[pos] = r.s;
+            if (relation) relation[pos] = rr;
+            if (object) object[pos] = out_obj[r.p];
         }
     }
 }
@@ -121,12 +209,15 @@ unsigned blocks_for(long long items, int per_block) {
 }
 
 void drop_prepared(logoskg_result *r) {
-    r->g->pool.release(r->trip_ent);
-    r->g->pool.release(r->trip_off);
+    for (void *p : {(void *)r->trip_ent, (void *)r->trip_off, (void *)r->trip_chunk_entry, (void *)r->trip_chunk_first})
+        r->g->pool.release(p);
     r->trip_ent = nullptr;
     r->trip_off = nullptr;
+    r->trip_chunk_entry = nullptr;
+    r->trip_chunk_first = nullptr;
     r->trip_h = -1;
     r->trip_n = 0;
+    r->trip_total = 0;
     r->trip_off_host.clear();
 }
 
@@ -152,54 +243,84 @@ extern "C" logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int3
     LKG_TRY(logoskg_result_level_offsets(r, h - 1, level_off.data(), stream));
     const int64_t n = level_off[(size_t)q1] - level_off[(size_t)q0];
     const int nq = q1 - q0;
-    LKG_TRY(g->pool.alloc((void **)&r->trip_ent, std::max<int64_t>(n, 1) * sizeof(int32_t)));
-    LKG_TRY(g->pool.alloc((void **)&r->trip_off, (size_t)(n + 1) * sizeof(long long)));
-    LKG_TRY(logoskg_result_level_fetch(r, h - 1, q0, q1, n, r->trip_ent, stream));
+    const bool mask = r->has_mask;
 
-    long long *d_deg = nullptr, *d_picked = nullptr;
+    long long *d_len = nullptr, *d_count = nullptr, *d_picked = nullptr;
     void *d_tmp = nullptr;
     auto done = [&](logoskg_status s) {
-        g->pool.release(d_deg);
-        g->pool.release(d_picked);
-        g->pool.release(d_tmp);
+        for (void *p : {(void *)d_len, (void *)d_count, (void *)d_picked, d_tmp}) g->pool.release(p);
         if (s != LOGOSKG_OK) drop_prepared(r);
         return s;
     };
+    auto check = [&](hipError_t e, const char *what) {
+        if (e == hipSuccess) return LOGOSKG_OK;
+        set_error("%s failed: %s", what, hipGetErrorString(e));
+        return e == hipErrorOutOfMemory ? LOGOSKG_ENOMEM : LOGOSKG_EDEVICE;
+    };
+    // exclusive prefix sum of `count` int64 values through rocPRIM, temporary storage from the pool
+    auto prefix_sum = [&](long long *in, long long *out, size_t count) -> logoskg_status {
+        size_t bytes = 0;
+        logoskg_status s2 = check(rocprim::exclusive_scan(nullptr, bytes, in, out, 0ll, count,
+                                                          rocprim::plus<long long>(), st), "sizing the prefix sum");
+        if (s2 != LOGOSKG_OK) return s2;
+        g->pool.release(d_tmp);
+        d_tmp = nullptr;
+        if ((s2 = g->pool.alloc(&d_tmp, std::max<size_t>(bytes, 8))) != LOGOSKG_OK) return s2;
+        return check(rocprim::exclusive_scan(d_tmp, bytes, in, out, 0ll, count, rocprim::plus<long long>(), st),
+                     "prefix sum");
+    };
     logoskg_status s;
-    if ((s = g->pool.alloc((void **)&d_deg, (size_t)(n + 1) * sizeof(long long))) != LOGOSKG_OK) return done(s);
-    if ((s = g->pool.alloc((void **)&d_picked, (size_t)(nq + 1) * sizeof(long long))) != LOGOSKG_OK) return done(s);
-    size_t tmp_bytes = 0;
-    hipError_t e = rocprim::exclusive_scan(nullptr, tmp_bytes, d_deg, r->trip_off, 0ll, (size_t)(n + 1),
-                                           rocprim::plus<long long>(), st);
-    if (e == hipSuccess && (s = g->pool.alloc(&d_tmp, std::max<size_t>(tmp_bytes, 8))) != LOGOSKG_OK) return done(s);
-    if (e == hipSuccess) {
-        if (r->has_mask)
-            k_triple_degree_masked<<<dim3(blocks_for(n + 1, kBlock / 64)), dim3(kBlock), 0, st>>>(
-                r->trip_ent, n, g->out_off, g->out_rel, r->allow, r->W, r->d_level_off, q0, q1, d_deg);
-        else
-            k_triple_degree<<<dim3(blocks_for(n + 1, kBlock)), dim3(kBlock), 0, st>>>(r->trip_ent, n, g->out_off,
-                                                                                      d_deg);
-        e = rocprim::exclusive_scan(d_tmp, tmp_bytes, d_deg, r->trip_off, 0ll, (size_t)(n + 1),
-                                    rocprim::plus<long long>(), st);
+    if ((s = g->pool.alloc((void **)&r->trip_ent, std::max<int64_t>(n, 1) * sizeof(int32_t))) != LOGOSKG_OK ||
+        (s = g->pool.alloc((void **)&r->trip_off, (size_t)(n + 1) * sizeof(long long))) != LOGOSKG_OK ||
+        (s = g->pool.alloc((void **)&d_len, (size_t)(n + 1) * sizeof(long long))) != LOGOSKG_OK ||
+        (s = g->pool.alloc((void **)&d_picked, (size_t)(nq + 1) * sizeof(long long))) != LOGOSKG_OK)
+        return done(s);
+    if ((s = logoskg_result_level_fetch(r, h - 1, q0, q1, n, r->trip_ent, stream)) != LOGOSKG_OK) return done(s);
+
+    // 1. where every entry's row starts in the concatenation of the rows
+    k_row_length<<<dim3(blocks_for(n + 1, kBlock)), dim3(kBlock), 0, st>>>(r->trip_ent, n, g->out_off, d_len);
+    if ((s = prefix_sum(d_len, r->trip_off, (size_t)n + 1)) != LOGOSKG_OK) return done(s);
+    long long total = 0;
+    if ((s = check(hipMemcpyAsync(&total, r->trip_off + n, sizeof(total), hipMemcpyDeviceToHost, st), "copy")) !=
+            LOGOSKG_OK ||
+        (s = check(hipStreamSynchronize(st), "row lengths")) != LOGOSKG_OK)
+        return done(s);
+    const long long nchunks = (total + kBlock - 1) / kBlock;
+    // 2. the entry behind the first position of every chunk
+    if ((s = g->pool.alloc((void **)&r->trip_chunk_entry, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK)
+        return done(s);
+    if (n > 0)
+        k_chunk_entry<<<dim3(blocks_for(n, kBlock)), dim3(kBlock), 0, st>>>(r->trip_off, n, nchunks,
+                                                                            r->trip_chunk_entry);
+    // 3. with a whitelist: allowed triples per chunk and their prefix sums
+    if (mask) {
+        if ((s = g->pool.alloc((void **)&d_count, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK ||
+            (s = g->pool.alloc((void **)&r->trip_chunk_first, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK)
+            return done(s);
+        k_chunk_count<<<dim3(blocks_for(nchunks + 1, 1)), dim3(kBlock), 0, st>>>(
+            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_ent, g->out_off, g->out_rel, r->allow, r->W,
+            r->d_level_off, q0, q1, d_count);
+        if ((s = prefix_sum(d_count, r->trip_chunk_first, (size_t)nchunks + 1)) != LOGOSKG_OK) return done(s);
+        k_pick_offsets<true><<<dim3(nq + 1), dim3(kBlock), 0, st>>>(
+            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_chunk_first, r->trip_ent, g->out_off, g->out_rel,
+            r->allow, r->W, r->d_level_off, q0, q1, d_picked);
+    } else {
+        k_pick_offsets<false><<<dim3(nq + 1), dim3(kBlock), 0, st>>>(
+            total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr, r->trip_ent, g->out_off, g->out_rel, nullptr,
+            r->W, r->d_level_off, q0, q1, d_picked);
     }
     std::vector<long long> picked((size_t)nq + 1, 0);
-    if (e == hipSuccess) {
-        k_pick_offsets<<<dim3((nq + 1 + kBlock - 1) / kBlock), dim3(kBlock), 0, st>>>(r->trip_off, r->d_level_off, q0,
-                                                                                      q1, d_picked);
-        e = hipGetLastError();
-    }
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(picked.data(), d_picked, (size_t)(nq + 1) * sizeof(long long), hipMemcpyDeviceToHost, st);
-    if (e == hipSuccess) e = hipStreamSynchronize(st);
-    if (e != hipSuccess) {
-        set_error("counting the active triples failed: %s", hipGetErrorString(e));
-        return done(LOGOSKG_EDEVICE);
-    }
+    if ((s = check(hipGetLastError(), "launch")) != LOGOSKG_OK ||
+        (s = check(hipMemcpyAsync(picked.data(), d_picked, (size_t)(nq + 1) * sizeof(long long),
+                                  hipMemcpyDeviceToHost, st), "copy")) != LOGOSKG_OK ||
+        (s = check(hipStreamSynchronize(st), "counting the active triples")) != LOGOSKG_OK)
+        return done(s);
     r->trip_off_host.assign(picked.begin(), picked.end());
     r->trip_h = h;
     r->trip_q0 = q0;
     r->trip_q1 = q1;
     r->trip_n = n;
+    r->trip_total = total;
     for (int j = 0; j <= nq; ++j) triple_off[j] = (int64_t)picked[(size_t)j];
     return done(LOGOSKG_OK);
 }
@@ -226,20 +347,26 @@ extern "C" logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
-    const long long n = r->trip_n;
-    dim3 grid(blocks_for(n, kBlock / 64)), block(kBlock);
+    const long long total = r->trip_total, nchunks = (total + kBlock - 1) / kBlock;
+    dim3 grid(blocks_for(nchunks, 1)), block(kBlock);
     {
         ProfScope ps(g->prof, KK_TRIPLES, st);
         if (r->has_mask)
-            k_triple_expand<true><<<grid, block, 0, st>>>(r->trip_ent, n, r->trip_off, g->out_off, g->out_obj,
+            k_triple_expand<true><<<grid, block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off,
+                                                          r->trip_chunk_first, r->trip_ent, g->out_off, g->out_obj,
                                                           g->out_rel, g->out_eid, r->allow, r->W, r->d_level_off, q0,
                                                           q1, triple, subject, relation, object);
         else
-            k_triple_expand<false><<<grid, block, 0, st>>>(r->trip_ent, n, r->trip_off, g->out_off, g->out_obj,
-                                                           g->out_rel, g->out_eid, nullptr, r->W, r->d_level_off, q0,
-                                                           q1, triple, subject, relation, object);
+            k_triple_expand<false><<<grid, block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr,
+                                                           r->trip_ent, g->out_off, g->out_obj, g->out_rel, g->out_eid,
+                                                           nullptr, r->W, r->d_level_off, q0, q1, triple, subject,
+                                                           relation, object);
     }
     LKG_HIP(hipGetLastError());
-    if (g->prof.on) g->prof.acc[KK_TRIPLES].units[3] += need;
+    if (g->prof.on) {
+        g->prof.acc[KK_TRIPLES].units[0] += r->trip_n;  // rows of SUB copied
+        g->prof.acc[KK_TRIPLES].units[1] += total;      // triples read
+        g->prof.acc[KK_TRIPLES].units[3] += need;       // triples written
+    }
     return LOGOSKG_OK;
 }

@@ -129,6 +129,37 @@ def test_config2_full_size_walk_exact_levels():
     g.close()
 
 
+def test_config2_full_size_active_triples():
+    # T_h (Eq. 5-7) at full size: sampled queries, every hop, all four columns against the oracle;
+    # and for every query of a 64-query range |T_h| = the traversed count of that hop
+    m = lkg()
+    w = kggen.config2()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    res = g.khop(w.seed_off, w.seeds, w.k)
+    qs = sampled_queries(w.num_queries, 6, 21, np.diff(res.offsets()))
+    so, sd, sm = sub_batch(w, qs)
+    ro, ent, hop, _, _ = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, w.k, sm)
+    trav = res.traversed().cpu().numpy()
+    for h in range(1, w.k + 1):
+        for i, q in enumerate(qs):
+            a, b = int(ro[i]), int(ro[i + 1])
+            t0 = time.time()
+            want = oracle.active_triples(w.num_entities, w.subj, w.rel, ent[a:b][hop[a:b] == h - 1])
+            off, t, s_, r_, o_ = res.active_triples(h, int(q), int(q) + 1)
+            assert off[-1] == len(want) == trav[q, h - 1], f"hop {h} query {q}: count"
+            t = t.cpu().numpy()
+            assert np.array_equal(t, want), f"hop {h} query {q}: triples"
+            assert np.array_equal(s_.cpu().numpy(), w.subj[want])
+            assert np.array_equal(r_.cpu().numpy(), w.rel[want])
+            assert np.array_equal(o_.cpu().numpy(), w.obj[want])
+            if i == 0:
+                log(f"hop {h} query {q}: {len(want)} triples, oracle + compare {time.time() - t0:.1f}s")
+        off = res.active_triples(h, 128, 192, components=False)[0]
+        assert np.array_equal(np.diff(off), trav[128:192, h - 1]), f"hop {h}: counts of a 64-query range"
+    res.close()
+    g.close()
+
+
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 def test_config3_full_size_masks_and_paths(k):
     m = lkg()
