@@ -48,6 +48,10 @@ def _load():
         lib.oracle_walk_levels.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, P, ctypes.c_int32,
                                            P, P, ctypes.c_int32, P, ctypes.c_int32, ctypes.c_int32,
                                            P, ctypes.POINTER(P)]
+        lib.oracle_walk_paths.restype = ctypes.c_int
+        lib.oracle_walk_paths.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, P, ctypes.c_int32,
+                                          P, P, ctypes.c_int32, P, ctypes.c_int32, ctypes.c_int64,
+                                          P, P, P, ctypes.c_int32, P, P]
         lib.oracle_active_triples.restype = ctypes.c_int64
         lib.oracle_active_triples.argtypes = [ctypes.c_int64, ctypes.c_int32, P, P, ctypes.c_int64, P, P,
                                               ctypes.POINTER(P)]
@@ -203,3 +207,38 @@ def active_triples(num_entities: int, subj, rel, frontier, rel_mask_row: Optiona
         res = np.ctypeslib.as_array(ctypes.cast(out, ctypes.POINTER(ctypes.c_int32)), shape=(n,)).copy()
     lib.oracle_free(out)
     return res
+
+
+def walk_paths(num_entities: int, subj, rel, obj, seed_off, seeds, k: int, pair_query, pair_target,
+               pair_len, max_paths: int = 16, rel_mask: Optional[np.ndarray] = None):
+    """First ``max_paths`` walks of exactly ``pair_len[i]`` allowed triples from a seed of
+    ``pair_query[i]`` to ``pair_target[i]``, ordered by (t_d, .., t_1).
+
+    Returns ``(count int32[n], edges int32[n, max_paths, k])`` with -1 padding;
+    every walk is written seed -> target.
+    """
+    lib = _load()
+    subj, p_s = _c(subj, np.int32)
+    rel, p_r = _c(rel, np.int32)
+    obj, p_o = _c(obj, np.int32)
+    seed_off, p_so = _c(seed_off, np.int64)
+    seeds, p_sd = _c(seeds, np.int32)
+    pq, p_pq = _c(pair_query, np.int32)
+    pt, p_pt = _c(pair_target, np.int32)
+    pl, p_pl = _c(pair_len, np.int32)
+    Q = seed_off.shape[0] - 1
+    if rel_mask is not None:
+        rel_mask, p_m = _c(rel_mask, np.uint64)
+        rw = rel_mask.shape[1]
+    else:
+        p_m, rw = None, 0
+    n = pq.shape[0]
+    count = np.zeros(n, dtype=np.int32)
+    edges = np.full((n, max_paths, max(k, 0)), -1, dtype=np.int32)
+    rc = lib.oracle_walk_paths(subj.shape[0], num_entities, p_s, p_r, p_o, Q, p_so, p_sd, k,
+                               p_m, rw, n, p_pq, p_pt, p_pl, max_paths,
+                               count.ctypes.data_as(ctypes.c_void_p),
+                               edges.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise RuntimeError("oracle_walk_paths failed")
+    return count, edges

@@ -43,6 +43,17 @@
  * closed forms on cycles / paths / self loops, and against oracle_khop itself
  * (union over h = reached set, first h = hop).
  *
+ * Walk listing (oracle_walk_paths): the complete paths of Sec. 3.3 for the
+ * iteration without a visited set.  For a pair (query, target, length d) the
+ * walks are all edge sequences (t_1..t_d) with s_{t_1} a seed, o_{t_i} =
+ * s_{t_{i+1}}, o_{t_d} = target and every r_{t_i} in M; an entity may repeat.
+ * They are ordered lexicographically by (t_d, t_{d-1}, .., t_1) and the first
+ * max_paths are returned, each written seed -> target.  Evaluated backward from
+ * the target through the sets q^(d-1), .., q^(0), which are rebuilt here by
+ * rescanning the triple list once per hop.  Pins
+ * (tests/test_oracle_walk_paths_pins.py): forward enumeration of every walk,
+ * walk counts from integer powers of the adjacency matrix, closed forms.
+ *
  * Active-triple sets (oracle_active_triples): T_h of Eq. 5-6 for one query,
  * given the support of q^(h-1) as an entity list: every triple whose subject
  * is in that list and whose relation is in M, written out with the triple list
@@ -489,4 +500,85 @@ int64_t oracle_active_triples(int64_t T, int32_t E, const int32_t *subj, const i
     free(act);
     free(in_q);
     return n;
+}
+
+/* ------------------------------------------------------------------------
+ * Walks of exactly pair_len[i] allowed triples from a seed of pair_query[i] to
+ * pair_target[i] (Sec. 3.3, "complete paths"), first max_paths in
+ * (t_d, .., t_1) order.  count[i] = number written (0 when the target does not
+ * end such a walk; 1 empty walk for length 0 at a seed); edges is
+ * int32[n_pairs][max_paths][k], -1 padded, each walk written seed -> target.
+ */
+typedef struct {
+    const int32_t *subj, *rel;
+    const int64_t *ofirst;
+    const int32_t *oids;
+    const uint8_t *member;   /* [(k+1)][E]: member[h * E + e] = q^(h)[e] */
+    int32_t E;
+    const uint64_t *mask;
+    int32_t k, d, max_paths, found;
+    int32_t *out;
+    int32_t *stack;
+} walk_ctx;
+
+static void extend_walk(walk_ctx *c, int32_t v, int level)
+{
+    if (c->found >= c->max_paths) return;
+    if (level == 0) {                       /* v is a seed: q^(0)[v] = 1 was checked by the caller */
+        int32_t *row = c->out + (size_t)c->found * c->k;
+        for (int i = 0; i < c->d; ++i) row[i] = c->stack[c->d - 1 - i];
+        c->found++;
+        return;
+    }
+    for (int64_t j = c->ofirst[v]; j < c->ofirst[v + 1]; ++j) {
+        int32_t t = c->oids[j];
+        if (!c->member[(size_t)(level - 1) * c->E + c->subj[t]]) continue;   /* s_t ends a walk of level-1 triples */
+        if (!relation_allowed(c->mask, c->rel[t])) continue;
+        c->stack[c->d - level] = t;
+        extend_walk(c, c->subj[t], level - 1);
+        if (c->found >= c->max_paths) return;
+    }
+}
+
+int oracle_walk_paths(int64_t T, int32_t E, const int32_t *subj, const int32_t *rel,
+                      const int32_t *obj, int32_t Q, const int64_t *seed_off,
+                      const int32_t *seeds, int32_t k, const uint64_t *rel_mask,
+                      int32_t rel_words, int64_t n_pairs, const int32_t *pair_query,
+                      const int32_t *pair_target, const int32_t *pair_len, int32_t max_paths,
+                      int32_t *count, int32_t *edges)
+{
+    if (k < 0 || k > 254 || max_paths < 1 || E <= 0) return -1;
+    int64_t *ofirst = NULL;
+    int32_t *oids = NULL;
+    if (build_index(obj, T, E, &ofirst, &oids) != 0) return -1;
+    uint8_t *member = (uint8_t *)malloc((size_t)(k + 1) * (size_t)E);
+    int32_t *stack = (int32_t *)malloc((size_t)(k > 0 ? k : 1) * sizeof(int32_t));
+    if (!member || !stack) { free(member); free(stack); free(ofirst); free(oids); return -1; }
+    for (int64_t i = 0; i < n_pairs * (int64_t)max_paths * k; ++i) edges[i] = -1;
+    int32_t cur_q = -1;
+    for (int64_t i = 0; i < n_pairs; ++i) {
+        int32_t q = pair_query[i], v = pair_target[i], d = pair_len[i];
+        count[i] = 0;
+        if (q < 0 || q >= Q || v < 0 || v >= E || d < 0 || d > k) continue;
+        const uint64_t *mask = rel_mask ? rel_mask + (size_t)q * rel_words : NULL;
+        if (q != cur_q) {                   /* q^(0) .. q^(k) of this query, Eq. 4 hop by hop */
+            memset(member, 0, (size_t)(k + 1) * (size_t)E);
+            for (int64_t a = seed_off[q]; a < seed_off[q + 1]; ++a) member[seeds[a]] = 1;
+            for (int h = 1; h <= k; ++h)
+                for (int64_t t = 0; t < T; ++t)
+                    if (member[(size_t)(h - 1) * E + subj[t]] && relation_allowed(mask, rel[t]))
+                        member[(size_t)h * E + obj[t]] = 1;
+            cur_q = q;
+        }
+        if (!member[(size_t)d * E + v]) continue;
+        walk_ctx c;
+        c.subj = subj; c.rel = rel; c.ofirst = ofirst; c.oids = oids; c.member = member; c.E = E;
+        c.mask = mask; c.k = k; c.d = d; c.max_paths = max_paths; c.found = 0;
+        c.out = edges + (size_t)i * max_paths * k;
+        c.stack = stack;
+        extend_walk(&c, v, d);
+        count[i] = c.found;
+    }
+    free(member); free(stack); free(ofirst); free(oids);
+    return 0;
 }

@@ -11,6 +11,7 @@ import oracle
 import test_oracle_pins as pins
 import test_oracle_walk_pins as wpins
 import test_oracle_triples_pins as tpins
+import test_oracle_walk_paths_pins as wppins
 
 MUTATIONS = {
     "tie_break_dropped": ("} else if (st->hop[v] == h && t < st->pred[v]) {",
@@ -37,6 +38,13 @@ MUTATIONS = {
     "walk_sets_the_subject": ("                        int32_t v = obj[t];\n                        if (stamp[v] != mark)",
                               "                        int32_t v = subj[t];\n                        if (stamp[v] != mark)"),
     "walk_last_level_missing": ("                if (h == k) break;", "                if (h >= k - 1) break;"),
+    # walk listing
+    "walk_paths_wrong_level": ("if (!c->member[(size_t)(level - 1) * c->E + c->subj[t]]) continue;",
+                               "if (!c->member[(size_t)level * c->E + c->subj[t]]) continue;"),
+    "walk_paths_start_anywhere": ("for (int64_t a = seed_off[q]; a < seed_off[q + 1]; ++a) member[seeds[a]] = 1;",
+                                  "memset(member, 1, (size_t)E);"),
+    "walk_paths_levels_never_advance": ("                        member[(size_t)h * E + obj[t]] = 1;",
+                                        "                        member[(size_t)h * E + subj[t]] = 1;"),
     # active-triple sets
     "triples_ignore_whitelist": ("in_q[subj[t]] && relation_allowed(mask, rel[t])", "in_q[subj[t]]"),
     "triples_ordered_by_index_only": ("    if (x->s != y->s) return x->s < y->s ? -1 : 1;\n", ""),
@@ -53,6 +61,9 @@ PIN_CALLS = [
     lambda: pins.test_first_path_is_the_pred_chain(),
     lambda: [wpins.test_against_boolean_matrix_powers(s, m) for s in range(3) for m in (False, True)],
     lambda: wpins.test_cycle_path_self_loop_and_bipartite(),
+    lambda: wppins.test_hand_worked_example(),
+    lambda: [wppins.test_against_forward_enumeration(s, m) for s in range(3) for m in (False, True)],
+    lambda: wppins.test_closed_forms(),
     lambda: tpins.test_hand_worked_example(),
     lambda: [tpins.test_against_dense_incidence_product(s, m) for s in range(3) for m in (False, True)],
     lambda: tpins.test_closed_forms(),
@@ -71,7 +82,8 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
                            str(mutated)])
     good = oracle._load()
     lib = ctypes.CDLL(lib_path)
-    for fn in ("oracle_khop", "oracle_paths", "oracle_walk_levels", "oracle_active_triples", "oracle_free",
+    for fn in ("oracle_khop", "oracle_paths", "oracle_walk_levels", "oracle_walk_paths", "oracle_active_triples",
+               "oracle_free",
                "oracle_num_threads"):
         getattr(lib, fn).argtypes = getattr(good, fn).argtypes
         getattr(lib, fn).restype = getattr(good, fn).restype
