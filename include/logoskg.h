@@ -292,6 +292,21 @@ logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const in
                              const int32_t *target, int64_t n_pairs, int32_t max_paths,
                              int32_t *path_count, int32_t *path_edges, void *stream);
 
+/*
+ * Sec. 3.3, complete paths of the plain iteration: for pair i = (query_idx[i],
+ * target[i], length[i]) the walks are the sequences (t_1..t_d), d = length[i]
+ * in [0, k], of allowed triples that chain from a seed of the query to the
+ * target (o_{t_j} = s_{t_{j+1}}; entities may repeat).  Same order
+ * ((t_d, .., t_1) lexicographic), limit, layout and memory rules as
+ * logoskg_paths; path_count[i] = 0 when the target ends no such walk, 1 empty
+ * walk for length 0 at a seed.  `r` must come from a LOGOSKG_WALK_EXACT search
+ * (LOGOSKG_EINVAL otherwise); with the targets of logoskg_result_level_fetch(k)
+ * and length k this lists every complete path of length k.
+ */
+logoskg_status logoskg_walks(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                             const int32_t *target, const int32_t *length, int64_t n_pairs,
+                             int32_t max_paths, int32_t *path_count, int32_t *path_edges, void *stream);
+
 const char *logoskg_last_error(void);
 const char *logoskg_version(void);
 

@@ -121,6 +121,8 @@ def _load():
     lib.logoskg_result_free.argtypes = [P]
     lib.logoskg_paths.restype = ctypes.c_int
     lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_walks.restype = ctypes.c_int
+    lib.logoskg_walks.argtypes = [P, P, P, P, P, I64, I32, P, P, P]
     lib.logoskg_profile_enable.restype = ctypes.c_int
     lib.logoskg_profile_enable.argtypes = [P, I32]
     lib.logoskg_profile_read.restype = ctypes.c_int
@@ -363,6 +365,20 @@ class Graph:
         count = torch.empty(n, dtype=torch.int32, device=self.device)
         edges = torch.empty((n, max_paths, result.k), dtype=torch.int32, device=self.device)
         _check(_load().logoskg_paths(self._h, result._h, q.data_ptr(), t.data_ptr(), n, max_paths,
+                                     count.data_ptr(), edges.data_ptr() if edges.numel() else None,
+                                     _stream_handle(stream)))
+        return count, edges
+
+    def walks(self, result: Result, query_idx, target, length, max_paths: int = 16, stream=None):
+        """``logoskg_walks``: (count int32[n], edges int32[n, max_paths, k]) device tensors."""
+        torch = _torch()
+        q = _dev_tensor(query_idx, torch.int32, self.device)
+        t = _dev_tensor(target, torch.int32, self.device)
+        d = _dev_tensor(length, torch.int32, self.device)
+        n = q.numel()
+        count = torch.empty(n, dtype=torch.int32, device=self.device)
+        edges = torch.empty((n, max_paths, result.k), dtype=torch.int32, device=self.device)
+        _check(_load().logoskg_walks(self._h, result._h, q.data_ptr(), t.data_ptr(), d.data_ptr(), n, max_paths,
                                      count.data_ptr(), edges.data_ptr() if edges.numel() else None,
                                      _stream_handle(stream)))
         return count, edges

@@ -5,6 +5,12 @@
 // ends at a seed, so a depth-first walk over the object rows (edge ids
 // ascending) lists the paths in (t_d, t_{d-1}, .., t_1) order and can stop at
 // max_paths.
+//
+// logoskg_walks lists walks of a given number of triples on a result of the
+// plain iteration (no visited set) with the same kernel: there level h holds
+// the ends of the walks of h triples, so the backward walk from level d of the
+// target through levels d-1 .. 0 meets exactly the walks of d allowed triples
+// from a seed (Sec. 3.3: complete paths, extended hop by hop).
 #include "common.h"
 
 namespace lkg {
@@ -14,7 +20,8 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
                         const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ in_off,
                         const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
                         const int32_t *__restrict__ in_eid, const int32_t *__restrict__ query_idx,
-                        const int32_t *__restrict__ target, int max_paths, int32_t *path_count,
+                        const int32_t *__restrict__ target, const int32_t *__restrict__ length, int max_paths,
+                        int32_t *path_count,
                         int32_t *path_edges, int32_t *stk_vertex, uint32_t *stk_pos, int32_t *stk_edge) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pairs) return;
@@ -26,8 +33,13 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
     const int w = q >> 6;
     const unsigned long long bit = 1ull << (q & 63);
     int d = -1;
-    for (int h = 0; h <= k; ++h)
-        if (levels[(size_t)h * plane + (size_t)v * W + w] & bit) { d = h; break; }
+    if (length) {  // walks of exactly that many triples: the target has to sit in that level
+        const int want = length[i];
+        if (want >= 0 && want <= k && (levels[(size_t)want * plane + (size_t)v * W + w] & bit)) d = want;
+    } else {       // shortest paths: the first level that holds the target
+        for (int h = 0; h <= k; ++h)
+            if (levels[(size_t)h * plane + (size_t)v * W + w] & bit) { d = h; break; }
+    }
     if (d < 0) return;
     if (d == 0) { path_count[i] = 1; return; }
     // explicit stack, entry l (1..d) = the vertex at hop l of the partial path, the next
@@ -70,10 +82,9 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
 
 using namespace lkg;
 
-extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
-                                        const int32_t *target, int64_t n_pairs, int32_t max_paths,
-                                        int32_t *path_count, int32_t *path_edges, void *stream) {
-    if (!g || !r || r->g != g) { set_error("graph / result mismatch"); return LOGOSKG_EINVAL; }
+static logoskg_status list_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                 const int32_t *target, const int32_t *length, int64_t n_pairs, int32_t max_paths,
+                                 int32_t *path_count, int32_t *path_edges, void *stream) {
     if (n_pairs < 0 || max_paths < 1 || max_paths > LOGOSKG_MAX_PATHS) {
         set_error("bad n_pairs / max_paths");
         return LOGOSKG_EINVAL;
@@ -84,7 +95,6 @@ extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *
         return LOGOSKG_EINVAL;
     }
     if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
-    if (r->walk_exact) { set_error("shortest paths are not defined for a LOGOSKG_WALK_EXACT result"); return LOGOSKG_EINVAL; }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
     const int k = r->k;
@@ -97,11 +107,34 @@ extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *
     k_paths<<<dim3((unsigned)((n_pairs + 127) / 128)), dim3(128), 0, st>>>(
         n_pairs, r->Q, k, r->W, g->E, r->Epad * r->W, (const unsigned long long *)r->levels,
         r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, g->in_sub, g->in_rel, g->in_eid,
-        query_idx, target, max_paths, path_count, path_edges, sv, sp, se);
+        query_idx, target, length, max_paths, path_count, path_edges, sv, sp, se);
     hipError_t e = hipGetLastError();
     hipError_t e2 = hipStreamSynchronize(st);  // the workspace goes back to the pool below
     g->pool.release(ws);
     LKG_HIP(e);
     LKG_HIP(e2);
     return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                        const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                                        int32_t *path_count, int32_t *path_edges, void *stream) {
+    if (!g || !r || r->g != g) { set_error("graph / result mismatch"); return LOGOSKG_EINVAL; }
+    if (r->walk_exact) {
+        set_error("shortest paths are not defined for a LOGOSKG_WALK_EXACT result: use logoskg_walks");
+        return LOGOSKG_EINVAL;
+    }
+    return list_paths(g, r, query_idx, target, nullptr, n_pairs, max_paths, path_count, path_edges, stream);
+}
+
+extern "C" logoskg_status logoskg_walks(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                        const int32_t *target, const int32_t *length, int64_t n_pairs,
+                                        int32_t max_paths, int32_t *path_count, int32_t *path_edges, void *stream) {
+    if (!g || !r || r->g != g) { set_error("graph / result mismatch"); return LOGOSKG_EINVAL; }
+    if (!r->walk_exact) {
+        set_error("walks of a given length need a LOGOSKG_WALK_EXACT result (levels = ends of the walks of h triples)");
+        return LOGOSKG_EINVAL;
+    }
+    if (n_pairs > 0 && !length) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    return list_paths(g, r, query_idx, target, length, n_pairs, max_paths, path_count, path_edges, stream);
 }

@@ -125,6 +125,22 @@ def test_config2_full_size_walk_exact_levels():
             assert off[q + 1] - off[q] == b - a, f"level {h} query {q}: count"
             _, ent = res.level(h, int(q), int(q) + 1)
             assert np.array_equal(ent.cpu().numpy(), want_ent[a:b]), f"level {h} query {q}: entities"
+    # complete paths: walks of exactly h triples to sampled members of levels 2 and 3 (and a few misses)
+    rng = np.random.default_rng(17)
+    pq_local, pq, pt, pl = [], [], [], []
+    for i, q in enumerate(qs[:6]):
+        for h in (2, 3):
+            a, b = int(want_off[h * n + i]), int(want_off[h * n + i + 1])
+            if b > a:
+                for v in want_ent[a:b][rng.integers(0, b - a, size=40)]:
+                    pq_local.append(i); pq.append(int(q)); pt.append(int(v)); pl.append(h)
+            pq_local.append(i); pq.append(int(q)); pt.append(int(rng.integers(0, w.num_entities))); pl.append(h)
+    t0 = time.time()
+    cnt_o, edges_o = oracle.walk_paths(w.num_entities, w.subj, w.rel, w.obj, so, sd, w.k, pq_local, pt, pl, 16, sm)
+    log(f"oracle walks for {len(pt)} pairs: {time.time() - t0:.1f}s, {int(cnt_o.sum())} walks")
+    cnt, edges = g.walks(res, pq, pt, pl, 16)
+    assert np.array_equal(cnt.cpu().numpy(), cnt_o)
+    assert np.array_equal(edges.cpu().numpy(), edges_o)
     res.close()
     g.close()
 
