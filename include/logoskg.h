@@ -131,6 +131,22 @@ logoskg_status logoskg_profile_read(logoskg_graph *g, logoskg_kernel_profile *ou
 logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_t *shard_of_entity /*[E]*/,
                                        int64_t *triples_per_shard /*[num_shards]*/);
 
+/*
+ * Sec. 3.4 "On-demand caching", batch processing: queries are grouped by the
+ * sub-graphs they need, processed jointly and the results restored afterwards.
+ * The need of a query is taken from its seeds through the map P (the sub-graphs
+ * its first hop loads).  order[i] = index of the query to run i-th: queries are
+ * sorted by their ascending list of distinct shard ids, compared
+ * lexicographically (a query none of whose seeds is a subject comes first);
+ * queries with the same list keep their input order.  The caller cuts `order`
+ * into batches, builds the seed lists of each batch in that order and puts the
+ * results back with the same permutation.  seed_off (int64[num_queries + 1]),
+ * seeds and order (int32[num_queries]) are HOST arrays; nothing runs on the GPU.
+ * On an unsharded graph the order is the identity.
+ */
+logoskg_status logoskg_schedule_queries(const logoskg_graph *g, const int64_t *seed_off, const int32_t *seeds,
+                                        int64_t num_queries, int32_t *order);
+
 /* ------------------------------------------------------------------- khop */
 
 #define LOGOSKG_DIR_AUTO 0u       /* choose push or pull per hop from the frontier's edge count */

@@ -10,6 +10,9 @@ INFRASTRUCTURE ONLY, plain Python.
   least-recently-used replacement, counting loads, evictions and hits.
 * shard_accesses: the sub-graphs Algorithm 1 touches, hop by hop (those that
   hold a subject of the current frontier), in ascending shard order.
+* schedule_queries: the batch-processing order of Sec. 3.4 -- queries grouped by
+  the sub-graphs their seeds need (through P), identical needs adjacent, the
+  input order kept among equals.
 """
 from __future__ import annotations
 
@@ -80,3 +83,20 @@ def shard_accesses(P, subj, num_entities, k, entity, hop):
             order.reverse()
         seq.extend(order)
     return seq
+
+
+def query_needs(P, seed_off, seeds):
+    """needs[q] = ascending tuple of the distinct sub-graphs that hold a seed of query q."""
+    needs = []
+    for q in range(len(seed_off) - 1):
+        shards = {int(P[e]) for e in seeds[seed_off[q]:seed_off[q + 1]] if P[e] >= 0}
+        needs.append(tuple(sorted(shards)))
+    return needs
+
+
+def schedule_queries(P, seed_off, seeds):
+    """Order in which to process the queries: sorted by their needs (tuples compared
+    lexicographically, the empty need first), input order kept among equal needs."""
+    needs = query_needs(P, seed_off, seeds)
+    return np.array(sorted(range(len(needs)), key=lambda q: needs[q]), dtype=np.int32)
+

@@ -121,6 +121,8 @@ def _load():
     lib.logoskg_result_free.argtypes = [P]
     lib.logoskg_paths.restype = ctypes.c_int
     lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_schedule_queries.restype = ctypes.c_int
+    lib.logoskg_schedule_queries.argtypes = [P, P, P, I64, P]
     lib.logoskg_walks.restype = ctypes.c_int
     lib.logoskg_walks.argtypes = [P, P, P, P, P, I64, I32, P, P, P]
     lib.logoskg_profile_enable.restype = ctypes.c_int
@@ -368,6 +370,17 @@ class Graph:
                                      count.data_ptr(), edges.data_ptr() if edges.numel() else None,
                                      _stream_handle(stream)))
         return count, edges
+
+    def schedule_queries(self, seed_off, seeds) -> np.ndarray:
+        """``logoskg_schedule_queries``: the order (int32[Q] of query indices) that groups the
+        queries by the sub-graphs their seeds need; host arrays in, host array out."""
+        so = np.ascontiguousarray(seed_off, dtype=np.int64)
+        sd = np.ascontiguousarray(seeds, dtype=np.int32)
+        order = np.zeros(so.shape[0] - 1, dtype=np.int32)
+        _check(_load().logoskg_schedule_queries(self._h, so.ctypes.data_as(ctypes.c_void_p),
+                                                sd.ctypes.data_as(ctypes.c_void_p), so.shape[0] - 1,
+                                                order.ctypes.data_as(ctypes.c_void_p)))
+        return order
 
     def walks(self, result: Result, query_idx, target, length, max_paths: int = 16, stream=None):
         """``logoskg_walks``: (count int32[n], edges int32[n, max_paths, k]) device tensors."""

@@ -613,3 +613,37 @@ extern "C" logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_
         memcpy(triples_per_shard, g->shard_triples.data(), (size_t)g->num_shards * sizeof(int64_t));
     return LOGOSKG_OK;
 }
+
+extern "C" logoskg_status logoskg_schedule_queries(const logoskg_graph *g, const int64_t *seed_off,
+                                                   const int32_t *seeds, int64_t num_queries, int32_t *order) {
+    if (!g || !seed_off || !order || num_queries < 0 || num_queries > 0x7fffffff) {
+        set_error("bad argument");
+        return LOGOSKG_EINVAL;
+    }
+    if (seed_off[0] != 0) { set_error("seed_off[0] must be 0"); return LOGOSKG_EINVAL; }
+    for (int64_t q = 0; q < num_queries; ++q)
+        if (seed_off[q + 1] < seed_off[q]) { set_error("seed_off decreases at query %lld", (long long)q); return LOGOSKG_EINVAL; }
+    if (seed_off[num_queries] > 0 && !seeds) { set_error("NULL seeds"); return LOGOSKG_EINVAL; }
+    for (int64_t i = 0; i < seed_off[num_queries]; ++i)
+        if ((uint32_t)seeds[i] >= (uint32_t)g->E) {
+            set_error("seed %d at position %lld is out of range", seeds[i], (long long)i);
+            return LOGOSKG_EINVAL;
+        }
+    for (int64_t q = 0; q < num_queries; ++q) order[q] = (int32_t)q;
+    if (g->num_shards <= 1) return LOGOSKG_OK;
+    // the sub-graphs every query's seeds live in, ascending and distinct
+    std::vector<std::vector<int32_t>> need((size_t)num_queries);
+    for (int64_t q = 0; q < num_queries; ++q) {
+        std::vector<int32_t> &v = need[(size_t)q];
+        for (int64_t i = seed_off[q]; i < seed_off[q + 1]; ++i) {
+            const int32_t sh = g->shard_of[(size_t)seeds[i]];
+            if (sh >= 0) v.push_back(sh);
+        }
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());
+    }
+    std::stable_sort(order, order + num_queries,
+                     [&](int32_t a, int32_t b) { return need[(size_t)a] < need[(size_t)b]; });
+    return LOGOSKG_OK;
+}
+

@@ -87,3 +87,44 @@ def test_byte_budget_and_errors():
     assert np.array_equal(pred.cpu().numpy(), want[3][a:b]) and np.array_equal(ent.cpu().numpy(), want[1][a:b])
     res.close()
     g.close()
+
+
+def test_scheduled_batches_restore_results_and_cut_first_hop_loads():
+    # Sec. 3.4 batch processing: queries grouped by the sub-graphs of their seeds, run in batches of
+    # 128 in that order and put back; the cache counters follow the oracle's LRU model for the batch
+    # sequence actually run, and at k = 1 (where a batch touches only its seeds' sub-graphs) the
+    # grouped order loads fewer sub-graphs than the input order
+    m = lkg()
+    w = kggen.config5(0.0005, num_queries=1024)
+    B, shards, cap = 128, 8, 2
+    P_o, _ = part.degree_aware_partition(w.num_entities, w.subj, shards)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, 1, w.rel_mask)
+    loads = {}
+    for name in ("input", "grouped"):
+        g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=shards,
+                    max_resident_shards=cap)
+        order = g.schedule_queries(w.seed_off, w.seeds)
+        assert np.array_equal(order, part.schedule_queries(P_o, w.seed_off, w.seeds))
+        if name == "input":
+            order = np.arange(w.num_queries, dtype=np.int32)
+        seq = []
+        for b0 in range(0, w.num_queries, B):
+            qs = order[b0:b0 + B]
+            so = np.concatenate([[0], np.cumsum(w.seed_off[qs + 1] - w.seed_off[qs])]).astype(np.int64)
+            sd = np.concatenate([w.seeds[w.seed_off[q]:w.seed_off[q + 1]] for q in qs]).astype(np.int32)
+            res = g.khop(so, sd, 1)
+            off = res.offsets()
+            ent, hop, pred = (x.cpu().numpy() for x in res.fetch())
+            res.close()
+            for i, q in enumerate(qs):       # restore: batch position i is input query q
+                a, b = want[0][q], want[0][q + 1]
+                assert np.array_equal(ent[off[i]:off[i + 1]], want[1][a:b])
+                assert np.array_equal(hop[off[i]:off[i + 1]], want[2][a:b])
+                assert np.array_equal(pred[off[i]:off[i + 1]], want[3][a:b])
+            seq += part.shard_accesses(P_o, w.subj, w.num_entities, 1, ent, hop)
+        info = g.info()
+        g.close()
+        assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == part.lru_counts(seq, cap)
+        loads[name] = info["shard_loads"]
+    print("sub-graph loads, 8 batches of 128 queries, 2 cache slots:", loads, flush=True)
+    assert loads["grouped"] < loads["input"]

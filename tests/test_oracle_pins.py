@@ -368,3 +368,41 @@ def test_partition_properties_and_lru_accounting():
     for cap in (1, 2, 4):
         l2, e2, h2 = part.lru_counts(seq, cap)
         assert l2 - e2 <= cap and l2 >= loads and l2 + h2 == len(seq)
+
+
+def test_query_schedule_groups_queries_by_the_subgraphs_of_their_seeds():
+    from oracle import partition as part
+    # hand example: P maps entities 0..7 to shards; entity 6 is no subject
+    P = np.array([2, 0, 1, 0, 2, 1, -1, 0], dtype=np.int32)
+    seed_off = np.array([0, 1, 3, 4, 4, 6, 7, 9, 10], dtype=np.int64)
+    seeds = np.array([0,  1, 2,  3,  4, 0,  6,  5, 1,  7], dtype=np.int32)
+    # needs: q0 (2) q1 (0,1) q2 (0) q3 () q4 (2) q5 () q6 (0,1) q7 (0)
+    assert part.query_needs(P, seed_off, seeds) == [(2,), (0, 1), (0,), (), (2,), (), (0, 1), (0,)]
+    # () first, then (0), (0,1), (2); equal needs keep their input order
+    assert part.schedule_queries(P, seed_off, seeds).tolist() == [3, 5, 2, 7, 1, 6, 0, 4]
+    # properties on a generated workload: a permutation; equal needs contiguous and in input order;
+    # with one sub-graph per query and one cache slot, the first hop loads each needed sub-graph once
+    w = kggen.config5(0.0005, num_queries=512)
+    P, _ = part.degree_aware_partition(w.num_entities, w.subj, 8)
+    order = part.schedule_queries(P, w.seed_off, w.seeds)
+    assert sorted(order.tolist()) == list(range(w.num_queries))
+    needs = part.query_needs(P, w.seed_off, w.seeds)
+    seen, last = {}, None
+    for q in order:
+        nd = needs[q]
+        if nd != last:
+            assert nd not in seen, "a need appears in two separate runs"
+            seen[nd] = True
+            last = nd
+    for nd in seen:
+        run = [int(q) for q in order if needs[q] == nd]
+        assert run == sorted(run)
+    single = [q for q in range(w.num_queries) if len(needs[q]) == 1]
+    so = np.concatenate([[0], np.cumsum([w.seed_off[q + 1] - w.seed_off[q] for q in single])])
+    sd = np.concatenate([w.seeds[w.seed_off[q]:w.seed_off[q + 1]] for q in single])
+    o1 = part.schedule_queries(P, so, sd)
+    first_hop = [needs[single[i]][0] for i in o1]
+    loads, _, _ = part.lru_counts(first_hop, 1)
+    assert loads == len(set(first_hop))
+    unsorted_loads, _, _ = part.lru_counts([needs[q][0] for q in single], 1)
+    assert unsorted_loads > loads
