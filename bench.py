@@ -5,10 +5,13 @@ One step = one pass of logoskg_khop (seed scatter, 3 hops of push/pull
 expansion with the visited/level update, per-query counts) followed by
 logoskg_result_fetch of every query (query-major entity / hop / predecessor
 lists) on the 3,000,000-entity / 30,000,000-triple synthetic KG with 1,024
-queries (benchmark configs[1]).  Seeds and the graph are resident in HBM
-before the timed region; outputs stay in HBM.
+queries (the second of the five benchmark configurations).  Seeds and the graph
+are resident in HBM before the timed region; outputs stay in HBM.
 
-Prints one JSON line.
+Prints one JSON line: throughput of the whole step, per-kernel times from HIP
+events around every launch, the roofline figure of the kernel with the largest
+time per step, the expansion kernels taken alone, and the CPU oracle timed on a
+sample of the same queries.
 """
 from __future__ import annotations
 
@@ -27,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_bytes: float,
                       lists_fused: bool = False, level_lists: bool = False) -> float:
     """Bytes the named kernel has to move per step for the work units it reported
-    (rows / edges / lines / items), per the per-unit figures of the design doc."""
+    (rows / edges / lines / items); the per-unit figures are stated case by case below."""
     line = 8 * W
     e_bytes = 4 + (2 if masked else 0)
     rows, edges, lines, items = p["rows"], p["edges"], p["lines"], p["items"]
@@ -83,7 +86,7 @@ def main():
                     help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
     ap.add_argument("--config", type=int, choices=[1, 2, 3, 4, 5], default=2,
                     help="workload: 2 (default) is the one the metric is quoted on; the others are the "
-                         "parity-test shapes, timed the same way for the table in DESIGN.md "
+                         "parity-test shapes, timed the same way "
                          "(4: the first of its four 1,024-query batches; 5: 8 shards, 64 GB shard budget)")
     ap.add_argument("--k", type=int, default=0, help="hops (config 3 sweeps 1..4; 0 = the workload's own)")
     ap.add_argument("--fetch-queries", type=int, default=0,
