@@ -124,7 +124,7 @@ static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
 // Object rows with >= 1 entry: short rows, segments of the longer ones (longest
 // rows first), rows with several segments, and the hub rows.
 static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_min,
-                          std::vector<int32_t> &tail, std::vector<RowSegment> &seg,
+                          std::vector<ShortRow> &tail, std::vector<RowSegment> &seg,
                           std::vector<int32_t> &multi, std::vector<int32_t> &longer, int64_t *n_hub) {
     std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
     *n_hub = 0;
@@ -135,7 +135,8 @@ static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_m
         if (d > (uint32_t)kTailMaxDegree) longer.push_back(v);
         else bucket[d].push_back(v);
     }
-    for (int d = kTailMaxDegree; d >= 1; --d) tail.insert(tail.end(), bucket[d].begin(), bucket[d].end());
+    for (int d = kTailMaxDegree; d >= 1; --d)
+        for (int32_t v : bucket[d]) tail.push_back({v, off[v], off[v + 1]});
     std::stable_sort(longer.begin(), longer.end(), [&](int32_t a, int32_t b) {
         return off[a + 1] - off[a] > off[b + 1] - off[b];
     });
@@ -200,7 +201,8 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     try {
         // row classes of the object-sorted CSR (pull and predecessor work lists)
         auto object_row_classes = [&](const std::vector<uint32_t> &ioff) -> logoskg_status {
-            std::vector<int32_t> tail, multi, longer;
+            std::vector<int32_t> multi, longer;
+            std::vector<ShortRow> tail;
             std::vector<RowSegment> seg;
             classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
             g->in_rows.n_tail = (int64_t)tail.size();

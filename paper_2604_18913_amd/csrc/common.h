@@ -73,8 +73,13 @@ struct RowSegment {  // part [begin, min(begin + segment, row end)) of one CSR r
     uint32_t begin;
 };
 
+struct ShortRow {  // a CSR row with its bounds, so that a kernel needs no look-up in the offsets
+    int32_t row;
+    uint32_t begin, end;
+};
+
 struct RowClasses {             // device work lists over the object rows, split by degree
-    int32_t *tail = nullptr;    // rows with 1 .. kTailMaxDegree entries, descending degree
+    ShortRow *tail = nullptr;   // rows with 1 .. kTailMaxDegree entries, descending degree
     RowSegment *seg = nullptr;  // segments of the longer rows, longest rows first
     int32_t *multi = nullptr;   // rows cut into more than one segment
     int32_t *longrows = nullptr;  // rows with more than kTailMaxDegree entries, descending degree

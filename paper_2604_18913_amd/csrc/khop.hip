@@ -457,76 +457,162 @@ __device__ __forceinline__ unsigned group_ballot(bool p) {
     }
 }
 
-// One W-lane group per short object row (<= 32 entries): the group's lanes load
-// W entries at once, then gather the frontier lines of the candidates.
+// Short object rows (<= 32 entries): a W-lane group works on kTailRows rows at
+// once.  A row is a chain of dependent loads (row record -> visited line and
+// subject ids -> frontier bits -> frontier lines), and with all wavefront
+// slots of a CU taken the kernel is bound by that latency, so the work list carries
+// the row bounds (no look-up in the offsets) and every group keeps
+// the chains of two rows in flight: each stage is issued for both rows before
+// either result is used.  Per stage the group's lanes load W entries of a row,
+// then gather the frontier lines of its candidates, two per row at a time.
+// (three or four rows per group measured the same: the kernel then runs at the
+// rate at which the memory system serves its scattered lines.)
+constexpr int kTailRows = 2;
+constexpr int kTailLines = 2;  // candidate lines of each row requested together
+
 template <int W, bool MASK, bool STATS>
 __global__ void __launch_bounds__(256)
-k_pull_tail(const int32_t *__restrict__ rows, long long n, const uint32_t *__restrict__ off,
-            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
+k_pull_tail(const ShortRow *__restrict__ rows, long long n, const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
             const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
             const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
             unsigned long long *visited, unsigned long long *cur, uint32_t *act_cur,
             unsigned long long *stats, int walk_exact) {
-    long long gidx = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
+    constexpr int NR = kTailRows;
+    const long long group = ((long long)blockIdx.x * blockDim.x + threadIdx.x) / W;
     const int lw = threadIdx.x & (W - 1), g0 = lane() & ~(W - 1);
-    uint32_t lo = 0, hi = 0;
-    int v = 0;
-    unsigned long long vis = 0, need = 0, acc = 0;
-    if (gidx < n) {  // offsets and the visited line are requested together
-        v = rows[gidx];
-        vis = visited[(size_t)v * W + lw];
-        lo = off[v];
-        hi = off[v + 1];
-        need = (walk_exact ? ~0ull : ~vis) & live[lw];
+    uint32_t lo[NR], hi[NR], j0[NR];
+    int v[NR];
+    bool have[NR];
+    unsigned long long vis[NR], need[NR], acc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {  // the row's id and bounds come in one record
+        have[r] = group * NR + r < n;
+        v[r] = 0;
+        lo[r] = hi[r] = 0;
+        if (have[r]) {
+            const ShortRow row = rows[group * NR + r];
+            v[r] = row.row;
+            lo[r] = row.begin;
+            hi[r] = row.end;
+        }
     }
-    if (!group_any<W>(need != 0)) hi = lo;
+    int s_next[NR], rel_next[NR];  // subject (and relation) ids of the next W entries, loaded one stage ahead
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {  // the visited line and the first entries are requested together
+        vis[r] = need[r] = acc[r] = 0;
+        s_next[r] = -1;
+        rel_next[r] = 0;
+        if (have[r]) {
+            vis[r] = visited[(size_t)v[r] * W + lw];
+            if (lo[r] + lw < hi[r]) {
+                s_next[r] = in_sub[lo[r] + lw];
+                if (MASK) rel_next[r] = in_rel[lo[r] + lw];
+            }
+        }
+    }
+    const unsigned long long live_w = live[lw];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        need[r] = (walk_exact ? ~0ull : ~vis[r]) & live_w;
+        if (!have[r]) need[r] = 0;
+        if (!group_any<W>(need[r] != 0)) hi[r] = lo[r];
+        j0[r] = lo[r];
+    }
+    uint32_t row_end[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) row_end[r] = hi[r];
     long long n_edges = 0, n_lines = 0;
-    for (uint32_t j0 = lo; j0 < hi; j0 += W) {
-        uint32_t j = j0 + lw;
-        int s = 0, r = 0;
-        bool cand = false;
-        if (j < hi) {
-            s = in_sub[j];
-            cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
-            if (MASK && cand) r = in_rel[j];
-        }
-        unsigned gm = group_ballot<W>(cand);
-        n_edges += min((uint32_t)W, hi - j0);
-        n_lines += __popc(gm);
-        while (gm) {  // up to four candidate lines in flight
-            int c[4];
-            unsigned long long l[4];
+    auto any_open = [&]() {
+        bool o = false;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                c[x] = -1;
-                if (gm) {
-                    c[x] = __ffs((int)gm) - 1;
-                    gm &= gm - 1;
-                }
-            }
+        for (int r = 0; r < NR; ++r) o |= j0[r] < hi[r];
+        return o;
+    };
+    while (any_open()) {
+        int s[NR], rl[NR];
+        bool cand[NR];
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int sx = __shfl(s, g0 + (c[x] < 0 ? 0 : c[x]));
-                l[x] = 0;
-                if (c[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
-                if (MASK) {
-                    const int rx = __shfl(r, g0 + (c[x] < 0 ? 0 : c[x]));
-                    if (c[x] >= 0) l[x] &= allow[(size_t)rx * W + lw];
-                }
+        for (int r = 0; r < NR; ++r) {
+            const bool open = j0[r] < hi[r];
+            s[r] = open ? s_next[r] : -1;
+            rl[r] = rel_next[r];
+            s_next[r] = -1;
+            const uint32_t j = j0[r] + W + lw;
+            if (open && j < hi[r]) {
+                s_next[r] = in_sub[j];
+                if (MASK) rel_next[r] = in_rel[j];
             }
-            acc |= (l[0] | l[1]) | (l[2] | l[3]);
         }
-        if (!group_any<W>((need & ~acc) != 0)) break;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) cand[r] = s[r] >= 0 && ((act_prev[s[r] >> 5] >> (s[r] & 31)) & 1u);
+        unsigned gm[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            gm[r] = group_ballot<W>(cand[r]);
+            if (j0[r] < hi[r]) n_edges += min((uint32_t)W, hi[r] - j0[r]);
+            n_lines += __popc(gm[r]);
+        }
+        auto any_candidate = [&]() {
+            unsigned o = 0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) o |= gm[r];
+            return o != 0;
+        };
+        constexpr int NL = kTailLines;
+        while (any_candidate()) {  // two candidate lines of each row in flight
+            int c[NR][NL];
+            unsigned long long l[NR][NL];
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int x = 0; x < NL; ++x) {
+                    c[r][x] = -1;
+                    if (gm[r]) {
+                        c[r][x] = __ffs((int)gm[r]) - 1;
+                        gm[r] &= gm[r] - 1;
+                    }
+                }
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int x = 0; x < NL; ++x) {
+                    const int src = g0 + (c[r][x] < 0 ? 0 : c[r][x]);
+                    const int sx = __shfl(s[r], src);
+                    l[r][x] = 0;
+                    if (c[r][x] >= 0) l[r][x] = prev[(size_t)sx * W + lw];
+                    if (MASK) {
+                        const int rx = __shfl(rl[r], src);
+                        if (c[r][x] >= 0) l[r][x] &= allow[(size_t)rx * W + lw];
+                    }
+                }
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int x = 0; x < NL; ++x) acc[r] |= l[r][x];
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            if (j0[r] < hi[r]) {
+                j0[r] += W;
+                if (!group_any<W>((need[r] & ~acc[r]) != 0)) hi[r] = j0[r];  // nothing left to find in this row
+            }
+        }
     }
-    unsigned long long nw = acc & need;
-    if (hi > lo && group_any<W>(nw != 0)) {
-        cur[(size_t)v * W + lw] = nw;
-        visited[(size_t)v * W + lw] = vis | nw;
-        if (lw == 0) atomicOr(&act_cur[v >> 5], 1u << (v & 31));
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const unsigned long long nw = acc[r] & need[r];
+        if (row_end[r] > lo[r] && group_any<W>(nw != 0)) {
+            cur[(size_t)v[r] * W + lw] = nw;
+            visited[(size_t)v[r] * W + lw] = vis[r] | nw;
+            if (lw == 0) atomicOr(&act_cur[v[r] >> 5], 1u << (v[r] & 31));
+        }
     }
     if (STATS) {
-        bool lead = (lw == 0);
-        add_stats(stats, (lead && hi > lo) ? 1 : 0, lead ? n_edges : 0, lead ? n_lines : 0);
+        const bool lead = (lw == 0);
+        long long n_rows = 0;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) n_rows += (row_end[r] > lo[r]) ? 1 : 0;
+        add_stats(stats, lead ? n_rows : 0, lead ? n_edges : 0, lead ? n_lines : 0);
     }
 }
 
@@ -684,9 +770,10 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
     }
     if (rc.n_tail > 0) {
         ProfScope ps(g->prof, KK_PULL_TAIL, st);
-        k_pull_tail<W, MASK, STATS><<<dim3(blocks_for(rc.n_tail * W, 256)), dim3(256), 0, st>>>(
-            rc.tail, rc.n_tail, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
-            act_cur, stats(KK_PULL_TAIL), r->walk_exact ? 1 : 0);
+        const long long groups = (rc.n_tail + kTailRows - 1) / kTailRows;
+        k_pull_tail<W, MASK, STATS><<<dim3(blocks_for(groups * W, 256)), dim3(256), 0, st>>>(
+            rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur, act_cur,
+            stats(KK_PULL_TAIL), r->walk_exact ? 1 : 0);
     }
     if (rc.n_multi > 0) {
         ProfScope ps(g->prof, KK_PULL_FINISH, st);
