@@ -205,6 +205,10 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
             std::vector<ShortRow> tail;
             std::vector<RowSegment> seg;
             classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
+            g->in_rows.n_giant = 0;
+            for (int32_t v : longer)  // longest first
+                if (ioff[(size_t)v + 1] - ioff[v] >= (uint32_t)std::max(kGiantRowMin, g->hub_min)) g->in_rows.n_giant++;
+                else break;
             g->in_rows.n_tail = (int64_t)tail.size();
             g->in_rows.n_seg = (int64_t)seg.size();
             g->in_rows.n_multi = (int64_t)multi.size();

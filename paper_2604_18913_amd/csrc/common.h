@@ -62,6 +62,7 @@ constexpr int kPullSegment = 1024;      // longer object rows are cut into segme
 constexpr int kPushSegment = 256;       // same for the subject rows of a push frontier
 constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
                                         // (shorter long rows: one wavefront per row)
+constexpr int kGiantRowMin = 8192;      // hub rows from this size get a 16-wave block in the predecessor pass, smaller ones 4 waves
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
 constexpr int kSuperTiles = 16;         // tiles per super tile (1024 entities)
 constexpr int kPredTiles = 4;           // tiles per block of the 16-word predecessor kernel
@@ -86,6 +87,7 @@ struct RowClasses {             // device work lists over the object rows, split
                                   // (per streamed chunk when sharded); the first n_hub of them
                                   // have >= hub_min entries
     int64_t n_tail = 0, n_seg = 0, n_multi = 0, n_hub = 0, n_long = 0;
+    int64_t n_giant = 0;  // the first n_giant long rows have >= kGiantRowMin entries
 };
 
 // ---------------------------------------------------------------- profiling
@@ -327,6 +329,7 @@ struct FillArgs {
     int32_t *pred;
     unsigned long long *stats_pred, *stats_hub, *stats_mid;  // rows / edges / lines counters or NULL
     int fuse_lists;  // the 16-word tile kernel also writes the entity and hop lists
+    long long n_giant_rows;  // hub rows of the launch that get a 16-wave block (the first ones); -1 = all
 };
 
 logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,

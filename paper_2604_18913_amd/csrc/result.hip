@@ -260,24 +260,31 @@ __device__ __forceinline__ int pred_resolve(uint32_t j0, int s, bool cand, const
     const int lw = lane() & (W - 1);
     unsigned long long cm = __ballot(cand);
     int gathered = 0;
-    while (cm) {  // two rounds of 64/W candidates each, both loads in flight before either is resolved
-        gathered += min(__popcll(cm), 2 * (64 / W));
-        int p0 = next_candidates<W>(cm);
-        int p1 = next_candidates<W>(cm);
-        int s0 = __shfl(s, p0 < 0 ? 0 : p0), s1 = __shfl(s, p1 < 0 ? 0 : p1);
-        unsigned long long l0 = 0, l1 = 0;
-        if (p0 >= 0) l0 = prev[(size_t)s0 * W + lw];
-        if (p1 >= 0) l1 = prev[(size_t)s1 * W + lw];
-        if (MASK) {
-            if (p0 >= 0) l0 &= a.allow[(size_t)a.in_rel[j0 + p0] * W + lw];
-            if (p1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + p1] * W + lw];
+    constexpr int NR = 2;  // rounds of 64/W candidates whose loads are in flight before any is resolved
+                           // (three or four measured the same)
+    while (cm) {
+        gathered += min(__popcll(cm), NR * (64 / W));
+        int p[NR];
+        unsigned long long l[NR];
+#pragma unroll
+        for (int x = 0; x < NR; ++x) p[x] = next_candidates<W>(cm);
+#pragma unroll
+        for (int x = 0; x < NR; ++x) {
+            const int sx = __shfl(s, p[x] < 0 ? 0 : p[x]);
+            l[x] = 0;
+            if (p[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
         }
-        unsigned long long hit0 = l0 & rem & ~groups_before<W>(l0);
-        rem &= ~or_groups<W>(l0);
-        unsigned long long hit1 = l1 & rem & ~groups_before<W>(l1);
-        rem &= ~or_groups<W>(l1);
-        if (hit0) emit(hit0, a.in_eid[j0 + p0]);
-        if (hit1) emit(hit1, a.in_eid[j0 + p1]);
+        if (MASK) {
+#pragma unroll
+            for (int x = 0; x < NR; ++x)
+                if (p[x] >= 0) l[x] &= a.allow[(size_t)a.in_rel[j0 + p[x]] * W + lw];
+        }
+#pragma unroll
+        for (int x = 0; x < NR; ++x) {  // resolved in candidate order
+            const unsigned long long hit = l[x] & rem & ~groups_before<W>(l[x]);
+            rem &= ~or_groups<W>(l[x]);
+            if (hit) emit(hit, a.in_eid[j0 + p[x]]);
+        }
         if (!wave_any(rem != 0)) break;
     }
     return gathered;
@@ -712,8 +719,9 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, in
 
 // Object rows of more than 32 entries: one block per row (4 waves; 16 for hub
 // rows).  Phase 1 rebuilds the list positions of the row's entity (ranks inside
-// its tile).  Phase 2 walks the row in steps of (waves x 64) entries: inside a
-// step the waves take disjoint 64-entry chunks and keep, per query, the smallest
+// its tile).  Phase 2 walks the row in steps of (waves x 4 x 64) entries: inside a
+// step the waves take disjoint 64-entry chunks (interleaved, so that a row
+// shorter than a step still occupies every wave) and keep, per query, the smallest
 // edge id any of them found (LDS atomicMin); after the step the resolved queries
 // are removed from the shared mask, so a later step (larger edge ids) never
 // touches them.  Each predecessor is then written once.
@@ -744,32 +752,39 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
         const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
         if (wave == 0) ++n_rows;
-        for (uint32_t s0 = lo; s0 < hi; s0 += 64u * C * nw) {
+        // The first step is short (one chunk per wavefront): on a dense frontier the first
+        // candidates of a row resolve most queries, and what is resolved after that step is not
+        // claimed again by sixteen wavefronts in parallel.
+        uint32_t span = 64u * nw;
+        for (uint32_t s0 = lo; s0 < hi; s0 += span, span = 64u * C * nw) {
+            const uint32_t step_hi = min(hi, s0 + span);
             unsigned long long rem = srem[lw];
             if (!wave_any(rem != 0)) break;  // same decision in every wave
             const unsigned long long before = rem;
-            const uint32_t w0 = s0 + 64u * C * wave;
+            // chunk c of this wavefront is chunk c * nw + wave of the step: a row shorter than a
+            // step still spreads over all wavefronts
+            const uint32_t w0 = s0 + 64u * wave;
             int sj[C];
             bool cj[C];
 #pragma unroll
             for (int c = 0; c < C; ++c) {  // all loads of the step first
-                uint32_t j = w0 + 64u * c + v;
+                uint32_t j = w0 + 64u * nw * c + v;
                 sj[c] = 0;
                 cj[c] = false;
-                if (j < hi) {
+                if (j < step_hi) {
                     sj[c] = a.in_sub[j];
                     cj[c] = (act_prev[sj[c] >> 5] >> (sj[c] & 31)) & 1u;
                 }
             }
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                uint32_t j0 = w0 + 64u * c;
-                if (j0 < hi && wave_any(rem != 0)) {
+                uint32_t j0 = w0 + 64u * nw * c;
+                if (j0 < step_hi && wave_any(rem != 0)) {
                     n_lines += pred_resolve<W, MASK>(j0, sj[c], cj[c], a, prev, rem, [&](unsigned long long hit, int eid) {
                         for (unsigned long long m = hit; m; m &= m - 1)
                             atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
                     });
-                    n_edges += min((uint32_t)64, hi - j0);
+                    n_edges += min((uint32_t)64, step_hi - j0);
                 }
             }
             unsigned long long resolved = before & ~rem;
@@ -918,7 +933,13 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
     }
     if (n_hub_rows > 0) {  // writes the lists itself: independent of the other two kernels
         ProfScope ps(prof, KK_PRED_HUB, st_hub);
-        k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)n_hub_rows), dim3(1024), 0, st_hub>>>(a, 0);
+        // 16 wavefronts per row for the longest rows, 4 for the others: a row of a thousand entries
+        // leaves most of a large block waiting at its barriers, and the smaller blocks disturb the
+        // tile kernel less while both run
+        const long long giants = a.n_giant_rows < 0 ? n_hub_rows : std::min(a.n_giant_rows, n_hub_rows);
+        if (giants > 0) k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants), dim3(1024), 0, st_hub>>>(a, 0);
+        if (n_hub_rows > giants)
+            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants)), dim3(256), 0, st_hub>>>(a, giants);
     }
     if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
         hipStream_t st = a.row_pred ? st_tiles : st_hub;
@@ -1021,6 +1042,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.rows = g->in_rows.longrows;
     a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
+    a.n_giant_rows = g->num_shards > 1 ? -1 : g->in_rows.n_giant;
     if (pred && W == 16) {
         LKG_TRY(prepare_row_pred(g, st));
         a.long_index = g->long_index;
