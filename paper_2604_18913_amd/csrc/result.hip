@@ -290,6 +290,47 @@ __device__ __forceinline__ int pred_resolve(uint32_t j0, int s, bool cand, const
     return gathered;
 }
 
+// The same 64 in-edges for a caller that merges claims with a minimum over edge ids (the
+// block-per-row kernel): every W-lane group keeps a mask of its own, takes every (64/W)-th
+// candidate and claims whatever its own mask still holds, with no exchange between the groups -
+// the cross-lane prefix-OR of the ordered walk is a chain of dependent LDS permutes, which is what
+// that kernel waited on.  A query may be claimed by several groups; the smallest edge id wins.
+template <int W, bool MASK, typename Emit>
+__device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool cand, const FillArgs &a,
+                                                      const unsigned long long *__restrict__ prev,
+                                                      unsigned long long &rem, Emit emit) {
+    const int lw = lane() & (W - 1);
+    unsigned long long cm = __ballot(cand);
+    int gathered = 0;
+    constexpr int NR = 2;
+    while (cm) {
+        gathered += min(__popcll(cm), NR * (64 / W));
+        int p[NR];
+        unsigned long long l[NR];
+#pragma unroll
+        for (int x = 0; x < NR; ++x) p[x] = next_candidates<W>(cm);
+#pragma unroll
+        for (int x = 0; x < NR; ++x) {
+            const int sx = __shfl(s, p[x] < 0 ? 0 : p[x]);
+            l[x] = 0;
+            if (p[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
+        }
+        if (MASK) {
+#pragma unroll
+            for (int x = 0; x < NR; ++x)
+                if (p[x] >= 0) l[x] &= a.allow[(size_t)a.in_rel[j0 + p[x]] * W + lw];
+        }
+#pragma unroll
+        for (int x = 0; x < NR; ++x) {
+            const unsigned long long hit = l[x] & rem;
+            rem &= ~l[x];
+            if (hit) emit(hit, a.in_eid[j0 + p[x]]);
+        }
+        if (!wave_any(rem != 0)) break;
+    }
+    return gathered;
+}
+
 template <int W, bool MASK, typename Emit>
 __device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
                                           const uint32_t *__restrict__ act_prev,
@@ -780,16 +821,17 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
             for (int c = 0; c < C; ++c) {
                 uint32_t j0 = w0 + 64u * nw * c;
                 if (j0 < step_hi && wave_any(rem != 0)) {
-                    n_lines += pred_resolve<W, MASK>(j0, sj[c], cj[c], a, prev, rem, [&](unsigned long long hit, int eid) {
+                    n_lines += pred_resolve_unordered<W, MASK>(j0, sj[c], cj[c], a, prev, rem,
+                                                               [&](unsigned long long hit, int eid) {
                         for (unsigned long long m = hit; m; m &= m - 1)
                             atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
                     });
                     n_edges += min((uint32_t)64, step_hi - j0);
                 }
             }
-            unsigned long long resolved = before & ~rem;
+            unsigned long long resolved = before & ~rem;  // by this group of lanes
             __syncthreads();
-            if (v < W && resolved) atomicAnd(&srem[v], ~resolved);
+            if (resolved) atomicAnd(&srem[lw], ~resolved);
             __syncthreads();
         }
         __syncthreads();
