@@ -59,7 +59,7 @@ private:
 constexpr int kTailMaxDegree = 32;      // rows up to this degree: one W-lane group per row
 constexpr int kPullSegment = 1024;      // longer object rows are cut into segments of this many
                                         // entries, one wavefront each
-constexpr int kPushSegment = 256;       // same for the subject rows of a push frontier
+constexpr int kPushSegment = 64;        // same for the subject rows of a push frontier
 constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
                                         // (shorter long rows: one wavefront per row)
 constexpr int kGiantRowMin = 8192;      // hub rows from this size get a 16-wave block in the predecessor pass, smaller ones 4 waves

@@ -291,12 +291,28 @@ k_push_seg(const RowSegment *__restrict__ segs, const unsigned long long *__rest
 }
 
 // visited |= level[h] on the lines the push kernels touched.
-__global__ void k_update_visited(long long nwords64, int W, const uint32_t *__restrict__ act_cur,
-                                 const unsigned long long *__restrict__ cur, unsigned long long *visited) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nwords64) return;
-    long long e = i / W;
-    if ((act_cur[e >> 5] >> (e & 31)) & 1u) visited[i] |= cur[i];
+// One wavefront per 64 entities: it reads their two words of the active bitmap once and touches
+// only the lines of the active ones (after a push from a small frontier almost none), W lanes per
+// line, so a dense level is still updated with contiguous accesses.
+template <int W>
+__global__ void __launch_bounds__(256)
+k_update_visited(long long Epad, const uint32_t *__restrict__ act_cur, const unsigned long long *__restrict__ cur,
+                 unsigned long long *visited) {
+    const long long base = ((long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+    if (base >= Epad) return;  // Epad is a multiple of 64
+    const unsigned long long m =
+        ((unsigned long long)act_cur[base / 32 + 1] << 32) | (unsigned long long)act_cur[base / 32];
+    if (m == 0) return;
+    constexpr int GPW = 64 / W;
+    const int g = lane() / W, lw = lane() & (W - 1);
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        const int e = i * GPW + g;
+        if ((m >> e) & 1ull) {
+            const size_t x = ((size_t)base + e) * W + lw;
+            visited[x] |= cur[x];
+        }
+    }
 }
 
 // ---------------------------------------------------------------- pull
@@ -740,8 +756,7 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
     }
     if (!update) return;
     ProfScope ps(g->prof, KK_UPDATE, st);
-    k_update_visited<<<dim3(blocks_for((long long)plane, 256)), dim3(256), 0, st>>>((long long)plane, W, act_cur,
-                                                                                    cur, r->visited);
+    k_update_visited<W><<<dim3(blocks_for(r->Epad / 64, 4)), dim3(256), 0, st>>>(r->Epad, act_cur, cur, r->visited);
 }
 
 // STATS: the counting mode runs instantiations of its own, so that kernel statistics of the

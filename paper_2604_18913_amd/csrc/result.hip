@@ -75,43 +75,55 @@ __global__ void k_count(const unsigned long long *__restrict__ visited, long lon
     super_sum[(size_t)st * Qp + threadIdx.x] = (uint32_t)run;
 }
 
-// exclusive prefix of `sum` over groups of `group` consecutive rows; total per group to `up`
+// exclusive prefix of `sum` over groups of `group` consecutive rows; total per group to `up`.
+// One thread per (group, query); the rows are read sixteen at a time before any is rewritten,
+// so the loads of a batch are in flight together.
 __global__ void k_scan_level(long long nrows, int group, int Qp, uint32_t *sum_to_base, uint32_t *up) {
-    long long g = blockIdx.x;
-    for (int q = threadIdx.x; q < Qp; q += blockDim.x) {
-        uint32_t run = 0;
-        for (int t = 0; t < group; ++t) {
-            long long row = g * group + t;
-            if (row >= nrows) break;
-            uint32_t x = sum_to_base[(size_t)row * Qp + q];
-            sum_to_base[(size_t)row * Qp + q] = run;
-            run += x;
+    const long long g = blockIdx.x;
+    const int q = blockIdx.y * blockDim.x + threadIdx.x;
+    if (q >= Qp) return;
+    uint32_t run = 0;
+    for (int t0 = 0; t0 < group; t0 += 16) {
+        uint32_t x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const long long row = g * group + t0 + i;
+            x[i] = (t0 + i < group && row < nrows) ? sum_to_base[(size_t)row * Qp + q] : 0u;
         }
-        up[(size_t)g * Qp + q] = run;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const long long row = g * group + t0 + i;
+            if (t0 + i < group && row < nrows) sum_to_base[(size_t)row * Qp + q] = run;
+            run += x[i];
+        }
     }
+    up[(size_t)g * Qp + q] = run;
 }
 
-// one block: prefix over mega tiles for every query, then the prefix over queries
+// one block of Qp threads: prefix over mega tiles for every query, then the prefix over queries
+// (Hillis-Steele steps in LDS)
 __global__ void k_scan_top(long long nmega, int Q, int Qp, uint32_t *mega_base, long long *reached_off) {
-    __shared__ long long total[1024];
-    for (int q = threadIdx.x; q < Qp; q += blockDim.x) {
-        long long run = 0;
-        for (long long m = 0; m < nmega; ++m) {
-            uint32_t x = mega_base[(size_t)m * Qp + q];
-            mega_base[(size_t)m * Qp + q] = (uint32_t)run;
-            run += x;
-        }
-        total[q] = q < Q ? run : 0;
+    __shared__ long long total[2][1024];
+    const int q = threadIdx.x;
+    long long run = 0;
+    for (long long m = 0; m < nmega; ++m) {
+        uint32_t x = mega_base[(size_t)m * Qp + q];
+        mega_base[(size_t)m * Qp + q] = (uint32_t)run;
+        run += x;
     }
+    const long long mine = q < Q ? run : 0;
+    int cur = 0;
+    total[0][q] = mine;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        long long run = 0;
-        for (int q = 0; q < Q; ++q) {
-            reached_off[q] = run;
-            run += total[q];
-        }
-        for (int q = Q; q <= Qp; ++q) reached_off[q] = run;
+    for (int d = 1; d < Qp; d <<= 1) {  // inclusive prefix
+        long long v = total[cur][q];
+        if (q >= d) v += total[cur][q - d];
+        total[cur ^ 1][q] = v;
+        cur ^= 1;
+        __syncthreads();
     }
+    reached_off[q] = total[cur][q] - mine;  // exclusive
+    if (q == Qp - 1) reached_off[Qp] = total[cur][q];
 }
 
 __device__ __forceinline__ unsigned long long range_bits(int q0, int q1, int w) {
@@ -900,8 +912,9 @@ static logoskg_status count_plane(logoskg_result *r, const unsigned long long *p
     }
     {
         ProfScope ps(g->prof, KK_SCAN, st);
-        k_scan_level<<<dim3((unsigned)nmega), dim3(std::min(Qp, 256)), 0, st>>>(nsuper, kMegaSupers, Qp, *super_base,
-                                                                              *mega_base);
+        const int threads = std::min(Qp, 256);
+        k_scan_level<<<dim3((unsigned)nmega, (unsigned)(Qp / threads)), dim3(threads), 0, st>>>(
+            nsuper, kMegaSupers, Qp, *super_base, *mega_base);
         k_scan_top<<<dim3(1), dim3(Qp), 0, st>>>(nmega, r->Q, Qp, *mega_base, *d_off);
     }
     LKG_HIP(hipGetLastError());
