@@ -787,11 +787,18 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
     __shared__ unsigned long long srem[16], slevel[16];
     const int ev = a.rows[first_row + blockIdx.x];
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, v = lane(), lw = v & (W - 1);
+    // gridDim.y > 1: one block per (row, hop level), so the levels of a long row run side by side
+    const int h_first = gridDim.y > 1 ? (int)blockIdx.y + 1 : 1, h_last = gridDim.y > 1 ? h_first : a.k;
+    if (gridDim.y > 1) {  // nothing of this level in the row's entity: leave before the list positions
+        const unsigned long long x =
+            lw < W ? a.levels[(size_t)h_first * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw) : 0ull;
+        if (!wave_any(x != 0)) return;  // the same words in every wavefront
+    }
     if (!BUF) row_slots<W>(a, ev, wave, nw, slot);
     int32_t *out = BUF ? a.row_pred + (size_t)(first_row + blockIdx.x) * Qp : a.pred;
     const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
     long long n_rows = 0, n_edges = 0, n_lines = 0;
-    for (int h = 1; h <= a.k; ++h) {
+    for (int h = h_first; h <= h_last; ++h) {
         __syncthreads();
         if (t < 16) {
             unsigned long long x =
@@ -992,9 +999,14 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         // leaves most of a large block waiting at its barriers, and the smaller blocks disturb the
         // tile kernel less while both run
         const long long giants = a.n_giant_rows < 0 ? n_hub_rows : std::min(a.n_giant_rows, n_hub_rows);
-        if (giants > 0) k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants), dim3(1024), 0, st_hub>>>(a, 0);
+        // and one block per hop level of a row: the levels are independent, and the longest row
+        // sets the duration of the launch
+        const unsigned levels = (unsigned)std::max(a.k, 1);
+        if (giants > 0)
+            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
         if (n_hub_rows > giants)
-            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants)), dim3(256), 0, st_hub>>>(a, giants);
+            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
+                a, giants);
     }
     if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
         hipStream_t st = a.row_pred ? st_tiles : st_hub;
