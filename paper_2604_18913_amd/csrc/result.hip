@@ -17,12 +17,13 @@
 //   pred  : the predecessor edge (smallest edge id whose subject sits one hop
 //           closer and whose relation the query allows - the first active
 //           triple of Eq. 5-7 in edge-id order) is found by walking the object
-//           row of the entity in ascending edge id with a mask of still
-//           unresolved queries, so every (query, entity) pair is written once.
-//           Object rows of up to 32 entries belong to a tile kernel (k_pred_mt
-//           for 16-word planes and k <= 6, which writes the entity and hop
-//           lists as well; k_pred otherwise), rows of 33 .. hub_min-1 entries to
-//           k_pred_wave, longer ones to k_pred_row.
+//           row of the entity with a mask of still unresolved queries, so every
+//           (query, entity) pair is written once.  Object rows of up to 32
+//           entries belong to a tile kernel (k_pred_mt for 16-word planes and
+//           k <= 6, which writes the entity and hop lists as well; k_pred
+//           otherwise) that walks them in ascending edge id; rows of 33 ..
+//           hub_min-1 entries belong to k_pred_wave and longer ones to
+//           k_pred_row, whose lanes claim in parallel and keep the minimum.
 #include <algorithm>
 #include <climits>
 #include <cstdlib>
@@ -219,29 +220,6 @@ __global__ void __launch_bounds__(64 * W) k_lists(FillArgs a) {
 }
 
 // ---------------------------------------------------------------- predecessor edges
-// Exclusive prefix-OR over the 64/W groups of a wavefront (word lw of each group).
-template <int W>
-__device__ __forceinline__ unsigned long long groups_before(unsigned long long x) {
-    if constexpr (W >= 64) return 0ull;
-    else {
-        unsigned long long inc = x;
-#pragma unroll
-        for (int d = W; d < 64; d <<= 1) {
-            unsigned long long y = shfl_up64(inc, d);
-            if (lane() >= d) inc |= y;
-        }
-        unsigned long long ex = shfl_up64(inc, W);
-        return lane() >= W ? ex : 0ull;
-    }
-}
-
-template <int W>
-__device__ __forceinline__ unsigned long long or_groups(unsigned long long acc) {
-#pragma unroll
-    for (int m = W; m < 64; m <<= 1) acc |= shfl_xor64(acc, m);
-    return acc;
-}
-
 // Removes up to 64/W candidates from the wave-uniform mask; group g gets the
 // g-th of them (lane position) or -1.
 template <int W>
@@ -259,54 +237,14 @@ __device__ __forceinline__ int next_candidates(unsigned long long &rest) {
     return mine;
 }
 
-// Ordered walk over the 64 in-edges [j0, j0+64) of an object row.  Every group
-// holds the same `rem` (word lw of the still unresolved queries).  64/W
-// candidate subjects are gathered at once; a group's line resolves the bits
-// that no earlier candidate of the round has, so the result equals a strictly
-// sequential walk in ascending edge id.  emit(hit, eid) runs on lanes whose word
-// has newly resolved bits; returns the number of lines gathered.
-template <int W, bool MASK, typename Emit>
-__device__ __forceinline__ int pred_resolve(uint32_t j0, int s, bool cand, const FillArgs &a,
-                                            const unsigned long long *__restrict__ prev,
-                                            unsigned long long &rem, Emit emit) {
-    const int lw = lane() & (W - 1);
-    unsigned long long cm = __ballot(cand);
-    int gathered = 0;
-    constexpr int NR = 2;  // rounds of 64/W candidates whose loads are in flight before any is resolved
-                           // (three or four measured the same)
-    while (cm) {
-        gathered += min(__popcll(cm), NR * (64 / W));
-        int p[NR];
-        unsigned long long l[NR];
-#pragma unroll
-        for (int x = 0; x < NR; ++x) p[x] = next_candidates<W>(cm);
-#pragma unroll
-        for (int x = 0; x < NR; ++x) {
-            const int sx = __shfl(s, p[x] < 0 ? 0 : p[x]);
-            l[x] = 0;
-            if (p[x] >= 0) l[x] = prev[(size_t)sx * W + lw];
-        }
-        if (MASK) {
-#pragma unroll
-            for (int x = 0; x < NR; ++x)
-                if (p[x] >= 0) l[x] &= a.allow[(size_t)a.in_rel[j0 + p[x]] * W + lw];
-        }
-#pragma unroll
-        for (int x = 0; x < NR; ++x) {  // resolved in candidate order
-            const unsigned long long hit = l[x] & rem & ~groups_before<W>(l[x]);
-            rem &= ~or_groups<W>(l[x]);
-            if (hit) emit(hit, a.in_eid[j0 + p[x]]);
-        }
-        if (!wave_any(rem != 0)) break;
-    }
-    return gathered;
-}
-
-// The same 64 in-edges for a caller that merges claims with a minimum over edge ids (the
-// block-per-row kernel): every W-lane group keeps a mask of its own, takes every (64/W)-th
-// candidate and claims whatever its own mask still holds, with no exchange between the groups -
-// the cross-lane prefix-OR of the ordered walk is a chain of dependent LDS permutes, which is what
-// that kernel waited on.  A query may be claimed by several groups; the smallest edge id wins.
+// The 64 in-edges [j0, j0+64) of an object row for a caller that merges claims with a minimum over
+// edge ids (the row kernels): every W-lane group keeps a mask `rem` of its own (word lw of the
+// queries it has not resolved), takes every (64/W)-th candidate subject, gathers its line and
+// claims whatever its mask still holds, with no exchange between the groups.  (An ordered walk -
+// a candidate claims only what no earlier candidate of the round has, found with an exclusive
+// prefix-OR across the groups - costs ten dependent LDS permutes per round, which is what these
+// kernels then wait on.)  A query may be claimed by several groups; the smallest edge id wins.
+// emit(hit, eid) runs on lanes whose word has newly claimed bits; returns the lines gathered.
 template <int W, bool MASK, typename Emit>
 __device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool cand, const FillArgs &a,
                                                       const unsigned long long *__restrict__ prev,
@@ -343,21 +281,6 @@ __device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool c
     return gathered;
 }
 
-template <int W, bool MASK, typename Emit>
-__device__ __forceinline__ int pred_chunk(uint32_t j0, uint32_t hi, const FillArgs &a,
-                                          const uint32_t *__restrict__ act_prev,
-                                          const unsigned long long *__restrict__ prev,
-                                          unsigned long long &rem, Emit emit) {
-    uint32_t j = j0 + lane();
-    int s = 0;
-    bool cand = false;
-    if (j < hi) {
-        s = a.in_sub[j];
-        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
-    }
-    return pred_resolve<W, MASK>(j0, s, cand, a, prev, rem, emit);
-}
-
 // List positions of entity `ev` for every query: slot[q] = start of the tile's run in query q's
 // list + rank of the entity inside the tile.  Called by a whole wavefront for the words
 // w = w_first, w_first + w_step, ..
@@ -380,40 +303,69 @@ __device__ __forceinline__ void row_slots(const FillArgs &a, int ev, int w_first
     }
 }
 
-// Object rows of 33 .. hub_min-1 entries: one wavefront per row, four rows per block.  A single
-// wavefront walks the row in order, so every predecessor is final when it is found.
+// AND over the 64/W groups of a wavefront (word lw of each group).
+template <int W>
+__device__ __forceinline__ unsigned long long and_groups(unsigned long long x) {
+#pragma unroll
+    for (int m = W; m < 64; m <<= 1) x &= shfl_xor64(x, m);
+    return x;
+}
+
+// Object rows of 33 .. hub_min-1 entries: one wavefront per row, four rows per block.  The W-lane
+// groups of the wavefront claim independently (pred_resolve_unordered) and the smallest edge id per
+// query is kept in a table of the wavefront in LDS; the groups' masks are merged once per 64
+// entries, and after a level the table is written out (one contiguous store per 64 queries in the
+// row-buffer mode) and reset.
 template <int W, bool MASK, bool STATS, bool BUF>
 __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_row, long long n_rows_total) {
     constexpr int Qp = 64 * W;
     __shared__ long long slots[BUF ? 1 : 4][BUF ? 1 : Qp];
+    __shared__ int smin_all[4][Qp];
     const int wave = threadIdx.x >> 6, v = lane(), lw = v & (W - 1);
     const long long idx = (long long)blockIdx.x * 4 + wave;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     if (idx < n_rows_total) {  // wave-uniform
         const int ev = a.rows[first_row + idx];
         long long *slot = slots[BUF ? 0 : wave];
+        int *smin = smin_all[wave];
         int32_t *out = BUF ? a.row_pred + (size_t)(first_row + idx) * Qp : a.pred;
-        if (!BUF) {
-            row_slots<W>(a, ev, 0, 1, slot);
-            __builtin_amdgcn_wave_barrier();
-        }
+        if (!BUF) row_slots<W>(a, ev, 0, 1, slot);
+        for (int q = v; q < Qp; q += 64) smin[q] = INT_MAX;
+        __builtin_amdgcn_wave_barrier();
         const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
         for (int h = 1; h <= a.k; ++h) {
-            unsigned long long rem = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
+            const unsigned long long level = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
+            unsigned long long rem = level;
             if (!wave_any(rem != 0)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
             ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
-                n_lines += pred_chunk<W, MASK>(j0, hi, a, act_prev, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1) {
-                        const int q = lw * 64 + (__ffsll((long long)m) - 1);
-                        out[BUF ? (long long)q : slot[q]] = eid;
-                    }
+                const uint32_t j = j0 + v;
+                int s = 0;
+                bool cand = false;
+                if (j < hi) {
+                    s = a.in_sub[j];
+                    cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+                }
+                n_lines += pred_resolve_unordered<W, MASK>(j0, s, cand, a, prev, rem, [&](unsigned long long hit, int eid) {
+                    for (unsigned long long m = hit; m; m &= m - 1)
+                        atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
                 });
                 n_edges += min((uint32_t)64, hi - j0);
+                rem = and_groups<W>(rem);  // what any group has resolved is resolved
                 if (!wave_any(rem != 0)) break;
             }
+            __builtin_amdgcn_wave_barrier();
+            for (int i = 0; i < W; ++i) {  // queries 64 i .. 64 i + 63: word i of the level, held by lane i
+                const unsigned long long word = shfl64(level, i);
+                const int q = 64 * i + v;
+                if ((word >> v) & 1ull) {
+                    out[BUF ? (long long)q : slot[q]] = smin[q];
+                    smin[q] = INT_MAX;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
     if (STATS && v == 0) {
