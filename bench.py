@@ -244,6 +244,30 @@ def main():
     if not args.serial_fetch:
         os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
 
+    # where a step's time goes: a few more steps with an event after the khop call and after the
+    # list call (not part of the timed region)
+    phase_ms = [0.0, 0.0]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(5):
+        ev[0].record()
+        if walk:
+            r = g.khop(seed_off, seeds, k, rel_mask, walk_exact=True)
+            ev[1].record()
+            r.level(k, 0, nf)
+        elif triples:
+            r = g.khop(seed_off, seeds, k, rel_mask)
+            ev[1].record()
+            r.active_triples(k, 0, nf, out=cols)
+        else:
+            r = g.khop(seed_off, seeds, k, rel_mask)
+            ev[1].record()
+            r.fetch(0, nf, out=(ent, hop, pred))
+        ev[2].record()
+        torch.cuda.synchronize()
+        r.close()
+        phase_ms[0] += ev[0].elapsed_time(ev[1]) / 5
+        phase_ms[1] += ev[1].elapsed_time(ev[2]) / 5
+
     ab = functools.partial(algorithmic_bytes, level_lists=walk or triples)
     masked_arg = masked
     ms_per_step = dt / args.steps * 1e3
@@ -337,6 +361,8 @@ def main():
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
         "logical_edges_per_step": logical_edges, "physical_edges_per_step": physical_edges,
         "ms_per_step_serialized": round(dt_serial / args.steps * 1e3, 4),
+        "phase_ms": {"khop": round(phase_ms[0], 4), "lists": round(phase_ms[1], 4),
+                     "measured": "events after each of the two calls, 5 extra steps"},
         "expansion": {"ms_per_step": round(expansion_ms, 4),
                       "queries_per_s": round(Q / (expansion_ms * 1e-3), 1) if expansion_ms > 0 else None,
                       "algorithmic_GBps": round(expansion_bytes / (expansion_ms * 1e-3) / 1e9, 1) if expansion_ms else None,
