@@ -945,6 +945,14 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         a.row_pred = nullptr;
         a.fuse_lists = 0;
     }
+    // issued first: the tile kernel waits for it, and launched after the hub kernel it ran half as fast
+    if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
+        hipStream_t st = a.row_pred ? st_tiles : st_hub;
+        ProfScope ps(prof, KK_PRED_MID, st);
+        const dim3 gw((unsigned)((n_other_rows + 3) / 4));
+        if (a.row_pred) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+        else k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+    }
     if (n_hub_rows > 0) {  // writes the lists itself: independent of the other two kernels
         ProfScope ps(prof, KK_PRED_HUB, st_hub);
         // 16 wavefronts per row for the longest rows, 4 for the others: a row of a thousand entries
@@ -959,13 +967,6 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         if (n_hub_rows > giants)
             k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
                 a, giants);
-    }
-    if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
-        hipStream_t st = a.row_pred ? st_tiles : st_hub;
-        ProfScope ps(prof, KK_PRED_MID, st);
-        const dim3 gw((unsigned)((n_other_rows + 3) / 4));
-        if (a.row_pred) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
-        else k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
     }
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st_tiles);
