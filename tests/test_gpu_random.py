@@ -28,6 +28,10 @@ def one_case(seed):
     direction = ["auto", "push", "pull"][rng.integers(0, 3)]
     hub_min = int([0, 40, 200][rng.integers(0, 3)])
     walk = bool(rng.integers(0, 3) == 0)
+    shards = int([0, 0, 0, 2, 5][rng.integers(0, 5)])     # Alg. 1: subject-partitioned graph behind a shard cache
+    resident = int(rng.integers(1, shards + 1)) if shards else 0
+    if shards and direction == "pull":
+        direction = "push"
     if seed % 3 == 0:   # power-law degrees: long and hub object rows, dense frontiers
         scale = float(rng.uniform(0.0005, 0.004))
         k = min(k, 4)
@@ -36,11 +40,11 @@ def one_case(seed):
     else:
         w = kggen.random_tiny(5000 + seed, E=E, T=T, R=R, Q=Q, k=k, masked=masked, max_seeds=4)
     what = dict(seed=seed, E=E, T=w.num_triples, R=R, Q=Q, k=k, masked=masked, direction=direction,
-                hub_min=hub_min, walk=walk)
+                hub_min=hub_min, walk=walk, shards=shards, resident=resident)
     print(what, flush=True)
     m = lkg()
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=hub_min,
-                host_build=bool(seed % 5 == 0))
+                host_build=bool(seed % 5 == 0), num_shards=shards, max_resident_shards=resident)
     res = g.khop(w.seed_off, w.seeds, k, w.rel_mask, direction=direction, walk_exact=walk)
     want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, w.rel_mask)
     assert np.array_equal(res.offsets(), want[0]), what          # the reached set is the same in both modes
@@ -54,7 +58,7 @@ def one_case(seed):
             a = loff[h * Q:(h + 1) * Q + 1]
             assert np.array_equal(off, a - a[0]), (what, h)
             assert np.array_equal(ent.cpu().numpy(), lent[a[q0]:a[q1]]), (what, h)
-        if k > 0:   # walks to sampled members of the last non-empty level
+        if k > 0 and not shards:   # walks to sampled members of the last non-empty level
             h = max(hh for hh in range(k + 1) if any(len(x) for x in levels[hh]))
             qs = [q for q in range(Q) if len(levels[h][q])][:40]
             pt = [int(levels[h][q][rng.integers(0, len(levels[h][q]))]) for q in qs]
@@ -74,12 +78,12 @@ def one_case(seed):
         assert np.array_equal(ent.cpu().numpy(), want[1][a:b]) and np.array_equal(pred.cpu().numpy(), want[3][a:b]), what
         levels = [[want[1][want[0][q]:want[0][q + 1]][want[2][want[0][q]:want[0][q + 1]] == h] for q in range(Q)]
                   for h in range(k + 1)]
-        if want[0][-1] > 0:
+        if want[0][-1] > 0 and not shards:
             pq, pt = kggen.sample_reached_pairs(seed, want[0], want[1], 60)
             cnt, edges = g.paths(res, pq, pt, 8)
             c_o, e_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, pq, pt, 8, w.rel_mask)
             assert np.array_equal(cnt.cpu().numpy(), c_o) and np.array_equal(edges.cpu().numpy(), e_o), what
-    if k > 0:
+    if k > 0 and not shards:
         h = int(rng.integers(1, k + 1))
         off, t, s_, r_, o_ = res.active_triples(h, q0, q1)
         want_t = [oracle.active_triples(w.num_entities, w.subj, w.rel, levels[h - 1][q],
