@@ -41,7 +41,8 @@ typedef enum {
     LOGOSKG_ENOMEM = 2,    /* host or device allocation failed, or budget below one shard  */
     LOGOSKG_EDEVICE = 3,   /* a HIP call failed (text in logoskg_last_error)               */
     LOGOSKG_ERANGE = 4,    /* a caller-provided capacity is too small                      */
-    LOGOSKG_EINTERNAL = 5
+    LOGOSKG_EINTERNAL = 5,
+    LOGOSKG_EIO = 6        /* a shard file could not be written or read                    */
 } logoskg_status;
 
 #define LOGOSKG_MAX_QUERIES 1024 /* queries per logoskg_khop call: 16 uint64 words per entity */
@@ -65,6 +66,13 @@ typedef struct {
                                         are copied to HBM first).  1: counting sorts on the host.
                                         Both give the same arrays.  Sharded graphs are always
                                         sorted on the host.                                      */
+    const char *shard_dir;           /* NULL: the shards stay in pinned host memory.  Else a
+                                        directory (it must exist): every shard is written to
+                                        <shard_dir>/shard_<i>.lkg at build and read from there
+                                        when the cache misses (Sec. 3.4: sub-graphs on disk, the
+                                        tau_io of a miss), through one pinned staging buffer per
+                                        cache slot.  The files are left in place at
+                                        logoskg_graph_free.  Only with num_shards > 1.           */
 } logoskg_build_opts;
 
 /*
@@ -98,6 +106,7 @@ typedef struct {
     int64_t pinned_host_bytes;          /* pinned host memory held by the shards            */
     int64_t shard_loads, shard_evictions, shard_hits; /* cache counters since build (Sec. 3.4) */
     int64_t shard_bytes_h2d;
+    int64_t shard_bytes_disk;           /* bytes read from the shard files (0 without shard_dir) */
 } logoskg_graph_info;
 
 logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg_graph_info *out);

@@ -19,7 +19,7 @@ _lib = None
 DIRECTIONS = {"auto": 0, "push": 1, "pull": 2}
 NO_COUNTS = 4
 WALK_EXACT = 8
-STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EDEVICE", 4: "ERANGE", 5: "EINTERNAL"}
+STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EDEVICE", 4: "ERANGE", 5: "EINTERNAL", 6: "EIO"}
 
 
 class LogosKGError(RuntimeError):
@@ -32,7 +32,7 @@ class _BuildOpts(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("device", ctypes.c_int32),
                 ("num_shards", ctypes.c_int32), ("max_resident_shards", ctypes.c_int32),
                 ("hbm_shard_budget_bytes", ctypes.c_uint64), ("hub_min_degree", ctypes.c_int32),
-                ("host_build", ctypes.c_int32)]
+                ("host_build", ctypes.c_int32), ("shard_dir", ctypes.c_char_p)]
 
 
 class _QueryBatch(ctypes.Structure):
@@ -50,7 +50,7 @@ class _GraphInfo(ctypes.Structure):
                 ("num_in_hubs", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
                 ("pinned_host_bytes", ctypes.c_int64), ("shard_loads", ctypes.c_int64),
                 ("shard_evictions", ctypes.c_int64), ("shard_hits", ctypes.c_int64),
-                ("shard_bytes_h2d", ctypes.c_int64)]
+                ("shard_bytes_h2d", ctypes.c_int64), ("shard_bytes_disk", ctypes.c_int64)]
 
 
 class _ResultInfo(ctypes.Structure):
@@ -279,7 +279,7 @@ class Graph:
 
     def __init__(self, subj, rel, obj, num_entities: int, num_relations: int, device: int = 0,
                  num_shards: int = 0, max_resident_shards: int = 0, hbm_shard_budget_bytes: int = 0,
-                 hub_min_degree: int = 0, host_build: bool = False):
+                 hub_min_degree: int = 0, host_build: bool = False, shard_dir: Optional[str] = None):
         lib = _load()
         torch = _torch()
         if not _NP:
@@ -292,7 +292,8 @@ class Graph:
         if not (subj.shape == rel.shape == obj.shape and subj.ndim == 1):
             raise ValueError("subj, rel, obj must be 1-D arrays of equal length")
         opts = _BuildOpts(ctypes.sizeof(_BuildOpts), device, num_shards, max_resident_shards,
-                          hbm_shard_budget_bytes, hub_min_degree, 1 if host_build else 0)
+                          hbm_shard_budget_bytes, hub_min_degree, 1 if host_build else 0,
+                          None if shard_dir is None else os.fsencode(shard_dir))
         h = ctypes.c_void_p()
         _check(lib.logoskg_build(subj.ctypes.data_as(ctypes.c_void_p), rel.ctypes.data_as(ctypes.c_void_p),
                                  obj.ctypes.data_as(ctypes.c_void_p), subj.shape[0], num_entities,

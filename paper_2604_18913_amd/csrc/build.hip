@@ -173,6 +173,10 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         set_error("bad build options");
         return LOGOSKG_EINVAL;
     }
+    if (o.shard_dir && o.shard_dir[0] && o.num_shards <= 1) {
+        set_error("shard_dir needs num_shards > 1");
+        return LOGOSKG_EINVAL;
+    }
     const bool device_build = o.num_shards <= 1 && !o.host_build;  // else ids are checked here
     for (int64_t t = 0; !device_build && t < T; ++t) {
         if ((uint32_t)subj[t] >= (uint32_t)E || (uint32_t)obj[t] >= (uint32_t)E ||

@@ -15,6 +15,9 @@
 
 #include "logoskg.h"
 
+static_assert(sizeof(logoskg_build_opts) == 40 && sizeof(logoskg_graph_info) == 112,
+              "the ctypes binding mirrors these layouts");
+
 namespace lkg {
 
 // ---------------------------------------------------------------- errors

@@ -11,8 +11,14 @@
 // evict), restrict the frontier to its subjects, push, OR into the global next
 // level (object ids are global, so "map back" is free).  The next shard's load
 // is issued on a copy stream while the current one computes.
+#include <fcntl.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
 #include <algorithm>
+#include <cerrno>
 #include <queue>
+#include <string>
 
 #include "common.h"
 
@@ -34,6 +40,12 @@ struct ShardSet {
     uint64_t tick = 0;
     hipStream_t copy_stream = nullptr;
     int64_t loads = 0, evictions = 0, hits = 0, bytes_h2d = 0;
+    // sub-graphs on disk (build option shard_dir): one file per shard instead of h_obj / h_rel,
+    // read on a miss into the slot's pinned staging buffer and copied from there
+    std::vector<int> fd;
+    std::vector<int32_t *> host_obj;   // [n_slots] pinned, slot_edges entries
+    std::vector<uint16_t *> host_rel;
+    int64_t bytes_disk = 0;
     unsigned long long *d_route = nullptr, *h_route = nullptr;  // [kRouteWords], see k_route_count
     // object-sorted triples (for predecessor edges): pinned host arrays, streamed through two
     // staging buffers in chunks of whole 64-entity tiles
@@ -199,6 +211,9 @@ void free_shards(logoskg_graph *g) {
     if (ss->h_in_rel) (void)hipHostFree(ss->h_in_rel);
     if (ss->h_obj) (void)hipHostFree(ss->h_obj);
     if (ss->h_rel) (void)hipHostFree(ss->h_rel);
+    for (auto p : ss->host_obj) if (p) (void)hipHostFree(p);
+    for (auto p : ss->host_rel) if (p) (void)hipHostFree(p);
+    for (int f : ss->fd) if (f >= 0) (void)close(f);
     if (ss->d_route) (void)hipFree(ss->d_route);
     if (ss->h_route) (void)hipHostFree(ss->h_route);
     if (g->row_begin && g->row_begin != g->out_off) (void)hipFree(g->row_begin);
@@ -343,6 +358,82 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
     return LOGOSKG_OK;
 }
 
+// Shard file: 32-byte header (magic, shard index, number of triples, 0), then the objects
+// (int32) and the relation ids (uint16) of the shard's triples in the shard-grouped order.
+struct ShardFileHeader {
+    char magic[8];
+    int64_t shard, count, reserved;
+};
+static const char kShardMagic[8] = {'L', 'K', 'G', 'S', 'H', 'R', 'D', '1'};
+
+static bool write_all(int fd, const void *buf, size_t bytes) {
+    const char *p = (const char *)buf;
+    while (bytes > 0) {
+        ssize_t w = write(fd, p, std::min<size_t>(bytes, (size_t)1 << 30));
+        if (w < 0) {
+            if (errno == EINTR) continue;
+            return false;
+        }
+        p += w;
+        bytes -= (size_t)w;
+    }
+    return true;
+}
+
+static bool read_all_at(int fd, void *buf, size_t bytes, off_t at) {
+    char *p = (char *)buf;
+    while (bytes > 0) {
+        ssize_t r = pread(fd, p, std::min<size_t>(bytes, (size_t)1 << 30), at);
+        if (r < 0 && errno == EINTR) continue;
+        if (r <= 0) return false;
+        p += r;
+        at += r;
+        bytes -= (size_t)r;
+    }
+    return true;
+}
+
+// Sec. 3.4, sub-graphs on disk: writes every shard to <dir>/shard_<i>.lkg, releases the pinned
+// copy of all shards and keeps one pinned staging buffer per cache slot instead.
+static logoskg_status shards_to_disk(logoskg_graph *g, ShardSet *ss, const char *dir) {
+    ss->fd.assign((size_t)ss->n, -1);
+    for (int s = 0; s < ss->n; ++s) {
+        const std::string path = std::string(dir) + "/shard_" + std::to_string(s) + ".lkg";
+        const int64_t b = ss->edge_begin[s], cnt = ss->edge_begin[(size_t)s + 1] - b;
+        int fd = open(path.c_str(), O_CREAT | O_TRUNC | O_WRONLY, 0644);
+        ShardFileHeader h;
+        memcpy(h.magic, kShardMagic, 8);
+        h.shard = s;
+        h.count = cnt;
+        h.reserved = 0;
+        const bool ok = fd >= 0 && write_all(fd, &h, sizeof(h)) &&
+                        write_all(fd, ss->h_obj + b, (size_t)cnt * sizeof(int32_t)) &&
+                        write_all(fd, ss->h_rel + b, (size_t)cnt * sizeof(uint16_t));
+        if (fd >= 0 && close(fd) != 0 && ok) { set_error("closing %s failed: %s", path.c_str(), strerror(errno)); return LOGOSKG_EIO; }
+        if (!ok) { set_error("writing %s failed: %s", path.c_str(), strerror(errno)); return LOGOSKG_EIO; }
+        ss->fd[s] = open(path.c_str(), O_RDONLY);
+        if (ss->fd[s] < 0) { set_error("opening %s failed: %s", path.c_str(), strerror(errno)); return LOGOSKG_EIO; }
+    }
+    const size_t all = std::max<int64_t>(g->T, 1) * (sizeof(int32_t) + sizeof(uint16_t));
+    (void)hipHostFree(ss->h_obj);
+    (void)hipHostFree(ss->h_rel);
+    ss->h_obj = nullptr;
+    ss->h_rel = nullptr;
+    g->pinned_bytes -= all;
+    ss->host_obj.assign((size_t)ss->n_slots, nullptr);
+    ss->host_rel.assign((size_t)ss->n_slots, nullptr);
+    for (int i = 0; i < ss->n_slots; ++i) {
+        if (hipHostMalloc((void **)&ss->host_obj[i], ss->slot_edges * sizeof(int32_t), hipHostMallocDefault) != hipSuccess ||
+            hipHostMalloc((void **)&ss->host_rel[i], ss->slot_edges * sizeof(uint16_t), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            set_error("pinned staging buffer of %zu bytes failed", ss->slot_edges * 6);
+            return LOGOSKG_ENOMEM;
+        }
+        g->pinned_bytes += ss->slot_edges * (sizeof(int32_t) + sizeof(uint16_t));
+    }
+    return LOGOSKG_OK;
+}
+
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
                             const logoskg_build_opts *opts) {
     const int n = g->num_shards;
@@ -453,6 +544,7 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         LKG_HIP(hipEventCreateWithFlags(&ss->slot_idle[i], hipEventDisableTiming));
     }
     LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
+    if (opts->shard_dir && opts->shard_dir[0]) LKG_TRY(shards_to_disk(g, ss, opts->shard_dir));
     LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
     LKG_HIP(hipMalloc((void **)&ss->d_route, 1024 * sizeof(unsigned long long)));
     if (hipHostMalloc((void **)&ss->h_route, 1024 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
@@ -481,12 +573,31 @@ static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStre
             ss->evictions++;
         }
         int64_t b = ss->edge_begin[shard], cnt = ss->edge_begin[(size_t)shard + 1] - b;
+        const int32_t *src_obj = ss->h_obj ? ss->h_obj + b : nullptr;
+        const uint16_t *src_rel = ss->h_rel ? ss->h_rel + b : nullptr;
+        if (!ss->fd.empty()) {  // the shard comes from its file, through the slot's staging buffer
+            LKG_HIP(hipEventSynchronize(ss->slot_ready[slot]));  // the buffer's last copy has left it
+            ShardFileHeader h;
+            const bool ok = read_all_at(ss->fd[shard], &h, sizeof(h), 0) && memcmp(h.magic, kShardMagic, 8) == 0 &&
+                            h.shard == shard && h.count == cnt &&
+                            (cnt == 0 ||
+                             (read_all_at(ss->fd[shard], ss->host_obj[slot], (size_t)cnt * sizeof(int32_t), sizeof(h)) &&
+                              read_all_at(ss->fd[shard], ss->host_rel[slot], (size_t)cnt * sizeof(uint16_t),
+                                          (off_t)(sizeof(h) + (size_t)cnt * sizeof(int32_t)))));
+            if (!ok) {
+                set_error("reading the file of shard %d failed (missing, truncated or not written by this build)", shard);
+                return LOGOSKG_EIO;
+            }
+            src_obj = ss->host_obj[slot];
+            src_rel = ss->host_rel[slot];
+            ss->bytes_disk += (int64_t)sizeof(h) + cnt * (int64_t)(sizeof(int32_t) + sizeof(uint16_t));
+        }
         LKG_HIP(hipStreamWaitEvent(ss->copy_stream, ss->slot_idle[slot], 0));
         if (cnt > 0) {
             g->prof.begin(KK_SHARD_COPY, ss->copy_stream);
-            LKG_HIP(hipMemcpyAsync(ss->slot_obj[slot], ss->h_obj + b, (size_t)cnt * sizeof(int32_t),
+            LKG_HIP(hipMemcpyAsync(ss->slot_obj[slot], src_obj, (size_t)cnt * sizeof(int32_t),
                                    hipMemcpyHostToDevice, ss->copy_stream));
-            LKG_HIP(hipMemcpyAsync(ss->slot_rel[slot], ss->h_rel + b, (size_t)cnt * sizeof(uint16_t),
+            LKG_HIP(hipMemcpyAsync(ss->slot_rel[slot], src_rel, (size_t)cnt * sizeof(uint16_t),
                                    hipMemcpyHostToDevice, ss->copy_stream));
             g->prof.end(ss->copy_stream);
         }
@@ -546,10 +657,6 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
     for (size_t i = 0; i < active.size(); ++i) {
         const int shard = active[i];
         if (slot_of[i] < 0) LKG_TRY(acquire(g, ss, shard, st, &slot_of[i]));
-        // with at least two slots the next shard's access can be issued now: it never
-        // evicts the shard in use (that one is the most recently used)
-        if (i + 1 < active.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
-            LKG_TRY(acquire(g, ss, active[i + 1], st, &slot_of[i + 1]));
         const int slot = slot_of[i];
         unsigned long long hc[C_TOTAL] = {};
         hc[C_NTAIL] = ss->h_route[256 + shard];
@@ -561,6 +668,11 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
                           ss->d_route + kRouteCursor + 2 * shard, st);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->slot_idle[slot], st));
+        // with at least two slots the next shard's access is issued now, while this one is being
+        // expanded (a shard file is read by the calling thread): it never evicts the shard in use,
+        // which is the most recently used
+        if (i + 1 < active.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
+            LKG_TRY(acquire(g, ss, active[i + 1], st, &slot_of[i + 1]));
     }
     return LOGOSKG_OK;
 }
@@ -572,6 +684,7 @@ void shard_info(const logoskg_graph *g, logoskg_graph_info *o) {
     o->shard_evictions = ss->evictions;
     o->shard_hits = ss->hits;
     o->shard_bytes_h2d = ss->bytes_h2d + ss->in_bytes_h2d;
+    o->shard_bytes_disk = ss->bytes_disk;
 }
 
 }  // namespace lkg

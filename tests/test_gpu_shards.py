@@ -2,6 +2,8 @@
 (paper Sec. 3.4, Algorithm 1): results must not depend on the number of shards
 or on the cache capacity, the partition must equal the oracle's, and loads /
 evictions / hits must equal an LRU simulation of the shard access sequence."""
+import os
+
 import numpy as np
 import pytest
 
@@ -128,3 +130,49 @@ def test_scheduled_batches_restore_results_and_cut_first_hop_loads():
         loads[name] = info["shard_loads"]
     print("sub-graph loads, 8 batches of 128 queries, 2 cache slots:", loads, flush=True)
     assert loads["grouped"] < loads["input"]
+
+
+def test_shards_on_disk_give_the_same_results_and_counters(tmp_path):
+    # Sec. 3.4: sub-graphs kept on disk and loaded on a cache miss.  Same results, same LRU counters
+    # as with the shards in pinned host memory; every load reads its shard's file
+    m = lkg()
+    w = kggen.config5(0.0005)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
+    infos = {}
+    for name, kw in (("memory", {}), ("disk", {"shard_dir": str(tmp_path)})):
+        g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8, max_resident_shards=2, **kw)
+        for _ in range(2):
+            res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+            assert np.array_equal(res.offsets(), want[0])
+            ent, hop, pred = res.fetch()
+            assert np.array_equal(ent.cpu().numpy(), want[1]) and np.array_equal(hop.cpu().numpy(), want[2])
+            assert np.array_equal(pred.cpu().numpy(), want[3])
+            res.close()
+        infos[name] = g.info()
+        P, per = g.partition()
+        g.close()
+    a, b = infos["memory"], infos["disk"]
+    for key in ("shard_loads", "shard_evictions", "shard_hits", "shard_bytes_h2d"):
+        assert a[key] == b[key], key
+    assert a["shard_bytes_disk"] == 0
+    files = sorted(os.listdir(tmp_path))
+    assert files == [f"shard_{i}.lkg" for i in range(8)]
+    sizes = [os.path.getsize(tmp_path / f) for f in files]
+    assert sizes == [32 + 6 * int(n) for n in per]                        # header + objects + relation ids
+    assert b["shard_bytes_disk"] > 0 and b["shard_loads"] > 8             # two slots: shards are read again
+    # pinned memory: two slot-sized staging buffers instead of all subject-sorted triples
+    assert b["pinned_host_bytes"] == a["pinned_host_bytes"] - 6 * w.num_triples + 2 * 6 * int(per.max())
+    # a damaged file is reported, not used
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8, max_resident_shards=2,
+                shard_dir=str(tmp_path))
+    with open(tmp_path / "shard_3.lkg", "r+b") as f:
+        f.truncate(40)
+    with pytest.raises(m.LogosKGError):
+        for _ in range(2):
+            g.khop(w.seed_off, w.seeds, w.k, w.rel_mask).close()
+    g.close()
+    with pytest.raises(m.LogosKGError):
+        m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, shard_dir=str(tmp_path))   # not sharded
+    with pytest.raises(m.LogosKGError):
+        m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=4,
+                shard_dir=str(tmp_path / "missing"))
