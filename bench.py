@@ -93,6 +93,9 @@ def main():
                     help="fetch the lists of the first N queries only (0 = all; configs 4 and 5 default to 64)")
     ap.add_argument("--resident-shards", type=int, default=0,
                     help="config 5: capacity of the shard cache in shards (the paper's n); 0 = the byte budget only")
+    ap.add_argument("--shard-dir", default="",
+                    help="config 5: keep the shards in files under this directory (created if missing) "
+                         "instead of pinned host memory")
     ap.add_argument("--mode", choices=["minhop", "walk", "triples"], default="minhop",
                     help="minhop (default): the headline path; walk: Eq. 4 iterated without the visited set "
                          "(LOGOSKG_WALK_EXACT), one step = khop + the list of level k of every query; "
@@ -130,6 +133,9 @@ def main():
     else:
         w = kggen.config5(args.scale)
         graph_opts = dict(num_shards=8, hbm_shard_budget_bytes=64 << 30, max_resident_shards=args.resident_shards)
+        if args.shard_dir:
+            os.makedirs(args.shard_dir, exist_ok=True)
+            graph_opts["shard_dir"] = args.shard_dir
     if args.k:
         w.k = args.k
     t_gen = time.time() - t0
@@ -345,7 +351,8 @@ def main():
         workload += " (first of four 1,024-query batches)"
     if cfg == 5:
         workload += " (8 shards, 64 GB shard budget, shards cached from pinned host memory" + \
-                    (f", at most {args.resident_shards} resident" if args.resident_shards else "") + ")"
+                    (f", at most {args.resident_shards} resident" if args.resident_shards else "") + \
+                    (", shards read from files on a cache miss" if args.shard_dir else "") + ")"
     out = {
         "metric": metric,
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

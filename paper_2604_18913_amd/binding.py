@@ -275,7 +275,11 @@ class Result:
 
 
 class Graph:
-    """A knowledge graph built on one GPU (``logoskg_build``)."""
+    """A knowledge graph built on one GPU (``logoskg_build``).
+
+    ``num_shards`` > 1 keeps the subject-sorted triples outside HBM, shard by shard (pinned host
+    memory, or files under ``shard_dir``), behind a cache of ``max_resident_shards`` /
+    ``hbm_shard_budget_bytes``; ``host_build`` sorts a resident graph on the host."""
 
     def __init__(self, subj, rel, obj, num_entities: int, num_relations: int, device: int = 0,
                  num_shards: int = 0, max_resident_shards: int = 0, hbm_shard_budget_bytes: int = 0,
