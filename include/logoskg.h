@@ -156,6 +156,18 @@ logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_t *shard_of
 logoskg_status logoskg_schedule_queries(const logoskg_graph *g, const int64_t *seed_off, const int32_t *seeds,
                                         int64_t num_queries, int32_t *order);
 
+/*
+ * Sec. 3.4, cache warm-up across batches: asks the shard cache for the given
+ * shards, in the given order, as a hop of a batch would (a resident shard is a
+ * hit, a missing one is loaded into an empty or the least recently used slot and
+ * counted as a load).  The copies run on the graph's copy stream, so a caller who
+ * knows the next batch - its seeds' shards through logoskg_graph_partition, or
+ * the order of logoskg_schedule_queries - can issue them while the current
+ * batch's lists are written.  shards: host int32[n], each in [0, num_shards); at
+ * most as many as there are cache slots are useful.  No-op on an unsharded graph.
+ */
+logoskg_status logoskg_prefetch_shards(logoskg_graph *g, const int32_t *shards, int32_t n);
+
 /* ------------------------------------------------------------------- khop */
 
 #define LOGOSKG_DIR_AUTO 0u       /* choose push or pull per hop from the frontier's edge count */

@@ -121,6 +121,8 @@ def _load():
     lib.logoskg_result_free.argtypes = [P]
     lib.logoskg_paths.restype = ctypes.c_int
     lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_prefetch_shards.restype = ctypes.c_int
+    lib.logoskg_prefetch_shards.argtypes = [P, P, I32]
     lib.logoskg_schedule_queries.restype = ctypes.c_int
     lib.logoskg_schedule_queries.argtypes = [P, P, P, I64, P]
     lib.logoskg_walks.restype = ctypes.c_int
@@ -375,6 +377,11 @@ class Graph:
                                      count.data_ptr(), edges.data_ptr() if edges.numel() else None,
                                      _stream_handle(stream)))
         return count, edges
+
+    def prefetch_shards(self, shards) -> None:
+        """``logoskg_prefetch_shards``: ask the shard cache for these shards now (host list)."""
+        ids = np.ascontiguousarray(shards, dtype=np.int32)
+        _check(_load().logoskg_prefetch_shards(self._h, ids.ctypes.data_as(ctypes.c_void_p), ids.shape[0]))
 
     def schedule_queries(self, seed_off, seeds) -> np.ndarray:
         """``logoskg_schedule_queries``: the order (int32[Q] of query indices) that groups the

@@ -727,6 +727,24 @@ extern "C" logoskg_status logoskg_graph_partition(const logoskg_graph *g, int32_
     return LOGOSKG_OK;
 }
 
+extern "C" logoskg_status logoskg_prefetch_shards(logoskg_graph *g, const int32_t *shards, int32_t n) {
+    if (!g || n < 0 || (n > 0 && !shards)) { set_error("bad argument"); return LOGOSKG_EINVAL; }
+    if (g->num_shards <= 1 || n == 0) return LOGOSKG_OK;
+    ShardSet *ss = (ShardSet *)g->shards;
+    if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
+    for (int32_t i = 0; i < n; ++i)
+        if (shards[i] < 0 || shards[i] >= ss->n) {
+            set_error("shard %d outside [0, %d)", shards[i], ss->n);
+            return LOGOSKG_EINVAL;
+        }
+    LKG_HIP(hipSetDevice(g->device));
+    for (int32_t i = 0; i < n; ++i) {
+        int slot = -1;
+        LKG_TRY(acquire(g, ss, shards[i], nullptr, &slot));
+    }
+    return LOGOSKG_OK;
+}
+
 extern "C" logoskg_status logoskg_schedule_queries(const logoskg_graph *g, const int64_t *seed_off,
                                                    const int32_t *seeds, int64_t num_queries, int32_t *order) {
     if (!g || !seed_off || !order || num_queries < 0 || num_queries > 0x7fffffff) {

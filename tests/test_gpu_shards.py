@@ -176,3 +176,33 @@ def test_shards_on_disk_give_the_same_results_and_counters(tmp_path):
     with pytest.raises(m.LogosKGError):
         m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=4,
                 shard_dir=str(tmp_path / "missing"))
+
+
+def test_prefetch_warms_the_cache_for_the_next_batch():
+    # the shards of the next batch's seeds are asked for ahead of its khop: they count as loads at
+    # the prefetch and as hits in the hop; the counters follow the LRU model of the whole sequence
+    m = lkg()
+    w = kggen.config5(0.0005, num_queries=256)
+    P_o, _ = part.degree_aware_partition(w.num_entities, w.subj, 8)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, 1, w.rel_mask)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8, max_resident_shards=3)
+    needs = sorted({s for nd in part.query_needs(P_o, w.seed_off, w.seeds) for s in nd})
+    first = needs[:3]
+    g.prefetch_shards(first)
+    info = g.info()
+    assert (info["shard_loads"], info["shard_hits"], info["shard_evictions"]) == (3, 0, 0)
+    g.prefetch_shards(first[:1])                      # resident: a hit
+    assert g.info()["shard_hits"] == 1
+    res = g.khop(w.seed_off, w.seeds, 1)
+    ent, hop, pred = (x.cpu().numpy() for x in res.fetch())
+    assert np.array_equal(res.offsets(), want[0]) and np.array_equal(ent, want[1]) and np.array_equal(pred, want[3])
+    res.close()
+    seq = first + first[:1] + part.shard_accesses(P_o, w.subj, w.num_entities, 1, want[1], want[2])
+    info = g.info()
+    assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == part.lru_counts(seq, 3)
+    with pytest.raises(m.LogosKGError):
+        g.prefetch_shards([8])
+    g.close()
+    g1 = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    g1.prefetch_shards([0, 5])                        # unsharded: nothing to do
+    g1.close()
