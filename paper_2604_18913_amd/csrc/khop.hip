@@ -316,6 +316,12 @@ k_update_visited(long long Epad, const uint32_t *__restrict__ act_cur, const uns
 }
 
 // ---------------------------------------------------------------- pull
+// From this share of the triples leaving the frontier the pull kernels gather every edge's line
+// without asking for its frontier bit first.  A bit test is a scattered 4-byte load, i.e. a 64-byte
+// sector through the L1 per edge, and these kernels are bound by what the L2s deliver; skipping the
+// test costs the lines of the edges outside the frontier (zero lines: a level line is non-zero only
+// where its active bit is set), which is less traffic as soon as half the edges are inside.
+constexpr int kDensePullPercent = 60;
 // Removes up to 64/W candidates from the (wave-uniform) mask and returns the
 // lane position of the one that belongs to the caller's group, or -1.
 template <int W>
@@ -486,7 +492,7 @@ __device__ __forceinline__ unsigned group_ballot(bool p) {
 constexpr int kTailRows = 2;
 constexpr int kTailLines = 2;  // candidate lines of each row requested together
 
-template <int W, bool MASK, bool STATS>
+template <int W, bool MASK, bool STATS, bool DENSE>
 __global__ void __launch_bounds__(256)
 k_pull_tail(const ShortRow *__restrict__ rows, long long n, const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
             const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
@@ -560,7 +566,8 @@ k_pull_tail(const ShortRow *__restrict__ rows, long long n, const int32_t *__res
             }
         }
 #pragma unroll
-        for (int r = 0; r < NR; ++r) cand[r] = s[r] >= 0 && ((act_prev[s[r] >> 5] >> (s[r] & 31)) & 1u);
+        for (int r = 0; r < NR; ++r)
+            cand[r] = s[r] >= 0 && (DENSE || ((act_prev[s[r] >> 5] >> (s[r] & 31)) & 1u));
         unsigned gm[NR];
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
@@ -636,7 +643,7 @@ k_pull_tail(const ShortRow *__restrict__ rows, long long n, const int32_t *__res
 // with one segment is finished here; segments of a multi-segment row merge
 // through atomicOr on level[h] and look at what the others have found so far
 // to stop early; k_pull_finish then folds those rows into visited.
-template <int W, bool MASK, bool STATS>
+template <int W, bool MASK, bool STATS, bool DENSE>
 __global__ void __launch_bounds__(256)
 k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__restrict__ off,
            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
@@ -672,11 +679,13 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
         // before the lines of chunk i are gathered
         PullEdges e0 = pull_load_edges<MASK>(lo, hi, in_sub, in_rel);
         PullEdges e1 = pull_load_edges<MASK>(lo + 64, hi, in_sub, in_rel);
-        bool c0 = pull_test(e0, act_prev);
+        // DENSE: nearly every subject is in the frontier, so the one-bit test (a 64-byte sector per
+        // edge) is skipped and every edge's line is gathered: the line of an entity outside the frontier is zero
+        bool c0 = DENSE ? e0.s >= 0 : pull_test(e0, act_prev);
         int it = 0;
         for (uint32_t j0 = lo; j0 < hi; j0 += 64, ++it) {
             PullEdges e2 = pull_load_edges<MASK>(j0 + 128, hi, in_sub, in_rel);
-            const bool c1 = pull_test(e1, act_prev);
+            const bool c1 = DENSE ? e1.s >= 0 : pull_test(e1, act_prev);
             n_lines += pull_gather<W, MASK>(e0, c0, prev, allow, a0, a1, queue_s[threadIdx.x >> 6], queue_r[threadIdx.x >> 6]);
             n_edges += min((uint32_t)64, hi - j0);
             e0 = e1;
@@ -777,18 +786,34 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
         unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
         k_live<W><<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, prev, live);
     }
+    // when most triples leave the frontier the kernels gather every edge's line without asking for
+    // its frontier bit first (never in the counting mode: its statistics count frontier lines)
+    const bool dense = !STATS && (long long)hc[C_FEDGES] * 100 >= g->T * (long long)kDensePullPercent;
+    const int walk = r->walk_exact ? 1 : 0;
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
-        k_pull_seg<W, MASK, STATS><<<dim3(blocks_for(rc.n_seg, 4)), dim3(256), 0, st>>>(
-            rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur,
-            act_cur, stats(KK_PULL_SEG), r->walk_exact ? 1 : 0);
+        const dim3 grid(blocks_for(rc.n_seg, 4)), block(256);
+        if (dense)
+            k_pull_seg<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel,
+                                                                     r->allow, act_prev, prev, live, r->visited, cur,
+                                                                     act_cur, stats(KK_PULL_SEG), walk);
+        else
+            k_pull_seg<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel,
+                                                                      r->allow, act_prev, prev, live, r->visited, cur,
+                                                                      act_cur, stats(KK_PULL_SEG), walk);
     }
     if (rc.n_tail > 0) {
         ProfScope ps(g->prof, KK_PULL_TAIL, st);
         const long long groups = (rc.n_tail + kTailRows - 1) / kTailRows;
-        k_pull_tail<W, MASK, STATS><<<dim3(blocks_for(groups * W, 256)), dim3(256), 0, st>>>(
-            rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow, act_prev, prev, live, r->visited, cur, act_cur,
-            stats(KK_PULL_TAIL), r->walk_exact ? 1 : 0);
+        const dim3 grid(blocks_for(groups * W, 256)), block(256);
+        if (dense)
+            k_pull_tail<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow,
+                                                                      act_prev, prev, live, r->visited, cur, act_cur,
+                                                                      stats(KK_PULL_TAIL), walk);
+        else
+            k_pull_tail<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow,
+                                                                       act_prev, prev, live, r->visited, cur, act_cur,
+                                                                       stats(KK_PULL_TAIL), walk);
     }
     if (rc.n_multi > 0) {
         ProfScope ps(g->prof, KK_PULL_FINISH, st);
