@@ -187,6 +187,13 @@ k_live(const uint32_t *__restrict__ act, int32_t E, const uint32_t *__restrict__
     }
 }
 
+// Every query counts as live: used instead of k_live where the frontier holds most of the
+// graph's triples (then hardly any query has none, and a query wrongly taken as live only keeps
+// a row from stopping early: its bit is in no frontier line).
+__global__ void k_live_all(int Q, int W, unsigned long long *live) {
+    if ((int)threadIdx.x < W) live[threadIdx.x] = query_bits(Q, (int)threadIdx.x);
+}
+
 // ---------------------------------------------------------------- push
 __device__ __forceinline__ void mark_active(uint32_t *act, int e) {
     uint32_t bit = 1u << (e & 31);
@@ -781,14 +788,15 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
     unsigned long long *live = r->live + (size_t)16 * (h - 1);
     auto stats = [&](int kind) { return want_stats ? g->d_ctr + C_STATS + 4 * kind : nullptr; };
     const RowClasses &rc = g->in_rows;
-    {
-        ProfScope ps(g->prof, KK_LIVE, st);
-        unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
-        k_live<W><<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, prev, live);
-    }
     // when most triples leave the frontier the kernels gather every edge's line without asking for
     // its frontier bit first (never in the counting mode: its statistics count frontier lines)
     const bool dense = !STATS && (long long)hc[C_FEDGES] * 100 >= g->T * (long long)kDensePullPercent;
+    {
+        ProfScope ps(g->prof, KK_LIVE, st);
+        unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
+        if (dense) k_live_all<<<dim3(1), dim3(64), 0, st>>>(r->Q, W, live);
+        else k_live<W><<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, prev, live);
+    }
     const int walk = r->walk_exact ? 1 : 0;
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
