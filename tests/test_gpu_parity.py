@@ -88,6 +88,12 @@ def test_config2_one_percent(direction, hub_min):
     assert_same(got, want, f"config2/100 {direction} hub_min={hub_min}")
     check_invariants(w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask, *got[:4],
                      queries=range(0, 1024, 97))
+    if direction == "pull":
+        # the pull kernels have two forms: one tests an edge's frontier bit before it gathers the
+        # line, the other (from 60 % of the triples leaving the frontier) gathers every line; this
+        # workload must have gone through both
+        share = [s["frontier_edges"] / len(w.subj) for s in stats if s["direction"] == 2]
+        assert any(x < 0.6 for x in share) and any(x >= 0.6 for x in share), share
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
