@@ -178,82 +178,100 @@ k_triple_expand(long long total, long long nchunks, const long long *__restrict_
                 const int32_t *__restrict__ out_eid, const unsigned long long *__restrict__ allow, int W,
                 const long long *__restrict__ level_off, int q0, int q1, int32_t *__restrict__ triple,
                 int32_t *__restrict__ subject, int32_t *__restrict__ relation, int32_t *__restrict__ object) {
-    __shared__ int wave_count[kBlock / 64];
-    if constexpr (!MASK) {
-        // A position is a chain of dependent loads (chunk bounds, search steps, subject, row start,
-        // then the triple itself) and the kernel is bound by that latency, not by bytes: a thread
-        // takes the same position of kExpandChunks consecutive chunks and walks their chains together.
-        constexpr int U = kExpandChunks;
-        for (long long c0 = (long long)blockIdx.x * U; c0 < nchunks; c0 += (long long)gridDim.x * U) {
-            long long x[U], lo[U], hi[U];
+    // A position is a chain of dependent loads (chunk bounds, search steps, subject, row start,
+    // with a whitelist the entry's query, then the triple itself) and the kernel is bound by that
+    // latency, not by bytes: a thread takes the same position of kExpandChunks consecutive chunks
+    // and walks their chains together.
+    constexpr int U = kExpandChunks;
+    __shared__ int wave_count[MASK ? U : 1][kBlock / 64];
+    for (long long c0 = (long long)blockIdx.x * U; c0 < nchunks; c0 += (long long)gridDim.x * U) {  // block-uniform
+        long long x[U], lo[U], hi[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long long c = c0 + u;
+            x[u] = c * kBlock + threadIdx.x;
+            const bool have = c < nchunks && x[u] < total;
+            lo[u] = have ? chunk_entry[c] : 0;
+            hi[u] = have ? chunk_entry[c + 1] : -1;  // lo > hi: nothing to copy
+        }
+        // the last entry in [lo, hi] whose row starts at or before x
+        for (bool open = true; open;) {
+            open = false;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (lo[u] < hi[u]) {
+                    const long long mid = (lo[u] + hi[u] + 1) >> 1;
+                    if (row_first[mid] <= x[u]) lo[u] = mid;
+                    else hi[u] = mid - 1;
+                    open |= lo[u] < hi[u];
+                }
+        }
+        bool ok[U];
+        int32_t sub[U];
+        uint32_t p[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ok[u] = hi[u] >= 0;
+            sub[u] = ok[u] ? ent[lo[u]] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) p[u] = ok[u] ? out_off[sub[u]] + (uint32_t)(x[u] - row_first[lo[u]]) : 0u;
+        int32_t ve[U], vr[U], vo[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ve[u] = vr[u] = vo[u] = 0;
+            if (ok[u]) {
+                if (triple) ve[u] = out_eid[p[u]];
+                if (MASK || relation) vr[u] = out_rel[p[u]];
+                if (object) vo[u] = out_obj[p[u]];
+            }
+        }
+        long long pos[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) pos[u] = x[u];
+        if constexpr (MASK) {
+            // the entry's query: the last q in [q0, q1 - 1] with level_off[q] <= its place in the lists
+            int ql[U], qh[U];
+            const long long first = level_off[q0];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const long long c = c0 + u;
-                x[u] = c * kBlock + threadIdx.x;
-                const bool have = c < nchunks && x[u] < total;
-                lo[u] = have ? chunk_entry[c] : 0;
-                hi[u] = have ? chunk_entry[c + 1] : -1;  // lo > hi: nothing to copy
+                ql[u] = q0;
+                qh[u] = ok[u] ? q1 - 1 : q0;
             }
             for (bool open = true; open;) {
                 open = false;
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    if (lo[u] < hi[u]) {
-                        const long long mid = (lo[u] + hi[u] + 1) >> 1;
-                        if (row_first[mid] <= x[u]) lo[u] = mid;
-                        else hi[u] = mid - 1;
-                        open |= lo[u] < hi[u];
+                    if (ql[u] < qh[u]) {
+                        const int mid = (ql[u] + qh[u] + 1) >> 1;
+                        if (level_off[mid] <= first + lo[u]) ql[u] = mid;
+                        else qh[u] = mid - 1;
+                        open |= ql[u] < qh[u];
                     }
             }
-            int32_t sub[U];
-            uint32_t p[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) sub[u] = hi[u] >= 0 ? ent[lo[u]] : 0;
-#pragma unroll
-            for (int u = 0; u < U; ++u) p[u] = hi[u] >= 0 ? out_off[sub[u]] + (uint32_t)(x[u] - row_first[lo[u]]) : 0u;
-            int32_t ve[U], vr[U], vo[U];
+            unsigned long long b[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                ve[u] = vr[u] = vo[u] = 0;
-                if (hi[u] >= 0) {
-                    if (triple) ve[u] = out_eid[p[u]];
-                    if (relation) vr[u] = out_rel[p[u]];
-                    if (object) vo[u] = out_obj[p[u]];
-                }
+                if (ok[u]) ok[u] = allowed(allow, W, vr[u], ql[u]);
+                b[u] = __ballot(ok[u]);
+                if (lane() == 0) wave_count[u][threadIdx.x >> 6] = __popcll(b[u]);
             }
+            __syncthreads();
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (hi[u] >= 0) {
-                    if (triple) triple[x[u]] = ve[u];
-                    if (subject) subject[x[u]] = sub[u];
-                    if (relation) relation[x[u]] = vr[u];
-                    if (object) object[x[u]] = vo[u];
-                }
+            for (int u = 0; u < U; ++u) {
+                pos[u] = (c0 + u < nchunks ? chunk_first[c0 + u] : 0) + __popcll(b[u] & ((1ull << lane()) - 1ull));
+                for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pos[u] += wave_count[u][w];
+            }
+            __syncthreads();  // the counts are rewritten by the next turn
         }
-        return;
-    }
-    for (long long c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        const long long x = c * kBlock + threadIdx.x;
-        const Position r = locate(x, total, c, chunk_entry, row_first, ent, out_off);
-        bool ok = r.entry >= 0;
-        int rr = 0;
-        if (ok) rr = out_rel[r.p];
-        long long pos = x;
-        if (MASK) {
-            if (ok) ok = allowed(allow, W, rr, query_of(level_off, q0, q1 - 1, level_off[q0] + r.entry));
-            const unsigned long long b = __ballot(ok);
-            if (lane() == 0) wave_count[threadIdx.x >> 6] = __popcll(b);
-            __syncthreads();
-            pos = chunk_first[c] + __popcll(b & ((1ull << lane()) - 1ull));
-            for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) pos += wave_count[w];
-            __syncthreads();
-        }
-        if (ok) {
-            if (triple) triple[pos] = out_eid[r.p];
-            if (subject) subject[pos] = r.s;
-            if (relation) relation[pos] = rr;
-            if (object) object[pos] = out_obj[r.p];
-        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) {
+                if (triple) triple[pos[u]] = ve[u];
+                if (subject) subject[pos[u]] = sub[u];
+                if (relation) relation[pos[u]] = vr[u];
+                if (object) object[pos[u]] = vo[u];
+            }
     }
 }
 
@@ -402,7 +420,7 @@ extern "C" logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
     const long long total = r->trip_total, nchunks = (total + kBlock - 1) / kBlock;
-    dim3 grid(blocks_for(nchunks, 1)), block(kBlock);
+    dim3 grid(blocks_for((nchunks + kExpandChunks - 1) / kExpandChunks, 1)), block(kBlock);
     {
         ProfScope ps(g->prof, KK_TRIPLES, st);
         if (r->has_mask)
@@ -411,7 +429,7 @@ extern "C" logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_
                                                           g->out_rel, g->out_eid, r->allow, r->W, r->d_level_off, q0,
                                                           q1, triple, subject, relation, object);
         else
-            k_triple_expand<false><<<dim3(blocks_for((nchunks + kExpandChunks - 1) / kExpandChunks, 1)), block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr,
+            k_triple_expand<false><<<grid, block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr,
                                                            r->trip_ent, g->out_off, g->out_obj, g->out_rel, g->out_eid,
                                                            nullptr, r->W, r->d_level_off, q0, q1, triple, subject,
                                                            relation, object);
