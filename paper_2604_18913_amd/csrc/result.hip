@@ -556,6 +556,16 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, in
     const bool shortrow = deg > 0 && deg <= (uint32_t)kTailMaxDegree;
     u.stage[vi][lw] = visw;
     const bool longrow = deg > (uint32_t)kTailMaxDegree;
+    // requested now, used after the barriers below: the list position of query t's run, and the
+    // level words of the first hops
+    long long early_base = 0;
+    if (t < 256 && tile0 < a.tile_begin + a.tile_count)
+        early_base = super_start(a, tile0 / kSuperTiles, Qp, slab * 256 + t) + a.tile_base[(size_t)tile0 * Qp + slab * 256 + t];
+    unsigned long long lvl_pre[3] = {0, 0, 0};
+    if (visw & ~seedw)
+#pragma unroll
+        for (int h = 1; h <= 3; ++h)
+            if (h <= a.k) lvl_pre[h - 1] = a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
     if (lw == 0) {
         roff[vi] = shortrow ? (uint16_t)deg : (uint16_t)0;
         in_lo[vi] = lo;
@@ -602,10 +612,7 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, in
         pos0[3][t] = (uint32_t)(ex + c0 + c1 + c2);
         roff[t] = (uint16_t)dx;
         if (t == 255) short_entries = dx + my_deg;
-        const int q = slab * 256 + t;
-        long long b = 0;
-        if (tot > 0) b = super_start(a, tile0 / kSuperTiles, Qp, q) + a.tile_base[(size_t)tile0 * Qp + q];
-        base[t] = b;
+        base[t] = tot > 0 ? early_base : 0;
     }
     __syncthreads();
     const int my_roff = roff[vi];
@@ -638,12 +645,12 @@ k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, in
         if (mine && seedw) emit(seedw, (unsigned)vi << 5);
         if (mine && longrow && (visw & ~seedw))
             for (int h = 1; h <= a.k; ++h) {
-                unsigned long long lv = a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
+                unsigned long long lv = h <= 3 ? lvl_pre[h - 1] : a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
                 if (lv) emit(lv, ((unsigned)h << 13) | ((unsigned)vi << 5));
             }
         if (shortrow && reached)
             for (int h = 1; h <= a.k; ++h) {
-                unsigned long long rem = mine ? a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w : 0ull;
+                unsigned long long rem = !mine ? 0ull : h <= 3 ? lvl_pre[h - 1] : a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
                 if (!group_any<G>(rem != 0)) continue;
                 const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
                 const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
