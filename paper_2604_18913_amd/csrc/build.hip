@@ -124,7 +124,7 @@ static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
 // Object rows with >= 1 entry: short rows, segments of the longer ones (longest
 // rows first), rows with several segments, and the hub rows.
 static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_min,
-                          std::vector<ShortRow> &tail, std::vector<RowSegment> &seg,
+                          std::vector<ShortRow> &tail, std::vector<PullSegment> &seg,
                           std::vector<int32_t> &multi, std::vector<int32_t> &longer, int64_t *n_hub) {
     std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
     *n_hub = 0;
@@ -141,8 +141,10 @@ static void classify_rows(const std::vector<uint32_t> &off, int32_t E, int hub_m
         return off[a + 1] - off[a] > off[b + 1] - off[b];
     });
     for (int32_t v : longer) {
-        if (off[v + 1] - off[v] > (uint32_t)kPullSegment) multi.push_back(v);
-        for (uint32_t j = off[v]; j < off[v + 1]; j += kPullSegment) seg.push_back({v, j});
+        const bool several = off[v + 1] - off[v] > (uint32_t)kPullSegment;
+        if (several) multi.push_back(v);
+        for (uint32_t j = off[v]; j < off[v + 1]; j += kPullSegment)
+            seg.push_back({v, j, std::min(j + (uint32_t)kPullSegment, off[v + 1]), several ? 1u : 0u});
     }
 }
 
@@ -207,7 +209,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         auto object_row_classes = [&](const std::vector<uint32_t> &ioff) -> logoskg_status {
             std::vector<int32_t> multi, longer;
             std::vector<ShortRow> tail;
-            std::vector<RowSegment> seg;
+            std::vector<PullSegment> seg;
             classify_rows(ioff, E, g->hub_min, tail, seg, multi, longer, &g->in_rows.n_hub);
             g->in_rows.n_giant = 0;
             for (int32_t v : longer)  // longest first

@@ -77,6 +77,12 @@ struct RowSegment {  // part [begin, min(begin + segment, row end)) of one CSR r
     uint32_t begin;
 };
 
+struct PullSegment {  // a segment [begin, end) of an object row; multi: the row has several segments
+    int32_t row;
+    uint32_t begin, end;
+    uint32_t multi;
+};
+
 struct ShortRow {  // a CSR row with its bounds, so that a kernel needs no look-up in the offsets
     int32_t row;
     uint32_t begin, end;
@@ -84,7 +90,7 @@ struct ShortRow {  // a CSR row with its bounds, so that a kernel needs no look-
 
 struct RowClasses {             // device work lists over the object rows, split by degree
     ShortRow *tail = nullptr;   // rows with 1 .. kTailMaxDegree entries, descending degree
-    RowSegment *seg = nullptr;  // segments of the longer rows, longest rows first
+    PullSegment *seg = nullptr;  // segments of the longer rows, longest rows first
     int32_t *multi = nullptr;   // rows cut into more than one segment
     int32_t *longrows = nullptr;  // rows with more than kTailMaxDegree entries, descending degree
                                   // (per streamed chunk when sharded); the first n_hub of them

@@ -652,7 +652,7 @@ k_pull_tail(const ShortRow *__restrict__ rows, long long n, const int32_t *__res
 // to stop early; k_pull_finish then folds those rows into visited.
 template <int W, bool MASK, bool STATS, bool DENSE>
 __global__ void __launch_bounds__(256)
-k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__restrict__ off,
+k_pull_seg(const PullSegment *__restrict__ segs, long long n,
            const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
            const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ act_prev,
            const unsigned long long *__restrict__ prev, const unsigned long long *__restrict__ live,
@@ -668,12 +668,11 @@ k_pull_seg(const RowSegment *__restrict__ segs, long long n, const uint32_t *__r
     bool multi = false;
     unsigned long long vis = 0, need = 0, acc = 0;
     if (have) {
-        RowSegment sg = segs[item];
+        const PullSegment sg = segs[item];  // carries its bounds: no look-up in the offsets before the first loads
         v = sg.row;
         lo = sg.begin;
-        uint32_t row_lo = off[v], row_hi = off[v + 1];
-        hi = min(lo + (uint32_t)kPullSegment, row_hi);
-        multi = (row_hi - row_lo) > (uint32_t)kPullSegment;
+        hi = sg.end;
+        multi = sg.multi != 0;
         vis = visited[(size_t)v * W + lw];
         need = (walk_exact ? ~0ull : ~vis) & live[lw];
         if (multi) need &= ~__atomic_load_n(&cur[(size_t)v * W + lw], __ATOMIC_RELAXED);
@@ -802,11 +801,11 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
         ProfScope ps(g->prof, KK_PULL_SEG, st);
         const dim3 grid(blocks_for(rc.n_seg, 4)), block(256);
         if (dense)
-            k_pull_seg<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel,
+            k_pull_seg<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_sub, g->in_rel,
                                                                      r->allow, act_prev, prev, live, r->visited, cur,
                                                                      act_cur, stats(KK_PULL_SEG), walk);
         else
-            k_pull_seg<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_off, g->in_sub, g->in_rel,
+            k_pull_seg<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_sub, g->in_rel,
                                                                       r->allow, act_prev, prev, live, r->visited, cur,
                                                                       act_cur, stats(KK_PULL_SEG), walk);
     }
