@@ -916,7 +916,8 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     if (!r) return;
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
-    void *ptrs[] = {r->visited, r->levels, r->act, r->allow, r->live, r->tile_base,
+    // levels follows visited and live follows act in one allocation each
+    void *ptrs[] = {r->visited, r->act, r->allow, r->tile_base,
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
                     r->lvl_mega_base, r->d_level_off, r->trip_ent, r->trip_off,
                     r->trip_chunk_entry, r->trip_chunk_first};
@@ -961,10 +962,13 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     const size_t actw = (size_t)r->Epad / 32;
     logoskg_status s;
     auto fail = [&](logoskg_status e) { logoskg_result_free(r); return e; };
-    if ((s = g->pool.alloc((void **)&r->visited, plane * 8)) != LOGOSKG_OK) return fail(s);
-    if ((s = g->pool.alloc((void **)&r->levels, plane * 8 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
-    if ((s = g->pool.alloc((void **)&r->act, actw * 4 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
-    if ((s = g->pool.alloc((void **)&r->live, (size_t)16 * 8 * (size_t)(k + 1))) != LOGOSKG_OK) return fail(s);
+    // visited and the level planes are one allocation, the active bitmaps and the live words
+    // another: each is cleared by one fill
+    const size_t act_bytes = actw * 4 * (size_t)(k + 1), live_bytes = (size_t)16 * 8 * (size_t)(k + 1);
+    if ((s = g->pool.alloc((void **)&r->visited, plane * 8 * (size_t)(k + 2))) != LOGOSKG_OK) return fail(s);
+    r->levels = r->visited + plane;
+    if ((s = g->pool.alloc((void **)&r->act, act_bytes + live_bytes)) != LOGOSKG_OK) return fail(s);
+    r->live = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(r->act) + act_bytes);
     if (r->has_mask && (s = g->pool.alloc((void **)&r->allow, (size_t)g->R * W * 8)) != LOGOSKG_OK) return fail(s);
 
 #define KH(call)                                  \
@@ -975,10 +979,8 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
 
     {
         ProfScope ps(g->prof, KK_CLEAR, st);
-        KH(hipMemsetAsync(r->visited, 0, plane * 8, st));
-        KH(hipMemsetAsync(r->levels, 0, plane * 8 * (size_t)(k + 1), st));
-        KH(hipMemsetAsync(r->act, 0, actw * 4 * (size_t)(k + 1), st));
-        KH(hipMemsetAsync(r->live, 0, (size_t)16 * 8 * (size_t)(k + 1), st));
+        KH(hipMemsetAsync(r->visited, 0, plane * 8 * (size_t)(k + 2), st));
+        KH(hipMemsetAsync(r->act, 0, act_bytes + live_bytes, st));
         KH(hipMemsetAsync(g->d_ctr, 0, C_TOTAL * sizeof(unsigned long long), st));
         g->prof.acc[KK_CLEAR].units[3] += g->prof.on ? (long long)(plane * (size_t)(k + 2)) : 0;
     }
