@@ -110,6 +110,81 @@ __device__ __forceinline__ bool position_allowed(const Position &r, const uint16
     return allowed(allow, W, out_rel[r.p], q);
 }
 
+// The copy of a position is a chain of dependent loads (chunk bounds, search steps, subject, row
+// start, with a whitelist the entry's query, then the triple itself), and a kernel with one
+// position per thread runs at the rate that latency allows, not at the rate of its bytes.  So a
+// thread takes the same position of U consecutive chunks and walks their chains together.
+template <int U>
+struct Chains {
+    long long x[U];    // concatenated position
+    long long lo[U];   // its list entry
+    bool ok[U];        // the position exists
+    int32_t sub[U];    // subject of the entry
+    uint32_t p[U];     // index into the arrays of SUB's rows
+};
+
+template <int U>
+__device__ __forceinline__ void walk_chains(long long c0, long long total, long long nchunks,
+                                            const long long *__restrict__ chunk_entry,
+                                            const long long *__restrict__ row_first,
+                                            const int32_t *__restrict__ ent, const uint32_t *__restrict__ out_off,
+                                            Chains<U> &k) {
+    long long hi[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const long long c = c0 + u;
+        k.x[u] = c * kBlock + threadIdx.x;
+        k.ok[u] = c < nchunks && k.x[u] < total;
+        k.lo[u] = k.ok[u] ? chunk_entry[c] : 0;
+        hi[u] = k.ok[u] ? chunk_entry[c + 1] : 0;
+    }
+    // the last entry in [lo, hi] whose row starts at or before x
+    for (bool open = true; open;) {
+        open = false;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (k.lo[u] < hi[u]) {
+                const long long mid = (k.lo[u] + hi[u] + 1) >> 1;
+                if (row_first[mid] <= k.x[u]) k.lo[u] = mid;
+                else hi[u] = mid - 1;
+                open |= k.lo[u] < hi[u];
+            }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) k.sub[u] = k.ok[u] ? ent[k.lo[u]] : 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) k.p[u] = k.ok[u] ? out_off[k.sub[u]] + (uint32_t)(k.x[u] - row_first[k.lo[u]]) : 0u;
+}
+
+// ok[u] &= the relation rel[u] of position u is on the whitelist of the entry's query (the last q
+// in [q0, q1 - 1] with level_off[q] <= the entry's place in the level lists)
+template <int U>
+__device__ __forceinline__ void filter_chains(Chains<U> &k, const int32_t *rel,
+                                              const unsigned long long *__restrict__ allow, int W,
+                                              const long long *__restrict__ level_off, int q0, int q1) {
+    int ql[U], qh[U];
+    const long long first = level_off[q0];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        ql[u] = q0;
+        qh[u] = k.ok[u] ? q1 - 1 : q0;
+    }
+    for (bool open = true; open;) {
+        open = false;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ql[u] < qh[u]) {
+                const int mid = (ql[u] + qh[u] + 1) >> 1;
+                if (level_off[mid] <= first + k.lo[u]) ql[u] = mid;
+                else qh[u] = mid - 1;
+                open |= ql[u] < qh[u];
+            }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (k.ok[u]) k.ok[u] = allowed(allow, W, rel[u], ql[u]);
+}
+
 // chunk_count[c] = allowed triples among the positions of chunk c; chunk_count[nchunks] = 0
 __global__ void __launch_bounds__(kBlock)
 k_chunk_count(long long total, long long nchunks, const long long *__restrict__ chunk_entry,
@@ -117,20 +192,25 @@ k_chunk_count(long long total, long long nchunks, const long long *__restrict__ 
               const uint32_t *__restrict__ out_off, const uint16_t *__restrict__ out_rel,
               const unsigned long long *__restrict__ allow, int W, const long long *__restrict__ level_off, int q0,
               int q1, long long *chunk_count) {
-    __shared__ int wave_count[kBlock / 64];
-    for (long long c = blockIdx.x; c <= nchunks; c += gridDim.x) {
-        bool ok = false;
-        if (c < nchunks) {
-            const Position r = locate(c * kBlock + threadIdx.x, total, c, chunk_entry, row_first, ent, out_off);
-            ok = position_allowed(r, out_rel, allow, W, level_off, q0, q1);
+    constexpr int U = kExpandChunks;
+    __shared__ int wave_count[U][kBlock / 64];
+    for (long long c0 = (long long)blockIdx.x * U; c0 <= nchunks; c0 += (long long)gridDim.x * U) {  // block-uniform
+        Chains<U> k;
+        walk_chains<U>(c0, total, nchunks, chunk_entry, row_first, ent, out_off, k);
+        int32_t rel[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) rel[u] = k.ok[u] ? out_rel[k.p[u]] : 0;
+        filter_chains<U>(k, rel, allow, W, level_off, q0, q1);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long b = __ballot(k.ok[u]);
+            if (lane() == 0) wave_count[u][threadIdx.x >> 6] = __popcll(b);
         }
-        const unsigned long long b = __ballot(ok);
-        if (lane() == 0) wave_count[threadIdx.x >> 6] = __popcll(b);
         __syncthreads();
-        if (threadIdx.x == 0) {
+        if (threadIdx.x < U && c0 + threadIdx.x <= nchunks) {
             int sum = 0;
-            for (int w = 0; w < kBlock / 64; ++w) sum += wave_count[w];
-            chunk_count[c] = sum;
+            for (int w = 0; w < kBlock / 64; ++w) sum += wave_count[threadIdx.x][w];
+            chunk_count[c0 + threadIdx.x] = sum;
         }
         __syncthreads();
     }
@@ -178,82 +258,30 @@ k_triple_expand(long long total, long long nchunks, const long long *__restrict_
                 const int32_t *__restrict__ out_eid, const unsigned long long *__restrict__ allow, int W,
                 const long long *__restrict__ level_off, int q0, int q1, int32_t *__restrict__ triple,
                 int32_t *__restrict__ subject, int32_t *__restrict__ relation, int32_t *__restrict__ object) {
-    // A position is a chain of dependent loads (chunk bounds, search steps, subject, row start,
-    // with a whitelist the entry's query, then the triple itself) and the kernel is bound by that
-    // latency, not by bytes: a thread takes the same position of kExpandChunks consecutive chunks
-    // and walks their chains together.
     constexpr int U = kExpandChunks;
     __shared__ int wave_count[MASK ? U : 1][kBlock / 64];
     for (long long c0 = (long long)blockIdx.x * U; c0 < nchunks; c0 += (long long)gridDim.x * U) {  // block-uniform
-        long long x[U], lo[U], hi[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long long c = c0 + u;
-            x[u] = c * kBlock + threadIdx.x;
-            const bool have = c < nchunks && x[u] < total;
-            lo[u] = have ? chunk_entry[c] : 0;
-            hi[u] = have ? chunk_entry[c + 1] : -1;  // lo > hi: nothing to copy
-        }
-        // the last entry in [lo, hi] whose row starts at or before x
-        for (bool open = true; open;) {
-            open = false;
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (lo[u] < hi[u]) {
-                    const long long mid = (lo[u] + hi[u] + 1) >> 1;
-                    if (row_first[mid] <= x[u]) lo[u] = mid;
-                    else hi[u] = mid - 1;
-                    open |= lo[u] < hi[u];
-                }
-        }
-        bool ok[U];
-        int32_t sub[U];
-        uint32_t p[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            ok[u] = hi[u] >= 0;
-            sub[u] = ok[u] ? ent[lo[u]] : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) p[u] = ok[u] ? out_off[sub[u]] + (uint32_t)(x[u] - row_first[lo[u]]) : 0u;
+        Chains<U> k;
+        walk_chains<U>(c0, total, nchunks, chunk_entry, row_first, ent, out_off, k);
         int32_t ve[U], vr[U], vo[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             ve[u] = vr[u] = vo[u] = 0;
-            if (ok[u]) {
-                if (triple) ve[u] = out_eid[p[u]];
-                if (MASK || relation) vr[u] = out_rel[p[u]];
-                if (object) vo[u] = out_obj[p[u]];
+            if (k.ok[u]) {
+                if (triple) ve[u] = out_eid[k.p[u]];
+                if (MASK || relation) vr[u] = out_rel[k.p[u]];
+                if (object) vo[u] = out_obj[k.p[u]];
             }
         }
         long long pos[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) pos[u] = x[u];
+        for (int u = 0; u < U; ++u) pos[u] = k.x[u];
         if constexpr (MASK) {
-            // the entry's query: the last q in [q0, q1 - 1] with level_off[q] <= its place in the lists
-            int ql[U], qh[U];
-            const long long first = level_off[q0];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                ql[u] = q0;
-                qh[u] = ok[u] ? q1 - 1 : q0;
-            }
-            for (bool open = true; open;) {
-                open = false;
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (ql[u] < qh[u]) {
-                        const int mid = (ql[u] + qh[u] + 1) >> 1;
-                        if (level_off[mid] <= first + lo[u]) ql[u] = mid;
-                        else qh[u] = mid - 1;
-                        open |= ql[u] < qh[u];
-                    }
-            }
+            filter_chains<U>(k, vr, allow, W, level_off, q0, q1);
             unsigned long long b[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (ok[u]) ok[u] = allowed(allow, W, vr[u], ql[u]);
-                b[u] = __ballot(ok[u]);
+                b[u] = __ballot(k.ok[u]);
                 if (lane() == 0) wave_count[u][threadIdx.x >> 6] = __popcll(b[u]);
             }
             __syncthreads();
@@ -266,9 +294,9 @@ k_triple_expand(long long total, long long nchunks, const long long *__restrict_
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) {
+            if (k.ok[u]) {
                 if (triple) triple[pos[u]] = ve[u];
-                if (subject) subject[pos[u]] = sub[u];
+                if (subject) subject[pos[u]] = k.sub[u];
                 if (relation) relation[pos[u]] = vr[u];
                 if (object) object[pos[u]] = vo[u];
             }
@@ -369,7 +397,7 @@ extern "C" logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int3
         if ((s = g->pool.alloc((void **)&d_count, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK ||
             (s = g->pool.alloc((void **)&r->trip_chunk_first, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK)
             return done(s);
-        k_chunk_count<<<dim3(blocks_for(nchunks + 1, 1)), dim3(kBlock), 0, st>>>(
+        k_chunk_count<<<dim3(blocks_for((nchunks + kExpandChunks) / kExpandChunks, 1)), dim3(kBlock), 0, st>>>(
             total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_ent, g->out_off, g->out_rel, r->allow, r->W,
             r->d_level_off, q0, q1, d_count);
         if ((s = prefix_sum(d_count, r->trip_chunk_first, (size_t)nchunks + 1)) != LOGOSKG_OK) return done(s);
