@@ -200,8 +200,8 @@ typedef struct {
  * k-hop retrieval.  For query j and entity v the result records
  *   hop_j(v)  = the least h <= k at which v is set in q_j^(h) (0 for seeds), and
  *   the reached set {v : hop_j(v) defined}.
- * Device state: one bit plane per hop level, entity-major, W = 1,2,4,8 or 16
- * uint64 words per entity (bit j%64 of word j/64 belongs to query j), plus the
+ * Device state: one bit plane per hop level, entity-major, W = 1, 4 or 16
+ * uint64 words per entity for up to 64 / 256 / 1024 queries (bit j%64 of word j/64 belongs to query j), plus the
  * OR of all levels ("visited").  Unless LOGOSKG_NO_COUNTS is set the per-query
  * reached counts are computed too.  The call returns after the stream has been
  * synchronised; bad seed ids or offsets are detected on the device and
@@ -322,8 +322,9 @@ void logoskg_result_free(logoskg_result *r);
  * path_edges[i][p][0..d), the rest of each row of k entries is -1.
  * path_count[i] = number written (0 if the target is not reached; 1 empty
  * path if it is a seed).  All four arrays are device memory; path_edges is
- * int32[n_pairs][max_paths][k].  Needs a resident (unsharded) graph.
- * Asynchronous on `stream`.
+ * int32[n_pairs][max_paths][k].  Needs a resident (unsharded) graph.  The
+ * call takes its working memory from the graph's pool and returns after
+ * `stream` has been synchronised.
  */
 logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
                              const int32_t *target, int64_t n_pairs, int32_t max_paths,
@@ -343,6 +344,25 @@ logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const in
 logoskg_status logoskg_walks(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
                              const int32_t *target, const int32_t *length, int64_t n_pairs,
                              int32_t max_paths, int32_t *path_count, int32_t *path_edges, void *stream);
+
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): logoskg_paths with the
+ * same arguments, results and order, whose only working memory - three int32
+ * depth-first stacks of n_pairs * max(k, 1) entries - lives in an array that is
+ * part of the library's device image (12 MiB per GPU, held until the process
+ * ends) instead of a block of the graph's pool.  The call allocates and frees
+ * nothing on the device and does not synchronise: it is asynchronous on
+ * `stream`.  n_pairs * max(k, 1) above LOGOSKG_STATIC_PATH_SLOTS is refused
+ * with LOGOSKG_ERANGE (nothing is launched).  Every call on a GPU uses that
+ * GPU's one array: calls that overlap on one GPU (two streams, two threads,
+ * two graphs) race; issue them on one stream or wait in between.  Nothing
+ * needs clearing between calls (a stack entry is written before it is read).
+ */
+#define LOGOSKG_STATIC_PATH_SLOTS (1ll << 20)
+logoskg_status logoskg_paths_static(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                    const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                                    int32_t *path_count, int32_t *path_edges, void *stream);
 
 const char *logoskg_last_error(void);
 const char *logoskg_version(void);

@@ -9,7 +9,10 @@ INFRASTRUCTURE ONLY, plain Python.
 * lru_counts: the on-demand cache of capacity n sub-graphs under
   least-recently-used replacement, counting loads, evictions and hits.
 * shard_accesses: the sub-graphs Algorithm 1 touches, hop by hop (those that
-  hold a subject of the current frontier), in ascending shard order.
+  hold a subject of the current frontier); the algorithm leaves the order inside
+  a hop open, the reading taken is ascending shard index on odd hops and
+  descending on even hops.  Pinned by a hand-worked trace in
+  tests/test_oracle_pins.py.
 * schedule_queries: the batch-processing order of Sec. 3.4 -- queries grouped by
   the sub-graphs their seeds need (through P), identical needs adjacent, the
   input order kept among equals.

@@ -121,6 +121,8 @@ def _load():
     lib.logoskg_result_free.argtypes = [P]
     lib.logoskg_paths.restype = ctypes.c_int
     lib.logoskg_paths.argtypes = [P, P, P, P, I64, I32, P, P, P]
+    lib.logoskg_paths_static.restype = ctypes.c_int
+    lib.logoskg_paths_static.argtypes = [P, P, P, P, I64, I32, P, P, P]
     lib.logoskg_prefetch_shards.restype = ctypes.c_int
     lib.logoskg_prefetch_shards.argtypes = [P, P, I32]
     lib.logoskg_schedule_queries.restype = ctypes.c_int
@@ -377,6 +379,15 @@ class Graph:
                                      count.data_ptr(), edges.data_ptr() if edges.numel() else None,
                                      _stream_handle(stream)))
         return count, edges
+
+    def paths_static(self, result: Result, query_idx, target, count, edges, max_paths: int = 16, stream=None):
+        """``logoskg_paths_static``: the listing of ``paths`` written into the caller's device tensors
+        ``count`` int32[n] and ``edges`` int32[n, max_paths, k]; ``query_idx`` and ``target`` must
+        already be int32 device tensors.  Nothing is allocated on the device."""
+        n = query_idx.numel()
+        _check(_load().logoskg_paths_static(self._h, result._h, query_idx.data_ptr(), target.data_ptr(), n,
+                                            max_paths, count.data_ptr(), edges.data_ptr() if edges.numel() else None,
+                                            _stream_handle(stream)))
 
     def prefetch_shards(self, shards) -> None:
         """``logoskg_prefetch_shards``: ask the shard cache for these shards now (host list)."""

@@ -11,6 +11,9 @@
 // the ends of the walks of h triples, so the backward walk from level d of the
 // target through levels d-1 .. 0 meets exactly the walks of d allowed triples
 // from a seed (Sec. 3.3: complete paths, extended hop by hop).
+#include <algorithm>
+#include <mutex>
+
 #include "common.h"
 
 namespace lkg {
@@ -82,25 +85,13 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
 
 using namespace lkg;
 
-static logoskg_status list_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
-                                 const int32_t *target, const int32_t *length, int64_t n_pairs, int32_t max_paths,
-                                 int32_t *path_count, int32_t *path_edges, void *stream) {
-    if (n_pairs < 0 || max_paths < 1 || max_paths > LOGOSKG_MAX_PATHS) {
-        set_error("bad n_pairs / max_paths");
-        return LOGOSKG_EINVAL;
-    }
-    if (n_pairs == 0) return LOGOSKG_OK;
-    if (!query_idx || !target || !path_count || (r->k > 0 && !path_edges)) {
-        set_error("NULL argument");
-        return LOGOSKG_EINVAL;
-    }
-    if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
-    LKG_HIP(hipSetDevice(g->device));
-    hipStream_t st = (hipStream_t)stream;
+// Launches the listing kernel with the three depth-first stacks (vertex, next row position,
+// chosen edge; n_pairs * max(k, 1) int32 each) laid out one after another in `ws`.
+static logoskg_status launch_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                   const int32_t *target, const int32_t *length, int64_t n_pairs, int32_t max_paths,
+                                   int32_t *path_count, int32_t *path_edges, void *ws, hipStream_t st) {
     const int k = r->k;
-    void *ws = nullptr;
-    size_t per = (size_t)n_pairs * (size_t)std::max(k, 1) * 4;
-    LKG_TRY(g->pool.alloc(&ws, per * 3));
+    const size_t per = (size_t)n_pairs * (size_t)std::max(k, 1) * 4;
     int32_t *sv = (int32_t *)ws;
     uint32_t *sp = (uint32_t *)((char *)ws + per);
     int32_t *se = (int32_t *)((char *)ws + 2 * per);
@@ -108,12 +99,92 @@ static logoskg_status list_paths(logoskg_graph *g, const logoskg_result *r, cons
         n_pairs, r->Q, k, r->W, g->E, r->Epad * r->W, (const unsigned long long *)r->levels,
         r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, g->in_sub, g->in_rel, g->in_eid,
         query_idx, target, length, max_paths, path_count, path_edges, sv, sp, se);
-    hipError_t e = hipGetLastError();
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}
+
+static logoskg_status check_path_args(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                      const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                                      const int32_t *path_count, const int32_t *path_edges) {
+    if (n_pairs < 0 || max_paths < 1 || max_paths > LOGOSKG_MAX_PATHS) {
+        set_error("bad n_pairs / max_paths");
+        return LOGOSKG_EINVAL;
+    }
+    if (n_pairs > 0 && (!query_idx || !target || !path_count || (r->k > 0 && !path_edges))) {
+        set_error("NULL argument");
+        return LOGOSKG_EINVAL;
+    }
+    if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
+    return LOGOSKG_OK;
+}
+
+static logoskg_status list_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                 const int32_t *target, const int32_t *length, int64_t n_pairs, int32_t max_paths,
+                                 int32_t *path_count, int32_t *path_edges, void *stream) {
+    LKG_TRY(check_path_args(g, r, query_idx, target, n_pairs, max_paths, path_count, path_edges));
+    if (n_pairs == 0) return LOGOSKG_OK;
+    LKG_HIP(hipSetDevice(g->device));
+    hipStream_t st = (hipStream_t)stream;
+    void *ws = nullptr;
+    LKG_TRY(g->pool.alloc(&ws, (size_t)n_pairs * (size_t)std::max(r->k, 1) * 4 * 3));
+    logoskg_status s = launch_paths(g, r, query_idx, target, length, n_pairs, max_paths, path_count, path_edges, ws, st);
     hipError_t e2 = hipStreamSynchronize(st);  // the workspace goes back to the pool below
     g->pool.release(ws);
-    LKG_HIP(e);
+    LKG_TRY(s);
     LKG_HIP(e2);
     return LOGOSKG_OK;
+}
+
+// ---------------------------------------------------------------- listing without any allocation
+// The depth-first stacks of logoskg_paths_static live in this array instead of a block from the
+// graph's pool.  Every GPU the library runs on holds its own copy until the process ends; in host
+// code the array's name is only a handle for hipGetSymbolAddress, the address that kernels and
+// copies use is looked up once per device and kept in static_stack_ptr.
+static __device__ __align__(256) unsigned char static_stacks[LOGOSKG_STATIC_PATH_SLOTS * 4 * 3];
+
+constexpr int kMaxDevices = 64;
+static void *static_stack_ptr[kMaxDevices];
+static std::mutex static_stack_lock;
+
+// Address of the calling device's copy of static_stacks (`device` must be current).
+static logoskg_status static_stack_address(int device, void **out) {
+    if (device < 0 || device >= kMaxDevices) {
+        set_error("device ordinal %d is outside [0, %d)", device, kMaxDevices);
+        return LOGOSKG_EINVAL;
+    }
+    std::lock_guard<std::mutex> lock(static_stack_lock);
+    if (!static_stack_ptr[device]) {
+        void *p = nullptr;
+        LKG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(static_stacks)));
+        if (!p) { set_error("hipGetSymbolAddress returned a null address"); return LOGOSKG_EDEVICE; }
+        static_stack_ptr[device] = p;
+    }
+    *out = static_stack_ptr[device];
+    return LOGOSKG_OK;
+}
+
+extern "C" logoskg_status logoskg_paths_static(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
+                                               const int32_t *target, int64_t n_pairs, int32_t max_paths,
+                                               int32_t *path_count, int32_t *path_edges, void *stream) {
+    if (!g || !r || r->g != g) { set_error("graph / result mismatch"); return LOGOSKG_EINVAL; }
+    if (r->walk_exact) {
+        set_error("shortest paths are not defined for a LOGOSKG_WALK_EXACT result");
+        return LOGOSKG_EINVAL;
+    }
+    LKG_TRY(check_path_args(g, r, query_idx, target, n_pairs, max_paths, path_count, path_edges));
+    const long long slots = (long long)n_pairs * std::max(r->k, 1);
+    if (slots > (long long)LOGOSKG_STATIC_PATH_SLOTS) {
+        set_error("logoskg_paths_static: n_pairs * max(k, 1) = %lld exceeds LOGOSKG_STATIC_PATH_SLOTS = %lld; "
+                  "split the pair list or use logoskg_paths", slots, (long long)LOGOSKG_STATIC_PATH_SLOTS);
+        return LOGOSKG_ERANGE;
+    }
+    if (n_pairs == 0) return LOGOSKG_OK;
+    LKG_HIP(hipSetDevice(g->device));
+    void *ws = nullptr;
+    LKG_TRY(static_stack_address(g->device, &ws));
+    // every stack entry is written before it is read, so nothing has to be cleared between calls
+    return launch_paths(g, r, query_idx, target, nullptr, n_pairs, max_paths, path_count, path_edges, ws,
+                        (hipStream_t)stream);
 }
 
 extern "C" logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,

@@ -1,13 +1,12 @@
-"""Full-size parity on the workloads of the benchmark spec, in the launch
-configuration bench.py times.  The oracle cannot list 10^9 (query, entity)
-pairs in seconds, so it runs on a seeded sample of the queries of the batch and
-every output integer of those queries is compared; invariants that hold at any
-size are checked on further queries.
+"""Full-size parity on the five workloads of the benchmark spec, in the launch
+configuration bench.py times.
 
-configs 2 and 3 always run.  configs 4 (300 M triples) and 5 (1 G triples)
-need minutes of input generation and tens of GB of host memory; they run when
-LOGOSKG_FULLSIZE names them, e.g. LOGOSKG_FULLSIZE=4,5."""
-import os
+configs 2 and 3 (k = 3): every one of the 1,024 queries is compared with the
+oracle, every output integer.  configs 4 (300 M triples, 10^10 reached pairs per
+batch) and 5 (1 G triples): the oracle cannot list that many pairs in seconds,
+so it runs on a seeded sample of the queries of each batch and every output
+integer of those queries is compared.  Both always run; they are skipped only
+when the machine lacks the host memory their inputs need (checked below)."""
 import time
 
 import numpy as np
@@ -18,7 +17,29 @@ import oracle
 from helpers import check_invariants
 
 pytestmark = pytest.mark.gpu
-FULL = {int(x) for x in os.environ.get("LOGOSKG_FULLSIZE", "").split(",") if x.strip()}
+
+
+def host_memory_available_gib():
+    """MemAvailable of /proc/meminfo in GiB (0 when it cannot be read)."""
+    try:
+        with open("/proc/meminfo") as f:
+            for line in f:
+                if line.startswith("MemAvailable:"):
+                    return int(line.split()[1]) / (1 << 20)
+    except OSError:
+        pass
+    return 0.0
+
+
+# peak host memory of the two large cases: generator arrays (stubs, permutations: int64) plus, for
+# config 5, 16 GB of pinned shards and the oracle's index
+NEED_GIB = {4: 40.0, 5: 120.0}
+
+
+def require_host_memory(config):
+    have = host_memory_available_gib()
+    if have < NEED_GIB[config]:
+        pytest.skip(f"config {config} needs about {NEED_GIB[config]:.0f} GiB of host memory, {have:.0f} GiB available")
 
 
 def lkg():
@@ -72,15 +93,39 @@ def compare_sample(w, res, qs, k, with_pred=True, n_invariants=2):
     return want
 
 
+def compare_all_queries(w, res, k, chunk=256):
+    """Every query of the batch against the oracle, every output integer; the lists are fetched
+    and compared `chunk` queries at a time (a chunk of config 2 is about 1.5 GB of lists)."""
+    off = res.offsets()
+    trav = res.traversed().cpu().numpy()
+    Q = w.num_queries
+    for q0 in range(0, Q, chunk):
+        q1 = min(Q, q0 + chunk)
+        qs = np.arange(q0, q1)
+        so, sd, sm = sub_batch(w, qs)
+        t0 = time.time()
+        ro, ent_o, hop_o, pred_o, trav_o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, sm)
+        t1 = time.time()
+        assert np.array_equal(off[q0:q1 + 1] - off[q0], ro), f"queries {q0}..{q1}: reached counts"
+        ent, hop, pred = res.fetch(q0, q1)
+        assert np.array_equal(ent.cpu().numpy(), ent_o), f"queries {q0}..{q1}: entities"
+        assert np.array_equal(hop.cpu().numpy(), hop_o), f"queries {q0}..{q1}: hops"
+        assert np.array_equal(pred.cpu().numpy(), pred_o), f"queries {q0}..{q1}: predecessor edges"
+        assert np.array_equal(trav[q0:q1], trav_o), f"queries {q0}..{q1}: traversed"
+        del ent, hop, pred, ent_o, hop_o, pred_o
+        log(f"queries {q0}..{q1}: oracle {t1 - t0:.1f}s, {int(ro[-1])} pairs equal")
+
+
 def test_config2_full_size():
     m = lkg()
     w = kggen.config2()
     log("generated", w.manifest)
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
     res = g.khop(w.seed_off, w.seeds, w.k)
+    compare_all_queries(w, res, w.k)
     qs = sampled_queries(w.num_queries, 24, 2, np.diff(res.offsets()))
-    compare_sample(w, res, qs, w.k)
-    # invariants on queries the oracle did not see
+    # the single-query fetch path (a sub-range of the lists) on a sample, and the invariants
+    compare_sample(w, res, qs[:4], w.k)
     others = [int(q) for q in sampled_queries(w.num_queries, 40, 3) if q not in set(qs.tolist())][:3]
     off = res.offsets()
     for q in others:
@@ -183,6 +228,8 @@ def test_config3_full_size_masks_and_paths(k):
     log("generated", w.name, "k", k)
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
     res = g.khop(w.seed_off, w.seeds, k, w.rel_mask)
+    if k == 3:
+        compare_all_queries(w, res, k)
     qs = sampled_queries(w.num_queries, 12, 10 + k, np.diff(res.offsets()))
     want = compare_sample(w, res, qs, k)
     # up to 16 shortest paths for a seeded sample of 4,096 reached (query, entity) pairs
@@ -198,8 +245,8 @@ def test_config3_full_size_masks_and_paths(k):
     g.close()
 
 
-@pytest.mark.skipif(4 not in FULL, reason="set LOGOSKG_FULLSIZE=4 (300 M triples; minutes of generation)")
 def test_config4_full_size():
+    require_host_memory(4)
     m = lkg()
     t0 = time.time()
     w = kggen.config4()
@@ -221,8 +268,8 @@ def test_config4_full_size():
     g.close()
 
 
-@pytest.mark.skipif(5 not in FULL, reason="set LOGOSKG_FULLSIZE=5 (1 G triples; ~100 GB of host memory)")
 def test_config5_full_size_sharded():
+    require_host_memory(5)
     m = lkg()
     t0 = time.time()
     w = kggen.config5()

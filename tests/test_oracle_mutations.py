@@ -96,3 +96,33 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
             caught = True
             break
     assert caught, f"no pin noticed the planted mistake '{name}'"
+
+
+# ---------------------------------------------------------------- Sec. 3.4 helpers (plain Python)
+PARTITION_MUTATIONS = {
+    "shard_order_flipped": ("if h % 2 == 0:", "if h % 2 == 1:"),
+    "shard_order_never_reversed": ("if h % 2 == 0:", "if False:"),
+    "rows_without_triples_routed": ("front = front[deg[front] > 0]", "front = front[deg[front] >= 0]"),
+    "frontier_from_the_wrong_level": ("front = np.unique(entity[hop == h - 1])", "front = np.unique(entity[hop == h])"),
+    "lru_evicts_most_recent": ("cache.popitem(last=False)", "cache.popitem(last=True)"),
+    "lru_hit_does_not_refresh": ("            cache.move_to_end(a)\n", ""),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PARTITION_MUTATIONS))
+def test_planted_mistake_in_partition_helpers_is_caught(name):
+    import types
+    old, new = PARTITION_MUTATIONS[name]
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "partition.py")).read()
+    assert src.count(old) == 1, "mutation site vanished"
+    mod = types.ModuleType("partition_mutant")
+    exec(compile(src.replace(old, new), "partition_mutant.py", "exec"), mod.__dict__)
+    caught = False
+    try:
+        seq = pins.shard_access_trace(mod)
+        assert seq == [0, 2, 3, 1, 0, 1]
+        assert mod.lru_counts(seq, 2) == (5, 3, 1)
+        assert mod.lru_counts([0, 1, 0, 2, 0, 3], 2) == (4, 2, 2)
+    except (AssertionError, IndexError):
+        caught = True
+    assert caught, f"no pin noticed the planted mistake '{name}'"

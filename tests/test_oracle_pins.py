@@ -370,6 +370,41 @@ def test_partition_properties_and_lru_accounting():
         assert l2 - e2 <= cap and l2 >= loads and l2 + h2 == len(seq)
 
 
+def shard_access_trace(part):
+    """Hand-worked trace of Alg. 1's routing step over 4 sub-graphs and 3 hops.
+
+    Entities 0..9; subjects (with a triple) are 0,1,2,3,4,5,7; entities 6, 8, 9 are no subject.
+    Map P:     e: 0  1  2  3  4  5  6  7  8  9
+               P: 2  3  1  1  0  0 -1  3 -1 -1
+    Batch result (all queries together): level 0 = {0, 5}, level 1 = {1, 2, 7}, level 2 = {3, 4, 8},
+    level 3 = {9}.
+      hop 1 expands level 0: sub-graphs {P[0], P[5]} = {2, 0}, odd hop -> ascending:   0, 2
+      hop 2 expands level 1: {P[1], P[2], P[7]} = {3, 1},       even hop -> descending: 3, 1
+      hop 3 expands level 2: {P[3], P[4]} = {1, 0} (8 is no subject), odd -> ascending: 0, 1
+    """
+    P = np.array([2, 3, 1, 1, 0, 0, -1, 3, -1, -1], dtype=np.int32)
+    subj = np.array([0, 1, 2, 3, 4, 5, 7, 0, 5], dtype=np.int32)
+    entity = np.array([0, 5, 1, 2, 7, 3, 4, 8, 9, 0, 2], dtype=np.int32)   # two queries' lists, concatenated
+    hop = np.array([0, 0, 1, 1, 1, 2, 2, 2, 3, 0, 1], dtype=np.uint8)
+    return part.shard_accesses(P, subj, 10, 3, entity, hop)
+
+
+def test_shard_visit_order_hand_trace():
+    from oracle import partition as part
+    seq = shard_access_trace(part)
+    assert seq == [0, 2, 3, 1, 0, 1]
+    # the cache counters that follow from it with two slots: 0 L, 2 L, 3 L (evicts 0), 1 L (evicts 2),
+    # 0 L (evicts 3), 1 hit
+    assert part.lru_counts(seq, 2) == (5, 3, 1)
+    # with one slot nothing is ever hit; with four slots every sub-graph is loaded once
+    assert part.lru_counts(seq, 1) == (6, 5, 0)
+    assert part.lru_counts(seq, 4) == (4, 0, 2)
+    # fewer hops: a prefix of the same trace; an empty frontier ends it
+    P = np.array([0, 1], dtype=np.int32)
+    assert part.shard_accesses(P, np.array([0], dtype=np.int32), 2, 3, np.array([0, 1], dtype=np.int32),
+                               np.array([0, 1], dtype=np.uint8)) == [0]
+
+
 def test_query_schedule_groups_queries_by_the_subgraphs_of_their_seeds():
     from oracle import partition as part
     # hand example: P maps entities 0..7 to shards; entity 6 is no subject

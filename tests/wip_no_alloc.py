@@ -1,0 +1,64 @@
+"""logoskg_paths_static: the shortest-path listing for callers that cannot allocate device
+memory.  Its output must equal logoskg_paths' (and the oracle's) bit for bit, on two calls in a
+row of which the second is smaller (the static stacks keep the first call's contents), and sizes
+beyond the static array are refused."""
+import numpy as np
+import pytest
+
+import kggen
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def test_static_path_listing_equals_the_pooled_one():
+    import torch
+    import paper_2604_18913_amd as m
+    w = kggen.config3(0.004, k=4)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=64)
+    res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
+    dev = g.device
+    for n_pairs, seed in ((6000, 1), (700, 2)):       # the second call is the smaller one
+        pq, pt = kggen.sample_reached_pairs(seed, want[0], want[1], n_pairs)
+        # a few pairs that are not reached, and the same pair twice
+        pq = np.concatenate([pq, pq[:3], [0, 1]]).astype(np.int32)
+        pt = np.concatenate([pt, pt[:3], [w.num_entities - 1, w.num_entities - 2]]).astype(np.int32)
+        q_d = torch.from_numpy(pq).to(dev)
+        t_d = torch.from_numpy(pt).to(dev)
+        for max_paths in (16, 3):
+            cnt_ref, edges_ref = g.paths(res, q_d, t_d, max_paths)
+            cnt = torch.full((len(pq),), -7, dtype=torch.int32, device=dev)
+            edges = torch.full((len(pq), max_paths, w.k), -7, dtype=torch.int32, device=dev)
+            g.paths_static(res, q_d, t_d, cnt, edges, max_paths)
+            torch.cuda.synchronize()
+            assert torch.equal(cnt, cnt_ref), (n_pairs, max_paths)
+            assert torch.equal(edges, edges_ref), (n_pairs, max_paths)
+            cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, pq, pt,
+                                          max_paths, w.rel_mask)
+            assert np.array_equal(cnt.cpu().numpy(), cnt_o)
+            assert np.array_equal(edges.cpu().numpy(), edges_o)
+    # beyond the static array: refused, nothing launched, the buffers stay as they were
+    too_many = (1 << 20) // w.k + 1
+    q_d = torch.zeros(too_many, dtype=torch.int32, device=dev)
+    cnt = torch.full((too_many,), -7, dtype=torch.int32, device=dev)
+    edges = torch.full((too_many, 1, w.k), -7, dtype=torch.int32, device=dev)
+    with pytest.raises(m.LogosKGError) as err:
+        g.paths_static(res, q_d, q_d, cnt, edges, 1)
+    assert err.value.status == 4 and "LOGOSKG_STATIC_PATH_SLOTS" in str(err.value)
+    torch.cuda.synchronize()
+    assert int(cnt.max()) == -7 and int(cnt.min()) == -7
+    # the largest size that fits is accepted
+    n_fit = (1 << 20) // w.k
+    g.paths_static(res, q_d[:n_fit], q_d[:n_fit], cnt[:n_fit], edges[:n_fit], 1)
+    cnt_ref, edges_ref = g.paths(res, q_d[:n_fit], q_d[:n_fit], 1)
+    torch.cuda.synchronize()
+    assert torch.equal(cnt[:n_fit], cnt_ref) and torch.equal(edges[:n_fit], edges_ref)
+    # an empty list is fine and a walk-exact result is refused as by logoskg_paths
+    g.paths_static(res, q_d[:0], q_d[:0], cnt[:0], edges[:0], 1)
+    rw = g.khop(w.seed_off, w.seeds, 2, w.rel_mask, walk_exact=True)
+    with pytest.raises(m.LogosKGError):
+        g.paths_static(rw, q_d[:4], q_d[:4], cnt[:4], edges[:4, :, :2].contiguous(), 1)
+    rw.close()
+    res.close()
+    g.close()
