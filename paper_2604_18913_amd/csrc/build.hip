@@ -297,7 +297,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     if ((st = dev_alloc((void **)&g->fr_tail, (size_t)E * sizeof(int32_t))) != LOGOSKG_OK) return fail(st);
     if ((st = dev_alloc((void **)&g->fr_seg, (size_t)g->fr_seg_cap * sizeof(RowSegment))) != LOGOSKG_OK) return fail(st);
     if ((st = dev_alloc((void **)&g->d_ctr, C_TOTAL * sizeof(unsigned long long))) != LOGOSKG_OK) return fail(st);
-    if (hipHostMalloc((void **)&g->h_ctr, C_TOTAL * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc((void **)&g->h_ctr, (C_TOTAL + 1) * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
         return fail(LOGOSKG_ENOMEM);
     }

@@ -111,7 +111,7 @@ extern const char *const kKernelNames[KK_NUM];
 // words per kernel class: rows, edges, lines, items
 enum {
     C_NTAIL = 0, C_NSEG = 1, C_NROWS = 2, C_FEDGES = 3, C_NACTIVE = 4, C_ERR = 5,
-    C_STATS = 8, C_TOTAL = C_STATS + 4 * KK_NUM
+    C_STATS = 8, C_TOTAL = C_STATS + 4 * KK_NUM  // the pinned host mirror holds one word more
 };
 
 struct Profiler {
@@ -209,6 +209,13 @@ struct logoskg_result {
     uint32_t *super_base = nullptr; // [nsuper][64W]  super tiles (1024 entities) inside their mega tile
     uint32_t *mega_base = nullptr;  // [nmega][64W]   mega tiles (65536 entities)
     long long *d_reached_off = nullptr;  // [64W+1]
+    // active entities (a bit in some level), ascending, and the place of each in that list; the
+    // tiles of the count / list / predecessor kernels are cut from it (resident graphs)
+    int32_t *tile_ent = nullptr;   // [Epad + 64], -1 behind the last id
+    int32_t *cpos = nullptr;       // [Epad], defined for the listed entities
+    uint32_t *act_chunk = nullptr; // per 2,048-entity chunk: listed entities before it; then *d_nact
+    unsigned long long *d_nact = nullptr;
+    long long n_active = -1;       // length of the list (known after the count pass)
     std::vector<int64_t> reached_off;  // host copy [Q+1]
     // the same bookkeeping for one level plane (logoskg_result_level_offsets)
     int level_counted = -1;
@@ -317,6 +324,9 @@ struct FillArgs {
     int32_t E;
     int Q, k, q0, q1, hub_min;
     long long ntiles;
+    const int32_t *tile_ent;  // the tiles' entities (list of active entities) or NULL: tile i = ids 64 i ..
+    const int32_t *cpos;      // entity -> place in tile_ent (garbage for entities not in the list), or NULL
+    long long n_listed;       // length of tile_ent's list
     long long tile_begin, tile_count;  // tiles this predecessor launch covers
     long long plane;   // words per plane
     long long actw;    // uint32 words per active bitmap

@@ -920,7 +920,7 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     void *ptrs[] = {r->visited, r->act, r->allow, r->tile_base,
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
                     r->lvl_mega_base, r->d_level_off, r->trip_ent, r->trip_off,
-                    r->trip_chunk_entry, r->trip_chunk_first};
+                    r->trip_chunk_entry, r->trip_chunk_first, r->tile_ent, r->cpos, r->act_chunk};
     for (void *p : ptrs) g->pool.release(p);
     delete r;
 }

@@ -32,16 +32,100 @@
 
 namespace lkg {
 
+// Tiles.  A tile is 64 entities.  Without a list (tile_ent == NULL) tile i holds the ids
+// 64 i .. 64 i + 63; with the list of a result's active entities (those with a bit in any level,
+// ascending, built by k_active_*) tile i holds entries 64 i .. 64 i + 63 of the list, so that the
+// tiles carry no entity that no query reached (-1 pads the last tile).
+__device__ __forceinline__ long long tile_entity(const int32_t *__restrict__ tile_ent, long long tile, int i,
+                                                 int32_t E) {
+    if (tile_ent) return tile_ent[tile * 64 + i];
+    const long long e = tile * 64 + i;
+    return e < E ? e : -1;
+}
+
 template <int W>
 __device__ __forceinline__ unsigned long long stage_word(unsigned long long (*stage)[W + 1],
-                                                         const unsigned long long *__restrict__ plane_tile,
-                                                         int wave) {
-    // coalesced load of a 64-entity tile of one plane, then lane v takes word `wave` of entity v
-    int t = threadIdx.x;
+                                                         const unsigned long long *__restrict__ plane,
+                                                         const int32_t *__restrict__ tile_ent, long long tile,
+                                                         int32_t E, int wave) {
+    // load of a tile's lines of one plane (W consecutive lanes per line), then lane v takes word
+    // `wave` of the tile's entity v
+    const int t = threadIdx.x;
+    const long long e = tile_entity(tile_ent, tile, t / W, E);
     __syncthreads();
-    stage[t / W][t % W] = plane_tile[t];
+    stage[t / W][t % W] = e >= 0 ? plane[(size_t)e * W + t % W] : 0ull;
     __syncthreads();
     return stage[lane()][wave];
+}
+
+// ---------------------------------------------------------------- list of the active entities
+// act holds one bitmap per level (one bit per entity with a non-zero line); their union marks the
+// entities some query reached.  Chunks of 2,048 entities (64 bitmap words, one wavefront):
+// k_active_count counts a chunk, k_active_scan turns the counts into exclusive offsets and the
+// total, k_active_fill writes the ids (ascending) and every listed entity's position.
+constexpr int kActChunkWords = 64;
+
+__device__ __forceinline__ uint32_t active_word(const uint32_t *__restrict__ act, long long actw, int levels,
+                                                long long word) {
+    uint32_t u = 0;
+    if (word < actw)
+        for (int h = 0; h < levels; ++h) u |= act[(size_t)h * actw + word];
+    return u;
+}
+
+__global__ void __launch_bounds__(256)
+k_active_count(const uint32_t *__restrict__ act, long long actw, int levels, long long nchunks, uint32_t *chunk_cnt) {
+    const long long chunk = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (chunk >= nchunks) return;
+    const uint32_t u = active_word(act, actw, levels, chunk * kActChunkWords + lane());
+    const long long c = wave_sum((long long)__popc(u));
+    if (lane() == 0) chunk_cnt[chunk] = (uint32_t)c;
+}
+
+// one block: exclusive prefix over the chunk counts (in place), total to *n_active, and -1 in the
+// 64 list entries behind the last id
+__global__ void __launch_bounds__(1024)
+k_active_scan(long long nchunks, uint32_t *chunk_cnt, unsigned long long *n_active, int32_t *tile_ent) {
+    __shared__ unsigned long long part[2][1024];
+    const int t = threadIdx.x;
+    const long long per = (nchunks + 1023) / 1024, lo = (long long)t * per, hi = min(nchunks, lo + per);
+    unsigned long long sum = 0;
+    for (long long i = lo; i < hi; ++i) sum += chunk_cnt[i];
+    int cur = 0;
+    part[0][t] = sum;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {
+        unsigned long long x = part[cur][t];
+        if (t >= d) x += part[cur][t - d];
+        part[cur ^ 1][t] = x;
+        cur ^= 1;
+        __syncthreads();
+    }
+    unsigned long long run = part[cur][t] - sum;
+    for (long long i = lo; i < hi; ++i) {
+        const uint32_t c = chunk_cnt[i];
+        chunk_cnt[i] = (uint32_t)run;
+        run += c;
+    }
+    const unsigned long long total = part[cur][1023];
+    if (t == 0) *n_active = total;
+    if (t < 64) tile_ent[total + t] = -1;
+}
+
+__global__ void __launch_bounds__(256)
+k_active_fill(const uint32_t *__restrict__ act, long long actw, int levels, long long nchunks,
+              const uint32_t *__restrict__ chunk_base, int32_t *tile_ent, int32_t *cpos) {
+    const long long chunk = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (chunk >= nchunks) return;
+    const long long word = chunk * kActChunkWords + lane();
+    uint32_t u = active_word(act, actw, levels, word);
+    int total;
+    long long at = (long long)chunk_base[chunk] + wave_excl_scan(__popc(u), total);
+    for (; u; u &= u - 1, ++at) {
+        const int32_t e = (int32_t)(word * 32 + (__ffs((int)u) - 1));
+        tile_ent[at] = e;
+        cpos[e] = (int32_t)at;
+    }
 }
 
 // blocks are dealt round-robin to the 8 XCDs; give every XCD a contiguous run of
@@ -56,18 +140,22 @@ __device__ __forceinline__ long long xcd_contiguous(long long block, long long n
 // One block per super tile, one wavefront per word: tile_base[tile][q] = entities
 // query q reached in the earlier tiles of the super tile, super_sum[st][q] = in
 // the whole super tile.
+// With a list the number of tiles follows from *n_active (the grid covers the largest possible
+// number of super tiles; those behind the list write zero sums).
 template <int W>
-__global__ void k_count(const unsigned long long *__restrict__ visited, long long ntiles, uint16_t *tile_base,
-                        uint32_t *super_sum) {
+__global__ void k_count(const unsigned long long *__restrict__ visited, long long ntiles, int32_t E,
+                        const int32_t *__restrict__ tile_ent, const unsigned long long *__restrict__ n_active,
+                        uint16_t *tile_base, uint32_t *super_sum) {
     constexpr int Qp = 64 * W;
     __shared__ unsigned long long stage[64][W + 1];
     const long long st = blockIdx.x;
     const int wave = threadIdx.x >> 6;
+    if (tile_ent) ntiles = (long long)((*n_active + 63) / 64);
     int run = 0;
     for (int i = 0; i < kSuperTiles; ++i) {
         long long tile = st * kSuperTiles + i;
         if (tile >= ntiles) break;
-        unsigned long long x = stage_word<W>(stage, visited + (size_t)tile * 64 * W, wave);
+        unsigned long long x = stage_word<W>(stage, visited, tile_ent, tile, E, wave);
         tile_base[(size_t)tile * Qp + threadIdx.x] = (uint16_t)run;
         int mine = 0;
         if (wave_any(x != 0)) mine = __popcll(transpose64(x));  // lane qq: entities of the tile query qq reached
@@ -151,7 +239,12 @@ __global__ void __launch_bounds__(64 * W) k_lists(FillArgs a) {
     __shared__ unsigned long long stage[64][W + 1];
     __shared__ uint16_t s_ent[W][TILES * 64];
     __shared__ uint8_t s_hop[NB > 0 ? W : 1][TILES * 64];
+    __shared__ int32_t blk_ent[TILES * 64];  // entity ids of the block's tiles
     const long long first_tile = (long long)blockIdx.x * TILES;
+    for (int i = threadIdx.x; i < TILES * 64; i += 64 * W) {
+        const long long tile = first_tile + i / 64;
+        blk_ent[i] = tile < a.ntiles ? (int32_t)tile_entity(a.tile_ent, tile, i % 64, a.E) : -1;
+    }
     const long long st = first_tile / kSuperTiles;
     const int wave = threadIdx.x >> 6, v = lane();
     unsigned long long visw[TILES];
@@ -163,11 +256,11 @@ __global__ void __launch_bounds__(64 * W) k_lists(FillArgs a) {
 #pragma unroll
         for (int b = 0; b < NBX; ++b) hb[b][i] = 0;
         if (tile < a.ntiles) {  // block-uniform
-            visw[i] = stage_word<W>(stage, a.visited + (size_t)tile * 64 * W, wave);
+            visw[i] = stage_word<W>(stage, a.visited, a.tile_ent, tile, a.E, wave);
             if constexpr (NB > 0)
                 for (int h = 1; h <= a.k; ++h) {  // hop number of each bit, bit-sliced over NB words
                     unsigned long long x =
-                        stage_word<W>(stage, a.levels + (size_t)h * a.plane + (size_t)tile * 64 * W, wave);
+                        stage_word<W>(stage, a.levels + (size_t)h * a.plane, a.tile_ent, tile, a.E, wave);
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
                         if ((h >> b) & 1) hb[b][i] |= x;
@@ -210,9 +303,8 @@ __global__ void __launch_bounds__(64 * W) k_lists(FillArgs a) {
         }
         __builtin_amdgcn_wave_barrier();
         const long long base = (long long)shfl64((unsigned long long)mybase, qq);
-        const int e0 = (int)(first_tile * 64);
         for (int p = v; p < cnt; p += 64) {
-            a.entity[base + p] = e0 + ent[p];
+            a.entity[base + p] = blk_ent[ent[p]];
             if constexpr (NB > 0) a.hop[base + p] = hp[p];
         }
         __builtin_amdgcn_wave_barrier();
@@ -287,11 +379,17 @@ __device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool c
 template <int W>
 __device__ __forceinline__ void row_slots(const FillArgs &a, int ev, int w_first, int w_step, long long *slot) {
     constexpr int Qp = 64 * W;
-    const long long tile = ev >> 6;
-    const int vi = ev & 63, v = lane();
+    long long at = ev;  // place of the entity in the tiles
+    if (a.cpos) {       // an entity no query reached is not listed: it needs no positions
+        at = a.cpos[ev];
+        if (at < 0 || at >= a.n_listed || a.tile_ent[at] != ev) return;
+    }
+    const long long tile = at >> 6;
+    const int vi = (int)(at & 63), v = lane();
     const unsigned long long below = (1ull << vi) - 1ull;
+    const long long ent_v = tile_entity(a.tile_ent, tile, v, a.E);
     for (int w = w_first; w < W; w += w_step) {  // lane v = entity v of the tile
-        unsigned long long x = a.visited[((size_t)tile * 64 + v) * W + w] & range_bits(a.q0, a.q1, w);
+        unsigned long long x = ent_v >= 0 ? a.visited[(size_t)ent_v * W + w] & range_bits(a.q0, a.q1, w) : 0ull;
         int rank = 0;
         if (shfl64(x, vi) != 0ull)  // only queries that reached this entity matter
             rank = __popcll(transpose64(x) & below);
@@ -398,8 +496,8 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
         base[q] = b;
     }
     const unsigned long long range_w = range_bits(a.q0, a.q1, wave);
-    unsigned long long visw = stage_word<W>(stage, a.visited + (size_t)tile * 64 * W, wave) & range_w;
-    unsigned long long seedw = stage_word<W>(stage, a.levels + (size_t)tile * 64 * W, wave) & range_w;
+    unsigned long long visw = stage_word<W>(stage, a.visited, a.tile_ent, tile, a.E, wave) & range_w;
+    unsigned long long seedw = stage_word<W>(stage, a.levels, a.tile_ent, tile, a.E, wave) & range_w;
     unsigned long long mine = 0;
     if (wave_any(visw != 0)) mine = transpose64(visw);  // lane qq: mask of tile entities query qq reached
     mT[t] = mine;
@@ -413,9 +511,9 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
             a.pred[slot(wave * 64 + (__ffsll((long long)m) - 1), below_v)] = -1;
     }
     const int vi = t / W, g0 = v & ~(W - 1);
-    const long long ev = tile * 64 + vi;
+    const long long ev = tile_entity(a.tile_ent, tile, vi, a.E);
     uint32_t lo = 0, hi = 0;
-    if (ev < a.E) {
+    if (ev >= 0) {
         lo = a.in_off[ev];
         hi = a.in_off[ev + 1];
     }
@@ -489,235 +587,217 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     }
 }
 
-// Predecessor kernel for 16-word planes.  One block = a macro tile of 256
-// entities (4 tiles) x 4 words (256 queries); one 4-lane group per entity, lane
-// lw owns word 4*slab + lw.  A (query, entity) pair found during the row walk is
-// not stored to its scattered list position: a 16-bit code (entity, position in
-// its object row) goes to the block's staging buffer at the pair's place in the
-// query's run, and afterwards every query's run (up to 256 consecutive list
-// entries) leaves with full-width stores, which keeps the lines that reach HBM
-// whole.  A code is (hop << 13) | (entity << 5) | position, so k <= 6 (0xFFFF
-// marks a place nothing was staged for).  Hop 0 = seed (-1).  Rows of more than
-// 32 entries belong to the row kernels: the pairs of such an entity are staged
-// with their hop only, and their predecessor is either fetched from row_pred
-// (rows below hub_min, whose kernel ran before on the same stream) or left to
-// the block-per-row kernel, which writes the lists itself.  With a.fuse_lists
-// the run's entity ids and hop numbers are written as well, which replaces the
-// list kernel.  When a macro tile has more pairs than the staging buffer
-// holds, its words are processed in several passes.
-constexpr int kMtCap = 16384;   // staged codes per pass (>= 256 entities x 64 queries)
-constexpr int kMtEids = 3072;   // staged edge ids of the short rows
-constexpr unsigned kCodeNone = 0xFFFFu;
-constexpr int kMtMaxK = 6;       // hop numbers 0..6 fit the code's three bits beside kCodeNone
+// Predecessor kernel for 16-word planes, bit-sliced.  One block = one tile of 64 entities x all
+// 16 words (1,024 queries).
+//
+// Walk phase: a 16-lane group per entity, lane lw owns word lw of the entity's lines.  The group
+// walks the entity's object row (<= 32 entries) in edge-id order with a mask of unresolved
+// queries per hop level; a candidate's line resolves the queries in (line & mask), all at once.
+// What a (query, entity) pair needs later - its hop number and the position of its predecessor
+// in the row - is kept bit-sliced: NB words H[b] hold bit b of (hop + 1) of each of the lane's 64
+// queries (so H[0] | H[1] | .. is the visited word) and five words J[b] hold bit b of the row
+// position.  A resolving line costs a fixed fifteen instructions for up to 64 pairs, whatever
+// the number of set bits.  The planes then change owner through LDS.
+//
+// Write phase: wavefront w owns word w, lane v the entity v of the tile, with its NB + 5 plane
+// words in registers.  For every query of the word that reached the tile (a scalar loop) the
+// lanes test their bit, a ballot ranks them inside the query's run, the eight plane bits give hop
+// and row position, and the lanes store (entity, hop, predecessor edge) at consecutive list
+// positions: every lane issues the same instructions, and a store instruction covers one
+// contiguous piece of a list.  Rows of more than 32 entries belong to the row kernels as before:
+// such an entity's predecessor comes from row_pred (rows below hub_min, whose kernel ran before
+// on the same stream) or is left to the block-per-row kernel.
+constexpr int kSlicedMaxK = 6;    // hop + 1 <= 7 fits three bits
+constexpr int kSlicedEidStride = 33;  // edge ids staged per entity (32 + 1: lanes = entities read it without bank conflicts)
 
-// Two blocks per CU need 8 wavefronts per SIMD; measured, the second block is only co-resident
-// while a wavefront asks for at most 80 scalar registers (SQ_WAVE_CYCLES / SQ_BUSY_CYCLES halves
-// above that), hence the cap: spilling a few scalars costs far less than half the occupancy.
-template <bool MASK, bool STATS>
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(72)))
-k_pred_mt(FillArgs a, long long mt_begin, long long mt_count, int slab_first, int slab_count) {
-    constexpr int W = 16, Qp = 1024, G = kPredGroup;
-    __shared__ unsigned long long mT[4][256];  // [tile][query]: tile entities the query reached
-    __shared__ uint32_t pos0[4][256];          // start of the tile's part of the query's staged run
-    __shared__ uint32_t lbase[257];            // start of the query's staged run
-    __shared__ long long base[256];            // list position of the query's run
-    __shared__ union {
-        unsigned long long stage[256][5];
-        uint16_t code[kMtCap];
-    } u;
-    __shared__ int eid_tab[kMtEids + 32];
-    __shared__ uint16_t roff[256];
-    __shared__ uint32_t in_lo[256];
-    __shared__ int long_li[256];
-    __shared__ int wsum[8];
-    __shared__ int short_entries;  // entries of all short rows of the block
-    const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
-    if (L >= mt_count * slab_count) return;
-    const long long mt = mt_begin + L / slab_count;
-    const int slab = slab_first + (int)(L % slab_count);  // slabs without a fetched query are not launched
+__device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) x |= shfl_xor64(x, m);
+    return x;
+}
+
+template <int NB, bool MASK, bool STATS>
+__global__ void __launch_bounds__(1024) k_pred_sliced(FillArgs a) {
+    constexpr int W = 16, Qp = 1024, G = 16, NP = NB + 5;
+    constexpr int HMAX = (1 << NB) - 2;  // largest hop number the NB bits of (hop + 1) can hold
+    // plane words of entity e sit at [e][w ^ (e & 15)]: the walk phase writes an entity's sixteen
+    // words side by side, the write phase reads one word of 64 entities, both without bank conflicts
+    __shared__ unsigned long long sm[NP][64][16];
+    __shared__ int eid_tab[64 * kSlicedEidStride];  // edge ids of the tile's short rows, by row position
+    const long long tile_rel = xcd_contiguous(blockIdx.x, gridDim.x);
+    if (tile_rel >= a.tile_count) return;  // block-uniform
+    const long long tile = a.tile_begin + tile_rel;
     const int t = threadIdx.x, wave = t >> 6, v = lane();
-    const int vi = t / G, lw = t % G, wq = G * slab + lw, g0 = v & ~(G - 1);
-    const int tt = vi >> 6;
-    const long long tile0 = mt * kPredTiles;
-    const long long ev = tile0 * 64 + vi;
-    const bool valid = tile0 + tt < a.tile_begin + a.tile_count;
-    const unsigned long long range_w = range_bits(a.q0, a.q1, wq);
-    unsigned long long visw = 0, seedw = 0;
+    const int vi = t >> 4, lw = t & 15, g0 = v & ~(G - 1);
+    const long long ev = tile_entity(a.tile_ent, tile, vi, a.E);
+    const unsigned long long range_w = range_bits(a.q0, a.q1, lw);
+    // ---- requested now, used in the write phase (thread t = query t there, lane v = entity v)
+    long long pos = 0;
+    if (t >= a.q0 && t < a.q1) pos = super_start(a, tile / kSuperTiles, Qp, t) + a.tile_base[(size_t)tile * Qp + t];
+    const long long ew = tile_entity(a.tile_ent, tile, v, a.E);
+    uint32_t wlo = 0, whi = 0;
+    if (ew >= 0) {
+        wlo = a.in_off[ew];
+        whi = a.in_off[ew + 1];
+    }
+    // ---- walk phase
+    unsigned long long visw = 0, lv0 = 0;
     uint32_t lo = 0, hi = 0;
-    if (valid) {
-        visw = a.visited[(size_t)ev * W + wq] & range_w;
-        seedw = a.levels[(size_t)ev * W + wq] & range_w;
-        if (ev < a.E) {
-            lo = a.in_off[ev];
-            hi = a.in_off[ev + 1];
-        }
+    if (ev >= 0) {
+        visw = a.visited[(size_t)ev * W + lw] & range_w;
+        lv0 = a.levels[(size_t)ev * W + lw] & range_w;
+        lo = a.in_off[ev];
+        hi = a.in_off[ev + 1];
     }
     const uint32_t deg = hi - lo;
     const bool shortrow = deg > 0 && deg <= (uint32_t)kTailMaxDegree;
-    u.stage[vi][lw] = visw;
-    const bool longrow = deg > (uint32_t)kTailMaxDegree;
-    // requested now, used after the barriers below: the list position of query t's run, and the
-    // level words of the first hops
-    long long early_base = 0;
-    if (t < 256 && tile0 < a.tile_begin + a.tile_count)
-        early_base = super_start(a, tile0 / kSuperTiles, Qp, slab * 256 + t) + a.tile_base[(size_t)tile0 * Qp + slab * 256 + t];
-    unsigned long long lvl_pre[3] = {0, 0, 0};
-    if (visw & ~seedw)
+    unsigned long long H[NB], J[5];
+    H[0] = lv0;  // hop 0: hop + 1 = 1
 #pragma unroll
-        for (int h = 1; h <= 3; ++h)
-            if (h <= a.k) lvl_pre[h - 1] = a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
-    if (lw == 0) {
-        roff[vi] = shortrow ? (uint16_t)deg : (uint16_t)0;
-        in_lo[vi] = lo;
-        // -1: short row (edge ids staged here), >= 0: line of row_pred, -2: predecessor written elsewhere
-        int li = -1;
-        if (longrow) li = (a.row_pred && deg < (uint32_t)a.hub_min) ? (int)(a.long_index[ev] - a.row_base) : -2;
-        long_li[vi] = li;
-    }
-    if (!__syncthreads_or(visw != 0)) return;  // none of the slab's queries reached the macro tile
-    {   // wave = (tile, word): lane qq gets the mask of tile entities query qq reached
-        const int wt = wave >> 2, wj = wave & 3;
-        unsigned long long x = u.stage[wt * 64 + v][wj], m = 0;
-        if (wave_any(x != 0)) m = transpose64(x);
-        mT[wt][wj * 64 + v] = m;
-    }
-    __syncthreads();
-    // staged layout: query-major, inside a query tile by tile; offsets into the edge-id table
-    int c0 = 0, c1 = 0, c2 = 0, tot = 0, ex = 0, dx = 0, my_deg = 0;
-    if (t < 256) {
-        my_deg = roff[t];
-        c0 = __popcll(mT[0][t]);
-        c1 = __popcll(mT[1][t]);
-        c2 = __popcll(mT[2][t]);
-        tot = c0 + c1 + c2 + __popcll(mT[3][t]);
-        int wtot, dtot;
-        ex = wave_excl_scan(tot, wtot);
-        dx = wave_excl_scan(my_deg, dtot);
-        if (v == 0) {
-            wsum[wave] = wtot;
-            wsum[4 + wave] = dtot;
-        }
-    }
-    __syncthreads();
-    if (t < 256) {
-        for (int w2 = 0; w2 < wave; ++w2) {
-            ex += wsum[w2];
-            dx += wsum[4 + w2];
-        }
-        lbase[t] = (uint32_t)ex;
-        if (t == 255) lbase[256] = (uint32_t)(ex + tot);
-        pos0[0][t] = (uint32_t)ex;
-        pos0[1][t] = (uint32_t)(ex + c0);
-        pos0[2][t] = (uint32_t)(ex + c0 + c1);
-        pos0[3][t] = (uint32_t)(ex + c0 + c1 + c2);
-        roff[t] = (uint16_t)dx;
-        if (t == 255) short_entries = dx + my_deg;
-        base[t] = tot > 0 ? early_base : 0;
-    }
-    __syncthreads();
-    const int my_roff = roff[vi];
-    const bool eids_staged = short_entries <= kMtEids;  // block-uniform: the table holds every short row
-    const bool reached = group_any<G>((visw & ~seedw) != 0);  // by an edge, for some query of the slab
-    if (shortrow && eids_staged && reached)
-        for (uint32_t j = lw; j < deg; j += G) eid_tab[my_roff + j] = a.in_eid[lo + j];
-    const unsigned long long below = (1ull << (vi & 63)) - 1ull;
+    for (int b = 1; b < NB; ++b) H[b] = 0;
+#pragma unroll
+    for (int b = 0; b < 5; ++b) J[b] = 0;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
-    for (int ja = 0; ja < 4;) {  // pass over the words [ja, jb)
-        int jb = ja + 1;
-        while (jb < 4 && lbase[64 * (jb + 1)] - lbase[64 * ja] <= (uint32_t)kMtCap) ++jb;
-        const uint32_t goff = lbase[64 * ja], gcount = lbase[64 * jb] - goff;
-        for (uint32_t i = t; i * 4 < gcount; i += 1024)
-            reinterpret_cast<uint2 *>(u.code)[i] = make_uint2(kCodeNone * 0x10001u, kCodeNone * 0x10001u);
-        __syncthreads();
-        const bool mine = lw >= ja && lw < jb;
-        // the two 32-bit halves of a mask are walked one after the other: 32-bit bit tricks are
-        // half the instructions of their 64-bit forms
-        const uint32_t *const my_pos0 = &pos0[tt][lw * 64];
-        const unsigned long long *const my_mT = &mT[tt][lw * 64];
-        auto emit = [&](unsigned long long bits, unsigned code) {
+    if (group_any<G>((visw & ~lv0) != 0)) {  // some query of the range reached the entity by an edge
+        if (shortrow) {
+            if (lw < deg) eid_tab[vi * kSlicedEidStride + lw] = a.in_eid[lo + lw];
+            if (lw + G < deg) eid_tab[vi * kSlicedEidStride + lw + G] = a.in_eid[lo + lw + G];
+        }
+        // the level words of the first hops are requested together
+        constexpr int PRE = HMAX < 3 ? HMAX : 3;
+        unsigned long long pre[PRE];
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
-                for (uint32_t m = (uint32_t)(bits >> (32 * half)); m; m &= m - 1) {
-                    const int b = 32 * half + __ffs((int)m) - 1;
-                    u.code[my_pos0[b] + __popcll(my_mT[b] & below) - goff] = (uint16_t)code;
+        for (int h = 1; h <= PRE; ++h)
+            pre[h - 1] = h <= a.k ? a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_w : 0ull;
+#pragma unroll
+        for (int h = 1; h <= HMAX; ++h) {
+            if (h > a.k) break;
+            unsigned long long rem;
+            if (h <= PRE) rem = pre[h - 1];
+            else rem = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_w;
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                if (((h + 1) >> b) & 1) H[b] |= rem;
+            if (!shortrow || !group_any<G>(rem != 0)) continue;
+            const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
+            const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+            if (STATS && lw == 0) ++n_rows;
+            for (uint32_t j0 = lo; j0 < hi; j0 += G) {
+                const uint32_t j = j0 + lw;
+                int s = 0;
+                bool cand = false;
+                if (j < hi) {
+                    s = a.in_sub[j];
+                    cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
                 }
-        };
-        if (mine && seedw) emit(seedw, (unsigned)vi << 5);
-        if (mine && longrow && (visw & ~seedw))
-            for (int h = 1; h <= a.k; ++h) {
-                unsigned long long lv = h <= 3 ? lvl_pre[h - 1] : a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
-                if (lv) emit(lv, ((unsigned)h << 13) | ((unsigned)vi << 5));
-            }
-        if (shortrow && reached)
-            for (int h = 1; h <= a.k; ++h) {
-                unsigned long long rem = !mine ? 0ull : h <= 3 ? lvl_pre[h - 1] : a.levels[(size_t)h * a.plane + (size_t)ev * W + wq] & range_w;
-                if (!group_any<G>(rem != 0)) continue;
-                const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
-                const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
-                if (STATS && lw == 0) ++n_rows;
-                for (uint32_t j0 = lo; j0 < hi; j0 += G) {
-                    uint32_t j = j0 + lw;
-                    int s = 0;
-                    bool cand = false;
-                    if (j < hi) {
-                        s = a.in_sub[j];
-                        cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
-                    }
-                    unsigned gm = (unsigned)((__ballot(cand) >> g0) & ((1u << G) - 1u));
-                    if (STATS && lw == 0) {
-                        n_edges += min((uint32_t)G, hi - j0);
-                        n_lines += __popc(gm);
-                    }
-                    while (gm) {  // two candidate lines in flight, resolved in edge order
-                        int d0 = __ffs((int)gm) - 1;
+                unsigned gm = (unsigned)((__ballot(cand) >> g0) & 0xFFFFu);
+                if (STATS && lw == 0) {
+                    n_edges += min((uint32_t)G, hi - j0);
+                    n_lines += __popc(gm);
+                }
+                while (gm) {  // two candidate lines in flight, resolved in edge order
+                    const int d0 = __ffs((int)gm) - 1;
+                    gm &= gm - 1;
+                    int d1 = -1;
+                    if (gm) {
+                        d1 = __ffs((int)gm) - 1;
                         gm &= gm - 1;
-                        int d1 = -1;
-                        if (gm) {
-                            d1 = __ffs((int)gm) - 1;
-                            gm &= gm - 1;
-                        }
-                        int s0 = __shfl(s, g0 + d0), s1 = __shfl(s, g0 + (d1 < 0 ? d0 : d1));
-                        unsigned long long l0 = prev[(size_t)s0 * W + wq], l1 = 0;
-                        if (d1 >= 0) l1 = prev[(size_t)s1 * W + wq];
-                        if (MASK) {
-                            l0 &= a.allow[(size_t)a.in_rel[j0 + d0] * W + wq];
-                            if (d1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + d1] * W + wq];
-                        }
-                        unsigned long long hit0 = l0 & rem, hit1 = l1 & rem & ~l0;
-                        rem &= ~(l0 | l1);
-                        if (hit0) emit(hit0, ((unsigned)h << 13) | ((unsigned)vi << 5) | (j0 + d0 - lo));
-                        if (hit1) emit(hit1, ((unsigned)h << 13) | ((unsigned)vi << 5) | (j0 + d1 - lo));
-                        if (!group_any<G>(rem != 0)) break;
+                    }
+                    const int s0 = __shfl(s, g0 + d0), s1 = __shfl(s, g0 + (d1 < 0 ? d0 : d1));
+                    unsigned long long l0 = prev[(size_t)s0 * W + lw], l1 = 0;
+                    if (d1 >= 0) l1 = prev[(size_t)s1 * W + lw];
+                    if (MASK) {
+                        l0 &= a.allow[(size_t)a.in_rel[j0 + d0] * W + lw];
+                        if (d1 >= 0) l1 &= a.allow[(size_t)a.in_rel[j0 + d1] * W + lw];
+                    }
+                    const unsigned long long hit0 = l0 & rem, hit1 = l1 & rem & ~l0;
+                    rem &= ~(l0 | l1);
+                    const int p0 = (int)(j0 - lo) + d0, p1 = (int)(j0 - lo) + (d1 < 0 ? 0 : d1);
+#pragma unroll
+                    for (int b = 0; b < 5; ++b) {  // all-ones or zero from bit b of the position
+                        const unsigned long long m0 = (unsigned long long)(long long)(-((p0 >> b) & 1));
+                        const unsigned long long m1 = (unsigned long long)(long long)(-((p1 >> b) & 1));
+                        J[b] |= (hit0 & m0) | (hit1 & m1);
                     }
                     if (!group_any<G>(rem != 0)) break;
                 }
+                if (!group_any<G>(rem != 0)) break;
             }
-        __syncthreads();
-        for (int ql = 64 * ja + wave; ql < 64 * jb; ql += 16) {  // one wavefront per query's run
-            const uint32_t src = lbase[ql] - goff, n = lbase[ql + 1] - lbase[ql];
-            const long long dst = base[ql];
-            for (uint32_t i = v; i < n; i += 64) {
-                const unsigned code = u.code[src + i];
-                const bool have = code != kCodeNone;
-                const int e = (code >> 5) & 255, jp = code & 31, hopv = code >> 13, li = long_li[e];
-                int val;
-                if (eids_staged) val = eid_tab[min((int)roff[e] + jp, kMtEids + 31)];  // unused for long rows
-                else val = have && li == -1 && hopv != 0 ? a.in_eid[in_lo[e] + jp] : -1;
-                if (have && li >= 0 && hopv != 0) val = a.row_pred[(size_t)li * Qp + slab * 256 + ql];
-                if (hopv == 0) val = -1;
-                if (have) {
-                    if (a.fuse_lists) {
-                        a.entity[dst + i] = (int32_t)(tile0 * 64 + e);
-                        if (a.hop) a.hop[dst + i] = (uint8_t)hopv;
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) sm[b][vi][lw ^ (vi & 15)] = H[b];
+#pragma unroll
+    for (int b = 0; b < 5; ++b) sm[NB + b][vi][lw ^ (vi & 15)] = J[b];
+    __syncthreads();
+    // ---- write phase: wavefront = word, lane = entity
+    unsigned long long P[NP];
+#pragma unroll
+    for (int b = 0; b < NP; ++b) P[b] = sm[b][v][wave ^ (v & 15)];
+    unsigned long long vis = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) vis |= P[b];
+    const unsigned long long live = wave_or64(vis);
+    if (live != 0ull) {
+        const uint32_t wdeg = whi - wlo;
+        // where a lane's predecessors come from: the staged edge ids of its own short row (indexed
+        // by the row position), its line of row_pred (indexed by the query), or nowhere (the row
+        // kernels write them, only seeds get their -1 here)
+        const bool longrow = wdeg > (uint32_t)kTailMaxDegree;
+        const bool by_query = longrow && a.row_pred && wdeg < (uint32_t)a.hub_min;
+        const bool elsewhere = longrow && !by_query;
+        const int32_t *src = nullptr;
+        if (by_query) src = a.row_pred + (size_t)(a.long_index[ew] - a.row_base) * Qp + wave * 64;
+        const bool any_by_query = wave_any(by_query);
+        const int *const my_eids = eid_tab + v * kSlicedEidStride;
+        const int ent_id = (int)ew;
+        const uint32_t pos_lo = (uint32_t)(unsigned long long)pos, pos_hi = (uint32_t)((unsigned long long)pos >> 32);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            uint32_t ph[NP];
+#pragma unroll
+            for (int b = 0; b < NP; ++b) ph[b] = (uint32_t)(P[b] >> (32 * half));
+            const uint32_t vis_h = (uint32_t)(vis >> (32 * half));
+            uint32_t rest = __builtin_amdgcn_readfirstlane((uint32_t)(live >> (32 * half)));
+            while (rest) {  // scalar loop over the queries of this half word that reached the tile
+                const int qq = __builtin_ctz(rest);
+                rest &= rest - 1;
+                const bool bit = (vis_h & (1u << qq)) != 0u;
+                const unsigned long long m = __ballot(bit);
+                const unsigned rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                const unsigned long long base =
+                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)pos_hi, 32 * half + qq) << 32) |
+                    (uint32_t)__builtin_amdgcn_readlane((int)pos_lo, 32 * half + qq);
+                // bits of (hop + 1) and of the row position, most significant first: one bit
+                // extraction and one shift-or each
+                unsigned hc = 0, jp = 0;
+#pragma unroll
+                for (int b = NB - 1; b >= 0; --b) hc = (hc << 1) | __builtin_amdgcn_ubfe(ph[b], (unsigned)qq, 1u);
+#pragma unroll
+                for (int b = 4; b >= 0; --b) jp = (jp << 1) | __builtin_amdgcn_ubfe(ph[NB + b], (unsigned)qq, 1u);
+                if (bit) {
+                    int32_t *const pe = a.entity + base;
+                    pe[rank] = ent_id;
+                    if (a.hop) {
+                        uint8_t *const ph8 = a.hop + base;
+                        ph8[rank] = (uint8_t)(hc - 1u);
                     }
-                    if (li != -2 || hopv == 0) a.pred[dst + i] = val;
+                    const bool seed = hc == 1u;
+                    int val = my_eids[jp];  // (unused for seeds and long rows)
+                    asm volatile("" : "+v"(val));  // keeps the LDS read apart from the global one below
+                    if (any_by_query) {  // wave-uniform: only then is there a global load in the loop
+                        if (by_query && !seed) val = src[32 * half + qq];
+                    }
+                    if (seed) val = -1;
+                    if (!elsewhere || seed) {
+                        int32_t *const pp = a.pred + base;
+                        pp[rank] = val;
+                    }
                 }
             }
         }
-        __syncthreads();
-        ja = jb;
     }
-    if (STATS && slab == slab_first) {  // work counters on one slab of words
+    if (STATS) {
         n_rows = wave_sum(n_rows);
         n_edges = wave_sum(n_edges);
         n_lines = wave_sum(n_lines);
@@ -852,6 +932,28 @@ __global__ void k_traversed(int32_t E, int Q, int k, long long plane, long long 
     }
 }
 
+// The list of a result's active entities and their positions in it, built once per result.  The
+// tiles of every count / list / predecessor kernel of a resident graph are cut from this list.
+// A sharded graph keeps tiles of consecutive ids: its predecessor pass works on ranges of ids,
+// the ranges its object-sorted triples are streamed in.
+static logoskg_status ensure_active_list(logoskg_result *r, hipStream_t st) {
+    logoskg_graph *g = r->g;
+    if (r->tile_ent || g->num_shards > 1) return LOGOSKG_OK;
+    const long long actw = r->Epad / 32, nchunks = (actw + kActChunkWords - 1) / kActChunkWords;
+    LKG_TRY(g->pool.alloc((void **)&r->tile_ent, ((size_t)r->Epad + 64) * sizeof(int32_t)));
+    LKG_TRY(g->pool.alloc((void **)&r->cpos, (size_t)r->Epad * sizeof(int32_t)));
+    LKG_TRY(g->pool.alloc((void **)&r->act_chunk, ((size_t)nchunks + 2) * sizeof(uint32_t) + 8));
+    r->d_nact = reinterpret_cast<unsigned long long *>(r->act_chunk + (nchunks + 1) / 2 * 2);
+    r->n_active = -1;
+    ProfScope ps(g->prof, KK_SCAN, st);
+    const unsigned nb = (unsigned)((nchunks + 3) / 4);
+    k_active_count<<<dim3(nb), dim3(256), 0, st>>>(r->act, actw, r->k + 1, nchunks, r->act_chunk);
+    k_active_scan<<<dim3(1), dim3(1024), 0, st>>>(nchunks, r->act_chunk, r->d_nact, r->tile_ent);
+    k_active_fill<<<dim3(nb), dim3(256), 0, st>>>(r->act, actw, r->k + 1, nchunks, r->act_chunk, r->tile_ent, r->cpos);
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}
+
 // Per-query counts of the set bits of one plane (visited, or a level) as three nested exclusive
 // prefixes plus the offsets of the query-major lists; the tables are allocated on first use.
 static logoskg_status count_plane(logoskg_result *r, const unsigned long long *plane_bits, uint16_t **tile_base,
@@ -866,15 +968,15 @@ static logoskg_status count_plane(logoskg_result *r, const unsigned long long *p
     if (!*super_base) LKG_TRY(g->pool.alloc((void **)super_base, (size_t)nsuper * Qp * 4));
     if (!*mega_base) LKG_TRY(g->pool.alloc((void **)mega_base, (size_t)nmega * Qp * 4));
     if (!*d_off) LKG_TRY(g->pool.alloc((void **)d_off, (size_t)(Qp + 1) * 8));
+    LKG_TRY(ensure_active_list(r, st));
     {
         ProfScope ps(g->prof, KK_COUNT, st);
         dim3 grid((unsigned)nsuper), block(Qp);
         switch (W) {
-            case 1: k_count<1><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
-            case 4: k_count<4><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
-            default: k_count<16><<<grid, block, 0, st>>>(plane_bits, ntiles, *tile_base, *super_base); break;
+            case 1: k_count<1><<<grid, block, 0, st>>>(plane_bits, ntiles, g->E, r->tile_ent, r->d_nact, *tile_base, *super_base); break;
+            case 4: k_count<4><<<grid, block, 0, st>>>(plane_bits, ntiles, g->E, r->tile_ent, r->d_nact, *tile_base, *super_base); break;
+            default: k_count<16><<<grid, block, 0, st>>>(plane_bits, ntiles, g->E, r->tile_ent, r->d_nact, *tile_base, *super_base); break;
         }
-        g->prof.acc[KK_COUNT].units[3] += g->prof.on ? r->Epad * W : 0;
     }
     {
         ProfScope ps(g->prof, KK_SCAN, st);
@@ -886,7 +988,12 @@ static logoskg_status count_plane(logoskg_result *r, const unsigned long long *p
     LKG_HIP(hipGetLastError());
     off->assign((size_t)r->Q + 1, 0);
     LKG_HIP(hipMemcpyAsync(off->data(), *d_off, (size_t)(r->Q + 1) * 8, hipMemcpyDeviceToHost, st));
+    unsigned long long *h_nact = g->h_ctr + C_TOTAL;  // one more pinned word behind the counters' mirror
+    if (r->tile_ent && r->n_active < 0)
+        LKG_HIP(hipMemcpyAsync(h_nact, r->d_nact, 8, hipMemcpyDeviceToHost, st));
     LKG_HIP(hipStreamSynchronize(st));
+    if (r->tile_ent && r->n_active < 0) r->n_active = (long long)*h_nact;
+    if (g->prof.on) g->prof.acc[KK_COUNT].units[3] += (r->tile_ent ? (r->n_active + 63) / 64 * 64 : r->Epad) * W;
     return LOGOSKG_OK;
 }
 
@@ -940,7 +1047,7 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
 // True when the 16-word tile kernel can serve this launch (it then can also write the entity and
 // hop lists, see FillArgs::fuse_lists).
 bool pred_uses_staged_kernel(const FillArgs &a, int W) {
-    return W == 16 && a.k <= kMtMaxK && a.tile_begin % kPredTiles == 0;
+    return W == 16 && a.k <= kSlicedMaxK;
 }
 
 template <int W, bool MASK, bool STATS>
@@ -978,11 +1085,9 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
     if (a.tile_count > 0) {
         ProfScope ps(prof, KK_PRED, st_tiles);
         if (mt) {
-            const long long mt_count = (a.tile_count + kPredTiles - 1) / kPredTiles;
-            const int slab_first = a.q0 / 256, slab_count = (a.q1 - 1) / 256 - slab_first + 1;
-            dim3 grid((unsigned)((mt_count * slab_count + 7) / 8 * 8));
-            k_pred_mt<MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a, a.tile_begin / kPredTiles, mt_count, slab_first,
-                                                                      slab_count);
+            dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8));
+            if (a.k <= 2) k_pred_sliced<2, MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a);
+            else k_pred_sliced<3, MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a);
         } else {
             dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
             k_pred<W, MASK, STATS><<<grid, block, 0, st_tiles>>>(a);
@@ -1060,7 +1165,8 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     const int W = r->W;
     FillArgs a;
     a.E = g->E; a.Q = r->Q; a.k = r->k; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
-    a.ntiles = r->Epad / kTileEntities;
+    a.tile_ent = r->tile_ent; a.cpos = r->cpos; a.n_listed = r->n_active;
+    a.ntiles = r->tile_ent ? (r->n_active + 63) / 64 : r->Epad / kTileEntities;
     a.tile_begin = 0; a.tile_count = a.ntiles;
     a.plane = r->Epad * W; a.actw = r->Epad / 32;
     a.visited = r->visited; a.levels = r->levels; a.allow = r->allow;
@@ -1158,7 +1264,8 @@ extern "C" logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t 
     FillArgs a = {};
     // the level plane plays the part of the visited plane; no hop numbers are asked for
     a.E = g->E; a.Q = r->Q; a.k = 0; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
-    a.ntiles = r->Epad / kTileEntities;
+    a.tile_ent = r->tile_ent; a.cpos = r->cpos; a.n_listed = r->n_active;
+    a.ntiles = r->tile_ent ? (r->n_active + 63) / 64 : r->Epad / kTileEntities;
     a.tile_begin = 0; a.tile_count = a.ntiles;
     a.plane = r->Epad * W; a.actw = r->Epad / 32;
     a.visited = r->levels + (size_t)h * r->Epad * W; a.levels = a.visited; a.allow = r->allow;
