@@ -51,11 +51,19 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
             return n * plane_bytes + items * 4
         return n * (k + 1) * plane_bytes + items * 5
     if kernel == "pred":
-        # visited + level 0 streamed, 4 B written per list entry, 4 B per object-row entry walked;
-        # when the kernel also writes the entity / hop lists: all k+1 levels read, 9 B per entry
+        # list writer of the two-kernel predecessor pass (16-word planes): per (entity, word) of the
+        # tiles it covers 64 code bytes + one visited word read (rows = entities x words), per list
+        # entry 4 B entity + 1 B hop + 4 B predecessor written
         if lists_fused:
-            return n * (k + 2) * plane_bytes + items * 9 + edges * 4
+            return rows * 72 + items * 9
+        # tile kernel with scattered stores (1 and 4 words, or k > 6): visited + level 0 streamed,
+        # 4 B written per list entry, 4 B per object-row entry walked
         return n * 2 * plane_bytes + items * 4 + edges * 4
+    if kernel == "pred_walk":
+        # first kernel of that pass: per (entity, word) (items) the visited word and the k + 1 level
+        # words read, 72 B written; 4 B per object-row entry read; one line per candidate line gathered,
+        # but not more than the graph has lines (caches are assumed to absorb repeats)
+        return items * 8 * (k + 2) + items * 72 + edges * 4 + min(lines * line, plane_bytes)
     if kernel in ("pred_rows", "pred_mid_rows"):
         return edges * 4
     if kernel == "clear_planes":
@@ -67,6 +75,27 @@ def algorithmic_bytes(kernel: str, p: dict, W: int, k: int, masked: bool, plane_
     if kernel == "count_tiles":
         return items * 8 * 1.25  # plane read + uint16 per (tile, query) written
     return 0.0
+
+
+def kernel_sources_sha256(root: str) -> str:
+    """Hash of the HIP sources and headers the library is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(root, "paper_2604_18913_amd", "csrc")
+    names = sorted(f for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for path in [os.path.join(csrc, f) for f in names] + [os.path.join(root, "include", "logoskg.h")]:
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
+def cpu_model() -> str:
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def note(*a):
@@ -289,7 +318,7 @@ def main():
                              avg_ms=p["total_ms"] / p["launches"],
                              ms_per_step_overlapped=prof_overlapped.get(name, {}).get("total_ms", 0.0) / args.steps,
                              **per_step)
-    expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_")
+    expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_", "hop_")
     expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith(expansion_names))
     plane_bytes = float(res_epad * W * 8)
     expansion_bytes = sum(ab(n, v, W, k, masked_arg, plane_bytes) for n, v in kernels.items()
@@ -302,11 +331,22 @@ def main():
     # HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE,
     # calibrated); counters cannot be read from inside this process
     traffic = None
+    traffic_source = None
     valu_view = None
     expansion_measured = None
-    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "pmc_traffic.json")
+    here = os.path.dirname(os.path.abspath(__file__))
+    tfile = os.path.join(here, "profiles", "pmc_traffic.json")
     if os.path.exists(tfile) and args.scale == 1.0 and cfg == 2 and not walk and nf == Q:
-        tk = json.load(open(tfile)).get("kernels", {})
+        stored = json.load(open(tfile))
+        # the stored counter readings belong to one build of the kernels: they are used only while
+        # the kernel sources are the ones they were measured on
+        if stored.get("kernel_sources_sha256") == kernel_sources_sha256(here):
+            tk = stored.get("kernels", {})
+            traffic_source = (f"stored: {stored.get('source')} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                              f"commit {stored.get('commit', '?')}, same kernel sources; not read in this run)")
+        else:
+            tk = {}
+            traffic_source = "none: the kernel sources differ from those profiles/pmc_traffic.json was measured on"
         traffic = tk.get(dom, {}).get("hbm_bytes_per_launch")
         sq = tk.get(dom, {}).get("sq_counters")
         if sq and dk["avg_ms"] > 0:  # how busy the vector ALUs are: the kernel may be bound by instruction issue
@@ -319,7 +359,7 @@ def main():
                                  for n in kernels if n.startswith(expansion_names) and n in tk)
         expansion_measured += kernels.get("clear_planes", {}).get("items", 0) * 8  # a memset: its own size
     roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic, traffic_source=traffic_source,
                     algorithmic_bytes_per_launch=int(alg), avg_launch_ms=round(dk["avg_ms"], 4),
                     measured="HIP events around every launch, fetch kernels serialized", valu=valu_view)
     # the same figure for every kernel that has a byte model
@@ -419,6 +459,16 @@ def main():
         else:
             o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         t_cpu = time.perf_counter() - t0
+        # the oracle's own index build (an empty batch builds it and runs no query), and a
+        # single-thread run on the first 64 queries
+        t0 = time.perf_counter()
+        oracle.khop(w.num_entities, w.subj, w.rel, w.obj, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), k, None)
+        t_index = time.perf_counter() - t0
+        n1 = min(64, nq) if cfg <= 3 else min(2, nq)
+        t0 = time.perf_counter()
+        oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off[: n1 + 1], w.seeds[: w.seed_off[n1]], k,
+                    None if w.rel_mask is None else w.rel_mask[:n1], nthreads=1)
+        t_one = time.perf_counter() - t0
         got = g.khop(seed_off, seeds, k, rel_mask, walk_exact=walk)
         if triples:
             t_off, t_id, t_s, t_r, t_o = got.active_triples(k, 0, nq)
@@ -440,7 +490,12 @@ def main():
                                "kind": "oracle",
                                "sample": f"first {nq} of the {Q} queries of the same workload, one query per "
                                          f"thread, index build included ({t_cpu:.1f} s)",
-                               "matches_gpu": bool(same), "host_cpus": os.cpu_count()}
+                               "matches_gpu": bool(same), "host_cpus": os.cpu_count(), "cpu_model": cpu_model(),
+                               "index_build_s": round(t_index, 2),
+                               "value_without_index_build": round(nq / max(t_cpu - t_index, 1e-9), 2),
+                               "single_thread": {"queries": n1, "seconds": round(t_one, 2),
+                                                 "queries_per_s_without_index_build":
+                                                     round(n1 / max(t_one - t_index, 1e-9), 2)}}
     g.close()
     print(json.dumps(out))
 

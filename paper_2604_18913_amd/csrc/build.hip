@@ -70,7 +70,8 @@ void DevPool::trim() {
 const char *const kKernelNames[KK_NUM] = {
     "clear_planes", "seed_scatter", "frontier_census", "live_queries", "push_tail", "push_seg",
     "update_visited", "pull_tail", "pull_seg", "pull_finish", "count_tiles", "scan_counts",
-    "lists", "pred", "pred_rows", "pred_mid_rows", "traversed", "paths", "shard_copy", "active_triples"};
+    "lists", "pred", "pred_rows", "pred_mid_rows", "traversed", "paths", "shard_copy", "active_triples",
+    "pred_walk"};
 
 void Profiler::begin(int kind, hipStream_t st) {
     if (!on) return;
@@ -326,9 +327,10 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
         if (g->ev_join[i]) (void)hipEventDestroy(g->ev_join[i]);
     }
     if (g->ev_fork) (void)hipEventDestroy(g->ev_fork);
+
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
                     g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,
-                    g->fr_seg, g->d_ctr, g->long_index, g->row_pred, g->out_eid};
+                    g->fr_seg, g->d_ctr, g->long_index, g->row_pred, g->out_eid, g->plane_buf};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (g->h_ctr) (void)hipHostFree(g->h_ctr);

@@ -103,7 +103,7 @@ struct RowClasses {             // device work lists over the object rows, split
 enum KernelKind {
     KK_CLEAR = 0, KK_SEED, KK_CENSUS, KK_LIVE, KK_PUSH_TAIL, KK_PUSH_SEG, KK_UPDATE, KK_PULL_TAIL,
     KK_PULL_SEG, KK_PULL_FINISH, KK_COUNT, KK_SCAN, KK_LISTS, KK_PRED, KK_PRED_HUB, KK_PRED_MID, KK_TRAVERSED,
-    KK_PATHS, KK_SHARD_COPY, KK_TRIPLES, KK_NUM
+    KK_PATHS, KK_SHARD_COPY, KK_TRIPLES, KK_PRED_WALK, KK_NUM
 };
 extern const char *const kKernelNames[KK_NUM];
 
@@ -180,6 +180,8 @@ struct logoskg_graph {
     int32_t *row_pred = nullptr;    // [row_pred_rows][1024]
     int64_t row_pred_rows = 0;
     bool row_pred_tried = false;
+    unsigned long long *plane_buf = nullptr;  // plane words of the bit-sliced predecessor pass (same first use)
+    size_t plane_buf_bytes = 0;
 
     // side streams (default priority) so that the independent result kernels of a fetch overlap
     hipStream_t side[2] = {nullptr, nullptr};
@@ -327,6 +329,9 @@ struct FillArgs {
     const int32_t *tile_ent;  // the tiles' entities (list of active entities) or NULL: tile i = ids 64 i ..
     const int32_t *cpos;      // entity -> place in tile_ent (garbage for entities not in the list), or NULL
     long long n_listed;       // length of tile_ent's list
+    unsigned long long *plane_buf;  // bit-sliced plane words between k_pred_walk and k_pred_emit, or NULL
+    size_t plane_buf_bytes;
+    int emit_eid_cap, emit_line_cap;  // capacities of k_pred_emit's two LDS tables (entries / lines)
     long long tile_begin, tile_count;  // tiles this predecessor launch covers
     long long plane;   // words per plane
     long long actw;    // uint32 words per active bitmap

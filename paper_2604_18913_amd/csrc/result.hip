@@ -27,6 +27,7 @@
 #include <algorithm>
 #include <climits>
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 
@@ -587,28 +588,31 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
     }
 }
 
-// Predecessor kernel for 16-word planes, bit-sliced.  One block = one tile of 64 entities x all
-// 16 words (1,024 queries).
+// Predecessor pass for 16-word planes, bit-sliced, in two kernels.
 //
-// Walk phase: a 16-lane group per entity, lane lw owns word lw of the entity's lines.  The group
+// k_pred_walk: a 16-lane group per entity, lane lw owns word lw of the entity's lines.  The group
 // walks the entity's object row (<= 32 entries) in edge-id order with a mask of unresolved
 // queries per hop level; a candidate's line resolves the queries in (line & mask), all at once.
 // What a (query, entity) pair needs later - its hop number and the position of its predecessor
 // in the row - is kept bit-sliced: NB words H[b] hold bit b of (hop + 1) of each of the lane's 64
 // queries (so H[0] | H[1] | .. is the visited word) and five words J[b] hold bit b of the row
 // position.  A resolving line costs a fixed fifteen instructions for up to 64 pairs, whatever
-// the number of set bits.  The planes then change owner through LDS.
+// the number of set bits.  At the end the planes of a lane are turned into one code byte per
+// query, (row position << 3) | (hop + 1), with eight 8 x 8 bit transposes, and the 64 bytes of
+// every (entity, word) go to a buffer laid out [tile][word][entity][query], which a chunk of
+// tiles fills and the second kernel empties while it is still in the caches.
 //
-// Write phase: wavefront w owns word w, lane v the entity v of the tile, with its NB + 5 plane
-// words in registers.  For every query of the word that reached the tile (a scalar loop) the
-// lanes test their bit, a ballot ranks them inside the query's run, the eight plane bits give hop
-// and row position, and the lanes store (entity, hop, predecessor edge) at consecutive list
-// positions: every lane issues the same instructions, and a store instruction covers one
-// contiguous piece of a list.  Rows of more than 32 entries belong to the row kernels as before:
-// such an entity's predecessor comes from row_pred (rows below hub_min, whose kernel ran before
-// on the same stream) or is left to the block-per-row kernel.
-constexpr int kSlicedMaxK = 6;    // hop + 1 <= 7 fits three bits
-constexpr int kSlicedEidStride = 33;  // edge ids staged per entity (32 + 1: lanes = entities read it without bank conflicts)
+// k_pred_emit: a block = one tile, its four wavefronts share the words of the fetched range; lane =
+// entity, with the lane's 64 code bytes of the current word in registers.  A wavefront walks the
+// queries of the word that reached the tile in a scalar loop; per query the lanes pick their code
+// byte, a ballot ranks the reached ones inside the tile's piece of the query's run, and the lanes
+// store (entity, hop, predecessor edge) at consecutive list positions: every lane issues the same
+// few instructions and a store instruction covers one contiguous piece of a list.  The loop holds
+// no load from memory (the edge ids of the tile's short rows are staged in LDS once per block), so
+// nothing in it waits for its own stores.  Rows of more than 32 entries belong to the row
+// kernels: such an entity's predecessors come from row_pred (rows below hub_min, whose kernel ran
+// before on the same stream) or are left to the block-per-row kernel.
+constexpr int kSlicedMaxK = 6;     // hop + 1 <= 7 fits three bits
 
 __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
 #pragma unroll
@@ -617,30 +621,17 @@ __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
 }
 
 template <int NB, bool MASK, bool STATS>
-__global__ void __launch_bounds__(1024) k_pred_sliced(FillArgs a) {
-    constexpr int W = 16, Qp = 1024, G = 16, NP = NB + 5;
+__global__ void __launch_bounds__(256)
+k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long long *__restrict__ visbuf,
+            long long tile0, long long ntile, int w0, int nw) {
+    constexpr int W = 16, G = 16;
     constexpr int HMAX = (1 << NB) - 2;  // largest hop number the NB bits of (hop + 1) can hold
-    // plane words of entity e sit at [e][w ^ (e & 15)]: the walk phase writes an entity's sixteen
-    // words side by side, the write phase reads one word of 64 entities, both without bank conflicts
-    __shared__ unsigned long long sm[NP][64][16];
-    __shared__ int eid_tab[64 * kSlicedEidStride];  // edge ids of the tile's short rows, by row position
-    const long long tile_rel = xcd_contiguous(blockIdx.x, gridDim.x);
-    if (tile_rel >= a.tile_count) return;  // block-uniform
-    const long long tile = a.tile_begin + tile_rel;
-    const int t = threadIdx.x, wave = t >> 6, v = lane();
-    const int vi = t >> 4, lw = t & 15, g0 = v & ~(G - 1);
-    const long long ev = tile_entity(a.tile_ent, tile, vi, a.E);
+    const long long grp = xcd_contiguous(blockIdx.x, gridDim.x) * 16 + (threadIdx.x >> 4);  // entity slot of the chunk
+    const long long tile_rel = grp >> 6;
+    if (tile_rel >= ntile) return;  // block-uniform: a block holds 16 entities of one tile
+    const int vi = (int)(grp & 63), lw = threadIdx.x & 15, v = lane(), g0 = v & ~(G - 1);
+    const long long ev = tile_entity(a.tile_ent, tile0 + tile_rel, vi, a.E);
     const unsigned long long range_w = range_bits(a.q0, a.q1, lw);
-    // ---- requested now, used in the write phase (thread t = query t there, lane v = entity v)
-    long long pos = 0;
-    if (t >= a.q0 && t < a.q1) pos = super_start(a, tile / kSuperTiles, Qp, t) + a.tile_base[(size_t)tile * Qp + t];
-    const long long ew = tile_entity(a.tile_ent, tile, v, a.E);
-    uint32_t wlo = 0, whi = 0;
-    if (ew >= 0) {
-        wlo = a.in_off[ew];
-        whi = a.in_off[ew + 1];
-    }
-    // ---- walk phase
     unsigned long long visw = 0, lv0 = 0;
     uint32_t lo = 0, hi = 0;
     if (ev >= 0) {
@@ -659,10 +650,6 @@ __global__ void __launch_bounds__(1024) k_pred_sliced(FillArgs a) {
     for (int b = 0; b < 5; ++b) J[b] = 0;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     if (group_any<G>((visw & ~lv0) != 0)) {  // some query of the range reached the entity by an edge
-        if (shortrow) {
-            if (lw < deg) eid_tab[vi * kSlicedEidStride + lw] = a.in_eid[lo + lw];
-            if (lw + G < deg) eid_tab[vi * kSlicedEidStride + lw + G] = a.in_eid[lo + lw + G];
-        }
         // the level words of the first hops are requested together
         constexpr int PRE = HMAX < 3 ? HMAX : 3;
         unsigned long long pre[PRE];
@@ -725,77 +712,40 @@ __global__ void __launch_bounds__(1024) k_pred_sliced(FillArgs a) {
             }
         }
     }
+    if (lw >= w0 && lw < w0 + nw) {
+        // From bit planes to one byte per query: plane b = bit b of the code, NB bits of (hop + 1)
+        // below five bits of the row position.  Byte g of every plane forms an 8 x 8 bit matrix
+        // (row = plane, column = query 8 g + j); its transpose holds the codes of those 8 queries.
+        uint4 *out = reinterpret_cast<uint4 *>(codes) + (((size_t)tile_rel * nw + (lw - w0)) * 64 + vi) * 4;
+        unsigned long long reached = 0;  // H[0] | H[1] | ..: the queries of the word that reached the entity
 #pragma unroll
-    for (int b = 0; b < NB; ++b) sm[b][vi][lw ^ (vi & 15)] = H[b];
+        for (int b = 0; b < NB; ++b) reached |= H[b];
+        visbuf[((size_t)tile_rel * nw + (lw - w0)) * 64 + vi] = reached;
+        unsigned long long P[8];
 #pragma unroll
-    for (int b = 0; b < 5; ++b) sm[NB + b][vi][lw ^ (vi & 15)] = J[b];
-    __syncthreads();
-    // ---- write phase: wavefront = word, lane = entity
-    unsigned long long P[NP];
+        for (int b = 0; b < 8; ++b) P[b] = 0;
 #pragma unroll
-    for (int b = 0; b < NP; ++b) P[b] = sm[b][v][wave ^ (v & 15)];
-    unsigned long long vis = 0;
+        for (int b = 0; b < NB; ++b) P[b] = H[b];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) vis |= P[b];
-    const unsigned long long live = wave_or64(vis);
-    if (live != 0ull) {
-        const uint32_t wdeg = whi - wlo;
-        // where a lane's predecessors come from: the staged edge ids of its own short row (indexed
-        // by the row position), its line of row_pred (indexed by the query), or nowhere (the row
-        // kernels write them, only seeds get their -1 here)
-        const bool longrow = wdeg > (uint32_t)kTailMaxDegree;
-        const bool by_query = longrow && a.row_pred && wdeg < (uint32_t)a.hub_min;
-        const bool elsewhere = longrow && !by_query;
-        const int32_t *src = nullptr;
-        if (by_query) src = a.row_pred + (size_t)(a.long_index[ew] - a.row_base) * Qp + wave * 64;
-        const bool any_by_query = wave_any(by_query);
-        const int *const my_eids = eid_tab + v * kSlicedEidStride;
-        const int ent_id = (int)ew;
-        const uint32_t pos_lo = (uint32_t)(unsigned long long)pos, pos_hi = (uint32_t)((unsigned long long)pos >> 32);
+        for (int b = 0; b < 5; ++b) P[3 + b] = J[b];  // the position always starts at bit 3
+        uint32_t d[16];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            uint32_t ph[NP];
+        for (int g = 0; g < 8; ++g) {
+            unsigned long long x = 0;
 #pragma unroll
-            for (int b = 0; b < NP; ++b) ph[b] = (uint32_t)(P[b] >> (32 * half));
-            const uint32_t vis_h = (uint32_t)(vis >> (32 * half));
-            uint32_t rest = __builtin_amdgcn_readfirstlane((uint32_t)(live >> (32 * half)));
-            while (rest) {  // scalar loop over the queries of this half word that reached the tile
-                const int qq = __builtin_ctz(rest);
-                rest &= rest - 1;
-                const bool bit = (vis_h & (1u << qq)) != 0u;
-                const unsigned long long m = __ballot(bit);
-                const unsigned rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                const unsigned long long base =
-                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)pos_hi, 32 * half + qq) << 32) |
-                    (uint32_t)__builtin_amdgcn_readlane((int)pos_lo, 32 * half + qq);
-                // bits of (hop + 1) and of the row position, most significant first: one bit
-                // extraction and one shift-or each
-                unsigned hc = 0, jp = 0;
-#pragma unroll
-                for (int b = NB - 1; b >= 0; --b) hc = (hc << 1) | __builtin_amdgcn_ubfe(ph[b], (unsigned)qq, 1u);
-#pragma unroll
-                for (int b = 4; b >= 0; --b) jp = (jp << 1) | __builtin_amdgcn_ubfe(ph[NB + b], (unsigned)qq, 1u);
-                if (bit) {
-                    int32_t *const pe = a.entity + base;
-                    pe[rank] = ent_id;
-                    if (a.hop) {
-                        uint8_t *const ph8 = a.hop + base;
-                        ph8[rank] = (uint8_t)(hc - 1u);
-                    }
-                    const bool seed = hc == 1u;
-                    int val = my_eids[jp];  // (unused for seeds and long rows)
-                    asm volatile("" : "+v"(val));  // keeps the LDS read apart from the global one below
-                    if (any_by_query) {  // wave-uniform: only then is there a global load in the loop
-                        if (by_query && !seed) val = src[32 * half + qq];
-                    }
-                    if (seed) val = -1;
-                    if (!elsewhere || seed) {
-                        int32_t *const pp = a.pred + base;
-                        pp[rank] = val;
-                    }
-                }
-            }
+            for (int b = 0; b < 8; ++b) x |= ((P[b] >> (8 * g)) & 0xFFull) << (8 * b);
+            unsigned long long t;
+            t = (x ^ (x >> 7)) & 0x00AA00AA00AA00AAull;
+            x = x ^ t ^ (t << 7);
+            t = (x ^ (x >> 14)) & 0x0000CCCC0000CCCCull;
+            x = x ^ t ^ (t << 14);
+            t = (x ^ (x >> 28)) & 0x00000000F0F0F0F0ull;
+            x = x ^ t ^ (t << 28);
+            d[2 * g] = (uint32_t)x;
+            d[2 * g + 1] = (uint32_t)(x >> 32);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = make_uint4(d[4 * i], d[4 * i + 1], d[4 * i + 2], d[4 * i + 3]);
     }
     if (STATS) {
         n_rows = wave_sum(n_rows);
@@ -806,6 +756,247 @@ __global__ void __launch_bounds__(1024) k_pred_sliced(FillArgs a) {
             if (n_edges) atomicAdd(&a.stats_pred[1], (unsigned long long)n_edges);
             if (n_lines) atomicAdd(&a.stats_pred[2], (unsigned long long)n_lines);
         }
+    }
+}
+
+// A block = 16 consecutive tiles (one wavefront each) x every wsplit-th word of the fetched range.
+// 8 wavefronts per SIMD = at most 64 vector registers.
+constexpr int kEmitTiles = 16;
+constexpr int kEmitEids = 10240;  // LDS: edge ids of the short rows of the block's 1,024 entities
+constexpr int kEmitLines = 96;    // LDS: row_pred values (64 queries each) of the block's entities with rows of 33 .. hub_min-1 entries
+
+// STAGED: the edge ids of the block's short rows fit eid_tab; LINES: the block's row_pred entities
+// fit rp_tab.  Otherwise the loop reads the edge ids from memory / a pass of its own moves the
+// row_pred values with lanes = queries.
+template <bool STAGED, bool LINES>
+__device__ __forceinline__ void emit_word(const FillArgs &a, const uint32_t (&c)[16], unsigned long long live,
+                                          uint32_t pos_lo, uint32_t pos_hi, int ent_id, bool longrow, bool by_query,
+                                          const int *my_eids, const int32_t *my_row, const int *my_line) {
+    const uint32_t live_lo = __builtin_amdgcn_readfirstlane((uint32_t)live);
+    const uint32_t live_hi = __builtin_amdgcn_readfirstlane((uint32_t)(live >> 32));
+    // unrolled over the sixteen code registers (four queries each): a query's byte is picked with
+    // one bit-field extract
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        uint32_t rest = ((r < 8 ? live_lo : live_hi) >> (4 * (r & 7))) & 15u;
+        while (rest) {  // scalar loop over the queries 4 r .. 4 r + 3 that reached the block's tiles
+            const int j = __builtin_ctz(rest);
+            rest &= rest - 1;
+            const int qq = 4 * r + j;
+            const uint32_t code = __builtin_amdgcn_ubfe(c[r], (unsigned)(8 * j), 8u);
+            const uint32_t hc = code & 7u, jp = code >> 3;
+            const bool bit = hc != 0u;
+            const unsigned long long m = __ballot(bit);
+            if (bit) {
+                const unsigned rank =
+                    __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                const unsigned long long base =
+                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)pos_hi, qq) << 32) |
+                    (uint32_t)__builtin_amdgcn_readlane((int)pos_lo, qq);
+                int32_t *const pe = a.entity + base;
+                pe[rank] = ent_id;
+                if (a.hop) {
+                    uint8_t *const ph8 = a.hop + base;
+                    ph8[rank] = (uint8_t)(hc - 1u);
+                }
+                const bool seed = hc == 1u;
+                if (!longrow || seed || (LINES && by_query)) {
+                    int val = -1;
+                    if (!seed) {
+                        if constexpr (LINES) {
+                            if constexpr (STAGED) val = by_query ? my_line[qq] : my_eids[jp];
+                            else val = by_query ? my_line[qq] : my_row[jp];
+                        } else {
+                            if constexpr (STAGED) val = my_eids[jp];
+                            else val = my_row[jp];
+                        }
+                    }
+                    int32_t *const pp = a.pred + base;
+                    pp[rank] = val;
+                }
+            }
+            __builtin_amdgcn_s_barrier();  // the sixteen tiles write their pieces of a query together
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kEmitTiles * 64) __attribute__((amdgpu_waves_per_eu(8, 8)))
+k_pred_emit(FillArgs a, const unsigned long long *__restrict__ codes, const unsigned long long *__restrict__ visbuf,
+            long long tile0, long long ntile, int w0, int nw, int wsplit, int eid_cap, int line_cap) {
+    constexpr int Qp = 1024, TPB = kEmitTiles;
+    __shared__ int eid_tab[kEmitEids];
+    __shared__ int rp_tab[kEmitLines * 64];
+    __shared__ unsigned long long s_live[2];
+    __shared__ int s_wsum[2][TPB];
+    const long long L = xcd_contiguous(blockIdx.x, gridDim.x);
+    const long long nsup = (ntile + TPB - 1) / TPB;
+    if (L >= nsup * wsplit) return;  // block-uniform
+    const int part = (int)(L % wsplit);
+    const int t = threadIdx.x, wave = t >> 6, v = lane();
+    const long long tile_rel = (L / wsplit) * TPB + wave, tile = tile0 + tile_rel;
+    const bool valid = tile_rel < ntile;  // wave-uniform
+    if (t < 2) s_live[t] = 0ull;
+    // ---- once per block: the tiles' entities (lane = entity)
+    const long long ew = valid ? tile_entity(a.tile_ent, tile, v, a.E) : -1;
+    uint32_t wlo = 0, whi = 0;
+    if (ew >= 0) {
+        wlo = a.in_off[ew];
+        whi = a.in_off[ew + 1];
+    }
+    const uint32_t wdeg = whi - wlo;
+    // where a lane's predecessors come from: the edge ids of its own short row (by row position),
+    // its line of row_pred (by query), or nowhere (the block-per-row kernel writes them).  Seeds
+    // get their -1 in the loop.
+    const bool longrow = wdeg > (uint32_t)kTailMaxDegree;
+    const bool by_query = longrow && a.row_pred && wdeg < (uint32_t)a.hub_min;
+    int li = 0;
+    if (by_query) li = (int)(a.long_index[ew] - a.row_base);
+    const int n_stage = longrow ? 0 : (int)wdeg;
+    int wtot, ltot;
+    int off = wave_excl_scan(n_stage, wtot);
+    const unsigned long long bq_wave = __ballot(by_query);
+    int slot = __popcll(bq_wave & ((1ull << v) - 1ull));
+    ltot = __popcll(bq_wave);
+    if (v == 0) {
+        s_wsum[0][wave] = wtot;
+        s_wsum[1][wave] = ltot;
+    }
+    __syncthreads();
+    int total = 0, lines = 0, line0 = 0;
+#pragma unroll
+    for (int x = 0; x < TPB; ++x) {
+        if (x < wave) {
+            off += s_wsum[0][x];
+            line0 += s_wsum[1][x];
+        }
+        total += s_wsum[0][x];
+        lines += s_wsum[1][x];
+    }
+    slot += line0;
+    const bool staged = total <= eid_cap, lined = lines <= line_cap;  // block-uniform
+    if (staged)  // eight entries of the lane's row are requested before the first is stored
+        for (int i0 = 0; i0 < n_stage; i0 += 8) {
+            int e[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) e[x] = i0 + x < n_stage ? a.in_eid[wlo + i0 + x] : 0;
+#pragma unroll
+            for (int x = 0; x < 8; ++x)
+                if (i0 + x < n_stage) eid_tab[off + i0 + x] = e[x];
+        }
+    const int ent_id = (int)ew;
+    const int *const my_eids = eid_tab + (staged ? off : 0);
+    const int32_t *const my_row = a.in_eid + wlo;
+    const int *const my_line = rp_tab + (lined ? slot : 0) * 64;
+    int turn = 0;
+    for (int wi = part; wi < nw; wi += wsplit, turn ^= 1) {  // block-uniform trip count
+        const int w = w0 + wi;
+        // where query 64 w + v continues in this tile (lane = query here)
+        long long pos = 0;
+        const int ql = w * 64 + v;
+        if (valid && ql >= a.q0 && ql < a.q1)
+            pos = super_start(a, tile / kSuperTiles, Qp, ql) + a.tile_base[(size_t)tile * Qp + ql];
+        // lane = entity: one code byte per query of the word, (row position << 3) | (hop + 1), zero where
+        // the query did not reach the entity; vis = the queries that reached it
+        uint32_t c[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c[i] = 0;
+        unsigned long long vis = 0;
+        if (ew >= 0) {
+            const size_t at = ((size_t)tile_rel * nw + wi) * 64 + v;
+            const uint4 *in = reinterpret_cast<const uint4 *>(codes) + at * 4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint4 x = in[i];
+                c[4 * i] = x.x; c[4 * i + 1] = x.y; c[4 * i + 2] = x.z; c[4 * i + 3] = x.w;
+            }
+            vis = visbuf[at];
+        }
+        // the row_pred values of this word: 64 queries x the wavefront's entities of that kind, eight
+        // lines requested together (lanes = queries)
+        if (lined) {
+            unsigned long long bq = bq_wave;
+            int s_at = line0;
+            while (bq) {
+                int val[8];
+                int n = 0;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    val[x] = 0;
+                    if (bq) {
+                        const int Lx = __builtin_ctzll(bq);
+                        bq &= bq - 1;
+                        val[x] = a.row_pred[(size_t)__builtin_amdgcn_readlane(li, Lx) * Qp + ql];
+                        ++n;
+                    }
+                }
+#pragma unroll
+                for (int x = 0; x < 8; ++x)
+                    if (x < n) rp_tab[(s_at + x) * 64 + v] = val[x];
+                s_at += n;
+            }
+        }
+        const unsigned long long live_wave = wave_or64(vis);
+        if (v == 0 && live_wave) atomicOr(&s_live[turn], live_wave);
+        __syncthreads();
+        const unsigned long long live = s_live[turn];
+        if (t == 0) s_live[turn ^ 1] = 0ull;  // for the next word (read again only after its barrier)
+        uint32_t pos_lo = (uint32_t)(unsigned long long)pos, pos_hi = (uint32_t)((unsigned long long)pos >> 32);
+        if (live != 0ull) {  // block-uniform
+            if (!lined) {
+                // Entities whose predecessors wait in row_pred, too many for rp_tab: lanes = queries.
+                // Lane i knows where query i's run of this tile starts (pos) and, after a 64 x 64
+                // transpose of the visited words, which of the tile's entities query i reached: the
+                // rank of entity L in the run is the number of those below L.  Four lines are
+                // requested before the first is stored.  Seeds (hop + 1 == 1) are left to the loop.
+                unsigned long long bq = bq_wave;
+                if (bq) {
+                    const unsigned long long mT = transpose64(vis);
+                    unsigned long long seed_w = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            seed_w |= (unsigned long long)(((c[i] >> (8 * j)) & 7u) == 1u) << (4 * i + j);
+                    const uint32_t seed_lo = (uint32_t)seed_w, seed_hi = (uint32_t)(seed_w >> 32);
+                    const int32_t *const rp = a.row_pred + ql;
+                    int32_t *const pp = a.pred + pos;
+                    while (bq) {
+                        int Lx[4], val[4];
+                        bool on[4];
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            Lx[x] = -1;
+                            on[x] = false;
+                            val[x] = 0;
+                            if (bq) {
+                                Lx[x] = __builtin_ctzll(bq);
+                                bq &= bq - 1;
+                                const int liL = __builtin_amdgcn_readlane(li, Lx[x]);
+                                const unsigned long long seedL =
+                                    ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)seed_hi, Lx[x]) << 32) |
+                                    (uint32_t)__builtin_amdgcn_readlane((int)seed_lo, Lx[x]);
+                                on[x] = ((mT >> Lx[x]) & 1ull) && !((seedL >> v) & 1ull);
+                                if (on[x]) val[x] = rp[(size_t)liL * Qp];
+                            }
+                        }
+#pragma unroll
+                        for (int x = 0; x < 4; ++x)
+                            if (on[x]) pp[__popcll(mT & ((1ull << Lx[x]) - 1ull))] = val[x];
+                    }
+                }
+            }
+            // Everything requested from memory so far is consumed here, so that the loop holds stores
+            // only: a wait on a load inside it would also wait for the loop's own stores.
+            asm volatile("" : "+v"(pos_lo), "+v"(pos_hi));
+            if (staged) {
+                if (lined) emit_word<true, true>(a, c, live, pos_lo, pos_hi, ent_id, longrow, by_query, my_eids, my_row, my_line);
+                else emit_word<true, false>(a, c, live, pos_lo, pos_hi, ent_id, longrow, by_query, my_eids, my_row, my_line);
+            } else {
+                if (lined) emit_word<false, true>(a, c, live, pos_lo, pos_hi, ent_id, longrow, by_query, my_eids, my_row, my_line);
+                else emit_word<false, false>(a, c, live, pos_lo, pos_hi, ent_id, longrow, by_query, my_eids, my_row, my_line);
+            }
+        }
+        __syncthreads();  // rp_tab is rewritten for the next word
     }
 }
 
@@ -1015,6 +1206,15 @@ __global__ void k_long_index(const int32_t *__restrict__ rows, long long n, int3
 logoskg_status prepare_row_pred(logoskg_graph *g, hipStream_t st) {
     if (g->row_pred_tried) return LOGOSKG_OK;
     g->row_pred_tried = true;
+    // code bytes and visited words between the two kernels of the bit-sliced predecessor pass: room
+    // for every tile of the graph and 16 words, but not more than 1.25 GiB
+    g->plane_buf_bytes = std::min<size_t>((size_t)5 << 28, (size_t)(g->Epad / 64 + kEmitTiles) * 16 * 64 * (64 + 8));
+    if (hipMalloc((void **)&g->plane_buf, g->plane_buf_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        g->plane_buf = nullptr;
+        g->plane_buf_bytes = 0;
+    }
+
     const long long rows = g->num_shards > 1 ? max_chunk_rows(g) : (long long)g->in_rows.n_long;
     if (rows <= 0 || (size_t)rows * 4096 > ((size_t)8 << 30)) return LOGOSKG_OK;
     LKG_HIP(hipMalloc((void **)&g->long_index, (size_t)g->E * sizeof(int32_t)));
@@ -1047,7 +1247,7 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
 // True when the 16-word tile kernel can serve this launch (it then can also write the entity and
 // hop lists, see FillArgs::fuse_lists).
 bool pred_uses_staged_kernel(const FillArgs &a, int W) {
-    return W == 16 && a.k <= kSlicedMaxK;
+    return W == 16 && a.k <= kSlicedMaxK && a.plane_buf != nullptr;
 }
 
 template <int W, bool MASK, bool STATS>
@@ -1082,16 +1282,40 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
             k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
                 a, giants);
     }
-    if (a.tile_count > 0) {
-        ProfScope ps(prof, KK_PRED, st_tiles);
-        if (mt) {
-            dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8));
-            if (a.k <= 2) k_pred_sliced<2, MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a);
-            else k_pred_sliced<3, MASK, STATS><<<grid, dim3(1024), 0, st_tiles>>>(a);
-        } else {
-            dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
-            k_pred<W, MASK, STATS><<<grid, block, 0, st_tiles>>>(a);
+    if (a.tile_count > 0 && mt) {
+        // in chunks of tiles whose code bytes (64 per entity and word) and visited words fit the buffer
+        const int w0 = a.q0 / 64, nw = (a.q1 - 1) / 64 - w0 + 1;
+        const size_t per_tile = (size_t)nw * 64 * (64 + 8);
+        long long chunk = (long long)(a.plane_buf_bytes / per_tile);
+        chunk = std::max<long long>(kEmitTiles, chunk / kEmitTiles * kEmitTiles);
+        for (long long c0 = 0; c0 < a.tile_count; c0 += chunk) {
+            const long long n = std::min(chunk, a.tile_count - c0), t0 = a.tile_begin + c0;
+            unsigned long long *visbuf = a.plane_buf + (size_t)n * nw * 64 * 8;  // behind the codes
+            // each block of the second kernel takes every wsplit-th word: enough blocks to go
+            // round the GPU a few times, as many words per block as that allows
+            const long long nsup = (n + kEmitTiles - 1) / kEmitTiles;
+            int wsplit = 1;
+            while (wsplit < nw && nsup * wsplit < 8192) wsplit *= 2;
+            wsplit = std::min(wsplit, nw);
+            dim3 gw((unsigned)((n * 4 + 7) / 8 * 8));
+            dim3 ge((unsigned)((nsup * wsplit + 7) / 8 * 8));
+            {
+                ProfScope ps(prof, KK_PRED_WALK, st_tiles);
+                if (a.k <= 2) k_pred_walk<2, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
+                else k_pred_walk<3, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
+            }
+            ProfScope ps(prof, KK_PRED, st_tiles);
+            k_pred_emit<<<ge, dim3(kEmitTiles * 64), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wsplit,
+                                                                   a.emit_eid_cap, a.emit_line_cap);
+            if (prof.on) {  // entities x words whose code bytes pass from the first kernel to the second
+                prof.acc[KK_PRED_WALK].units[3] += n * 64 * nw;
+                prof.acc[KK_PRED].units[0] += n * 64 * nw;
+            }
         }
+    } else if (a.tile_count > 0) {
+        ProfScope ps(prof, KK_PRED, st_tiles);
+        dim3 grid((unsigned)((a.tile_count + 7) / 8 * 8)), block(64 * W);
+        k_pred<W, MASK, STATS><<<grid, block, 0, st_tiles>>>(a);
     }
 }
 
@@ -1175,11 +1399,24 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.rows = g->in_rows.longrows;
     a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
+    a.plane_buf = nullptr; a.plane_buf_bytes = 0;
     a.n_giant_rows = g->num_shards > 1 ? -1 : g->in_rows.n_giant;
     if (pred && W == 16) {
         LKG_TRY(prepare_row_pred(g, st));
         a.long_index = g->long_index;
         a.row_pred = g->row_pred;
+        a.plane_buf = g->plane_buf;
+        a.plane_buf_bytes = g->plane_buf_bytes;
+        // (LOGOSKG_EMIT_CAPS="e,l" shrinks the two LDS tables of k_pred_emit so that tests reach its other paths)
+        a.emit_eid_cap = kEmitEids;
+        a.emit_line_cap = kEmitLines;
+        if (const char *caps = getenv("LOGOSKG_EMIT_CAPS")) {
+            int e = kEmitEids, l = kEmitLines;
+            if (sscanf(caps, "%d,%d", &e, &l) == 2) {
+                a.emit_eid_cap = std::max(0, std::min(e, kEmitEids));
+                a.emit_line_cap = std::max(0, std::min(l, kEmitLines));
+            }
+        }
     }
     a.entity = entity; a.hop = hop; a.pred = pred;
     const bool counting = g->prof.counters;
@@ -1224,8 +1461,10 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     if (counting) {  // measurement mode only: wait for the counters
         LKG_HIP(hipMemcpyAsync(g->h_ctr, g->d_ctr, C_TOTAL * sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
         LKG_HIP(hipStreamSynchronize(st));
-        for (int kind : {KK_PRED, KK_PRED_HUB, KK_PRED_MID})
-            for (int u = 0; u < 3; ++u) g->prof.acc[kind].units[u] += (long long)g->h_ctr[C_STATS + 4 * kind + u];
+        for (int kind : {KK_PRED, KK_PRED_HUB, KK_PRED_MID})  // (the two-kernel tile pass counts in its first kernel)
+            for (int u = 0; u < 3; ++u)
+                g->prof.acc[kind == KK_PRED && a.fuse_lists ? KK_PRED_WALK : kind].units[u] +=
+                    (long long)g->h_ctr[C_STATS + 4 * kind + u];
     }
     return LOGOSKG_OK;
 }

@@ -174,6 +174,30 @@ def test_sixteen_word_planes_deep_hops_serial_fetch_and_no_hop_output(monkeypatc
     g.close()
 
 
+@pytest.mark.parametrize("caps", ["0,0", "0,96", "10240,0", "700,3"])
+@pytest.mark.parametrize("masked", [False, True])
+def test_list_writer_without_room_in_its_tables(caps, masked, monkeypatch):
+    # the kernel that writes the lists of a 1,024-query batch keeps the edge ids of short object rows
+    # and the predecessor lines of mid-size rows in two LDS tables; with the tables shrunk (or gone)
+    # it reads the edge ids from memory and moves the lines in a pass of its own: same lists.
+    # Fetched whole, as a sub-range of queries that starts inside a word, and without hop numbers.
+    w = kggen.config3(0.006, k=3) if masked else kggen.config2(0.006, num_queries=700)
+    want = run_oracle(w)
+    monkeypatch.setenv("LOGOSKG_EMIT_CAPS", caps)
+    got, _ = run_gpu(w, "auto", hub_min_degree=200)
+    assert_same(got, want, f"caps {caps}")
+    m = lkg()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=200)
+    res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+    q0, q1 = 70, min(w.num_queries, 650)
+    a, b = int(want[0][q0]), int(want[0][q1])
+    ent, hop, pred = res.fetch(q0, q1, want_hop=False)
+    assert hop is None
+    assert np.array_equal(ent.cpu().numpy(), want[1][a:b]) and np.array_equal(pred.cpu().numpy(), want[3][a:b])
+    res.close()
+    g.close()
+
+
 def test_two_runs_are_bit_identical():
     w = kggen.config3(0.01, k=3)
     a, _ = run_gpu(w, "auto", hub_min_degree=100)
