@@ -23,14 +23,26 @@ void set_error(const char *fmt, ...) {
 
 const char *get_error() { return g_err.c_str(); }
 
-logoskg_status DevPool::alloc(void **out, size_t bytes) {
+logoskg_status DevPool::alloc(void **out, size_t bytes, hipStream_t st, bool have_stream, bool *zeroed) {
+    if (zeroed) *zeroed = false;
     if (bytes == 0) bytes = 256;
     bytes = (bytes + 255) & ~size_t(255);
     auto it = free_.lower_bound(bytes);
     if (it != free_.end() && it->first <= bytes * 2) {
-        *out = it->second;
-        live_[it->second] = it->first;
+        Block b = it->second;
+        live_[b.p] = it->first;
         free_.erase(it);
+        if (b.after) {  // released behind work that may still run
+            hipError_t e = hipSuccess;
+            if (!have_stream) e = hipEventSynchronize(b.after->ev);
+            else if (b.after->stream != st) e = hipStreamWaitEvent(st, b.after->ev, 0);
+            if (e != hipSuccess) {
+                set_error("waiting for a released block failed: %s", hipGetErrorString(e));
+                return LOGOSKG_EDEVICE;
+            }
+        }
+        if (zeroed) *zeroed = b.zeroed;
+        *out = b.p;
         return LOGOSKG_OK;
     }
     void *p = nullptr;
@@ -55,16 +67,54 @@ void DevPool::release(void *p) {
     if (!p) return;
     auto it = live_.find(p);
     if (it == live_.end()) return;
-    free_.emplace(it->second, p);
+    free_.emplace(it->second, Block{p, nullptr, false});
     live_.erase(it);
+}
+
+// The blocks become reusable behind the work issued on `st` so far: one event for all of them
+// (it goes back to the spare list when the last of these blocks has been handed out again).
+void DevPool::release_after(void *const *ptrs, const bool *zeroed, int n, hipStream_t st) {
+    hipEvent_t ev = nullptr;
+    if (!spare_events_.empty()) {
+        ev = spare_events_.back();
+        spare_events_.pop_back();
+    } else if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        ev = nullptr;
+    }
+    std::shared_ptr<After> after;
+    if (ev && hipEventRecord(ev, st) == hipSuccess) {
+        after = std::shared_ptr<After>(new After{ev, st}, [this](After *a) {
+            spare_events_.push_back(a->ev);
+            delete a;
+        });
+    } else {  // no event: wait here, then the blocks are free without conditions
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(st);
+        if (ev) spare_events_.push_back(ev);
+    }
+    for (int i = 0; i < n; ++i) {
+        if (!ptrs[i]) continue;
+        auto it = live_.find(ptrs[i]);
+        if (it == live_.end()) continue;
+        free_.emplace(it->second, Block{ptrs[i], after, zeroed ? zeroed[i] : false});
+        live_.erase(it);
+    }
 }
 
 void DevPool::trim() {
     for (auto &kv : free_) {
-        (void)hipFree(kv.second);
+        if (kv.second.after) (void)hipEventSynchronize(kv.second.after->ev);
+        (void)hipFree(kv.second.p);
         held_ -= kv.first;
     }
     free_.clear();
+}
+
+DevPool::~DevPool() {
+    free_.clear();  // returns the events of pending releases to the spare list
+    for (hipEvent_t e : spare_events_) (void)hipEventDestroy(e);
+    spare_events_.clear();
 }
 
 const char *const kKernelNames[KK_NUM] = {

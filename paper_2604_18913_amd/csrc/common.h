@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <string>
 #include <unordered_map>
 #include <vector>
@@ -44,17 +45,29 @@ const char *get_error();
 // k-hop calls need several planes of hundreds of MB each; hipMalloc/hipFree of
 // that size cost far more than the kernels, so freed blocks are kept and handed
 // out again (exact-size match first, else the smallest block that is large
-// enough and at most 2x the request).
+// enough and at most 2x the request).  A block released behind work that may
+// still run (release_after) carries an event recorded on that work's stream: a
+// later user on another stream waits for it, a user without a stream waits on
+// the host.  Such a block can also be marked as holding zeros only.
 class DevPool {
 public:
-    logoskg_status alloc(void **out, size_t bytes);
-    void release(void *p);
+    logoskg_status alloc(void **out, size_t bytes) { return alloc(out, bytes, nullptr, false, nullptr); }
+    logoskg_status alloc(void **out, size_t bytes, hipStream_t st, bool *zeroed = nullptr) {
+        return alloc(out, bytes, st, true, zeroed);
+    }
+    void release(void *p);  // usable at once (the caller has waited for the block's last use)
+    void release_after(void *const *ptrs, const bool *zeroed, int n, hipStream_t st);
     void trim();  // hipFree everything that is not handed out
     size_t bytes_held() const { return held_; }
+    ~DevPool();
 
 private:
-    std::multimap<size_t, void *> free_;
+    struct After { hipEvent_t ev; hipStream_t stream; };
+    struct Block { void *p; std::shared_ptr<After> after; bool zeroed; };
+    logoskg_status alloc(void **out, size_t bytes, hipStream_t st, bool have_stream, bool *zeroed);
+    std::multimap<size_t, Block> free_;
     std::unordered_map<void *, size_t> live_;
+    std::vector<hipEvent_t> spare_events_;
     size_t held_ = 0;
 };
 
@@ -235,6 +248,8 @@ struct logoskg_result {
     long long *trip_chunk_first = nullptr;  // [chunks + 1] with a whitelist: allowed triples before the chunk
     std::vector<int64_t> trip_off_host;  // [trip_q1 - trip_q0 + 1]
     std::vector<logoskg_hop_stats> stats;
+    mutable hipStream_t last_stream = nullptr;  // stream of the latest call that used the result
+    bool complete = false;  // logoskg_khop ran to its end: every non-zero line of the planes has its bit in act
 };
 
 namespace lkg {

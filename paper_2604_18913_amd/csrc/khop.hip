@@ -742,6 +742,41 @@ k_pull_finish(const int32_t *__restrict__ rows, long long n, unsigned long long 
     }
 }
 
+// ---------------------------------------------------------------- planes back to zero
+// A finished result's planes are zero except in the lines of entities that have their bit in some
+// level's active bitmap: when the result is released those lines (of the level and of visited) and
+// the bitmaps are cleared, so that the next call that gets the block starts from zeros without a
+// fill of all k + 2 planes.  One wavefront per 64 entities, W lanes per line.
+template <int W>
+__global__ void __launch_bounds__(256)
+k_sparse_clear(long long Epad, int levels, uint32_t *act, long long actw, unsigned long long *visited,
+               unsigned long long *level_planes, long long plane, unsigned long long *live) {
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < levels * 16; i += blockDim.x) live[i] = 0ull;
+    const long long base = ((long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * 64;
+    if (base >= Epad) return;  // Epad is a multiple of 64
+    constexpr int GPW = 64 / W;
+    const int g = lane() / W, lw = lane() & (W - 1);
+    unsigned long long any = 0;
+    for (int h = 0; h <= levels; ++h) {  // the levels, then visited with the union of their bits
+        unsigned long long m = any;
+        unsigned long long *dst = visited;
+        if (h < levels) {
+            uint32_t *a = act + (size_t)h * actw + base / 32;
+            m = ((unsigned long long)a[1] << 32) | (unsigned long long)a[0];
+            any |= m;
+            dst = level_planes + (size_t)h * plane;
+            if (m && lane() < 2) a[lane()] = 0u;
+        }
+        if (m == 0) continue;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            const int e = i * GPW + g;
+            if ((m >> e) & 1ull) dst[((size_t)base + e) * W + lw] = 0ull;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- host side
 static inline unsigned blocks_for(long long threads, int block) {
     return (unsigned)((threads + block - 1) / block);
@@ -921,7 +956,23 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,
                     r->lvl_mega_base, r->d_level_off, r->trip_ent, r->trip_off,
                     r->trip_chunk_entry, r->trip_chunk_first, r->tile_ent, r->cpos, r->act_chunk};
-    for (void *p : ptrs) g->pool.release(p);
+    constexpr int n = (int)(sizeof(ptrs) / sizeof(ptrs[0]));
+    bool zeroed[n] = {};
+    const hipStream_t st = r->last_stream;
+    if (r->complete && r->visited && r->act) {  // hand the planes and the bitmaps back as zeros
+        ProfScope ps(g->prof, KK_CLEAR, st);
+        const long long plane = r->Epad * r->W, actw = r->Epad / 32;
+        const dim3 grid(blocks_for(r->Epad / 64, 4)), block(256);
+        switch (r->W) {
+            case 1: k_sparse_clear<1><<<grid, block, 0, st>>>(r->Epad, r->k + 1, r->act, actw, r->visited, r->levels, plane, r->live); break;
+            case 4: k_sparse_clear<4><<<grid, block, 0, st>>>(r->Epad, r->k + 1, r->act, actw, r->visited, r->levels, plane, r->live); break;
+            default: k_sparse_clear<16><<<grid, block, 0, st>>>(r->Epad, r->k + 1, r->act, actw, r->visited, r->levels, plane, r->live); break;
+        }
+        if (hipGetLastError() == hipSuccess) zeroed[0] = zeroed[1] = true;
+        if (g->prof.on && r->n_active > 0) g->prof.acc[KK_CLEAR].units[3] += 2 * r->n_active * r->W;
+    }
+    // the blocks may still be in use by work on the stream of the result's last call
+    g->pool.release_after(ptrs, zeroed, n, st);
     delete r;
 }
 
@@ -965,11 +1016,13 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     // visited and the level planes are one allocation, the active bitmaps and the live words
     // another: each is cleared by one fill
     const size_t act_bytes = actw * 4 * (size_t)(k + 1), live_bytes = (size_t)16 * 8 * (size_t)(k + 1);
-    if ((s = g->pool.alloc((void **)&r->visited, plane * 8 * (size_t)(k + 2))) != LOGOSKG_OK) return fail(s);
+    r->last_stream = st;
+    bool planes_zero = false, act_zero = false;  // a block released by an earlier result comes back cleared
+    if ((s = g->pool.alloc((void **)&r->visited, plane * 8 * (size_t)(k + 2), st, &planes_zero)) != LOGOSKG_OK) return fail(s);
     r->levels = r->visited + plane;
-    if ((s = g->pool.alloc((void **)&r->act, act_bytes + live_bytes)) != LOGOSKG_OK) return fail(s);
+    if ((s = g->pool.alloc((void **)&r->act, act_bytes + live_bytes, st, &act_zero)) != LOGOSKG_OK) return fail(s);
     r->live = reinterpret_cast<unsigned long long *>(reinterpret_cast<char *>(r->act) + act_bytes);
-    if (r->has_mask && (s = g->pool.alloc((void **)&r->allow, (size_t)g->R * W * 8)) != LOGOSKG_OK) return fail(s);
+    if (r->has_mask && (s = g->pool.alloc((void **)&r->allow, (size_t)g->R * W * 8, st)) != LOGOSKG_OK) return fail(s);
 
 #define KH(call)                                  \
     do {                                          \
@@ -979,10 +1032,12 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
 
     {
         ProfScope ps(g->prof, KK_CLEAR, st);
-        KH(hipMemsetAsync(r->visited, 0, plane * 8 * (size_t)(k + 2), st));
-        KH(hipMemsetAsync(r->act, 0, act_bytes + live_bytes, st));
+        if (!planes_zero) {
+            KH(hipMemsetAsync(r->visited, 0, plane * 8 * (size_t)(k + 2), st));
+            g->prof.acc[KK_CLEAR].units[3] += g->prof.on ? (long long)(plane * (size_t)(k + 2)) : 0;
+        }
+        if (!act_zero) KH(hipMemsetAsync(r->act, 0, act_bytes + live_bytes, st));
         KH(hipMemsetAsync(g->d_ctr, 0, C_TOTAL * sizeof(unsigned long long), st));
-        g->prof.acc[KK_CLEAR].units[3] += g->prof.on ? (long long)(plane * (size_t)(k + 2)) : 0;
     }
     g->prof.begin(KK_SEED, st);
     if (r->has_mask) {
@@ -1049,6 +1104,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
         if ((s = count_reached(r, st)) != LOGOSKG_OK) return fail(s);
     }
 #undef KH
+    r->complete = true;
     *out = r;
     return LOGOSKG_OK;
 }

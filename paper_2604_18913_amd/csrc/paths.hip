@@ -91,6 +91,7 @@ static logoskg_status launch_paths(logoskg_graph *g, const logoskg_result *r, co
                                    const int32_t *target, const int32_t *length, int64_t n_pairs, int32_t max_paths,
                                    int32_t *path_count, int32_t *path_edges, void *ws, hipStream_t st) {
     const int k = r->k;
+    r->last_stream = st;
     const size_t per = (size_t)n_pairs * (size_t)std::max(k, 1) * 4;
     int32_t *sv = (int32_t *)ws;
     uint32_t *sp = (uint32_t *)((char *)ws + per);

@@ -1131,9 +1131,9 @@ static logoskg_status ensure_active_list(logoskg_result *r, hipStream_t st) {
     logoskg_graph *g = r->g;
     if (r->tile_ent || g->num_shards > 1) return LOGOSKG_OK;
     const long long actw = r->Epad / 32, nchunks = (actw + kActChunkWords - 1) / kActChunkWords;
-    LKG_TRY(g->pool.alloc((void **)&r->tile_ent, ((size_t)r->Epad + 64) * sizeof(int32_t)));
-    LKG_TRY(g->pool.alloc((void **)&r->cpos, (size_t)r->Epad * sizeof(int32_t)));
-    LKG_TRY(g->pool.alloc((void **)&r->act_chunk, ((size_t)nchunks + 2) * sizeof(uint32_t) + 8));
+    LKG_TRY(g->pool.alloc((void **)&r->tile_ent, ((size_t)r->Epad + 64) * sizeof(int32_t), st));
+    LKG_TRY(g->pool.alloc((void **)&r->cpos, (size_t)r->Epad * sizeof(int32_t), st));
+    LKG_TRY(g->pool.alloc((void **)&r->act_chunk, ((size_t)nchunks + 2) * sizeof(uint32_t) + 8, st));
     r->d_nact = reinterpret_cast<unsigned long long *>(r->act_chunk + (nchunks + 1) / 2 * 2);
     r->n_active = -1;
     ProfScope ps(g->prof, KK_SCAN, st);
@@ -1155,10 +1155,11 @@ static logoskg_status count_plane(logoskg_result *r, const unsigned long long *p
     const long long ntiles = r->Epad / kTileEntities;
     const long long nsuper = (ntiles + kSuperTiles - 1) / kSuperTiles;
     const long long nmega = (nsuper + kMegaSupers - 1) / kMegaSupers;
-    if (!*tile_base) LKG_TRY(g->pool.alloc((void **)tile_base, (size_t)ntiles * Qp * 2));
-    if (!*super_base) LKG_TRY(g->pool.alloc((void **)super_base, (size_t)nsuper * Qp * 4));
-    if (!*mega_base) LKG_TRY(g->pool.alloc((void **)mega_base, (size_t)nmega * Qp * 4));
-    if (!*d_off) LKG_TRY(g->pool.alloc((void **)d_off, (size_t)(Qp + 1) * 8));
+    r->last_stream = st;
+    if (!*tile_base) LKG_TRY(g->pool.alloc((void **)tile_base, (size_t)ntiles * Qp * 2, st));
+    if (!*super_base) LKG_TRY(g->pool.alloc((void **)super_base, (size_t)nsuper * Qp * 4, st));
+    if (!*mega_base) LKG_TRY(g->pool.alloc((void **)mega_base, (size_t)nmega * Qp * 4, st));
+    if (!*d_off) LKG_TRY(g->pool.alloc((void **)d_off, (size_t)(Qp + 1) * 8, st));
     LKG_TRY(ensure_active_list(r, st));
     {
         ProfScope ps(g->prof, KK_COUNT, st);
@@ -1386,6 +1387,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
+    r->last_stream = st;
     const int W = r->W;
     FillArgs a;
     a.E = g->E; a.Q = r->Q; a.k = r->k; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
@@ -1499,6 +1501,7 @@ extern "C" logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t 
     if (!entity) { set_error("entity buffer is NULL"); return LOGOSKG_EINVAL; }
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
+    r->last_stream = (hipStream_t)stream;
     const int W = r->W;
     FillArgs a = {};
     // the level plane plays the part of the visited plane; no hop numbers are asked for
@@ -1523,6 +1526,7 @@ extern "C" logoskg_status logoskg_result_traversed(logoskg_result *r, int64_t *t
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
+    r->last_stream = st;
     const int W = r->W;
     const long long ntiles = r->Epad / kTileEntities;
     const long long nblocks = (ntiles + kMegaSupers - 1) / kMegaSupers;

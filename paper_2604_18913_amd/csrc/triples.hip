@@ -336,6 +336,7 @@ extern "C" logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int3
     if (g->num_shards > 1) { set_error("active triples need a resident (unsharded) graph"); return LOGOSKG_EINVAL; }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
+    r->last_stream = st;
     drop_prepared(r);
     LKG_TRY(ensure_out_eid(g, st));
     // level h-1 of every query, then the lists of the range
@@ -447,6 +448,7 @@ extern "C" logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_
     logoskg_graph *g = r->g;
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
+    r->last_stream = st;
     const long long total = r->trip_total, nchunks = (total + kBlock - 1) / kBlock;
     dim3 grid(blocks_for((nchunks + kExpandChunks - 1) / kExpandChunks, 1)), block(kBlock);
     {
