@@ -377,6 +377,7 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
         if (g->ev_join[i]) (void)hipEventDestroy(g->ev_join[i]);
     }
     if (g->ev_fork) (void)hipEventDestroy(g->ev_fork);
+    if (g->ev_rows) (void)hipEventDestroy(g->ev_rows);
 
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
                     g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,

@@ -195,6 +195,7 @@ struct logoskg_graph {
     bool row_pred_tried = false;
     unsigned long long *plane_buf = nullptr;  // plane words of the bit-sliced predecessor pass (same first use)
     size_t plane_buf_bytes = 0;
+    hipEvent_t ev_rows = nullptr;
 
     // side streams (default priority) so that the independent result kernels of a fetch overlap
     hipStream_t side[2] = {nullptr, nullptr};
@@ -347,6 +348,7 @@ struct FillArgs {
     unsigned long long *plane_buf;  // bit-sliced plane words between k_pred_walk and k_pred_emit, or NULL
     size_t plane_buf_bytes;
     int emit_eid_cap, emit_line_cap;  // capacities of k_pred_emit's two LDS tables (entries / lines)
+    void *ev_rows;                    // host side: event between the block-per-row kernel and the list writer
     long long tile_begin, tile_count;  // tiles this predecessor launch covers
     long long plane;   // words per plane
     long long actw;    // uint32 words per active bitmap

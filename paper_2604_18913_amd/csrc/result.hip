@@ -610,8 +610,8 @@ __global__ void __launch_bounds__(64 * W) k_pred(FillArgs a) {
 // few instructions and a store instruction covers one contiguous piece of a list.  The loop holds
 // no load from memory (the edge ids of the tile's short rows are staged in LDS once per block), so
 // nothing in it waits for its own stores.  Rows of more than 32 entries belong to the row
-// kernels: such an entity's predecessors come from row_pred (rows below hub_min, whose kernel ran
-// before on the same stream) or are left to the block-per-row kernel.
+// kernels: such an entity's predecessors come from row_pred, which those kernels fill before
+// this one starts (or, without that buffer, the row kernels write them to the lists themselves).
 constexpr int kSlicedMaxK = 6;     // hop + 1 <= 7 fits three bits
 
 __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
@@ -762,8 +762,9 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
 // A block = 16 consecutive tiles (one wavefront each) x every wsplit-th word of the fetched range.
 // 8 wavefronts per SIMD = at most 64 vector registers.
 constexpr int kEmitTiles = 16;
-constexpr int kEmitEids = 10240;  // LDS: edge ids of the short rows of the block's 1,024 entities
-constexpr int kEmitLines = 96;    // LDS: row_pred values (64 queries each) of the block's entities with rows of 33 .. hub_min-1 entries
+constexpr int kEmitEids = 9216;   // LDS: edge ids of the short rows of the block's 1,024 entities
+constexpr int kEmitLines = 160;   // LDS: row_pred values (64 queries each) of the block's entities with longer rows
+// (36 KB + 40 KB: two blocks per CU)
 
 // STAGED: the edge ids of the block's short rows fit eid_tab; LINES: the block's row_pred entities
 // fit rp_tab.  Otherwise the loop reads the edge ids from memory / a pass of its own moves the
@@ -848,7 +849,7 @@ k_pred_emit(FillArgs a, const unsigned long long *__restrict__ codes, const unsi
     // its line of row_pred (by query), or nowhere (the block-per-row kernel writes them).  Seeds
     // get their -1 in the loop.
     const bool longrow = wdeg > (uint32_t)kTailMaxDegree;
-    const bool by_query = longrow && a.row_pred && wdeg < (uint32_t)a.hub_min;
+    const bool by_query = longrow && a.row_pred;
     int li = 0;
     if (by_query) li = (int)(a.long_index[ew] - a.row_base);
     const int n_stage = longrow ? 0 : (int)wdeg;
@@ -1215,6 +1216,7 @@ logoskg_status prepare_row_pred(logoskg_graph *g, hipStream_t st) {
         g->plane_buf = nullptr;
         g->plane_buf_bytes = 0;
     }
+    LKG_HIP(hipEventCreateWithFlags(&g->ev_rows, hipEventDisableTiming));
 
     const long long rows = g->num_shards > 1 ? max_chunk_rows(g) : (long long)g->in_rows.n_long;
     if (rows <= 0 || (size_t)rows * 4096 > ((size_t)8 << 30)) return LOGOSKG_OK;
@@ -1277,12 +1279,23 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         // and one block per hop level of a row: the levels are independent, and the longest row
         // sets the duration of the launch
         const unsigned levels = (unsigned)std::max(a.k, 1);
-        if (giants > 0)
-            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
-        if (n_hub_rows > giants)
-            k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
-                a, giants);
+        if (a.row_pred) {  // into the row buffer, from which the list writer takes them
+            if (giants > 0)
+                k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
+            if (n_hub_rows > giants)
+                k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
+                    a, giants);
+        } else {  // straight into the lists
+            if (giants > 0)
+                k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
+            if (n_hub_rows > giants)
+                k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
+                    a, giants);
+        }
     }
+    // the list writer reads the row buffer: it starts behind the block-per-row kernel
+    const bool rows_first = n_hub_rows > 0 && a.row_pred && mt && st_hub != st_tiles && a.ev_rows;
+    if (rows_first) (void)hipEventRecord((hipEvent_t)a.ev_rows, st_hub);
     if (a.tile_count > 0 && mt) {
         // in chunks of tiles whose code bytes (64 per entity and word) and visited words fit the buffer
         const int w0 = a.q0 / 64, nw = (a.q1 - 1) / 64 - w0 + 1;
@@ -1305,6 +1318,7 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
                 if (a.k <= 2) k_pred_walk<2, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
                 else k_pred_walk<3, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
             }
+            if (rows_first && c0 == 0) (void)hipStreamWaitEvent(st_tiles, (hipEvent_t)a.ev_rows, 0);
             ProfScope ps(prof, KK_PRED, st_tiles);
             k_pred_emit<<<ge, dim3(kEmitTiles * 64), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wsplit,
                                                                    a.emit_eid_cap, a.emit_line_cap);
@@ -1401,7 +1415,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.in_off = g->in_off; a.in_sub = g->in_sub; a.in_eid = g->in_eid; a.in_rel = g->in_rel;
     a.rows = g->in_rows.longrows;
     a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
-    a.plane_buf = nullptr; a.plane_buf_bytes = 0;
+    a.plane_buf = nullptr; a.plane_buf_bytes = 0; a.ev_rows = nullptr;
     a.n_giant_rows = g->num_shards > 1 ? -1 : g->in_rows.n_giant;
     if (pred && W == 16) {
         LKG_TRY(prepare_row_pred(g, st));
@@ -1409,6 +1423,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
         a.row_pred = g->row_pred;
         a.plane_buf = g->plane_buf;
         a.plane_buf_bytes = g->plane_buf_bytes;
+        a.ev_rows = g->ev_rows;
         // (LOGOSKG_EMIT_CAPS="e,l" shrinks the two LDS tables of k_pred_emit so that tests reach its other paths)
         a.emit_eid_cap = kEmitEids;
         a.emit_line_cap = kEmitLines;
