@@ -18,21 +18,30 @@
 
 namespace lkg {
 
-__global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long long plane,
-                        const unsigned long long *__restrict__ levels,
-                        const unsigned long long *__restrict__ allow, const uint32_t *__restrict__ in_off,
-                        const int32_t *__restrict__ in_sub, const uint16_t *__restrict__ in_rel,
-                        const int32_t *__restrict__ in_eid, const int32_t *__restrict__ query_idx,
-                        const int32_t *__restrict__ target, const int32_t *__restrict__ length, int max_paths,
-                        int32_t *path_count,
-                        int32_t *path_edges, int32_t *stk_vertex, uint32_t *stk_pos, int32_t *stk_edge) {
-    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_pairs) return;
+// One wavefront per (query, target) pair.  The depth-first state is the same in every lane: all
+// lanes compute it, write it to the pair's three stacks (same address, same value) and read it
+// back, so a lane only ever reads what it has written itself.  An object row is scanned 64
+// entries at a time: every lane tests one entry (subject one level closer for the query, relation
+// allowed) and a ballot gives the admissible entries in ascending position = ascending edge id,
+// so a row of a hundred thousand entries is not a single lane's loop.
+__global__ void __launch_bounds__(256)
+k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long long plane,
+        const unsigned long long *__restrict__ levels, const unsigned long long *__restrict__ allow,
+        const uint32_t *__restrict__ in_off, const int32_t *__restrict__ in_sub,
+        const uint16_t *__restrict__ in_rel, const int32_t *__restrict__ in_eid,
+        const int32_t *__restrict__ query_idx, const int32_t *__restrict__ target,
+        const int32_t *__restrict__ length, int max_paths, int32_t *path_count, int32_t *path_edges,
+        int32_t *stk_vertex, uint32_t *stk_pos, int32_t *stk_edge) {
+    const long long i = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (i >= n_pairs) return;  // wave-uniform
+    const int v_lane = lane();
     int32_t *out = path_edges + (size_t)i * max_paths * k;
-    for (long long x = 0; x < (long long)max_paths * k; ++x) out[x] = -1;
-    int q = query_idx[i], v = target[i];
-    path_count[i] = 0;
-    if ((uint32_t)q >= (uint32_t)Q || (uint32_t)v >= (uint32_t)E) return;
+    for (long long x = v_lane; x < (long long)max_paths * k; x += 64) out[x] = -1;
+    const int q = query_idx[i], v = target[i];
+    if ((uint32_t)q >= (uint32_t)Q || (uint32_t)v >= (uint32_t)E) {
+        if (v_lane == 0) path_count[i] = 0;
+        return;
+    }
     const int w = q >> 6;
     const unsigned long long bit = 1ull << (q & 63);
     int d = -1;
@@ -43,8 +52,10 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
         for (int h = 0; h <= k; ++h)
             if (levels[(size_t)h * plane + (size_t)v * W + w] & bit) { d = h; break; }
     }
-    if (d < 0) return;
-    if (d == 0) { path_count[i] = 1; return; }
+    if (d <= 0) {  // not reached: no path; a seed: one empty path
+        if (v_lane == 0) path_count[i] = d == 0 ? 1 : 0;
+        return;
+    }
     // explicit stack, entry l (1..d) = the vertex at hop l of the partial path, the next
     // in-edge position to try for it, and the edge chosen into it
     int32_t *sv = stk_vertex + (size_t)i * k - 1;
@@ -54,23 +65,44 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
     sv[d] = v;
     sp[d] = in_off[v];
     while (l <= d && found < max_paths) {
-        int x = sv[l];
-        uint32_t j = sp[l], hi = in_off[x + 1];
+        const int x = sv[l];
+        uint32_t j = sp[l];
+        const uint32_t hi = in_off[x + 1];
         bool descended = false;
         const unsigned long long *lv = levels + (size_t)(l - 1) * plane;
-        for (; j < hi; ++j) {
-            int s = in_sub[j];
-            if (!(lv[(size_t)s * W + w] & bit)) continue;
-            if (allow && !(allow[(size_t)in_rel[j] * W + w] & bit)) continue;
-            se[l] = in_eid[j];
-            if (l == 1) {
-                int32_t *row = out + (size_t)found * k;
-                for (int a = 1; a <= d; ++a) row[a - 1] = se[a];
-                if (++found >= max_paths) break;
-            } else {
-                sp[l] = j + 1;
-                sv[l - 1] = s;
-                sp[l - 1] = in_off[s];
+        while (j < hi && found < max_paths) {
+            const uint32_t jj = j + (uint32_t)v_lane;
+            int s = 0, eid = 0;
+            bool ok = false;
+            if (jj < hi) {
+                s = in_sub[jj];
+                ok = (lv[(size_t)s * W + w] & bit) != 0ull;
+                if (ok && allow) ok = (allow[(size_t)in_rel[jj] * W + w] & bit) != 0ull;
+                if (ok) eid = in_eid[jj];
+            }
+            unsigned long long m = __ballot(ok);
+            if (m == 0ull) {
+                j += 64;
+                continue;
+            }
+            if (l == 1) {  // every admissible entry of the chunk ends a path, in this order
+                while (m && found < max_paths) {
+                    const int f = __builtin_ctzll(m);
+                    m &= m - 1;
+                    int32_t *row = out + (size_t)found * k;
+                    for (int a = 2 + v_lane; a <= d; a += 64) row[a - 1] = se[a];
+                    const int ef = __shfl(eid, f);
+                    if (v_lane == 0) row[0] = ef;
+                    ++found;
+                }
+                j += 64;
+            } else {  // take the first one and go down; the rest of the row is tried after coming back
+                const int f = __builtin_ctzll(m);
+                se[l] = __shfl(eid, f);
+                sp[l] = j + (uint32_t)f + 1u;
+                const int sf = __shfl(s, f);
+                sv[l - 1] = sf;
+                sp[l - 1] = in_off[sf];
                 --l;
                 descended = true;
                 break;
@@ -78,7 +110,7 @@ __global__ void k_paths(long long n_pairs, int Q, int k, int W, int32_t E, long 
         }
         if (!descended) ++l;  // this vertex's row is exhausted: back to the vertex after it
     }
-    path_count[i] = found;
+    if (v_lane == 0) path_count[i] = found;
 }
 
 }  // namespace lkg
@@ -96,7 +128,8 @@ static logoskg_status launch_paths(logoskg_graph *g, const logoskg_result *r, co
     int32_t *sv = (int32_t *)ws;
     uint32_t *sp = (uint32_t *)((char *)ws + per);
     int32_t *se = (int32_t *)((char *)ws + 2 * per);
-    k_paths<<<dim3((unsigned)((n_pairs + 127) / 128)), dim3(128), 0, st>>>(
+    ProfScope ps(g->prof, KK_PATHS, st);
+    k_paths<<<dim3((unsigned)((n_pairs + 3) / 4)), dim3(256), 0, st>>>(
         n_pairs, r->Q, k, r->W, g->E, r->Epad * r->W, (const unsigned long long *)r->levels,
         r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, g->in_sub, g->in_rel, g->in_eid,
         query_idx, target, length, max_paths, path_count, path_edges, sv, sp, se);

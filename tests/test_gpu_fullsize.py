@@ -238,7 +238,11 @@ def test_config3_full_size_masks_and_paths(k):
     t0 = time.time()
     cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, pq_local, pt, 16, sm)
     log(f"oracle paths: {time.time() - t0:.1f}s, {int(cnt_o.sum())} paths")
+    g.profile_enable(1)
+    g.profile_read()
     cnt, edges = g.paths(res, qs[pq_local].astype(np.int32), pt, 16)
+    log(f"logoskg_paths for {len(pt)} pairs: kernel {g.profile_read()['paths']['total_ms']:.3f} ms")
+    g.profile_enable(0)
     assert np.array_equal(cnt.cpu().numpy(), cnt_o)
     assert np.array_equal(edges.cpu().numpy(), edges_o)
     res.close()
