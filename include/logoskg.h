@@ -322,9 +322,10 @@ void logoskg_result_free(logoskg_result *r);
  * path_edges[i][p][0..d), the rest of each row of k entries is -1.
  * path_count[i] = number written (0 if the target is not reached; 1 empty
  * path if it is a seed).  All four arrays are device memory; path_edges is
- * int32[n_pairs][max_paths][k].  Needs a resident (unsharded) graph.  The
- * call takes its working memory from the graph's pool and returns after
- * `stream` has been synchronised.
+ * int32[n_pairs][max_paths][k].  On a sharded graph the kernel reads the
+ * object rows it walks from pinned host memory, in place.  The call takes its
+ * working memory from the graph's pool and returns after `stream` has been
+ * synchronised.
  */
 logoskg_status logoskg_paths(logoskg_graph *g, const logoskg_result *r, const int32_t *query_idx,
                              const int32_t *target, int64_t n_pairs, int32_t max_paths,

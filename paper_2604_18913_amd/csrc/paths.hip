@@ -128,10 +128,18 @@ static logoskg_status launch_paths(logoskg_graph *g, const logoskg_result *r, co
     int32_t *sv = (int32_t *)ws;
     uint32_t *sp = (uint32_t *)((char *)ws + per);
     int32_t *se = (int32_t *)((char *)ws + 2 * per);
+    // a sharded graph keeps its object-sorted triples in pinned host memory: the kernel reads the
+    // rows it walks from there
+    const int32_t *in_sub = g->in_sub, *in_eid = g->in_eid;
+    const uint16_t *in_rel = g->in_rel;
+    if (g->num_shards > 1 && !shard_in_arrays(g, &in_sub, &in_rel, &in_eid)) {
+        set_error("the object-sorted triples of the sharded graph are not available");
+        return LOGOSKG_EINTERNAL;
+    }
     ProfScope ps(g->prof, KK_PATHS, st);
     k_paths<<<dim3((unsigned)((n_pairs + 3) / 4)), dim3(256), 0, st>>>(
         n_pairs, r->Q, k, r->W, g->E, r->Epad * r->W, (const unsigned long long *)r->levels,
-        r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, g->in_sub, g->in_rel, g->in_eid,
+        r->has_mask ? (const unsigned long long *)r->allow : nullptr, g->in_off, in_sub, in_rel, in_eid,
         query_idx, target, length, max_paths, path_count, path_edges, sv, sp, se);
     LKG_HIP(hipGetLastError());
     return LOGOSKG_OK;
@@ -148,7 +156,6 @@ static logoskg_status check_path_args(logoskg_graph *g, const logoskg_result *r,
         set_error("NULL argument");
         return LOGOSKG_EINVAL;
     }
-    if (g->num_shards > 1) { set_error("path listing needs a resident graph"); return LOGOSKG_EINVAL; }
     return LOGOSKG_OK;
 }
 

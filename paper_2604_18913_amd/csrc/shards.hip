@@ -677,6 +677,17 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipSt
     return LOGOSKG_OK;
 }
 
+// The object-sorted triples of a sharded graph (pinned host memory, which kernels can read in
+// place over the host link): for the few rows a path listing walks.
+bool shard_in_arrays(const logoskg_graph *g, const int32_t **sub, const uint16_t **rel, const int32_t **eid) {
+    const ShardSet *ss = (const ShardSet *)g->shards;
+    if (!ss || !ss->h_in_sub || !ss->h_in_eid || !ss->h_in_rel) return false;
+    *sub = ss->h_in_sub;
+    *rel = ss->h_in_rel;
+    *eid = ss->h_in_eid;
+    return true;
+}
+
 void shard_info(const logoskg_graph *g, logoskg_graph_info *o) {
     const ShardSet *ss = (const ShardSet *)g->shards;
     if (!ss) return;

@@ -80,8 +80,25 @@ def test_byte_budget_and_errors():
     with pytest.raises(m.LogosKGError):
         g.khop(w.seed_off, w.seeds, w.k, direction="pull")
     res = g.khop(w.seed_off, w.seeds, w.k)
-    with pytest.raises(m.LogosKGError):
-        g.paths(res, [0], [0], 4)  # path listing needs a resident graph
+    # shortest paths on a sharded graph: the object rows are read from pinned host memory
+    pq, pt = kggen.sample_reached_pairs(7, want[0], want[1], 600)
+    cnt, edges = g.paths(res, pq, pt, 16)
+    cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, pq, pt, 16,
+                                  w.rel_mask)
+    assert np.array_equal(cnt.cpu().numpy(), cnt_o) and np.array_equal(edges.cpu().numpy(), edges_o)
+    rw = g.khop(w.seed_off, w.seeds, 2, walk_exact=True)
+    lo, lent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, w.seed_off[:9], w.seeds[:w.seed_off[8]], 2, None)
+    wq, wt, wl = [], [], []
+    for q in range(8):
+        a2, b2 = int(lo[2 * 8 + q]), int(lo[2 * 8 + q + 1])
+        for v in lent[a2:b2][:20]:
+            wq.append(q); wt.append(int(v)); wl.append(2)
+    if wq:
+        c1, e1 = g.walks(rw, wq, wt, wl, 16)
+        c2, e2 = oracle.walk_paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off[:9], w.seeds[:w.seed_off[8]], 2,
+                                   wq, wt, wl, 16, None)
+        assert np.array_equal(c1.cpu().numpy(), c2) and np.array_equal(e1.cpu().numpy(), e2)
+    rw.close()
     # sub-ranges of queries stream the object-sorted chunks again and give the same lists
     ent, hop, pred = res.fetch(100, 164)
     off = res.offsets()
