@@ -21,6 +21,15 @@ import numpy as np
 
 BASE_SEED = 2604189130
 
+# Optional callable(str): told when a step of a generator ends (the large workloads take
+# minutes to draw; a caller that must show it is alive sets this).
+progress = None
+
+
+def _step(what: str) -> None:
+    if progress is not None:
+        progress(what)
+
 
 @dataclass
 class Workload:
@@ -118,8 +127,10 @@ def _assemble(rng, T, E, R, s_stubs, o_stubs, draw_rel):
     locality.  Ids are whatever the stub lists hold (callers may pass dense
     ranks and map them back)."""
     n = int(min(s_stubs.shape[0], o_stubs.shape[0], T))
-    keys = np.unique(_pack_keys(s_stubs[:n], draw_rel(n),
-                                o_stubs[rng.permutation(o_stubs.shape[0])[:n]], E, R))
+    keys = _pack_keys(s_stubs[:n], draw_rel(n), o_stubs[rng.permutation(o_stubs.shape[0])[:n]], E, R)
+    _step(f"generator: {n:,} stub pairs drawn")
+    keys = np.unique(keys)
+    _step(f"generator: {keys.shape[0]:,} distinct triples")
     for _ in range(5):
         missing = T - keys.shape[0]
         if missing <= 0:
@@ -132,8 +143,10 @@ def _assemble(rng, T, E, R, s_stubs, o_stubs, draw_rel):
         keep[1:] = merged[1:] != merged[:-1]
         keys = merged[keep]
         del merged, keep, new
+        _step(f"generator: topped up to {keys.shape[0]:,} distinct triples")
     perm = rng.permutation(keys.shape[0])[:T]
     s, r, o = _unpack_keys(keys[perm], E, R)
+    _step("generator: triples shuffled")
     return s, r, o
 
 
@@ -185,6 +198,7 @@ def _correlated_powerlaw_graph(rng, E, T, R, alpha, cap, rel_alpha):
     perm = rng.permutation(E)
     dout = np.sort(draw_degrees(rng, E, T, alpha, dmin, cap))[::-1]
     din = np.sort(draw_degrees(rng, E, T, alpha, dmin, cap))[::-1]
+    _step("generator: degree sequences drawn")
     if rel_alpha is None:
         draw_rel = lambda n: rng.integers(0, R, size=n)
     else:
@@ -211,6 +225,7 @@ def _finish_manifest(w: Workload, extra: dict) -> Workload:
         num_subjects=int((outdeg > 0).sum()), num_objects=int((indeg > 0).sum()),
         live_seed_fraction=float(live.mean()) if live.size else 0.0,
         masked=w.rel_mask is not None, **extra)
+    _step(f"generator: {w.name} done")
     return w
 
 

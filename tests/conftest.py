@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    import helpers
+    helpers.PYTEST_CONFIG = config
 
 
 def _have_gpu():

@@ -2,7 +2,25 @@
 the oracle.  Nothing here is used by the product path."""
 from __future__ import annotations
 
+import sys
+import time
+
 import numpy as np
+
+PYTEST_CONFIG = None  # set by conftest.py
+
+
+def progress(*a):
+    """One time-stamped line on the real terminal, past pytest's capture: the full-size cases run
+    for minutes, and every finished step of theirs says so."""
+    line = time.strftime("%H:%M:%S") + " " + " ".join(str(x) for x in a)
+    capman = PYTEST_CONFIG.pluginmanager.getplugin("capturemanager") if PYTEST_CONFIG is not None else None
+    if capman is None:
+        print(line, flush=True)
+        return
+    with capman.global_and_fixture_disabled():
+        sys.stderr.write("\n" + line)
+        sys.stderr.flush()
 
 
 def pack_mask(allowed_lists, R):

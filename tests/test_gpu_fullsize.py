@@ -14,7 +14,7 @@ import pytest
 
 import kggen
 import oracle
-from helpers import check_invariants
+from helpers import check_invariants, progress
 
 pytestmark = pytest.mark.gpu
 
@@ -48,7 +48,14 @@ def lkg():
 
 
 def log(*a):
-    print(time.strftime("%H:%M:%S"), *a, flush=True)
+    progress(*a)
+
+
+@pytest.fixture(autouse=True)
+def generator_reports_its_steps():
+    kggen.progress = progress
+    yield
+    kggen.progress = None
 
 
 def sampled_queries(Q, n, seed, counts=None):
