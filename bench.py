@@ -459,6 +459,7 @@ def main():
         else:
             o = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, so, sd, k, mk)
         t_cpu = time.perf_counter() - t0
+        cores = oracle.num_threads()  # read here: the single-thread run below leaves the OpenMP setting at 1
         # the oracle's own index build (an empty batch builds it and runs no query), and a
         # single-thread run on the first 64 queries
         t0 = time.perf_counter()
@@ -486,7 +487,7 @@ def main():
             same = (np.array_equal(off[: nq + 1], o[0]) and np.array_equal(e2.cpu().numpy(), o[1])
                     and np.array_equal(h2.cpu().numpy(), o[2]) and np.array_equal(p2.cpu().numpy(), o[3]))
         got.close()
-        out["cpu_baseline"] = {"value": round(nq / t_cpu, 2), "unit": "queries/s", "cores": oracle.num_threads(),
+        out["cpu_baseline"] = {"value": round(nq / t_cpu, 2), "unit": "queries/s", "cores": cores,
                                "kind": "oracle",
                                "sample": f"first {nq} of the {Q} queries of the same workload, one query per "
                                          f"thread, index build included ({t_cpu:.1f} s)",

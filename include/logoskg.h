@@ -57,7 +57,11 @@ typedef struct {
     int32_t num_shards;              /* 0 or 1: whole graph resident in HBM.  >1: degree-aware
                                         partition of the subjects (Sec. 3.4) into this many
                                         shards kept in pinned host memory and cached in HBM      */
-    int32_t max_resident_shards;     /* cache capacity in shards (the paper's n); 0 = no cap     */
+    int32_t max_resident_shards;     /* cache capacity in sub-graphs (the paper's n); 0 = no cap.
+                                        The cache holds the shards (visited by push hops) and
+                                        the sub-graphs by object range that pull hops visit
+                                        (logoskg_graph_info.num_object_ranges of them), one per
+                                        slot, 6 bytes per triple either way                      */
     uint64_t hbm_shard_budget_bytes; /* cache capacity in bytes; 0 = no cap                      */
     int32_t hub_min_degree;          /* rows with at least this many edges take the
                                         block-per-row kernels; 0 = default (1024).  Never changes
@@ -107,6 +111,9 @@ typedef struct {
     int64_t shard_loads, shard_evictions, shard_hits; /* cache counters since build (Sec. 3.4) */
     int64_t shard_bytes_h2d;
     int64_t shard_bytes_disk;           /* bytes read from the shard files (0 without shard_dir) */
+    int32_t num_object_ranges;          /* sharded graphs: sub-graphs by object range that pull hops visit
+                                           (units of the same cache as the shards); 0 when resident  */
+    int32_t cache_slots;                /* sub-graphs the cache can hold at once (0 when resident)       */
 } logoskg_graph_info;
 
 logoskg_status logoskg_graph_get_info(const logoskg_graph *g, logoskg_graph_info *out);
@@ -172,7 +179,7 @@ logoskg_status logoskg_prefetch_shards(logoskg_graph *g, const int32_t *shards, 
 
 #define LOGOSKG_DIR_AUTO 0u       /* choose push or pull per hop from the frontier's edge count */
 #define LOGOSKG_DIR_PUSH 1u       /* always expand from the frontier's subject rows             */
-#define LOGOSKG_DIR_PULL 2u       /* always gather over the object rows (resident graphs only)  */
+#define LOGOSKG_DIR_PULL 2u       /* always gather over the object rows                         */
 #define LOGOSKG_DIR_MASK 3u
 #define LOGOSKG_NO_COUNTS 4u      /* skip the per-query reached counts (planes only)            */
 #define LOGOSKG_WALK_EXACT 8u     /* Eq. 4 iterated literally, without the visited set: level h
@@ -224,7 +231,8 @@ logoskg_status logoskg_result_get_info(const logoskg_result *r, logoskg_result_i
 
 typedef struct {
     int32_t direction;        /* LOGOSKG_DIR_PUSH or LOGOSKG_DIR_PULL; 0 = hop not run (empty frontier) */
-    int32_t shards_touched;   /* shards with an active subject (1 for resident graphs)                  */
+    int32_t shards_touched;   /* sub-graphs the hop visited: shards with an active subject (push) or
+                                 object ranges (pull); 1 for resident graphs                            */
     int64_t active_rows;      /* subjects in the frontier with >= 1 triple                              */
     int64_t frontier_edges;   /* sum of their out-degrees                                               */
     int64_t rows_scanned;     /* pull: object rows visited that were not already complete (profiling on) */

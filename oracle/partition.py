@@ -11,8 +11,10 @@ INFRASTRUCTURE ONLY, plain Python.
 * shard_accesses: the sub-graphs Algorithm 1 touches, hop by hop (those that
   hold a subject of the current frontier); the algorithm leaves the order inside
   a hop open, the reading taken is ascending shard index on odd hops and
-  descending on even hops.  Pinned by a hand-worked trace in
-  tests/test_oracle_pins.py.
+  descending on even hops.  A hop that the caller says was evaluated by object
+  rows (pull) touches every sub-graph of the partition by object range instead,
+  numbered after the shards, in the same alternating order.  Pinned by
+  hand-worked traces in tests/test_oracle_pins.py.
 * schedule_queries: the batch-processing order of Sec. 3.4 -- queries grouped by
   the sub-graphs their seeds need (through P), identical needs adjacent, the
   input order kept among equals.
@@ -69,8 +71,10 @@ def lru_counts(accesses, capacity: int):
     return loads, evictions, hits
 
 
-def shard_accesses(P, subj, num_entities, k, entity, hop):
-    """entity / hop: concatenated result lists of all queries of one batch."""
+def shard_accesses(P, subj, num_entities, k, entity, hop, pull_hops=(), num_shards=0, num_ranges=0):
+    """entity / hop: concatenated result lists of all queries of one batch.
+    pull_hops: the hops (1-based) evaluated by object rows; they touch the sub-graphs
+    num_shards .. num_shards + num_ranges - 1 (the partition by object range)."""
     deg = np.bincount(subj, minlength=num_entities)
     seq = []
     for h in range(1, k + 1):
@@ -78,7 +82,10 @@ def shard_accesses(P, subj, num_entities, k, entity, hop):
         front = front[deg[front] > 0]
         if front.size == 0:
             break
-        order = sorted(set(int(x) for x in P[front]))
+        if h in pull_hops:
+            order = list(range(num_shards, num_shards + num_ranges))
+        else:
+            order = sorted(set(int(x) for x in P[front]))
         # Alg. 1 does not fix the order in which a hop visits its shards; the reading taken is
         # ascending on odd hops and descending on even ones, so that consecutive hops share the
         # shards at the turning point and a small LRU cache does not thrash

@@ -50,7 +50,8 @@ class _GraphInfo(ctypes.Structure):
                 ("num_in_hubs", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
                 ("pinned_host_bytes", ctypes.c_int64), ("shard_loads", ctypes.c_int64),
                 ("shard_evictions", ctypes.c_int64), ("shard_hits", ctypes.c_int64),
-                ("shard_bytes_h2d", ctypes.c_int64), ("shard_bytes_disk", ctypes.c_int64)]
+                ("shard_bytes_h2d", ctypes.c_int64), ("shard_bytes_disk", ctypes.c_int64),
+                ("num_object_ranges", ctypes.c_int32), ("cache_slots", ctypes.c_int32)]
 
 
 class _ResultInfo(ctypes.Structure):
@@ -268,7 +269,8 @@ class Result:
 
     def close(self):
         if self._h:
-            _load().logoskg_result_free(self._h)
+            if self._g._h:  # a result never outlives its graph: Graph.close releases its results first
+                _load().logoskg_result_free(self._h)
             self._h = None
 
     def __del__(self):

@@ -16,7 +16,7 @@
 
 #include "logoskg.h"
 
-static_assert(sizeof(logoskg_build_opts) == 40 && sizeof(logoskg_graph_info) == 112,
+static_assert(sizeof(logoskg_build_opts) == 40 && sizeof(logoskg_graph_info) == 120,
               "the ctypes binding mirrors these layouts");
 
 namespace lkg {
@@ -387,8 +387,11 @@ void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigne
                        const lkg::RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st);
 void shard_info(const logoskg_graph *g, logoskg_graph_info *o);
 bool shard_in_arrays(const logoskg_graph *g, const int32_t **sub, const uint16_t **rel, const int32_t **eid);
-logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
-                               logoskg_hop_stats *hs);
+void launch_pull_range(logoskg_graph *g, logoskg_result *r, int h, const RowClasses &rc, const int32_t *in_sub,
+                       const uint16_t *in_rel, const unsigned long long *hc, bool want_stats, bool first,
+                       hipStream_t st);
+logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
+                               const unsigned long long *hc, hipStream_t st, logoskg_hop_stats *hs);
 void free_shards(logoskg_graph *g);
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel,
                             const int32_t *obj, const logoskg_build_opts *opts);

@@ -810,37 +810,47 @@ static void launch_push(logoskg_graph *g, logoskg_result *r, int h, const unsign
 }
 
 // STATS: the counting mode runs instantiations of its own, so that kernel statistics of the
-// ordinary ones are not mixed with it
+// ordinary ones are not mixed with it.
+// When most triples leave the frontier the kernels gather every edge's line without asking for
+// its frontier bit first (never in the counting mode: its statistics count frontier lines).
+static inline bool dense_pull(const logoskg_graph *g, const unsigned long long *hc, bool want_stats) {
+    return !want_stats && (long long)hc[C_FEDGES] * 100 >= g->T * (long long)kDensePullPercent;
+}
+
+// live[h-1]: the queries this hop can still reach something for (once per hop).
+template <int W>
+static void launch_live(logoskg_graph *g, logoskg_result *r, int h, bool dense, hipStream_t st) {
+    const size_t plane = (size_t)r->Epad * W;
+    ProfScope ps(g->prof, KK_LIVE, st);
+    unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
+    unsigned long long *live = r->live + (size_t)16 * (h - 1);
+    if (dense) k_live_all<<<dim3(1), dim3(64), 0, st>>>(r->Q, W, live);
+    else k_live<W><<<dim3(nb), dim3(256), 0, st>>>(r->act + (size_t)(r->Epad / 32) * (h - 1), g->E, g->out_off,
+                                                   r->levels + plane * (h - 1), live);
+}
+
+// Pull over the object rows of the work lists `rc`, whose entries index in_sub / in_rel (the whole
+// object-sorted CSR of a resident graph, or one object range of a sharded one in a cache slot).
 template <int W, bool MASK, bool STATS>
-static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_stats,
-                        const unsigned long long *hc, hipStream_t st) {
+static void launch_pull_rows(logoskg_graph *g, logoskg_result *r, int h, const RowClasses &rc, const int32_t *in_sub,
+                             const uint16_t *in_rel, bool dense, hipStream_t st) {
     const size_t plane = (size_t)r->Epad * W;
     const unsigned long long *prev = r->levels + plane * (h - 1);
     unsigned long long *cur = r->levels + plane * h;
     const uint32_t *act_prev = r->act + (size_t)(r->Epad / 32) * (h - 1);
     uint32_t *act_cur = r->act + (size_t)(r->Epad / 32) * h;
-    unsigned long long *live = r->live + (size_t)16 * (h - 1);
-    auto stats = [&](int kind) { return want_stats ? g->d_ctr + C_STATS + 4 * kind : nullptr; };
-    const RowClasses &rc = g->in_rows;
-    // when most triples leave the frontier the kernels gather every edge's line without asking for
-    // its frontier bit first (never in the counting mode: its statistics count frontier lines)
-    const bool dense = !STATS && (long long)hc[C_FEDGES] * 100 >= g->T * (long long)kDensePullPercent;
-    {
-        ProfScope ps(g->prof, KK_LIVE, st);
-        unsigned nb = std::min<unsigned>(2048u, std::max(1u, blocks_for(g->E, 256)));
-        if (dense) k_live_all<<<dim3(1), dim3(64), 0, st>>>(r->Q, W, live);
-        else k_live<W><<<dim3(nb), dim3(256), 0, st>>>(act_prev, g->E, g->out_off, prev, live);
-    }
+    const unsigned long long *live = r->live + (size_t)16 * (h - 1);
+    auto stats = [&](int kind) { return STATS ? g->d_ctr + C_STATS + 4 * kind : nullptr; };
     const int walk = r->walk_exact ? 1 : 0;
     if (rc.n_seg > 0) {
         ProfScope ps(g->prof, KK_PULL_SEG, st);
         const dim3 grid(blocks_for(rc.n_seg, 4)), block(256);
         if (dense)
-            k_pull_seg<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_sub, g->in_rel,
+            k_pull_seg<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, in_sub, in_rel,
                                                                      r->allow, act_prev, prev, live, r->visited, cur,
                                                                      act_cur, stats(KK_PULL_SEG), walk);
         else
-            k_pull_seg<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, g->in_sub, g->in_rel,
+            k_pull_seg<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.seg, rc.n_seg, in_sub, in_rel,
                                                                       r->allow, act_prev, prev, live, r->visited, cur,
                                                                       act_cur, stats(KK_PULL_SEG), walk);
     }
@@ -849,11 +859,11 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
         const long long groups = (rc.n_tail + kTailRows - 1) / kTailRows;
         const dim3 grid(blocks_for(groups * W, 256)), block(256);
         if (dense)
-            k_pull_tail<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow,
+            k_pull_tail<W, MASK, STATS, true><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, in_sub, in_rel, r->allow,
                                                                       act_prev, prev, live, r->visited, cur, act_cur,
                                                                       stats(KK_PULL_TAIL), walk);
         else
-            k_pull_tail<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, g->in_sub, g->in_rel, r->allow,
+            k_pull_tail<W, MASK, STATS, false><<<grid, block, 0, st>>>(rc.tail, rc.n_tail, in_sub, in_rel, r->allow,
                                                                        act_prev, prev, live, r->visited, cur, act_cur,
                                                                        stats(KK_PULL_TAIL), walk);
     }
@@ -865,16 +875,44 @@ static void launch_pull(logoskg_graph *g, logoskg_result *r, int h, bool want_st
 }
 
 template <int W>
+static void pull_rows_w(logoskg_graph *g, logoskg_result *r, int h, const RowClasses &rc, const int32_t *in_sub,
+                        const uint16_t *in_rel, bool dense, bool want_stats, hipStream_t st) {
+    if (r->has_mask) {
+        if (want_stats) launch_pull_rows<W, true, true>(g, r, h, rc, in_sub, in_rel, dense, st);
+        else launch_pull_rows<W, true, false>(g, r, h, rc, in_sub, in_rel, dense, st);
+    } else {
+        if (want_stats) launch_pull_rows<W, false, true>(g, r, h, rc, in_sub, in_rel, dense, st);
+        else launch_pull_rows<W, false, false>(g, r, h, rc, in_sub, in_rel, dense, st);
+    }
+}
+
+// One object range of a pull hop (a sharded graph visits them one after the other; `first`: the
+// live words of the hop are computed before the range).
+void launch_pull_range(logoskg_graph *g, logoskg_result *r, int h, const RowClasses &rc, const int32_t *in_sub,
+                       const uint16_t *in_rel, const unsigned long long *hc, bool want_stats, bool first,
+                       hipStream_t st) {
+    const bool dense = dense_pull(g, hc, want_stats);
+    switch (r->W) {
+        case 1:
+            if (first) launch_live<1>(g, r, h, dense, st);
+            pull_rows_w<1>(g, r, h, rc, in_sub, in_rel, dense, want_stats, st);
+            break;
+        case 4:
+            if (first) launch_live<4>(g, r, h, dense, st);
+            pull_rows_w<4>(g, r, h, rc, in_sub, in_rel, dense, want_stats, st);
+            break;
+        default:
+            if (first) launch_live<16>(g, r, h, dense, st);
+            pull_rows_w<16>(g, r, h, rc, in_sub, in_rel, dense, want_stats, st);
+            break;
+    }
+}
+
+template <int W>
 static void run_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
                     const unsigned long long *hc, hipStream_t st) {
     if (pull) {
-        if (r->has_mask) {
-            if (want_stats) launch_pull<W, true, true>(g, r, h, true, hc, st);
-            else launch_pull<W, true, false>(g, r, h, false, hc, st);
-        } else {
-            if (want_stats) launch_pull<W, false, true>(g, r, h, true, hc, st);
-            else launch_pull<W, false, false>(g, r, h, false, hc, st);
-        }
+        launch_pull_range(g, r, h, g->in_rows, g->in_sub, g->in_rel, hc, want_stats, true, st);
     } else {
         if (r->has_mask) launch_push<W, true>(g, r, h, hc, g->out_obj, g->out_rel, true, g->fr_tail, g->fr_seg, g->d_ctr, st);
         else launch_push<W, false>(g, r, h, hc, g->out_obj, g->out_rel, true, g->fr_tail, g->fr_seg, g->d_ctr, st);
@@ -991,10 +1029,6 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
     uint32_t dir = b->flags & LOGOSKG_DIR_MASK;
     const bool walk_exact = (b->flags & LOGOSKG_WALK_EXACT) != 0;
     if (dir == 3u) { set_error("bad direction flags"); return LOGOSKG_EINVAL; }
-    if (g->num_shards > 1 && dir == LOGOSKG_DIR_PULL) {
-        set_error("pull is only available on resident graphs");
-        return LOGOSKG_EINVAL;
-    }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)b->stream;
 
@@ -1065,20 +1099,19 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
         if (rows == 0) break;  // nothing can be reached any more: the remaining levels stay empty
         hs.active_rows = rows;
         hs.frontier_edges = fedges;
+        const bool pull = dir == LOGOSKG_DIR_PULL || (dir == LOGOSKG_DIR_AUTO && fedges * 12 > g->T);
+        hs.direction = pull ? LOGOSKG_DIR_PULL : LOGOSKG_DIR_PUSH;
+        unsigned long long hc[C_TOTAL];
+        memcpy(hc, g->h_ctr, sizeof(hc));
+        if (want_stats)
+            KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
         if (g->num_shards > 1) {
-            hs.direction = LOGOSKG_DIR_PUSH;
-            if ((s = run_sharded_hop(g, r, h, st, &hs)) != LOGOSKG_OK) return fail(s);
-            hs.edges_scanned = fedges;
-            hs.lines_gathered = fedges;
+            // Alg. 1: the hop visits sub-graphs one after the other through the cache -- the
+            // subject shards that hold a frontier row (push) or every object range (pull)
+            if ((s = run_sharded_hop(g, r, h, pull, want_stats, hc, st, &hs)) != LOGOSKG_OK) return fail(s);
             KH(hipGetLastError());
         } else {
-            bool pull = dir == LOGOSKG_DIR_PULL || (dir == LOGOSKG_DIR_AUTO && fedges * 12 > g->T);
-            hs.direction = pull ? LOGOSKG_DIR_PULL : LOGOSKG_DIR_PUSH;
             hs.shards_touched = 1;
-            unsigned long long hc[C_TOTAL];
-            memcpy(hc, g->h_ctr, sizeof(hc));
-            if (want_stats)
-                KH(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
             if (!pull && (s = census_lists(g, r, h - 1, -1, st)) != LOGOSKG_OK) return fail(s);
             launch_resident_hop(g, r, h, pull, want_stats, hc, st);
             KH(hipGetLastError());
@@ -1095,7 +1128,7 @@ extern "C" logoskg_status logoskg_khop(logoskg_graph *g, const logoskg_query_bat
                 // distinct frontier lines this kernel can have gathered
                 g->prof.acc[kind].units[3] += std::min<long long>((long long)c[2], (long long)hs.active_rows);
             }
-        } else if (g->num_shards <= 1) {
+        } else {
             hs.edges_scanned = fedges;
             hs.lines_gathered = fedges;
         }

@@ -6,11 +6,19 @@
 // triples of a subject stay together.  The map P (shard of each subject) lives
 // in HBM; the triples (objects, relations) are kept in pinned host memory,
 // grouped by shard, and move into a fixed number of HBM slots on demand under a
-// least-recently-used policy.  One hop = for every shard that has an active
-// subject, in ascending shard order: make it resident (hit, or load and maybe
-// evict), restrict the frontier to its subjects, push, OR into the global next
-// level (object ids are global, so "map back" is free).  The next shard's load
-// is issued on a copy stream while the current one computes.
+// least-recently-used policy.  A push hop = for every shard that has an active
+// subject (ascending shard index on odd hops, descending on even ones): make it
+// resident (hit, or load and maybe evict), restrict the frontier to its
+// subjects, push, OR into the global next level (object ids are global, so
+// "map back" is free).  The next shard's load is issued on a copy stream while
+// the current one computes.
+//
+// A dense hop pulls instead, as on a resident graph: the same triples cut a
+// second way, by object range, into sub-graphs that hold whole rows of OBJ (the
+// chunks the predecessor pass streams).  They are units of the same cache: a
+// pull hop visits every object range in turn (subjects and relation ids of its
+// rows in a cache slot), gathers the frontier lines of each row's subjects and
+// writes that range's part of the next level, without atomics.
 #include <fcntl.h>
 #include <sys/stat.h>
 #include <unistd.h>
@@ -53,6 +61,12 @@ struct ShardSet {
     uint16_t *h_in_rel = nullptr;
     struct Chunk { long long tile_begin, tile_count; int64_t edge_begin, edge_count; long long row_begin, hub_count, row_count; };
     std::vector<Chunk> chunks;
+    // pull work lists of every chunk (object range), concatenated on the device
+    std::vector<RowClasses> pull_lists;
+    ShortRow *d_tail = nullptr;
+    PullSegment *d_seg = nullptr;
+    int32_t *d_multi = nullptr;
+    int units() const { return n + (int)chunks.size(); }  // cacheable sub-graphs: shards, then object ranges
     size_t stage_edges = 0;
     int32_t *stage_sub[2] = {nullptr, nullptr}, *stage_eid[2] = {nullptr, nullptr};
     uint16_t *stage_rel[2] = {nullptr, nullptr};
@@ -216,6 +230,9 @@ void free_shards(logoskg_graph *g) {
     for (int f : ss->fd) if (f >= 0) (void)close(f);
     if (ss->d_route) (void)hipFree(ss->d_route);
     if (ss->h_route) (void)hipHostFree(ss->h_route);
+    if (ss->d_tail) (void)hipFree(ss->d_tail);
+    if (ss->d_seg) (void)hipFree(ss->d_seg);
+    if (ss->d_multi) (void)hipFree(ss->d_multi);
     if (g->row_begin && g->row_begin != g->out_off) (void)hipFree(g->row_begin);
     if (g->shard_of_dev) (void)hipFree(g->shard_of_dev);
     g->row_begin = nullptr;
@@ -287,6 +304,54 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
         ss->chunks.push_back(c);
         ss->stage_edges = std::max(ss->stage_edges, (size_t)c.edge_count);
         t0 = t1;
+    }
+    {   // pull work lists per chunk: short rows by descending length, segments of the long rows
+        // (already longest first), rows with several segments
+        std::vector<ShortRow> tail;
+        std::vector<PullSegment> seg;
+        std::vector<int32_t> multi;
+        std::vector<std::vector<int32_t>> bucket(kTailMaxDegree + 1);
+        struct First { size_t tail, seg, multi; };
+        std::vector<First> first;  // where every chunk's lists begin in the concatenations
+        for (const ShardSet::Chunk &c : ss->chunks) {
+            RowClasses rc;
+            const size_t t_begin = tail.size(), s_begin = seg.size(), m_begin = multi.size();
+            for (auto &b : bucket) b.clear();
+            for (long long e = c.tile_begin * 64; e < std::min<long long>((c.tile_begin + c.tile_count) * 64, E); ++e) {
+                const uint32_t d = ioff[(size_t)e + 1] - ioff[(size_t)e];
+                if (d >= 1 && d <= (uint32_t)kTailMaxDegree) bucket[d].push_back((int32_t)e);
+            }
+            for (int d = kTailMaxDegree; d >= 1; --d)
+                for (int32_t v : bucket[d]) tail.push_back({v, ioff[(size_t)v], ioff[(size_t)v + 1]});
+            for (long long i = 0; i < c.row_count; ++i) {
+                const int32_t v = longrows[(size_t)(c.row_begin + i)];
+                const uint32_t lo = ioff[(size_t)v], hi = ioff[(size_t)v + 1];
+                const bool several = hi - lo > (uint32_t)kPullSegment;
+                if (several) multi.push_back(v);
+                for (uint32_t j = lo; j < hi; j += kPullSegment)
+                    seg.push_back({v, j, std::min(j + (uint32_t)kPullSegment, hi), several ? 1u : 0u});
+            }
+            rc.n_tail = (int64_t)(tail.size() - t_begin);
+            rc.n_seg = (int64_t)(seg.size() - s_begin);
+            rc.n_multi = (int64_t)(multi.size() - m_begin);
+            first.push_back({t_begin, s_begin, m_begin});
+            ss->pull_lists.push_back(rc);
+        }
+        LKG_HIP(hipMalloc((void **)&ss->d_tail, std::max<size_t>(tail.size(), 1) * sizeof(ShortRow)));
+        LKG_HIP(hipMalloc((void **)&ss->d_seg, std::max<size_t>(seg.size(), 1) * sizeof(PullSegment)));
+        LKG_HIP(hipMalloc((void **)&ss->d_multi, std::max<size_t>(multi.size(), 1) * sizeof(int32_t)));
+        if (!tail.empty()) LKG_HIP(hipMemcpy(ss->d_tail, tail.data(), tail.size() * sizeof(ShortRow), hipMemcpyHostToDevice));
+        if (!seg.empty()) LKG_HIP(hipMemcpy(ss->d_seg, seg.data(), seg.size() * sizeof(PullSegment), hipMemcpyHostToDevice));
+        if (!multi.empty()) LKG_HIP(hipMemcpy(ss->d_multi, multi.data(), multi.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+        g->static_bytes += tail.size() * sizeof(ShortRow) + seg.size() * sizeof(PullSegment) + multi.size() * sizeof(int32_t);
+        for (size_t i = 0; i < ss->pull_lists.size(); ++i) {
+            ss->pull_lists[i].tail = ss->d_tail + first[i].tail;
+            ss->pull_lists[i].seg = ss->d_seg + first[i].seg;
+            ss->pull_lists[i].multi = ss->d_multi + first[i].multi;
+        }
+        g->in_rows.n_tail = (int64_t)tail.size();
+        g->in_rows.n_seg = (int64_t)seg.size();
+        g->in_rows.n_multi = (int64_t)multi.size();
     }
     g->in_rows.n_long = (int64_t)longrows.size();
     LKG_HIP(hipMalloc((void **)&g->in_rows.longrows, std::max<size_t>(longrows.size(), 1) * sizeof(int32_t)));
@@ -512,12 +577,15 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         LKG_HIP(hipMemcpy(g->shard_of_dev, p8.data(), (size_t)g->Epad, hipMemcpyHostToDevice));
         g->static_bytes += (size_t)g->Epad;
     }
-    // cache slots
+    LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
+    // cache slots: each holds one sub-graph, a subject shard (objects + relation ids) or an object
+    // range (subjects + relation ids): 6 bytes per triple either way
     int64_t largest = 1;
     for (int s = 0; s < n; ++s) largest = std::max(largest, g->shard_triples[s]);
+    for (const ShardSet::Chunk &c : ss->chunks) largest = std::max<int64_t>(largest, c.edge_count);
     ss->slot_edges = (size_t)largest;
     size_t slot_bytes = ss->slot_edges * (sizeof(int32_t) + sizeof(uint16_t));
-    int slots = n;
+    int slots = ss->units();
     if (opts->max_resident_shards > 0) slots = std::min(slots, opts->max_resident_shards);
     if (opts->hbm_shard_budget_bytes > 0) {
         uint64_t fit = opts->hbm_shard_budget_bytes / slot_bytes;
@@ -532,7 +600,7 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
     ss->slot_obj.assign((size_t)slots, nullptr);
     ss->slot_rel.assign((size_t)slots, nullptr);
     ss->slot_shard.assign((size_t)slots, -1);
-    ss->shard_slot.assign((size_t)n, -1);
+    ss->shard_slot.assign((size_t)ss->units(), -1);
     ss->slot_used.assign((size_t)slots, 0);
     ss->slot_ready.assign((size_t)slots, nullptr);
     ss->slot_idle.assign((size_t)slots, nullptr);
@@ -545,7 +613,6 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
     }
     LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
     if (opts->shard_dir && opts->shard_dir[0]) LKG_TRY(shards_to_disk(g, ss, opts->shard_dir));
-    LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
     LKG_HIP(hipMalloc((void **)&ss->d_route, 1024 * sizeof(unsigned long long)));
     if (hipHostMalloc((void **)&ss->h_route, 1024 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
         set_error("hipHostMalloc failed");
@@ -554,10 +621,12 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
     return LOGOSKG_OK;
 }
 
-// Makes `shard` resident and returns its slot: a hit refreshes its use stamp; a
+// Makes a sub-graph resident and returns its slot: a hit refreshes its use stamp; a
 // miss takes an empty slot or evicts the least recently used one and starts the
-// copy on the copy stream (after the kernels that last read the slot).
+// copy on the copy stream (after the kernels that last read the slot).  Units below
+// ss->n are subject shards, the others object ranges (always kept in pinned memory).
 static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStream_t compute, int *slot_out) {
+    const bool range = shard >= ss->n;
     int slot = ss->shard_slot[shard];
     if (slot >= 0) {
         ss->hits++;
@@ -572,10 +641,11 @@ static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStre
             ss->shard_slot[ss->slot_shard[slot]] = -1;
             ss->evictions++;
         }
-        int64_t b = ss->edge_begin[shard], cnt = ss->edge_begin[(size_t)shard + 1] - b;
-        const int32_t *src_obj = ss->h_obj ? ss->h_obj + b : nullptr;
-        const uint16_t *src_rel = ss->h_rel ? ss->h_rel + b : nullptr;
-        if (!ss->fd.empty()) {  // the shard comes from its file, through the slot's staging buffer
+        int64_t b = range ? ss->chunks[(size_t)(shard - ss->n)].edge_begin : ss->edge_begin[shard];
+        int64_t cnt = range ? ss->chunks[(size_t)(shard - ss->n)].edge_count : ss->edge_begin[(size_t)shard + 1] - b;
+        const int32_t *src_obj = range ? ss->h_in_sub + b : (ss->h_obj ? ss->h_obj + b : nullptr);
+        const uint16_t *src_rel = range ? ss->h_in_rel + b : (ss->h_rel ? ss->h_rel + b : nullptr);
+        if (!range && !ss->fd.empty()) {  // the shard comes from its file, through the slot's staging buffer
             LKG_HIP(hipEventSynchronize(ss->slot_ready[slot]));  // the buffer's last copy has left it
             ShardFileHeader h;
             const bool ok = read_all_at(ss->fd[shard], &h, sizeof(h), 0) && memcmp(h.magic, kShardMagic, 8) == 0 &&
@@ -613,10 +683,37 @@ static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStre
     return LOGOSKG_OK;
 }
 
-logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, hipStream_t st,
-                               logoskg_hop_stats *hs) {
+// A pull hop: every object range in turn (down on even hops, up on odd ones, like the shards of
+// a push hop), its rows of OBJ in a cache slot.
+static logoskg_status run_sharded_pull(logoskg_graph *g, ShardSet *ss, logoskg_result *r, int h, bool want_stats,
+                                       const unsigned long long *hc, hipStream_t st, logoskg_hop_stats *hs) {
+    std::vector<int> order;
+    for (int c = 0; c < (int)ss->chunks.size(); ++c)
+        if (ss->chunks[(size_t)c].edge_count > 0) order.push_back(c);
+    if ((h & 1) == 0) std::reverse(order.begin(), order.end());
+    hs->shards_touched = (int)order.size();
+    std::vector<int> slot_of(order.size(), -1);
+    for (size_t i = 0; i < order.size(); ++i) {
+        const int c = order[i];
+        if (slot_of[i] < 0) LKG_TRY(acquire(g, ss, ss->n + c, st, &slot_of[i]));
+        const int slot = slot_of[i];
+        LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[slot], 0));
+        const int64_t b = ss->chunks[(size_t)c].edge_begin;
+        launch_pull_range(g, r, h, ss->pull_lists[(size_t)c], ss->slot_obj[slot] - b, ss->slot_rel[slot] - b, hc,
+                          want_stats, i == 0, st);
+        LKG_HIP(hipGetLastError());
+        LKG_HIP(hipEventRecord(ss->slot_idle[slot], st));
+        if (i + 1 < order.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
+            LKG_TRY(acquire(g, ss, ss->n + order[i + 1], st, &slot_of[i + 1]));
+    }
+    return LOGOSKG_OK;
+}
+
+logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
+                               const unsigned long long *hc_in, hipStream_t st, logoskg_hop_stats *hs) {
     ShardSet *ss = (ShardSet *)g->shards;
     if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
+    if (pull) return run_sharded_pull(g, ss, r, h, want_stats, hc_in, st, hs);
     const long long nwords = r->Epad / 32;
     const uint32_t *act_prev = r->act + (size_t)nwords * (h - 1);
     const unsigned nb = (unsigned)std::min<long long>(1024, std::max<long long>(1, ((long long)g->E + 255) / 256));
@@ -696,6 +793,8 @@ void shard_info(const logoskg_graph *g, logoskg_graph_info *o) {
     o->shard_hits = ss->hits;
     o->shard_bytes_h2d = ss->bytes_h2d + ss->in_bytes_h2d;
     o->shard_bytes_disk = ss->bytes_disk;
+    o->num_object_ranges = (int32_t)ss->chunks.size();
+    o->cache_slots = ss->n_slots;
 }
 
 }  // namespace lkg

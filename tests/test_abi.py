@@ -34,7 +34,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(b._QueryBatch) == 56
     assert ctypes.sizeof(b._HopStats) == 56
     assert ctypes.sizeof(b._ResultInfo) == 48
-    assert ctypes.sizeof(b._GraphInfo) == 112
+    assert ctypes.sizeof(b._GraphInfo) == 120
 
 
 def test_product_path_does_not_touch_the_oracle():

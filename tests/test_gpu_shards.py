@@ -19,13 +19,24 @@ def lkg():
     return m
 
 
-def run_sharded(w, num_shards, max_resident=0, budget=0, repeat=1):
+def pull_hops(stats):
+    """The hops (1-based) a call evaluated by object rows: the direction is the library's own choice
+    from the frontier's edge count, so the cache model takes it from the hop statistics."""
+    return {h + 1 for h, s in enumerate(stats) if s["direction"] == 2}
+
+
+def accesses(P, w, k, ent, hop, stats, info):
+    return part.shard_accesses(P, w.subj, w.num_entities, k, ent, hop, pull_hops(stats), info["num_shards"],
+                               info["num_object_ranges"])
+
+
+def run_sharded(w, num_shards, max_resident=0, budget=0, repeat=1, direction="auto"):
     m = lkg()
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=num_shards,
                 max_resident_shards=max_resident, hbm_shard_budget_bytes=budget)
     outs = []
     for _ in range(repeat):
-        res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+        res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask, direction=direction)
         off = res.offsets()
         ent, hop, pred = res.fetch()
         trav = res.traversed().cpu().numpy()
@@ -40,11 +51,12 @@ def run_sharded(w, num_shards, max_resident=0, budget=0, repeat=1):
 @pytest.mark.parametrize("make", [lambda: kggen.config5(0.0005), lambda: kggen.config3(0.005, k=3),
                                   lambda: kggen.config1()])
 @pytest.mark.parametrize("num_shards,max_resident", [(2, 0), (8, 0), (8, 1), (8, 2), (8, 3)])
-def test_sharded_results_and_cache_counters(make, num_shards, max_resident):
+@pytest.mark.parametrize("direction", ["auto", "push", "pull"])
+def test_sharded_results_and_cache_counters(make, num_shards, max_resident, direction):
     w = make()
-    print("case", w.name, num_shards, max_resident, flush=True)
+    print("case", w.name, num_shards, max_resident, direction, flush=True)
     want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
-    outs, info, P, per = run_sharded(w, num_shards, max_resident, repeat=2)
+    outs, info, P, per = run_sharded(w, num_shards, max_resident, repeat=2, direction=direction)
     for off, ent, hop, trav, stats, pred in outs:
         assert np.array_equal(off, want[0])
         assert np.array_equal(ent, want[1])
@@ -54,11 +66,17 @@ def test_sharded_results_and_cache_counters(make, num_shards, max_resident):
     P_o, loads_o = part.degree_aware_partition(w.num_entities, w.subj, num_shards)
     assert np.array_equal(P, P_o)
     assert np.array_equal(per, loads_o)
-    seq = part.shard_accesses(P_o, w.subj, w.num_entities, w.k, want[1], want[2])
-    cap = num_shards if max_resident == 0 else min(max_resident, num_shards)
+    stats = outs[0][4]
+    if direction != "auto":
+        assert all(s["direction"] in (0, 1 if direction == "push" else 2) for s in stats)
+    seq = accesses(P_o, w, w.k, want[1], want[2], stats, info)
+    # the cache holds sub-graphs of both kinds: the shards and the object ranges of the pull hops
+    units = num_shards + info["num_object_ranges"]
+    cap = units if max_resident == 0 else min(max_resident, units)
+    assert info["cache_slots"] == cap
     loads, ev, hits = part.lru_counts(seq + seq, cap)   # two identical batches on one graph
     assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == (loads, ev, hits)
-    touched = [s["shards_touched"] for s in outs[0][4]]
+    touched = [s["shards_touched"] for s in stats]
     assert sum(touched) == len(seq)
     assert info["pinned_host_bytes"] == 16 * max(w.num_triples, 1)  # 6 B subject-sorted + 10 B object-sorted
 
@@ -71,14 +89,13 @@ def test_byte_budget_and_errors():
     slot_bytes = int(loads_o.max()) * 6
     outs, info, _, _ = run_sharded(w, 8, budget=int(2.5 * slot_bytes))
     want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k)
-    seq = part.shard_accesses(P_o, w.subj, w.num_entities, w.k, want[1], want[2])
+    seq = accesses(P_o, w, w.k, want[1], want[2], outs[0][4], info)
+    assert info["cache_slots"] == 2
     assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == part.lru_counts(seq, 2)
     with pytest.raises(m.LogosKGError):
         m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8,
                 hbm_shard_budget_bytes=slot_bytes // 2)
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=4)
-    with pytest.raises(m.LogosKGError):
-        g.khop(w.seed_off, w.seeds, w.k, direction="pull")
     res = g.khop(w.seed_off, w.seeds, w.k)
     # shortest paths on a sharded graph: the object rows are read from pinned host memory
     pq, pt = kggen.sample_reached_pairs(7, want[0], want[1], 600)
@@ -131,7 +148,7 @@ def test_scheduled_batches_restore_results_and_cut_first_hop_loads():
             qs = order[b0:b0 + B]
             so = np.concatenate([[0], np.cumsum(w.seed_off[qs + 1] - w.seed_off[qs])]).astype(np.int64)
             sd = np.concatenate([w.seeds[w.seed_off[q]:w.seed_off[q + 1]] for q in qs]).astype(np.int32)
-            res = g.khop(so, sd, 1)
+            res = g.khop(so, sd, 1, direction="push")
             off = res.offsets()
             ent, hop, pred = (x.cpu().numpy() for x in res.fetch())
             res.close()
@@ -210,7 +227,7 @@ def test_prefetch_warms_the_cache_for_the_next_batch():
     assert (info["shard_loads"], info["shard_hits"], info["shard_evictions"]) == (3, 0, 0)
     g.prefetch_shards(first[:1])                      # resident: a hit
     assert g.info()["shard_hits"] == 1
-    res = g.khop(w.seed_off, w.seeds, 1)
+    res = g.khop(w.seed_off, w.seeds, 1, direction="push")
     ent, hop, pred = (x.cpu().numpy() for x in res.fetch())
     assert np.array_equal(res.offsets(), want[0]) and np.array_equal(ent, want[1]) and np.array_equal(pred, want[3])
     res.close()

@@ -86,10 +86,21 @@ def test_error_paths():
     assert cnt.numel() == 0
     res.close()
     g.close()
+    # a sharded graph lists walks too (the object rows are read from pinned host memory)
     ws = kggen.config5(0.0003)
     gs = m.Graph(ws.subj, ws.rel, ws.obj, ws.num_entities, ws.num_relations, num_shards=4)
     rs = gs.khop(ws.seed_off, ws.seeds, 2, walk_exact=True)
-    with pytest.raises(m.LogosKGError):
-        gs.walks(rs, [0], [0], [1])
+    lo, lent = oracle.walk_levels(ws.num_entities, ws.subj, ws.rel, ws.obj, ws.seed_off, ws.seeds, 2, None)
+    Q = ws.num_queries
+    wq, wt = [], []
+    for q in range(Q):
+        for v in lent[int(lo[2 * Q + q]):int(lo[2 * Q + q + 1])][:4]:
+            wq.append(q)
+            wt.append(int(v))
+    if wq:
+        c1, e1 = gs.walks(rs, wq, wt, [2] * len(wq), 16)
+        c2, e2 = oracle.walk_paths(ws.num_entities, ws.subj, ws.rel, ws.obj, ws.seed_off, ws.seeds, 2, wq, wt,
+                                   [2] * len(wq), 16, None)
+        assert np.array_equal(c1.cpu().numpy(), c2) and np.array_equal(e1.cpu().numpy(), e2)
     rs.close()
     gs.close()

@@ -399,6 +399,19 @@ def test_shard_visit_order_hand_trace():
     # with one slot nothing is ever hit; with four slots every sub-graph is loaded once
     assert part.lru_counts(seq, 1) == (6, 5, 0)
     assert part.lru_counts(seq, 4) == (4, 0, 2)
+    # hop 2 evaluated by object rows: it touches every sub-graph of the partition by object range
+    # (three of them here, numbered 4, 5, 6 behind the four shards), an even hop -> descending
+    P4 = np.array([2, 3, 1, 1, 0, 0, -1, 3, -1, -1], dtype=np.int32)
+    subj = np.array([0, 1, 2, 3, 4, 5, 7, 0, 5], dtype=np.int32)
+    entity = np.array([0, 5, 1, 2, 7, 3, 4, 8, 9, 0, 2], dtype=np.int32)
+    hop = np.array([0, 0, 1, 1, 1, 2, 2, 2, 3, 0, 1], dtype=np.uint8)
+    seq = part.shard_accesses(P4, subj, 10, 3, entity, hop, pull_hops={2}, num_shards=4, num_ranges=3)
+    assert seq == [0, 2, 6, 5, 4, 0, 1]
+    # hops 2 and 3 by object rows: 6, 5, 4 then (odd hop) 4, 5, 6: the turning point is a hit
+    seq = part.shard_accesses(P4, subj, 10, 3, entity, hop, pull_hops={2, 3}, num_shards=4, num_ranges=3)
+    assert seq == [0, 2, 6, 5, 4, 4, 5, 6]
+    # two slots: 0 L, 2 L, 6 L (evicts 0), 5 L (evicts 2), 4 L (evicts 6), 4 hit, 5 hit, 6 L (evicts 4)
+    assert part.lru_counts(seq, 2) == (6, 4, 2)
     # fewer hops: a prefix of the same trace; an empty frontier ends it
     P = np.array([0, 1], dtype=np.int32)
     assert part.shard_accesses(P, np.array([0], dtype=np.int32), 2, 3, np.array([0, 1], dtype=np.int32),
