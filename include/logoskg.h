@@ -355,6 +355,35 @@ logoskg_status logoskg_walks(logoskg_graph *g, const logoskg_result *r, const in
                              int32_t max_paths, int32_t *path_count, int32_t *path_edges, void *stream);
 
 /*
+ * Sec. 3.3, complete paths in bulk (Eq. 5-7 chained over the hops): EVERY chain
+ * (t_1, .., t_d), d = length, of allowed triples of one query with s_{t_1} a
+ * seed, o_{t_i} = s_{t_{i+1}} and s_{t_i} in level i-1 -- on a
+ * LOGOSKG_WALK_EXACT result all walks of d triples from a seed (the complete
+ * paths of length d), on a minimum-hop result all shortest paths to the
+ * entities at hop d -- with no bound per target.  The chains are numbered
+ * 0 .. total-1: by target (ascending entity id), the chains of one target in
+ * the order of logoskg_paths / logoskg_walks ((t_d, .., t_1) lexicographic).
+ *
+ * logoskg_result_walks_count builds the count tables of (query, length) on the
+ * device (8 bytes x (length x num_triples + (length + 2) x padded_entities)
+ * from the graph's pool, kept until the result is freed or another
+ * (query, length) is counted), returns the number of chains in *total (host)
+ * and synchronises `stream`.  LOGOSKG_ERANGE when 2^56 or more chains end in
+ * one entity.  logoskg_result_walks_fetch writes the chains
+ * [first, first + count) of the (query, length) counted last: walk_edges is
+ * device int32[count][length], each chain written seed -> target; walk_target
+ * (device int32[count], may be NULL when length > 0) receives the entity each
+ * chain ends in.  Asynchronous on `stream`; any page can be asked for in any
+ * order, so a caller with a fixed buffer pages through the whole list.  On a
+ * sharded graph the kernels read the object-sorted triples from pinned host
+ * memory in place.
+ */
+logoskg_status logoskg_result_walks_count(logoskg_result *r, int32_t query, int32_t length, int64_t *total,
+                                          void *stream);
+logoskg_status logoskg_result_walks_fetch(logoskg_result *r, int32_t query, int32_t length, int64_t first,
+                                          int64_t count, int32_t *walk_edges, int32_t *walk_target, void *stream);
+
+/*
  * For callers that cannot allocate device memory (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): logoskg_paths with the
  * same arguments, results and order, whose only working memory - three int32

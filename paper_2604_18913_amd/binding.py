@@ -116,6 +116,10 @@ def _load():
     lib.logoskg_result_triples_offsets.argtypes = [P, I32, I32, I32, P, P]
     lib.logoskg_result_triples_fetch.restype = ctypes.c_int
     lib.logoskg_result_triples_fetch.argtypes = [P, I32, I32, I32, I64, P, P, P, P, P]
+    lib.logoskg_result_walks_count.restype = ctypes.c_int
+    lib.logoskg_result_walks_count.argtypes = [P, I32, I32, P, P]
+    lib.logoskg_result_walks_fetch.restype = ctypes.c_int
+    lib.logoskg_result_walks_fetch.argtypes = [P, I32, I32, I64, I64, P, P, P]
     lib.logoskg_result_traversed.restype = ctypes.c_int
     lib.logoskg_result_traversed.argtypes = [P, P, P]
     lib.logoskg_result_free.restype = None
@@ -260,6 +264,25 @@ class Result:
         ptrs = [None if b is None else b.data_ptr() for b in bufs]
         _check(_load().logoskg_result_triples_fetch(self._h, h, q_begin, q_end, cap, *ptrs, _stream_handle(stream)))
         return (off, *[None if b is None else b[:n] for b in bufs])
+
+    def walks_count(self, query: int, length: int, stream=None) -> int:
+        """``logoskg_result_walks_count``: number of chains of ``length`` allowed triples of ``query``."""
+        total = ctypes.c_int64()
+        _check(_load().logoskg_result_walks_count(self._h, query, length, ctypes.byref(total), _stream_handle(stream)))
+        return int(total.value)
+
+    def walks_fetch(self, query: int, length: int, first: int, count: int, out=None, stream=None):
+        """``logoskg_result_walks_fetch``: chains [first, first + count) of the (query, length) counted
+        last as (edges int32[count, length], target int32[count]) device tensors."""
+        torch = _torch()
+        if out is None:
+            edges = torch.empty((count, length), dtype=torch.int32, device=self._g.device)
+            target = torch.empty(count, dtype=torch.int32, device=self._g.device)
+        else:
+            edges, target = out
+        _check(_load().logoskg_result_walks_fetch(self._h, query, length, first, count, edges.data_ptr(),
+                                                  target.data_ptr(), _stream_handle(stream)))
+        return edges[:count], target[:count]
 
     def traversed(self, stream=None):
         torch = _torch()

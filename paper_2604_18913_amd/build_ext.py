@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblogoskg.so")
-SOURCES = ["build.hip", "build_device.hip", "khop.hip", "result.hip", "paths.hip", "shards.hip", "triples.hip"]
+SOURCES = ["build.hip", "build_device.hip", "khop.hip", "result.hip", "paths.hip", "shards.hip", "triples.hip", "walks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -248,6 +248,12 @@ struct logoskg_result {
     long long *trip_chunk_entry = nullptr;  // [chunks + 1] entry behind the first position of every 256-position chunk
     long long *trip_chunk_first = nullptr;  // [chunks + 1] with a whitelist: allowed triples before the chunk
     std::vector<int64_t> trip_off_host;  // [trip_q1 - trip_q0 + 1]
+    // chain-count tables of one (query, length) (logoskg_result_walks_count)
+    int walk_q = -1, walk_d = -1;
+    int64_t walk_total = 0;
+    unsigned long long *walk_cnt = nullptr;   // [walk_d + 1][Epad] chains that end in the entity after h triples
+    unsigned long long *walk_cum = nullptr;   // [walk_d][T] per hop: running sums inside the rows of OBJ
+    unsigned long long *walk_pref = nullptr;  // [E + 1] chains that end in a smaller entity
     std::vector<logoskg_hop_stats> stats;
     mutable hipStream_t last_stream = nullptr;  // stream of the latest call that used the result
     bool complete = false;  // logoskg_khop ran to its end: every non-zero line of the planes has its bit in act
@@ -376,6 +382,7 @@ struct FillArgs {
 logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
                                    std::vector<uint32_t> *ooff, std::vector<uint32_t> *ioff);
 logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st);
+void drop_walk_tables(logoskg_result *r);
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
 void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows, long long n_other_rows, bool mask,
                  hipStream_t st_tiles, hipStream_t st_rows);

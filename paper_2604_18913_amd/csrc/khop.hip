@@ -989,6 +989,7 @@ extern "C" void logoskg_result_free(logoskg_result *r) {
     if (!r) return;
     logoskg_graph *g = r->g;
     (void)hipSetDevice(g->device);
+    drop_walk_tables(r);
     // levels follows visited and live follows act in one allocation each
     void *ptrs[] = {r->visited, r->act, r->allow, r->tile_base,
                     r->super_base, r->mega_base, r->d_reached_off, r->lvl_tile_base, r->lvl_super_base,

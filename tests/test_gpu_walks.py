@@ -104,3 +104,88 @@ def test_error_paths():
         assert np.array_equal(c1.cpu().numpy(), c2) and np.array_equal(e1.cpu().numpy(), e2)
     rs.close()
     gs.close()
+
+
+def bulk_expected(w, k, q, d, walk_exact, cap):
+    """Every chain of d triples of query q from the oracle: targets ascending (level d of the walk
+    levels, or the entities at hop d), each target's chains in (t_d, .., t_1) order."""
+    Q = w.num_queries
+    if walk_exact:
+        off, ent = oracle.walk_levels(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, w.rel_mask)
+        targets = ent[int(off[d * Q + q]):int(off[d * Q + q + 1])]
+    else:
+        ro, ent, hop, _, _ = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, w.rel_mask)
+        a, b = int(ro[q]), int(ro[q + 1])
+        targets = ent[a:b][hop[a:b] == d]
+    n = len(targets)
+    if n == 0:
+        return np.zeros((0, d), np.int32), np.zeros(0, np.int32)
+    qs = np.full(n, q, np.int32)
+    if walk_exact:
+        cnt, edges = oracle.walk_paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, qs, targets,
+                                       np.full(n, d, np.int32), cap, w.rel_mask)
+    else:
+        cnt, edges = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, qs, targets, cap,
+                                  w.rel_mask)
+    assert cnt.max() < cap, "raise the oracle's bound: a target has more chains than it lists"
+    rows = [edges[i, :cnt[i], :d] for i in range(n)]
+    return np.concatenate(rows).reshape(int(cnt.sum()), d), np.repeat(targets, cnt).astype(np.int32)
+
+
+def check_bulk(w, k, queries, walk_exact, cap=4096, page=777, **graph_opts):
+    m = lkg()
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, **graph_opts)
+    res = g.khop(w.seed_off, w.seeds, k, w.rel_mask, walk_exact=walk_exact)
+    listed = 0
+    for q in queries:
+        for d in range(k + 1):
+            want_e, want_t = bulk_expected(w, k, q, d, walk_exact, cap)
+            total = res.walks_count(q, d)
+            assert total == len(want_t), f"query {q} length {d}: number of chains"
+            got_e, got_t = [], []
+            for first in range(0, total, page):      # page through the whole list with a fixed buffer
+                e, t = res.walks_fetch(q, d, first, min(page, total - first))
+                got_e.append(e.cpu().numpy())
+                got_t.append(t.cpu().numpy())
+            if total:
+                assert np.array_equal(np.concatenate(got_t), want_t), f"query {q} length {d}: targets"
+                assert np.array_equal(np.concatenate(got_e), want_e), f"query {q} length {d}: chains"
+                lo = total // 3                      # any page can be asked for on its own
+                e, t = res.walks_fetch(q, d, lo, min(5, total - lo))
+                assert np.array_equal(e.cpu().numpy(), want_e[lo:lo + 5]) and np.array_equal(t.cpu().numpy(), want_t[lo:lo + 5])
+            listed += total
+            with pytest.raises(m.LogosKGError):
+                res.walks_fetch(q, d, total, 1)      # past the end
+    with pytest.raises(m.LogosKGError):
+        res.walks_count(w.num_queries, 0)
+    with pytest.raises(m.LogosKGError):
+        res.walks_count(0, k + 1)
+    with pytest.raises(m.LogosKGError):
+        res.walks_fetch(queries[0], k + 5, 0, 0)     # not the (query, length) counted last
+    res.close()
+    g.close()
+    return listed
+
+
+@pytest.mark.parametrize("walk_exact", [True, False])
+def test_bulk_chains_every_query_on_tiny_graphs(walk_exact):
+    # every chain of every length of every query: walks of d triples (walk-exact result) and all
+    # shortest paths to the entities at hop d (minimum-hop result)
+    for seed in range(3):
+        w = kggen.random_tiny(1500 + seed, E=30, T=100, R=4, Q=70, k=4, masked=bool(seed & 1))
+        n = check_bulk(w, w.k, range(w.num_queries), walk_exact, cap=20000)
+        assert n > 0
+
+
+@pytest.mark.parametrize("walk_exact", [True, False])
+def test_bulk_chains_on_scaled_workloads(walk_exact):
+    w = kggen.config1()
+    assert check_bulk(w, 2, [0, 5, 33, 63], walk_exact) > 0
+    w = kggen.config3(0.002, k=3)                       # whitelists, 16-word planes
+    live = np.nonzero(np.diff(oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, 3,
+                                          w.rel_mask)[0]) > 3)[0]
+    assert check_bulk(w, 3, [int(x) for x in live[:4]] + [1023], walk_exact, cap=60000, hub_min_degree=64) > 0
+    ws = kggen.config5(0.0003)                          # sharded: rows read from pinned host memory
+    live = np.nonzero(np.diff(oracle.khop(ws.num_entities, ws.subj, ws.rel, ws.obj, ws.seed_off, ws.seeds, 2,
+                                          None)[0]) > 3)[0]
+    assert check_bulk(ws, 2, [int(x) for x in live[:3]], walk_exact, cap=20000, num_shards=4) > 0
