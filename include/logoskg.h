@@ -66,10 +66,10 @@ typedef struct {
     int32_t hub_min_degree;          /* rows with at least this many edges take the
                                         block-per-row kernels; 0 = default (1024).  Never changes
                                         results.                                                 */
-    int32_t host_build;              /* 0: a resident graph is sorted on the GPU (the triples
-                                        are copied to HBM first).  1: counting sorts on the host.
-                                        Both give the same arrays.  Sharded graphs are always
-                                        sorted on the host.                                      */
+    int32_t host_build;              /* 0: the two sorts of the triple list run on the GPU (the
+                                        triples are copied to HBM first; a sharded graph's sorted
+                                        arrays are copied back to pinned host memory).  1: counting
+                                        sorts on the host.  Both give the same arrays.           */
     const char *shard_dir;           /* NULL: the shards stay in pinned host memory.  Else a
                                         directory (it must exist): every shard is written to
                                         <shard_dir>/shard_<i>.lkg at build and read from there

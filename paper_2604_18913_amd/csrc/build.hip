@@ -230,8 +230,9 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         set_error("shard_dir needs num_shards > 1");
         return LOGOSKG_EINVAL;
     }
-    const bool device_build = o.num_shards <= 1 && !o.host_build;  // else ids are checked here
-    for (int64_t t = 0; !device_build && t < T; ++t) {
+    const bool device_build = o.num_shards <= 1 && !o.host_build;
+    const bool device_sorts = !o.host_build;  // then the ids are checked on the device
+    for (int64_t t = 0; !device_sorts && t < T; ++t) {
         if ((uint32_t)subj[t] >= (uint32_t)E || (uint32_t)obj[t] >= (uint32_t)E ||
             (uint32_t)rel[t] >= (uint32_t)R) {
             set_error("triple %lld = (%d, %d, %d) is out of range", (long long)t, subj[t], rel[t], obj[t]);
@@ -289,6 +290,16 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
             g->row_begin = g->out_off;
             subject_row_counts(ooff);
             if ((st = object_row_classes(ioff)) != LOGOSKG_OK) return fail(st);
+        } else if (device_sorts) {
+            // a sharded graph whose two sorts run on the device; the sorted arrays go to pinned host memory
+            TripleSorter *sorter = nullptr;
+            if ((st = sorter_create(g, subj, rel, obj, &sorter)) != LOGOSKG_OK) return fail(st);
+            std::unique_ptr<TripleSorter, void (*)(TripleSorter *)> guard(sorter, sorter_destroy);
+            std::vector<uint32_t> ooff;
+            if ((st = sorter_offsets(sorter, false, &ooff)) != LOGOSKG_OK) return fail(st);
+            subject_row_counts(ooff);
+            if ((st = upload(&g->out_off, ooff, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
+            if ((st = build_shards(g, subj, rel, obj, &o, ooff, sorter)) != LOGOSKG_OK) return fail(st);
         } else {
         // out-degrees are needed by both the resident and the sharded form
         std::vector<uint32_t> ooff((size_t)E + 1, 0);
@@ -298,7 +309,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         if ((st = upload(&g->out_off, ooff, &g->static_bytes)) != LOGOSKG_OK) return fail(st);
 
         if (g->num_shards > 1) {
-            if ((st = build_shards(g, subj, rel, obj, &o)) != LOGOSKG_OK) return fail(st);
+            if ((st = build_shards(g, subj, rel, obj, &o, ooff, nullptr)) != LOGOSKG_OK) return fail(st);
         } else {
             g->row_begin = g->out_off;
             {   // SUB: stable counting sort by subject

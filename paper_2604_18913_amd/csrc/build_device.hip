@@ -1,6 +1,7 @@
-// Device-side part of logoskg_build for a resident graph: the two stable sorts
-// of the triple list (by subject for SUB, by object for OBJ, Sec. 3.2, Eq. 1-3)
-// run on the GPU.  A least-significant-digit radix sort of (key, triple index)
+// Device-side part of logoskg_build: the two stable sorts of the triple list
+// (by subject for SUB, by object for OBJ, Sec. 3.2, Eq. 1-3) run on the GPU, for
+// a resident graph (the sorted arrays stay in HBM) and for a sharded one (the
+// sorted arrays go to pinned host memory, the subject order grouped by shard).  A least-significant-digit radix sort of (key, triple index)
 // pairs is stable, so triple indices ascend inside a row exactly as in the host
 // counting sort; the row offsets come from a histogram and a prefix sum.  The
 // sort and the scan are rocPRIM's device-wide primitives; everything else is a
@@ -171,6 +172,121 @@ logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const 
     LKG_HIP(hipMemcpy(ooff->data(), g->out_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
     LKG_HIP(hipMemcpy(ioff->data(), g->in_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
     LKG_HIP(hipDeviceSynchronize());
+    return LOGOSKG_OK;
+}
+
+// ---------------------------------------------------------------- sharded graphs
+// The triple list on the device with the scratch of the sorts, alive during logoskg_build only.
+struct TripleSorter {
+    int64_t T = 0;
+    int32_t E = 0;
+    unsigned key_bits = 1;
+    Scratch tmp;
+    int32_t *d_subj = nullptr, *d_rel = nullptr, *d_obj = nullptr;
+    uint32_t *d_iota = nullptr, *d_keys = nullptr, *d_eid = nullptr, *d_off = nullptr, *d_key_in = nullptr;
+    int32_t *d_a = nullptr, *d_b = nullptr;  // gathered 4-byte columns
+    uint16_t *d_r = nullptr;                 // gathered relation ids
+    char *d_tmp = nullptr;
+    size_t tmp_bytes = 0;
+};
+
+__global__ void k_row_keys(const int32_t *__restrict__ subj, long long T, const uint32_t *__restrict__ row_begin,
+                           uint32_t *key) {
+    long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) key[t] = row_begin[subj[t]];
+}
+
+logoskg_status sorter_create(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                             TripleSorter **out) {
+    *out = nullptr;
+    std::unique_ptr<TripleSorter> s(new (std::nothrow) TripleSorter());
+    if (!s) { set_error("out of host memory"); return LOGOSKG_ENOMEM; }
+    const int64_t T = g->T;
+    s->T = T;
+    s->E = g->E;
+    unsigned long long *d_bad = nullptr;
+    LKG_TRY(s->tmp.get(&s->d_subj, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_rel, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_obj, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_iota, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_keys, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_eid, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_key_in, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_a, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_b, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_r, (size_t)T));
+    LKG_TRY(s->tmp.get(&s->d_off, (size_t)g->E + 1));
+    LKG_TRY(s->tmp.get(&d_bad, 1));
+    if (T > 0) {
+        LKG_HIP(hipMemcpy(s->d_subj, subj, (size_t)T * 4, hipMemcpyHostToDevice));
+        LKG_HIP(hipMemcpy(s->d_rel, rel, (size_t)T * 4, hipMemcpyHostToDevice));
+        LKG_HIP(hipMemcpy(s->d_obj, obj, (size_t)T * 4, hipMemcpyHostToDevice));
+    }
+    const unsigned long long none = ~0ull;
+    LKG_HIP(hipMemcpy(d_bad, &none, sizeof(none), hipMemcpyHostToDevice));
+    if (T > 0) {
+        k_check_triples<<<dim3(grid_for(T)), dim3(kBlock)>>>(s->d_subj, s->d_rel, s->d_obj, T, g->E, g->R, d_bad);
+        k_iota<<<dim3(grid_for(T)), dim3(kBlock)>>>(s->d_iota, T);
+    }
+    unsigned long long bad = none;
+    LKG_HIP(hipMemcpy(&bad, d_bad, sizeof(bad), hipMemcpyDeviceToHost));
+    if (bad != none) {
+        set_error("triple %llu = (%d, %d, %d) is out of range", bad, subj[bad], rel[bad], obj[bad]);
+        return LOGOSKG_EINVAL;
+    }
+    while (s->key_bits < 32 && (1ull << s->key_bits) < (unsigned long long)g->E) ++s->key_bits;
+    size_t sort_bytes = 0, scan_bytes = 0;
+    LKG_HIP(rocprim::radix_sort_pairs(nullptr, sort_bytes, s->d_key_in, s->d_keys, s->d_iota, s->d_eid,
+                                      (size_t)std::max<int64_t>(T, 1), 0u, 32u));
+    LKG_HIP(rocprim::inclusive_scan(nullptr, scan_bytes, (uint32_t *)nullptr, (uint32_t *)nullptr, (size_t)g->E + 1,
+                                    rocprim::plus<uint32_t>()));
+    s->tmp_bytes = std::max(sort_bytes, scan_bytes);
+    LKG_TRY(s->tmp.get(&s->d_tmp, s->tmp_bytes));
+    *out = s.release();
+    return LOGOSKG_OK;
+}
+
+void sorter_destroy(TripleSorter *s) { delete s; }
+
+// Row offsets of SUB (by_object = false) or OBJ on the host: off[e] = triples of smaller keys.
+logoskg_status sorter_offsets(TripleSorter *s, bool by_object, std::vector<uint32_t> *off) {
+    const int32_t *key = by_object ? s->d_obj : s->d_subj;
+    LKG_HIP(hipMemsetAsync(s->d_off, 0, ((size_t)s->E + 1) * sizeof(uint32_t), nullptr));
+    if (s->T > 0) k_degrees<<<dim3(grid_for(s->T)), dim3(kBlock)>>>(key, s->T, s->d_off);
+    size_t need = s->tmp_bytes;
+    LKG_HIP(rocprim::inclusive_scan(s->d_tmp, need, s->d_off, s->d_off, (size_t)s->E + 1, rocprim::plus<uint32_t>()));
+    off->resize((size_t)s->E + 1);
+    LKG_HIP(hipMemcpy(off->data(), s->d_off, ((size_t)s->E + 1) * 4, hipMemcpyDeviceToHost));
+    return LOGOSKG_OK;
+}
+
+// Objects and relation ids in the shard-grouped subject order: triples sorted (stably, so triple
+// indices ascend inside a subject) by the place where their subject's run begins.
+logoskg_status sorter_subject_order(TripleSorter *s, const uint32_t *d_row_begin, int32_t *h_obj, uint16_t *h_rel) {
+    const int64_t T = s->T;
+    if (T == 0) return LOGOSKG_OK;
+    k_row_keys<<<dim3(grid_for(T)), dim3(kBlock)>>>(s->d_subj, T, d_row_begin, s->d_key_in);
+    size_t need = s->tmp_bytes;
+    LKG_HIP(rocprim::radix_sort_pairs(s->d_tmp, need, s->d_key_in, s->d_keys, s->d_iota, s->d_eid, (size_t)T, 0u, 32u));
+    k_gather_sub_rows<<<dim3(grid_for(T)), dim3(kBlock)>>>(s->d_eid, T, s->d_obj, s->d_rel, s->d_a, s->d_r);
+    LKG_HIP(hipGetLastError());
+    LKG_HIP(hipMemcpy(h_obj, s->d_a, (size_t)T * 4, hipMemcpyDeviceToHost));
+    LKG_HIP(hipMemcpy(h_rel, s->d_r, (size_t)T * 2, hipMemcpyDeviceToHost));
+    return LOGOSKG_OK;
+}
+
+// Subjects, relation ids and triple indices in object order (rows of OBJ, indices ascending inside a row).
+logoskg_status sorter_object_order(TripleSorter *s, int32_t *h_sub, uint16_t *h_rel, int32_t *h_eid) {
+    const int64_t T = s->T;
+    if (T == 0) return LOGOSKG_OK;
+    size_t need = s->tmp_bytes;
+    LKG_HIP(rocprim::radix_sort_pairs(s->d_tmp, need, reinterpret_cast<const uint32_t *>(s->d_obj), s->d_keys, s->d_iota,
+                                      s->d_eid, (size_t)T, 0u, s->key_bits));
+    k_gather_obj_rows<<<dim3(grid_for(T)), dim3(kBlock)>>>(s->d_eid, T, s->d_subj, s->d_rel, s->d_a, s->d_r, s->d_b);
+    LKG_HIP(hipGetLastError());
+    LKG_HIP(hipMemcpy(h_sub, s->d_a, (size_t)T * 4, hipMemcpyDeviceToHost));
+    LKG_HIP(hipMemcpy(h_rel, s->d_r, (size_t)T * 2, hipMemcpyDeviceToHost));
+    LKG_HIP(hipMemcpy(h_eid, s->d_b, (size_t)T * 4, hipMemcpyDeviceToHost));
     return LOGOSKG_OK;
 }
 

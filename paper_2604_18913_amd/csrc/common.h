@@ -381,6 +381,13 @@ struct FillArgs {
 
 logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
                                    std::vector<uint32_t> *ooff, std::vector<uint32_t> *ioff);
+struct TripleSorter;  // the triple list on the device during a sharded build (build_device.hip)
+logoskg_status sorter_create(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
+                             TripleSorter **out);
+void sorter_destroy(TripleSorter *s);
+logoskg_status sorter_offsets(TripleSorter *s, bool by_object, std::vector<uint32_t> *off);
+logoskg_status sorter_subject_order(TripleSorter *s, const uint32_t *d_row_begin, int32_t *h_obj, uint16_t *h_rel);
+logoskg_status sorter_object_order(TripleSorter *s, int32_t *h_sub, uint16_t *h_rel, int32_t *h_eid);
 logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st);
 void drop_walk_tables(logoskg_result *r);
 void launch_lists(Profiler &prof, const FillArgs &a, int W, hipStream_t st);
@@ -401,6 +408,7 @@ logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, bool 
                                const unsigned long long *hc, hipStream_t st, logoskg_hop_stats *hs);
 void free_shards(logoskg_graph *g);
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel,
-                            const int32_t *obj, const logoskg_build_opts *opts);
+                            const int32_t *obj, const logoskg_build_opts *opts, const std::vector<uint32_t> &ooff,
+                            TripleSorter *sorter);
 
 }  // namespace lkg

@@ -245,12 +245,17 @@ void free_shards(logoskg_graph *g) {
 // the hub list stay in HBM, the per-triple arrays go to pinned host memory and
 // are cut into chunks of whole tiles holding about T / num_shards triples each.
 static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int32_t *subj, const int32_t *rel,
-                                      const int32_t *obj) {
+                                      const int32_t *obj, TripleSorter *sorter) {
     const int32_t E = g->E;
     const int64_t T = g->T;
-    std::vector<uint32_t> ioff((size_t)E + 1, 0);
-    for (int64_t t = 0; t < T; ++t) ioff[(size_t)obj[t] + 1]++;
-    for (int32_t e = 0; e < E; ++e) ioff[(size_t)e + 1] += ioff[e];
+    std::vector<uint32_t> ioff;
+    if (sorter) {
+        LKG_TRY(sorter_offsets(sorter, true, &ioff));
+    } else {
+        ioff.assign((size_t)E + 1, 0);
+        for (int64_t t = 0; t < T; ++t) ioff[(size_t)obj[t] + 1]++;
+        for (int32_t e = 0; e < E; ++e) ioff[(size_t)e + 1] += ioff[e];
+    }
     std::vector<int32_t> longrows;  // rows of more than kTailMaxDegree entries, chunk by chunk
     size_t n4 = std::max<int64_t>(T, 1) * sizeof(int32_t), n2 = std::max<int64_t>(T, 1) * sizeof(uint16_t);
     if (hipHostMalloc((void **)&ss->h_in_sub, n4, hipHostMallocDefault) != hipSuccess ||
@@ -261,7 +266,9 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
         return LOGOSKG_ENOMEM;
     }
     g->pinned_bytes += 2 * n4 + n2;
-    {
+    if (sorter) {
+        LKG_TRY(sorter_object_order(sorter, ss->h_in_sub, ss->h_in_rel, ss->h_in_eid));
+    } else {
         std::vector<uint32_t> cur(ioff.begin(), ioff.end() - 1);
         for (int64_t t = 0; t < T; ++t) {
             uint32_t p = cur[obj[t]]++;
@@ -500,7 +507,7 @@ static logoskg_status shards_to_disk(logoskg_graph *g, ShardSet *ss, const char 
 }
 
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,
-                            const logoskg_build_opts *opts) {
+                            const logoskg_build_opts *opts, const std::vector<uint32_t> &ooff, TripleSorter *sorter) {
     const int n = g->num_shards;
     const int32_t E = g->E;
     const int64_t T = g->T;
@@ -511,7 +518,7 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
 
     // out-degrees
     std::vector<uint32_t> deg((size_t)E, 0);
-    for (int64_t t = 0; t < T; ++t) deg[subj[t]]++;
+    for (int32_t e = 0; e < E; ++e) deg[e] = ooff[(size_t)e + 1] - ooff[e];
     // subjects by (degree desc, id asc); counting sort on the degree keeps it O(E + maxdeg)
     uint32_t maxdeg = 0;
     for (int32_t e = 0; e < E; ++e) maxdeg = std::max(maxdeg, deg[e]);
@@ -558,7 +565,13 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         return LOGOSKG_ENOMEM;
     }
     g->pinned_bytes += ob + rb;
-    {
+    // device metadata: row_begin and the map P
+    LKG_HIP(hipMalloc((void **)&g->row_begin, (size_t)E * sizeof(uint32_t)));
+    LKG_HIP(hipMemcpy(g->row_begin, row_begin.data(), (size_t)E * sizeof(uint32_t), hipMemcpyHostToDevice));
+    g->static_bytes += (size_t)E * sizeof(uint32_t);
+    if (sorter) {
+        LKG_TRY(sorter_subject_order(sorter, g->row_begin, ss->h_obj, ss->h_rel));
+    } else {
         std::vector<uint32_t> cur(row_begin);
         for (int64_t t = 0; t < T; ++t) {
             uint32_t p = cur[subj[t]]++;
@@ -566,10 +579,6 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
             ss->h_rel[p] = (uint16_t)rel[t];
         }
     }
-    // device metadata: row_begin and the map P
-    LKG_HIP(hipMalloc((void **)&g->row_begin, (size_t)E * sizeof(uint32_t)));
-    LKG_HIP(hipMemcpy(g->row_begin, row_begin.data(), (size_t)E * sizeof(uint32_t), hipMemcpyHostToDevice));
-    g->static_bytes += (size_t)E * sizeof(uint32_t);
     {
         std::vector<uint8_t> p8((size_t)g->Epad, 255);
         for (int32_t e = 0; e < E; ++e) if (g->shard_of[e] >= 0) p8[e] = (uint8_t)g->shard_of[e];
@@ -577,7 +586,7 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         LKG_HIP(hipMemcpy(g->shard_of_dev, p8.data(), (size_t)g->Epad, hipMemcpyHostToDevice));
         g->static_bytes += (size_t)g->Epad;
     }
-    LKG_TRY(build_in_chunks(g, ss, subj, rel, obj));
+    LKG_TRY(build_in_chunks(g, ss, subj, rel, obj, sorter));
     // cache slots: each holds one sub-graph, a subject shard (objects + relation ids) or an object
     // range (subjects + relation ids): 6 bytes per triple either way
     int64_t largest = 1;

@@ -240,3 +240,36 @@ def test_prefetch_warms_the_cache_for_the_next_batch():
     g1 = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
     g1.prefetch_shards([0, 5])                        # unsharded: nothing to do
     g1.close()
+
+
+@pytest.mark.parametrize("make", [lambda: kggen.config5(0.0005), lambda: kggen.config3(0.005, k=3)])
+def test_sharded_graph_sorted_on_the_device_equals_the_host_build(make):
+    # the stable sorts of a sharded build run on the GPU by default; host_build=1 keeps the counting
+    # sorts on the host.  Same partition, same results (predecessors and paths read the sorted arrays)
+    m = lkg()
+    w = make()
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
+    pq, pt = kggen.sample_reached_pairs(11, want[0], want[1], 300)
+    cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, pq, pt, 16,
+                                  w.rel_mask)
+    parts = []
+    for host_build in (0, 1):
+        g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, num_shards=8, max_resident_shards=3,
+                    host_build=host_build)
+        for direction in ("push", "pull"):
+            res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask, direction=direction)
+            ent, hop, pred = res.fetch()
+            assert np.array_equal(res.offsets(), want[0]) and np.array_equal(ent.cpu().numpy(), want[1])
+            assert np.array_equal(hop.cpu().numpy(), want[2]) and np.array_equal(pred.cpu().numpy(), want[3])
+            cnt, edges = g.paths(res, pq, pt, 16)
+            assert np.array_equal(cnt.cpu().numpy(), cnt_o) and np.array_equal(edges.cpu().numpy(), edges_o)
+            res.close()
+        parts.append(g.partition() + (g.info(),))
+        g.close()
+    assert np.array_equal(parts[0][0], parts[1][0]) and np.array_equal(parts[0][1], parts[1][1])
+    for key in ("num_out_rows", "num_out_hubs", "num_in_rows", "num_in_hubs", "pinned_host_bytes", "num_object_ranges"):
+        assert parts[0][2][key] == parts[1][2][key], key
+    with pytest.raises(m.LogosKGError):   # ids are checked on the device too
+        bad = w.obj.copy()
+        bad[5] = w.num_entities
+        m.Graph(w.subj, w.rel, bad, w.num_entities, w.num_relations, num_shards=4)
