@@ -193,6 +193,44 @@ def test_config2_full_size_walk_exact_levels():
     cnt, edges = g.walks(res, pq, pt, pl, 16)
     assert np.array_equal(cnt.cpu().numpy(), cnt_o)
     assert np.array_equal(edges.cpu().numpy(), edges_o)
+    # every complete path of length 3 of one query, numbered (bulk export): the total against walk
+    # counts propagated through the triple list in numpy, a page of a million against the properties
+    # a chain list has, and the chains of sampled targets against the oracle's listing
+    q = int(qs[0])
+    t0 = time.time()
+    total = res.walks_count(q, 3)
+    log(f"query {q}: {total:,} complete paths of length 3 counted in {time.time() - t0:.2f}s")
+    c = np.zeros(w.num_entities, dtype=np.int64)
+    c[w.seeds[w.seed_off[q]:w.seed_off[q + 1]]] = 1
+    for _ in range(3):
+        nxt = np.zeros_like(c)
+        live = np.nonzero(c[w.subj])[0]
+        np.add.at(nxt, w.obj[live], c[w.subj[live]])
+        c = nxt
+    assert total == int(c.sum())
+    n_page = min(total, 1_000_000)
+    first = (total - n_page) // 2
+    t0 = time.time()
+    e, t = res.walks_fetch(q, 3, first, n_page)
+    e, t = e.cpu().numpy().astype(np.int64), t.cpu().numpy()
+    log(f"page of {n_page:,} paths from number {first:,}: {time.time() - t0:.2f}s with the copy to the host")
+    seeds = np.zeros(w.num_entities, dtype=bool)
+    seeds[w.seeds[w.seed_off[q]:w.seed_off[q + 1]]] = True
+    assert seeds[w.subj[e[:, 0]]].all() and np.array_equal(w.obj[e[:, 2]], t)
+    assert np.array_equal(w.obj[e[:, 0]], w.subj[e[:, 1]]) and np.array_equal(w.obj[e[:, 1]], w.subj[e[:, 2]])
+    key = np.stack([t.astype(np.int64), e[:, 2], e[:, 1], e[:, 0]], axis=1)   # (target, t_3, t_2, t_1) ascends strictly
+    d = key[1:] - key[:-1]
+    lead = np.argmax(d != 0, axis=1)
+    assert (d[np.arange(len(d)), lead] > 0).all()
+    bounds = np.cumsum(c)   # the chains of target v are numbered bounds[v] - c[v] .. bounds[v] - 1
+    checked = 0
+    for i in np.nonzero((np.array(pl) == 3) & (np.array(pq) == q) & (cnt_o > 0) & (cnt_o < 16))[0][:6]:
+        v, n_v = int(pt[i]), int(cnt_o[i])
+        assert int(c[v]) == n_v
+        e, t = res.walks_fetch(q, 3, int(bounds[v]) - n_v, n_v)
+        assert (t.cpu().numpy() == v).all() and np.array_equal(e.cpu().numpy(), edges_o[i, :n_v, :3])
+        checked += 1
+    log(f"bulk numbering agrees with the oracle's listing for {checked} sampled targets")
     res.close()
     g.close()
 
@@ -295,5 +333,17 @@ def test_config5_full_size_sharded():
     qs = sampled_queries(w.num_queries, 8, 50, np.diff(res.offsets()))
     compare_sample(w, res, qs, w.k)
     log(g.info())
+    # the dense hops pulled over the object ranges; the same batch with every hop pushed through the
+    # subject shards gives the same counts and lists
+    assert [s["direction"] for s in res.hop_stats()] == [1, 2, 2]
+    t0 = time.time()
+    r2 = g.khop(w.seed_off, w.seeds, w.k, direction="push")
+    log(f"khop, every hop pushed: {time.time() - t0:.2f}s")
+    assert np.array_equal(r2.offsets(), res.offsets())
+    for q in qs[:2]:
+        a = [t.cpu().numpy() for t in res.fetch(int(q), int(q) + 1)]
+        b = [t.cpu().numpy() for t in r2.fetch(int(q), int(q) + 1)]
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    r2.close()
     res.close()
     g.close()
