@@ -267,6 +267,15 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
             for (int32_t v : longer)  // longest first
                 if (ioff[(size_t)v + 1] - ioff[v] >= (uint32_t)std::max(kGiantRowMin, g->hub_min)) g->in_rows.n_giant++;
                 else break;
+            {   // segments of the giant rows, for the predecessor pass
+                std::vector<uint32_t> first((size_t)g->in_rows.n_giant + 1, 0);
+                for (int64_t i = 0; i < g->in_rows.n_giant; ++i) {
+                    const int32_t v = longer[(size_t)i];
+                    first[(size_t)i + 1] = first[(size_t)i] + (ioff[(size_t)v + 1] - ioff[v] + kGiantSegment - 1) / kGiantSegment;
+                }
+                g->in_rows.n_giant_segs = first.back();
+                LKG_TRY(upload(&g->in_rows.giant_seg_first, first, &g->static_bytes));
+            }
             g->in_rows.n_tail = (int64_t)tail.size();
             g->in_rows.n_seg = (int64_t)seg.size();
             g->in_rows.n_multi = (int64_t)multi.size();
@@ -391,7 +400,7 @@ extern "C" void logoskg_graph_free(logoskg_graph *g) {
     if (g->ev_rows) (void)hipEventDestroy(g->ev_rows);
 
     void *ptrs[] = {g->out_off, g->out_obj, g->out_rel, g->in_off, g->in_sub, g->in_rel, g->in_eid,
-                    g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->fr_tail,
+                    g->in_rows.tail, g->in_rows.seg, g->in_rows.multi, g->in_rows.longrows, g->in_rows.giant_seg_first, g->fr_tail,
                     g->fr_seg, g->d_ctr, g->long_index, g->row_pred, g->out_eid, g->plane_buf};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);

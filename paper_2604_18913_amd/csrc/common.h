@@ -78,6 +78,7 @@ constexpr int kPullSegment = 1024;      // longer object rows are cut into segme
 constexpr int kPushSegment = 64;        // same for the subject rows of a push frontier
 constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
                                         // (shorter long rows: one wavefront per row)
+constexpr int kGiantSegment = 8192;     // a giant row is walked by one 16-wave block per this many entries
 constexpr int kGiantRowMin = 8192;      // hub rows from this size get a 16-wave block in the predecessor pass, smaller ones 4 waves
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
 constexpr int kSuperTiles = 16;         // tiles per super tile (1024 entities)
@@ -110,6 +111,8 @@ struct RowClasses {             // device work lists over the object rows, split
                                   // have >= hub_min entries
     int64_t n_tail = 0, n_seg = 0, n_multi = 0, n_hub = 0, n_long = 0;
     int64_t n_giant = 0;  // the first n_giant long rows have >= kGiantRowMin entries
+    uint32_t *giant_seg_first = nullptr;  // [n_giant + 1] segments of kGiantSegment entries before every giant row
+    int64_t n_giant_segs = 0;
 };
 
 // ---------------------------------------------------------------- profiling
@@ -377,6 +380,8 @@ struct FillArgs {
     unsigned long long *stats_pred, *stats_hub, *stats_mid;  // rows / edges / lines counters or NULL
     int fuse_lists;  // the 16-word tile kernel also writes the entity and hop lists
     long long n_giant_rows;  // hub rows of the launch that get a 16-wave block (the first ones); -1 = all
+    const uint32_t *giant_seg_first;  // [n_giant_rows + 1] or NULL: a block per giant row instead of one per segment
+    long long n_giant_segs;
 };
 
 logoskg_status build_csr_on_device(logoskg_graph *g, const int32_t *subj, const int32_t *rel, const int32_t *obj,

@@ -345,7 +345,7 @@ __device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool c
     const int lw = lane() & (W - 1);
     unsigned long long cm = __ballot(cand);
     int gathered = 0;
-    constexpr int NR = 2;
+    constexpr int NR = 4;
     while (cm) {
         gathered += min(__popcll(cm), NR * (64 / W));
         int p[NR];
@@ -1009,14 +1009,31 @@ k_pred_emit(FillArgs a, const unsigned long long *__restrict__ codes, const unsi
 // edge id any of them found (LDS atomicMin); after the step the resolved queries
 // are removed from the shared mask, so a later step (larger edge ids) never
 // touches them.  Each predecessor is then written once.
-template <int W, bool MASK, bool STATS, bool BUF>
+// SEG (row-buffer mode only): a block per kGiantSegment entries of a giant row instead of one per
+// row; the blocks of a row keep the smallest edge id per query in the row's line of the row buffer
+// (atomicMin; the line starts at INT_MAX).  A block that walks a whole 140,000-entry row is a chain
+// of dependent gathers that outlasts everything else in the launch; the segments of a row run side
+// by side, at the price of the early exit between them (it saved a quarter of the entries).
+template <int W, bool MASK, bool STATS, bool BUF, bool SEG = false>
 __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
+    static_assert(!SEG || BUF, "segments merge in the row buffer");
     constexpr int Qp = 64 * W;
     constexpr int C = 4;  // 64-entry chunks per wavefront and step, loaded together
     __shared__ long long slot[BUF ? 1 : Qp];
     __shared__ int smin[Qp];
     __shared__ unsigned long long srem[16], slevel[16];
-    const int ev = a.rows[first_row + blockIdx.x];
+    long long row_i = blockIdx.x;
+    uint32_t seg = 0;
+    if (SEG) {  // the giant row this segment belongs to: last row whose first segment is <= blockIdx.x
+        long long lo_r = 0, hi_r = a.n_giant_rows;
+        while (hi_r - lo_r > 1) {
+            const long long m = (lo_r + hi_r) >> 1;
+            if (a.giant_seg_first[m] <= blockIdx.x) lo_r = m; else hi_r = m;
+        }
+        row_i = lo_r;
+        seg = blockIdx.x - a.giant_seg_first[lo_r];
+    }
+    const int ev = a.rows[first_row + row_i];
     const int t = threadIdx.x, wave = t >> 6, nw = blockDim.x >> 6, v = lane(), lw = v & (W - 1);
     // gridDim.y > 1: one block per (row, hop level), so the levels of a long row run side by side
     const int h_first = gridDim.y > 1 ? (int)blockIdx.y + 1 : 1, h_last = gridDim.y > 1 ? h_first : a.k;
@@ -1026,8 +1043,10 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         if (!wave_any(x != 0)) return;  // the same words in every wavefront
     }
     if (!BUF) row_slots<W>(a, ev, wave, nw, slot);
-    int32_t *out = BUF ? a.row_pred + (size_t)(first_row + blockIdx.x) * Qp : a.pred;
-    const uint32_t lo = a.in_off[ev], hi = a.in_off[ev + 1];
+    int32_t *out = BUF ? a.row_pred + (size_t)(first_row + row_i) * Qp : a.pred;
+    const uint32_t row_lo = a.in_off[ev], row_hi = a.in_off[ev + 1];
+    const uint32_t lo = SEG ? row_lo + seg * (uint32_t)kGiantSegment : row_lo;
+    const uint32_t hi = SEG ? min(row_hi, lo + (uint32_t)kGiantSegment) : row_hi;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     for (int h = h_first; h <= h_last; ++h) {
         __syncthreads();
@@ -1086,7 +1105,13 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         }
         __syncthreads();
         for (int q = t; q < Qp; q += blockDim.x)
-            if ((slevel[q >> 6] >> (q & 63)) & 1ull) out[BUF ? (long long)q : slot[q]] = smin[q];
+            if ((slevel[q >> 6] >> (q & 63)) & 1ull) {
+                if (SEG) {
+                    if (smin[q] != INT_MAX) atomicMin(&out[q], smin[q]);
+                } else {
+                    out[BUF ? (long long)q : slot[q]] = smin[q];
+                }
+            }
     }
     if (STATS && v == 0) {
         if (n_rows) atomicAdd(&a.stats_hub[0], (unsigned long long)n_rows);
@@ -1253,6 +1278,14 @@ bool pred_uses_staged_kernel(const FillArgs &a, int W) {
     return W == 16 && a.k <= kSlicedMaxK && a.plane_buf != nullptr;
 }
 
+__global__ void k_fill_int(int32_t *p, long long n, int32_t value) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+template <int W>
+constexpr long long Qp_of() { return 64 * W; }
+
 template <int W, bool MASK, bool STATS>
 static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_rows, long long n_other_rows,
                             hipStream_t st_tiles, hipStream_t st_hub) {
@@ -1280,7 +1313,11 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         // sets the duration of the launch
         const unsigned levels = (unsigned)std::max(a.k, 1);
         if (a.row_pred) {  // into the row buffer, from which the list writer takes them
-            if (giants > 0)
+            if (giants > 0 && a.giant_seg_first && giants == a.n_giant_rows) {
+                k_fill_int<<<dim3((unsigned)((giants * Qp_of<W>() + 255) / 256)), dim3(256), 0, st_hub>>>(
+                    a.row_pred, giants * Qp_of<W>(), INT_MAX);
+                k_pred_row<W, MASK, STATS, true, true><<<dim3((unsigned)a.n_giant_segs, levels), dim3(1024), 0, st_hub>>>(a, 0);
+            } else if (giants > 0)
                 k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
             if (n_hub_rows > giants)
                 k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
@@ -1403,7 +1440,7 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     hipStream_t st = (hipStream_t)stream;
     r->last_stream = st;
     const int W = r->W;
-    FillArgs a;
+    FillArgs a = {};
     a.E = g->E; a.Q = r->Q; a.k = r->k; a.q0 = q0; a.q1 = q1; a.hub_min = g->hub_min;
     a.tile_ent = r->tile_ent; a.cpos = r->cpos; a.n_listed = r->n_active;
     a.ntiles = r->tile_ent ? (r->n_active + 63) / 64 : r->Epad / kTileEntities;
@@ -1417,6 +1454,8 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
     a.plane_buf = nullptr; a.plane_buf_bytes = 0; a.ev_rows = nullptr;
     a.n_giant_rows = g->num_shards > 1 ? -1 : g->in_rows.n_giant;
+    a.giant_seg_first = g->num_shards > 1 ? nullptr : g->in_rows.giant_seg_first;
+    a.n_giant_segs = g->num_shards > 1 ? 0 : g->in_rows.n_giant_segs;
     if (pred && W == 16) {
         LKG_TRY(prepare_row_pred(g, st));
         a.long_index = g->long_index;
