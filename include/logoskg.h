@@ -45,7 +45,11 @@ typedef enum {
     LOGOSKG_EIO = 6        /* a shard file could not be written or read                    */
 } logoskg_status;
 
-#define LOGOSKG_MAX_QUERIES 1024 /* queries per logoskg_khop call: 16 uint64 words per entity */
+#define LOGOSKG_MAX_QUERIES 1024 /* queries per logoskg_khop call: 16 uint64 words per entity.
+                                    A larger workload (the 4,096 queries of the hub-heavy
+                                    benchmark shape) is run by the caller as consecutive calls on
+                                    slices of its queries, each slice's seed_off rebased to 0:
+                                    queries are independent, so the results concatenate.        */
 #define LOGOSKG_MAX_K 254
 #define LOGOSKG_MAX_PATHS 16
 
@@ -77,6 +81,18 @@ typedef struct {
                                         tau_io of a miss), through one pinned staging buffer per
                                         cache slot.  The files are left in place at
                                         logoskg_graph_free.  Only with num_shards > 1.           */
+    /* Optional allocator for the memory the calls on this graph take and give back (bit planes,
+     * bitmaps, count tables, list bookkeeping, workspaces: the graph's pool), so that a harness
+     * can hand out memory it owns (a framework's caching allocator).  dev_alloc returns device
+     * memory on `device`, at least 256-byte aligned, or NULL (reported as LOGOSKG_ENOMEM);
+     * dev_free takes back exactly what dev_alloc returned, from logoskg_graph_free at the latest.
+     * Both run on the calling thread, never inside a kernel launch sequence that a stream
+     * capture could see.  Both NULL (or a struct_size that ends before them): hipMalloc /
+     * hipFree.  The graph's own arrays (sorted triples, work lists, cache slots) are allocated
+     * with hipMalloc at build either way.                                                      */
+    void *(*dev_alloc)(size_t bytes, void *alloc_ctx);
+    void (*dev_free)(void *ptr, void *alloc_ctx);
+    void *alloc_ctx;
 } logoskg_build_opts;
 
 /*

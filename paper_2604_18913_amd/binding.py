@@ -32,7 +32,12 @@ class _BuildOpts(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("device", ctypes.c_int32),
                 ("num_shards", ctypes.c_int32), ("max_resident_shards", ctypes.c_int32),
                 ("hbm_shard_budget_bytes", ctypes.c_uint64), ("hub_min_degree", ctypes.c_int32),
-                ("host_build", ctypes.c_int32), ("shard_dir", ctypes.c_char_p)]
+                ("host_build", ctypes.c_int32), ("shard_dir", ctypes.c_char_p),
+                ("dev_alloc", ctypes.c_void_p), ("dev_free", ctypes.c_void_p), ("alloc_ctx", ctypes.c_void_p)]
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
 
 class _QueryBatch(ctypes.Structure):
@@ -308,11 +313,14 @@ class Graph:
 
     ``num_shards`` > 1 keeps the subject-sorted triples outside HBM, shard by shard (pinned host
     memory, or files under ``shard_dir``), behind a cache of ``max_resident_shards`` /
-    ``hbm_shard_budget_bytes``; ``host_build`` sorts a resident graph on the host."""
+    ``hbm_shard_budget_bytes``; ``host_build`` sorts the triples on the host.  ``dev_alloc(nbytes) ->
+    device address (0 = out of memory)`` and ``dev_free(address)`` become the allocator of the memory
+    the calls on this graph take and give back (``logoskg_build_opts.dev_alloc / dev_free``)."""
 
     def __init__(self, subj, rel, obj, num_entities: int, num_relations: int, device: int = 0,
                  num_shards: int = 0, max_resident_shards: int = 0, hbm_shard_budget_bytes: int = 0,
-                 hub_min_degree: int = 0, host_build: bool = False, shard_dir: Optional[str] = None):
+                 hub_min_degree: int = 0, host_build: bool = False, shard_dir: Optional[str] = None,
+                 dev_alloc=None, dev_free=None):
         lib = _load()
         torch = _torch()
         if not _NP:
@@ -324,9 +332,14 @@ class Graph:
         obj = np.ascontiguousarray(obj, dtype=np.int32)
         if not (subj.shape == rel.shape == obj.shape and subj.ndim == 1):
             raise ValueError("subj, rel, obj must be 1-D arrays of equal length")
+        # the C callbacks stay referenced by the graph for as long as the library may call them
+        self._alloc_cb = None if dev_alloc is None else _ALLOC_FN(lambda nbytes, ctx: dev_alloc(nbytes) or None)
+        self._free_cb = None if dev_free is None else _FREE_FN(lambda ptr, ctx: dev_free(ptr))
         opts = _BuildOpts(ctypes.sizeof(_BuildOpts), device, num_shards, max_resident_shards,
                           hbm_shard_budget_bytes, hub_min_degree, 1 if host_build else 0,
-                          None if shard_dir is None else os.fsencode(shard_dir))
+                          None if shard_dir is None else os.fsencode(shard_dir),
+                          None if self._alloc_cb is None else ctypes.cast(self._alloc_cb, ctypes.c_void_p),
+                          None if self._free_cb is None else ctypes.cast(self._free_cb, ctypes.c_void_p), None)
         h = ctypes.c_void_p()
         _check(lib.logoskg_build(subj.ctypes.data_as(ctypes.c_void_p), rel.ctypes.data_as(ctypes.c_void_p),
                                  obj.ctypes.data_as(ctypes.c_void_p), subj.shape[0], num_entities,

@@ -46,14 +46,10 @@ logoskg_status DevPool::alloc(void **out, size_t bytes, hipStream_t st, bool hav
         return LOGOSKG_OK;
     }
     void *p = nullptr;
-    hipError_t e = hipMalloc(&p, bytes);
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
+    if (!raw_alloc(&p, bytes)) {
         trim();  // give cached blocks back and retry once
-        e = hipMalloc(&p, bytes);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            set_error("hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        if (!raw_alloc(&p, bytes)) {
+            set_error("device allocation of %zu bytes failed%s", bytes, alloc_fn_ ? " (caller's allocator)" : "");
             return LOGOSKG_ENOMEM;
         }
     }
@@ -61,6 +57,22 @@ logoskg_status DevPool::alloc(void **out, size_t bytes, hipStream_t st, bool hav
     live_[p] = bytes;
     *out = p;
     return LOGOSKG_OK;
+}
+
+bool DevPool::raw_alloc(void **p, size_t bytes) {
+    if (alloc_fn_) {
+        *p = alloc_fn_(bytes, ctx_);
+        return *p != nullptr;
+    }
+    if (hipMalloc(p, bytes) == hipSuccess) return true;
+    (void)hipGetLastError();
+    *p = nullptr;
+    return false;
+}
+
+void DevPool::raw_free(void *p) {
+    if (free_fn_) free_fn_(p, ctx_);
+    else (void)hipFree(p);
 }
 
 void DevPool::release(void *p) {
@@ -105,7 +117,7 @@ void DevPool::release_after(void *const *ptrs, const bool *zeroed, int n, hipStr
 void DevPool::trim() {
     for (auto &kv : free_) {
         if (kv.second.after) (void)hipEventSynchronize(kv.second.after->ev);
-        (void)hipFree(kv.second.p);
+        raw_free(kv.second.p);
         held_ -= kv.first;
     }
     free_.clear();
@@ -226,6 +238,10 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         set_error("bad build options");
         return LOGOSKG_EINVAL;
     }
+    if ((o.dev_alloc == nullptr) != (o.dev_free == nullptr)) {
+        set_error("dev_alloc and dev_free must be given together");
+        return LOGOSKG_EINVAL;
+    }
     if (o.shard_dir && o.shard_dir[0] && o.num_shards <= 1) {
         set_error("shard_dir needs num_shards > 1");
         return LOGOSKG_EINVAL;
@@ -253,6 +269,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     g->Epad = ((int64_t)E + 63) / 64 * 64;
     g->hub_min = o.hub_min_degree > 0 ? std::max(o.hub_min_degree, kTailMaxDegree + 1) : kDefaultHubMin;
     g->num_shards = o.num_shards > 1 ? o.num_shards : 1;
+    if (o.dev_alloc) g->pool.set_allocator(o.dev_alloc, o.dev_free, o.alloc_ctx);
 
     logoskg_status st = LOGOSKG_OK;
     auto fail = [&](logoskg_status s) { logoskg_graph_free(g); return s; };

@@ -16,7 +16,7 @@
 
 #include "logoskg.h"
 
-static_assert(sizeof(logoskg_build_opts) == 40 && sizeof(logoskg_graph_info) == 120,
+static_assert(sizeof(logoskg_build_opts) == 64 && sizeof(logoskg_graph_info) == 120,
               "the ctypes binding mirrors these layouts");
 
 namespace lkg {
@@ -59,6 +59,12 @@ public:
     void release_after(void *const *ptrs, const bool *zeroed, int n, hipStream_t st);
     void trim();  // hipFree everything that is not handed out
     size_t bytes_held() const { return held_; }
+    // the caller's allocator instead of hipMalloc / hipFree (set before the first alloc)
+    void set_allocator(void *(*alloc_fn)(size_t, void *), void (*free_fn)(void *, void *), void *ctx) {
+        alloc_fn_ = alloc_fn;
+        free_fn_ = free_fn;
+        ctx_ = ctx;
+    }
     ~DevPool();
 
 private:
@@ -69,6 +75,11 @@ private:
     std::unordered_map<void *, size_t> live_;
     std::vector<hipEvent_t> spare_events_;
     size_t held_ = 0;
+    void *(*alloc_fn_)(size_t, void *) = nullptr;
+    void (*free_fn_)(void *, void *) = nullptr;
+    void *ctx_ = nullptr;
+    bool raw_alloc(void **p, size_t bytes);
+    void raw_free(void *p);
 };
 
 // ---------------------------------------------------------------- graph

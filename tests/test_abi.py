@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_header():
     from paper_2604_18913_amd import binding as b
     # sizes follow from the field lists in logoskg.h under the x86-64 SysV ABI
-    assert ctypes.sizeof(b._BuildOpts) == 40
+    assert ctypes.sizeof(b._BuildOpts) == 64
     assert ctypes.sizeof(b._QueryBatch) == 56
     assert ctypes.sizeof(b._HopStats) == 56
     assert ctypes.sizeof(b._ResultInfo) == 48

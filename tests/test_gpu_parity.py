@@ -318,3 +318,52 @@ def test_bad_inputs_are_reported_not_faulted():
         res.fetch(out=(small, None, None))
     res.close()
     g.close()
+
+
+def test_the_callers_allocator_serves_the_memory_of_the_calls():
+    # logoskg_build_opts.dev_alloc / dev_free: planes, tables and workspaces of the calls come from
+    # the caller (here torch's caching allocator); same results, every block given back
+    import torch
+    m = lkg()
+    w = kggen.config3(0.004, k=3)
+    want = oracle.khop(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, w.rel_mask)
+    held, calls = {}, {"alloc": 0, "free": 0, "bytes": 0}
+
+    def dev_alloc(nbytes):
+        t = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+        held[t.data_ptr()] = t
+        calls["alloc"] += 1
+        calls["bytes"] += nbytes
+        return t.data_ptr()
+
+    def dev_free(ptr):
+        del held[ptr]
+        calls["free"] += 1
+
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, dev_alloc=dev_alloc, dev_free=dev_free)
+    for _ in range(2):
+        res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+        ent, hop, pred = res.fetch()
+        assert np.array_equal(res.offsets(), want[0]) and np.array_equal(ent.cpu().numpy(), want[1])
+        assert np.array_equal(hop.cpu().numpy(), want[2]) and np.array_equal(pred.cpu().numpy(), want[3])
+        pq, pt = kggen.sample_reached_pairs(3, want[0], want[1], 200)
+        cnt, edges = g.paths(res, pq, pt, 16)
+        cnt_o, edges_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, w.k, pq, pt, 16,
+                                      w.rel_mask)
+        assert np.array_equal(cnt.cpu().numpy(), cnt_o) and np.array_equal(edges.cpu().numpy(), edges_o)
+        res.close()
+    plane_bytes = (w.num_entities + 63) // 64 * 64 * 16 * 8 * (w.k + 2)
+    assert calls["alloc"] >= 3 and calls["bytes"] >= plane_bytes      # the planes alone are that large
+    first_round = calls["alloc"]
+    res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)                # a third call reuses the pool's blocks
+    res.close()
+    assert calls["alloc"] == first_round
+    g.close()
+    assert calls["free"] == calls["alloc"] and not held
+    with pytest.raises(m.LogosKGError):                               # one callback without the other
+        m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, dev_alloc=dev_alloc)
+    fail = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, dev_alloc=lambda n: 0,
+                   dev_free=lambda p: None)
+    with pytest.raises(m.LogosKGError):                               # an allocator that has nothing left
+        fail.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+    fail.close()
