@@ -66,7 +66,11 @@ struct ShardSet {
     ShortRow *d_tail = nullptr;
     PullSegment *d_seg = nullptr;
     int32_t *d_multi = nullptr;
-    int units() const { return n + (int)chunks.size(); }  // cacheable sub-graphs: shards, then object ranges
+    // cacheable units: the shards, then the object ranges (subjects + relation ids of their rows of
+    // OBJ), then the triple indices of the object ranges (read by the predecessor pass only)
+    int units() const { return n + 2 * (int)chunks.size(); }
+    int range_unit(int c) const { return n + c; }
+    int index_unit(int c) const { return n + (int)chunks.size() + c; }
     size_t stage_edges = 0;
     int32_t *stage_sub[2] = {nullptr, nullptr}, *stage_eid[2] = {nullptr, nullptr};
     uint16_t *stage_rel[2] = {nullptr, nullptr};
@@ -366,14 +370,6 @@ static logoskg_status build_in_chunks(logoskg_graph *g, ShardSet *ss, const int3
         LKG_HIP(hipMemcpy(g->in_rows.longrows, longrows.data(), longrows.size() * sizeof(int32_t),
                           hipMemcpyHostToDevice));
     ss->stage_edges = std::max<size_t>(ss->stage_edges, 1);
-    for (int i = 0; i < 2; ++i) {
-        LKG_HIP(hipMalloc((void **)&ss->stage_sub[i], ss->stage_edges * sizeof(int32_t)));
-        LKG_HIP(hipMalloc((void **)&ss->stage_eid[i], ss->stage_edges * sizeof(int32_t)));
-        LKG_HIP(hipMalloc((void **)&ss->stage_rel[i], ss->stage_edges * sizeof(uint16_t)));
-        g->static_bytes += ss->stage_edges * 10;
-        LKG_HIP(hipEventCreateWithFlags(&ss->stage_ready[i], hipEventDisableTiming));
-        LKG_HIP(hipEventCreateWithFlags(&ss->stage_idle[i], hipEventDisableTiming));
-    }
     return LOGOSKG_OK;
 }
 
@@ -385,11 +381,72 @@ long long max_chunk_rows(const logoskg_graph *g) {
     return m;
 }
 
-// Predecessor pass of a sharded graph: the object-sorted triples are streamed
-// chunk by chunk (double buffered: the next chunk copies while this one runs).
+static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStream_t compute, int *slot_out);
+
+// The two staging buffers of the streamed predecessor pass, allocated at its first use.
+static logoskg_status ensure_staging(logoskg_graph *g, ShardSet *ss) {
+    if (ss->stage_sub[0]) return LOGOSKG_OK;
+    for (int i = 0; i < 2; ++i) {
+        LKG_HIP(hipMalloc((void **)&ss->stage_sub[i], ss->stage_edges * sizeof(int32_t)));
+        LKG_HIP(hipMalloc((void **)&ss->stage_eid[i], ss->stage_edges * sizeof(int32_t)));
+        LKG_HIP(hipMalloc((void **)&ss->stage_rel[i], ss->stage_edges * sizeof(uint16_t)));
+        g->static_bytes += ss->stage_edges * 10;
+        LKG_HIP(hipEventCreateWithFlags(&ss->stage_ready[i], hipEventDisableTiming));
+        LKG_HIP(hipEventCreateWithFlags(&ss->stage_idle[i], hipEventDisableTiming));
+    }
+    return LOGOSKG_OK;
+}
+
+// Predecessor pass of a sharded graph, object range after object range.  With four or more cache
+// slots the rows of OBJ come through the cache: a range's subjects and relation ids (the unit the
+// pull hops use) and its triple indices (a unit of their own) are made resident like a shard, so
+// a cache that holds the graph serves every fetch without a copy.  A smaller cache would only
+// thrash: then the three arrays are streamed through two staging buffers (the next range copies
+// while this one runs).
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st) {
     ShardSet *ss = (ShardSet *)g->shards;
     if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
+    auto launch = [&](const ShardSet::Chunk &c, const int32_t *sub, const uint16_t *rel, const int32_t *eid) {
+        FillArgs x = *a;
+        x.in_sub = sub - c.edge_begin;
+        x.in_eid = eid - c.edge_begin;
+        x.in_rel = rel - c.edge_begin;
+        x.tile_begin = c.tile_begin;
+        x.tile_count = c.tile_count;
+        x.rows = g->in_rows.longrows + c.row_begin;
+        x.row_base = c.row_begin;
+        launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st, st);
+    };
+    if (ss->n_slots >= 4) {
+        const size_t nc = ss->chunks.size();
+        std::vector<int> s_range(nc, -1), s_index(nc, -1);
+        auto make_resident = [&](size_t ci) -> logoskg_status {
+            if (ss->chunks[ci].edge_count == 0 || s_range[ci] >= 0) return LOGOSKG_OK;
+            LKG_TRY(acquire(g, ss, ss->range_unit((int)ci), st, &s_range[ci]));
+            LKG_TRY(acquire(g, ss, ss->index_unit((int)ci), st, &s_index[ci]));
+            return LOGOSKG_OK;
+        };
+        for (size_t ci = 0; ci < nc; ++ci) {
+            const ShardSet::Chunk &c = ss->chunks[ci];
+            LKG_TRY(make_resident(ci));
+            if (c.edge_count > 0) {
+                LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[s_range[ci]], 0));
+                LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[s_index[ci]], 0));
+            }
+            const int a_slot = c.edge_count > 0 ? s_range[ci] : 0, b_slot = c.edge_count > 0 ? s_index[ci] : 0;
+            launch(c, ss->slot_obj[a_slot], ss->slot_rel[a_slot], ss->slot_obj[b_slot]);
+            LKG_HIP(hipGetLastError());
+            if (c.edge_count > 0) {
+                LKG_HIP(hipEventRecord(ss->slot_idle[s_range[ci]], st));
+                LKG_HIP(hipEventRecord(ss->slot_idle[s_index[ci]], st));
+            }
+            // the next range's two units are asked for while this one runs: the two in use are the
+            // most recently used, so with four slots they are not the ones evicted
+            if (ci + 1 < nc) LKG_TRY(make_resident(ci + 1));
+        }
+        return LOGOSKG_OK;
+    }
+    LKG_TRY(ensure_staging(g, ss));
     auto issue = [&](size_t ci) -> logoskg_status {
         const ShardSet::Chunk &c = ss->chunks[ci];
         const int b = (int)(ci & 1);
@@ -415,15 +472,7 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
         const int b = (int)(ci & 1);
         if (ci + 1 < ss->chunks.size()) LKG_TRY(issue(ci + 1));
         LKG_HIP(hipStreamWaitEvent(st, ss->stage_ready[b], 0));
-        FillArgs x = *a;
-        x.in_sub = ss->stage_sub[b] - c.edge_begin;
-        x.in_eid = ss->stage_eid[b] - c.edge_begin;
-        x.in_rel = ss->stage_rel[b] - c.edge_begin;
-        x.tile_begin = c.tile_begin;
-        x.tile_count = c.tile_count;
-        x.rows = g->in_rows.longrows + c.row_begin;
-        x.row_base = c.row_begin;
-        launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st, st);
+        launch(c, ss->stage_sub[b], ss->stage_rel[b], ss->stage_eid[b]);
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->stage_idle[b], st));
     }
@@ -635,7 +684,10 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
 // copy on the copy stream (after the kernels that last read the slot).  Units below
 // ss->n are subject shards, the others object ranges (always kept in pinned memory).
 static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStream_t compute, int *slot_out) {
+    const int nc = (int)ss->chunks.size();
     const bool range = shard >= ss->n;
+    const bool index = shard >= ss->n + nc;           // triple indices of an object range: 4 bytes per triple
+    const int chunk = range ? (shard - ss->n) % std::max(nc, 1) : 0;
     int slot = ss->shard_slot[shard];
     if (slot >= 0) {
         ss->hits++;
@@ -650,10 +702,10 @@ static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStre
             ss->shard_slot[ss->slot_shard[slot]] = -1;
             ss->evictions++;
         }
-        int64_t b = range ? ss->chunks[(size_t)(shard - ss->n)].edge_begin : ss->edge_begin[shard];
-        int64_t cnt = range ? ss->chunks[(size_t)(shard - ss->n)].edge_count : ss->edge_begin[(size_t)shard + 1] - b;
-        const int32_t *src_obj = range ? ss->h_in_sub + b : (ss->h_obj ? ss->h_obj + b : nullptr);
-        const uint16_t *src_rel = range ? ss->h_in_rel + b : (ss->h_rel ? ss->h_rel + b : nullptr);
+        int64_t b = range ? ss->chunks[(size_t)chunk].edge_begin : ss->edge_begin[shard];
+        int64_t cnt = range ? ss->chunks[(size_t)chunk].edge_count : ss->edge_begin[(size_t)shard + 1] - b;
+        const int32_t *src_obj = index ? ss->h_in_eid + b : range ? ss->h_in_sub + b : (ss->h_obj ? ss->h_obj + b : nullptr);
+        const uint16_t *src_rel = index ? nullptr : range ? ss->h_in_rel + b : (ss->h_rel ? ss->h_rel + b : nullptr);
         if (!range && !ss->fd.empty()) {  // the shard comes from its file, through the slot's staging buffer
             LKG_HIP(hipEventSynchronize(ss->slot_ready[slot]));  // the buffer's last copy has left it
             ShardFileHeader h;
@@ -676,15 +728,16 @@ static logoskg_status acquire(logoskg_graph *g, ShardSet *ss, int shard, hipStre
             g->prof.begin(KK_SHARD_COPY, ss->copy_stream);
             LKG_HIP(hipMemcpyAsync(ss->slot_obj[slot], src_obj, (size_t)cnt * sizeof(int32_t),
                                    hipMemcpyHostToDevice, ss->copy_stream));
-            LKG_HIP(hipMemcpyAsync(ss->slot_rel[slot], src_rel, (size_t)cnt * sizeof(uint16_t),
-                                   hipMemcpyHostToDevice, ss->copy_stream));
+            if (src_rel)
+                LKG_HIP(hipMemcpyAsync(ss->slot_rel[slot], src_rel, (size_t)cnt * sizeof(uint16_t),
+                                       hipMemcpyHostToDevice, ss->copy_stream));
             g->prof.end(ss->copy_stream);
         }
         LKG_HIP(hipEventRecord(ss->slot_ready[slot], ss->copy_stream));
         ss->slot_shard[slot] = shard;
         ss->shard_slot[shard] = slot;
         ss->loads++;
-        ss->bytes_h2d += cnt * (int64_t)(sizeof(int32_t) + sizeof(uint16_t));
+        ss->bytes_h2d += cnt * (int64_t)(sizeof(int32_t) + (src_rel ? sizeof(uint16_t) : 0));
     }
     ss->slot_used[slot] = ++ss->tick;
     (void)compute;
@@ -704,7 +757,7 @@ static logoskg_status run_sharded_pull(logoskg_graph *g, ShardSet *ss, logoskg_r
     std::vector<int> slot_of(order.size(), -1);
     for (size_t i = 0; i < order.size(); ++i) {
         const int c = order[i];
-        if (slot_of[i] < 0) LKG_TRY(acquire(g, ss, ss->n + c, st, &slot_of[i]));
+        if (slot_of[i] < 0) LKG_TRY(acquire(g, ss, ss->range_unit(c), st, &slot_of[i]));
         const int slot = slot_of[i];
         LKG_HIP(hipStreamWaitEvent(st, ss->slot_ready[slot], 0));
         const int64_t b = ss->chunks[(size_t)c].edge_begin;
@@ -713,7 +766,7 @@ static logoskg_status run_sharded_pull(logoskg_graph *g, ShardSet *ss, logoskg_r
         LKG_HIP(hipGetLastError());
         LKG_HIP(hipEventRecord(ss->slot_idle[slot], st));
         if (i + 1 < order.size() && ss->n_slots >= 2 && slot_of[i + 1] < 0)
-            LKG_TRY(acquire(g, ss, ss->n + order[i + 1], st, &slot_of[i + 1]));
+            LKG_TRY(acquire(g, ss, ss->range_unit(order[i + 1]), st, &slot_of[i + 1]));
     }
     return LOGOSKG_OK;
 }

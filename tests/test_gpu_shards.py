@@ -69,15 +69,18 @@ def test_sharded_results_and_cache_counters(make, num_shards, max_resident, dire
     stats = outs[0][4]
     if direction != "auto":
         assert all(s["direction"] in (0, 1 if direction == "push" else 2) for s in stats)
-    seq = accesses(P_o, w, w.k, want[1], want[2], stats, info)
-    # the cache holds sub-graphs of both kinds: the shards and the object ranges of the pull hops
-    units = num_shards + info["num_object_ranges"]
+    # the cache holds the shards, the object ranges of the pull hops, and the triple indices of the
+    # object ranges (for the predecessor pass, which goes through the cache from four slots on)
+    units = num_shards + 2 * info["num_object_ranges"]
     cap = units if max_resident == 0 else min(max_resident, units)
     assert info["cache_slots"] == cap
+    seq = accesses(P_o, w, w.k, want[1], want[2], stats, info)
+    n_hop_accesses = len(seq)
+    seq = seq + part.fetch_accesses(num_shards, info["num_object_ranges"], cap)   # khop, then the lists
     loads, ev, hits = part.lru_counts(seq + seq, cap)   # two identical batches on one graph
     assert (info["shard_loads"], info["shard_evictions"], info["shard_hits"]) == (loads, ev, hits)
     touched = [s["shards_touched"] for s in stats]
-    assert sum(touched) == len(seq)
+    assert sum(touched) == n_hop_accesses
     assert info["pinned_host_bytes"] == 16 * max(w.num_triples, 1)  # 6 B subject-sorted + 10 B object-sorted
 
 

@@ -412,6 +412,9 @@ def test_shard_visit_order_hand_trace():
     assert seq == [0, 2, 6, 5, 4, 4, 5, 6]
     # two slots: 0 L, 2 L, 6 L (evicts 0), 5 L (evicts 2), 4 L (evicts 6), 4 hit, 5 hit, 6 L (evicts 4)
     assert part.lru_counts(seq, 2) == (6, 4, 2)
+    # a fetch of predecessor edges: range 0 and its triple indices, range 1 and its triple indices, ..
+    assert part.fetch_accesses(4, 3, 4) == [4, 7, 5, 8, 6, 9]
+    assert part.fetch_accesses(4, 3, 3) == []      # below four slots the cache is bypassed
     # fewer hops: a prefix of the same trace; an empty frontier ends it
     P = np.array([0, 1], dtype=np.int32)
     assert part.shard_accesses(P, np.array([0], dtype=np.int32), 2, 3, np.array([0, 1], dtype=np.int32),
