@@ -315,9 +315,11 @@ logoskg_status logoskg_result_level_fetch(logoskg_result *r, int32_t h, int32_t 
  * count level h-1 (they replace the level counted by
  * logoskg_result_level_offsets) and keep the level's entity list, one int64
  * per entry and one or two int64 per 256 triples in device memory until the
- * result is freed or another range is prepared.  The first call on a graph builds the triple indices of SUB's
- * rows (4 bytes per triple, freed with the graph).  Needs a resident
- * (unsharded) graph: LOGOSKG_EINVAL otherwise.
+ * result is freed or another range is prepared.  The first call on a graph
+ * builds the triple indices of SUB's rows (4 bytes per triple in device
+ * memory, freed with the graph).  On a sharded graph the kernels read SUB's
+ * rows from the pinned host copy of the shards in place; shards kept in files
+ * (shard_dir) have no such copy: LOGOSKG_EINVAL.
  */
 logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int32_t h, int32_t q_begin, int32_t q_end,
                                               int64_t *triple_off, void *stream);

@@ -15,9 +15,9 @@ INFRASTRUCTURE ONLY, plain Python.
   rows (pull) touches every sub-graph of the partition by object range instead,
   numbered after the shards, in the same alternating order.  Pinned by
   hand-worked traces in tests/test_oracle_pins.py.
-* fetch_accesses: what a fetch of predecessor edges touches when the cache has four or more
-  slots: every object range in ascending order, first the range itself, then its triple indices
-  (units numbered behind the ranges).
+* fetch_accesses: what a fetch of predecessor edges touches when the cache can hold every unit
+  (shards, object ranges, triple indices of the ranges): every object range in ascending order,
+  first the range itself, then its triple indices (units numbered behind the ranges).
 * schedule_queries: the batch-processing order of Sec. 3.4 -- queries grouped by
   the sub-graphs their seeds need (through P), identical needs adjacent, the
   input order kept among equals.
@@ -99,9 +99,9 @@ def shard_accesses(P, subj, num_entities, k, entity, hop, pull_hops=(), num_shar
 
 
 def fetch_accesses(num_shards, num_ranges, capacity):
-    """Units a list fetch with predecessor edges makes resident (none below four cache slots:
-    the object-sorted triples are then streamed past the cache)."""
-    if capacity < 4:
+    """Units a list fetch with predecessor edges makes resident (none when the cache cannot hold
+    all num_shards + 2 * num_ranges units: the object-sorted triples are then streamed past it)."""
+    if capacity < num_shards + 2 * num_ranges:
         return []
     seq = []
     for c in range(num_ranges):

@@ -190,7 +190,7 @@ struct TripleSorter {
     size_t tmp_bytes = 0;
 };
 
-__global__ void k_row_keys(const int32_t *__restrict__ subj, long long T, const uint32_t *__restrict__ row_begin,
+__global__ void k_row_keys(const int32_t *subj, long long T, const uint32_t *__restrict__ row_begin,
                            uint32_t *key) {
     long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < T) key[t] = row_begin[subj[t]];
@@ -295,7 +295,15 @@ logoskg_status sorter_object_order(TripleSorter *s, int32_t *h_sub, uint16_t *h_
 // by subject on (subject, triple index) pairs, so the order is the one of out_obj / out_rel.
 logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st) {
     if (g->out_eid) return LOGOSKG_OK;
-    if (g->num_shards > 1) { set_error("needs a resident (unsharded) graph"); return LOGOSKG_EINVAL; }
+    // a sharded graph keeps the object-sorted triples in pinned host memory (read in place here) and
+    // its rows of SUB in the shard-grouped order: the sort key is the place where a subject's run begins
+    const int32_t *in_sub = g->in_sub, *in_eid = g->in_eid;
+    const uint16_t *in_rel = g->in_rel;
+    const bool sharded = g->num_shards > 1;
+    if (sharded && !shard_in_arrays(g, &in_sub, &in_rel, &in_eid)) {
+        set_error("the object-sorted triples of the sharded graph are not available");
+        return LOGOSKG_EINTERNAL;
+    }
     const int64_t T = g->T;
     Scratch tmp;
     uint32_t *d_subject = nullptr, *d_iota = nullptr, *d_keys = nullptr;
@@ -308,7 +316,11 @@ logoskg_status ensure_out_eid(logoskg_graph *g, hipStream_t st) {
     if (T > 0) {
         unsigned key_bits = 1;
         while (key_bits < 32 && (1ull << key_bits) < (unsigned long long)g->E) ++key_bits;
-        k_subject_of_triple<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(g->in_sub, g->in_eid, T, d_subject);
+        if (sharded) key_bits = 32;
+        k_subject_of_triple<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(in_sub, in_eid, T, d_subject);
+        if (sharded)
+            k_row_keys<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(reinterpret_cast<const int32_t *>(d_subject), T,
+                                                                   g->row_begin, d_subject);
         k_iota<<<dim3(grid_for(T)), dim3(kBlock), 0, st>>>(d_iota, T);
         size_t bytes = 0;
         hipError_t e = rocprim::radix_sort_pairs(nullptr, bytes, d_subject, d_keys, d_iota, (uint32_t *)eid, (size_t)T,

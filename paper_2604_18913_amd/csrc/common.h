@@ -416,6 +416,7 @@ void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigne
                        const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
                        const lkg::RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st);
 void shard_info(const logoskg_graph *g, logoskg_graph_info *o);
+bool shard_out_arrays(const logoskg_graph *g, const int32_t **obj, const uint16_t **rel);
 bool shard_in_arrays(const logoskg_graph *g, const int32_t **sub, const uint16_t **rel, const int32_t **eid);
 void launch_pull_range(logoskg_graph *g, logoskg_result *r, int h, const RowClasses &rc, const int32_t *in_sub,
                        const uint16_t *in_rel, const unsigned long long *hc, bool want_stats, bool first,

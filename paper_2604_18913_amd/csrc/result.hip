@@ -19,11 +19,12 @@
 //           triple of Eq. 5-7 in edge-id order) is found by walking the object
 //           row of the entity with a mask of still unresolved queries, so every
 //           (query, entity) pair is written once.  Object rows of up to 32
-//           entries belong to a tile kernel (k_pred_mt for 16-word planes and
-//           k <= 6, which writes the entity and hop lists as well; k_pred
-//           otherwise) that walks them in ascending edge id; rows of 33 ..
-//           hub_min-1 entries belong to k_pred_wave and longer ones to
-//           k_pred_row, whose lanes claim in parallel and keep the minimum.
+//           entries belong to the tile kernels that walk them in ascending
+//           edge id (for 16-word planes and k <= 6 the pair k_pred_walk /
+//           k_pred_emit, which writes the entity and hop lists as well;
+//           k_pred otherwise); rows of 33 .. hub_min-1 entries belong to
+//           k_pred_wave and longer ones to k_pred_row, whose lanes claim in
+//           parallel and keep the minimum.
 #include <algorithm>
 #include <climits>
 #include <cstdlib>

@@ -397,12 +397,13 @@ static logoskg_status ensure_staging(logoskg_graph *g, ShardSet *ss) {
     return LOGOSKG_OK;
 }
 
-// Predecessor pass of a sharded graph, object range after object range.  With four or more cache
-// slots the rows of OBJ come through the cache: a range's subjects and relation ids (the unit the
+// Predecessor pass of a sharded graph, object range after object range.  When the cache can hold
+// every unit, the rows of OBJ come through it: a range's subjects and relation ids (the unit the
 // pull hops use) and its triple indices (a unit of their own) are made resident like a shard, so
 // a cache that holds the graph serves every fetch without a copy.  A smaller cache would only
-// thrash: then the three arrays are streamed through two staging buffers (the next range copies
-// while this one runs).
+// thrash, and push out what the hops need (measured: 17 slots for 26 units, 284 ms per step with
+// the pass through the cache): then the three arrays are streamed through two staging buffers
+// (the next range copies while this one runs) and the cache is left to the hops.
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st) {
     ShardSet *ss = (ShardSet *)g->shards;
     if (!ss) { set_error("graph has no shards"); return LOGOSKG_EINTERNAL; }
@@ -417,7 +418,7 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
         x.row_base = c.row_begin;
         launch_pred(g->prof, x, W, c.hub_count, c.row_count - c.hub_count, mask, st, st);
     };
-    if (ss->n_slots >= 4) {
+    if (ss->n_slots >= ss->units()) {
         const size_t nc = ss->chunks.size();
         std::vector<int> s_range(nc, -1), s_index(nc, -1);
         auto make_resident = [&](size_t ci) -> logoskg_status {
@@ -440,8 +441,8 @@ logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hip
                 LKG_HIP(hipEventRecord(ss->slot_idle[s_range[ci]], st));
                 LKG_HIP(hipEventRecord(ss->slot_idle[s_index[ci]], st));
             }
-            // the next range's two units are asked for while this one runs: the two in use are the
-            // most recently used, so with four slots they are not the ones evicted
+            // the next range's two units are asked for while this one runs (nothing is evicted: every
+            // unit has a slot)
             if (ci + 1 < nc) LKG_TRY(make_resident(ci + 1));
         }
         return LOGOSKG_OK;
@@ -844,6 +845,16 @@ bool shard_in_arrays(const logoskg_graph *g, const int32_t **sub, const uint16_t
     *sub = ss->h_in_sub;
     *rel = ss->h_in_rel;
     *eid = ss->h_in_eid;
+    return true;
+}
+
+// The subject-sorted triples of a sharded graph in the shard-grouped order (pinned host memory;
+// absent when the shards live in files): for the rows an active-triple export copies.
+bool shard_out_arrays(const logoskg_graph *g, const int32_t **obj, const uint16_t **rel) {
+    const ShardSet *ss = (const ShardSet *)g->shards;
+    if (!ss || !ss->h_obj || !ss->h_rel) return false;
+    *obj = ss->h_obj;
+    *rel = ss->h_rel;
     return true;
 }
 

@@ -333,7 +333,12 @@ extern "C" logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int3
     if (h < 1 || h > r->k) { set_error("hop %d outside [1, %d]", h, r->k); return LOGOSKG_EINVAL; }
     if (q0 < 0 || q1 > r->Q || q0 > q1) { set_error("bad query range [%d, %d)", q0, q1); return LOGOSKG_EINVAL; }
     logoskg_graph *g = r->g;
-    if (g->num_shards > 1) { set_error("active triples need a resident (unsharded) graph"); return LOGOSKG_EINVAL; }
+    const int32_t *out_obj = g->out_obj;
+    const uint16_t *out_rel = g->out_rel;
+    if (g->num_shards > 1 && !shard_out_arrays(g, &out_obj, &out_rel)) {
+        set_error("active triples of a sharded graph need its shards in pinned host memory (not in files)");
+        return LOGOSKG_EINVAL;
+    }
     LKG_HIP(hipSetDevice(g->device));
     hipStream_t st = (hipStream_t)stream;
     r->last_stream = st;
@@ -399,15 +404,15 @@ extern "C" logoskg_status logoskg_result_triples_offsets(logoskg_result *r, int3
             (s = g->pool.alloc((void **)&r->trip_chunk_first, (size_t)(nchunks + 1) * sizeof(long long))) != LOGOSKG_OK)
             return done(s);
         k_chunk_count<<<dim3(blocks_for((nchunks + kExpandChunks) / kExpandChunks, 1)), dim3(kBlock), 0, st>>>(
-            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_ent, g->out_off, g->out_rel, r->allow, r->W,
+            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_ent, g->row_begin, out_rel, r->allow, r->W,
             r->d_level_off, q0, q1, d_count);
         if ((s = prefix_sum(d_count, r->trip_chunk_first, (size_t)nchunks + 1)) != LOGOSKG_OK) return done(s);
         k_pick_offsets<true><<<dim3(nq + 1), dim3(kBlock), 0, st>>>(
-            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_chunk_first, r->trip_ent, g->out_off, g->out_rel,
+            total, nchunks, r->trip_chunk_entry, r->trip_off, r->trip_chunk_first, r->trip_ent, g->row_begin, out_rel,
             r->allow, r->W, r->d_level_off, q0, q1, d_picked);
     } else {
         k_pick_offsets<false><<<dim3(nq + 1), dim3(kBlock), 0, st>>>(
-            total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr, r->trip_ent, g->out_off, g->out_rel, nullptr,
+            total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr, r->trip_ent, g->row_begin, out_rel, nullptr,
             r->W, r->d_level_off, q0, q1, d_picked);
     }
     std::vector<long long> picked((size_t)nq + 1, 0);
@@ -450,17 +455,23 @@ extern "C" logoskg_status logoskg_result_triples_fetch(logoskg_result *r, int32_
     hipStream_t st = (hipStream_t)stream;
     r->last_stream = st;
     const long long total = r->trip_total, nchunks = (total + kBlock - 1) / kBlock;
+    const int32_t *out_obj = g->out_obj;
+    const uint16_t *out_rel = g->out_rel;
+    if (g->num_shards > 1 && !shard_out_arrays(g, &out_obj, &out_rel)) {
+        set_error("active triples of a sharded graph need its shards in pinned host memory (not in files)");
+        return LOGOSKG_EINVAL;
+    }
     dim3 grid(blocks_for((nchunks + kExpandChunks - 1) / kExpandChunks, 1)), block(kBlock);
     {
         ProfScope ps(g->prof, KK_TRIPLES, st);
         if (r->has_mask)
             k_triple_expand<true><<<grid, block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off,
-                                                          r->trip_chunk_first, r->trip_ent, g->out_off, g->out_obj,
-                                                          g->out_rel, g->out_eid, r->allow, r->W, r->d_level_off, q0,
+                                                          r->trip_chunk_first, r->trip_ent, g->row_begin, out_obj,
+                                                          out_rel, g->out_eid, r->allow, r->W, r->d_level_off, q0,
                                                           q1, triple, subject, relation, object);
         else
             k_triple_expand<false><<<grid, block, 0, st>>>(total, nchunks, r->trip_chunk_entry, r->trip_off, nullptr,
-                                                           r->trip_ent, g->out_off, g->out_obj, g->out_rel, g->out_eid,
+                                                           r->trip_ent, g->row_begin, out_obj, out_rel, g->out_eid,
                                                            nullptr, r->W, r->d_level_off, q0, q1, triple, subject,
                                                            relation, object);
     }

@@ -70,7 +70,7 @@ def test_sharded_results_and_cache_counters(make, num_shards, max_resident, dire
     if direction != "auto":
         assert all(s["direction"] in (0, 1 if direction == "push" else 2) for s in stats)
     # the cache holds the shards, the object ranges of the pull hops, and the triple indices of the
-    # object ranges (for the predecessor pass, which goes through the cache from four slots on)
+    # object ranges (for the predecessor pass, which goes through the cache when it holds every unit)
     units = num_shards + 2 * info["num_object_ranges"]
     cap = units if max_resident == 0 else min(max_resident, units)
     assert info["cache_slots"] == cap

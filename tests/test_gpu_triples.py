@@ -77,7 +77,7 @@ def test_whitelists_on_four_and_sixteen_word_planes():
     check(w, 3, True, [(0, 200)])
 
 
-def test_error_paths_and_repeated_calls():
+def test_error_paths_and_repeated_calls(tmp_path):
     m = lkg()
     w = kggen.config2(0.003, num_queries=100)
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
@@ -109,11 +109,23 @@ def test_error_paths_and_repeated_calls():
     assert np.array_equal(b[1].cpu().numpy(), want)
     res.close()
     g.close()
-    # a sharded graph refuses
+    # shards kept in files have no pinned copy of SUB's rows to copy from: refused
     ws = kggen.config5(0.0003)
-    gs = m.Graph(ws.subj, ws.rel, ws.obj, ws.num_entities, ws.num_relations, num_shards=4)
+    gs = m.Graph(ws.subj, ws.rel, ws.obj, ws.num_entities, ws.num_relations, num_shards=4, shard_dir=str(tmp_path))
     rs = gs.khop(ws.seed_off, ws.seeds, 2)
     with pytest.raises(m.LogosKGError):
         rs.active_triples(1, 0, 1)
     rs.close()
     gs.close()
+
+
+@pytest.mark.parametrize("walk_exact", [False, True])
+def test_sharded_graphs_export_the_same_triples(walk_exact):
+    # the rows of SUB are read from the pinned, shard-grouped copy; the triple indices of that order are
+    # sorted out on the device at the first export
+    w = kggen.config5(0.0005)
+    n = check(w, 3, walk_exact, [(0, 40), (1000, 1024)], graph_kw=dict(num_shards=8, max_resident_shards=3))
+    assert n > 0
+    w = kggen.config3(0.004, k=3)
+    n = check(w, 3, walk_exact, [(5, 9), (600, 640)], graph_kw=dict(num_shards=4), host_build=True)
+    assert n > 0

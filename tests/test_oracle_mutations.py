@@ -106,6 +106,12 @@ PARTITION_MUTATIONS = {
     "frontier_from_the_wrong_level": ("front = np.unique(entity[hop == h - 1])", "front = np.unique(entity[hop == h])"),
     "lru_evicts_most_recent": ("cache.popitem(last=False)", "cache.popitem(last=True)"),
     "lru_hit_does_not_refresh": ("            cache.move_to_end(a)\n", ""),
+    "pulled_hop_routed_by_subject": ("        if h in pull_hops:", "        if False:"),
+    "object_ranges_numbered_from_zero": ("order = list(range(num_shards, num_shards + num_ranges))",
+                                         "order = list(range(0, num_ranges))"),
+    "fetch_takes_the_indices_first": ("seq += [num_shards + c, num_shards + num_ranges + c]",
+                                      "seq += [num_shards + num_ranges + c, num_shards + c]"),
+    "fetch_through_a_small_cache": ("    if capacity < num_shards + 2 * num_ranges:", "    if capacity < 4:"),
 }
 
 
@@ -123,6 +129,8 @@ def test_planted_mistake_in_partition_helpers_is_caught(name):
         assert seq == [0, 2, 3, 1, 0, 1]
         assert mod.lru_counts(seq, 2) == (5, 3, 1)
         assert mod.lru_counts([0, 1, 0, 2, 0, 3], 2) == (4, 2, 2)
+        assert pins.shard_access_trace(mod, pull_hops={2}) == [0, 2, 6, 5, 4, 0, 1]
+        assert mod.fetch_accesses(4, 3, 10) == [4, 7, 5, 8, 6, 9] and mod.fetch_accesses(4, 3, 9) == []
     except (AssertionError, IndexError):
         caught = True
     assert caught, f"no pin noticed the planted mistake '{name}'"

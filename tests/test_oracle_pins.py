@@ -370,7 +370,7 @@ def test_partition_properties_and_lru_accounting():
         assert l2 - e2 <= cap and l2 >= loads and l2 + h2 == len(seq)
 
 
-def shard_access_trace(part):
+def shard_access_trace(part, pull_hops=()):
     """Hand-worked trace of Alg. 1's routing step over 4 sub-graphs and 3 hops.
 
     Entities 0..9; subjects (with a triple) are 0,1,2,3,4,5,7; entities 6, 8, 9 are no subject.
@@ -386,6 +386,8 @@ def shard_access_trace(part):
     subj = np.array([0, 1, 2, 3, 4, 5, 7, 0, 5], dtype=np.int32)
     entity = np.array([0, 5, 1, 2, 7, 3, 4, 8, 9, 0, 2], dtype=np.int32)   # two queries' lists, concatenated
     hop = np.array([0, 0, 1, 1, 1, 2, 2, 2, 3, 0, 1], dtype=np.uint8)
+    if pull_hops:   # three sub-graphs by object range, numbered 4, 5, 6 behind the four shards
+        return part.shard_accesses(P, subj, 10, 3, entity, hop, pull_hops=pull_hops, num_shards=4, num_ranges=3)
     return part.shard_accesses(P, subj, 10, 3, entity, hop)
 
 
@@ -413,8 +415,8 @@ def test_shard_visit_order_hand_trace():
     # two slots: 0 L, 2 L, 6 L (evicts 0), 5 L (evicts 2), 4 L (evicts 6), 4 hit, 5 hit, 6 L (evicts 4)
     assert part.lru_counts(seq, 2) == (6, 4, 2)
     # a fetch of predecessor edges: range 0 and its triple indices, range 1 and its triple indices, ..
-    assert part.fetch_accesses(4, 3, 4) == [4, 7, 5, 8, 6, 9]
-    assert part.fetch_accesses(4, 3, 3) == []      # below four slots the cache is bypassed
+    assert part.fetch_accesses(4, 3, 10) == [4, 7, 5, 8, 6, 9]
+    assert part.fetch_accesses(4, 3, 9) == []      # a cache that cannot hold all 4 + 3 + 3 units is bypassed
     # fewer hops: a prefix of the same trace; an empty frontier ends it
     P = np.array([0, 1], dtype=np.int32)
     assert part.shard_accesses(P, np.array([0], dtype=np.int32), 2, 3, np.array([0, 1], dtype=np.int32),
