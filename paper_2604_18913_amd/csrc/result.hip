@@ -732,9 +732,16 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
         uint32_t d[16];
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            unsigned long long x = 0;
+            // byte b of x = byte g of plane b, picked with byte permutes (two planes per permute, then
+            // the two pairs): six instructions instead of a shift, a mask and an or per plane and half
+            uint32_t src[8];
 #pragma unroll
-            for (int b = 0; b < 8; ++b) x |= ((P[b] >> (8 * g)) & 0xFFull) << (8 * b);
+            for (int b = 0; b < 8; ++b) src[b] = g < 4 ? (uint32_t)P[b] : (uint32_t)(P[b] >> 32);
+            const uint32_t pick = 0x0c0c0000u | (uint32_t)((4 + (g & 3)) << 8) | (uint32_t)(g & 3);  // [b.byte, a.byte, 0, 0]
+            const uint32_t t01 = __builtin_amdgcn_perm(src[1], src[0], pick), t23 = __builtin_amdgcn_perm(src[3], src[2], pick);
+            const uint32_t t45 = __builtin_amdgcn_perm(src[5], src[4], pick), t67 = __builtin_amdgcn_perm(src[7], src[6], pick);
+            const uint32_t xlo = __builtin_amdgcn_perm(t23, t01, 0x05040100u), xhi = __builtin_amdgcn_perm(t67, t45, 0x05040100u);
+            unsigned long long x = ((unsigned long long)xhi << 32) | xlo;
             unsigned long long t;
             t = (x ^ (x >> 7)) & 0x00AA00AA00AA00AAull;
             x = x ^ t ^ (t << 7);

@@ -30,8 +30,6 @@ def one_case(seed):
     walk = bool(rng.integers(0, 3) == 0)
     shards = int([0, 0, 0, 2, 5][rng.integers(0, 5)])     # Alg. 1: subject-partitioned graph behind a shard cache
     resident = int(rng.integers(1, shards + 1)) if shards else 0
-    if shards and direction == "pull":
-        direction = "push"
     if seed % 3 == 0:   # power-law degrees: long and hub object rows, dense frontiers
         scale = float(rng.uniform(0.0005, 0.004))
         k = min(k, 4)
@@ -58,7 +56,7 @@ def one_case(seed):
             a = loff[h * Q:(h + 1) * Q + 1]
             assert np.array_equal(off, a - a[0]), (what, h)
             assert np.array_equal(ent.cpu().numpy(), lent[a[q0]:a[q1]]), (what, h)
-        if k > 0 and not shards:   # walks to sampled members of the last non-empty level
+        if k > 0:   # walks to sampled members of the last non-empty level
             h = max(hh for hh in range(k + 1) if any(len(x) for x in levels[hh]))
             qs = [q for q in range(Q) if len(levels[h][q])][:40]
             pt = [int(levels[h][q][rng.integers(0, len(levels[h][q]))]) for q in qs]
@@ -78,12 +76,12 @@ def one_case(seed):
         assert np.array_equal(ent.cpu().numpy(), want[1][a:b]) and np.array_equal(pred.cpu().numpy(), want[3][a:b]), what
         levels = [[want[1][want[0][q]:want[0][q + 1]][want[2][want[0][q]:want[0][q + 1]] == h] for q in range(Q)]
                   for h in range(k + 1)]
-        if want[0][-1] > 0 and not shards:
+        if want[0][-1] > 0:
             pq, pt = kggen.sample_reached_pairs(seed, want[0], want[1], 60)
             cnt, edges = g.paths(res, pq, pt, 8)
             c_o, e_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, pq, pt, 8, w.rel_mask)
             assert np.array_equal(cnt.cpu().numpy(), c_o) and np.array_equal(edges.cpu().numpy(), e_o), what
-    if k > 0 and not shards:
+    if k > 0:
         h = int(rng.integers(1, k + 1))
         off, t, s_, r_, o_ = res.active_triples(h, q0, q1)
         want_t = [oracle.active_triples(w.num_entities, w.subj, w.rel, levels[h - 1][q],
@@ -92,6 +90,30 @@ def one_case(seed):
         cat = np.concatenate(want_t) if want_t else np.zeros(0, dtype=np.int32)
         assert np.array_equal(t.cpu().numpy(), cat), (what, h)
         assert np.array_equal(o_.cpu().numpy(), w.obj[cat]) and np.array_equal(r_.cpu().numpy(), w.rel[cat])
+    # bulk export: every chain of one (query, length), numbered, against the oracle's listing per target
+    q = int(rng.integers(0, Q))
+    d = int(rng.integers(0, k + 1))
+    targets = levels[d][q]
+    total = res.walks_count(q, d)
+    if len(targets) == 0:
+        assert total == 0, what
+    else:
+        qs = np.full(len(targets), q, np.int32)
+        cap = 2000
+        if walk:
+            c_o, e_o = oracle.walk_paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, qs, targets,
+                                         np.full(len(targets), d, np.int32), cap, w.rel_mask)
+        else:
+            c_o, e_o = oracle.paths(w.num_entities, w.subj, w.rel, w.obj, w.seed_off, w.seeds, k, qs, targets, cap,
+                                    w.rel_mask)
+        if c_o.max() < cap:   # the oracle listed every chain of every target
+            assert total == int(c_o.sum()), (what, q, d)
+            e, t = res.walks_fetch(q, d, 0, total)
+            assert np.array_equal(t.cpu().numpy(), np.repeat(targets, c_o)), (what, q, d)
+            want_e = np.concatenate([e_o[i, :c_o[i], :d] for i in range(len(targets))]).reshape(total, d)
+            assert np.array_equal(e.cpu().numpy(), want_e), (what, q, d)
+        else:
+            assert total >= int(c_o.sum()), (what, q, d)
     res.close()
     g.close()
 
