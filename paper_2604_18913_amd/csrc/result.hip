@@ -621,16 +621,22 @@ __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
     return x;
 }
 
-template <int NB, bool MASK, bool STATS>
+// G = lanes per entity: 16 (lane = word of the line), or 4 for a fetch whose queries sit in four
+// aligned words or fewer (lane = word wb + lane % 4), which then walks four times as many entities
+// per wavefront.
+template <int NB, bool MASK, bool STATS, int G>
 __global__ void __launch_bounds__(256)
 k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long long *__restrict__ visbuf,
-            long long tile0, long long ntile, int w0, int nw) {
-    constexpr int W = 16, G = 16;
+            long long tile0, long long ntile, int w0, int nw, int wb) {
+    constexpr int W = 16;
+    constexpr int EPB = 256 / G;         // entities per block (a divisor of 64: one tile per block)
+    constexpr unsigned GMASK = (1u << G) - 1u;
     constexpr int HMAX = (1 << NB) - 2;  // largest hop number the NB bits of (hop + 1) can hold
-    const long long grp = xcd_contiguous(blockIdx.x, gridDim.x) * 16 + (threadIdx.x >> 4);  // entity slot of the chunk
+    const long long grp = xcd_contiguous(blockIdx.x, gridDim.x) * EPB + (threadIdx.x / G);  // entity slot of the chunk
     const long long tile_rel = grp >> 6;
-    if (tile_rel >= ntile) return;  // block-uniform: a block holds 16 entities of one tile
-    const int vi = (int)(grp & 63), lw = threadIdx.x & 15, v = lane(), g0 = v & ~(G - 1);
+    if (tile_rel >= ntile) return;  // block-uniform: the entities of a block belong to one tile
+    const int vi = (int)(grp & 63), lw = wb + (threadIdx.x & (G - 1)), v = lane(), g0 = v & ~(G - 1);
+    const int gl = threadIdx.x & (G - 1);  // the lane's place in its group
     const long long ev = tile_entity(a.tile_ent, tile0 + tile_rel, vi, a.E);
     const unsigned long long range_w = range_bits(a.q0, a.q1, lw);
     unsigned long long visw = 0, lv0 = 0;
@@ -669,17 +675,17 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
             if (!shortrow || !group_any<G>(rem != 0)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
-            if (STATS && lw == 0) ++n_rows;
+            if (STATS && gl == 0) ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += G) {
-                const uint32_t j = j0 + lw;
+                const uint32_t j = j0 + gl;
                 int s = 0;
                 bool cand = false;
                 if (j < hi) {
                     s = a.in_sub[j];
                     cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
                 }
-                unsigned gm = (unsigned)((__ballot(cand) >> g0) & 0xFFFFu);
-                if (STATS && lw == 0) {
+                unsigned gm = (unsigned)((__ballot(cand) >> g0) & GMASK);
+                if (STATS && gl == 0) {
                     n_edges += min((uint32_t)G, hi - j0);
                     n_lines += __popc(gm);
                 }
@@ -1360,8 +1366,16 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
             dim3 ge((unsigned)((nsup * wsplit + 7) / 8 * 8));
             {
                 ProfScope ps(prof, KK_PRED_WALK, st_tiles);
-                if (a.k <= 2) k_pred_walk<2, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
-                else k_pred_walk<3, MASK, STATS><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw);
+                // a range inside four aligned words takes four lanes per entity (16 entities per wavefront)
+                const int wb = w0 & ~3;
+                if (w0 + nw <= wb + 4) {
+                    dim3 g4((unsigned)((n + 7) / 8 * 8));  // 64 entities per block
+                    if (a.k <= 2) k_pred_walk<2, MASK, STATS, 4><<<g4, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wb);
+                    else k_pred_walk<3, MASK, STATS, 4><<<g4, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wb);
+                } else {
+                    if (a.k <= 2) k_pred_walk<2, MASK, STATS, 16><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, 0);
+                    else k_pred_walk<3, MASK, STATS, 16><<<gw, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, 0);
+                }
             }
             if (rows_first && c0 == 0) (void)hipStreamWaitEvent(st_tiles, (hipEvent_t)a.ev_rows, 0);
             ProfScope ps(prof, KK_PRED, st_tiles);
