@@ -175,6 +175,21 @@ void Profiler::release() {
     spare.clear();
 }
 
+// The helper streams (two for the fetch's side work, one for shard copies) are made once per
+// device and shared by every graph on it; they live until the process ends.  Work of different
+// graphs on one helper stream is only serialised: every dependency goes through events.
+hipStream_t helper_stream(int device, int which) {
+    static std::mutex mu;
+    static std::map<int, std::array<hipStream_t, 3>> table;
+    std::lock_guard<std::mutex> lock(mu);
+    auto &row = table[device];  // value-initialised to null handles
+    if (!row[which] && hipStreamCreateWithFlags(&row[which], hipStreamNonBlocking) != hipSuccess) {
+        (void)hipGetLastError();
+        row[which] = nullptr;
+    }
+    return row[which];
+}
+
 template <typename T>
 static logoskg_status upload(T **dst, const std::vector<T> &src, size_t *acct) {
     size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
@@ -390,7 +405,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
         return fail(LOGOSKG_ENOMEM);
     }
     for (int i = 0; i < 2; ++i) {
-        if (hipStreamCreateWithFlags(&g->side[i], hipStreamNonBlocking) != hipSuccess ||
+        if (!(g->side[i] = helper_stream(g->device, i)) ||
             hipEventCreateWithFlags(&g->ev_join[i], hipEventDisableTiming) != hipSuccess) {
             set_error("could not create side streams");
             return fail(LOGOSKG_EDEVICE);
@@ -407,10 +422,13 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
 extern "C" void logoskg_graph_free(logoskg_graph *g) {
     if (!g) return;
     (void)hipSetDevice(g->device);
+    // nothing of this graph may still be queued when its events, streams and buffers go away
+    // (a caller's stream can hold a wait on one of the events below)
+    (void)hipDeviceSynchronize();
     free_shards(g);
     g->prof.release();
     for (int i = 0; i < 2; ++i) {
-        if (g->side[i]) { (void)hipStreamSynchronize(g->side[i]); (void)hipStreamDestroy(g->side[i]); }
+        if (g->side[i]) (void)hipStreamSynchronize(g->side[i]);
         if (g->ev_join[i]) (void)hipEventDestroy(g->ev_join[i]);
     }
     if (g->ev_fork) (void)hipEventDestroy(g->ev_fork);

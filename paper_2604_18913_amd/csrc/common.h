@@ -7,8 +7,10 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <array>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <memory>
 #include <string>
 #include <unordered_map>
@@ -424,6 +426,8 @@ void launch_pull_range(logoskg_graph *g, logoskg_result *r, int h, const RowClas
 logoskg_status run_sharded_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, bool want_stats,
                                const unsigned long long *hc, hipStream_t st, logoskg_hop_stats *hs);
 void free_shards(logoskg_graph *g);
+// build.hip: per-device helper streams shared by all graphs (which = 0, 1: fetch side work; 2: shard copies)
+hipStream_t helper_stream(int device, int which);
 logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t *rel,
                             const int32_t *obj, const logoskg_build_opts *opts, const std::vector<uint32_t> &ooff,
                             TripleSorter *sorter);

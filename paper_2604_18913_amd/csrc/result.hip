@@ -1511,7 +1511,8 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     // independent of the rest and overlaps it on a side stream of the graph.
     a.fuse_lists = pred && pred_uses_staged_kernel(a, W);
     const long long n_hub = g->in_rows.n_hub, n_mid = g->in_rows.n_long - g->in_rows.n_hub;
-    if (pred && g->num_shards <= 1 && !serial) {
+    // (nothing to fork for when the fused tile pass has no hub rows beside it)
+    if (pred && g->num_shards <= 1 && !serial && (n_hub > 0 || !a.fuse_lists)) {
         LKG_HIP(hipEventRecord(g->ev_fork, st));
         for (int i = 0; i < 2; ++i) LKG_HIP(hipStreamWaitEvent(g->side[i], g->ev_fork, 0));
         if (a.fuse_lists) {

@@ -216,7 +216,6 @@ void free_shards(logoskg_graph *g) {
     for (auto p : ss->slot_rel) if (p) (void)hipFree(p);
     for (auto e : ss->slot_ready) if (e) (void)hipEventDestroy(e);
     for (auto e : ss->slot_idle) if (e) (void)hipEventDestroy(e);
-    if (ss->copy_stream) (void)hipStreamDestroy(ss->copy_stream);
     for (int i = 0; i < 2; ++i) {
         if (ss->stage_sub[i]) (void)hipFree(ss->stage_sub[i]);
         if (ss->stage_eid[i]) (void)hipFree(ss->stage_eid[i]);
@@ -670,7 +669,10 @@ logoskg_status build_shards(logoskg_graph *g, const int32_t *subj, const int32_t
         LKG_HIP(hipEventCreateWithFlags(&ss->slot_ready[i], hipEventDisableTiming));
         LKG_HIP(hipEventCreateWithFlags(&ss->slot_idle[i], hipEventDisableTiming));
     }
-    LKG_HIP(hipStreamCreateWithFlags(&ss->copy_stream, hipStreamNonBlocking));
+    if (!(ss->copy_stream = helper_stream(g->device, 2))) {
+        set_error("could not create the copy stream");
+        return LOGOSKG_EDEVICE;
+    }
     if (opts->shard_dir && opts->shard_dir[0]) LKG_TRY(shards_to_disk(g, ss, opts->shard_dir));
     LKG_HIP(hipMalloc((void **)&ss->d_route, 1024 * sizeof(unsigned long long)));
     if (hipHostMalloc((void **)&ss->h_route, 1024 * sizeof(unsigned long long), hipHostMallocDefault) != hipSuccess) {
