@@ -112,7 +112,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-queries", type=int, default=0, help="0 = 512 for configs 1-3, 6 for configs 4 and 5")
     ap.add_argument("--serial-fetch", action="store_true",
-                    help="issue the kernels of every fetch back to back (for rocprofv3 kernel statistics)")
+                    help="no effect any more (the kernels of a fetch always run in turn unless --overlap-fetch "
+                         "is given); kept so that older command lines still run")
+    ap.add_argument("--overlap-fetch", action="store_true",
+                    help="put the independent kernels of a fetch on helper streams (LOGOSKG_OVERLAP_FETCH=1) in the "
+                         "timed region; the per-kernel figures still come from a region without it")
     ap.add_argument("--config", type=int, choices=[1, 2, 3, 4, 5], default=2,
                     help="workload: 2 (default) is the one the metric is quoted on; the others are the "
                          "parity-test shapes, timed the same way "
@@ -249,8 +253,8 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
-    if args.serial_fetch:
-        os.environ["LOGOSKG_SERIAL_FETCH"] = "1"
+    if args.overlap_fetch:
+        os.environ["LOGOSKG_OVERLAP_FETCH"] = "1"
 
     # work units of every kernel (counting mode; not timed)
     g.profile_enable(2)
@@ -265,23 +269,21 @@ def main():
     note("work units counted; warm-up")
     run_steps(args.warmup)
     note("timed region")
-    # timed region: exactly args.steps steps of the default path (list / predecessor kernels of a
-    # fetch overlap on side streams), nothing else on the streams: `value` comes from here
+    # timed region: exactly args.steps steps of the default path, nothing else on the streams:
+    # `value` comes from here
     dt = run_steps(args.steps)
     # the same steps with every launch bracketed by HIP events on its own stream (two event records
-    # per launch cost a few per cent of a step, which is why they stay out of `value`)
+    # per launch cost a few per cent of a step, which is why they stay out of `value`); the kernels
+    # of a fetch run in turn, so each event pair times one kernel alone: these durations feed the
+    # per-kernel table and the roofline figures
+    os.environ["LOGOSKG_OVERLAP_FETCH"] = "0"
     g.profile_enable(1)
     g.profile_read()
     dt_events = run_steps(args.steps)
-    prof_overlapped = g.profile_read()
-    # the same steps with the kernels of a fetch issued back to back, so that each event pair
-    # times one kernel alone: these durations feed the roofline figures
-    os.environ["LOGOSKG_SERIAL_FETCH"] = "1"
-    dt_serial = run_steps(args.steps)
     prof = g.profile_read()
     g.profile_enable(0)
-    if not args.serial_fetch:
-        os.environ["LOGOSKG_SERIAL_FETCH"] = "0"
+    if args.overlap_fetch:
+        os.environ["LOGOSKG_OVERLAP_FETCH"] = "1"
 
     # where a step's time goes: a few more steps with an event after the khop call and after the
     # list call (not part of the timed region)
@@ -320,7 +322,6 @@ def main():
         kernels[name] = dict(launches_per_step=p["launches"] / args.steps,
                              ms_per_step=p["total_ms"] / args.steps,
                              avg_ms=p["total_ms"] / p["launches"],
-                             ms_per_step_overlapped=prof_overlapped.get(name, {}).get("total_ms", 0.0) / args.steps,
                              **per_step)
     expansion_names = ("push_", "pull_", "update_", "frontier_", "seed_", "clear_", "live_", "hop_")
     expansion_ms = sum(v["ms_per_step"] for n, v in kernels.items() if n.startswith(expansion_names))
@@ -412,7 +413,7 @@ def main():
         "gteps_physical": round(physical_edges / (dt / args.steps) / 1e9, 3),
         "logical_edges_per_step": logical_edges, "physical_edges_per_step": physical_edges,
         "ms_per_step_with_events": round(dt_events / args.steps * 1e3, 4),
-        "ms_per_step_serialized": round(dt_serial / args.steps * 1e3, 4),
+        "fetch_kernels": "overlapped on helper streams" if args.overlap_fetch else "in turn on one stream",
         "phase_ms": {"khop": round(phase_ms[0], 4), "lists": round(phase_ms[1], 4),
                      "measured": "events after each of the two calls, 5 extra steps"},
         "expansion": {"ms_per_step": round(expansion_ms, 4),

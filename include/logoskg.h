@@ -272,9 +272,10 @@ logoskg_status logoskg_result_offsets(const logoskg_result *r, int64_t *reached_
  *   pred_edge = the smallest edge id t with o_t = v, r_t allowed for the query
  *   and hop(s_t) = hop(v) - 1 (the active triple of Eq. 5-7 that reaches v
  *   first in edge-id order); -1 for seeds.
- * Asynchronous on `stream`; the list kernel and the predecessor kernels run on
- * helper streams (made once per device, shared by all graphs on it, kept until
- * the process ends) and join `stream` before the call returns.  The
+ * Asynchronous on `stream`: the kernels of a fetch run in turn on it.  (With
+ * LOGOSKG_OVERLAP_FETCH=1 in the environment the independent ones run on helper
+ * streams - made once per device, shared by all graphs on it, kept until the
+ * process ends - and join `stream` before the call returns; measured, no gain.)  The
  * first call on a graph that asks for pred_edge with more than 256 queries
  * allocates a buffer of 4 KiB per object row of more than 32 entries (not
  * above 8 GiB; freed with the graph).  On a sharded graph pred_edge streams the

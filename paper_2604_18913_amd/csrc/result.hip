@@ -1502,13 +1502,16 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
     a.stats_mid = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_MID : nullptr;
     if (counting) LKG_HIP(hipMemsetAsync(g->d_ctr + C_STATS, 0, 4 * KK_NUM * sizeof(unsigned long long), st));
-    // lists, the per-tile predecessor kernel and the per-row predecessor kernels are independent:
-    // on a resident graph they run on three streams and join on the caller's
-    const char *serial_env = getenv("LOGOSKG_SERIAL_FETCH");  // measurement aid: one kernel at a time
-    const bool serial = serial_env && serial_env[0] == '1';
+    // The kernels of a fetch run in turn on the caller's stream.  The list kernel, the per-tile
+    // predecessor kernel and the per-row predecessor kernels are independent, and with
+    // LOGOSKG_OVERLAP_FETCH=1 a resident graph puts them on the helper streams and joins them on the
+    // caller's; measured on every benchmark configuration that gains nothing (they are bound by
+    // instruction issue and gather latency and share the same units) and costs small batches the
+    // fork and join, so it is not the default.
+    const char *overlap_env = getenv("LOGOSKG_OVERLAP_FETCH");
+    const bool serial = !(overlap_env && overlap_env[0] == '1');
     // With predecessors on 16-word planes the tile kernel writes all three lists; otherwise the
-    // list kernel runs beside the predecessor kernels.  The block-per-row kernel of the hub rows is
-    // independent of the rest and overlaps it on a side stream of the graph.
+    // list kernel runs beside the predecessor kernels.
     a.fuse_lists = pred && pred_uses_staged_kernel(a, W);
     const long long n_hub = g->in_rows.n_hub, n_mid = g->in_rows.n_long - g->in_rows.n_hub;
     // (nothing to fork for when the fused tile pass has no hub rows beside it)

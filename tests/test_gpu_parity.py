@@ -150,21 +150,24 @@ def test_fetch_subranges_and_optional_outputs():
     g.close()
 
 
-def test_sixteen_word_planes_deep_hops_serial_fetch_and_no_hop_output(monkeypatch):
+def test_sixteen_word_planes_deep_hops_overlapped_fetch_and_no_hop_output(monkeypatch):
     # more than 256 queries: k <= 6 takes the staged predecessor kernel that also writes the
     # entity / hop lists, deeper searches take the tile kernel with scattered stores plus the
-    # list kernel; both must agree with the oracle, also when a fetch is issued on one stream
+    # list kernel; both must agree with the oracle, also when a fetch spreads its kernels over the
+    # helper streams
     m = lkg()
     w = kggen.config2(0.004, num_queries=300)
     for k in (6, 7, 9):
         want = run_oracle(w, k=k)
         got, _ = run_gpu(w, "auto", hub_min_degree=100, k=k)
         assert_same(got, want, f"k={k}")
-    monkeypatch.setenv("LOGOSKG_SERIAL_FETCH", "1")
+    monkeypatch.setenv("LOGOSKG_OVERLAP_FETCH", "1")
     want = run_oracle(w)
     got, _ = run_gpu(w, "auto", hub_min_degree=100)
-    assert_same(got, want, "serial fetch")
-    monkeypatch.delenv("LOGOSKG_SERIAL_FETCH")
+    assert_same(got, want, "overlapped fetch")
+    for k in (2, 7):
+        assert_same(run_gpu(w, "auto", hub_min_degree=100, k=k)[0], run_oracle(w, k=k), f"overlapped fetch, k={k}")
+    monkeypatch.delenv("LOGOSKG_OVERLAP_FETCH")
     g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=100)
     res = g.khop(w.seed_off, w.seeds, w.k)
     ent, hop, pred = res.fetch(want_hop=False)
