@@ -91,6 +91,7 @@ constexpr int kPullSegment = 1024;      // longer object rows are cut into segme
 constexpr int kPushSegment = 64;        // same for the subject rows of a push frontier
 constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
                                         // (shorter long rows: one wavefront per row)
+constexpr int kDensePullPercent = 60;   // from this share of the triples leaving the frontier a hop is taken as dense
 constexpr int kGiantSegment = 8192;     // a giant row is walked by one 16-wave block per this many entries
 constexpr int kGiantRowMin = 8192;      // hub rows from this size get a 16-wave block in the predecessor pass, smaller ones 4 waves
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
@@ -370,6 +371,8 @@ struct FillArgs {
     unsigned long long *plane_buf;  // bit-sliced plane words between k_pred_walk and k_pred_emit, or NULL
     size_t plane_buf_bytes;
     int emit_eid_cap, emit_line_cap;  // capacities of k_pred_emit's two LDS tables (entries / lines)
+    uint32_t dense_levels;  // bit h: nearly every triple leaves level h - 1, so the predecessor kernels gather the
+                            // line of every entry of a row at level h without asking for its frontier bit first
     void *ev_rows;                    // host side: event between the block-per-row kernel and the list writer
     long long tile_begin, tile_count;  // tiles this predecessor launch covers
     long long plane;   // words per plane

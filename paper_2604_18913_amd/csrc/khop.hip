@@ -328,7 +328,6 @@ k_update_visited(long long Epad, const uint32_t *__restrict__ act_cur, const uns
 // sector through the L1 per edge, and these kernels are bound by what the L2s deliver; skipping the
 // test costs the lines of the edges outside the frontier (zero lines: a level line is non-zero only
 // where its active bit is set), which is less traffic as soon as half the edges are inside.
-constexpr int kDensePullPercent = 60;
 // Removes up to 64/W candidates from the (wave-uniform) mask and returns the
 // lane position of the one that belongs to the caller's group, or -1.
 template <int W>

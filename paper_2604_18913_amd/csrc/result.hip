@@ -439,6 +439,7 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
             if (!wave_any(rem != 0)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+            const bool dense = !STATS && ((a.dense_levels >> h) & 1u);  // the line of an entity outside the level is zero
             ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += 64) {
                 const uint32_t j = j0 + v;
@@ -446,7 +447,7 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
                 bool cand = false;
                 if (j < hi) {
                     s = a.in_sub[j];
-                    cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+                    cand = dense || ((act_prev[s >> 5] >> (s & 31)) & 1u);
                 }
                 n_lines += pred_resolve_unordered<W, MASK>(j0, s, cand, a, prev, rem, [&](unsigned long long hit, int eid) {
                     for (unsigned long long m = hit; m; m &= m - 1)
@@ -675,6 +676,7 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
             if (!shortrow || !group_any<G>(rem != 0)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+            const bool dense = !STATS && ((a.dense_levels >> h) & 1u);  // the line of an entity outside the level is zero
             if (STATS && gl == 0) ++n_rows;
             for (uint32_t j0 = lo; j0 < hi; j0 += G) {
                 const uint32_t j = j0 + gl;
@@ -682,7 +684,7 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
                 bool cand = false;
                 if (j < hi) {
                     s = a.in_sub[j];
-                    cand = (act_prev[s >> 5] >> (s & 31)) & 1u;
+                    cand = dense || ((act_prev[s >> 5] >> (s & 31)) & 1u);
                 }
                 unsigned gm = (unsigned)((__ballot(cand) >> g0) & GMASK);
                 if (STATS && gl == 0) {
@@ -1075,6 +1077,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         if (!wave_any(slevel[lw] != 0)) continue;  // block-uniform
         const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
         const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
+        const bool dense = !STATS && ((a.dense_levels >> h) & 1u);  // the line of an entity outside the level is zero
         if (wave == 0) ++n_rows;
         // The first step is short (one chunk per wavefront): on a dense frontier the first
         // candidates of a row resolve most queries, and what is resolved after that step is not
@@ -1097,7 +1100,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
                 cj[c] = false;
                 if (j < step_hi) {
                     sj[c] = a.in_sub[j];
-                    cj[c] = (act_prev[sj[c] >> 5] >> (sj[c] & 31)) & 1u;
+                    cj[c] = dense || ((act_prev[sj[c] >> 5] >> (sj[c] & 31)) & 1u);
                 }
             }
 #pragma unroll
@@ -1475,6 +1478,10 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     a.rows = g->in_rows.longrows;
     a.row_base = 0; a.long_index = nullptr; a.row_pred = nullptr; a.fuse_lists = 0;
     a.plane_buf = nullptr; a.plane_buf_bytes = 0; a.ev_rows = nullptr;
+    // levels whose frontier (the level below) holds most of the triples: the same rule as the pull hops
+    for (int h = 1; h <= r->k && h < 32; ++h)
+        if ((long long)r->stats[(size_t)h - 1].frontier_edges * 100 >= g->T * (long long)kDensePullPercent)
+            a.dense_levels |= 1u << h;
     a.n_giant_rows = g->num_shards > 1 ? -1 : g->in_rows.n_giant;
     a.giant_seg_first = g->num_shards > 1 ? nullptr : g->in_rows.giant_seg_first;
     a.n_giant_segs = g->num_shards > 1 ? 0 : g->in_rows.n_giant_segs;
