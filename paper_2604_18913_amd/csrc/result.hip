@@ -622,9 +622,9 @@ __device__ __forceinline__ unsigned long long wave_or64(unsigned long long x) {
     return x;
 }
 
-// G = lanes per entity: 16 (lane = word of the line), or 4 for a fetch whose queries sit in four
+// G = lanes per entity: 16 (lane = word of the line), 4 for a fetch whose queries sit in four
 // aligned words or fewer (lane = word wb + lane % 4), which then walks four times as many entities
-// per wavefront.
+// per wavefront, or 1 for a fetch inside one word (lane = entity, word wb).
 template <int NB, bool MASK, bool STATS, int G>
 __global__ void __launch_bounds__(256)
 k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long long *__restrict__ visbuf,
@@ -635,7 +635,7 @@ k_pred_walk(FillArgs a, unsigned long long *__restrict__ codes, unsigned long lo
     constexpr int HMAX = (1 << NB) - 2;  // largest hop number the NB bits of (hop + 1) can hold
     const long long grp = xcd_contiguous(blockIdx.x, gridDim.x) * EPB + (threadIdx.x / G);  // entity slot of the chunk
     const long long tile_rel = grp >> 6;
-    if (tile_rel >= ntile) return;  // block-uniform: the entities of a block belong to one tile
+    if (tile_rel >= ntile) return;  // wavefront-uniform: a wavefront's entities belong to one tile
     const int vi = (int)(grp & 63), lw = wb + (threadIdx.x & (G - 1)), v = lane(), g0 = v & ~(G - 1);
     const int gl = threadIdx.x & (G - 1);  // the lane's place in its group
     const long long ev = tile_entity(a.tile_ent, tile0 + tile_rel, vi, a.E);
@@ -1371,7 +1371,11 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
                 ProfScope ps(prof, KK_PRED_WALK, st_tiles);
                 // a range inside four aligned words takes four lanes per entity (16 entities per wavefront)
                 const int wb = w0 & ~3;
-                if (w0 + nw <= wb + 4) {
+                if (nw == 1) {  // one word: a lane per entity (64 entities per wavefront)
+                    dim3 g1((unsigned)(((n + 3) / 4 + 7) / 8 * 8));  // 256 entities per block
+                    if (a.k <= 2) k_pred_walk<2, MASK, STATS, 1><<<g1, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, w0);
+                    else k_pred_walk<3, MASK, STATS, 1><<<g1, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, w0);
+                } else if (w0 + nw <= wb + 4) {
                     dim3 g4((unsigned)((n + 7) / 8 * 8));  // 64 entities per block
                     if (a.k <= 2) k_pred_walk<2, MASK, STATS, 4><<<g4, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wb);
                     else k_pred_walk<3, MASK, STATS, 4><<<g4, dim3(256), 0, st_tiles>>>(a, a.plane_buf, visbuf, t0, n, w0, nw, wb);
