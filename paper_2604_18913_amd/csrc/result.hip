@@ -375,6 +375,31 @@ __device__ __forceinline__ int pred_resolve_unordered(uint32_t j0, int s, bool c
     return gathered;
 }
 
+// The same 64 in-edges when the fetched queries sit in one word `wq` of the 16-word lines: lane =
+// entry, every lane gathers that one word of its own candidate, and a 64 x 64 bit transpose turns
+// "entry -> queries it resolves" into "query -> entries that resolve it" (lane = query), whose lowest
+// set bit is the entry with the smallest edge id (edge ids ascend inside a row).  One round of 64
+// eight-byte gathers where the line-wide form needs sixteen rounds of four lines.  `rem` is
+// wavefront-uniform; emit(q, eid) runs on lane q for the queries resolved here.
+template <bool MASK, typename Emit>
+__device__ __forceinline__ int pred_resolve_word(uint32_t j0, int s, bool cand, int wq, const FillArgs &a,
+                                                 const unsigned long long *__restrict__ prev,
+                                                 unsigned long long &rem, Emit emit) {
+    unsigned long long l = 0;
+    if (cand) {
+        l = prev[(size_t)s * 16 + wq];
+        if (MASK) l &= a.allow[(size_t)a.in_rel[j0 + lane()] * 16 + wq];
+        l &= rem;
+    }
+    const int gathered = __popcll(__ballot(cand));
+    if (wave_any(l != 0)) {
+        const unsigned long long from = transpose64(l);  // lane q: the entries whose line holds query q
+        if (from) emit(lane(), a.in_eid[j0 + (uint32_t)(__ffsll((long long)from) - 1)]);
+        rem &= ~__ballot(from != 0);
+    }
+    return gathered;
+}
+
 // List positions of entity `ev` for every query: slot[q] = start of the tile's run in query q's
 // list + rank of the entity inside the tile.  Called by a whole wavefront for the words
 // w = w_first, w_first + w_step, ..
@@ -416,12 +441,15 @@ __device__ __forceinline__ unsigned long long and_groups(unsigned long long x) {
 // query is kept in a table of the wavefront in LDS; the groups' masks are merged once per 64
 // entries, and after a level the table is written out (one contiguous store per 64 queries in the
 // row-buffer mode) and reset.
-template <int W, bool MASK, bool STATS, bool BUF>
+// ONE (16-word lines, the fetched queries inside one word): every lane works on that word and
+// takes an entry of its own (pred_resolve_word).
+template <int W, bool MASK, bool STATS, bool BUF, bool ONE = false>
 __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_row, long long n_rows_total) {
+    static_assert(!ONE || (W == 16 && !STATS), "the one-word form is for 16-word lines");
     constexpr int Qp = 64 * W;
     __shared__ long long slots[BUF ? 1 : 4][BUF ? 1 : Qp];
     __shared__ int smin_all[4][Qp];
-    const int wave = threadIdx.x >> 6, v = lane(), lw = v & (W - 1);
+    const int wave = threadIdx.x >> 6, v = lane(), lw = ONE ? (a.q0 >> 6) : (v & (W - 1));
     const long long idx = (long long)blockIdx.x * 4 + wave;
     long long n_rows = 0, n_edges = 0, n_lines = 0;
     if (idx < n_rows_total) {  // wave-uniform
@@ -449,17 +477,22 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
                     s = a.in_sub[j];
                     cand = dense || ((act_prev[s >> 5] >> (s & 31)) & 1u);
                 }
-                n_lines += pred_resolve_unordered<W, MASK>(j0, s, cand, a, prev, rem, [&](unsigned long long hit, int eid) {
-                    for (unsigned long long m = hit; m; m &= m - 1)
-                        atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
-                });
+                if constexpr (ONE) {
+                    n_lines += pred_resolve_word<MASK>(j0, s, cand, lw, a, prev, rem,
+                                                       [&](int q, int eid) { smin[lw * 64 + q] = eid; });
+                } else {
+                    n_lines += pred_resolve_unordered<W, MASK>(j0, s, cand, a, prev, rem, [&](unsigned long long hit, int eid) {
+                        for (unsigned long long m = hit; m; m &= m - 1)
+                            atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
+                    });
+                    rem = and_groups<W>(rem);  // what any group has resolved is resolved
+                }
                 n_edges += min((uint32_t)64, hi - j0);
-                rem = and_groups<W>(rem);  // what any group has resolved is resolved
                 if (!wave_any(rem != 0)) break;
             }
             __builtin_amdgcn_wave_barrier();
-            for (int i = 0; i < W; ++i) {  // queries 64 i .. 64 i + 63: word i of the level, held by lane i
-                const unsigned long long word = shfl64(level, i);
+            for (int i = ONE ? lw : 0; i < (ONE ? lw + 1 : W); ++i) {  // queries 64 i .. 64 i + 63: word i of the level, held by lane i
+                const unsigned long long word = ONE ? level : shfl64(level, i);
                 const int q = 64 * i + v;
                 if ((word >> v) & 1ull) {
                     out[BUF ? (long long)q : slot[q]] = smin[q];
@@ -1030,9 +1063,11 @@ k_pred_emit(FillArgs a, const unsigned long long *__restrict__ codes, const unsi
 // (atomicMin; the line starts at INT_MAX).  A block that walks a whole 140,000-entry row is a chain
 // of dependent gathers that outlasts everything else in the launch; the segments of a row run side
 // by side, at the price of the early exit between them (it saved a quarter of the entries).
-template <int W, bool MASK, bool STATS, bool BUF, bool SEG = false>
+// ONE: as in k_pred_wave.
+template <int W, bool MASK, bool STATS, bool BUF, bool SEG = false, bool ONE = false>
 __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_row) {
     static_assert(!SEG || BUF, "segments merge in the row buffer");
+    static_assert(!ONE || (W == 16 && !STATS), "the one-word form is for 16-word lines");
     constexpr int Qp = 64 * W;
     constexpr int C = 4;  // 64-entry chunks per wavefront and step, loaded together
     __shared__ long long slot[BUF ? 1 : Qp];
@@ -1085,7 +1120,8 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         uint32_t span = 64u * nw;
         for (uint32_t s0 = lo; s0 < hi; s0 += span, span = 64u * C * nw) {
             const uint32_t step_hi = min(hi, s0 + span);
-            unsigned long long rem = srem[lw];
+            const int lr = ONE ? (a.q0 >> 6) : lw;  // the word of the shared mask this lane works on
+            unsigned long long rem = srem[lr];
             if (!wave_any(rem != 0)) break;  // same decision in every wave
             const unsigned long long before = rem;
             // chunk c of this wavefront is chunk c * nw + wave of the step: a row shorter than a
@@ -1107,17 +1143,22 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
             for (int c = 0; c < C; ++c) {
                 uint32_t j0 = w0 + 64u * nw * c;
                 if (j0 < step_hi && wave_any(rem != 0)) {
-                    n_lines += pred_resolve_unordered<W, MASK>(j0, sj[c], cj[c], a, prev, rem,
-                                                               [&](unsigned long long hit, int eid) {
-                        for (unsigned long long m = hit; m; m &= m - 1)
-                            atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
-                    });
+                    if constexpr (ONE) {
+                        n_lines += pred_resolve_word<MASK>(j0, sj[c], cj[c], lr, a, prev, rem,
+                                                           [&](int q, int eid) { atomicMin(&smin[lr * 64 + q], eid); });
+                    } else {
+                        n_lines += pred_resolve_unordered<W, MASK>(j0, sj[c], cj[c], a, prev, rem,
+                                                                   [&](unsigned long long hit, int eid) {
+                            for (unsigned long long m = hit; m; m &= m - 1)
+                                atomicMin(&smin[lw * 64 + (__ffsll((long long)m) - 1)], eid);
+                        });
+                    }
                     n_edges += min((uint32_t)64, step_hi - j0);
                 }
             }
-            unsigned long long resolved = before & ~rem;  // by this group of lanes
+            unsigned long long resolved = before & ~rem;  // by this group of lanes (ONE: by this wavefront)
             __syncthreads();
-            if (resolved) atomicAnd(&srem[lw], ~resolved);
+            if (resolved && (!ONE || v == 0)) atomicAnd(&srem[lr], ~resolved);
             __syncthreads();
         }
         __syncthreads();
@@ -1312,12 +1353,23 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         a.row_pred = nullptr;
         a.fuse_lists = 0;
     }
+    // a fetch whose queries sit in one word of 16-word lines: the row kernels take an entry per lane
+    const bool one = W == 16 && !STATS && a.q1 > a.q0 && (a.q0 >> 6) == ((a.q1 - 1) >> 6);
     // issued first: the tile kernel waits for it, and launched after the hub kernel it ran half as fast
     if (n_other_rows > 0) {  // with row_pred: must precede the tile kernel on its stream
         hipStream_t st = a.row_pred ? st_tiles : st_hub;
         ProfScope ps(prof, KK_PRED_MID, st);
         const dim3 gw((unsigned)((n_other_rows + 3) / 4));
-        if (a.row_pred) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+        bool done = false;
+        if constexpr (W == 16 && !STATS) {
+            if (one) {
+                if (a.row_pred) k_pred_wave<W, MASK, STATS, true, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+                else k_pred_wave<W, MASK, STATS, false, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
+                done = true;
+            }
+        }
+        if (done) {
+        } else if (a.row_pred) k_pred_wave<W, MASK, STATS, true><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
         else k_pred_wave<W, MASK, STATS, false><<<gw, dim3(256), 0, st>>>(a, n_hub_rows, n_other_rows);
     }
     if (n_hub_rows > 0) {  // writes the lists itself: independent of the other two kernels
@@ -1329,23 +1381,34 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         // and one block per hop level of a row: the levels are independent, and the longest row
         // sets the duration of the launch
         const unsigned levels = (unsigned)std::max(a.k, 1);
-        if (a.row_pred) {  // into the row buffer, from which the list writer takes them
-            if (giants > 0 && a.giant_seg_first && giants == a.n_giant_rows) {
-                k_fill_int<<<dim3((unsigned)((giants * Qp_of<W>() + 255) / 256)), dim3(256), 0, st_hub>>>(
-                    a.row_pred, giants * Qp_of<W>(), INT_MAX);
-                k_pred_row<W, MASK, STATS, true, true><<<dim3((unsigned)a.n_giant_segs, levels), dim3(1024), 0, st_hub>>>(a, 0);
-            } else if (giants > 0)
-                k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
-            if (n_hub_rows > giants)
-                k_pred_row<W, MASK, STATS, true><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
-                    a, giants);
-        } else {  // straight into the lists
-            if (giants > 0)
-                k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
-            if (n_hub_rows > giants)
-                k_pred_row<W, MASK, STATS, false><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
-                    a, giants);
+        auto rows = [&](auto one_c) {
+            constexpr bool ONE = decltype(one_c)::value;
+            if (a.row_pred) {  // into the row buffer, from which the list writer takes them
+                if (giants > 0 && a.giant_seg_first && giants == a.n_giant_rows) {
+                    k_fill_int<<<dim3((unsigned)((giants * Qp_of<W>() + 255) / 256)), dim3(256), 0, st_hub>>>(
+                        a.row_pred, giants * Qp_of<W>(), INT_MAX);
+                    k_pred_row<W, MASK, STATS, true, true, ONE><<<dim3((unsigned)a.n_giant_segs, levels), dim3(1024), 0, st_hub>>>(a, 0);
+                } else if (giants > 0)
+                    k_pred_row<W, MASK, STATS, true, false, ONE><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
+                if (n_hub_rows > giants)
+                    k_pred_row<W, MASK, STATS, true, false, ONE><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
+                        a, giants);
+            } else {  // straight into the lists
+                if (giants > 0)
+                    k_pred_row<W, MASK, STATS, false, false, ONE><<<dim3((unsigned)giants, levels), dim3(1024), 0, st_hub>>>(a, 0);
+                if (n_hub_rows > giants)
+                    k_pred_row<W, MASK, STATS, false, false, ONE><<<dim3((unsigned)(n_hub_rows - giants), levels), dim3(256), 0, st_hub>>>(
+                        a, giants);
+            }
+        };
+        bool done = false;
+        if constexpr (W == 16 && !STATS) {
+            if (one) {
+                rows(std::true_type{});
+                done = true;
+            }
         }
+        if (!done) rows(std::false_type{});
     }
     // the list writer reads the row buffer: it starts behind the block-per-row kernel
     const bool rows_first = n_hub_rows > 0 && a.row_pred && mt && st_hub != st_tiles && a.ev_rows;

@@ -370,3 +370,44 @@ def test_the_callers_allocator_serves_the_memory_of_the_calls():
     with pytest.raises(m.LogosKGError):                               # an allocator that has nothing left
         fail.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
     fail.close()
+
+
+@pytest.mark.parametrize("masked", [False, True])
+def test_fetch_inside_one_word_of_sixteen_word_planes(masked, monkeypatch):
+    # A fetch whose queries sit in one 64-query word takes row kernels of its own (an entry per
+    # lane, a bit transpose per 64 entries): ranges at word starts, inside a word and at the ragged
+    # end, hub rows (block per row and level) and mid rows (wavefront per row), with and without
+    # the row buffer, against the oracle's slices.
+    m = lkg()
+    Q = 700
+    w = kggen.config3(0.006, k=3, num_queries=Q) if masked else kggen.config2(0.006, num_queries=Q)
+    want = run_oracle(w)
+    for hub_min, caps in ((60, None), (0, None), (60, "64,2")):
+        if caps:
+            monkeypatch.setenv("LOGOSKG_EMIT_CAPS", caps)
+        g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations, hub_min_degree=hub_min)
+        res = g.khop(w.seed_off, w.seeds, w.k, w.rel_mask)
+        for q0, q1 in ((0, 64), (64, 128), (70, 100), (127, 128), (640, 700), (699, 700), (5, 6)):
+            ent, hop, pred = res.fetch(q0, q1)
+            a, b = want[0][q0], want[0][q1]
+            what = f"masked={masked} hub_min={hub_min} caps={caps} queries {q0}..{q1}"
+            assert np.array_equal(ent.cpu().numpy(), want[1][a:b]), what
+            assert np.array_equal(hop.cpu().numpy(), want[2][a:b]), what
+            assert np.array_equal(pred.cpu().numpy(), want[3][a:b]), what
+        ent, hop, pred = res.fetch(60, 130)  # three words: the line-wide kernels
+        a, b = want[0][60], want[0][130]
+        assert np.array_equal(pred.cpu().numpy(), want[3][a:b])
+        res.close()
+        if not caps:  # more than six hops: the row kernels write into the lists themselves
+            want7 = run_oracle(w, k=7)
+            res = g.khop(w.seed_off, w.seeds, 7, w.rel_mask)
+            for q0, q1 in ((64, 128), (650, 700), (3, 4)):
+                ent, hop, pred = res.fetch(q0, q1)
+                a, b = want7[0][q0], want7[0][q1]
+                assert np.array_equal(ent.cpu().numpy(), want7[1][a:b]), (masked, hub_min, q0, q1)
+                assert np.array_equal(hop.cpu().numpy(), want7[2][a:b]), (masked, hub_min, q0, q1)
+                assert np.array_equal(pred.cpu().numpy(), want7[3][a:b]), (masked, hub_min, q0, q1)
+            res.close()
+        g.close()
+        if caps:
+            monkeypatch.delenv("LOGOSKG_EMIT_CAPS")
