@@ -92,6 +92,7 @@ constexpr int kPushSegment = 64;        // same for the subject rows of a push f
 constexpr int kDefaultHubMin = 1024;    // object rows from this degree: block-per-row predecessor kernel
                                         // (shorter long rows: one wavefront per row)
 constexpr int kDensePullPercent = 60;   // from this share of the triples leaving the frontier a hop is taken as dense
+constexpr int kPredPushShare = 4;       // a level whose frontier holds at most T / this triples: long rows resolved from the subject side
 constexpr int kGiantSegment = 8192;     // a giant row is walked by one 16-wave block per this many entries
 constexpr int kGiantRowMin = 8192;      // hub rows from this size get a 16-wave block in the predecessor pass, smaller ones 4 waves
 constexpr int kTileEntities = 64;       // entities per result tile (one wavefront of lanes)
@@ -371,6 +372,9 @@ struct FillArgs {
     unsigned long long *plane_buf;  // bit-sliced plane words between k_pred_walk and k_pred_emit, or NULL
     size_t plane_buf_bytes;
     int emit_eid_cap, emit_line_cap;  // capacities of k_pred_emit's two LDS tables (entries / lines)
+    uint32_t push_levels;   // bit h: level h of the long rows is resolved from the subject side (k_pred_push), the row
+                            // kernels leave it out; host_graph / host_result are what the host code needs for that
+    void *host_graph, *host_result;
     uint32_t dense_levels;  // bit h: nearly every triple leaves level h - 1, so the predecessor kernels gather the
                             // line of every entry of a row at level h without asking for its frontier bit first
     void *ev_rows;                    // host side: event between the block-per-row kernel and the list writer
@@ -417,6 +421,7 @@ void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows,
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
 long long max_chunk_rows(const logoskg_graph *g);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
+logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
                        const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
                        const lkg::RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st);

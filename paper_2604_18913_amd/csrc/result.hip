@@ -464,7 +464,7 @@ __global__ void __launch_bounds__(256) k_pred_wave(FillArgs a, long long first_r
         for (int h = 1; h <= a.k; ++h) {
             const unsigned long long level = a.levels[(size_t)h * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw);
             unsigned long long rem = level;
-            if (!wave_any(rem != 0)) continue;
+            if (!wave_any(rem != 0) || ((a.push_levels >> h) & 1u)) continue;
             const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
             const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
             const bool dense = !STATS && ((a.dense_levels >> h) & 1u);  // the line of an entity outside the level is zero
@@ -1091,7 +1091,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
     if (gridDim.y > 1) {  // nothing of this level in the row's entity: leave before the list positions
         const unsigned long long x =
             lw < W ? a.levels[(size_t)h_first * a.plane + (size_t)ev * W + lw] & range_bits(a.q0, a.q1, lw) : 0ull;
-        if (!wave_any(x != 0)) return;  // the same words in every wavefront
+        if (!wave_any(x != 0) || ((a.push_levels >> h_first) & 1u)) return;  // the same words in every wavefront
     }
     if (!BUF) row_slots<W>(a, ev, wave, nw, slot);
     int32_t *out = BUF ? a.row_pred + (size_t)(first_row + row_i) * Qp : a.pred;
@@ -1109,7 +1109,7 @@ __global__ void __launch_bounds__(1024) k_pred_row(FillArgs a, long long first_r
         }
         for (int q = t; q < Qp; q += blockDim.x) smin[q] = INT_MAX;
         __syncthreads();
-        if (!wave_any(slevel[lw] != 0)) continue;  // block-uniform
+        if (!wave_any(slevel[lw] != 0) || ((a.push_levels >> h) & 1u)) continue;  // block-uniform
         const uint32_t *act_prev = a.act + (size_t)(h - 1) * a.actw;
         const unsigned long long *prev = a.levels + (size_t)(h - 1) * a.plane;
         const bool dense = !STATS && ((a.dense_levels >> h) & 1u);  // the line of an entity outside the level is zero
@@ -1310,6 +1310,7 @@ logoskg_status prepare_row_pred(logoskg_graph *g, hipStream_t st) {
         return LOGOSKG_OK;
     }
     g->row_pred_rows = rows;
+    LKG_HIP(hipMemsetAsync(g->long_index, 0xFF, (size_t)g->E * sizeof(int32_t), st));  // -1: not a long row
     k_long_index<<<dim3((unsigned)((g->in_rows.n_long + 255) / 256)), dim3(256), 0, st>>>(g->in_rows.longrows,
                                                                                          g->in_rows.n_long, g->long_index);
     LKG_HIP(hipGetLastError());
@@ -1332,6 +1333,71 @@ static void launch_lists_w(Profiler &prof, const FillArgs &a, hipStream_t st) {
 
 // True when the 16-word tile kernel can serve this launch (it then can also write the entity and
 // hop lists, see FillArgs::fuse_lists).
+// A level with a small frontier (at most a quarter of the triples leave it: the first level, whose
+// frontier is the seeds) reaches a long object row for few queries: walking the row from
+// its first entry until each of them has met a frontier subject reads most of the row.  Such a
+// level is resolved from the subject side instead: the out-rows of the frontier entities are
+// walked as in a push hop, and an edge (u -> o, id t) with o a long row offers t, for every query in
+// level[h-1](u) & level[h](o) (& the relation's whitelist), to o's line of the row buffer with an
+// atomicMin.  k_pred_push_init first sets the level's entries of the long rows to INT_MAX.
+__global__ void __launch_bounds__(256) k_pred_push_init(FillArgs a, int h, long long n_rows) {
+    const long long i = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= n_rows) return;  // wavefront-uniform
+    const int ev = a.rows[i];
+    if (!((a.act[(size_t)h * a.actw + (ev >> 5)] >> (ev & 31)) & 1u)) return;
+    const int w0 = a.q0 >> 6, w1 = (a.q1 - 1) >> 6;
+    for (int w = w0; w <= w1; ++w) {
+        const unsigned long long x = a.levels[(size_t)h * a.plane + (size_t)ev * 16 + w] & range_bits(a.q0, a.q1, w);
+        if ((x >> lane()) & 1ull) a.row_pred[(size_t)i * 1024 + w * 64 + lane()] = INT_MAX;
+    }
+}
+
+// One wavefront per short frontier row (SEG = false) or per 64-entry segment of a longer one; lane = out-edge.
+template <bool MASK, bool SEG>
+__global__ void __launch_bounds__(256)
+k_pred_push(FillArgs a, int h, const int32_t *__restrict__ tail_rows, const RowSegment *__restrict__ segs,
+            const unsigned long long *__restrict__ ctr, const uint32_t *__restrict__ out_off,
+            const int32_t *__restrict__ out_obj, const uint16_t *__restrict__ out_rel,
+            const int32_t *__restrict__ out_eid) {
+    const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= (long long)ctr[SEG ? C_NSEG : C_NTAIL]) return;  // wavefront-uniform
+    int u;
+    uint32_t lo, hi;
+    if (SEG) {
+        const RowSegment sg = segs[item];
+        u = sg.row;
+        lo = sg.begin;
+        hi = min(lo + (uint32_t)kPushSegment, out_off[u + 1]);
+    } else {
+        u = tail_rows[item];
+        lo = out_off[u];
+        hi = out_off[u + 1];
+    }
+    const int w0 = a.q0 >> 6, w1 = (a.q1 - 1) >> 6, v = lane();
+    unsigned long long mine = 0;  // lane w: word w of the subject's frontier line
+    if (v >= w0 && v <= w1)
+        mine = a.levels[(size_t)(h - 1) * a.plane + (size_t)u * 16 + v] & range_bits(a.q0, a.q1, v);
+    if (!wave_any(mine != 0)) return;  // none of the fetched queries has this subject in its frontier
+    const uint32_t j = lo + (uint32_t)v;  // a segment holds at most 64 entries, a short row 32
+    int o = 0, li = -1, rl = 0, eid = 0;
+    if (j < hi) {
+        o = out_obj[j];
+        li = a.long_index[o];  // -1: a short object row, which the row walk of the tiles resolves
+        if (li >= 0) {
+            eid = out_eid[j];
+            if (MASK) rl = out_rel[j];
+        }
+    }
+    for (int w = w0; w <= w1; ++w) {
+        const unsigned long long lu = shfl64(mine, w);
+        if (lu == 0ull || li < 0) continue;
+        unsigned long long m = lu & a.levels[(size_t)h * a.plane + (size_t)o * 16 + w];
+        if (MASK && m) m &= a.allow[(size_t)rl * 16 + w];
+        for (; m; m &= m - 1)
+            atomicMin(&a.row_pred[(size_t)li * 1024 + w * 64 + (__ffsll((long long)m) - 1)], eid);
+    }
+}
+
 bool pred_uses_staged_kernel(const FillArgs &a, int W) {
     return W == 16 && a.k <= kSlicedMaxK && a.plane_buf != nullptr;
 }
@@ -1353,6 +1419,7 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
         a.row_pred = nullptr;
         a.fuse_lists = 0;
     }
+    if (!mt || W != 16 || STATS) a.push_levels = 0;
     // a fetch whose queries sit in one word of 16-word lines: the row kernels take an entry per lane
     const bool one = W == 16 && !STATS && a.q1 > a.q0 && (a.q0 >> 6) == ((a.q1 - 1) >> 6);
     // issued first: the tile kernel waits for it, and launched after the hub kernel it ran half as fast
@@ -1409,6 +1476,29 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
             }
         }
         if (!done) rows(std::false_type{});
+    }
+    if constexpr (W == 16 && !STATS) {
+        if (a.push_levels) {  // the pushed levels of the long rows, from the subject side (behind the row kernels:
+                              // the giant rows' lines are filled before those run)
+            logoskg_graph *g = static_cast<logoskg_graph *>(a.host_graph);
+            logoskg_result *r = static_cast<logoskg_result *>(a.host_result);
+            const long long n_long = n_hub_rows + n_other_rows;
+            for (int h = 1; h <= a.k && n_long > 0; ++h) {
+                if (!((a.push_levels >> h) & 1u)) continue;
+                ProfScope ps(prof, KK_PRED_HUB, st_hub);
+                if (census_lists(g, r, h - 1, -1, st_hub) != LOGOSKG_OK) break;  // (the caller reads the last error)
+                k_pred_push_init<<<dim3((unsigned)((n_long + 3) / 4)), dim3(256), 0, st_hub>>>(a, h, n_long);
+                // the lists' lengths are on the device; the hop's own statistics bound them
+                const long long rows = r->stats[(size_t)h - 1].active_rows;
+                const long long max_seg = rows + r->stats[(size_t)h - 1].frontier_edges / kPushSegment;
+                if (rows > 0) {
+                    k_pred_push<MASK, false><<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st_hub>>>(
+                        a, h, g->fr_tail, g->fr_seg, g->d_ctr, g->out_off, g->out_obj, g->out_rel, g->out_eid);
+                    k_pred_push<MASK, true><<<dim3((unsigned)((max_seg + 3) / 4)), dim3(256), 0, st_hub>>>(
+                        a, h, g->fr_tail, g->fr_seg, g->d_ctr, g->out_off, g->out_obj, g->out_rel, g->out_eid);
+                }
+            }
+        }
     }
     // the list writer reads the row buffer: it starts behind the block-per-row kernel
     const bool rows_first = n_hub_rows > 0 && a.row_pred && mt && st_hub != st_tiles && a.ev_rows;
@@ -1572,6 +1662,22 @@ extern "C" logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q0, in
     }
     a.entity = entity; a.hop = hop; a.pred = pred;
     const bool counting = g->prof.counters;
+    // levels whose frontier holds at most a quarter of the triples: their long rows are resolved from the
+    // subject side (resident graphs, row buffer in use, minimum-hop search); needs the triple index of
+    // every entry of SUB
+    if (pred && W == 16 && g->num_shards <= 1 && !counting && !r->walk_exact && a.row_pred && a.long_index &&
+        pred_uses_staged_kernel(a, W)) {
+        uint32_t levels = 0;
+        for (int h = 1; h <= r->k && h < 32; ++h)
+            if (r->stats[(size_t)h - 1].active_rows > 0 &&
+                (long long)r->stats[(size_t)h - 1].frontier_edges * kPredPushShare <= g->T)
+                levels |= 1u << h;
+        if (levels && ensure_out_eid(g, st) == LOGOSKG_OK) {
+            a.push_levels = levels;
+            a.host_graph = g;
+            a.host_result = r;
+        }
+    }
     a.stats_pred = counting ? g->d_ctr + C_STATS + 4 * KK_PRED : nullptr;
     a.stats_hub = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_HUB : nullptr;
     a.stats_mid = counting ? g->d_ctr + C_STATS + 4 * KK_PRED_MID : nullptr;
