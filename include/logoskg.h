@@ -278,7 +278,8 @@ logoskg_status logoskg_result_offsets(const logoskg_result *r, int64_t *reached_
  * process ends - and join `stream` before the call returns; measured, no gain.)  The
  * first call on a graph that asks for pred_edge with more than 256 queries
  * allocates a buffer of 4 KiB per object row of more than 32 entries (not
- * above 8 GiB; freed with the graph).  On a sharded graph pred_edge streams the
+ * above 8 GiB; freed with the graph) and, on a resident graph, 4 bytes per
+ * triple for the triple index of every entry of SUB.  On a sharded graph pred_edge streams the
  * object-sorted triples from pinned host memory.
  */
 logoskg_status logoskg_result_fetch(logoskg_result *r, int32_t q_begin, int32_t q_end,

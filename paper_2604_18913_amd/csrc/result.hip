@@ -24,7 +24,8 @@
 //           k_pred_emit, which writes the entity and hop lists as well;
 //           k_pred otherwise); rows of 33 .. hub_min-1 entries belong to
 //           k_pred_wave and longer ones to k_pred_row, whose lanes claim in
-//           parallel and keep the minimum.
+//           parallel and keep the minimum.  A level with a small frontier is
+//           taken from the subject side for these longer rows (k_pred_push).
 #include <algorithm>
 #include <climits>
 #include <cstdlib>
