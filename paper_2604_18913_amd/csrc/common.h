@@ -421,7 +421,9 @@ void launch_pred(Profiler &prof, const FillArgs &a, int W, long long n_hub_rows,
 logoskg_status sharded_pred(logoskg_graph *g, FillArgs *a, int W, bool mask, hipStream_t st);
 long long max_chunk_rows(const logoskg_graph *g);
 logoskg_status census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool write_lists, hipStream_t st);
-logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st);
+// (prof_kind: the kernel class the launch is timed under)
+logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st,
+                            int prof_kind = KK_CENSUS);
 void launch_push_lists(logoskg_graph *g, logoskg_result *r, int h, const unsigned long long *hc,
                        const int32_t *obj, const uint16_t *rel, bool update, const int32_t *list_tail,
                        const lkg::RowSegment *list_seg, const unsigned long long *ctr, hipStream_t st);

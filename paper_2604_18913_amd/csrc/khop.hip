@@ -952,18 +952,19 @@ void launch_resident_hop(logoskg_graph *g, logoskg_result *r, int h, bool pull, 
 // Census of level h's active bitmap (all subjects, or those of one shard): counts the rows,
 // edges and list entries into g->h_ctr (stream synchronised); with write_lists a second pass
 // appends the push work lists.
-static void launch_census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool lists, hipStream_t st) {
+static void launch_census(logoskg_graph *g, logoskg_result *r, int h, int shard, bool lists, hipStream_t st,
+                          int prof_kind = KK_CENSUS) {
     const long long nwords = r->Epad / 32;
-    ProfScope ps(g->prof, KK_CENSUS, st);
+    ProfScope ps(g->prof, prof_kind, st);
     const unsigned nb = std::min<unsigned>(1024u, std::max(1u, blocks_for(g->E, 256)));
     k_census<<<dim3(nb), dim3(256), 0, st>>>(r->act + (size_t)nwords * h, g->E, g->out_off, g->row_begin,
                                              shard >= 0 ? g->shard_of_dev : nullptr, shard, lists ? 1 : 0,
                                              g->fr_tail, g->fr_seg, g->d_ctr);
 }
 
-logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st) {
+logoskg_status census_lists(logoskg_graph *g, logoskg_result *r, int h, int shard, hipStream_t st, int prof_kind) {
     LKG_HIP(hipMemsetAsync(g->d_ctr, 0, 2 * sizeof(unsigned long long), st));  // C_NTAIL, C_NSEG: append cursors
-    launch_census(g, r, h, shard, true, st);
+    launch_census(g, r, h, shard, true, st, prof_kind);
     LKG_HIP(hipGetLastError());
     return LOGOSKG_OK;
 }

@@ -1486,8 +1486,9 @@ static void launch_pred_wms(Profiler &prof, const FillArgs &a0, long long n_hub_
             const long long n_long = n_hub_rows + n_other_rows;
             for (int h = 1; h <= a.k && n_long > 0; ++h) {
                 if (!((a.push_levels >> h) & 1u)) continue;
+                // (timed with the row kernels whose work it takes over; profiler scopes do not nest)
+                if (census_lists(g, r, h - 1, -1, st_hub, KK_PRED_HUB) != LOGOSKG_OK) break;  // (the caller reads the last error)
                 ProfScope ps(prof, KK_PRED_HUB, st_hub);
-                if (census_lists(g, r, h - 1, -1, st_hub) != LOGOSKG_OK) break;  // (the caller reads the last error)
                 k_pred_push_init<<<dim3((unsigned)((n_long + 3) / 4)), dim3(256), 0, st_hub>>>(a, h, n_long);
                 // the lists' lengths are on the device; the hop's own statistics bound them
                 const long long rows = r->stats[(size_t)h - 1].active_rows;
