@@ -74,6 +74,12 @@ def one_case(seed):
         ent, hop, pred = res.fetch(q0, q1)
         a, b = want[0][q0], want[0][q1]
         assert np.array_equal(ent.cpu().numpy(), want[1][a:b]) and np.array_equal(pred.cpu().numpy(), want[3][a:b]), what
+        qe = min(Q, (q0 // 64 + 1) * 64)   # a fetch that stays inside one 64-query word
+        if qe > q0:
+            ent, hop, pred = res.fetch(q0, qe)
+            a, b = want[0][q0], want[0][qe]
+            assert np.array_equal(ent.cpu().numpy(), want[1][a:b]) and np.array_equal(hop.cpu().numpy(), want[2][a:b]), what
+            assert np.array_equal(pred.cpu().numpy(), want[3][a:b]), what
         levels = [[want[1][want[0][q]:want[0][q + 1]][want[2][want[0][q]:want[0][q + 1]] == h] for q in range(Q)]
                   for h in range(k + 1)]
         if want[0][-1] > 0:
