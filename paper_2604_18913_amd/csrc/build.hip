@@ -407,7 +407,7 @@ extern "C" logoskg_status logoskg_build(const int32_t *subj, const int32_t *rel,
     for (int i = 0; i < 2; ++i) {
         if (!(g->side[i] = helper_stream(g->device, i)) ||
             hipEventCreateWithFlags(&g->ev_join[i], hipEventDisableTiming) != hipSuccess) {
-            set_error("could not create side streams");
+            set_error("could not create the helper streams");
             return fail(LOGOSKG_EDEVICE);
         }
     }

@@ -215,7 +215,8 @@ struct logoskg_graph {
     size_t plane_buf_bytes = 0;
     hipEvent_t ev_rows = nullptr;
 
-    // side streams (default priority) so that the independent result kernels of a fetch overlap
+    // the device's helper streams (default priority; shared by all graphs on the device) on which the
+    // independent result kernels of a fetch can overlap (LOGOSKG_OVERLAP_FETCH=1)
     hipStream_t side[2] = {nullptr, nullptr};
     hipEvent_t ev_fork = nullptr, ev_join[2] = {nullptr, nullptr};
 
