@@ -309,6 +309,25 @@ def main():
         phase_ms[0] += ev[0].elapsed_time(ev[1]) / 5
         phase_ms[1] += ev[1].elapsed_time(ev[2]) / 5
 
+    # what the line gathers of a dense pull hop cost on their own on this graph (measurement aid of the
+    # library: every CSR entry's 128-byte subject line, the pull kernels' access shape, nothing else)
+    gather_probe = None
+    if W == 16 and cfg != 5:
+        plane = torch.zeros((w.num_entities, 16), dtype=torch.int64, device="cuda")
+        for _ in range(2):
+            g.probe_gather(plane)
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe[0].record()
+        for _ in range(5):
+            g.probe_gather(plane)
+        pe[1].record()
+        torch.cuda.synchronize()
+        probe_ms = pe[0].elapsed_time(pe[1]) / 5
+        gather_probe = {"lines": int(w.num_triples), "ms": round(probe_ms, 4),
+                        "lines_per_s": round(w.num_triples / (probe_ms * 1e-3), 1),
+                        "what": "one 128-byte line per entry of the object-sorted CSR, in CSR order"}
+        del plane
+
     ab = functools.partial(algorithmic_bytes, level_lists=walk or triples)
     masked_arg = masked
     ms_per_step = dt / args.steps * 1e3
@@ -328,6 +347,11 @@ def main():
     plane_bytes = float(res_epad * W * 8)
     expansion_bytes = sum(ab(n, v, W, k, masked_arg, plane_bytes) for n, v in kernels.items()
                           if n.startswith(expansion_names))
+    # lines the pull kernels gather per second: a dense hop takes the line of every entry it scans
+    pull_ms = sum(kernels[n]["ms_per_step"] for n in ("pull_tail", "pull_seg") if n in kernels)
+    pull_lines = sum(h["edges_scanned"] if h["frontier_edges"] * 100 >= w.num_triples * 60 else h["lines_gathered"]
+                     for h in counted_stats if h["direction"] == 2)
+    pull_lines_per_s = round(pull_lines / (pull_ms * 1e-3), 1) if pull_ms > 0 and pull_lines > 0 else None
     lists_fused = "lists" not in kernels  # the predecessor tile kernel wrote the entity / hop lists too
     dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
     dk = kernels[dom]
@@ -426,7 +450,12 @@ def main():
                       "counter_GBps": round(expansion_measured / (expansion_ms * 1e-3) / 1e9, 1)
                       if expansion_measured and expansion_ms else None,
                       "counter_hbm_frac": round(expansion_measured / (expansion_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-                      if expansion_measured and expansion_ms else None},
+                      if expansion_measured and expansion_ms else None,
+                      # the pull kernels' line gathers against the gathers alone (same lines per CSR entry)
+                      "gather_probe": gather_probe,
+                      "pull_lines_per_s": pull_lines_per_s,
+                      "pull_frac_of_gather_probe": round(pull_lines_per_s / gather_probe["lines_per_s"], 4)
+                      if gather_probe and pull_lines_per_s else None},
         "stream_copy_GBps": round(stream_copy_gbps, 1),
         "roofline": roofline,
         "kernels": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}

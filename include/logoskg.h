@@ -157,6 +157,21 @@ logoskg_status logoskg_profile_enable(logoskg_graph *g, int32_t enable);
 logoskg_status logoskg_profile_read(logoskg_graph *g, logoskg_kernel_profile *out, int32_t capacity,
                                     int32_t *n_out);
 
+/*
+ * Measurement aid, no part of the retrieval: the line gathers of a dense pull
+ * hop (Eq. 4 evaluated per object row on a batch of 1,024 queries) and nothing
+ * else.  For every entry of the object-sorted CSR of a resident graph, in
+ * order, the 128-byte line lines[16 * subject .. 16 * subject + 15] is loaded
+ * with the access shape of the pull kernels and ORed into out16; no row bounds,
+ * visited or level lines are touched and nothing else is written, so the time of
+ * this call is what the gathers of such a hop cost on this GPU and graph.
+ *   lines : device, [num_entities][16] uint64 (any content)
+ *   out16 : device, 16 uint64 (the OR of the lines of all subjects, for checks)
+ * Asynchronous on `stream`.  LOGOSKG_EINVAL on a sharded graph.
+ */
+logoskg_status logoskg_probe_gather(const logoskg_graph *g, const uint64_t *lines, uint64_t *out16,
+                                    void *stream);
+
 /* Sec. 3.4 metadata map P: shard of each subject entity (-1 for entities that are
  * never a subject), and the number of triples per shard.  host outputs; either
  * may be NULL. */

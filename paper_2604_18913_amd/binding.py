@@ -101,6 +101,8 @@ def _load():
     lib.logoskg_graph_free.argtypes = [P]
     lib.logoskg_graph_get_info.restype = ctypes.c_int
     lib.logoskg_graph_get_info.argtypes = [P, ctypes.POINTER(_GraphInfo)]
+    lib.logoskg_probe_gather.restype = ctypes.c_int
+    lib.logoskg_probe_gather.argtypes = [P, P, P, P]
     lib.logoskg_graph_partition.restype = ctypes.c_int
     lib.logoskg_graph_partition.argtypes = [P, P, P]
     lib.logoskg_khop.restype = ctypes.c_int
@@ -370,6 +372,16 @@ class Graph:
             out[rec.name.decode()] = dict(launches=int(rec.launches), total_ms=float(rec.total_ms),
                                           max_ms=float(rec.max_ms), rows=int(rec.rows), edges=int(rec.edges),
                                           lines=int(rec.lines), items=int(rec.items))
+        return out
+
+    def probe_gather(self, lines, stream=None):
+        """Measurement aid: the line gathers of a dense pull hop alone, on `lines` ([num_entities, 16]
+        int64 device tensor); returns the OR of the gathered lines (16 words, device)."""
+        torch = _torch()
+        assert lines.is_cuda and lines.dtype == torch.int64 and lines.is_contiguous()
+        assert tuple(lines.shape) == (self.num_entities, 16)
+        out = torch.empty(16, dtype=torch.int64, device=lines.device)
+        _check(_load().logoskg_probe_gather(self._h, lines.data_ptr(), out.data_ptr(), _stream_handle(stream)))
         return out
 
     def partition(self):

@@ -1161,3 +1161,71 @@ extern "C" logoskg_status logoskg_result_hop_stats(const logoskg_result *r, logo
     for (int i = 0; i < r->k; ++i) o[i] = r->stats[(size_t)i];
     return LOGOSKG_OK;
 }
+
+// ---------------------------------------------------------------- measurement aid
+// The line gathers of a dense pull hop and nothing else: for every entry of the object-sorted CSR,
+// in order, the 128-byte line of its subject is loaded with the access shape of k_pull_seg (one
+// wavefront per 1,024 entries, eight lanes per line, eight lines per load instruction, four rounds
+// in flight, the ids of the next 64 entries requested ahead) and ORed into sixteen words.  No row
+// bounds, no visited or level lines, no writes: what this takes is what the memory system needs
+// for the gathers of such a hop on this graph.
+namespace lkg {
+__global__ void __launch_bounds__(256)
+k_probe_gather(const int32_t *__restrict__ in_sub, long long T, const ulonglong2 *__restrict__ lines,
+               unsigned long long *out) {
+    const long long lo = ((long long)blockIdx.x * 4 + (threadIdx.x >> 6)) * kPullSegment;
+    if (lo >= T) return;  // wavefront-uniform
+    const long long hi = min(T, lo + (long long)kPullSegment);
+    const int l8 = lane() & 7, grp = lane() >> 3;
+    unsigned long long a0 = 0, a1 = 0;
+    int s_next = lo + lane() < hi ? in_sub[lo + lane()] : 0;
+    for (long long j0 = lo; j0 < hi; j0 += 64) {
+        const int s = s_next;
+        const long long jn = j0 + 64 + lane();
+        s_next = jn < hi ? in_sub[jn] : 0;
+        const int n = (int)min(64ll, hi - j0);
+        for (int base = 0; base < n; base += 32) {
+            ulonglong2 l[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int i = base + 8 * x + grp;
+                const int sx = __shfl(s, i & 63);
+                l[x] = make_ulonglong2(0, 0);
+                if (i < n) l[x] = lines[(size_t)sx * 8 + l8];
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                a0 |= l[x].x;
+                a1 |= l[x].y;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 8; m < 64; m <<= 1) {
+        a0 |= shfl_xor64(a0, m);
+        a1 |= shfl_xor64(a1, m);
+    }
+    if (lane() < 8) {
+        if (a0) atomicOr(&out[2 * lane()], a0);
+        if (a1) atomicOr(&out[2 * lane() + 1], a1);
+    }
+}
+}  // namespace lkg
+
+extern "C" logoskg_status logoskg_probe_gather(const logoskg_graph *g, const uint64_t *lines, uint64_t *out16,
+                                               void *stream) {
+    if (!g || !lines || !out16) { set_error("NULL argument"); return LOGOSKG_EINVAL; }
+    if (g->num_shards > 1 || !g->in_sub) {
+        set_error("the gather probe needs a resident graph");
+        return LOGOSKG_EINVAL;
+    }
+    LKG_HIP(hipSetDevice(g->device));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    LKG_HIP(hipMemsetAsync(out16, 0, 16 * sizeof(uint64_t), st));
+    const long long nseg = (g->T + kPullSegment - 1) / kPullSegment;
+    if (nseg > 0)
+        k_probe_gather<<<dim3((unsigned)((nseg + 3) / 4)), dim3(256), 0, st>>>(
+            g->in_sub, g->T, reinterpret_cast<const ulonglong2 *>(lines), reinterpret_cast<unsigned long long *>(out16));
+    LKG_HIP(hipGetLastError());
+    return LOGOSKG_OK;
+}

@@ -411,3 +411,17 @@ def test_fetch_inside_one_word_of_sixteen_word_planes(masked, monkeypatch):
         g.close()
         if caps:
             monkeypatch.delenv("LOGOSKG_EMIT_CAPS")
+
+
+def test_gather_probe_ors_the_lines_of_all_subjects():
+    # the measurement aid reads the line of every entry's subject: its result is the OR over the subjects
+    import torch
+    m = lkg()
+    w = kggen.config2(0.004, num_queries=64)
+    g = m.Graph(w.subj, w.rel, w.obj, w.num_entities, w.num_relations)
+    rng = np.random.default_rng(5)
+    lines = rng.integers(0, 2 ** 62, size=(w.num_entities, 16), dtype=np.int64) & rng.integers(0, 2 ** 62, size=(w.num_entities, 16), dtype=np.int64)
+    out = g.probe_gather(torch.from_numpy(lines).cuda())
+    want = np.bitwise_or.reduce(lines[np.unique(w.subj)], axis=0)
+    assert np.array_equal(out.cpu().numpy(), want)
+    g.close()
