@@ -44,3 +44,28 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src.lower(), f"{f} mentions the oracle"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build runs on exactly one GPU: bench.py says so and exits before it touches anything
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in (p.stderr + p.stdout)
+
+
+def test_bench_byte_model_of_the_list_writer():
+    # the roofline of the dominant kernel prices 72 bytes per (entity, word) cell handed over by the
+    # row walk plus 9 bytes per list entry (entity, hop, predecessor)
+    import os
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    units = dict(rows=1000, edges=0, lines=0, items=50000, launches_per_step=1)
+    got = bench.algorithmic_bytes("pred", units, 16, 3, False, 0.0, lists_fused=True)
+    assert got == 72 * 1000 + 9 * 50000
